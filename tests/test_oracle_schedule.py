@@ -1,0 +1,197 @@
+"""Pins for the schedule oracle: hand-derived peaks and trace, agreement of the literal
+interpreter with the closed-form memory formulas, schedule-independence of gradients,
+and rejection of infeasible schedules."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import network as onet
+from oracle import schedule as osch
+from workloads import graphs, schedules, tensors
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_kv(name):
+    out = {}
+    for ln in open(os.path.join(GOLD, name)):
+        ln = ln.split("#")[0].split()
+        if ln:
+            out[ln[0]] = int(ln[1])
+    return out
+
+
+def read_trace(name):
+    rows = []
+    for ln in open(os.path.join(GOLD, name)):
+        ln = ln.split("#")[0].split()
+        if ln:
+            rows.append(tuple(int(v) for v in ln))
+    return rows
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    g = graphs.tiny_chain()
+    exts, params = tensors.make_inputs(g, seed=0, gamma_beta="random")
+    oe, op = tensors.oracle_inputs(exts, params)
+    return g, g.text(), oe, op
+
+
+def test_hand_derived_peaks(tiny):
+    g, gt, _, _ = tiny
+    gold = read_kv("tiny_chain_peaks.txt")
+    r = osch.interpret(gt, schedules.store_everything_schedule(g).text())
+    assert (r["fwd_peak"], r["peak"], r["recomputes"]) == (
+        gold["store_all_forward_peak"], gold["store_all_step_peak"], gold["store_all_recomputes"])
+    r = osch.interpret(gt, schedules.tiny_chain_schedule(g, {0, 2}).text())
+    assert (r["fwd_peak"], r["peak"], r["recomputes"]) == (
+        gold["lean_c02_forward_peak"], gold["lean_c02_step_peak"], gold["lean_c02_recomputes"])
+
+
+def test_hand_derived_one_block_trace():
+    g = graphs.tiny_chain(batch=1, hw=4, channels=4, blocks=1, wgrad_splits=(4,))
+    st = schedules.store_everything_schedule(g).text()
+    r = osch.interpret(g.text(), st)
+    assert r["events"] == read_trace("one_block_trace.txt")
+
+
+def all_tiny_schedules(g):
+    for bits in itertools.product([0, 1], repeat=4):
+        C = {b for b in range(4) if bits[b]}
+        yield C, "lean", schedules.tiny_chain_schedule(g, C)
+        yield C, "standard", schedules.tiny_chain_schedule(g, C, schedules.STANDARD_VARIANTS)
+
+
+def test_interpreter_equals_closed_form_all_subsets(tiny):
+    g, gt, _, _ = tiny
+    for C, name, sch in all_tiny_schedules(g):
+        st = sch.text()
+        r = osch.interpret(gt, st)
+        cf = osch.closed_form(gt, st)
+        assert r["peak"] == cf["exact_peak"], (C, name)
+        assert cf["predicted_peak"] >= cf["exact_peak"], (C, name)
+        # per-operator agreement, not just the maximum
+        live_at = {}
+        for kind, stage, node, impl, aux, nbytes, live in r["events"]:
+            if kind in (osch.RUN_FWD, osch.RUN_RECOMPUTE, osch.RUN_BWD):
+                live_at[(kind, stage, node)] = live
+        B = len(g.bops)
+        for i, m in cf["m_fwd"].items():
+            assert live_at[(osch.RUN_FWD, B + 1, i)] == m
+        for k, m in cf["m_bwd"].items():
+            assert live_at[(osch.RUN_BWD, k, k)] == m
+        for (i, k), m in cf["m_rec"].items():
+            assert live_at[(osch.RUN_RECOMPUTE, k, i)] == m
+            assert cf["m_rec_bar"][(i, k)] >= m
+
+
+def test_trace_is_consistent(tiny):
+    g, gt, _, _ = tiny
+    for C, name, sch in all_tiny_schedules(g):
+        r = osch.interpret(gt, sch.text())
+        live = 0
+        runs = {}
+        for kind, stage, node, impl, aux, nbytes, after in r["events"]:
+            if kind == osch.ALLOC:
+                live += nbytes
+            elif kind == osch.FREE:
+                live -= nbytes
+            assert live == after and live >= 0
+            if kind == osch.RUN_RECOMPUTE:
+                runs[node] = runs.get(node, 0) + 1
+        assert live == 0
+        assert all(v == 1 for v in runs.values())       # nothing is recomputed twice under this policy
+
+
+def test_gradients_do_not_depend_on_the_schedule(tiny):
+    g, gt, oe, op = tiny
+    ref = onet.store_everything_step(gt, oe, op)
+    for C, name, sch in all_tiny_schedules(g):
+        r = osch.interpret(gt, sch.text(), oe, op)
+        assert abs(r["loss"] - ref["loss"]) <= 1e-12 * abs(ref["loss"])
+        for pid, want in ref["grads"].items():
+            err = np.linalg.norm(r["grads"][pid] - want) / np.linalg.norm(want)
+            assert err < 1e-12, (C, name, pid, err)
+
+
+def test_resnet_schedule_invariants():
+    g = graphs.resnet50(batch=2, hw=32, classes=10, widths=(4, 8, 8, 16), depths=(2, 2, 1, 1), stem=4)
+    gt = g.text()
+    exts, params = tensors.make_inputs(g, seed=1, gamma_beta="random")
+    oe, op = tensors.oracle_inputs(exts, params)
+    ref = onet.store_everything_step(gt, oe, op)
+    peaks = {}
+    for name, sch in (("store", schedules.store_everything_schedule(g)),
+                      ("store_lean", schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS)),
+                      ("blocks", schedules.block_output_schedule(g))):
+        st = sch.text()
+        r = osch.interpret(gt, st, oe, op)
+        cf = osch.closed_form(gt, st)
+        assert r["peak"] == cf["exact_peak"] <= cf["predicted_peak"], name
+        peaks[name] = r["peak"]
+        for pid, want in ref["grads"].items():
+            err = np.linalg.norm(r["grads"][pid] - want) / np.linalg.norm(want)
+            assert err < 1e-10, (name, pid, err)
+    assert peaks["blocks"] < peaks["store_lean"] < peaks["store"]
+
+
+# ------------------------------------------------------------------ infeasible schedules
+def _edit(text, drop=None, add=None):
+    lines = text.splitlines()
+    if drop is not None:
+        assert drop in lines, drop
+        lines.remove(drop)
+    if add is not None:
+        lines.append(add)
+    return "\n".join(lines) + "\n"
+
+
+def test_validator_rejects_each_violated_constraint(tiny):
+    g, gt, _, _ = tiny
+    st = schedules.tiny_chain_schedule(g, {0, 2}).text()
+    osch.interpret(gt, st)
+    # Eq. 8: relu backward of block 3 (stage 15) reads mask 16, recomputed there: drop the recomputation
+    with pytest.raises(osch.ScheduleError, match="Eq.8|Appendix D"):
+        osch.interpret(gt, _edit(st, drop="r 15 16 impl=-1"))
+    # Eq. 7 (dependency): stage 15 recomputes conv 13 from node 11; un-save node 11 at that stage
+    with pytest.raises(osch.ScheduleError, match="Eq.7"):
+        osch.interpret(gt, _edit(st, drop="s 15 11"))
+    # Eq. 7 (carry): save a tensor nobody holds
+    with pytest.raises(osch.ScheduleError, match="Eq.7"):
+        osch.interpret(gt, _edit(st, add="s 12 5"))
+    # Appendix D: aux without its creator
+    with pytest.raises(osch.ScheduleError, match="Appendix D"):
+        osch.interpret(gt, _edit(st, add="r 16 16 impl=-1"))
+    # C.3: in-place ReLU over a BN output that the output-activated BN backward needs
+    with pytest.raises(osch.ScheduleError, match="C.3"):
+        osch.interpret(gt, _edit(_edit(st, drop="r 15 15 impl=0"), add="r 15 15 impl=1"))
+    # C.3 in the forward pass: in-place over a saved tensor
+    with pytest.raises(osch.ScheduleError, match="C.3"):
+        osch.interpret(gt, st.replace("fwd 3 impl=0 save=1", "fwd 3 impl=1 save=1"))
+    # recomputing something already held
+    with pytest.raises(osch.ScheduleError, match="already held"):
+        osch.interpret(gt, _edit(st, add="r 16 2 impl=0"))
+    # Appendix B: recomputation beyond the stage's own node
+    with pytest.raises(osch.ScheduleError, match="Appendix B"):
+        osch.interpret(gt, _edit(st, add="r 2 5 impl=0"))
+
+
+def test_objective_counts_recomputation(tiny):
+    g, gt, _, _ = tiny
+    base = osch.objective(gt, schedules.tiny_chain_schedule(g, {0, 1, 2, 3}).text())
+    lean = osch.objective(gt, schedules.tiny_chain_schedule(g, {0, 2}).text())
+    block = sum(g.fimpls[i][0]["cost"] for i in (13, 14, 15))
+    assert lean == pytest.approx(base + 2 * block)
+
+
+def test_brute_force_respects_budget_and_prefers_cheap(tiny):
+    from oracle import search
+    g = tiny[0]
+    free = search.brute_force(g, budget=1 << 40)
+    assert free[2] == [0, 1, 2, 3]                       # no recomputation when memory is free
+    tight = search.brute_force(g, budget=232448)
+    assert tight is not None and tight[1] <= 232448 and tight[0] > free[0]
+    assert search.brute_force(g, budget=100000) is None  # below every schedule's peak

@@ -1,0 +1,342 @@
+"""Forward graphs of the synthetic networks, written as `monet-graph` text.
+
+The text is the forward DAG of the paper's Section 3 (nodes 1..N in
+topological order, edges given by each node's `in=` list), extended as its
+Appendix D describes: intermediate storage nodes (ReLU sign mask, max-pool
+window index) follow their creator, convolution and linear layers own two
+backward operators (input-gradient, parameter-gradient), and every forward
+and backward operator lists its implementations with workspace bytes, cost
+and, for backward ones, the forward tensors they depend on.
+
+Format (one record per line, fields separated by blanks):
+
+    monet-graph 1
+    ext   <ref<=0> <name> <f32|i32> <d0xd1x...>        caller-owned tensors
+    param <pid> <name> <d0xd1x...>                      fp32 parameters
+    node  <i> <op> in=<ref,...> par=<pid,...|-> shape=<dims> [key=value ...]
+    fimpl <i> <l> algo=<name> ws=<bytes> cost=<float> [inplace=1] [key=value]
+    bop   <k> <kind> node=<i>
+    bimpl <k> <l> algo=<name> deps=<ref,...|-> ws=<bytes> cost=<float> [key=value]
+
+Activations are NHWC, convolution weights K,R,S,C, linear weights out,in.
+`ref` > 0 names a node's output, `ref` <= 0 an `ext` tensor.  Backward
+operators are numbered in forward order of their node (input-gradient before
+parameter-gradient), so that running them from the highest number down gives
+the parameter gradient first (Appendix D).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+RIDGE_FLOP_PER_BYTE = 20.0  # cost unit: one byte moved counts as 20 flop
+
+
+def _dims(shape):
+    return "x".join(str(int(d)) for d in shape)
+
+
+def numel(shape):
+    n = 1
+    for d in shape:
+        n *= int(d)
+    return n
+
+
+@dataclass
+class Node:
+    id: int
+    op: str
+    ins: list
+    pars: list
+    shape: tuple
+    attrs: dict = field(default_factory=dict)
+
+
+class Graph:
+    AUX_OPS = ("mask", "poolidx")
+
+    def __init__(self):
+        self.exts = []      # (ref, name, dtype, shape)
+        self.params = []    # (pid, name, shape)
+        self.nodes = []     # Node, id = index+1
+        self.fimpls = {}    # node id -> [dict]
+        self.bops = []      # dict(k, kind, node)
+        self.bimpls = {}    # k -> [dict]
+        self.blocks = []    # [(name, [node ids])]  (builder-side grouping for schedule helpers)
+        self._cur_block = None
+
+    # ---- construction -------------------------------------------------
+    def ext(self, name, dtype, shape):
+        ref = -len(self.exts)
+        self.exts.append((ref, name, dtype, tuple(shape)))
+        return ref
+
+    def param(self, name, shape):
+        pid = len(self.params)
+        self.params.append((pid, name, tuple(shape)))
+        return pid
+
+    def shape_of(self, ref):
+        if ref <= 0:
+            return self.exts[-ref][3]
+        return self.nodes[ref - 1].shape
+
+    def begin_block(self, name):
+        self._cur_block = (name, [])
+        self.blocks.append(self._cur_block)
+
+    def end_block(self):
+        self._cur_block = None
+
+    def _add(self, op, ins, pars, shape, **attrs):
+        n = Node(len(self.nodes) + 1, op, list(ins), list(pars), tuple(shape), dict(attrs))
+        self.nodes.append(n)
+        if self._cur_block is not None:
+            self._cur_block[1].append(n.id)
+        return n.id
+
+    def _bytes(self, ref):
+        return 4 * numel(self.shape_of(ref))
+
+    # ---- operators ----------------------------------------------------
+    def conv(self, x, K, R, S=None, stride=1, pad=0, name="conv", wgrad_splits=(8,)):
+        S = R if S is None else S
+        N, H, W, C = self.shape_of(x)
+        P = (H + 2 * pad - R) // stride + 1
+        Q = (W + 2 * pad - S) // stride + 1
+        w = self.param(name + ".w", (K, R, S, C))
+        i = self._add("conv", [x], [w], (N, P, Q, K), R=R, S=S, stride=stride, pad=pad)
+        flop = 2.0 * N * P * Q * K * C * R * S
+        self.fimpls[i] = [dict(algo="igemm", ws=0, cost=flop)]
+        wbytes = 4 * K * R * S * C
+        wg = [dict(algo="direct", ws=0, cost=flop * 4.0)]
+        for sp in wgrad_splits:
+            wg.append(dict(algo="splitk", ws=_align(sp * wbytes), cost=flop * (1.0 + 0.02 * sp), splits=sp))
+        self._pending_bops(i, [("conv_dgrad", [dict(algo="igemm", deps=[], ws=0, cost=flop)])] if x > 0 else [],
+                           [("conv_wgrad", [dict(d, deps=[x] if x > 0 else []) for d in wg])])
+        return i
+
+    def bn(self, x, name="bn", eps=1e-5):
+        shp = self.shape_of(x)
+        C = shp[-1]
+        g = self.param(name + ".gamma", (C,))
+        b = self.param(name + ".beta", (C,))
+        i = self._add("bn", [x], [g, b], shp, eps=eps)
+        by = self._bytes(i)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="oop", ws=0, cost=3 * by * c),
+                          dict(algo="inplace", ws=0, cost=3 * by * c, inplace=1)]
+        self._pending_bops(i, [("bn_bwd", [dict(algo="from_input", deps=[x] if x > 0 else [], ws=0, cost=5 * by * c),
+                                            dict(algo="from_output", deps=[i], ws=0, cost=5 * by * c)])])
+        return i
+
+    def relu(self, x, six=False):
+        shp = self.shape_of(x)
+        op = "relu6" if six else "relu"
+        i = self._add(op, [x], [], shp)
+        words = (numel(shp) + 63) // 64
+        m = self._add("mask", [i], [], (words,))
+        by = self._bytes(i)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="oop", ws=0, cost=2 * by * c),
+                          dict(algo="inplace", ws=0, cost=2 * by * c, inplace=1)]
+        self._pending_bops(i, [(op + "_bwd", [dict(algo="from_input", deps=[x] if x > 0 else [], ws=0, cost=3 * by * c),
+                                               dict(algo="from_output", deps=[i], ws=0, cost=3 * by * c),
+                                               dict(algo="from_mask", deps=[m], ws=0, cost=(2 + 1 / 32) * by * c)])])
+        return i
+
+    def maxpool(self, x, k, stride, pad=0):
+        N, H, W, C = self.shape_of(x)
+        P = (H + 2 * pad - k) // stride + 1
+        Q = (W + 2 * pad - k) // stride + 1
+        i = self._add("maxpool", [x], [], (N, P, Q, C), k=k, stride=stride, pad=pad)
+        ix = self._add("poolidx", [i], [], (N, P, Q, C))
+        bi, bo = self._bytes(x), self._bytes(i)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="direct", ws=0, cost=(bi + bo) * c)]
+        self._pending_bops(i, [("maxpool_bwd", [dict(algo="from_input", deps=[x] if x > 0 else [], ws=0, cost=(2 * bi + bo) * c),
+                                                 dict(algo="from_index", deps=[ix], ws=0, cost=(bi + 1.25 * bo) * c)])])
+        return i
+
+    def add(self, a, b):
+        shp = self.shape_of(a)
+        assert shp == self.shape_of(b)
+        i = self._add("add", [a, b], [], shp)
+        by = self._bytes(i)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="oop", ws=0, cost=3 * by * c)]
+        self._pending_bops(i, [("add_bwd", [dict(algo="copy", deps=[], ws=0, cost=4 * by * c)])])
+        return i
+
+    def avgpool(self, x):
+        N, H, W, C = self.shape_of(x)
+        i = self._add("avgpool", [x], [], (N, C))
+        by = self._bytes(x)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="direct", ws=0, cost=by * c)]
+        self._pending_bops(i, [("avgpool_bwd", [dict(algo="direct", deps=[], ws=0, cost=by * c)])])
+        return i
+
+    def linear(self, x, out, name="fc"):
+        N, I = self.shape_of(x)
+        w = self.param(name + ".w", (out, I))
+        b = self.param(name + ".b", (out,))
+        i = self._add("linear", [x], [w, b], (N, out))
+        flop = 2.0 * N * I * out
+        self.fimpls[i] = [dict(algo="gemm", ws=0, cost=flop)]
+        self._pending_bops(i, [("linear_dgrad", [dict(algo="gemm", deps=[], ws=0, cost=flop)])] if x > 0 else [],
+                           [("linear_wgrad", [dict(algo="gemm", deps=[x] if x > 0 else [], ws=0, cost=flop)])])
+        return i
+
+    def softmaxce(self, x, labels):
+        i = self._add("softmaxce", [x, labels], [], (1,), persist=1)
+        by = self._bytes(x)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="direct", ws=0, cost=by * c)]
+        self._pending_bops(i, [("softmaxce_bwd", [dict(algo="direct", deps=[x], ws=0, cost=2 * by * c)])])
+        return i
+
+    def sumloss(self, x):
+        i = self._add("sumloss", [x], [], (1,), persist=1)
+        by = self._bytes(x)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="direct", ws=0, cost=by * c)]
+        self._pending_bops(i, [("sumloss_bwd", [dict(algo="fill", deps=[], ws=0, cost=by * c)])])
+        return i
+
+    def _pending_bops(self, node, *groups):
+        for grp in groups:
+            for kind, impls in grp:
+                k = len(self.bops) + 1
+                self.bops.append(dict(k=k, kind=kind, node=node))
+                self.bimpls[k] = impls
+
+    # ---- lookups used by schedule helpers -----------------------------
+    def is_aux(self, i):
+        return self.nodes[i - 1].op in self.AUX_OPS
+
+    def aux_of(self, i):
+        """Aux node created by node i, or 0."""
+        if i < len(self.nodes) and self.nodes[i].op in self.AUX_OPS and self.nodes[i].ins == [i]:
+            return i + 1
+        return 0
+
+    def bops_of(self, node):
+        return [b for b in self.bops if b["node"] == node]
+
+    def fimpl_index(self, i, algo):
+        for l, d in enumerate(self.fimpls.get(i, [])):
+            if d["algo"] == algo:
+                return l
+        raise KeyError((i, algo))
+
+    def bimpl_index(self, k, algo, **match):
+        for l, d in enumerate(self.bimpls[k]):
+            if d["algo"] == algo and all(d.get(a) == v for a, v in match.items()):
+                return l
+        raise KeyError((k, algo, match))
+
+    # ---- text ---------------------------------------------------------
+    def text(self):
+        out = ["monet-graph 1"]
+        for ref, name, dt, shp in self.exts:
+            out.append(f"ext {ref} {name} {dt} {_dims(shp)}")
+        for pid, name, shp in self.params:
+            out.append(f"param {pid} {name} {_dims(shp)}")
+        for n in self.nodes:
+            ins = ",".join(str(r) for r in n.ins)
+            par = ",".join(str(p) for p in n.pars) if n.pars else "-"
+            rec = f"node {n.id} {n.op} in={ins} par={par} shape={_dims(n.shape)}"
+            for k, v in n.attrs.items():
+                rec += f" {k}={v!r}" if isinstance(v, float) else f" {k}={v}"
+            out.append(rec)
+        for i in sorted(self.fimpls):
+            for l, d in enumerate(self.fimpls[i]):
+                rec = f"fimpl {i} {l} algo={d['algo']} ws={int(d['ws'])} cost={float(d['cost'])!r}"
+                for k, v in d.items():
+                    if k not in ("algo", "ws", "cost"):
+                        rec += f" {k}={v}"
+                out.append(rec)
+        for b in self.bops:
+            out.append(f"bop {b['k']} {b['kind']} node={b['node']}")
+        for k in sorted(self.bimpls):
+            for l, d in enumerate(self.bimpls[k]):
+                deps = ",".join(str(r) for r in d["deps"]) if d["deps"] else "-"
+                rec = f"bimpl {k} {l} algo={d['algo']} deps={deps} ws={int(d['ws'])} cost={float(d['cost'])!r}"
+                for kk, v in d.items():
+                    if kk not in ("algo", "ws", "cost", "deps"):
+                        rec += f" {kk}={v}"
+                out.append(rec)
+        return "\n".join(out) + "\n"
+
+
+def _align(b, a=256):
+    return (int(b) + a - 1) // a * a
+
+
+# ----------------------------------------------------------------------
+# networks
+# ----------------------------------------------------------------------
+def tiny_chain(batch=2, hw=16, channels=16, blocks=4, wgrad_splits=(4,)):
+    """Chain of conv3x3(s1,p1)-BN-ReLU blocks with a sum-of-outputs loss."""
+    g = Graph()
+    x = g.ext("x", "f32", (batch, hw, hw, channels))
+    a = x
+    for b in range(blocks):
+        g.begin_block(f"b{b}")
+        c = g.conv(a, channels, 3, stride=1, pad=1, name=f"conv{b}", wgrad_splits=wgrad_splits)
+        n = g.bn(c, name=f"bn{b}")
+        a = g.relu(n)
+        g.end_block()
+    g.sumloss(a)
+    return g
+
+
+def resnet50(batch=184, hw=224, classes=1000, widths=(64, 128, 256, 512), depths=(3, 4, 6, 3), stem=64,
+             wgrad_splits=None):
+    """Bottleneck ResNet (v1.5: stride on the 3x3), softmax cross-entropy loss."""
+    g = Graph()
+    x = g.ext("x", "f32", (batch, hw, hw, 3))
+    labels = g.ext("labels", "i32", (batch,))
+
+    def splits_for(ref_in, K, R, stride, pad):
+        if wgrad_splits is not None:
+            return wgrad_splits
+        N, H, W, C = g.shape_of(ref_in)
+        P = (H + 2 * pad - R) // stride + 1
+        M = N * P * P
+        tiles = math.ceil(K / 128) * math.ceil(C * R * R / 128)
+        sp = max(1, min(256, math.ceil(1024 / tiles), M // 512))
+        return (sp,)
+
+    def cbr(a, K, R, stride, pad, name, relu=True):
+        c = g.conv(a, K, R, stride=stride, pad=pad, name=name, wgrad_splits=splits_for(a, K, R, stride, pad))
+        n = g.bn(c, name=name.replace("conv", "bn"))
+        return g.relu(n) if relu else n
+
+    g.begin_block("stem")
+    a = cbr(x, stem, 7, 2, 3, "stem.conv")
+    a = g.maxpool(a, 3, 2, 1)
+    g.end_block()
+    for si, (wd, dp) in enumerate(zip(widths, depths)):
+        for bi in range(dp):
+            stride = 2 if (bi == 0 and si > 0) else 1
+            g.begin_block(f"l{si + 1}b{bi}")
+            nm = f"l{si + 1}b{bi}"
+            h = cbr(a, wd, 1, 1, 0, nm + ".conv1")
+            h = cbr(h, wd, 3, stride, 1, nm + ".conv2")
+            h = cbr(h, wd * 4, 1, 1, 0, nm + ".conv3", relu=False)
+            if bi == 0:
+                sk = cbr(a, wd * 4, 1, stride, 0, nm + ".convd", relu=False)
+            else:
+                sk = a
+            s = g.add(h, sk)
+            a = g.relu(s)
+            g.end_block()
+    g.begin_block("head")
+    p = g.avgpool(a)
+    f = g.linear(p, classes, name="fc")
+    g.softmaxce(f, labels)
+    g.end_block()
+    return g
