@@ -1,0 +1,69 @@
+/*
+ * monet_kernels.h -- C ABI of the individual gfx950 operator kernels that monet_step runs.
+ *
+ * These are the operator implementations the schedule selects between (the paper's
+ * Appendix D, "Operator optimizations": output-activated BatchNorm / ReLU backward,
+ * ReLU backward from a 1-bit sign code, max-pool backward from an 8-bit window index,
+ * convolution with selectable workspace, in-place activations; Appendix D also splits
+ * the convolution backward into a parameter-gradient and an input-gradient operator).
+ * Exported so that each kernel can be checked and timed on its own.
+ *
+ * All pointers are device pointers owned by the caller; activations N,H,W,C fp32,
+ * filters K,R,S,C.  `stream` is a hipStream_t (NULL = default stream).  Calls only
+ * enqueue work.  Return 0, or a negative monet_status with monet_last_error() set.
+ */
+#ifndef MONET_KERNELS_H
+#define MONET_KERNELS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* y[N,P,Q,K] = cross-correlation of x[N,H,W,C] with w[K,R,S,C], zero padding, no bias. */
+int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
+                   int N, int H, int W, int C, int K, int R, int S, int stride, int pad);
+/* dx[N,H,W,C] (+)= gradient of the above wrt x, from dy[N,P,Q,K]. */
+int monet_conv_dgrad(void *stream, const float *dy, const float *w, float *dx,
+                     int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int accumulate);
+/* dw[K,R,S,C] = gradient wrt w.  splits == 1: no workspace.  splits > 1: the sum over N,P,Q is cut
+ * into `splits` ranges whose partial results go to ws (>= splits*K*R*S*C floats) and are then added
+ * in range order. */
+int monet_conv_wgrad(void *stream, const float *x, const float *dy, float *dw,
+                     int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                     int splits, float *ws, size_t ws_bytes);
+
+/* BatchNorm over rows x C (rows = N*H*W): stats = mean[C] then 1/sqrt(var+eps)[C], biased variance.
+ * scratch: >= 4 MiB of device memory for slab partials. */
+int monet_bn_stats(void *stream, const float *x, float *stats, int64_t rows, int C, float eps,
+                   float *scratch, size_t scratch_bytes);
+/* y = gamma*(x-mean)*invstd + beta; y may alias x (in-place variant). */
+int monet_bn_apply(void *stream, const float *x, float *y, const float *gamma, const float *beta,
+                   const float *stats, int64_t rows, int C);
+/* t = BatchNorm input (from_output = 0) or its own output (from_output = 1, needs gamma != 0). */
+int monet_bn_bwd(void *stream, const float *dy, const float *t, int from_output,
+                 const float *gamma, const float *beta, const float *stats,
+                 float *dx, float *dgamma, float *dbeta, int64_t rows, int C, int accumulate,
+                 float *scratch, size_t scratch_bytes);
+
+/* y = max(x,0) (six: min(.,6)); mask (may be NULL) gets one bit per element, ceil(n/64) words. y may alias x. */
+int monet_relu_fwd(void *stream, const float *x, float *y, uint64_t *mask, int64_t n, int six);
+/* mode 0: t = forward input, 1: t = forward output, 2: t = packed mask. */
+int monet_relu_bwd(void *stream, const float *dz, const void *t, int mode, float *dx, int64_t n, int six, int accumulate);
+
+/* k x k max pool; idx (may be NULL) gets r*k+s of the first maximum per output element. */
+int monet_maxpool_fwd(void *stream, const float *x, float *y, uint8_t *idx,
+                      int N, int H, int W, int C, int k, int stride, int pad);
+/* from idx if non-NULL, else from x. */
+int monet_maxpool_bwd(void *stream, const float *dy, const float *x, const uint8_t *idx, float *dx,
+                      int N, int H, int W, int C, int k, int stride, int pad, int accumulate);
+
+/* plain device copy, for bandwidth calibration */
+int monet_copy(void *stream, const float *src, float *dst, int64_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONET_KERNELS_H */

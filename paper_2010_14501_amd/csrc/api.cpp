@@ -1,0 +1,388 @@
+// extern "C" boundary: plan handling, the step executor (Algorithm 1 then Algorithm 2, as
+// lowered by plan.cpp into a launch list) and the per-kernel entry points.
+#include <cmath>
+#include <cstring>
+#include <string>
+
+#include "../../include/monet.h"
+#include "../../include/monet_kernels.h"
+#include "kernels.hpp"
+#include "plan.hpp"
+
+using namespace monet;
+
+static thread_local std::string g_err;
+
+struct monet_plan {
+    Plan plan;
+    char *base = nullptr;      // device memory bound by the caller
+    size_t bound_bytes = 0;
+    bool poison = false;
+    int64_t stop_after = -1;
+    bool stats_valid = false;  // BatchNorm statistics are written by the first forward of a step
+};
+
+template <class F>
+static int guarded(F &&f) {
+    try {
+        f();
+        return MONET_OK;
+    } catch (const PlanError &e) {
+        g_err = e.what();
+        return e.code;
+    } catch (const KernelError &e) {
+        g_err = e.what();
+        return MONET_HIP_ERROR;
+    } catch (const std::exception &e) {
+        g_err = e.what();
+        return MONET_BAD_ARGUMENT;
+    }
+}
+
+extern "C" const char *monet_last_error(void) { return g_err.c_str(); }
+
+extern "C" int monet_plan_load(const char *graph, size_t graph_len, const char *schedule, size_t schedule_len, monet_plan **out) {
+    if (!graph || !schedule || !out) { g_err = "monet_plan_load: null argument"; return MONET_BAD_ARGUMENT; }
+    *out = nullptr;
+    monet_plan *p = nullptr;
+    int rc = guarded([&] {
+        p = new monet_plan();
+        p->plan.build(std::string(graph, graph_len), std::string(schedule, schedule_len));
+    });
+    if (rc != MONET_OK) { delete p; return rc; }
+    *out = p;
+    return MONET_OK;
+}
+
+extern "C" void monet_free(monet_plan *p) { delete p; }
+extern "C" int64_t monet_plan_exact_peak(const monet_plan *p) { return p ? p->plan.exact_peak : MONET_BAD_ARGUMENT; }
+extern "C" int64_t monet_plan_predicted_peak(const monet_plan *p) { return p ? p->plan.predicted_peak : MONET_BAD_ARGUMENT; }
+extern "C" int64_t monet_plan_arena_bytes(const monet_plan *p) { return p ? p->plan.persistent_bytes + p->plan.dynamic_bytes : MONET_BAD_ARGUMENT; }
+extern "C" int64_t monet_plan_persistent_bytes(const monet_plan *p) { return p ? p->plan.persistent_bytes : MONET_BAD_ARGUMENT; }
+extern "C" int monet_plan_num_params(const monet_plan *p) { return p ? (int)p->plan.g.params.size() : MONET_BAD_ARGUMENT; }
+extern "C" int monet_plan_num_inputs(const monet_plan *p) { return p ? (int)p->plan.g.exts.size() : MONET_BAD_ARGUMENT; }
+
+extern "C" int monet_plan_bind_arena(monet_plan *p, void *dev_base, size_t bytes) {
+    if (!p || !dev_base) { g_err = "monet_plan_bind_arena: null argument"; return MONET_BAD_ARGUMENT; }
+    if (((uintptr_t)dev_base) % kAlign) { g_err = "monet_plan_bind_arena: base must be 256-byte aligned"; return MONET_BAD_ARGUMENT; }
+    if ((int64_t)bytes < p->plan.persistent_bytes + p->plan.dynamic_bytes) {
+        g_err = "monet_plan_bind_arena: " + std::to_string(bytes) + " bytes bound, " +
+                std::to_string(p->plan.persistent_bytes + p->plan.dynamic_bytes) + " needed";
+        return MONET_ARENA_TOO_SMALL;
+    }
+    p->base = (char *)dev_base;
+    p->bound_bytes = bytes;
+    return MONET_OK;
+}
+
+extern "C" int monet_plan_trace(const monet_plan *p, const monet_event **events, size_t *count) {
+    if (!p || !events || !count) { g_err = "monet_plan_trace: null argument"; return MONET_BAD_ARGUMENT; }
+    *events = p->plan.events.data();
+    *count = p->plan.events.size();
+    return MONET_OK;
+}
+
+extern "C" int monet_plan_set_poison(monet_plan *p, int on) {
+    if (!p) return MONET_BAD_ARGUMENT;
+    p->poison = on != 0;
+    return MONET_OK;
+}
+
+extern "C" int monet_plan_set_stop_after(monet_plan *p, int64_t event_index) {
+    if (!p) return MONET_BAD_ARGUMENT;
+    p->stop_after = event_index;
+    return MONET_OK;
+}
+
+extern "C" int64_t monet_plan_tensor_offset(const monet_plan *p, size_t event_index, int node, int is_grad) {
+    if (!p) return MONET_BAD_ARGUMENT;
+    const Plan &pl = p->plan;
+    for (size_t i = 0; i < pl.launches.size(); ++i)
+        if (pl.launches[i].event == event_index) {
+            auto it = pl.where[i].find({node, is_grad ? 1 : 0});
+            return it == pl.where[i].end() ? -1 : pl.persistent_bytes + it->second;
+        }
+    return -1;
+}
+
+extern "C" int64_t monet_plan_bn_stats_offset(const monet_plan *p, int node) {
+    if (!p) return MONET_BAD_ARGUMENT;
+    auto it = p->plan.bn_stats_off.find(node);
+    return it == p->plan.bn_stats_off.end() ? -1 : it->second;
+}
+
+// ------------------------------------------------------------------ the step
+namespace {
+
+struct StepCtx {
+    monet_plan *mp;
+    hipStream_t st;
+    const void *const *inputs;
+    const float *const *weights;
+    float *const *grads;
+    char *arena() const { return mp->base + mp->plan.persistent_bytes; }
+    void *ptr(const Ref &r) const {
+        switch (r.region) {
+            case R_ARENA: return arena() + r.off;
+            case R_EXT: return const_cast<void *>(inputs[r.off]);
+            case R_PERSIST: return mp->base + r.off;
+            default: return nullptr;
+        }
+    }
+    float *scratch() const { return (float *)(mp->base + mp->plan.scratch_off); }
+    size_t scratch_bytes() const { return (size_t)mp->plan.scratch_bytes; }
+    float *bn_stats(int node) const { return (float *)(mp->base + mp->plan.bn_stats_off.at(node)); }
+};
+
+ConvShape conv_shape(const Graph &g, const Node &n) {
+    const auto &is = g.shape_of(n.ins[0]);
+    ConvShape cs;
+    cs.N = (int)is[0]; cs.H = (int)is[1]; cs.W = (int)is[2]; cs.C = (int)is[3];
+    cs.K = (int)n.shape[3]; cs.R = n.attr_int("R"); cs.S = n.attr_int("S");
+    cs.stride = n.attr_int("stride", 1); cs.pad = n.attr_int("pad", 0);
+    cs.P = (int)n.shape[1]; cs.Q = (int)n.shape[2];
+    return cs;
+}
+ConvShape linear_shape(const Graph &g, const Node &n) {   // a linear layer is a 1x1 convolution on a 1x1 image
+    const auto &is = g.shape_of(n.ins[0]);
+    ConvShape cs;
+    cs.N = (int)is[0]; cs.H = 1; cs.W = 1; cs.C = (int)is[1];
+    cs.K = (int)n.shape[1]; cs.R = 1; cs.S = 1; cs.stride = 1; cs.pad = 0; cs.P = 1; cs.Q = 1;
+    return cs;
+}
+PoolShape pool_shape(const Graph &g, const Node &n) {
+    const auto &is = g.shape_of(n.ins[0]);
+    PoolShape ps;
+    ps.N = (int)is[0]; ps.H = (int)is[1]; ps.W = (int)is[2]; ps.C = (int)is[3];
+    ps.k = n.attr_int("k"); ps.stride = n.attr_int("stride", 1); ps.pad = n.attr_int("pad", 0);
+    ps.P = (int)n.shape[1]; ps.Q = (int)n.shape[2];
+    return ps;
+}
+int64_t numel_of(const std::vector<int64_t> &s) {
+    int64_t n = 1;
+    for (auto d : s) n *= d;
+    return n;
+}
+
+void run_forward(const StepCtx &c, const Launch &L) {
+    const Graph &g = c.mp->plan.g;
+    const Node &n = g.nodes[L.id];
+    const float *in0 = (const float *)c.ptr(L.a[0]);
+    float *out = (float *)c.ptr(L.a[2]);
+    const std::string &op = n.op;
+    if (op == "conv") {
+        conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n));
+    } else if (op == "bn") {
+        int C = (int)n.shape.back();
+        int64_t rows = numel_of(n.shape) / C;
+        float *stats = c.bn_stats(L.id);
+        // statistics are computed by the forward pass and reused when the node is recomputed
+        if (L.kind == EV_RUN_FWD) bn_stats(c.st, in0, stats, rows, C, (float)n.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
+        bn_apply(c.st, in0, out, c.weights[n.pars[0]], c.weights[n.pars[1]], stats, rows, C);
+    } else if (op == "relu" || op == "relu6") {
+        relu_fwd(c.st, in0, out, (L.flags & 2) ? (uint64_t *)c.ptr(L.a[3]) : nullptr, numel_of(n.shape), op == "relu6");
+    } else if (op == "maxpool") {
+        maxpool_fwd(c.st, in0, out, (L.flags & 2) ? (uint8_t *)c.ptr(L.a[3]) : nullptr, pool_shape(g, n));
+    } else if (op == "add") {
+        add_fwd(c.st, in0, (const float *)c.ptr(L.a[1]), out, numel_of(n.shape));
+    } else if (op == "avgpool") {
+        const auto &is = g.shape_of(n.ins[0]);
+        avgpool_fwd(c.st, in0, out, (int)is[0], (int)(is[1] * is[2]), (int)is[3]);
+    } else if (op == "linear") {
+        const auto &is = g.shape_of(n.ins[0]);
+        linear_fwd(c.st, in0, c.weights[n.pars[0]], c.weights[n.pars[1]], out, (int)is[0], (int)is[1], (int)n.shape[1]);
+    } else if (op == "softmaxce") {
+        const auto &is = g.shape_of(n.ins[0]);
+        softmaxce_fwd(c.st, in0, (const int32_t *)c.ptr(L.a[1]), out, (int)is[0], (int)is[1], c.scratch());
+    } else if (op == "sumloss") {
+        sumloss_fwd(c.st, in0, out, numel_of(g.shape_of(n.ins[0])), c.scratch(), c.scratch_bytes());
+    } else {
+        throw KernelError("no kernel for forward operator " + op);
+    }
+}
+
+void run_backward(const StepCtx &c, const Launch &L) {
+    const Graph &g = c.mp->plan.g;
+    const Bop &b = g.bops[L.id];
+    const Node &n = g.nodes[b.node];
+    const BwdImpl &im = b.impls[L.impl];
+    const float *gy = (const float *)c.ptr(L.a[0]);
+    const void *dep = c.ptr(L.a[1]);
+    float *d0 = (float *)c.ptr(L.a[2]);
+    const bool acc0 = L.flags & 1;
+    const std::string &kd = b.kind;
+    if (kd == "conv_wgrad") {
+        int splits = 1;
+        if (im.algo == "splitk") {
+            auto it = im.extra.find("splits");
+            if (it == im.extra.end()) throw KernelError("splitk implementation without a 'splits' field");
+            splits = std::stoi(it->second);
+        }
+        conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits, (float *)c.ptr(L.a[4]),
+                   (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+    } else if (kd == "conv_dgrad") {
+        conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0);
+    } else if (kd == "bn_bwd") {
+        int C = (int)n.shape.back();
+        int64_t rows = numel_of(n.shape) / C;
+        bn_bwd(c.st, gy, (const float *)dep, im.algo == "from_output", c.weights[n.pars[0]], c.weights[n.pars[1]], c.bn_stats(b.node), d0,
+               c.grads[n.pars[0]], c.grads[n.pars[1]], rows, C, acc0, c.scratch(), c.scratch_bytes());
+    } else if (kd == "relu_bwd" || kd == "relu6_bwd") {
+        int mode = im.algo == "from_input" ? RELU_FROM_INPUT : (im.algo == "from_output" ? RELU_FROM_OUTPUT : RELU_FROM_MASK);
+        relu_bwd(c.st, gy, dep, mode, d0, numel_of(n.shape), kd == "relu6_bwd", acc0);
+    } else if (kd == "maxpool_bwd") {
+        bool from_idx = im.algo == "from_index";
+        maxpool_bwd(c.st, gy, from_idx ? nullptr : (const float *)dep, from_idx ? (const uint8_t *)dep : nullptr, d0, pool_shape(g, n), acc0);
+    } else if (kd == "add_bwd") {
+        int64_t cnt = numel_of(n.shape);
+        if (n.ins[0] > 0) copy_or_accumulate(c.st, gy, d0, cnt, acc0);
+        if (n.ins.size() > 1 && n.ins[1] > 0) copy_or_accumulate(c.st, gy, (float *)c.ptr(L.a[3]), cnt, (L.flags & 2) != 0);
+    } else if (kd == "avgpool_bwd") {
+        const auto &is = g.shape_of(n.ins[0]);
+        avgpool_bwd(c.st, gy, d0, (int)is[0], (int)(is[1] * is[2]), (int)is[3], acc0);
+    } else if (kd == "linear_wgrad") {
+        const auto &is = g.shape_of(n.ins[0]);
+        linear_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], c.grads[n.pars[1]], (int)is[0], (int)is[1], (int)n.shape[1]);
+    } else if (kd == "linear_dgrad") {
+        const auto &is = g.shape_of(n.ins[0]);
+        linear_dgrad(c.st, gy, c.weights[n.pars[0]], d0, (int)is[0], (int)is[1], (int)n.shape[1], acc0);
+    } else if (kd == "softmaxce_bwd") {
+        const auto &is = g.shape_of(n.ins[0]);
+        Ref lab; lab.region = R_EXT; lab.off = -n.ins[1];
+        softmaxce_bwd(c.st, (const float *)dep, (const int32_t *)c.ptr(lab), d0, (int)is[0], (int)is[1], acc0);
+    } else if (kd == "sumloss_bwd") {
+        int64_t cnt = numel_of(g.shape_of(n.ins[0]));
+        if (acc0) throw KernelError("sumloss_bwd cannot accumulate");
+        fill_f32(c.st, d0, cnt, 1.0f);
+    } else {
+        throw KernelError("no kernel for backward operator " + kd);
+    }
+}
+
+}  // namespace
+
+extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const *inputs, const float *const *weights,
+                              float *const *grads, float *dev_loss) {
+    if (!p || !inputs || !weights || !grads) { g_err = "monet_step: null argument"; return MONET_BAD_ARGUMENT; }
+    if (!p->base) { g_err = "monet_step: no arena bound"; return MONET_ARENA_TOO_SMALL; }
+    int64_t peak = 0;
+    int rc = guarded([&] {
+        const Plan &pl = p->plan;
+        StepCtx c{p, (hipStream_t)hip_stream, inputs, weights, grads};
+        // arena accounting: replay the trace's alloc/free records against the launches
+        int64_t live = 0;
+        size_t next_event = 0, next_poison = 0;
+        for (size_t li = 0; li < pl.launches.size(); ++li) {
+            const Launch &L = pl.launches[li];
+            if (p->stop_after >= 0 && (int64_t)L.event > p->stop_after) break;
+            for (; next_event <= L.event; ++next_event) {
+                const monet_event &e = pl.events[next_event];
+                if (e.kind == EV_ALLOC) live += e.bytes;
+                else if (e.kind == EV_FREE) live -= e.bytes;
+                if (live != e.live_after) throw KernelError("arena accounting diverged from the plan");
+                peak = std::max(peak, live);
+            }
+            if (p->poison)
+                for (; next_poison < pl.poison.size() && pl.poison[next_poison].before_launch <= li; ++next_poison)
+                    fill_u32(c.st, (uint32_t *)(c.arena() + pl.poison[next_poison].off), pl.poison[next_poison].bytes / 4, 0x7fc00000u);
+            if (L.kind == EV_RUN_BWD) run_backward(c, L);
+            else run_forward(c, L);
+        }
+        if (p->stop_after < 0) {
+            for (; next_event < pl.events.size(); ++next_event) {
+                const monet_event &e = pl.events[next_event];
+                if (e.kind == EV_ALLOC) live += e.bytes;
+                else if (e.kind == EV_FREE) live -= e.bytes;
+                peak = std::max(peak, live);
+            }
+            if (live != 0) throw KernelError("arena not empty at the end of the step");
+        }
+        if (dev_loss)
+            hip_check(hipMemcpyAsync(dev_loss, p->base + pl.loss_off, 4, hipMemcpyDeviceToDevice, c.st), "loss copy");
+    });
+    return rc == MONET_OK ? peak : rc;
+}
+
+// ------------------------------------------------------------------ linear layer = 1x1 convolution + bias
+namespace monet {
+
+void linear_bias_add(hipStream_t st, float *y, const float *b, int N, int out);
+void linear_bias_grad(hipStream_t st, const float *dy, float *db, int N, int out);
+
+void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out) {
+    ConvShape cs{N, 1, 1, in, out, 1, 1, 1, 0, 1, 1};
+    conv_fwd(st, x, w, y, cs);
+    linear_bias_add(st, y, b, N, out);
+}
+void linear_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, float *db, int N, int in, int out) {
+    ConvShape cs{N, 1, 1, in, out, 1, 1, 1, 0, 1, 1};
+    conv_wgrad(st, x, dy, dw, cs, 1, nullptr, 0);
+    linear_bias_grad(st, dy, db, N, out);
+}
+void linear_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, int N, int in, int out, bool accumulate) {
+    ConvShape cs{N, 1, 1, in, out, 1, 1, 1, 0, 1, 1};
+    conv_dgrad(st, dy, w, dx, cs, accumulate);
+}
+
+}  // namespace monet
+
+// ------------------------------------------------------------------ per-kernel entry points
+static ConvShape mk_conv(int N, int H, int W, int C, int K, int R, int S, int stride, int pad) {
+    ConvShape cs{N, H, W, C, K, R, S, stride, pad, 0, 0};
+    if (stride > 0) {
+        cs.P = (H + 2 * pad - R) / stride + 1;
+        cs.Q = (W + 2 * pad - S) / stride + 1;
+    }
+    return cs;
+}
+static PoolShape mk_pool(int N, int H, int W, int C, int k, int stride, int pad) {
+    PoolShape ps{N, H, W, C, k, stride, pad, 0, 0};
+    if (stride > 0) {
+        ps.P = (H + 2 * pad - k) / stride + 1;
+        ps.Q = (W + 2 * pad - k) / stride + 1;
+    }
+    return ps;
+}
+
+extern "C" int monet_conv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
+                              int stride, int pad) {
+    return guarded([&] { conv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad)); });
+}
+extern "C" int monet_conv_dgrad(void *stream, const float *dy, const float *w, float *dx, int N, int H, int W, int C, int K, int R, int S,
+                                int stride, int pad, int accumulate) {
+    return guarded([&] { conv_dgrad((hipStream_t)stream, dy, w, dx, mk_conv(N, H, W, C, K, R, S, stride, pad), accumulate != 0); });
+}
+extern "C" int monet_conv_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R, int S,
+                                int stride, int pad, int splits, float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, R, S, stride, pad), splits, ws, ws_bytes); });
+}
+extern "C" int monet_bn_stats(void *stream, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch, size_t scratch_bytes) {
+    return guarded([&] { bn_stats((hipStream_t)stream, x, stats, rows, C, eps, scratch, scratch_bytes); });
+}
+extern "C" int monet_bn_apply(void *stream, const float *x, float *y, const float *gamma, const float *beta, const float *stats,
+                              int64_t rows, int C) {
+    return guarded([&] { bn_apply((hipStream_t)stream, x, y, gamma, beta, stats, rows, C); });
+}
+extern "C" int monet_bn_bwd(void *stream, const float *dy, const float *t, int from_output, const float *gamma, const float *beta,
+                            const float *stats, float *dx, float *dgamma, float *dbeta, int64_t rows, int C, int accumulate,
+                            float *scratch, size_t scratch_bytes) {
+    return guarded([&] {
+        bn_bwd((hipStream_t)stream, dy, t, from_output != 0, gamma, beta, stats, dx, dgamma, dbeta, rows, C, accumulate != 0, scratch, scratch_bytes);
+    });
+}
+extern "C" int monet_relu_fwd(void *stream, const float *x, float *y, uint64_t *mask, int64_t n, int six) {
+    return guarded([&] { relu_fwd((hipStream_t)stream, x, y, mask, n, six != 0); });
+}
+extern "C" int monet_relu_bwd(void *stream, const float *dz, const void *t, int mode, float *dx, int64_t n, int six, int accumulate) {
+    return guarded([&] { relu_bwd((hipStream_t)stream, dz, t, mode, dx, n, six != 0, accumulate != 0); });
+}
+extern "C" int monet_maxpool_fwd(void *stream, const float *x, float *y, uint8_t *idx, int N, int H, int W, int C, int k, int stride, int pad) {
+    return guarded([&] { maxpool_fwd((hipStream_t)stream, x, y, idx, mk_pool(N, H, W, C, k, stride, pad)); });
+}
+extern "C" int monet_maxpool_bwd(void *stream, const float *dy, const float *x, const uint8_t *idx, float *dx, int N, int H, int W, int C,
+                                 int k, int stride, int pad, int accumulate) {
+    return guarded([&] { maxpool_bwd((hipStream_t)stream, dy, x, idx, dx, mk_pool(N, H, W, C, k, stride, pad), accumulate != 0); });
+}
+extern "C" int monet_copy(void *stream, const float *src, float *dst, int64_t n) {
+    return guarded([&] { copy_or_accumulate((hipStream_t)stream, src, dst, n, false); });
+}

@@ -1,0 +1,85 @@
+// Launchers of the gfx950 kernels.  Plain device pointers and sizes; every launch goes to
+// the given stream and returns without synchronising.  Host-side shape checks throw
+// KernelError before anything is enqueued.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <stdexcept>
+#include <string>
+
+namespace monet {
+
+struct KernelError : std::runtime_error {
+    using std::runtime_error::runtime_error;
+};
+
+inline void hip_check(hipError_t e, const char *what) {
+    if (e != hipSuccess) throw KernelError(std::string(what) + ": " + hipGetErrorString(e));
+}
+
+struct ConvShape {
+    int N, H, W, C;      // input  N,H,W,C
+    int K, R, S;         // filter K,R,S,C
+    int stride, pad;
+    int P, Q;            // output N,P,Q,K
+    __host__ __device__ int64_t M() const { return (int64_t)N * P * Q; }
+    __host__ __device__ int64_t RSC() const { return (int64_t)R * S * C; }
+};
+
+// ---- convolution (implicit GEMM on fp32 MFMA)
+void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);
+// dx (+)= transpose-conv of dy with w
+void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate);
+// dw = sum over N,P,Q; splits > 1 needs ws of splits*K*R*S*C floats (partial sums, reduced in split order)
+void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws,
+                size_t ws_bytes);
+
+// ---- BatchNorm over rows x C (rows = N*H*W), training mode, biased variance
+constexpr int64_t kBnScratchFloats = 1 << 20;
+// stats = mean[C] followed by invstd[C]; scratch holds per-slab partials
+void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch,
+              size_t scratch_bytes);
+void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, const float *beta, const float *stats,
+              int64_t rows, int C);
+// t is the BatchNorm input (from_output = false) or its own output (true)
+void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, const float *gamma, const float *beta,
+            const float *stats, float *dx, float *dgamma, float *dbeta, int64_t rows, int C, bool accumulate,
+            float *scratch, size_t scratch_bytes);
+
+// ---- ReLU / ReLU6; mask may be null; y may alias x
+void relu_fwd(hipStream_t st, const float *x, float *y, uint64_t *mask, int64_t n, bool six);
+enum ReluBwdMode { RELU_FROM_INPUT = 0, RELU_FROM_OUTPUT = 1, RELU_FROM_MASK = 2 };
+void relu_bwd(hipStream_t st, const float *dz, const void *t, int mode, float *dx, int64_t n, bool six, bool accumulate);
+
+// ---- pooling
+struct PoolShape {
+    int N, H, W, C, k, stride, pad, P, Q;
+};
+void maxpool_fwd(hipStream_t st, const float *x, float *y, uint8_t *idx, const PoolShape &ps);
+// from x (idx == null) or from the stored window index
+void maxpool_bwd(hipStream_t st, const float *dy, const float *x, const uint8_t *idx, float *dx, const PoolShape &ps,
+                 bool accumulate);
+void avgpool_fwd(hipStream_t st, const float *x, float *y, int N, int HW, int C);
+void avgpool_bwd(hipStream_t st, const float *dy, float *dx, int N, int HW, int C, bool accumulate);
+
+// ---- elementwise
+void add_fwd(hipStream_t st, const float *a, const float *b, float *y, int64_t n);
+void copy_or_accumulate(hipStream_t st, const float *src, float *dst, int64_t n, bool accumulate);
+void fill_f32(hipStream_t st, float *dst, int64_t n, float v);
+void fill_u32(hipStream_t st, uint32_t *dst, int64_t n, uint32_t v);
+
+// ---- linear layer: y[N,out] = x[N,in] w[out,in]^T + b
+void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out);
+void linear_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, float *db, int N, int in, int out);
+void linear_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, int N, int in, int out, bool accumulate);
+
+// ---- losses; scratch >= N floats
+void softmaxce_fwd(hipStream_t st, const float *logits, const int32_t *labels, float *loss, int N, int classes,
+                   float *scratch);
+void softmaxce_bwd(hipStream_t st, const float *logits, const int32_t *labels, float *dlogits, int N, int classes,
+                   bool accumulate);
+void sumloss_fwd(hipStream_t st, const float *x, float *loss, int64_t n, float *scratch, size_t scratch_bytes);
+
+}  // namespace monet

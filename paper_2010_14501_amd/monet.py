@@ -1,0 +1,155 @@
+"""ctypes binding of the C ABI in include/monet.h and include/monet_kernels.h.
+
+Argument marshalling only: every step of the path runs inside libmonet.so.  There is no
+fallback: if the library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+ALLOC, FREE, RUN_FWD, RUN_RECOMPUTE, RUN_BWD, SAVE, ALIAS = range(7)
+
+EVENT_DTYPE = np.dtype([("kind", "<i4"), ("stage", "<i4"), ("node", "<i4"), ("impl", "<i4"), ("aux", "<i4"),
+                        ("reserved", "<i4"), ("bytes", "<i8"), ("live_after", "<i8")])
+
+_LIB = None
+
+
+class MonetError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"monet error {code}: {msg}")
+        self.code = code
+
+
+def library_path():
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmonet.so")
+
+
+def load_library():
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is not built: run `python -m paper_2010_14501_amd.build`")
+    lib = C.CDLL(path)
+    vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+    lib.monet_last_error.restype = C.c_char_p
+    lib.monet_plan_load.argtypes = [C.c_char_p, sz, C.c_char_p, sz, C.POINTER(vp)]
+    lib.monet_plan_load.restype = i32
+    for name in ("monet_plan_exact_peak", "monet_plan_predicted_peak", "monet_plan_arena_bytes", "monet_plan_persistent_bytes"):
+        getattr(lib, name).argtypes = [vp]
+        getattr(lib, name).restype = i64
+    for name in ("monet_plan_num_params", "monet_plan_num_inputs"):
+        getattr(lib, name).argtypes = [vp]
+        getattr(lib, name).restype = i32
+    lib.monet_plan_bind_arena.argtypes = [vp, vp, sz]
+    lib.monet_plan_bind_arena.restype = i32
+    lib.monet_step.argtypes = [vp, vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp]
+    lib.monet_step.restype = i64
+    lib.monet_plan_trace.argtypes = [vp, C.POINTER(vp), C.POINTER(sz)]
+    lib.monet_plan_trace.restype = i32
+    lib.monet_plan_set_poison.argtypes = [vp, i32]
+    lib.monet_plan_set_poison.restype = i32
+    lib.monet_plan_set_stop_after.argtypes = [vp, i64]
+    lib.monet_plan_set_stop_after.restype = i32
+    lib.monet_plan_tensor_offset.argtypes = [vp, sz, i32, i32]
+    lib.monet_plan_tensor_offset.restype = i64
+    lib.monet_plan_bn_stats_offset.argtypes = [vp, i32]
+    lib.monet_plan_bn_stats_offset.restype = i64
+    lib.monet_free.argtypes = [vp]
+    lib.monet_free.restype = None
+    f = C.c_float
+    lib.monet_conv_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 9
+    lib.monet_conv_dgrad.argtypes = [vp, vp, vp, vp] + [i32] * 10
+    lib.monet_conv_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz]
+    lib.monet_bn_stats.argtypes = [vp, vp, vp, i64, i32, f, vp, sz]
+    lib.monet_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32]
+    lib.monet_bn_bwd.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, sz]
+    lib.monet_relu_fwd.argtypes = [vp, vp, vp, vp, i64, i32]
+    lib.monet_relu_bwd.argtypes = [vp, vp, vp, i32, vp, i64, i32, i32]
+    lib.monet_maxpool_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 7
+    lib.monet_maxpool_bwd.argtypes = [vp, vp, vp, vp, vp] + [i32] * 8
+    lib.monet_copy.argtypes = [vp, vp, vp, i64]
+    for name in ("monet_conv_fwd", "monet_conv_dgrad", "monet_conv_wgrad", "monet_bn_stats", "monet_bn_apply", "monet_bn_bwd",
+                 "monet_relu_fwd", "monet_relu_bwd", "monet_maxpool_fwd", "monet_maxpool_bwd", "monet_copy"):
+        getattr(lib, name).restype = i32
+    _LIB = lib
+    return lib
+
+
+def _check(rc):
+    if rc < 0:
+        raise MonetError(rc, load_library().monet_last_error().decode())
+    return rc
+
+
+def call(name, *args):
+    """Call a per-kernel entry point; pointers are passed as ints (e.g. tensor.data_ptr())."""
+    return _check(getattr(load_library(), name)(*args))
+
+
+def _ptr_array(ptrs):
+    arr = (C.c_void_p * len(ptrs))()
+    for i, p in enumerate(ptrs):
+        arr[i] = p
+    return arr
+
+
+class Plan:
+    """A loaded (graph, schedule) pair.  Device memory is the caller's (e.g. a torch tensor)."""
+
+    def __init__(self, graph_text, schedule_text):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        gt, st = graph_text.encode(), schedule_text.encode()
+        _check(self._lib.monet_plan_load(gt, len(gt), st, len(st), C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            self._lib.monet_free(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    exact_peak = property(lambda s: _check(s._lib.monet_plan_exact_peak(s._h)))
+    predicted_peak = property(lambda s: _check(s._lib.monet_plan_predicted_peak(s._h)))
+    arena_bytes = property(lambda s: _check(s._lib.monet_plan_arena_bytes(s._h)))
+    persistent_bytes = property(lambda s: _check(s._lib.monet_plan_persistent_bytes(s._h)))
+    num_params = property(lambda s: _check(s._lib.monet_plan_num_params(s._h)))
+    num_inputs = property(lambda s: _check(s._lib.monet_plan_num_inputs(s._h)))
+
+    def trace(self):
+        ev, n = C.c_void_p(), C.c_size_t()
+        _check(self._lib.monet_plan_trace(self._h, C.byref(ev), C.byref(n)))
+        buf = (C.c_char * (n.value * EVENT_DTYPE.itemsize)).from_address(ev.value)
+        return np.frombuffer(buf, dtype=EVENT_DTYPE).copy()
+
+    def trace_tuples(self):
+        return [(int(e["kind"]), int(e["stage"]), int(e["node"]), int(e["impl"]), int(e["aux"]), int(e["bytes"]),
+                 int(e["live_after"])) for e in self.trace()]
+
+    def bind_arena(self, dev_ptr, nbytes):
+        _check(self._lib.monet_plan_bind_arena(self._h, dev_ptr, nbytes))
+
+    def set_poison(self, on):
+        _check(self._lib.monet_plan_set_poison(self._h, 1 if on else 0))
+
+    def set_stop_after(self, event_index):
+        _check(self._lib.monet_plan_set_stop_after(self._h, event_index))
+
+    def tensor_offset(self, event_index, node, is_grad=False):
+        return self._lib.monet_plan_tensor_offset(self._h, event_index, node, 1 if is_grad else 0)
+
+    def bn_stats_offset(self, node):
+        return self._lib.monet_plan_bn_stats_offset(self._h, node)
+
+    def step(self, stream, input_ptrs, weight_ptrs, grad_ptrs, loss_ptr=None):
+        """Enqueue one training step; returns the peak logical live bytes."""
+        return _check(self._lib.monet_step(self._h, stream, _ptr_array(input_ptrs), _ptr_array(weight_ptrs),
+                                           _ptr_array(grad_ptrs), loss_ptr))

@@ -1,0 +1,120 @@
+"""Host-side checks of libmonet.so that need no GPU: every declared symbol is exported, and the
+plan lowering (event trace, exact and predicted peak, feasibility errors) agrees with the oracle's
+literal interpreter of the paper's forward/backward algorithms, record by record."""
+import itertools
+import os
+import re
+
+import pytest
+
+from oracle import schedule as osch
+from workloads import graphs, schedules
+import paper_2010_14501_amd as M
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = M.load_library()
+    names = set()
+    for hdr in ("monet.h", "monet_kernels.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(monet_[a-z0-9_]+)\s*\(", text))
+    assert len(names) >= 25
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def check_against_oracle(g, sch):
+    gt, st = g.text(), sch.text()
+    want = osch.interpret(gt, st)
+    cf = osch.closed_form(gt, st)
+    plan = M.Plan(gt, st)
+    assert plan.trace_tuples() == want["events"]
+    assert plan.exact_peak == want["peak"] == cf["exact_peak"]
+    assert plan.predicted_peak == cf["predicted_peak"]
+    assert plan.arena_bytes - plan.persistent_bytes >= plan.exact_peak
+    return plan
+
+
+def test_trace_matches_oracle_on_all_tiny_schedules():
+    g = graphs.tiny_chain()
+    for bits in itertools.product([0, 1], repeat=4):
+        C = {b for b in range(4) if bits[b]}
+        check_against_oracle(g, schedules.tiny_chain_schedule(g, C))
+        check_against_oracle(g, schedules.tiny_chain_schedule(g, C, schedules.STANDARD_VARIANTS))
+    check_against_oracle(g, schedules.store_everything_schedule(g))
+
+
+def test_trace_matches_oracle_on_resnet_shapes():
+    g = graphs.resnet50(batch=2, hw=32, classes=10, widths=(4, 8, 8, 16), depths=(2, 2, 1, 1), stem=4)
+    for sch in (schedules.store_everything_schedule(g),
+                schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS),
+                schedules.block_output_schedule(g)):
+        check_against_oracle(g, sch)
+
+
+def test_full_resnet50_plan_fragmentation_is_small():
+    g = graphs.resnet50(batch=184)
+    sch = schedules.block_output_schedule(g)
+    plan = M.Plan(g.text(), sch.text())
+    dynamic = plan.arena_bytes - plan.persistent_bytes
+    assert plan.exact_peak <= plan.predicted_peak
+    assert plan.exact_peak <= dynamic <= 1.25 * plan.exact_peak
+    store = M.Plan(g.text(), schedules.store_everything_schedule(g).text())
+    assert plan.exact_peak < 0.6 * store.exact_peak
+
+
+def _edit(text, drop=None, add=None):
+    lines = text.splitlines()
+    if drop is not None:
+        assert drop in lines, drop
+        lines.remove(drop)
+    if add is not None:
+        lines.append(add)
+    return "\n".join(lines) + "\n"
+
+
+def test_infeasible_schedules_are_rejected_with_the_constraint_named():
+    g = graphs.tiny_chain()
+    gt = g.text()
+    st = schedules.tiny_chain_schedule(g, {0, 2}).text()
+    cases = [
+        (_edit(st, drop="r 15 16 impl=-1"), "Eq.8"),
+        (_edit(st, drop="s 15 11"), "Eq.7"),
+        (_edit(st, add="s 12 5"), "Eq.7"),
+        (_edit(st, add="r 16 16 impl=-1"), "Appendix D"),
+        (_edit(_edit(st, drop="r 15 15 impl=0"), add="r 15 15 impl=1"), "C.3"),
+        (st.replace("fwd 3 impl=0 save=1", "fwd 3 impl=1 save=1"), "C.3"),
+        (_edit(st, add="r 16 2 impl=0"), "already held"),
+        (_edit(st, add="r 2 5 impl=0"), "Appendix B"),
+    ]
+    for bad, needle in cases:
+        with pytest.raises(M.MonetError) as ei:
+            M.Plan(gt, bad)
+        assert ei.value.code == -2 and needle in str(ei.value), (needle, str(ei.value))
+        with pytest.raises(osch.ScheduleError):     # the oracle rejects the same schedules
+            osch.interpret(gt, bad)
+
+
+def test_bad_text_is_a_graph_error():
+    g = graphs.tiny_chain()
+    st = schedules.tiny_chain_schedule(g, {0, 2}).text()
+    with pytest.raises(M.MonetError) as ei:
+        M.Plan("not a graph\n", st)
+    assert ei.value.code == -1
+    with pytest.raises(M.MonetError) as ei:
+        M.Plan(g.text().replace("deps=4 ", "deps=3 "), st)      # declared dependency differs from the kernel's
+    assert ei.value.code == -1
+
+
+def test_step_without_arena_is_refused():
+    g = graphs.tiny_chain()
+    plan = M.Plan(g.text(), schedules.tiny_chain_schedule(g, {0, 2}).text())
+    with pytest.raises(M.MonetError) as ei:
+        plan.step(None, [0], [0] * plan.num_params, [0] * plan.num_params)
+    assert ei.value.code == -3
+    with pytest.raises(M.MonetError) as ei:
+        plan.bind_arena(256, 1024)
+    assert ei.value.code == -3
