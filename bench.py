@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Throughput of the schedule-executed training step on one MI355X.
+
+A step is one pass of the whole hot path -- forward pass with greedy freeing and checkpoint
+saving, then the backward pass with recomputation -- of the ResNet-50-shaped network at batch
+184 (synthetic N(0,1) images, He-normal weights, uniform labels) under the block-output
+schedule with the lean operator variants, through libmonet.so.  Inputs, weights and the arena
+are resident in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_b184|tiny_chain]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3      # 256 CUs x 256 flop/clk x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+
+
+def build_workload(name):
+    from workloads import graphs, schedules
+    if name == "resnet50_b184":
+        g = graphs.resnet50(batch=184)
+        return g, schedules.block_output_schedule(g), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient"
+    if name == "tiny_chain":
+        g = graphs.tiny_chain()
+        return g, schedules.tiny_chain_schedule(g, {0, 2}), 2, "checkpoint blocks {0,2}, recompute {1,3}; lean variants"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(workload):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import network as onet
+    from workloads import graphs, tensors
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    if workload == "resnet50_b184":
+        batch = 16
+        g = graphs.resnet50(batch=batch)
+        sample = "same ResNet-50 graph at batch 16 (224x224, 1000 classes), one store-everything fp64 step"
+    else:
+        batch = 2
+        g = graphs.tiny_chain()
+        sample = "tiny chain at full size, one store-everything fp64 step"
+    exts, params = tensors.make_inputs(g, seed=0)
+    oe, op = tensors.oracle_inputs(exts, params)
+    gt = g.text()
+    t0 = time.perf_counter()
+    onet.store_everything_step(gt, oe, op)
+    dt = time.perf_counter() - t0
+    return {"value": batch / dt, "unit": "images/s", "cores": int(threads), "kind": "oracle", "sample": sample,
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet50_b184")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (the step has no collectives); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py: no GPU visible; the training step exists only as gfx950 kernels")
+    from workloads import tensors
+    from paper_2010_14501_amd.runner import StepRunner
+
+    g, sch, batch, sched_desc = build_workload(args.workload)
+    exts, params = tensors.make_inputs(g, seed=0)
+    run = StepRunner(g.text(), sch.text(), exts, params)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        run.step(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    peak = 0
+    for _ in range(args.steps):
+        peak = run.step(stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    loss = run.loss_value()
+
+    out = {
+        "metric": "train images/s at schedule peak-mem budget (ResNet-50 b184)" if args.workload == "resnet50_b184"
+        else "train images/s at schedule peak-mem budget",
+        "value": batch * args.steps / dt,
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "batch": batch, "schedule": sched_desc,
+                   "nodes": len(g.nodes), "backward_ops": len(g.bops)},
+        "peak_gb": peak / 1e9,
+        "predicted_peak_gb": run.plan.predicted_peak / 1e9,
+        "arena_gb": run.plan.arena_bytes / 1e9,
+        "loss": loss,
+    }
+
+    if not args.no_roofline:
+        # second pass over the same steps with a pair of HIP events around every operator launch
+        import numpy as np
+        info = run.plan.launches()
+        run.plan.set_timing(True)
+        tot = np.zeros(len(info))
+        n_timed = max(3, min(args.steps, 10))
+        for _ in range(n_timed):
+            run.step(stream)
+            tot += run.plan.read_timing()
+        run.plan.set_timing(False)
+        tot /= n_timed                                   # ms per launch, averaged over steps
+        classes = {}
+        for (label, kind, _id, impl, flops, nbytes), ms in zip(info, tot):
+            c = classes.setdefault(label, {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+            c["launches"] += 1
+            c["ms"] += float(ms)
+            c["flops"] += flops
+            c["bytes"] += nbytes
+        for c in classes.values():
+            c["tflops"] = c["flops"] / (c["ms"] * 1e-3) / 1e12 if c["ms"] > 0 else 0.0
+            c["gbs"] = c["bytes"] / (c["ms"] * 1e-3) / 1e9 if c["ms"] > 0 else 0.0
+        dom = max(classes, key=lambda k: classes[k]["ms"])
+        d = classes[dom]
+        if d["flops"] > 0:
+            roof = {"bound": "mfma", "achieved": d["tflops"], "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": d["tflops"] / MFMA_F32_PEAK_TFLOPS}
+        else:
+            roof = {"bound": "hbm", "achieved": d["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["gbs"] / HBM_PEAK_GBS}
+        roof.update({"kernel": dom, "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
+                     "traffic": None})
+        out["roofline"] = roof
+        out["classes"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 4), "tflops": round(v["tflops"], 2),
+                              "gbs": round(v["gbs"], 1)} for k, v in sorted(classes.items(), key=lambda kv: -kv[1]["ms"])}
+        out["timed_ms_per_step"] = float(tot.sum())
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

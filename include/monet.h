@@ -143,6 +143,33 @@ int64_t monet_plan_bn_stats_offset(const monet_plan *plan, int node);
  * wants to read is still in memory. */
 int monet_plan_set_stop_after(monet_plan *plan, int64_t event_index);
 
+/* ---- measurement aids ------------------------------------------------------------
+ * One record per operator launch of the step, in execution order.  `flops` and `bytes`
+ * are algorithmic figures (2*M*N*K of the contraction; bytes of the tensors the operator
+ * must read and write once), used to place measured time against the roofline.
+ *   kind  2 forward, 3 recomputation, 4 backward;  id = node (kind 2,3) or backward operator k
+ *   label e.g. "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_fwd", "bn_apply", "bn_bwd",
+ *         "relu_fwd", "relu_bwd", "maxpool_fwd", ... */
+typedef struct monet_launch_info {
+    int32_t kind;
+    int32_t id;
+    int32_t impl;
+    uint32_t flags;
+    double flops;
+    double bytes;
+    char label[32];
+} monet_launch_info;
+
+int monet_plan_num_launches(const monet_plan *plan);
+int monet_plan_launch_info(const monet_plan *plan, size_t index, monet_launch_info *out);
+
+/* When on, monet_step brackets every operator launch with a pair of HIP events on the
+ * step's stream (events are created once and reused; no synchronisation is added). */
+int monet_plan_set_timing(monet_plan *plan, int on);
+/* Waits for the last timed step to finish and writes the elapsed milliseconds of each
+ * launch of that step to ms[0..n) (n = monet_plan_num_launches).  Host array. */
+int monet_plan_read_timing(monet_plan *plan, float *ms, size_t n);
+
 const char *monet_last_error(void);     /* thread-local, static storage */
 void monet_free(monet_plan *plan);
 

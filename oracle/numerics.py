@@ -109,11 +109,12 @@ def bn_bwd_from_output(dy, y, gamma, beta, invstd):
 
 # ---------------------------------------------------------------- ReLU family
 def relu_fwd(x):
-    return np.maximum(x, 0.0)
+    """x where x > 0, else 0 (so 0, -0.0 and NaN all give 0: the same strict predicate as the sign code)."""
+    return np.where(x > 0, x, 0.0)
 
 
 def relu6_fwd(x):
-    return np.minimum(np.maximum(x, 0.0), 6.0)
+    return np.where(x > 0, np.minimum(x, 6.0), 0.0)
 
 
 def relu_pass(x):

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstring>
 #include <string>
+#include <vector>
 
 #include "../../include/monet.h"
 #include "../../include/monet_kernels.h"
@@ -19,7 +20,12 @@ struct monet_plan {
     size_t bound_bytes = 0;
     bool poison = false;
     int64_t stop_after = -1;
-    bool stats_valid = false;  // BatchNorm statistics are written by the first forward of a step
+    bool timing = false;
+    std::vector<hipEvent_t> ev;   // 2 per launch, created on first use
+    bool timed_step_done = false;
+    ~monet_plan() {
+        for (auto e : ev) (void)hipEventDestroy(e);
+    }
 };
 
 template <class F>
@@ -272,6 +278,10 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
         // arena accounting: replay the trace's alloc/free records against the launches
         int64_t live = 0;
         size_t next_event = 0, next_poison = 0;
+        if (p->timing && p->ev.size() != 2 * pl.launches.size()) {
+            p->ev.resize(2 * pl.launches.size());
+            for (auto &e : p->ev) hip_check(hipEventCreate(&e), "event create");
+        }
         for (size_t li = 0; li < pl.launches.size(); ++li) {
             const Launch &L = pl.launches[li];
             if (p->stop_after >= 0 && (int64_t)L.event > p->stop_after) break;
@@ -285,9 +295,12 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
             if (p->poison)
                 for (; next_poison < pl.poison.size() && pl.poison[next_poison].before_launch <= li; ++next_poison)
                     fill_u32(c.st, (uint32_t *)(c.arena() + pl.poison[next_poison].off), pl.poison[next_poison].bytes / 4, 0x7fc00000u);
+            if (p->timing) hip_check(hipEventRecord(p->ev[2 * li], c.st), "event record");
             if (L.kind == EV_RUN_BWD) run_backward(c, L);
             else run_forward(c, L);
+            if (p->timing) hip_check(hipEventRecord(p->ev[2 * li + 1], c.st), "event record");
         }
+        p->timed_step_done = p->timing;
         if (p->stop_after < 0) {
             for (; next_event < pl.events.size(); ++next_event) {
                 const monet_event &e = pl.events[next_event];
@@ -301,6 +314,81 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
             hip_check(hipMemcpyAsync(dev_loss, p->base + pl.loss_off, 4, hipMemcpyDeviceToDevice, c.st), "loss copy");
     });
     return rc == MONET_OK ? peak : rc;
+}
+
+// ------------------------------------------------------------------ measurement aids
+extern "C" int monet_plan_num_launches(const monet_plan *p) { return p ? (int)p->plan.launches.size() : MONET_BAD_ARGUMENT; }
+
+extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_launch_info *out) {
+    if (!p || !out || index >= p->plan.launches.size()) { g_err = "monet_plan_launch_info: bad argument"; return MONET_BAD_ARGUMENT; }
+    const Graph &g = p->plan.g;
+    const Launch &L = p->plan.launches[index];
+    std::memset(out, 0, sizeof(*out));
+    out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
+    std::string label;
+    double flops = 0, bytes = 0;
+    auto conv_cost = [&](const ConvShape &cs, const char *which) {
+        flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
+        double x = 4.0 * cs.N * cs.H * cs.W * cs.C, w = 4.0 * cs.K * (double)cs.RSC(), y = 4.0 * (double)cs.M() * cs.K;
+        bytes = x + w + y;
+        label = which;
+    };
+    if (L.kind == EV_RUN_BWD) {
+        const Bop &b = g.bops[L.id];
+        const Node &n = g.nodes[b.node];
+        double e = 4.0 * (double)numel_of(n.shape);
+        label = b.kind;
+        if (b.kind == "conv_wgrad") conv_cost(conv_shape(g, n), "conv_wgrad");
+        else if (b.kind == "conv_dgrad") conv_cost(conv_shape(g, n), "conv_dgrad");
+        else if (b.kind == "linear_wgrad") conv_cost(linear_shape(g, n), "linear_wgrad");
+        else if (b.kind == "linear_dgrad") conv_cost(linear_shape(g, n), "linear_dgrad");
+        else if (b.kind == "bn_bwd") bytes = 5 * e;                      // reduce pass reads dy,t; apply pass reads dy,t, writes dx
+        else if (b.kind == "relu_bwd" || b.kind == "relu6_bwd")
+            bytes = (b.impls[L.impl].algo == "from_mask" ? 2.0 + 1.0 / 32 : 3.0) * e;
+        else if (b.kind == "maxpool_bwd") {
+            double in = 4.0 * (double)numel_of(g.shape_of(n.ins[0]));
+            bytes = in + (b.impls[L.impl].algo == "from_index" ? 1.25 * e : e + in);
+        } else if (b.kind == "add_bwd") bytes = 4 * e;
+        else if (b.kind == "avgpool_bwd") bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e;
+        else bytes = 2.0 * 4.0 * (double)numel_of(g.shape_of(n.ins[0]));
+        if ((b.kind == "relu_bwd" || b.kind == "relu6_bwd" || b.kind == "bn_bwd" || b.kind == "conv_dgrad") && (L.flags & 1)) bytes += e;
+    } else {
+        const Node &n = g.nodes[L.id];
+        double e = 4.0 * (double)numel_of(n.shape);
+        label = n.op + "_fwd";
+        if (n.op == "conv") conv_cost(conv_shape(g, n), "conv_fwd");
+        else if (n.op == "linear") conv_cost(linear_shape(g, n), "linear_fwd");
+        else if (n.op == "bn") {
+            if (L.kind == EV_RUN_FWD) bytes = 3 * e;                     // statistics pass + apply pass
+            else { bytes = 2 * e; label = "bn_apply"; }                  // recomputation reuses the statistics
+        } else if (n.op == "relu" || n.op == "relu6") bytes = (2.0 + ((L.flags & 2) ? 1.0 / 32 : 0.0)) * e;
+        else if (n.op == "maxpool") bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e * ((L.flags & 2) ? 1.25 : 1.0);
+        else if (n.op == "add") bytes = 3 * e;
+        else bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e;
+    }
+    out->flops = flops;
+    out->bytes = bytes;
+    std::strncpy(out->label, label.c_str(), sizeof(out->label) - 1);
+    return MONET_OK;
+}
+
+extern "C" int monet_plan_set_timing(monet_plan *p, int on) {
+    if (!p) return MONET_BAD_ARGUMENT;
+    p->timing = on != 0;
+    p->timed_step_done = false;
+    return MONET_OK;
+}
+
+extern "C" int monet_plan_read_timing(monet_plan *p, float *ms, size_t n) {
+    if (!p || !ms) { g_err = "monet_plan_read_timing: null argument"; return MONET_BAD_ARGUMENT; }
+    if (!p->timed_step_done || n != p->plan.launches.size() || p->ev.size() != 2 * n) {
+        g_err = "monet_plan_read_timing: no timed step to read";
+        return MONET_BAD_ARGUMENT;
+    }
+    return guarded([&] {
+        hip_check(hipEventSynchronize(p->ev[2 * n - 1]), "event synchronize");
+        for (size_t i = 0; i < n; ++i) hip_check(hipEventElapsedTime(&ms[i], p->ev[2 * i], p->ev[2 * i + 1]), "event elapsed");
+    });
 }
 
 // ------------------------------------------------------------------ linear layer = 1x1 convolution + bias

@@ -16,6 +16,11 @@ EVENT_DTYPE = np.dtype([("kind", "<i4"), ("stage", "<i4"), ("node", "<i4"), ("im
 _LIB = None
 
 
+class LaunchInfo(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("id", C.c_int32), ("impl", C.c_int32), ("flags", C.c_uint32),
+                ("flops", C.c_double), ("bytes", C.c_double), ("label", C.c_char * 32)]
+
+
 class MonetError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__(f"monet error {code}: {msg}")
@@ -58,6 +63,14 @@ def load_library():
     lib.monet_plan_tensor_offset.restype = i64
     lib.monet_plan_bn_stats_offset.argtypes = [vp, i32]
     lib.monet_plan_bn_stats_offset.restype = i64
+    lib.monet_plan_num_launches.argtypes = [vp]
+    lib.monet_plan_num_launches.restype = i32
+    lib.monet_plan_launch_info.argtypes = [vp, sz, C.POINTER(LaunchInfo)]
+    lib.monet_plan_launch_info.restype = i32
+    lib.monet_plan_set_timing.argtypes = [vp, i32]
+    lib.monet_plan_set_timing.restype = i32
+    lib.monet_plan_read_timing.argtypes = [vp, C.POINTER(C.c_float), sz]
+    lib.monet_plan_read_timing.restype = i32
     lib.monet_free.argtypes = [vp]
     lib.monet_free.restype = None
     f = C.c_float
@@ -148,6 +161,24 @@ class Plan:
 
     def bn_stats_offset(self, node):
         return self._lib.monet_plan_bn_stats_offset(self._h, node)
+
+    def launches(self):
+        """[(label, kind, id, impl, flops, bytes)] per operator launch, in execution order."""
+        out = []
+        for i in range(_check(self._lib.monet_plan_num_launches(self._h))):
+            li = LaunchInfo()
+            _check(self._lib.monet_plan_launch_info(self._h, i, C.byref(li)))
+            out.append((li.label.decode(), li.kind, li.id, li.impl, li.flops, li.bytes))
+        return out
+
+    def set_timing(self, on):
+        _check(self._lib.monet_plan_set_timing(self._h, 1 if on else 0))
+
+    def read_timing(self):
+        n = _check(self._lib.monet_plan_num_launches(self._h))
+        buf = (C.c_float * n)()
+        _check(self._lib.monet_plan_read_timing(self._h, buf, n))
+        return np.frombuffer(buf, dtype=np.float32).copy()
 
     def step(self, stream, input_ptrs, weight_ptrs, grad_ptrs, loss_ptr=None):
         """Enqueue one training step; returns the peak logical live bytes."""

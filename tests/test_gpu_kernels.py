@@ -1,0 +1,212 @@
+"""Per-kernel parity on a real MI355X: each gfx950 kernel, called through the C ABI, against the
+fp64 oracle on identical seeded fp32 inputs.  Integer outputs (sign masks, pool indices) are
+bit-exact; floating point is compared normwise per tensor (activations 1e-4, gradients 1e-3)."""
+import numpy as np
+import pytest
+
+from oracle import numerics as nm
+from workloads import tensors as wt
+import paper_2010_14501_amd as M
+from paper_2010_14501_amd import monet
+
+pytestmark = pytest.mark.gpu
+
+ACT_TOL, GRAD_TOL = 1e-4, 1e-3
+
+
+def torch_mod():
+    import torch
+    return torch
+
+
+def dev(a):
+    torch = torch_mod()
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel(got, want):
+    want = np.asarray(want, np.float64)
+    d = np.linalg.norm(np.asarray(got, np.float64) - want)
+    n = np.linalg.norm(want)
+    return d if n == 0 else d / n
+
+
+CONV_CASES = [
+    # N, H, W, C, K, R, stride, pad
+    (2, 16, 16, 16, 16, 3, 1, 1),       # the tiny chain's layer
+    (3, 14, 14, 64, 128, 3, 1, 1),      # several tiles, ragged M (588 rows)
+    (2, 15, 13, 32, 80, 3, 2, 1),       # stride 2, odd sizes, ragged K
+    (2, 28, 28, 64, 256, 1, 1, 0),      # 1x1
+    (2, 28, 28, 128, 64, 1, 2, 0),      # 1x1 stride 2 (downsample path)
+    (2, 32, 32, 3, 64, 7, 2, 3),        # stem: C=3 takes the scalar-load path
+    (1, 9, 9, 20, 24, 3, 1, 1),         # C % 16 != 0 and K % 16 != 0
+    (5, 7, 7, 512, 512, 3, 1, 1),       # deep reduction (4608)
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_trio_matches_oracle(case):
+    torch = torch_mod()
+    N, H, W, C, K, R, stride, pad = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    dy = rng.standard_normal((N, P, Q, K), dtype=np.float32)
+    xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
+    dx, dwt, ddy = dev(x), dev(w), dev(dy)
+    # forward
+    y = torch.empty((N, P, Q, K), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad)
+    want = wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad))
+    assert rel(y.cpu().numpy(), want) < ACT_TOL
+    # input gradient, plain and accumulating
+    gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0)
+    want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, stride, pad))
+    assert rel(gx.cpu().numpy(), want) < GRAD_TOL
+    monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1)
+    assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    # weight gradient: no workspace, and split with workspace
+    want = wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, R, R, stride, pad))
+    for splits in (1, 3, 8):
+        gw = torch.full((K, R, R, C), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(splits * K * R * R * C, dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, R, R, stride, pad,
+                   splits, ws.data_ptr(), ws.numel() * 4)
+        assert rel(gw.cpu().numpy(), want) < GRAD_TOL, splits
+
+
+def test_conv_wgrad_rejects_small_workspace():
+    torch = torch_mod()
+    t = torch.zeros(16 * 16 * 16 * 2, device="cuda")
+    with pytest.raises(M.MonetError):
+        monet.call("monet_conv_wgrad", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 1, 1, 4, t.data_ptr(), 64)
+    with pytest.raises(M.MonetError):
+        monet.call("monet_conv_fwd", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 0, 1)
+
+
+BN_CASES = [(2 * 16 * 16, 16), (3 * 14 * 14, 64), (1000, 256), (77, 2048), (5 * 33 * 31, 128), (4096, 24)]
+
+
+@pytest.mark.parametrize("rows,C", BN_CASES)
+def test_batchnorm_matches_oracle(rows, C):
+    torch = torch_mod()
+    rng = np.random.default_rng(rows * 131 + C)
+    x = (rng.standard_normal((rows, C)) * rng.uniform(0.5, 3, C) + rng.standard_normal(C) * 2).astype(np.float32)
+    gamma = rng.uniform(0.5, 1.5, C).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(C)).astype(np.float32)
+    dy = rng.standard_normal((rows, C), dtype=np.float32)
+    eps = 1e-5
+    # oracle works on N,C,H,W: use N=rows, H=W=1
+    xo = x.astype(np.float64).reshape(rows, C, 1, 1)
+    dyo = dy.astype(np.float64).reshape(rows, C, 1, 1)
+    yo, mean, invstd = nm.bn_fwd(xo, gamma.astype(np.float64), beta.astype(np.float64), eps)
+    dxo, dgo, dbo = nm.bn_bwd_from_input(dyo, xo, gamma.astype(np.float64), mean, invstd)
+    dx_, dg_, dbeta_, dd = dev(x), dev(gamma), dev(beta), dev(dy)
+    scratch = torch.empty(2 << 20, dtype=torch.float32, device="cuda")
+    stats = torch.empty(2 * C, dtype=torch.float32, device="cuda")
+    monet.call("monet_bn_stats", None, dx_.data_ptr(), stats.data_ptr(), rows, C, eps, scratch.data_ptr(), scratch.numel() * 4)
+    st = stats.cpu().numpy()
+    assert rel(st[:C], mean) < 1e-5 and rel(st[C:], invstd) < 1e-5
+    y = torch.empty_like(dx_)
+    monet.call("monet_bn_apply", None, dx_.data_ptr(), y.data_ptr(), dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(), rows, C)
+    assert rel(y.cpu().numpy(), yo.reshape(rows, C)) < ACT_TOL
+    # in place
+    xin = dx_.clone()
+    monet.call("monet_bn_apply", None, xin.data_ptr(), xin.data_ptr(), dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(), rows, C)
+    assert torch.equal(xin, y)
+    for from_output, t in ((0, dx_), (1, y)):
+        gx = torch.full((rows, C), float("nan"), dtype=torch.float32, device="cuda")
+        gg = torch.empty(C, dtype=torch.float32, device="cuda")
+        gb = torch.empty(C, dtype=torch.float32, device="cuda")
+        monet.call("monet_bn_bwd", None, dd.data_ptr(), t.data_ptr(), from_output, dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(),
+                   gx.data_ptr(), gg.data_ptr(), gb.data_ptr(), rows, C, 0, scratch.data_ptr(), scratch.numel() * 4)
+        assert rel(gx.cpu().numpy(), dxo.reshape(rows, C)) < GRAD_TOL
+        assert rel(gg.cpu().numpy(), dgo) < GRAD_TOL and rel(gb.cpu().numpy(), dbo) < GRAD_TOL
+        monet.call("monet_bn_bwd", None, dd.data_ptr(), t.data_ptr(), from_output, dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(),
+                   gx.data_ptr(), gg.data_ptr(), gb.data_ptr(), rows, C, 1, scratch.data_ptr(), scratch.numel() * 4)
+        assert rel(gx.cpu().numpy(), 2 * dxo.reshape(rows, C)) < GRAD_TOL
+
+
+def test_batchnorm_statistics_with_large_offset():
+    """Mean far from zero: a sum-of-squares formulation would lose the variance here."""
+    torch = torch_mod()
+    rows, C = 200000, 16
+    rng = np.random.default_rng(7)
+    x = (1000.0 + rng.standard_normal((rows, C))).astype(np.float32)
+    mean, invstd = nm.bn_stats(x.astype(np.float64).reshape(rows, C, 1, 1), 1e-5)
+    scratch = torch.empty(2 << 20, dtype=torch.float32, device="cuda")
+    stats = torch.empty(2 * C, dtype=torch.float32, device="cuda")
+    d = dev(x)
+    monet.call("monet_bn_stats", None, d.data_ptr(), stats.data_ptr(), rows, C, 1e-5, scratch.data_ptr(), scratch.numel() * 4)
+    st = stats.cpu().numpy()
+    assert rel(st[:C], mean) < 1e-6 and rel(st[C:], invstd) < 1e-3
+
+
+@pytest.mark.parametrize("shape", [(2, 16, 16, 16), (1, 5, 7, 3), (3, 9, 11, 40), (1, 1, 1, 64), (1, 1, 1, 1), (2, 33, 17, 130)])
+@pytest.mark.parametrize("six", [0, 1])
+def test_relu_and_mask_bit_exact(shape, six):
+    torch = torch_mod()
+    rng = np.random.default_rng(sum(shape) + six)
+    x = (rng.standard_normal(shape) * (4 if six else 1)).astype(np.float32)
+    flat = x.reshape(-1)
+    flat[::7] = 0.0
+    if flat.size > 3:
+        flat[1] = -0.0
+        flat[2] = np.nan
+        flat[3] = 6.0
+    n = x.size
+    words = (n + 63) // 64
+    d = dev(x)
+    y = torch.empty_like(d)
+    mask = torch.full((words + 1,), -1, dtype=torch.int64, device="cuda")     # one guard word
+    monet.call("monet_relu_fwd", None, d.data_ptr(), y.data_ptr(), mask.data_ptr(), n, six)
+    xo = wt.act_to_oracle(x)
+    passes = nm.relu6_pass(xo) if six else nm.relu_pass(xo)
+    want_mask = nm.pack_mask(passes)
+    got_mask = mask.cpu().numpy().view(np.uint64)
+    assert np.array_equal(got_mask[:words], want_mask)          # bit-exact, tail bits zero
+    assert got_mask[words] == np.uint64(0xFFFFFFFFFFFFFFFF)     # nothing written past the end
+    want_y = wt.act_from_oracle((nm.relu6_fwd if six else nm.relu_fwd)(xo))
+    assert np.array_equal(y.cpu().numpy(), want_y.astype(np.float32))
+    # in place, without a mask
+    z = d.clone()
+    monet.call("monet_relu_fwd", None, z.data_ptr(), z.data_ptr(), None, n, six)
+    assert torch.equal(z, y)
+    # backward: three variants give the same bits
+    dz = rng.standard_normal(shape, dtype=np.float32)
+    ddz = dev(dz)
+    want = wt.act_from_oracle(wt.act_to_oracle(dz) * passes).astype(np.float32)
+    for mode, t in ((0, d), (1, y), (2, mask)):
+        gx = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_relu_bwd", None, ddz.data_ptr(), t.data_ptr(), mode, gx.data_ptr(), n, six, 0)
+        assert np.array_equal(gx.cpu().numpy(), want), mode
+        monet.call("monet_relu_bwd", None, ddz.data_ptr(), t.data_ptr(), mode, gx.data_ptr(), n, six, 1)
+        assert np.array_equal(gx.cpu().numpy(), want + want), mode
+
+
+@pytest.mark.parametrize("case", [(2, 16, 16, 8, 3, 2, 1), (1, 9, 7, 4, 2, 2, 0), (2, 12, 12, 64, 3, 2, 1), (1, 5, 5, 4, 3, 1, 1)])
+def test_maxpool_index_bit_exact(case):
+    torch = torch_mod()
+    N, H, W, C, k, stride, pad = case
+    rng = np.random.default_rng(sum(case))
+    x = np.maximum(rng.standard_normal((N, H, W, C)), 0).astype(np.float32)      # post-ReLU: many exact ties at 0
+    P = (H + 2 * pad - k) // stride + 1
+    Q = (W + 2 * pad - k) // stride + 1
+    dy = rng.standard_normal((N, P, Q, C), dtype=np.float32)
+    yo, idxo = nm.maxpool_fwd(wt.act_to_oracle(x), k, stride, pad)
+    d = dev(x)
+    y = torch.empty((N, P, Q, C), dtype=torch.float32, device="cuda")
+    idx = torch.empty((N, P, Q, C), dtype=torch.uint8, device="cuda")
+    monet.call("monet_maxpool_fwd", None, d.data_ptr(), y.data_ptr(), idx.data_ptr(), N, H, W, C, k, stride, pad)
+    assert np.array_equal(idx.cpu().numpy(), wt.act_from_oracle(idxo))
+    assert np.array_equal(y.cpu().numpy(), wt.act_from_oracle(yo).astype(np.float32))
+    want = wt.act_from_oracle(nm.maxpool_bwd_from_index(wt.act_to_oracle(dy), idxo, (N, C, H, W), k, stride, pad))
+    ddy = dev(dy)
+    for use_idx in (True, False):
+        gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_maxpool_bwd", None, ddy.data_ptr(), d.data_ptr(), idx.data_ptr() if use_idx else None, gx.data_ptr(),
+                   N, H, W, C, k, stride, pad, 0)
+        assert rel(gx.cpu().numpy(), want) < 1e-6
