@@ -23,12 +23,14 @@ def nchw_shape(shape):
     return tuple(shape)
 
 
-def forward_op(g: OGraph, n, get, params, stats, recompute=False):
+def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, decisions=None):
     """Output of node n (and its aux outputs as a dict op->array).
 
     `get(ref)` returns an input array.  BatchNorm statistics are taken from
     `stats[n.id]` on recomputation (Appendix D: statistics are reused) and
-    written there otherwise.
+    written there otherwise.  `ties` = (band, {relu node: boolean array}) resolves ReLU
+    decisions that fp32 cannot decide (see numerics.resolve_pass); the decisions taken are
+    written to `decisions[n.id]` so that the backward operator takes the same ones.
     """
     a = n.attrs
     x = get(n.ins[0])
@@ -43,12 +45,16 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False):
         else:
             y, mean, invstd = nm.bn_fwd(x, gamma, beta, float(a["eps"]))
             stats[n.id] = (mean, invstd)
-    elif n.op == "relu":
-        y = nm.relu_fwd(x)
-        aux["mask"] = lambda: nm.pack_mask(nm.relu_pass(x))
-    elif n.op == "relu6":
-        y = nm.relu6_fwd(x)
-        aux["mask"] = lambda: nm.pack_mask(nm.relu6_pass(x))
+    elif n.op in ("relu", "relu6"):
+        six = n.op == "relu6"
+        passes = nm.relu6_pass(x) if six else nm.relu_pass(x)
+        if ties is not None and n.id in ties[1]:
+            passes, undecided = nm.resolve_pass(x, passes, ties[1][n.id], ties[0], six)
+            decisions[n.id] = (passes, undecided)
+            y = np.where(passes, np.minimum(x, 6.0) if six else x, 0.0)
+        else:
+            y = nm.relu6_fwd(x) if six else nm.relu_fwd(x)
+        aux["mask"] = lambda: nm.pack_mask(passes)
     elif n.op == "maxpool":
         y, idx = nm.maxpool_fwd(x, int(a["k"]), int(a["stride"]), int(a["pad"]))
         aux["poolidx"] = lambda: idx
@@ -67,7 +73,7 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False):
     return y, aux
 
 
-def backward_op(g: OGraph, bop, algo, gy, get, params, stats):
+def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
     """(input gradients {input position: array}, parameter gradients {pid: array}).
 
     `get(ref)` returns a forward tensor the chosen implementation depends on.
@@ -93,7 +99,9 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats):
         return {0: dx}, {n.pars[0]: dg, n.pars[1]: db}
     if kind in ("relu_bwd", "relu6_bwd"):
         six = kind == "relu6_bwd"
-        if algo == "from_input":
+        if decisions is not None and n.id in decisions:
+            dx = gy * decisions[n.id][0]
+        elif algo == "from_input":
             dx = (nm.relu6_bwd_from_input if six else nm.relu_bwd_from_input)(gy, get(n.ins[0]))
         elif algo == "from_output":
             dx = (nm.relu6_bwd_from_output if six else nm.relu_bwd_from_output)(gy, get(n.id))
@@ -128,11 +136,13 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats):
     raise ValueError(kind)
 
 
-def store_everything_step(graph_text, exts, params):
+def store_everything_step(graph_text, exts, params, ties=None):
     """Plain training step.  Returns dict(loss, acts{i: array}, aux{i: array}, grads{pid: array},
-    agrads{i: array}, stats{i: (mean, invstd)})."""
+    agrads{i: array}, stats{i: (mean, invstd)}, decisions{relu node: (passes, undecided)}).
+
+    `ties` = (band, {relu node: boolean array}): see forward_op."""
     g = OGraph(graph_text)
-    acts, auxv, stats = {}, {}, {}
+    acts, auxv, stats, decisions = {}, {}, {}, {}
 
     def get(ref):
         return exts[ref] if ref <= 0 else acts[ref]
@@ -141,7 +151,7 @@ def store_everything_step(graph_text, exts, params):
         n = g.nodes[i]
         if n.is_aux:
             continue
-        y, aux = forward_op(g, n, get, params, stats)
+        y, aux = forward_op(g, n, get, params, stats, ties=ties, decisions=decisions)
         acts[i] = y
         for c in g.aux_children[i]:
             auxv[c] = aux[g.nodes[c].op]()
@@ -157,11 +167,11 @@ def store_everything_step(graph_text, exts, params):
         bop = g.bops[k]
         n = g.nodes[bop.node]
         gy = None if n.persist else agrads[n.id]
-        din, dpar = backward_op(g, bop, bop.impls[0]["algo"], gy, get_any, params, stats)
+        din, dpar = backward_op(g, bop, bop.impls[0]["algo"], gy, get_any, params, stats, decisions)
         for pos, d in din.items():
             j = n.ins[pos]
             if j > 0:
                 agrads[j] = agrads[j] + d if j in agrads else d.copy()
         for pid, d in dpar.items():
             grads[pid] = d
-    return dict(loss=loss, acts=acts, aux=auxv, grads=grads, agrads=agrads, stats=stats)
+    return dict(loss=loss, acts=acts, aux=auxv, grads=grads, agrads=agrads, stats=stats, decisions=decisions)

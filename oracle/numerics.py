@@ -126,6 +126,21 @@ def relu6_pass(x):
     return (x > 0) & (x < 6)
 
 
+def resolve_pass(x, passes, given, band, six=False):
+    """Sign decisions where a pre-activation is too close to a kink to be decided in fp32.
+
+    An fp32 computation reproduces x only to within the activation tolerance, so for
+    |x| < band * rms(x) (and, for ReLU6, |x - 6| below the same bound) either decision is a valid
+    result.  `given` says which one to take there; everywhere else the strict predicate stands.
+    Returns (decisions, undecided) as boolean arrays.
+    """
+    lim = band * np.sqrt(np.mean(x * x))
+    undecided = np.abs(x) < lim
+    if six:
+        undecided |= np.abs(x - 6.0) < lim
+    return np.where(undecided, given, passes), undecided
+
+
 def pack_mask(pass_nchw):
     """1-bit code: bit (e & 63) of little-endian 64-bit word (e >> 6), e = N,H,W,C linear index."""
     bits = np.ascontiguousarray(np.transpose(pass_nchw, (0, 2, 3, 1))).ravel().astype(np.uint8)

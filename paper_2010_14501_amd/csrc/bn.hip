@@ -108,32 +108,54 @@ __global__ __launch_bounds__(256) void bn_stats_partial(const float *__restrict_
     }
 }
 
+// Block = 16 channels x 16 slab lanes.  Lane sl merges slabs sl, sl+16, ... in order, then the 16
+// lanes of a channel are merged by a fixed tree.
 __global__ __launch_bounds__(256) void bn_stats_final(const float *__restrict__ part, float *__restrict__ stats, int64_t rows,
                                                       int C, int G, int64_t slab, float eps) {
-    int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
+    __shared__ float sh_n[256], sh_mean[256], sh_m2[256];
+    const int cl = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + cl;
     float n = 0, mean = 0, m2 = 0;
-    for (int g = 0; g < G; ++g) {
-        int64_t r0 = (int64_t)g * slab;
-        int64_t cnt = r0 + slab < rows ? slab : rows - r0;
-        if (cnt <= 0) break;
-        float nb = (float)cnt;
-        float mb = part[((int64_t)g * C + c) * 2 + 0], qb = part[((int64_t)g * C + c) * 2 + 1];
-        float nt = n + nb, d = mb - mean;
-        mean = n > 0 ? mean + d * (nb / nt) : mb;
-        m2 = m2 + qb + (n > 0 ? d * d * (n * nb / nt) : 0.0f);
-        n = nt;
+    if (c < C) {
+        for (int g = sl; g < G; g += 16) {
+            int64_t r0 = (int64_t)g * slab;
+            int64_t cnt = r0 + slab < rows ? slab : rows - r0;
+            if (cnt <= 0) break;
+            float nb = (float)cnt;
+            float mb = part[((int64_t)g * C + c) * 2 + 0], qb = part[((int64_t)g * C + c) * 2 + 1];
+            float nt = n + nb, d = mb - mean;
+            mean = n > 0 ? mean + d * (nb / nt) : mb;
+            m2 = m2 + qb + (n > 0 ? d * d * (n * nb / nt) : 0.0f);
+            n = nt;
+        }
     }
-    float var = m2 / n;
-    stats[c] = mean;
-    stats[C + c] = 1.0f / sqrtf(var + eps);
+    sh_n[threadIdx.x] = n; sh_mean[threadIdx.x] = mean; sh_m2[threadIdx.x] = m2;
+    __syncthreads();
+    for (int half = 8; half > 0; half >>= 1) {
+        if (sl < half) {
+            int a = threadIdx.x, b = (sl + half) * 16 + cl;
+            float na = sh_n[a], nb = sh_n[b], nt = na + nb;
+            if (nb > 0) {
+                float ma = sh_mean[a], mb = sh_mean[b], d = mb - ma;
+                sh_mean[a] = na > 0 ? ma + d * (nb / nt) : mb;
+                sh_m2[a] = sh_m2[a] + sh_m2[b] + (na > 0 ? d * d * (na * nb / nt) : 0.0f);
+                sh_n[a] = nt;
+            }
+        }
+        __syncthreads();
+    }
+    if (sl == 0 && c < C) {
+        float var = sh_m2[cl] / sh_n[cl];
+        stats[c] = sh_mean[cl];
+        stats[C + c] = 1.0f / sqrtf(var + eps);
+    }
 }
 
 void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch, size_t scratch_bytes) {
     if (rows <= 0) throw KernelError("BatchNorm: no rows");
     BnGeom g = bn_geom(rows, C, (int64_t)(scratch_bytes / 4), 2);
     hipLaunchKernelGGL(bn_stats_partial, dim3(g.G, g.CB), dim3(256), 0, st, x, scratch, rows, C, g.TPR, g.slab);
-    hipLaunchKernelGGL(bn_stats_final, dim3((C + 255) / 256), dim3(256), 0, st, (const float *)scratch, stats, rows, C, g.G, g.slab, eps);
+    hipLaunchKernelGGL(bn_stats_final, dim3((C + 15) / 16), dim3(256), 0, st, (const float *)scratch, stats, rows, C, g.G, g.slab, eps);
     hip_check(hipGetLastError(), "bn_stats launch");
 }
 
@@ -238,21 +260,35 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
     }
 }
 
-// sums the slab partials in slab order; writes dbeta, dgamma and, for the apply pass,
-// coef[c] = dbeta/m and coef[C+c] = dgamma/m behind the partials
+// Block = 16 channels x 16 slab lanes (lane sl adds slabs sl, sl+16, ... in order, then a fixed
+// tree); writes dbeta, dgamma and, for the apply pass, coef[c] = dbeta/m, coef[C+c] = dgamma/m
 __global__ __launch_bounds__(256) void bn_bwd_final(const float *__restrict__ part, float *__restrict__ dgamma,
                                                     float *__restrict__ dbeta, float *__restrict__ coef, int64_t rows, int C, int G) {
-    int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
+    __shared__ float sh_b[256], sh_g[256];
+    const int cl = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + cl;
     float b = 0, g = 0;
-    for (int s = 0; s < G; ++s) {
-        b += part[((int64_t)s * C + c) * 2 + 0];
-        g += part[((int64_t)s * C + c) * 2 + 1];
+    if (c < C)
+        for (int s = sl; s < G; s += 16) {
+            b += part[((int64_t)s * C + c) * 2 + 0];
+            g += part[((int64_t)s * C + c) * 2 + 1];
+        }
+    sh_b[threadIdx.x] = b; sh_g[threadIdx.x] = g;
+    __syncthreads();
+    for (int half = 8; half > 0; half >>= 1) {
+        if (sl < half) {
+            sh_b[threadIdx.x] += sh_b[(sl + half) * 16 + cl];
+            sh_g[threadIdx.x] += sh_g[(sl + half) * 16 + cl];
+        }
+        __syncthreads();
     }
-    dbeta[c] = b;
-    dgamma[c] = g;
-    coef[c] = b / (float)rows;
-    coef[C + c] = g / (float)rows;
+    if (sl == 0 && c < C) {
+        b = sh_b[cl]; g = sh_g[cl];
+        dbeta[c] = b;
+        dgamma[c] = g;
+        coef[c] = b / (float)rows;
+        coef[C + c] = g / (float)rows;
+    }
 }
 
 template <bool FROM_OUT, bool ACC>
@@ -301,7 +337,7 @@ void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, c
     float *coef = scratch + (int64_t)g.G * C * 2;
     if (from_output) hipLaunchKernelGGL((bn_bwd_partial<true>), dim3(g.G, g.CB), dim3(256), 0, st, dy, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
     else hipLaunchKernelGGL((bn_bwd_partial<false>), dim3(g.G, g.CB), dim3(256), 0, st, dy, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
-    hipLaunchKernelGGL(bn_bwd_final, dim3((C + 255) / 256), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
+    hipLaunchKernelGGL(bn_bwd_final, dim3((C + 15) / 16), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
     int64_t total4 = rows * (C / 4);
     int64_t want = (total4 + 256 * 4 - 1) / (256 * 4);
     int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, 8192));

@@ -160,16 +160,69 @@ def test_small_resnet_schedules_agree_with_oracle():
     assert all(same), [p for p, s in enumerate(same) if not s]
 
 
-def test_resnet50_reduced_batch_against_oracle():
-    """The full ResNet-50 graph (224x224, 1000 classes) at batch 2: what the fp64 oracle can do in seconds."""
-    g = graphs.resnet50(batch=2)
-    exts, params = tensors.make_inputs(g, seed=0)
-    ref = oracle_step(g, exts, params)
-    sch = schedules.block_output_schedule(g)
+UNDECIDED_BAND = 1e-3     # a ReLU input within 1e-3 * rms of the kink cannot be decided at the 1e-4 activation tolerance
+
+
+def gpu_relu_decisions(g, exts, params):
+    """ReLU sign bits as the GPU took them: a store-everything run (lean variants keep every mask),
+    stopped after the last forward operator."""
+    import torch
+    sch = schedules.store_everything_schedule(g, dict(schedules.DEFAULT_VARIANTS, inplace=False))
     run = StepRunner(g.text(), sch.text(), exts, params)
+    trace = run.plan.trace()
+    last = [i for i, e in enumerate(trace) if e["kind"] == M.RUN_FWD][-1]
+    run.plan.set_stop_after(last)
+    run.step()
+    torch.cuda.synchronize()
+    out, acts = {}, {}
+    for n in g.nodes:
+        off = run.plan.tensor_offset(last, n.id)
+        if off < 0:
+            continue
+        if n.op == "mask":
+            relu = g.nodes[n.ins[0] - 1]
+            N, H, W, C = relu.shape
+            words = run.read(off, (n.shape[0],), torch.int64).view(np.uint64)
+            out[relu.id] = nm.unpack_mask(words, (N, C, H, W))
+        elif n.op == "bn":
+            acts[n.id] = run.read(off, n.shape)
+    return out, acts
+
+
+@pytest.mark.parametrize("batch", [2, 8])
+def test_resnet50_reduced_batch_against_oracle(batch):
+    """The full ResNet-50 graph (224x224, 1000 classes) at the batches the fp64 oracle does in seconds.
+
+    In a network this deep some ReLU inputs land closer to zero than fp32 can resolve, and one
+    different sign bit moves a gradient tensor by about 1/sqrt(numel).  Both signs are valid there,
+    so the comparison first checks that the GPU's sign bits equal the oracle's everywhere outside a
+    narrow band around the kink, then lets the oracle take the GPU's decision inside the band, and
+    compares loss and gradients at the stated tolerances."""
+    g = graphs.resnet50(batch=batch)
+    exts, params = tensors.make_inputs(g, seed=0)
+    gt = g.text()
+    oe, op = tensors.oracle_inputs(exts, params)
+    gpu_bits, gpu_bn = gpu_relu_decisions(g, exts, params)
+    ref = onet.store_everything_step(gt, oe, op, ties=(UNDECIDED_BAND, gpu_bits))
+    flips_inside, undecided_total, total = 0, 0, 0
+    for node, (passes, undecided) in ref["decisions"].items():
+        n = g.nodes[node - 1]
+        x = ref["acts"][n.ins[0]]
+        strict = (x > 0)
+        assert np.array_equal(gpu_bits[node][~undecided], strict[~undecided]), node   # decided bits are bit-exact
+        flips_inside += int((gpu_bits[node][undecided] != strict[undecided]).sum())
+        undecided_total += int(undecided.sum())
+        total += x.size
+    print(f"batch {batch}: {flips_inside} sign bits differ, all among the {undecided_total} undecided of {total}")
+    assert undecided_total < 2e-3 * total
+    # activations along the depth of the network (BatchNorm outputs)
+    worst_act = max(rel(a, tensors.act_from_oracle(ref["acts"][i])) for i, a in gpu_bn.items())
+    print(f"batch {batch}: worst BatchNorm-output error {worst_act:.2e}")
+    sch = schedules.block_output_schedule(g)
+    run = StepRunner(gt, sch.text(), exts, params)
     peak = run.step()
     assert peak == run.plan.exact_peak <= run.plan.predicted_peak
     assert abs(run.loss_value() - ref["loss"]) < ACT_TOL * abs(ref["loss"])
-    # batch 2 puts only 2 samples per channel into the last BatchNorms, which amplifies rounding
-    # in the deepest layers; the stated gradient tolerance still has to hold
-    compare_grads(run.grads_numpy(), ref)
+    worst = compare_grads(run.grads_numpy(), ref)
+    print(f"batch {batch}: worst gradient error {worst:.2e}")
+    assert worst_act < 3 * ACT_TOL      # see DESIGN.md: rounding is amplified ~1.1x per layer at random init
