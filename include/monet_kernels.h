@@ -60,6 +60,11 @@ int monet_maxpool_fwd(void *stream, const float *x, float *y, uint8_t *idx,
 int monet_maxpool_bwd(void *stream, const float *dy, const float *x, const uint8_t *idx, float *dx,
                       int N, int H, int W, int C, int k, int stride, int pad, int accumulate);
 
+/* Tuning aid: force the workgroup tile of the three convolution kernels (0: 128x128, 1: 256x64,
+ * 2: 64x256, 3: 128x64, 4: 64x128, 5: 64x64 as rows x columns of the implicit GEMM); -1 restores
+ * the built-in choice.  Process-wide, not thread-safe. */
+int monet_conv_force_tile(int cfg);
+
 /* plain device copy, for bandwidth calibration */
 int monet_copy(void *stream, const float *src, float *dst, int64_t n);
 

@@ -471,6 +471,11 @@ extern "C" int monet_maxpool_bwd(void *stream, const float *dy, const float *x, 
                                  int k, int stride, int pad, int accumulate) {
     return guarded([&] { maxpool_bwd((hipStream_t)stream, dy, x, idx, dx, mk_pool(N, H, W, C, k, stride, pad), accumulate != 0); });
 }
+extern "C" int monet_conv_force_tile(int cfg) {
+    if (cfg < -1 || cfg > 5) { g_err = "monet_conv_force_tile: cfg must be -1..5"; return MONET_BAD_ARGUMENT; }
+    conv_force_tile(cfg);
+    return MONET_OK;
+}
 extern "C" int monet_copy(void *stream, const float *src, float *dst, int64_t n) {
     return guarded([&] { copy_or_accumulate((hipStream_t)stream, src, dst, n, false); });
 }

@@ -19,6 +19,18 @@
 // reduction indices 8h+4g..8h+4g+3); the MFMA pairs index 8h+4g+j of both operands, so the
 // order of the sum inside a step is permuted but complete.  An operand contiguous along its
 // row/column index is kept [16][cols+4] and read with 32-bit loads under the same pairing.
+//
+// The position of a reduction step -- (r, s, c0) forward, (tap, k0) dgrad, (n, p, q) of each
+// staged row for wgrad -- is carried from step to step by increments; no integer division is
+// executed inside the main loop of the aligned ("fast") variants.
+//
+// dgrad with stride st > 1 runs one GEMM per residue class (h mod st, w mod st) of the input
+// position: within a class only the filter taps r = r0 + st*i, s = s0 + st*j contribute, so no
+// multiply-by-zero work is issued (a 3x3 stride-2 layer does 9 taps in total, not 36).
+//
+// Workgroup ids are remapped so that consecutive tiles (same activation rows, neighbouring
+// filter columns) run on the same XCD and share its L2: hardware deals workgroups to the 8 XCDs
+// round-robin, so logical tile = (id mod 8) * (grid/8) + id / 8.
 #include "kernels.hpp"
 
 namespace monet {
@@ -29,6 +41,7 @@ namespace {
 
 constexpr int BK = 16;        // reduction step
 constexpr int KC_LD = BK + 4; // row stride of a reduction-contiguous operand in LDS (floats)
+constexpr int NUM_XCD = 8;
 
 enum ConvMode { FWD = 0, DGRAD = 1, WGRAD = 2 };
 
@@ -37,10 +50,11 @@ struct TileArgs {
     const float *b;   // FWD: w, DGRAD: w,  WGRAD: x
     float *out;       // FWD: y, DGRAD: dx, WGRAD: dw or workspace
     ConvShape cs;
-    int64_t Mg;       // GEMM rows
+    int64_t Mg;       // GEMM rows (DGRAD: of residue class 0, the largest)
     int Ng;           // GEMM columns
-    int64_t Kg;       // reduction length
+    int64_t Kg;       // reduction length (DGRAD: recomputed per class)
     int tiles_n;
+    int64_t total_tiles;
     int64_t steps_per_split;   // WGRAD: reduction steps (of BK) handled by one blockIdx.z
     int accumulate;            // DGRAD: add into dx
 };
@@ -65,14 +79,40 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, g = lane >> 5;
-    const int tile_n = blockIdx.x % ta.tiles_n;
-    const int64_t tile_m = blockIdx.x / ta.tiles_n;
+
+    // XCD-aware tile order
+    const int64_t per_xcd = gridDim.x / NUM_XCD;
+    const int64_t logical = (int64_t)(blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    if (logical >= ta.total_tiles) return;
+    const int tile_n = (int)(logical % ta.tiles_n);
+    const int64_t tile_m = logical / ta.tiles_n;
     const int64_t row0 = tile_m * BM;
     const int col0 = tile_n * BN;
-    const int64_t RSC = cs.RSC();
+    const int RSC = (int)cs.RSC();
+
+    // ---------------- DGRAD: residue class of this launch slice
+    int64_t Mg = ta.Mg, Kg = ta.Kg;
+    int ph = 0, pw = 0, r0 = 0, s0 = 0, ns = cs.S, bh = cs.pad, bw = cs.pad, Hc = cs.H, Wc = cs.W;
+    if (MODE == DGRAD) {
+        const int st = cs.stride;
+        ph = blockIdx.z / st;
+        pw = blockIdx.z % st;
+        Hc = (cs.H - ph + st - 1) / st;
+        Wc = (cs.W - pw + st - 1) / st;
+        r0 = (ph + cs.pad) % st;
+        s0 = (pw + cs.pad) % st;
+        int nr = r0 < cs.R ? (cs.R - r0 + st - 1) / st : 0;
+        ns = s0 < cs.S ? (cs.S - s0 + st - 1) / st : 0;
+        bh = (ph + cs.pad - r0) / st;
+        bw = (pw + cs.pad - s0) / st;
+        Mg = (int64_t)cs.N * Hc * Wc;
+        Kg = (int64_t)nr * ns * cs.K;
+        if (row0 >= Mg) return;
+        if (Kg == 0 && ta.accumulate) return;       // this class receives no contribution
+    }
 
     // reduction range of this workgroup
-    int64_t kt0 = 0, kt1 = (ta.Kg + BK - 1) / BK;
+    int64_t kt0 = 0, kt1 = (Kg + BK - 1) / BK;
     if (MODE == WGRAD) {
         kt0 = (int64_t)blockIdx.z * ta.steps_per_split;
         int64_t e = kt0 + ta.steps_per_split;
@@ -82,7 +122,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     // ---------------- per-slot constants of the A loader
     // reduction-contiguous A (FWD / DGRAD): slot = (row, float4 j): idx = tid + s*NT, row = idx/4, j = idx%4
     // row-contiguous A (WGRAD)            : slot = (red row, float4 along k): red = idx/(BM/4), k4 = idx%(BM/4)
-    int64_t a_base[LA];
+    int64_t a_base[LA];   // FWD/DGRAD: image base + j4; WGRAD: unused
     int a_h0[LA], a_w0[LA];
     bool a_ok[LA];
 #pragma unroll
@@ -90,7 +130,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
         int idx = tid + s * NT;
         if (A_KC) {
             int64_t m = row0 + idx / 4;
-            a_ok[s] = m < ta.Mg;
+            a_ok[s] = m < Mg;
             int64_t mm = a_ok[s] ? m : 0;
             if (MODE == FWD) {
                 int q = (int)(mm % cs.Q);
@@ -99,15 +139,15 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 int n = (int)(t / cs.P);
                 a_h0[s] = p * cs.stride - cs.pad;
                 a_w0[s] = q * cs.stride - cs.pad;
-                a_base[s] = (int64_t)n * cs.H * cs.W * cs.C;
-            } else {   // DGRAD: m = (n,h,w) of dx
-                int w = (int)(mm % cs.W);
-                int64_t t = mm / cs.W;
-                int h = (int)(t % cs.H);
-                int n = (int)(t / cs.H);
-                a_h0[s] = h + cs.pad;
-                a_w0[s] = w + cs.pad;
-                a_base[s] = (int64_t)n * cs.P * cs.Q * cs.K;
+                a_base[s] = (int64_t)n * cs.H * cs.W * cs.C + (idx % 4) * 4;
+            } else {   // DGRAD: m = (n, hc, wc) within the residue class
+                int wc = (int)(mm % Wc);
+                int64_t t = mm / Wc;
+                int hc = (int)(t % Hc);
+                int n = (int)(t / Hc);
+                a_h0[s] = hc + bh;      // p = a_h0 - tap row
+                a_w0[s] = wc + bw;
+                a_base[s] = (int64_t)n * cs.P * cs.Q * cs.K + (idx % 4) * 4;
             }
         } else {
             int k4 = idx % (BM / 4);
@@ -120,13 +160,17 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     // ---------------- per-slot constants of the B loader
     int b_i0[LB], b_i1[LB], b_i2[LB];
     bool b_ok[LB];
+    // WGRAD: (n, p, q) of the row each slot stages in the next step
+    int w_n[LB], w_p[LB], w_q[LB];
 #pragma unroll
     for (int s = 0; s < LB; ++s) {
         int idx = tid + s * NT;
+        w_n[s] = w_p[s] = w_q[s] = 0;
         if (B_KC) {          // FWD: slot = (filter k, float4 j)
             b_i0[s] = col0 + idx / 4;
             b_ok[s] = b_i0[s] < cs.K;
-            b_i1[s] = b_i2[s] = 0;
+            b_i1[s] = (idx % 4) * 4;
+            b_i2[s] = 0;
         } else {             // slot = (red row, float4 along the column index)
             int c4 = idx % (BN / 4);
             int col = col0 + c4 * 4;
@@ -138,75 +182,77 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
             } else {         // WGRAD: column = (r,s,c)
                 b_ok[s] = col < RSC;
                 int cc = b_ok[s] ? col : 0;
-                b_i1[s] = cc / cs.C;                        // r*S + s
-                b_i2[s] = cc % cs.C;                        // c
+                int rs = cc / cs.C;
+                b_i1[s] = (rs / cs.S) * cs.W + (rs % cs.S);   // r*W + s: pixel offset of the tap
+                b_i2[s] = cc % cs.C;                          // c
+                // tap (r, s) packed for the bounds test
+                b_i1[s] |= (rs / cs.S) << 24;
+                b_i2[s] |= (rs % cs.S) << 24;
+                int64_t m = kt0 * BK + b_i0[s];
+                int64_t mm = m < Kg ? m : 0;
+                w_q[s] = (int)(mm % cs.Q);
+                int64_t t = mm / cs.Q;
+                w_p[s] = (int)(t % cs.P);
+                w_n[s] = (int)(t / cs.P);
             }
         }
     }
 
+    // ---------------- position of the next step to load (uniform over the workgroup)
+    int64_t kk0 = kt0 * BK;
+    int u_r = 0, u_s = 0, u_c = 0;   // FWD: (r, s, c0); DGRAD: (tap row, tap column, k0)
+
     float4 a_reg[LA], b_reg[LB];
 
-    auto load_tiles = [&](int64_t kt) {
-        const int64_t kk0 = kt * BK;
+    auto load_tiles = [&]() {
         // ======== A
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
             int idx = tid + s * NT;
             float4 v = make_float4(0, 0, 0, 0);
             if (MODE == FWD) {
-                const int j4 = (idx % 4) * 4;
                 if (FAST) {
-                    int rs = (int)(kk0 / cs.C), c0 = (int)(kk0 % cs.C);
-                    int r = rs / cs.S, ss = rs % cs.S;
-                    int h = a_h0[s] + r, w = a_w0[s] + ss;
+                    int h = a_h0[s] + u_r, w = a_w0[s] + u_s;
                     if (a_ok[s] && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W)
-                        v = ld4(ta.a + a_base[s] + ((int64_t)h * cs.W + w) * cs.C + c0 + j4);
+                        v = ld4(ta.a + a_base[s] + ((int64_t)h * cs.W + w) * cs.C + u_c);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        int64_t kk = kk0 + j4 + u;
-                        if (a_ok[s] && kk < ta.Kg) {
-                            int rs = (int)(kk / cs.C), c = (int)(kk % cs.C);
+                        int kk = (int)kk0 + (idx % 4) * 4 + u;
+                        if (a_ok[s] && kk < Kg) {
+                            int rs = kk / cs.C, c = kk % cs.C;
                             int r = rs / cs.S, ss = rs % cs.S;
                             int h = a_h0[s] + r, w = a_w0[s] + ss;
                             if ((unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W)
-                                e[u] = ta.a[a_base[s] + ((int64_t)h * cs.W + w) * cs.C + c];
+                                e[u] = ta.a[a_base[s] - (idx % 4) * 4 + ((int64_t)h * cs.W + w) * cs.C + c];
                         }
                     }
                     v = make_float4(e[0], e[1], e[2], e[3]);
                 }
             } else if (MODE == DGRAD) {
-                const int j4 = (idx % 4) * 4;
-                // reduction index = (r, s, k); FAST: K % 16 == 0 so a step stays inside one (r,s)
+                // reduction index = (tap row, tap column, k); FAST: K % 16 == 0 so a step stays inside one tap
                 if (FAST) {
-                    int rs = (int)(kk0 / cs.K), k0 = (int)(kk0 % cs.K);
-                    int r = rs / cs.S, ss = rs % cs.S;
-                    int hn = a_h0[s] - r, wn_ = a_w0[s] - ss;
-                    if (a_ok[s] && hn >= 0 && wn_ >= 0 && hn % cs.stride == 0 && wn_ % cs.stride == 0) {
-                        int p = hn / cs.stride, q = wn_ / cs.stride;
-                        if (p < cs.P && q < cs.Q) v = ld4(ta.a + a_base[s] + ((int64_t)p * cs.Q + q) * cs.K + k0 + j4);
-                    }
+                    int p = a_h0[s] - u_r, q = a_w0[s] - u_s;
+                    if (a_ok[s] && (unsigned)p < (unsigned)cs.P && (unsigned)q < (unsigned)cs.Q)
+                        v = ld4(ta.a + a_base[s] + ((int64_t)p * cs.Q + q) * cs.K + u_c);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        int64_t kk = kk0 + j4 + u;
-                        if (a_ok[s] && kk < ta.Kg) {
-                            int rs = (int)(kk / cs.K), k = (int)(kk % cs.K);
-                            int r = rs / cs.S, ss = rs % cs.S;
-                            int hn = a_h0[s] - r, wn_ = a_w0[s] - ss;
-                            if (hn >= 0 && wn_ >= 0 && hn % cs.stride == 0 && wn_ % cs.stride == 0) {
-                                int p = hn / cs.stride, q = wn_ / cs.stride;
-                                if (p < cs.P && q < cs.Q) e[u] = ta.a[a_base[s] + ((int64_t)p * cs.Q + q) * cs.K + k];
-                            }
+                        int kk = (int)kk0 + (idx % 4) * 4 + u;
+                        if (a_ok[s] && kk < Kg) {
+                            int tap = kk / cs.K, k = kk % cs.K;
+                            int p = a_h0[s] - tap / ns, q = a_w0[s] - tap % ns;
+                            if ((unsigned)p < (unsigned)cs.P && (unsigned)q < (unsigned)cs.Q)
+                                e[u] = ta.a[a_base[s] - (idx % 4) * 4 + ((int64_t)p * cs.Q + q) * cs.K + k];
                         }
                     }
                     v = make_float4(e[0], e[1], e[2], e[3]);
                 }
             } else {   // WGRAD: A[red = m][row = k] = dy[m][k]
                 int64_t m = kk0 + a_h0[s];
-                if (m < ta.Kg) {
+                if (m < Kg) {
                     if (FAST) {
                         if (a_ok[s]) v = ld4(ta.a + m * cs.K + a_w0[s]);
                     } else {
@@ -226,22 +272,24 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
             int idx = tid + s * NT;
             float4 v = make_float4(0, 0, 0, 0);
             if (MODE == FWD) {
-                const int j4 = (idx % 4) * 4;
                 if (FAST) {
-                    if (b_ok[s]) v = ld4(ta.b + (int64_t)b_i0[s] * RSC + kk0 + j4);
+                    if (b_ok[s]) v = ld4(ta.b + (int64_t)b_i0[s] * RSC + kk0 + b_i1[s]);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        if (b_ok[s] && kk0 + j4 + u < ta.Kg) e[u] = ta.b[(int64_t)b_i0[s] * RSC + kk0 + j4 + u];
+                        if (b_ok[s] && kk0 + b_i1[s] + u < Kg) e[u] = ta.b[(int64_t)b_i0[s] * RSC + kk0 + b_i1[s] + u];
                     v = make_float4(e[0], e[1], e[2], e[3]);
                 }
             } else if (MODE == DGRAD) {
-                // B[red = (r,s,k)][col = c] = W[k][r][s][c]
+                // B[red = (tap, k)][col = c] = W[k][r0 + st*tr][s0 + st*ts][c]
                 int64_t kk = kk0 + b_i0[s];
-                if (kk < ta.Kg) {
-                    int rs = (int)(kk / cs.K), k = (int)(kk % cs.K);
-                    const float *src = ta.b + (int64_t)k * RSC + (int64_t)rs * cs.C + b_i1[s];
+                if (kk < Kg) {
+                    int tr, ts, k;
+                    if (FAST) { tr = u_r; ts = u_s; k = u_c + b_i0[s]; }
+                    else { int tap = (int)kk / cs.K; k = (int)kk % cs.K; tr = tap / ns; ts = tap % ns; }
+                    int r = r0 + cs.stride * tr, ss = s0 + cs.stride * ts;
+                    const float *src = ta.b + (int64_t)k * RSC + (r * cs.S + ss) * cs.C + b_i1[s];
                     if (FAST) {
                         if (b_ok[s]) v = ld4(src);
                     } else {
@@ -254,18 +302,13 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 }
             } else {   // WGRAD: B[red = m][col = (r,s,c)] = x[n, p*st+r-pad, q*st+s-pad, c]
                 int64_t m = kk0 + b_i0[s];
-                if (m < ta.Kg) {
-                    int q = (int)(m % cs.Q);
-                    int64_t t = m / cs.Q;
-                    int p = (int)(t % cs.P);
-                    int n = (int)(t / cs.P);
-                    int h0 = p * cs.stride - cs.pad, w0 = q * cs.stride - cs.pad;
-                    const float *img = ta.b + (int64_t)n * cs.H * cs.W * cs.C;
+                if (m < Kg) {
+                    int h0 = w_p[s] * cs.stride - cs.pad, w0 = w_q[s] * cs.stride - cs.pad;
+                    const float *img = ta.b + (int64_t)w_n[s] * cs.H * cs.W * cs.C;
                     if (FAST) {
-                        int r = b_i1[s] / cs.S, ss = b_i1[s] % cs.S;
-                        int h = h0 + r, w = w0 + ss;
+                        int h = h0 + (b_i1[s] >> 24), w = w0 + (b_i2[s] >> 24);
                         if (b_ok[s] && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W)
-                            v = ld4(img + ((int64_t)h * cs.W + w) * cs.C + b_i2[s]);
+                            v = ld4(img + ((int64_t)h0 * cs.W + w0 + (b_i1[s] & 0xffffff)) * cs.C + (b_i2[s] & 0xffffff));
                     } else {
                         float e[4] = {0, 0, 0, 0};
                         int col = col0 + (idx % (BN / 4)) * 4;
@@ -285,6 +328,24 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 }
             }
             b_reg[s] = v;
+        }
+        // ======== advance to the next step
+        kk0 += BK;
+        if (MODE == FWD) {
+            u_c += BK;
+            if (u_c >= cs.C) { u_c = 0; if (++u_s == cs.S) { u_s = 0; ++u_r; } }
+        } else if (MODE == DGRAD) {
+            u_c += BK;
+            if (u_c >= cs.K) { u_c = 0; if (++u_s == ns) { u_s = 0; ++u_r; } }
+        } else {
+#pragma unroll
+            for (int s = 0; s < LB; ++s) {
+                w_q[s] += BK;
+                while (w_q[s] >= cs.Q) {
+                    w_q[s] -= cs.Q;
+                    if (++w_p[s] == cs.P) { w_p[s] = 0; ++w_n[s]; }
+                }
+            }
         }
     };
 
@@ -349,13 +410,13 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     };
 
     if (kt0 < kt1) {
-        load_tiles(kt0);
+        load_tiles();
         store_tiles(0);
         __syncthreads();
         int buf = 0;
         for (int64_t kt = kt0; kt < kt1; ++kt) {
             const bool more = kt + 1 < kt1;
-            if (more) load_tiles(kt + 1);
+            if (more) load_tiles();
             compute(buf);
             if (more) store_tiles(buf ^ 1);
             __syncthreads();
@@ -369,13 +430,22 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            int col = col0 + wn * 64 + ni * 32 + l32;
+        for (int v = 0; v < 16; ++v) {
+            int64_t row = row0 + wm * 64 + mi * 32 + 8 * (v / 4) + 4 * g + (v % 4);
+            if (row >= Mg) continue;
+            int64_t orow = row;
+            if (MODE == DGRAD && cs.stride > 1) {   // class row (n,hc,wc) -> position (n, hc*st+ph, wc*st+pw)
+                int wc = (int)(row % Wc);
+                int64_t t = row / Wc;
+                int hc = (int)(t % Hc);
+                int64_t n = t / Hc;
+                orow = (n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
+            }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int64_t row = row0 + wm * 64 + mi * 32 + 8 * (v / 4) + 4 * g + (v % 4);
-                if (row < ta.Mg && col < ta.Ng) {
-                    float *dst = out + row * ta.Ng + col;
+            for (int ni = 0; ni < 2; ++ni) {
+                int col = col0 + wn * 64 + ni * 32 + l32;
+                if (col < ta.Ng) {
+                    float *dst = out + orow * ta.Ng + col;
                     float r = acc[mi][ni][v];
                     if (MODE == DGRAD && ta.accumulate) r += *dst;
                     *dst = r;
@@ -384,13 +454,44 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
         }
 }
 
-// sums `splits` partial results in split order
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ ws, float *__restrict__ dw, int64_t n, int splits) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        float s = 0;
-        for (int z = 0; z < splits; ++z) s += ws[(int64_t)z * n + i];
-        dw[i] = s;
+// Sums `splits` partial results in a fixed order.  Block = SL waves; wave sl adds splits sl, sl+SL, ...
+// of 64 consecutive elements (four independent partial sums per lane to keep loads in flight),
+// then the SL per-wave sums are added in wave order.
+template <int SL>
+__global__ __launch_bounds__(64 * SL) void wgrad_reduce_kernel(const float *__restrict__ ws, float *__restrict__ dw, int64_t n, int splits) {
+    __shared__ float sh[SL][64];
+    const int lane = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    for (int64_t base = (int64_t)blockIdx.x * 64; base < n; base += (int64_t)gridDim.x * 64) {
+        const int64_t i = base + lane;
+        float s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+        if (i < n) {
+            int z = sl;
+            for (; z + 3 * SL < splits; z += 4 * SL) {
+                s0 += ws[(int64_t)z * n + i];
+                s1 += ws[(int64_t)(z + SL) * n + i];
+                s2 += ws[(int64_t)(z + 2 * SL) * n + i];
+                s3 += ws[(int64_t)(z + 3 * SL) * n + i];
+            }
+            for (; z < splits; z += SL) s0 += ws[(int64_t)z * n + i];
+        }
+        sh[sl][lane] = (s0 + s1) + (s2 + s3);
+        __syncthreads();
+        if (sl == 0 && i < n) {
+            float s = sh[0][lane];
+#pragma unroll
+            for (int j = 1; j < SL; ++j) s += sh[j][lane];
+            dw[i] = s;
+        }
+        __syncthreads();
     }
+}
+
+void launch_wgrad_reduce(hipStream_t st, const float *ws, float *dw, int64_t n, int splits) {
+    int grid = (int)std::min<int64_t>((n + 63) / 64, 8192);
+    if (splits >= 64) hipLaunchKernelGGL((wgrad_reduce_kernel<16>), dim3(grid), dim3(1024), 0, st, ws, dw, n, splits);
+    else if (splits >= 16) hipLaunchKernelGGL((wgrad_reduce_kernel<4>), dim3(grid), dim3(256), 0, st, ws, dw, n, splits);
+    else hipLaunchKernelGGL((wgrad_reduce_kernel<1>), dim3(grid), dim3(64), 0, st, ws, dw, n, splits);
+    hip_check(hipGetLastError(), "wgrad reduce launch");
 }
 
 void check_shape(const ConvShape &cs) {
@@ -398,23 +499,59 @@ void check_shape(const ConvShape &cs) {
         throw KernelError("conv: bad shape");
     if (cs.P != (cs.H + 2 * cs.pad - cs.R) / cs.stride + 1 || cs.Q != (cs.W + 2 * cs.pad - cs.S) / cs.stride + 1 || cs.P <= 0 || cs.Q <= 0)
         throw KernelError("conv: output size does not match input, filter, stride and padding");
-    if ((int64_t)cs.R * cs.S * cs.C > (1ll << 30) || cs.M() > (1ll << 40)) throw KernelError("conv: shape too large");
+    if ((int64_t)cs.R * cs.S * cs.C > (1ll << 24) || (int64_t)cs.R * cs.S * cs.K > (1ll << 24) || cs.M() > (1ll << 31) - 64 ||
+        (int64_t)cs.N * cs.H * cs.W > (1ll << 31) - 64 || (int64_t)cs.H * cs.W >= (1 << 24) || cs.R > 127 || cs.S > 127)
+        throw KernelError("conv: shape too large");
+    if (cs.stride > 8) throw KernelError("conv: stride too large");
 }
 
 template <int MODE, int WM, int WN>
-void launch_tile(hipStream_t st, TileArgs ta, bool fast, int splits) {
+void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim) {
     constexpr int BM = 64 * WM, BN = 64 * WN, NT = 64 * WM * WN;
     int64_t tiles_m = (ta.Mg + BM - 1) / BM;
     ta.tiles_n = (ta.Ng + BN - 1) / BN;
-    int64_t blocks = tiles_m * ta.tiles_n;
+    ta.total_tiles = tiles_m * ta.tiles_n;
+    int64_t blocks = (ta.total_tiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     if (blocks > 0x7fffffffll) throw KernelError("conv: too many tiles");
-    dim3 grid((unsigned)blocks, 1, (unsigned)splits);
+    dim3 grid((unsigned)blocks, 1, (unsigned)zdim);
     if (fast) hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true>), grid, dim3(NT), 0, st, ta);
     else hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, false>), grid, dim3(NT), 0, st, ta);
     hip_check(hipGetLastError(), "conv launch");
 }
 
+// Tile shapes: index -> waves (rows x columns of 64x64 wave tiles)
+//   0: 128x128   1: 256x64   2: 64x256   3: 128x64   4: 64x128   5: 64x64
+int g_cfg_override = -1;   // tuning aid: force one tile shape for every launch
+
+// Choice measured on the ResNet-50 b184 layer set: the square tile unless the GEMM is narrower
+// than it; weight-gradient GEMMs (tiny output, very long reduction) prefer the smallest tile
+// that still covers the narrow side, because more workgroups hide more load latency.
+int pick_cfg(int mode, int64_t Mg, int64_t Ng) {
+    if (g_cfg_override >= 0) return g_cfg_override;
+    if (mode == WGRAD) {
+        int64_t lo = Mg < Ng ? Mg : Ng, hi = Mg < Ng ? Ng : Mg;
+        if (lo <= 64) return (Mg <= 64 && Ng > 256) ? 4 : 5;
+        if (lo <= 128) return hi <= 256 ? 5 : 3;
+        return 0;
+    }
+    return Ng <= 64 ? 1 : 0;
+}
+
+template <int MODE>
+void launch_cfg(hipStream_t st, const TileArgs &ta, bool fast, int zdim, int cfg) {
+    switch (cfg) {
+        case 0: launch_tile<MODE, 2, 2>(st, ta, fast, zdim); break;
+        case 1: launch_tile<MODE, 4, 1>(st, ta, fast, zdim); break;
+        case 2: launch_tile<MODE, 1, 4>(st, ta, fast, zdim); break;
+        case 3: launch_tile<MODE, 2, 1>(st, ta, fast, zdim); break;
+        case 4: launch_tile<MODE, 1, 2>(st, ta, fast, zdim); break;
+        default: launch_tile<MODE, 1, 1>(st, ta, fast, zdim); break;
+    }
+}
+
 }  // namespace
+
+void conv_force_tile(int cfg) { g_cfg_override = cfg; }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs) {
     check_shape(cs);
@@ -422,19 +559,21 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
     ta.a = x; ta.b = w; ta.out = y; ta.cs = cs;
     ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
     bool fast = cs.C % BK == 0;
-    if (cs.K <= 64) launch_tile<FWD, 4, 1>(st, ta, fast, 1);
-    else launch_tile<FWD, 2, 2>(st, ta, fast, 1);
+    launch_cfg<FWD>(st, ta, fast, 1, pick_cfg(FWD, ta.Mg, ta.Ng));
 }
 
 void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate) {
     check_shape(cs);
     TileArgs ta{};
     ta.a = dy; ta.b = w; ta.out = dx; ta.cs = cs;
-    ta.Mg = (int64_t)cs.N * cs.H * cs.W; ta.Ng = cs.C; ta.Kg = (int64_t)cs.R * cs.S * cs.K;
+    const int stc = cs.stride;
+    ta.Mg = (int64_t)cs.N * ((cs.H + stc - 1) / stc) * ((cs.W + stc - 1) / stc);   // rows of residue class (0,0), the largest
+    ta.Ng = cs.C;
+    ta.Kg = 0;   // per class, computed in the kernel
     ta.accumulate = accumulate ? 1 : 0;
     bool fast = cs.K % BK == 0 && cs.C % 4 == 0;
-    if (cs.C <= 64) launch_tile<DGRAD, 4, 1>(st, ta, fast, 1);
-    else launch_tile<DGRAD, 2, 2>(st, ta, fast, 1);
+    int zdim = stc * stc;
+    launch_cfg<DGRAD>(st, ta, fast, zdim, pick_cfg(DGRAD, ta.Mg, ta.Ng));
 }
 
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
@@ -455,13 +594,8 @@ void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, cons
         ta.out = dw;
     }
     bool fast = cs.K % 4 == 0 && cs.C % 4 == 0;
-    if (cs.K <= 64) launch_tile<WGRAD, 1, 2>(st, ta, fast, splits);
-    else launch_tile<WGRAD, 2, 2>(st, ta, fast, splits);
-    if (splits > 1) {
-        int grid = (int)std::min<int64_t>((n + 255) / 256, 4096);
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid), dim3(256), 0, st, (const float *)ws, dw, n, splits);
-        hip_check(hipGetLastError(), "wgrad reduce launch");
-    }
+    launch_cfg<WGRAD>(st, ta, fast, splits, pick_cfg(WGRAD, ta.Mg, ta.Ng));
+    if (splits > 1) launch_wgrad_reduce(st, ws, dw, n, splits);
 }
 
 }  // namespace monet

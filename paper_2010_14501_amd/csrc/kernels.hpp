@@ -36,6 +36,9 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws,
                 size_t ws_bytes);
 
+// tuning aid: cfg 0..5 forces tile shape (2x2, 4x1, 1x4, 2x1, 1x2, 1x1 waves of 64x64); -1 restores the heuristic
+void conv_force_tile(int cfg);
+
 // ---- BatchNorm over rows x C (rows = N*H*W), training mode, biased variance
 constexpr int64_t kBnScratchFloats = 1 << 20;
 // stats = mean[C] followed by invstd[C]; scratch holds per-slab partials

@@ -35,6 +35,9 @@ def load_library():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # PyTorch ships its own HIP runtime; it has to be the one already in the process when
+    # libmonet.so resolves its HIP symbols, or kernels and device memory end up in two runtimes.
+    import torch  # noqa: F401
     path = library_path()
     if not os.path.exists(path):
         raise FileNotFoundError(f"{path} is not built: run `python -m paper_2010_14501_amd.build`")
@@ -85,6 +88,8 @@ def load_library():
     lib.monet_maxpool_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 7
     lib.monet_maxpool_bwd.argtypes = [vp, vp, vp, vp, vp] + [i32] * 8
     lib.monet_copy.argtypes = [vp, vp, vp, i64]
+    lib.monet_conv_force_tile.argtypes = [i32]
+    lib.monet_conv_force_tile.restype = i32
     for name in ("monet_conv_fwd", "monet_conv_dgrad", "monet_conv_wgrad", "monet_bn_stats", "monet_bn_apply", "monet_bn_bwd",
                  "monet_relu_fwd", "monet_relu_bwd", "monet_maxpool_fwd", "monet_maxpool_bwd", "monet_copy"):
         getattr(lib, name).restype = i32

@@ -306,8 +306,13 @@ def resnet50(batch=184, hw=224, classes=1000, widths=(64, 128, 256, 512), depths
         N, H, W, C = g.shape_of(ref_in)
         P = (H + 2 * pad - R) // stride + 1
         M = N * P * P
-        tiles = math.ceil(K / 128) * math.ceil(C * R * R / 128)
-        sp = max(1, min(256, math.ceil(1024 / tiles), M // 512))
+        # enough waves to keep loads in flight on 256 CUs (about 16 per CU), at least 8 reduction
+        # steps of 16 rows per split, and at most 128 MiB of partial sums
+        lo = min(K, C * R * R)
+        tile_rows, tile_cols, waves = (64, 64, 1) if lo <= 128 else (128, 128, 4)
+        tiles = math.ceil(K / tile_rows) * math.ceil(C * R * R / tile_cols)
+        sp = math.ceil(4096 / (tiles * waves))
+        sp = max(1, min(sp, M // 128, (128 << 20) // (4 * K * C * R * R)))
         return (sp,)
 
     def cbr(a, K, R, stride, pad, name, relu=True):
