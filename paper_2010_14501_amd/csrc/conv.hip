@@ -202,9 +202,9 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     int64_t kk0 = kt0 * BK;
     int u_r = 0, u_s = 0, u_c = 0;   // FWD: (r, s, c0); DGRAD: (tap row, tap column, k0)
 
-    float4 a_reg[LA], b_reg[LB];
+    float4 a_set0[LA], b_set0[LB], a_set1[LA], b_set1[LB];   // two register stages: loads run two steps ahead
 
-    auto load_tiles = [&]() {
+    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB]) {
         // ======== A
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
         }
     };
 
-    auto store_tiles = [&](int buf) {
+    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB]) {
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
             int idx = tid + s * NT;
@@ -409,19 +409,29 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
         }
     };
 
+    // Software pipeline, loads two steps ahead: while step t is computed from LDS buffer t%2, the
+    // registers of stage (t+1)%2 hold step t+1 (on its way or landed) and the loads of step t+2 are
+    // issued into stage t%2.
     if (kt0 < kt1) {
-        load_tiles();
-        store_tiles(0);
+        const int64_t steps = kt1 - kt0;
+        load_tiles(a_set0, b_set0);
+        if (steps > 1) load_tiles(a_set1, b_set1);
+        store_tiles(0, a_set0, b_set0);
         __syncthreads();
-        int buf = 0;
-        for (int64_t kt = kt0; kt < kt1; ++kt) {
-            const bool more = kt + 1 < kt1;
-            if (more) load_tiles();
-            compute(buf);
-            if (more) store_tiles(buf ^ 1);
+        int64_t t = 0;
+        for (; t + 1 < steps; t += 2) {
+            // even step: LDS buffer 0, next step waits in stage 1
+            if (t + 2 < steps) load_tiles(a_set0, b_set0);
+            compute(0);
+            store_tiles(1, a_set1, b_set1);
             __syncthreads();
-            buf ^= 1;
+            // odd step: LDS buffer 1, next step waits in stage 0
+            if (t + 3 < steps) load_tiles(a_set1, b_set1);
+            compute(1);
+            if (t + 2 < steps) store_tiles(0, a_set0, b_set0);
+            __syncthreads();
         }
+        if (t < steps) compute(0);   // odd number of steps: the last one sits in buffer 0
     }
 
     // ---------------- epilogue: lane holds column l32 of rows 8*(v/4) + 4*g + v%4 of each 32x32 block
