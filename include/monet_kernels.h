@@ -22,15 +22,19 @@
 extern "C" {
 #endif
 
-/* y[N,P,Q,K] = cross-correlation of x[N,H,W,C] with w[K,R,S,C], zero padding, no bias. */
+/* All three convolution kernels take `splits`: 1 = no workspace; > 1 cuts the reduction into that
+ * many ranges whose partial results go to ws (>= splits * |output| floats, device memory) and are then
+ * added in range order -- more workgroups for layers whose output is small, at the price of workspace.
+ *
+ * y[N,P,Q,K] = cross-correlation of x[N,H,W,C] with w[K,R,S,C], zero padding, no bias. */
 int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
-                   int N, int H, int W, int C, int K, int R, int S, int stride, int pad);
+                   int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                   int splits, float *ws, size_t ws_bytes);
 /* dx[N,H,W,C] (+)= gradient of the above wrt x, from dy[N,P,Q,K]. */
 int monet_conv_dgrad(void *stream, const float *dy, const float *w, float *dx,
-                     int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int accumulate);
-/* dw[K,R,S,C] = gradient wrt w.  splits == 1: no workspace.  splits > 1: the sum over N,P,Q is cut
- * into `splits` ranges whose partial results go to ws (>= splits*K*R*S*C floats) and are then added
- * in range order. */
+                     int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int accumulate,
+                     int splits, float *ws, size_t ws_bytes);
+/* dw[K,R,S,C] = gradient wrt w (reduction over N,P,Q). */
 int monet_conv_wgrad(void *stream, const float *x, const float *dy, float *dw,
                      int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                      int splits, float *ws, size_t ws_bytes);

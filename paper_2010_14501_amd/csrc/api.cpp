@@ -170,6 +170,14 @@ int64_t numel_of(const std::vector<int64_t> &s) {
     return n;
 }
 
+// number of reduction splits an implementation record asks for ("splitk" / "igemm_splitk" carry splits=S)
+int splits_of(const std::string &algo, const Attrs &extra) {
+    if (algo.find("splitk") == std::string::npos) return 1;
+    auto it = extra.find("splits");
+    if (it == extra.end()) throw KernelError("split implementation without a 'splits' field");
+    return std::stoi(it->second);
+}
+
 void run_forward(const StepCtx &c, const Launch &L) {
     const Graph &g = c.mp->plan.g;
     const Node &n = g.nodes[L.id];
@@ -177,7 +185,9 @@ void run_forward(const StepCtx &c, const Launch &L) {
     float *out = (float *)c.ptr(L.a[2]);
     const std::string &op = n.op;
     if (op == "conv") {
-        conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n));
+        const FwdImpl &im = n.fimpls[L.impl];
+        conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
+                 (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (op == "bn") {
         int C = (int)n.shape.back();
         int64_t rows = numel_of(n.shape) / C;
@@ -218,16 +228,11 @@ void run_backward(const StepCtx &c, const Launch &L) {
     const bool acc0 = L.flags & 1;
     const std::string &kd = b.kind;
     if (kd == "conv_wgrad") {
-        int splits = 1;
-        if (im.algo == "splitk") {
-            auto it = im.extra.find("splits");
-            if (it == im.extra.end()) throw KernelError("splitk implementation without a 'splits' field");
-            splits = std::stoi(it->second);
-        }
-        conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits, (float *)c.ptr(L.a[4]),
-                   (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+        conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits_of(im.algo, im.extra),
+                   (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "conv_dgrad") {
-        conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0);
+        conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0, splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
+                   (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "bn_bwd") {
         int C = (int)n.shape.back();
         int64_t rows = numel_of(n.shape) / C;
@@ -433,12 +438,14 @@ static PoolShape mk_pool(int N, int H, int W, int C, int k, int stride, int pad)
 }
 
 extern "C" int monet_conv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
-                              int stride, int pad) {
-    return guarded([&] { conv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad)); });
+                              int stride, int pad, int splits, float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad), splits, ws, ws_bytes); });
 }
 extern "C" int monet_conv_dgrad(void *stream, const float *dy, const float *w, float *dx, int N, int H, int W, int C, int K, int R, int S,
-                                int stride, int pad, int accumulate) {
-    return guarded([&] { conv_dgrad((hipStream_t)stream, dy, w, dx, mk_conv(N, H, W, C, K, R, S, stride, pad), accumulate != 0); });
+                                int stride, int pad, int accumulate, int splits, float *ws, size_t ws_bytes) {
+    return guarded([&] {
+        conv_dgrad((hipStream_t)stream, dy, w, dx, mk_conv(N, H, W, C, K, R, S, stride, pad), accumulate != 0, splits, ws, ws_bytes);
+    });
 }
 extern "C" int monet_conv_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R, int S,
                                 int stride, int pad, int splits, float *ws, size_t ws_bytes) {

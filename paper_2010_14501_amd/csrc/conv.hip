@@ -55,8 +55,9 @@ struct TileArgs {
     int64_t Kg;       // reduction length (DGRAD: recomputed per class)
     int tiles_n;
     int64_t total_tiles;
-    int64_t steps_per_split;   // WGRAD: reduction steps (of BK) handled by one blockIdx.z
-    int accumulate;            // DGRAD: add into dx
+    int splits;                // reduction splits (>= 1); split z writes partial result z
+    int64_t out_elems;         // elements of one (partial) result
+    int accumulate;            // DGRAD, splits == 1: add into dx
 };
 
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
@@ -93,10 +94,14 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     // ---------------- DGRAD: residue class of this launch slice
     int64_t Mg = ta.Mg, Kg = ta.Kg;
     int ph = 0, pw = 0, r0 = 0, s0 = 0, ns = cs.S, bh = cs.pad, bw = cs.pad, Hc = cs.H, Wc = cs.W;
+    // blockIdx.z = reduction split (all modes), times the residue class for DGRAD
+    const int nsplit = ta.splits;
+    const int split = blockIdx.z % nsplit;
     if (MODE == DGRAD) {
         const int st = cs.stride;
-        ph = blockIdx.z / st;
-        pw = blockIdx.z % st;
+        const int cls = blockIdx.z / nsplit;
+        ph = cls / st;
+        pw = cls % st;
         Hc = (cs.H - ph + st - 1) / st;
         Wc = (cs.W - pw + st - 1) / st;
         r0 = (ph + cs.pad) % st;
@@ -108,14 +113,16 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
         Mg = (int64_t)cs.N * Hc * Wc;
         Kg = (int64_t)nr * ns * cs.K;
         if (row0 >= Mg) return;
-        if (Kg == 0 && ta.accumulate) return;       // this class receives no contribution
+        if (Kg == 0 && ta.accumulate && nsplit == 1) return;       // this class receives no contribution
     }
 
-    // reduction range of this workgroup
+    // reduction range of this workgroup: split z takes steps [z*sps, (z+1)*sps) (possibly none: it
+    // then contributes zeros to its partial result)
     int64_t kt0 = 0, kt1 = (Kg + BK - 1) / BK;
-    if (MODE == WGRAD) {
-        kt0 = (int64_t)blockIdx.z * ta.steps_per_split;
-        int64_t e = kt0 + ta.steps_per_split;
+    if (nsplit > 1) {
+        const int64_t sps = (kt1 + nsplit - 1) / nsplit;
+        kt0 = split * sps;
+        int64_t e = kt0 + sps;
         kt1 = e < kt1 ? e : kt1;
     }
 
@@ -201,20 +208,33 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     // ---------------- position of the next step to load (uniform over the workgroup)
     int64_t kk0 = kt0 * BK;
     int u_r = 0, u_s = 0, u_c = 0;   // FWD: (r, s, c0); DGRAD: (tap row, tap column, k0)
+    if (MODE != WGRAD && kt0 > 0) {  // a later reduction split starts in the middle: locate it once
+        const int inner = MODE == FWD ? cs.C : cs.K, cols = MODE == FWD ? cs.S : ns;
+        int tap = (int)(kk0 / inner);
+        u_c = (int)(kk0 % inner);
+        u_r = tap / cols;
+        u_s = tap % cols;
+    }
 
     float4 a_set0[LA], b_set0[LB], a_set1[LA], b_set1[LB];   // two register stages: loads run two steps ahead
 
-    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB]) {
+    // In the aligned variants every load is issued unconditionally (an out-of-range slot reads the
+    // tensor's first 16 bytes instead) and zeroed when it is written to LDS: without branches around
+    // the loads the compiler can count outstanding loads exactly and wait only for the older stage.
+    // pm: bit s = A slot s holds data, bit 16+s = B slot s holds data.
+    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB], unsigned &pm) {
+        pm = 0;
         // ======== A
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
             int idx = tid + s * NT;
             float4 v = make_float4(0, 0, 0, 0);
+            bool ok = !FAST;    // the element-wise variants zero what they do not load
             if (MODE == FWD) {
                 if (FAST) {
                     int h = a_h0[s] + u_r, w = a_w0[s] + u_s;
-                    if (a_ok[s] && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W)
-                        v = ld4(ta.a + a_base[s] + ((int64_t)h * cs.W + w) * cs.C + u_c);
+                    ok = a_ok[s] && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W;
+                    v = ld4(ok ? ta.a + a_base[s] + ((int64_t)h * cs.W + w) * cs.C + u_c : ta.a);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -234,8 +254,8 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 // reduction index = (tap row, tap column, k); FAST: K % 16 == 0 so a step stays inside one tap
                 if (FAST) {
                     int p = a_h0[s] - u_r, q = a_w0[s] - u_s;
-                    if (a_ok[s] && (unsigned)p < (unsigned)cs.P && (unsigned)q < (unsigned)cs.Q)
-                        v = ld4(ta.a + a_base[s] + ((int64_t)p * cs.Q + q) * cs.K + u_c);
+                    ok = a_ok[s] && (unsigned)p < (unsigned)cs.P && (unsigned)q < (unsigned)cs.Q;
+                    v = ld4(ok ? ta.a + a_base[s] + ((int64_t)p * cs.Q + q) * cs.K + u_c : ta.a);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -252,28 +272,30 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 }
             } else {   // WGRAD: A[red = m][row = k] = dy[m][k]
                 int64_t m = kk0 + a_h0[s];
-                if (m < Kg) {
-                    if (FAST) {
-                        if (a_ok[s]) v = ld4(ta.a + m * cs.K + a_w0[s]);
-                    } else {
-                        float e[4] = {0, 0, 0, 0};
+                if (FAST) {
+                    ok = a_ok[s] && m < Kg;
+                    v = ld4(ok ? ta.a + m * cs.K + a_w0[s] : ta.a);
+                } else if (m < Kg) {
+                    float e[4] = {0, 0, 0, 0};
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            if (a_w0[s] + u < cs.K) e[u] = ta.a[m * cs.K + a_w0[s] + u];
-                        v = make_float4(e[0], e[1], e[2], e[3]);
-                    }
+                    for (int u = 0; u < 4; ++u)
+                        if (a_w0[s] + u < cs.K) e[u] = ta.a[m * cs.K + a_w0[s] + u];
+                    v = make_float4(e[0], e[1], e[2], e[3]);
                 }
             }
             a_reg[s] = v;
+            if (ok) pm |= 1u << s;
         }
         // ======== B
 #pragma unroll
         for (int s = 0; s < LB; ++s) {
             int idx = tid + s * NT;
             float4 v = make_float4(0, 0, 0, 0);
+            bool ok = !FAST;
             if (MODE == FWD) {
                 if (FAST) {
-                    if (b_ok[s]) v = ld4(ta.b + (int64_t)b_i0[s] * RSC + kk0 + b_i1[s]);
+                    ok = b_ok[s];
+                    v = ld4(ok ? ta.b + (int64_t)b_i0[s] * RSC + kk0 + b_i1[s] : ta.b);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -284,32 +306,33 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
             } else if (MODE == DGRAD) {
                 // B[red = (tap, k)][col = c] = W[k][r0 + st*tr][s0 + st*ts][c]
                 int64_t kk = kk0 + b_i0[s];
-                if (kk < Kg) {
-                    int tr, ts, k;
-                    if (FAST) { tr = u_r; ts = u_s; k = u_c + b_i0[s]; }
-                    else { int tap = (int)kk / cs.K; k = (int)kk % cs.K; tr = tap / ns; ts = tap % ns; }
-                    int r = r0 + cs.stride * tr, ss = s0 + cs.stride * ts;
+                if (FAST) {
+                    int r = r0 + cs.stride * u_r, ss = s0 + cs.stride * u_s;
+                    ok = b_ok[s] && kk < Kg;
+                    v = ld4(ok ? ta.b + (int64_t)(u_c + b_i0[s]) * RSC + (r * cs.S + ss) * cs.C + b_i1[s] : ta.b);
+                } else if (kk < Kg) {
+                    int tap = (int)kk / cs.K, k = (int)kk % cs.K;
+                    int r = r0 + cs.stride * (tap / ns), ss = s0 + cs.stride * (tap % ns);
                     const float *src = ta.b + (int64_t)k * RSC + (r * cs.S + ss) * cs.C + b_i1[s];
-                    if (FAST) {
-                        if (b_ok[s]) v = ld4(src);
-                    } else {
-                        float e[4] = {0, 0, 0, 0};
+                    float e[4] = {0, 0, 0, 0};
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            if (b_i1[s] + u < cs.C) e[u] = src[u];
-                        v = make_float4(e[0], e[1], e[2], e[3]);
-                    }
+                    for (int u = 0; u < 4; ++u)
+                        if (b_i1[s] + u < cs.C) e[u] = src[u];
+                    v = make_float4(e[0], e[1], e[2], e[3]);
                 }
             } else {   // WGRAD: B[red = m][col = (r,s,c)] = x[n, p*st+r-pad, q*st+s-pad, c]
                 int64_t m = kk0 + b_i0[s];
-                if (m < Kg) {
+                if (FAST) {
+                    int h0 = w_p[s] * cs.stride - cs.pad, w0 = w_q[s] * cs.stride - cs.pad;
+                    int h = h0 + (b_i1[s] >> 24), w = w0 + (b_i2[s] >> 24);
+                    ok = b_ok[s] && m < Kg && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W;
+                    v = ld4(ok ? ta.b + ((int64_t)w_n[s] * cs.H * cs.W + (int64_t)h0 * cs.W + w0 + (b_i1[s] & 0xffffff)) * cs.C +
+                                     (b_i2[s] & 0xffffff)
+                               : ta.b);
+                } else if (m < Kg) {
                     int h0 = w_p[s] * cs.stride - cs.pad, w0 = w_q[s] * cs.stride - cs.pad;
                     const float *img = ta.b + (int64_t)w_n[s] * cs.H * cs.W * cs.C;
-                    if (FAST) {
-                        int h = h0 + (b_i1[s] >> 24), w = w0 + (b_i2[s] >> 24);
-                        if (b_ok[s] && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W)
-                            v = ld4(img + ((int64_t)h0 * cs.W + w0 + (b_i1[s] & 0xffffff)) * cs.C + (b_i2[s] & 0xffffff));
-                    } else {
+                    {
                         float e[4] = {0, 0, 0, 0};
                         int col = col0 + (idx % (BN / 4)) * 4;
 #pragma unroll
@@ -328,6 +351,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 }
             }
             b_reg[s] = v;
+            if (ok) pm |= 1u << (16 + s);
         }
         // ======== advance to the next step
         kk0 += BK;
@@ -349,18 +373,21 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
         }
     };
 
-    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB]) {
+    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB], unsigned pm) {
+        const float4 zero = make_float4(0, 0, 0, 0);
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
             int idx = tid + s * NT;
-            if (A_KC) *(float4 *)&As[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = a_reg[s];
-            else *(float4 *)&As[buf][(idx / (BM / 4)) * A_LD + (idx % (BM / 4)) * 4] = a_reg[s];
+            float4 v = (pm >> s) & 1 ? a_reg[s] : zero;
+            if (A_KC) *(float4 *)&As[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
+            else *(float4 *)&As[buf][(idx / (BM / 4)) * A_LD + (idx % (BM / 4)) * 4] = v;
         }
 #pragma unroll
         for (int s = 0; s < LB; ++s) {
             int idx = tid + s * NT;
-            if (B_KC) *(float4 *)&Bs[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = b_reg[s];
-            else *(float4 *)&Bs[buf][(idx / (BN / 4)) * B_LD + (idx % (BN / 4)) * 4] = b_reg[s];
+            float4 v = (pm >> (16 + s)) & 1 ? b_reg[s] : zero;
+            if (B_KC) *(float4 *)&Bs[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
+            else *(float4 *)&Bs[buf][(idx / (BN / 4)) * B_LD + (idx % (BN / 4)) * 4] = v;
         }
     };
 
@@ -414,29 +441,50 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     // issued into stage t%2.
     if (kt0 < kt1) {
         const int64_t steps = kt1 - kt0;
-        load_tiles(a_set0, b_set0);
-        if (steps > 1) load_tiles(a_set1, b_set1);
-        store_tiles(0, a_set0, b_set0);
+        unsigned pm0 = 0, pm1 = 0;
+        load_tiles(a_set0, b_set0, pm0);
+        if (steps > 1) load_tiles(a_set1, b_set1, pm1);
+        store_tiles(0, a_set0, b_set0, pm0);
         __syncthreads();
         int64_t t = 0;
-        for (; t + 1 < steps; t += 2) {
+        // The scheduling fences keep the order loads -> MFMAs -> LDS write -> barrier: left alone, the
+        // compiler hoists the LDS write (and with it the wait for the loads) above the MFMAs.
+        // Steady state: both halves always issue their loads, so the number of loads in flight at
+        // each LDS write is the same on every path and the wait can name exactly the older stage.
+        for (; t + 3 < steps; t += 2) {
             // even step: LDS buffer 0, next step waits in stage 1
-            if (t + 2 < steps) load_tiles(a_set0, b_set0);
+            load_tiles(a_set0, b_set0, pm0);
+            __builtin_amdgcn_sched_barrier(0);
             compute(0);
-            store_tiles(1, a_set1, b_set1);
+            __builtin_amdgcn_sched_barrier(0);
+            store_tiles(1, a_set1, b_set1, pm1);
             __syncthreads();
             // odd step: LDS buffer 1, next step waits in stage 0
-            if (t + 3 < steps) load_tiles(a_set1, b_set1);
+            load_tiles(a_set1, b_set1, pm1);
+            __builtin_amdgcn_sched_barrier(0);
             compute(1);
-            if (t + 2 < steps) store_tiles(0, a_set0, b_set0);
+            __builtin_amdgcn_sched_barrier(0);
+            store_tiles(0, a_set0, b_set0, pm0);
             __syncthreads();
         }
-        if (t < steps) compute(0);   // odd number of steps: the last one sits in buffer 0
+        // Drain: one to three steps are left; step t sits in buffer 0, step t+1 (if any) in stage 1.
+        if (t + 2 < steps) load_tiles(a_set0, b_set0, pm0);
+        compute(0);
+        if (t + 1 < steps) {
+            store_tiles(1, a_set1, b_set1, pm1);
+            __syncthreads();
+            compute(1);
+            if (t + 2 < steps) {
+                store_tiles(0, a_set0, b_set0, pm0);
+                __syncthreads();
+                compute(0);
+            }
+        }
     }
 
     // ---------------- epilogue: lane holds column l32 of rows 8*(v/4) + 4*g + v%4 of each 32x32 block
     float *out = ta.out;
-    if (MODE == WGRAD) out += (int64_t)blockIdx.z * ta.Mg * ta.Ng;
+    out += (int64_t)split * ta.out_elems;
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -457,7 +505,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
                 if (col < ta.Ng) {
                     float *dst = out + orow * ta.Ng + col;
                     float r = acc[mi][ni][v];
-                    if (MODE == DGRAD && ta.accumulate) r += *dst;
+                    if (MODE == DGRAD && ta.accumulate && nsplit == 1) r += *dst;
                     *dst = r;
                 }
             }
@@ -468,7 +516,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
 // of 64 consecutive elements (four independent partial sums per lane to keep loads in flight),
 // then the SL per-wave sums are added in wave order.
 template <int SL>
-__global__ __launch_bounds__(64 * SL) void wgrad_reduce_kernel(const float *__restrict__ ws, float *__restrict__ dw, int64_t n, int splits) {
+__global__ __launch_bounds__(64 * SL) void split_reduce_kernel(const float *__restrict__ ws, float *dw, int64_t n, int splits, int accumulate) {
     __shared__ float sh[SL][64];
     const int lane = threadIdx.x & 63, sl = threadIdx.x >> 6;
     for (int64_t base = (int64_t)blockIdx.x * 64; base < n; base += (int64_t)gridDim.x * 64) {
@@ -490,18 +538,19 @@ __global__ __launch_bounds__(64 * SL) void wgrad_reduce_kernel(const float *__re
             float s = sh[0][lane];
 #pragma unroll
             for (int j = 1; j < SL; ++j) s += sh[j][lane];
-            dw[i] = s;
+            dw[i] = accumulate ? dw[i] + s : s;
         }
         __syncthreads();
     }
 }
 
-void launch_wgrad_reduce(hipStream_t st, const float *ws, float *dw, int64_t n, int splits) {
+void launch_split_reduce(hipStream_t st, const float *ws, float *dw, int64_t n, int splits, bool accumulate) {
+    const int acc = accumulate ? 1 : 0;
     int grid = (int)std::min<int64_t>((n + 63) / 64, 8192);
-    if (splits >= 64) hipLaunchKernelGGL((wgrad_reduce_kernel<16>), dim3(grid), dim3(1024), 0, st, ws, dw, n, splits);
-    else if (splits >= 16) hipLaunchKernelGGL((wgrad_reduce_kernel<4>), dim3(grid), dim3(256), 0, st, ws, dw, n, splits);
-    else hipLaunchKernelGGL((wgrad_reduce_kernel<1>), dim3(grid), dim3(64), 0, st, ws, dw, n, splits);
-    hip_check(hipGetLastError(), "wgrad reduce launch");
+    if (splits >= 64) hipLaunchKernelGGL((split_reduce_kernel<16>), dim3(grid), dim3(1024), 0, st, ws, dw, n, splits, acc);
+    else if (splits >= 16) hipLaunchKernelGGL((split_reduce_kernel<4>), dim3(grid), dim3(256), 0, st, ws, dw, n, splits, acc);
+    else hipLaunchKernelGGL((split_reduce_kernel<1>), dim3(grid), dim3(64), 0, st, ws, dw, n, splits, acc);
+    hip_check(hipGetLastError(), "split reduce launch");
 }
 
 void check_shape(const ConvShape &cs) {
@@ -563,49 +612,60 @@ void launch_cfg(hipStream_t st, const TileArgs &ta, bool fast, int zdim, int cfg
 
 void conv_force_tile(int cfg) { g_cfg_override = cfg; }
 
-void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs) {
-    check_shape(cs);
-    TileArgs ta{};
-    ta.a = x; ta.b = w; ta.out = y; ta.cs = cs;
-    ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
-    bool fast = cs.C % BK == 0;
-    launch_cfg<FWD>(st, ta, fast, 1, pick_cfg(FWD, ta.Mg, ta.Ng));
+// splits > 1: partial results go to ws (splits * |out| floats) and are added in split order
+static float *split_target(float *out, int64_t out_elems, int &splits, float *ws, size_t ws_bytes, int64_t steps, const char *who) {
+    if (splits < 1) throw KernelError(std::string(who) + ": splits must be >= 1");
+    if (splits > steps) splits = (int)std::max<int64_t>(steps, 1);
+    if (splits == 1) return out;
+    if (!ws || ws_bytes < (size_t)splits * out_elems * 4) throw KernelError(std::string(who) + ": workspace too small for the requested splits");
+    return ws;
 }
 
-void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate) {
+void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
     check_shape(cs);
     TileArgs ta{};
-    ta.a = dy; ta.b = w; ta.out = dx; ta.cs = cs;
+    ta.a = x; ta.b = w; ta.cs = cs;
+    ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
+    ta.out_elems = ta.Mg * ta.Ng;
+    ta.out = split_target(y, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_fwd");
+    ta.splits = splits;
+    bool fast = cs.C % BK == 0;
+    launch_cfg<FWD>(st, ta, fast, splits, pick_cfg(FWD, ta.Mg, ta.Ng));
+    if (splits > 1) launch_split_reduce(st, ws, y, ta.out_elems, splits, false);
+}
+
+void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits, float *ws,
+                size_t ws_bytes) {
+    check_shape(cs);
+    TileArgs ta{};
+    ta.a = dy; ta.b = w; ta.cs = cs;
     const int stc = cs.stride;
     ta.Mg = (int64_t)cs.N * ((cs.H + stc - 1) / stc) * ((cs.W + stc - 1) / stc);   // rows of residue class (0,0), the largest
     ta.Ng = cs.C;
     ta.Kg = 0;   // per class, computed in the kernel
+    ta.out_elems = (int64_t)cs.N * cs.H * cs.W * cs.C;
+    // the shortest class reduction bounds the useful number of splits
+    int64_t min_steps = ((int64_t)std::max(1, cs.R / stc) * std::max(1, cs.S / stc) * cs.K + BK - 1) / BK;
+    ta.out = split_target(dx, ta.out_elems, splits, ws, ws_bytes, min_steps, "conv_dgrad");
+    ta.splits = splits;
     ta.accumulate = accumulate ? 1 : 0;
     bool fast = cs.K % BK == 0 && cs.C % 4 == 0;
-    int zdim = stc * stc;
+    int zdim = stc * stc * splits;
     launch_cfg<DGRAD>(st, ta, fast, zdim, pick_cfg(DGRAD, ta.Mg, ta.Ng));
+    if (splits > 1) launch_split_reduce(st, ws, dx, ta.out_elems, splits, accumulate);
 }
 
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
     check_shape(cs);
-    if (splits < 1) throw KernelError("conv_wgrad: splits must be >= 1");
     TileArgs ta{};
     ta.a = dy; ta.b = x; ta.cs = cs;
     ta.Mg = cs.K; ta.Ng = (int)cs.RSC(); ta.Kg = cs.M();
-    int64_t steps = (ta.Kg + BK - 1) / BK;
-    if (splits > steps) splits = (int)steps;
-    ta.steps_per_split = (steps + splits - 1) / splits;
-    splits = (int)((steps + ta.steps_per_split - 1) / ta.steps_per_split);   // no empty split
-    int64_t n = (int64_t)cs.K * cs.RSC();
-    if (splits > 1) {
-        if (!ws || ws_bytes < (size_t)splits * n * 4) throw KernelError("conv_wgrad: workspace too small for the requested splits");
-        ta.out = ws;
-    } else {
-        ta.out = dw;
-    }
+    ta.out_elems = (int64_t)cs.K * cs.RSC();
+    ta.out = split_target(dw, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_wgrad");
+    ta.splits = splits;
     bool fast = cs.K % 4 == 0 && cs.C % 4 == 0;
     launch_cfg<WGRAD>(st, ta, fast, splits, pick_cfg(WGRAD, ta.Mg, ta.Ng));
-    if (splits > 1) launch_wgrad_reduce(st, ws, dw, n, splits);
+    if (splits > 1) launch_split_reduce(st, ws, dw, ta.out_elems, splits, false);
 }
 
 }  // namespace monet

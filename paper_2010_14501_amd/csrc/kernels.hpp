@@ -29,10 +29,14 @@ struct ConvShape {
 };
 
 // ---- convolution (implicit GEMM on fp32 MFMA)
-void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);
+// Every variant can cut its reduction into `splits` ranges: partial results go to ws (splits * |output|
+// floats) and are added in range order.  splits == 1 needs no workspace.
+void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits = 1, float *ws = nullptr,
+              size_t ws_bytes = 0);
 // dx (+)= transpose-conv of dy with w
-void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate);
-// dw = sum over N,P,Q; splits > 1 needs ws of splits*K*R*S*C floats (partial sums, reduced in split order)
+void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits = 1,
+                float *ws = nullptr, size_t ws_bytes = 0);
+// dw = sum over N,P,Q
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws,
                 size_t ws_bytes);
 

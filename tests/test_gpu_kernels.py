@@ -58,16 +58,30 @@ def test_conv_trio_matches_oracle(case):
     dx, dwt, ddy = dev(x), dev(w), dev(dy)
     # forward
     y = torch.empty((N, P, Q, K), dtype=torch.float32, device="cuda")
-    monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad)
+    monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, None, 0)
     want = wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad))
     assert rel(y.cpu().numpy(), want) < ACT_TOL
+    big = torch.empty(5 * max(y.numel(), N * H * W * C), dtype=torch.float32, device="cuda")     # split workspace
+    for splits in (2, 5):
+        y.fill_(float("nan"))
+        monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad,
+                   splits, big.data_ptr(), big.numel() * 4)
+        assert rel(y.cpu().numpy(), want) < ACT_TOL, splits
     # input gradient, plain and accumulating
     gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
-    monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0)
+    monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0, 1, None, 0)
     want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, stride, pad))
     assert rel(gx.cpu().numpy(), want) < GRAD_TOL
-    monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1)
+    monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, 1, None, 0)
     assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    for splits in (2, 5):
+        gx.fill_(float("nan"))
+        monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0,
+                   splits, big.data_ptr(), big.numel() * 4)
+        assert rel(gx.cpu().numpy(), want) < GRAD_TOL, splits
+        monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1,
+                   splits, big.data_ptr(), big.numel() * 4)
+        assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL, splits
     # weight gradient: no workspace, and split with workspace
     want = wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, R, R, stride, pad))
     for splits in (1, 3, 8):
@@ -84,7 +98,9 @@ def test_conv_wgrad_rejects_small_workspace():
     with pytest.raises(M.MonetError):
         monet.call("monet_conv_wgrad", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 1, 1, 4, t.data_ptr(), 64)
     with pytest.raises(M.MonetError):
-        monet.call("monet_conv_fwd", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 0, 1)
+        monet.call("monet_conv_fwd", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 0, 1, 1, None, 0)
+    with pytest.raises(M.MonetError):
+        monet.call("monet_conv_fwd", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 1, 1, 4, t.data_ptr(), 64)
 
 
 BN_CASES = [(2 * 16 * 16, 16), (3 * 14 * 14, 64), (1000, 256), (77, 2048), (5 * 33 * 31, 128), (4096, 24)]

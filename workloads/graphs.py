@@ -109,11 +109,20 @@ class Graph:
         i = self._add("conv", [x], [w], (N, P, Q, K), R=R, S=S, stride=stride, pad=pad)
         flop = 2.0 * N * P * Q * K * C * R * S
         self.fimpls[i] = [dict(algo="igemm", ws=0, cost=flop)]
+        # Layers with few output tiles leave most of the 256 CUs idle: offer a variant that cuts the
+        # reduction into `splits` ranges (more workgroups) and pays for it with workspace.
+        sp = _fill_splits(N * P * Q, K, C * R * S)
+        if sp > 1:
+            self.fimpls[i].append(dict(algo="igemm_splitk", ws=_align(sp * 4 * N * P * Q * K), cost=flop * 0.8, splits=sp))
+        dg = [dict(algo="igemm", deps=[], ws=0, cost=flop)]
+        sp = _fill_splits(N * H * W // (stride * stride), C, max(1, R // stride) * max(1, S // stride) * K)
+        if sp > 1:
+            dg.append(dict(algo="igemm_splitk", deps=[], ws=_align(sp * 4 * N * H * W * C), cost=flop * 0.8, splits=sp))
         wbytes = 4 * K * R * S * C
         wg = [dict(algo="direct", ws=0, cost=flop * 4.0)]
         for sp in wgrad_splits:
             wg.append(dict(algo="splitk", ws=_align(sp * wbytes), cost=flop * (1.0 + 0.02 * sp), splits=sp))
-        self._pending_bops(i, [("conv_dgrad", [dict(algo="igemm", deps=[], ws=0, cost=flop)])] if x > 0 else [],
+        self._pending_bops(i, [("conv_dgrad", dg)] if x > 0 else [],
                            [("conv_wgrad", [dict(d, deps=[x] if x > 0 else []) for d in wg])])
         return i
 
@@ -269,6 +278,15 @@ class Graph:
                         rec += f" {kk}={v}"
                 out.append(rec)
         return "\n".join(out) + "\n"
+
+
+def _fill_splits(rows, cols, reduction):
+    """Reduction splits for a rows x cols GEMM with 128x128 tiles: aim at about four workgroups per CU,
+    keep at least eight reduction steps of 16 per split."""
+    tiles = math.ceil(rows / 128) * math.ceil(cols / 128)
+    if tiles >= 1024:
+        return 1
+    return max(1, min(math.ceil(1200 / tiles), reduction // 128, 16))
 
 
 def _align(b, a=256):

@@ -28,11 +28,11 @@ from .graphs import Graph
 
 DEFAULT_VARIANTS = dict(
     bn_bwd="from_output", relu_bwd="from_mask", relu6_bwd="from_mask", maxpool_bwd="from_index",
-    conv_wgrad="splitk", inplace=True,
+    conv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=True,
 )
 STANDARD_VARIANTS = dict(
     bn_bwd="from_input", relu_bwd="from_output", relu6_bwd="from_output", maxpool_bwd="from_input",
-    conv_wgrad="splitk", inplace=False,
+    conv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=False,
 )
 
 
@@ -90,7 +90,7 @@ def deps_of(g: Graph, k, l):
     return [d for d in g.bimpls[k][l]["deps"] if d > 0]
 
 
-def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm"):
+def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm_splitk"):
     """Schedule for forward-saved set F (node ids) and backward impl choice {k: l}."""
     N, B = len(g.nodes), len(g.bops)
     sch = Schedule(N, B)
@@ -108,7 +108,10 @@ def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm"):
     def pick_fimpl(i, inplace):
         n = g.nodes[i - 1]
         if n.op == "conv":
-            return g.fimpl_index(i, conv_algo)
+            try:
+                return g.fimpl_index(i, conv_algo)
+            except KeyError:        # the preferred variant is only offered where it pays
+                return 0
         if inplace:
             return g.fimpl_index(i, "inplace")
         return 0
@@ -245,13 +248,14 @@ def tiny_chain_schedule(g: Graph, checkpoint_blocks, variants=None):
     variants = DEFAULT_VARIANTS if variants is None else variants
     bimpl = choose_bimpls(g, variants)
     F = block_checkpoint_set(g, bimpl, set(checkpoint_blocks))
-    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True))
+    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True), conv_algo=variants.get("conv_fwd", "igemm"))
 
 
 def store_everything_schedule(g: Graph, variants=None):
     variants = STANDARD_VARIANTS if variants is None else variants
     bimpl = choose_bimpls(g, variants)
-    return expand(g, store_everything_set(g, bimpl), bimpl, allow_inplace=variants.get("inplace", False))
+    return expand(g, store_everything_set(g, bimpl), bimpl, allow_inplace=variants.get("inplace", False),
+                  conv_algo=variants.get("conv_fwd", "igemm"))
 
 
 def block_output_schedule(g: Graph, variants=None, blocks=None):
@@ -265,4 +269,4 @@ def block_output_schedule(g: Graph, variants=None, blocks=None):
         for d in deps_of(g, b["k"], bimpl[b["k"]]):
             if g.is_aux(d) and g.nodes[d - 1].ins[0] in F:
                 F.add(d)
-    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True))
+    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True), conv_algo=variants.get("conv_fwd", "igemm"))
