@@ -63,7 +63,7 @@ struct TileArgs {
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
 template <int MODE, int WM, int WN, bool FAST>
-__global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 ? 3 : 2)) void conv_tile_kernel(TileArgs ta) {
     constexpr int BM = 64 * WM, BN = 64 * WN, NT = 64 * WM * WN;
     constexpr bool A_KC = (MODE != WGRAD);          // A operand reduction-contiguous?
     constexpr bool B_KC = (MODE == FWD);
@@ -485,6 +485,44 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_tile_kernel(TileArgs ta) {
     // ---------------- epilogue: lane holds column l32 of rows 8*(v/4) + 4*g + v%4 of each 32x32 block
     float *out = ta.out;
     out += (int64_t)split * ta.out_elems;
+    const bool do_acc = MODE == DGRAD && ta.accumulate && nsplit == 1;
+    if (FAST && (ta.Ng & 3) == 0) {
+        // Vector path: each wave transposes its 64x64 result through a private 16x64 LDS patch, four
+        // passes of 16 rows, and writes whole 16-byte pieces, 256 contiguous bytes per row.
+        constexpr int NW = WM * WN;
+        __syncthreads();   // every wave has finished reading the operand tiles
+        float *stage = (2 * A_SZ >= NW * 1024 ? &As[0][0] : &Bs[0][0]) + wave * 1024;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int mi = q >> 1, vbase = 8 * (q & 1);
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int vv = 0; vv < 8; ++vv)
+                    stage[(8 * (vv >> 2) + 4 * g + (vv & 3)) * 64 + ni * 32 + l32] = acc[mi][ni][vbase + vv];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = lane + 64 * i, rl = idx >> 4, c4 = idx & 15;
+                float4 val = *(const float4 *)&stage[rl * 64 + 4 * c4];
+                const int64_t row = row0 + wm * 64 + 16 * q + rl;
+                const int col = col0 + wn * 64 + 4 * c4;
+                if (row < Mg && col < ta.Ng) {
+                    int64_t orow = row;
+                    if (MODE == DGRAD && cs.stride > 1) {
+                        int wc = (int)(row % Wc);
+                        int64_t t = row / Wc;
+                        int hc = (int)(t % Hc);
+                        int64_t n = t / Hc;
+                        orow = (n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
+                    }
+                    float4 *dst = (float4 *)(out + orow * ta.Ng + col);
+                    if (do_acc) { float4 o = *dst; val.x += o.x; val.y += o.y; val.z += o.z; val.w += o.w; }
+                    *dst = val;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
