@@ -160,6 +160,14 @@ typedef struct monet_launch_info {
     char label[32];
 } monet_launch_info;
 
+/* Adjacent bandwidth-bound operators (BatchNorm-apply or add followed by ReLU; ReLU backward followed
+ * by BatchNorm backward or by the add's backward) are launched as one fused kernel by default; the
+ * trace and the results are the same either way.  Off: one kernel per operator.  The poison and
+ * stop-after modes always run unfused. */
+int monet_plan_set_fusion(monet_plan *plan, int on);
+
+/* Launch records of the program monet_step currently runs (a fused pair counts once and carries a
+ * combined label such as "bn_relu_fwd"). */
 int monet_plan_num_launches(const monet_plan *plan);
 int monet_plan_launch_info(const monet_plan *plan, size_t index, monet_launch_info *out);
 

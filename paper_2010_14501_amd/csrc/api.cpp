@@ -14,8 +14,23 @@ using namespace monet;
 
 static thread_local std::string g_err;
 
+struct monet_plan;
+namespace {
+void build_programs(monet_plan *p);
+}
+
+// One entry of the step program: a single operator launch, or two neighbours run as one fused kernel.
+enum { FUSE_NONE = 0, FUSE_BN_RELU_FWD, FUSE_ADD_RELU_FWD, FUSE_RELU_BN_BWD, FUSE_RELU_ADD_BWD };
+struct ProgStep {
+    int fuse;
+    size_t a, b;   // indices into Plan::launches (b only when fused)
+};
+
 struct monet_plan {
     Plan plan;
+    std::vector<ProgStep> prog_plain, prog_fused;
+    bool fusion = true;
+    bool timed_fused = false;
     char *base = nullptr;      // device memory bound by the caller
     size_t bound_bytes = 0;
     bool poison = false;
@@ -54,6 +69,7 @@ extern "C" int monet_plan_load(const char *graph, size_t graph_len, const char *
     int rc = guarded([&] {
         p = new monet_plan();
         p->plan.build(std::string(graph, graph_len), std::string(schedule, schedule_len));
+        build_programs(p);
     });
     if (rc != MONET_OK) { delete p; return rc; }
     *out = p;
@@ -272,6 +288,140 @@ void run_backward(const StepCtx &c, const Launch &L) {
 
 }  // namespace
 
+namespace {
+
+// neighbouring operators whose kinds and data flow allow one kernel
+int fusable_pattern(const Plan &pl, const Launch &L1, const Launch &L2) {
+    const Graph &g = pl.g;
+    const bool f1 = L1.kind != EV_RUN_BWD, f2 = L2.kind != EV_RUN_BWD;
+    if (f1 && f2) {
+        const Node &n1 = g.nodes[L1.id], &n2 = g.nodes[L2.id];
+        if ((n2.op != "relu" && n2.op != "relu6") || n2.ins[0] != n1.id) return FUSE_NONE;
+        if (numel_of(n2.shape) % 4) return FUSE_NONE;
+        if (n1.op == "bn" && n1.shape.back() % 4 == 0) return FUSE_BN_RELU_FWD;
+        if (n1.op == "add") return FUSE_ADD_RELU_FWD;
+        return FUSE_NONE;
+    }
+    if (!f1 && !f2) {
+        const Bop &b1 = g.bops[L1.id], &b2 = g.bops[L2.id];
+        if (b1.kind != "relu_bwd" && b1.kind != "relu6_bwd") return FUSE_NONE;
+        const Node &r = g.nodes[b1.node];
+        if (b2.node != r.ins[0] || (L1.flags & 1) || numel_of(r.shape) % 4) return FUSE_NONE;
+        if (b2.kind == "bn_bwd" && b1.impls[L1.impl].algo == "from_mask") return FUSE_RELU_BN_BWD;
+        if (b2.kind == "add_bwd") return FUSE_RELU_ADD_BWD;
+    }
+    return FUSE_NONE;
+}
+
+// A fused kernel reads the first operator's inputs while it writes the second operator's outputs.
+// In the one-by-one order those inputs may already be freed when the outputs are allocated, so the
+// arena may have placed an output on top of them.  Same offset and same size is harmless for a
+// tensor that every thread reads and writes at its own index; any other overlap forbids fusion.
+struct Span { Ref r; int64_t bytes; bool same_index_ok; };
+bool spans_conflict(const std::vector<Span> &ins, const std::vector<Span> &outs) {
+    for (const Span &o : outs) {
+        if (o.r.region != R_ARENA) continue;
+        for (const Span &i : ins) {
+            if (i.r.region != R_ARENA) continue;
+            const bool disjoint = o.r.off + o.bytes <= i.r.off || i.r.off + i.bytes <= o.r.off;
+            if (disjoint) continue;
+            if (i.same_index_ok && i.r.off == o.r.off && i.bytes == o.bytes) continue;
+            return true;
+        }
+    }
+    return false;
+}
+
+// which neighbours can share a kernel
+int fusable(const Plan &pl, const Launch &L1, const Launch &L2) {
+    const Graph &g = pl.g;
+    int f = fusable_pattern(pl, L1, L2);
+    if (!f) return FUSE_NONE;
+    std::vector<Span> ins, outs;
+    if (f == FUSE_BN_RELU_FWD || f == FUSE_ADD_RELU_FWD) {
+        const Node &n1 = g.nodes[L1.id], &n2 = g.nodes[L2.id];
+        ins.push_back({L1.a[0], n1.bytes, true});
+        if (f == FUSE_ADD_RELU_FWD) ins.push_back({L1.a[1], n1.bytes, true});
+        if (!(L2.flags & 1)) outs.push_back({L1.a[2], n1.bytes, false});
+        outs.push_back({L2.a[2], n2.bytes, false});
+        if (L2.flags & 2) outs.push_back({L2.a[3], g.nodes[n2.aux_children[0]].bytes, false});
+    } else {
+        const Bop &b1 = g.bops[L1.id], &b2 = g.bops[L2.id];
+        const Node &r = g.nodes[b1.node];
+        const bool from_mask = b1.impls[L1.impl].algo == "from_mask";
+        ins.push_back({L1.a[0], r.bytes, true});
+        ins.push_back({L1.a[1], from_mask ? g.nodes[r.aux_children[0]].bytes : r.bytes, !from_mask});
+        if (f == FUSE_RELU_BN_BWD) ins.push_back({L2.a[1], r.bytes, true});
+        outs.push_back({L2.a[2], r.bytes, false});
+        if (f == FUSE_RELU_ADD_BWD) outs.push_back({L2.a[3], r.bytes, false});
+    }
+    // an output may sit exactly on one input, but then on no other, and two outputs never share memory
+    return spans_conflict(ins, outs) ? FUSE_NONE : f;
+}
+
+void build_programs(monet_plan *p) {
+    const Plan &pl = p->plan;
+    for (size_t i = 0; i < pl.launches.size(); ++i) p->prog_plain.push_back(ProgStep{FUSE_NONE, i, i});
+    for (size_t i = 0; i < pl.launches.size(); ++i) {
+        int f = i + 1 < pl.launches.size() ? fusable(pl, pl.launches[i], pl.launches[i + 1]) : FUSE_NONE;
+        if (f) { p->prog_fused.push_back(ProgStep{f, i, i + 1}); ++i; }
+        else p->prog_fused.push_back(ProgStep{FUSE_NONE, i, i});
+    }
+}
+
+void run_fused(const StepCtx &c, const ProgStep &ps) {
+    const Graph &g = c.mp->plan.g;
+    const Launch &L1 = c.mp->plan.launches[ps.a], &L2 = c.mp->plan.launches[ps.b];
+    if (ps.fuse == FUSE_BN_RELU_FWD || ps.fuse == FUSE_ADD_RELU_FWD) {
+        const Node &n1 = g.nodes[L1.id], &n2 = g.nodes[L2.id];
+        const float *x = (const float *)c.ptr(L1.a[0]);
+        const bool relu_inplace = L2.flags & 1;
+        float *pre = relu_inplace ? nullptr : (float *)c.ptr(L1.a[2]);   // the tensor between the two is only written if it survives
+        float *out = (float *)c.ptr(L2.a[2]);
+        uint64_t *mask = (L2.flags & 2) ? (uint64_t *)c.ptr(L2.a[3]) : nullptr;
+        const int64_t n = numel_of(n2.shape);
+        const bool six = n2.op == "relu6";
+        if (ps.fuse == FUSE_BN_RELU_FWD) {
+            const int C = (int)n1.shape.back();
+            float *stats = c.bn_stats(L1.id);
+            if (L1.kind == EV_RUN_FWD)
+                bn_stats(c.st, x, stats, n / C, C, (float)n1.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
+            fwd_chain(c.st, x, nullptr, c.weights[n1.pars[0]], c.weights[n1.pars[1]], stats, C, pre, out, mask, n, six);
+        } else {
+            fwd_chain(c.st, x, (const float *)c.ptr(L1.a[1]), nullptr, nullptr, nullptr, 0, pre, out, mask, n, six);
+        }
+        return;
+    }
+    const Bop &b1 = g.bops[L1.id], &b2 = g.bops[L2.id];
+    const Node &r = g.nodes[b1.node];
+    const std::string &algo = b1.impls[L1.impl].algo;
+    const float *dz = (const float *)c.ptr(L1.a[0]);
+    const void *t = c.ptr(L1.a[1]);
+    const int64_t n = numel_of(r.shape);
+    const bool six = b1.kind == "relu6_bwd";
+    if (ps.fuse == FUSE_RELU_BN_BWD) {
+        const Node &bn = g.nodes[b2.node];
+        const int C = (int)bn.shape.back();
+        bn_bwd(c.st, dz, (const float *)c.ptr(L2.a[1]), b2.impls[L2.impl].algo == "from_output", c.weights[bn.pars[0]], c.weights[bn.pars[1]],
+               c.bn_stats(b2.node), (float *)c.ptr(L2.a[2]), c.grads[bn.pars[0]], c.grads[bn.pars[1]], n / C, C, (L2.flags & 1) != 0, c.scratch(),
+               c.scratch_bytes(), (const uint64_t *)t);
+    } else {
+        const Node &ad = g.nodes[b2.node];
+        int mode = algo == "from_input" ? RELU_FROM_INPUT : (algo == "from_output" ? RELU_FROM_OUTPUT : RELU_FROM_MASK);
+        float *d0 = ad.ins[0] > 0 ? (float *)c.ptr(L2.a[2]) : nullptr;
+        float *d1 = ad.ins.size() > 1 && ad.ins[1] > 0 ? (float *)c.ptr(L2.a[3]) : nullptr;
+        relu_bwd_fanout(c.st, dz, t, mode, d0, (L2.flags & 1) != 0, d1, (L2.flags & 2) != 0, n, six);
+    }
+}
+
+}  // namespace
+
+extern "C" int monet_plan_set_fusion(monet_plan *p, int on) {
+    if (!p) return MONET_BAD_ARGUMENT;
+    p->fusion = on != 0;
+    return MONET_OK;
+}
+
 extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const *inputs, const float *const *weights,
                               float *const *grads, float *dev_loss) {
     if (!p || !inputs || !weights || !grads) { g_err = "monet_step: null argument"; return MONET_BAD_ARGUMENT; }
@@ -283,14 +433,20 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
         // arena accounting: replay the trace's alloc/free records against the launches
         int64_t live = 0;
         size_t next_event = 0, next_poison = 0;
-        if (p->timing && p->ev.size() != 2 * pl.launches.size()) {
+        if (p->timing && p->ev.size() != 2 * pl.launches.size()) {     // enough for either program
             p->ev.resize(2 * pl.launches.size());
             for (auto &e : p->ev) hip_check(hipEventCreate(&e), "event create");
         }
-        for (size_t li = 0; li < pl.launches.size(); ++li) {
-            const Launch &L = pl.launches[li];
-            if (p->stop_after >= 0 && (int64_t)L.event > p->stop_after) break;
-            for (; next_event <= L.event; ++next_event) {
+        // Debug modes (poison fill, early stop) run the operators one by one; otherwise adjacent
+        // bandwidth-bound operators go out as one fused kernel (same arithmetic, same trace).
+        const bool fuse = p->fusion && !p->poison && p->stop_after < 0;
+        const std::vector<ProgStep> &prog = fuse ? p->prog_fused : p->prog_plain;
+        for (size_t si = 0; si < prog.size(); ++si) {
+            const ProgStep &ps = prog[si];
+            const size_t li_last = ps.fuse ? ps.b : ps.a;
+            const Launch &Llast = pl.launches[li_last];
+            if (p->stop_after >= 0 && (int64_t)Llast.event > p->stop_after) break;
+            for (; next_event <= Llast.event; ++next_event) {
                 const monet_event &e = pl.events[next_event];
                 if (e.kind == EV_ALLOC) live += e.bytes;
                 else if (e.kind == EV_FREE) live -= e.bytes;
@@ -298,13 +454,16 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
                 peak = std::max(peak, live);
             }
             if (p->poison)
-                for (; next_poison < pl.poison.size() && pl.poison[next_poison].before_launch <= li; ++next_poison)
+                for (; next_poison < pl.poison.size() && pl.poison[next_poison].before_launch <= ps.a; ++next_poison)
                     fill_u32(c.st, (uint32_t *)(c.arena() + pl.poison[next_poison].off), pl.poison[next_poison].bytes / 4, 0x7fc00000u);
-            if (p->timing) hip_check(hipEventRecord(p->ev[2 * li], c.st), "event record");
-            if (L.kind == EV_RUN_BWD) run_backward(c, L);
+            if (p->timing) hip_check(hipEventRecord(p->ev[2 * si], c.st), "event record");
+            const Launch &L = pl.launches[ps.a];
+            if (ps.fuse) run_fused(c, ps);
+            else if (L.kind == EV_RUN_BWD) run_backward(c, L);
             else run_forward(c, L);
-            if (p->timing) hip_check(hipEventRecord(p->ev[2 * li + 1], c.st), "event record");
+            if (p->timing) hip_check(hipEventRecord(p->ev[2 * si + 1], c.st), "event record");
         }
+        p->timed_fused = fuse;
         p->timed_step_done = p->timing;
         if (p->stop_after < 0) {
             for (; next_event < pl.events.size(); ++next_event) {
@@ -322,13 +481,46 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
 }
 
 // ------------------------------------------------------------------ measurement aids
-extern "C" int monet_plan_num_launches(const monet_plan *p) { return p ? (int)p->plan.launches.size() : MONET_BAD_ARGUMENT; }
+static const std::vector<ProgStep> &current_program(const monet_plan *p) {
+    return (p->fusion && !p->poison && p->stop_after < 0) ? p->prog_fused : p->prog_plain;
+}
+
+extern "C" int monet_plan_num_launches(const monet_plan *p) { return p ? (int)current_program(p).size() : MONET_BAD_ARGUMENT; }
 
 extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_launch_info *out) {
-    if (!p || !out || index >= p->plan.launches.size()) { g_err = "monet_plan_launch_info: bad argument"; return MONET_BAD_ARGUMENT; }
+    if (!p || !out || index >= current_program(p).size()) { g_err = "monet_plan_launch_info: bad argument"; return MONET_BAD_ARGUMENT; }
     const Graph &g = p->plan.g;
-    const Launch &L = p->plan.launches[index];
+    const ProgStep &ps = current_program(p)[index];
+    const Launch &L = p->plan.launches[ps.a];
     std::memset(out, 0, sizeof(*out));
+    if (ps.fuse) {
+        const Launch &L2 = p->plan.launches[ps.b];
+        out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
+        double e, bytes;
+        const char *label;
+        if (ps.fuse == FUSE_BN_RELU_FWD || ps.fuse == FUSE_ADD_RELU_FWD) {
+            e = 4.0 * (double)numel_of(g.nodes[L2.id].shape);
+            const bool pre = !(L2.flags & 1), mk = L2.flags & 2;
+            bytes = (ps.fuse == FUSE_ADD_RELU_FWD ? 2 : 1) * e + (pre ? e : 0) + e + (mk ? e / 32 : 0);
+            if (ps.fuse == FUSE_BN_RELU_FWD && L.kind == EV_RUN_FWD) bytes += e;        // statistics pass
+            label = ps.fuse == FUSE_ADD_RELU_FWD ? "add_relu_fwd" : (L.kind == EV_RUN_FWD ? "bn_relu_fwd" : "bn_relu_apply");
+        } else {
+            const Bop &b1 = g.bops[L.id];
+            e = 4.0 * (double)numel_of(g.nodes[b1.node].shape);
+            const double t = b1.impls[L.impl].algo == "from_mask" ? e / 32 : e;
+            if (ps.fuse == FUSE_RELU_BN_BWD) { bytes = 2 * (e + t + e) + e + ((L2.flags & 1) ? e : 0); label = "relu_bn_bwd"; }
+            else {
+                const Node &ad = g.nodes[g.bops[L2.id].node];
+                bytes = e + t;
+                for (size_t q = 0; q < ad.ins.size() && q < 2; ++q)
+                    if (ad.ins[q] > 0) bytes += e + (((L2.flags >> q) & 1) ? e : 0);
+                label = "relu_add_bwd";
+            }
+        }
+        out->bytes = bytes;
+        std::strncpy(out->label, label, sizeof(out->label) - 1);
+        return MONET_OK;
+    }
     out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
     std::string label;
     double flops = 0, bytes = 0;
@@ -386,7 +578,7 @@ extern "C" int monet_plan_set_timing(monet_plan *p, int on) {
 
 extern "C" int monet_plan_read_timing(monet_plan *p, float *ms, size_t n) {
     if (!p || !ms) { g_err = "monet_plan_read_timing: null argument"; return MONET_BAD_ARGUMENT; }
-    if (!p->timed_step_done || n != p->plan.launches.size() || p->ev.size() != 2 * n) {
+    if (!p->timed_step_done || n != (p->timed_fused ? p->prog_fused : p->prog_plain).size() || p->ev.size() < 2 * n || n == 0) {
         g_err = "monet_plan_read_timing: no timed step to read";
         return MONET_BAD_ARGUMENT;
     }

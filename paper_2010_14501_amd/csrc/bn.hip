@@ -202,8 +202,8 @@ void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, cons
 //      = (y - beta)/gamma             (from the output; gamma must be non-zero)
 // dbeta = sum dy, dgamma = sum dy*xhat, dx = gamma*invstd*(dy - dbeta/m - xhat*dgamma/m)
 template <bool FROM_OUT>
-__global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ dy, const float *__restrict__ t,
-                                                      const float *__restrict__ gamma, const float *__restrict__ beta,
+__global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ dy, const uint64_t *__restrict__ mask,
+                                                      const float *__restrict__ t, const float *__restrict__ gamma, const float *__restrict__ beta,
                                                       const float *__restrict__ stats, float *__restrict__ part, int64_t rows,
                                                       int C, int TPR, int64_t slab) {
     __shared__ float sh_b[256 * 4];
@@ -223,9 +223,15 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
             else { sc[j] = stats[C + c]; sh[j] = -stats[c] * sc[j]; }
         }
         for (int64_t r = r0 + tr; r < r1; r += RPP) {
-            float4 g = ((const float4 *)dy)[r * C4 + cg];
-            float4 v = ((const float4 *)t)[r * C4 + cg];
+            const int64_t i4 = r * C4 + cg;
+            float4 g = ((const float4 *)dy)[i4];
+            float4 v = ((const float4 *)t)[i4];
             float gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w};
+            if (mask) {     // the incoming gradient still has to pass a ReLU: keep it where the sign bit is set
+                unsigned bits = (unsigned)(mask[i4 >> 4] >> ((i4 & 15) * 4)) & 15u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gg[j] = (bits >> j) & 1 ? gg[j] : 0.0f;
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 sb[j] += gg[j];
@@ -292,7 +298,8 @@ __global__ __launch_bounds__(256) void bn_bwd_final(const float *__restrict__ pa
 }
 
 template <bool FROM_OUT, bool ACC>
-__global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy, const float *__restrict__ t,
+__global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy, const uint64_t *__restrict__ mask,
+                                                    const float *__restrict__ t,
                                                     const float *__restrict__ gamma, const float *__restrict__ beta,
                                                     const float *__restrict__ stats, const float *__restrict__ coef, float *dx,
                                                     int64_t total4, int C) {
@@ -318,6 +325,11 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
         float4 g = ((const float4 *)dy)[i];
         float4 v = ((const float4 *)t)[i];
         float gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w}, r[4];
+        if (mask) {
+            unsigned bits = (unsigned)(mask[i >> 4] >> ((i & 15) * 4)) & 15u;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) gg[j] = (bits >> j) & 1 ? gg[j] : 0.0f;
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float xh = vv[j] * sc[j] + sh[j];
@@ -330,19 +342,19 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
 
 void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, const float *gamma, const float *beta,
             const float *stats, float *dx, float *dgamma, float *dbeta, int64_t rows, int C, bool accumulate, float *scratch,
-            size_t scratch_bytes) {
+            size_t scratch_bytes, const uint64_t *mask) {
     if (rows <= 0) throw KernelError("BatchNorm: no rows");
     int64_t floats = (int64_t)(scratch_bytes / 4) - 2 * C;    // tail of the scratch holds the two coefficient vectors
     BnGeom g = bn_geom(rows, C, floats, 2);
     float *coef = scratch + (int64_t)g.G * C * 2;
-    if (from_output) hipLaunchKernelGGL((bn_bwd_partial<true>), dim3(g.G, g.CB), dim3(256), 0, st, dy, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
-    else hipLaunchKernelGGL((bn_bwd_partial<false>), dim3(g.G, g.CB), dim3(256), 0, st, dy, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
+    if (from_output) hipLaunchKernelGGL((bn_bwd_partial<true>), dim3(g.G, g.CB), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
+    else hipLaunchKernelGGL((bn_bwd_partial<false>), dim3(g.G, g.CB), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
     hipLaunchKernelGGL(bn_bwd_final, dim3((C + 15) / 16), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
     int64_t total4 = rows * (C / 4);
     int64_t want = (total4 + 256 * 4 - 1) / (256 * 4);
     int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, 8192));
     if (grid > 2) grid &= ~1;
-#define BA(F, A) hipLaunchKernelGGL((bn_bwd_apply<F, A>), dim3(grid), dim3(256), 0, st, dy, t, gamma, beta, stats, (const float *)coef, dx, total4, C)
+#define BA(F, A) hipLaunchKernelGGL((bn_bwd_apply<F, A>), dim3(grid), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, (const float *)coef, dx, total4, C)
     if (from_output) { if (accumulate) BA(true, true); else BA(true, false); }
     else             { if (accumulate) BA(false, true); else BA(false, false); }
 #undef BA

@@ -70,6 +70,8 @@ def load_library():
     lib.monet_plan_num_launches.restype = i32
     lib.monet_plan_launch_info.argtypes = [vp, sz, C.POINTER(LaunchInfo)]
     lib.monet_plan_launch_info.restype = i32
+    lib.monet_plan_set_fusion.argtypes = [vp, i32]
+    lib.monet_plan_set_fusion.restype = i32
     lib.monet_plan_set_timing.argtypes = [vp, i32]
     lib.monet_plan_set_timing.restype = i32
     lib.monet_plan_read_timing.argtypes = [vp, C.POINTER(C.c_float), sz]
@@ -175,6 +177,9 @@ class Plan:
             _check(self._lib.monet_plan_launch_info(self._h, i, C.byref(li)))
             out.append((li.label.decode(), li.kind, li.id, li.impl, li.flops, li.bytes))
         return out
+
+    def set_fusion(self, on):
+        _check(self._lib.monet_plan_set_fusion(self._h, 1 if on else 0))
 
     def set_timing(self, on):
         _check(self._lib.monet_plan_set_timing(self._h, 1 if on else 0))

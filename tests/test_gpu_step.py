@@ -226,3 +226,26 @@ def test_resnet50_reduced_batch_against_oracle(batch):
     worst = compare_grads(run.grads_numpy(), ref)
     print(f"batch {batch}: worst gradient error {worst:.2e}")
     assert worst_act < 3 * ACT_TOL      # see the design doc: rounding is amplified ~1.1x per layer at random init
+
+
+def test_fused_neighbours_give_identical_bits():
+    """The executor launches BN-apply/add + ReLU and ReLU-backward + BN-backward/add-backward as one
+    kernel each; results must not differ from the one-kernel-per-operator path by a single bit."""
+    for g, sched in ((graphs.tiny_chain(), lambda g: schedules.tiny_chain_schedule(g, {0, 2})),
+                     (small_resnet(), schedules.block_output_schedule),
+                     (small_resnet(), schedules.store_everything_schedule)):
+        exts, params = tensors.make_inputs(g, seed=4, gamma_beta="random")
+        sch = sched(g)
+        run = StepRunner(g.text(), sch.text(), exts, params)
+        n_fused = len(run.plan.launches())
+        run.step()
+        fused, loss_f = run.grads_numpy(), run.loss_value()
+        run.plan.set_fusion(False)
+        n_plain = len(run.plan.launches())
+        assert n_fused < n_plain
+        run.step()
+        plain, loss_p = run.grads_numpy(), run.loss_value()
+        assert loss_f == loss_p
+        assert all(np.array_equal(fused[p], plain[p]) for p in fused)
+        labels = {l[0] for l in StepRunner(g.text(), sch.text(), exts, params).plan.launches()}
+        assert labels & {"bn_relu_fwd", "bn_relu_apply", "relu_bn_bwd", "add_relu_fwd", "relu_add_bwd"}
