@@ -28,9 +28,11 @@
 // position: within a class only the filter taps r = r0 + st*i, s = s0 + st*j contribute, so no
 // multiply-by-zero work is issued (a 3x3 stride-2 layer does 9 taps in total, not 36).
 //
-// Workgroup ids are remapped so that consecutive tiles (same activation rows, neighbouring
+// Workgroup ids are remapped so that consecutive work items (same activation rows, neighbouring
 // filter columns) run on the same XCD and share its L2: hardware deals workgroups to the 8 XCDs
-// round-robin, so logical tile = (id mod 8) * (grid/8) + id / 8.
+// round-robin, so logical item = (id mod 8) * (grid/8) + id / 8.  A work item is (tile, reduction
+// split) with the tile index fastest, so a launch with few tiles and many splits (weight
+// gradients) still spreads over all XCDs and the tiles of one split share their operand rows.
 #include "kernels.hpp"
 
 namespace monet {
@@ -81,10 +83,13 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 ? 3 : 2)) void conv_til
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, g = lane >> 5;
 
-    // XCD-aware tile order
+    // XCD-aware order of the (tile, split) work items
+    const int nsplit = ta.splits;
     const int64_t per_xcd = gridDim.x / NUM_XCD;
-    const int64_t logical = (int64_t)(blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
-    if (logical >= ta.total_tiles) return;
+    const int64_t item = (int64_t)(blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+    if (item >= ta.total_tiles * nsplit) return;
+    const int split = (int)(item / ta.total_tiles);
+    const int64_t logical = item - (int64_t)split * ta.total_tiles;
     const int tile_n = (int)(logical % ta.tiles_n);
     const int64_t tile_m = logical / ta.tiles_n;
     const int64_t row0 = tile_m * BM;
@@ -94,12 +99,10 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 ? 3 : 2)) void conv_til
     // ---------------- DGRAD: residue class of this launch slice
     int64_t Mg = ta.Mg, Kg = ta.Kg;
     int ph = 0, pw = 0, r0 = 0, s0 = 0, ns = cs.S, bh = cs.pad, bw = cs.pad, Hc = cs.H, Wc = cs.W;
-    // blockIdx.z = reduction split (all modes), times the residue class for DGRAD
-    const int nsplit = ta.splits;
-    const int split = blockIdx.z % nsplit;
+    // blockIdx.z = residue class (DGRAD only)
     if (MODE == DGRAD) {
         const int st = cs.stride;
-        const int cls = blockIdx.z / nsplit;
+        const int cls = blockIdx.z;
         ph = cls / st;
         pw = cls % st;
         Hc = (cs.H - ph + st - 1) / st;
@@ -608,7 +611,7 @@ void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim) {
     int64_t tiles_m = (ta.Mg + BM - 1) / BM;
     ta.tiles_n = (ta.Ng + BN - 1) / BN;
     ta.total_tiles = tiles_m * ta.tiles_n;
-    int64_t blocks = (ta.total_tiles + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    int64_t blocks = (ta.total_tiles * ta.splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
     if (blocks > 0x7fffffffll) throw KernelError("conv: too many tiles");
     dim3 grid((unsigned)blocks, 1, (unsigned)zdim);
     if (fast) hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true>), grid, dim3(NT), 0, st, ta);
@@ -620,15 +623,13 @@ void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim) {
 //   0: 128x128   1: 256x64   2: 64x256   3: 128x64   4: 64x128   5: 64x64
 int g_cfg_override = -1;   // tuning aid: force one tile shape for every launch
 
-// Choice measured on the ResNet-50 b184 layer set: the square tile unless the GEMM is narrower
-// than it; weight-gradient GEMMs (tiny output, very long reduction) prefer the smallest tile
-// that still covers the narrow side, because more workgroups hide more load latency.
+// Choice measured on the ResNet-50 b184 layer set: the square four-wave tile unless the GEMM is
+// narrower than it, then the four-wave (or smaller) tile that covers the narrow side exactly.
 int pick_cfg(int mode, int64_t Mg, int64_t Ng) {
     if (g_cfg_override >= 0) return g_cfg_override;
     if (mode == WGRAD) {
-        int64_t lo = Mg < Ng ? Mg : Ng, hi = Mg < Ng ? Ng : Mg;
-        if (lo <= 64) return (Mg <= 64 && Ng > 256) ? 4 : 5;
-        if (lo <= 128) return hi <= 256 ? 5 : 3;
+        if (Mg <= 64) return Ng % 256 == 0 ? 2 : 5;
+        if (Ng <= 64) return Mg >= 256 ? 1 : 3;
         return 0;
     }
     return Ng <= 64 ? 1 : 0;
@@ -668,7 +669,7 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
     ta.out = split_target(y, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_fwd");
     ta.splits = splits;
     bool fast = cs.C % BK == 0;
-    launch_cfg<FWD>(st, ta, fast, splits, pick_cfg(FWD, ta.Mg, ta.Ng));
+    launch_cfg<FWD>(st, ta, fast, 1, pick_cfg(FWD, ta.Mg, ta.Ng));
     if (splits > 1) launch_split_reduce(st, ws, y, ta.out_elems, splits, false);
 }
 
@@ -688,7 +689,7 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
     ta.splits = splits;
     ta.accumulate = accumulate ? 1 : 0;
     bool fast = cs.K % BK == 0 && cs.C % 4 == 0;
-    int zdim = stc * stc * splits;
+    int zdim = stc * stc;
     launch_cfg<DGRAD>(st, ta, fast, zdim, pick_cfg(DGRAD, ta.Mg, ta.Ng));
     if (splits > 1) launch_split_reduce(st, ws, dx, ta.out_elems, splits, accumulate);
 }
@@ -702,7 +703,7 @@ void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, cons
     ta.out = split_target(dw, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_wgrad");
     ta.splits = splits;
     bool fast = cs.K % 4 == 0 && cs.C % 4 == 0;
-    launch_cfg<WGRAD>(st, ta, fast, splits, pick_cfg(WGRAD, ta.Mg, ta.Ng));
+    launch_cfg<WGRAD>(st, ta, fast, 1, pick_cfg(WGRAD, ta.Mg, ta.Ng));
     if (splits > 1) launch_split_reduce(st, ws, dw, ta.out_elems, splits, false);
 }
 

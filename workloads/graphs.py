@@ -325,9 +325,15 @@ def resnet50(batch=184, hw=224, classes=1000, widths=(64, 128, 256, 512), depths
         P = (H + 2 * pad - R) // stride + 1
         M = N * P * P
         # enough waves to keep loads in flight on 256 CUs (about 16 per CU), at least 8 reduction
-        # steps of 16 rows per split, and at most 128 MiB of partial sums
-        lo = min(K, C * R * R)
-        tile_rows, tile_cols, waves = (64, 64, 1) if lo <= 128 else (128, 128, 4)
+        # steps of 16 rows per split, and at most 128 MiB of partial sums.  The tile shape follows
+        # the kernel library's choice for a K x (C*R*R) weight-gradient GEMM.
+        cols = C * R * R
+        if K <= 64:
+            tile_rows, tile_cols, waves = (64, 256, 4) if cols % 256 == 0 else (64, 64, 1)
+        elif cols <= 64:
+            tile_rows, tile_cols, waves = (256, 64, 4) if K >= 256 else (128, 64, 2)
+        else:
+            tile_rows, tile_cols, waves = (128, 128, 4)
         tiles = math.ceil(K / tile_rows) * math.ceil(C * R * R / tile_cols)
         sp = math.ceil(4096 / (tiles * waves))
         sp = max(1, min(sp, M // 128, (128 << 20) // (4 * K * C * R * R)))
