@@ -51,13 +51,20 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, dec
         if ties is not None and n.id in ties[1]:
             passes, undecided = nm.resolve_pass(x, passes, ties[1][n.id], ties[0], six)
             decisions[n.id] = (passes, undecided)
-            y = np.where(passes, np.minimum(x, 6.0) if six else x, 0.0)
+            # an element that does not pass sits on the nearer saturation value (0, or 6 for ReLU6)
+            y = np.where(passes, x, np.where(x < 3.0, 0.0, 6.0) if six else 0.0)
         else:
             y = nm.relu6_fwd(x) if six else nm.relu_fwd(x)
         aux["mask"] = lambda: nm.pack_mask(passes)
     elif n.op == "maxpool":
         y, idx = nm.maxpool_fwd(x, int(a["k"]), int(a["stride"]), int(a["pad"]))
         aux["poolidx"] = lambda: idx
+    elif n.op == "tconv":
+        y = nm.tconv2d_fwd(x, params[n.pars[0]], int(a["stride"]))
+    elif n.op == "dwconv":
+        y = nm.dwconv2d_fwd(x, params[n.pars[0]], int(a["stride"]), int(a["pad"]))
+    elif n.op == "concat":
+        y = nm.concat_fwd(x, get(n.ins[1]))
     elif n.op == "add":
         y = x + get(n.ins[1])
     elif n.op == "avgpool":
@@ -87,6 +94,18 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
     if kind == "conv_dgrad":
         xs = nchw_shape(g.shape_of(n.ins[0]))
         return {0: nm.conv2d_dgrad(gy, params[n.pars[0]], xs, int(a["stride"]), int(a["pad"]))}, {}
+    if kind == "tconv_wgrad":
+        return {}, {n.pars[0]: nm.tconv2d_wgrad(get(n.ins[0]), gy, int(a["R"]), int(a["S"]), int(a["stride"]))}
+    if kind == "tconv_dgrad":
+        return {0: nm.tconv2d_dgrad(gy, params[n.pars[0]], int(a["stride"]))}, {}
+    if kind == "dwconv_wgrad":
+        return {}, {n.pars[0]: nm.dwconv2d_wgrad(get(n.ins[0]), gy, int(a["R"]), int(a["S"]), int(a["stride"]), int(a["pad"]))}
+    if kind == "dwconv_dgrad":
+        xs = nchw_shape(g.shape_of(n.ins[0]))
+        return {0: nm.dwconv2d_dgrad(gy, params[n.pars[0]], xs, int(a["stride"]), int(a["pad"]))}, {}
+    if kind == "concat_bwd":
+        da, db = nm.concat_bwd(gy, nchw_shape(g.shape_of(n.ins[0]))[1])
+        return {0: da, 1: db}, {}
     if kind == "bn_bwd":
         gamma, beta = params[n.pars[0]], params[n.pars[1]]
         mean, invstd = stats[n.id]
@@ -128,7 +147,7 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
         dw, db = nm.linear_wgrad(get(n.ins[0]), gy)
         return {}, {n.pars[0]: dw, n.pars[1]: db}
     if kind == "linear_dgrad":
-        return {0: nm.linear_dgrad(gy, params[n.pars[0]])}, {}
+        return {0: nm.linear_dgrad(gy, params[n.pars[0]], nchw_shape(g.shape_of(n.ins[0])))}, {}
     if kind == "softmaxce_bwd":
         return {0: nm.softmaxce_bwd(get(n.ins[0]), get(n.ins[1]))}, {}
     if kind == "sumloss_bwd":

@@ -70,6 +70,95 @@ def conv2d_dgrad(dy, w, x_shape, stride, pad):
     return dxp[:, :, pad:pad + H, pad:pad + W].copy()
 
 
+# ---------------------------------------------------------------- transposed convolution
+def tconv2d_fwd(x, w, stride):
+    """y[n,k,h*stride+r,v*stride+s] += x[n,c,h,v] * w[c,k,r,s]  (no padding; w is C,K,R,S)."""
+    N, C, H, W = x.shape
+    C2, K, R, S = w.shape
+    assert C == C2
+    y = np.zeros((N, K, (H - 1) * stride + R, (W - 1) * stride + S), F64)
+    for r in range(R):
+        for s in range(S):
+            y[:, :, r:r + stride * (H - 1) + 1:stride, s:s + stride * (W - 1) + 1:stride] += np.einsum(
+                "nchv,ck->nkhv", x, w[:, :, r, s], optimize=True)
+    return y
+
+
+def tconv2d_dgrad(dy, w, stride):
+    """dx[n,c,h,v] = sum_{k,r,s} dy[n,k,h*stride+r,v*stride+s] * w[c,k,r,s]."""
+    C, K, R, S = w.shape
+    N, _, HO, WO = dy.shape
+    H, W = (HO - R) // stride + 1, (WO - S) // stride + 1
+    dx = np.zeros((N, C, H, W), F64)
+    for r in range(R):
+        for s in range(S):
+            win = dy[:, :, r:r + stride * (H - 1) + 1:stride, s:s + stride * (W - 1) + 1:stride]
+            dx += np.einsum("nkhv,ck->nchv", win, w[:, :, r, s], optimize=True)
+    return dx
+
+
+def tconv2d_wgrad(x, dy, R, S, stride):
+    """dw[c,k,r,s] = sum_{n,h,v} x[n,c,h,v] * dy[n,k,h*stride+r,v*stride+s]."""
+    N, C, H, W = x.shape
+    K = dy.shape[1]
+    dw = np.zeros((C, K, R, S), F64)
+    for r in range(R):
+        for s in range(S):
+            win = dy[:, :, r:r + stride * (H - 1) + 1:stride, s:s + stride * (W - 1) + 1:stride]
+            dw[:, :, r, s] = np.einsum("nchv,nkhv->ck", x, win, optimize=True)
+    return dw
+
+
+# ---------------------------------------------------------------- depthwise convolution
+def dwconv2d_fwd(x, w, stride, pad):
+    """y[n,c,p,q] = sum_{r,s} xpad[n,c,p*stride+r,q*stride+s] * w[c,0,r,s]  (one filter per channel)."""
+    N, C, H, W = x.shape
+    C2, one, R, S = w.shape
+    assert C == C2 and one == 1
+    P, Q = conv_out_hw(H, W, R, S, stride, pad)
+    xp = _pad(x, pad)
+    y = np.zeros((N, C, P, Q), F64)
+    for r in range(R):
+        for s in range(S):
+            win = xp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
+            y += win * w[None, :, 0, r, s, None, None]
+    return y
+
+
+def dwconv2d_wgrad(x, dy, R, S, stride, pad):
+    """dw[c,0,r,s] = sum_{n,p,q} dy[n,c,p,q] * xpad[n,c,p*stride+r,q*stride+s]."""
+    N, C, H, W = x.shape
+    _, _, P, Q = dy.shape
+    xp = _pad(x, pad)
+    dw = np.zeros((C, 1, R, S), F64)
+    for r in range(R):
+        for s in range(S):
+            win = xp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
+            dw[:, 0, r, s] = (dy * win).sum(axis=(0, 2, 3))
+    return dw
+
+
+def dwconv2d_dgrad(dy, w, x_shape, stride, pad):
+    """Transpose of dwconv2d_fwd in x."""
+    N, C, H, W = x_shape
+    _, _, R, S = w.shape
+    _, _, P, Q = dy.shape
+    dxp = np.zeros((N, C, H + 2 * pad, W + 2 * pad), F64)
+    for r in range(R):
+        for s in range(S):
+            dxp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride] += dy * w[None, :, 0, r, s, None, None]
+    return dxp[:, :, pad:pad + H, pad:pad + W].copy()
+
+
+# ---------------------------------------------------------------- channel concatenation
+def concat_fwd(a, b):
+    return np.concatenate([a, b], axis=1)
+
+
+def concat_bwd(dy, channels_a):
+    return dy[:, :channels_a].copy(), dy[:, channels_a:].copy()
+
+
 # ---------------------------------------------------------------- batch norm
 def bn_stats(x, eps):
     mean = x.mean(axis=(0, 2, 3))
@@ -143,7 +232,8 @@ def resolve_pass(x, passes, given, band, six=False):
 
 def pack_mask(pass_nchw):
     """1-bit code: bit (e & 63) of little-endian 64-bit word (e >> 6), e = N,H,W,C linear index."""
-    bits = np.ascontiguousarray(np.transpose(pass_nchw, (0, 2, 3, 1))).ravel().astype(np.uint8)
+    stored = np.transpose(pass_nchw, (0, 2, 3, 1)) if pass_nchw.ndim == 4 else pass_nchw
+    bits = np.ascontiguousarray(stored).ravel().astype(np.uint8)
     words = (bits.size + 63) // 64
     padded = np.zeros(words * 64, np.uint8)
     padded[:bits.size] = bits
@@ -151,8 +241,11 @@ def pack_mask(pass_nchw):
 
 
 def unpack_mask(words, nchw_shape):
+    count = int(np.prod(nchw_shape))
+    bits = np.unpackbits(np.ascontiguousarray(words).view(np.uint8), bitorder="little")[:count]
+    if len(nchw_shape) != 4:
+        return bits.reshape(nchw_shape).astype(bool)
     N, C, H, W = nchw_shape
-    bits = np.unpackbits(np.ascontiguousarray(words).view(np.uint8), bitorder="little")[:N * C * H * W]
     return np.transpose(bits.reshape(N, H, W, C), (0, 3, 1, 2)).astype(bool)
 
 
@@ -222,19 +315,33 @@ def avgpool_bwd(dy, x_shape):
 
 # ---------------------------------------------------------------- linear, losses
 def linear_fwd(x, w, b):
-    return x @ w.T + b[None, :]
+    """y = flatten(x) w^T + b; a 4-D x (N,C,H,W) is flattened per image, w is then out,C,H,W."""
+    n = x.shape[0]
+    return x.reshape(n, -1) @ w.reshape(w.shape[0], -1).T + b[None, :]
 
 
 def linear_wgrad(x, dy):
-    return dy.T @ x, dy.sum(axis=0)
+    n = x.shape[0]
+    return (dy.T @ x.reshape(n, -1)).reshape((dy.shape[1],) + x.shape[1:]), dy.sum(axis=0)
 
 
-def linear_dgrad(dy, w):
-    return dy @ w
+def linear_dgrad(dy, w, x_shape=None):
+    dx = dy @ w.reshape(w.shape[0], -1)
+    return dx if x_shape is None else dx.reshape(x_shape)
+
+
+def _rows(logits, labels):
+    """Class scores as rows: a 4-D score map N,K,H,W (one label per pixel) becomes N*H*W rows of K."""
+    if logits.ndim == 4:
+        k = logits.shape[1]
+        return np.transpose(logits, (0, 2, 3, 1)).reshape(-1, k), np.asarray(labels).reshape(-1)
+    return logits, np.asarray(labels)
+
 
 
 def softmaxce_fwd(logits, labels):
-    """Mean over the batch of -log softmax(logits)[label]."""
+    """Mean over the batch (for a score map: over batch and pixels) of -log softmax(logits)[label]."""
+    logits, labels = _rows(logits, labels)
     z = logits - logits.max(axis=1, keepdims=True)
     lse = np.log(np.exp(z).sum(axis=1))
     n = logits.shape[0]
@@ -242,12 +349,18 @@ def softmaxce_fwd(logits, labels):
 
 
 def softmaxce_bwd(logits, labels):
+    shape = logits.shape
+    logits, labels = _rows(logits, labels)
     z = logits - logits.max(axis=1, keepdims=True)
     p = np.exp(z)
     p /= p.sum(axis=1, keepdims=True)
     n = logits.shape[0]
     p[np.arange(n), labels] -= 1.0
-    return p / n
+    p /= n
+    if len(shape) == 4:
+        N, K, H, W = shape
+        return np.transpose(p.reshape(N, H, W, K), (0, 3, 1, 2)).copy()
+    return p
 
 
 def sumloss_fwd(x):

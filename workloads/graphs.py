@@ -100,11 +100,13 @@ class Graph:
         return 4 * numel(self.shape_of(ref))
 
     # ---- operators ----------------------------------------------------
-    def conv(self, x, K, R, S=None, stride=1, pad=0, name="conv", wgrad_splits=(8,)):
+    def conv(self, x, K, R, S=None, stride=1, pad=0, name="conv", wgrad_splits=None):
         S = R if S is None else S
         N, H, W, C = self.shape_of(x)
         P = (H + 2 * pad - R) // stride + 1
         Q = (W + 2 * pad - S) // stride + 1
+        if wgrad_splits is None:
+            wgrad_splits = (wgrad_split_count(N * P * Q, K, C * R * S),)
         w = self.param(name + ".w", (K, R, S, C))
         i = self._add("conv", [x], [w], (N, P, Q, K), R=R, S=S, stride=stride, pad=pad)
         flop = 2.0 * N * P * Q * K * C * R * S
@@ -187,9 +189,53 @@ class Graph:
         self._pending_bops(i, [("avgpool_bwd", [dict(algo="direct", deps=[], ws=0, cost=by * c)])])
         return i
 
+    def concat(self, a, b):
+        """Channel concatenation (last storage axis)."""
+        sa, sb = self.shape_of(a), self.shape_of(b)
+        assert sa[:-1] == sb[:-1]
+        i = self._add("concat", [a, b], [], sa[:-1] + (sa[-1] + sb[-1],))
+        by = self._bytes(i)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="copy", ws=0, cost=2 * by * c)]
+        self._pending_bops(i, [("concat_bwd", [dict(algo="copy", deps=[], ws=0, cost=2 * by * c)])])
+        return i
+
+    def tconv(self, x, K, R=2, stride=2, name="tconv"):
+        """Transposed convolution without padding; weights C_in,R,S,C_out (the K,R,S,C filter of the
+        convolution it is the adjoint of)."""
+        N, H, W, C = self.shape_of(x)
+        P, Q = (H - 1) * stride + R, (W - 1) * stride + R
+        w = self.param(name + ".w", (C, R, R, K))
+        i = self._add("tconv", [x], [w], (N, P, Q, K), R=R, S=R, stride=stride)
+        flop = 2.0 * N * H * W * K * C * R * R
+        self.fimpls[i] = [dict(algo="igemm", ws=0, cost=flop)]
+        wbytes = 4 * K * R * R * C
+        sp = wgrad_split_count(N * H * W, C, K * R * R)
+        wg = [dict(algo="direct", ws=0, cost=flop * 4.0),
+              dict(algo="splitk", ws=_align(sp * wbytes), cost=flop * (1.0 + 0.02 * sp), splits=sp)]
+        self._pending_bops(i, [("tconv_dgrad", [dict(algo="igemm", deps=[], ws=0, cost=flop)])] if x > 0 else [],
+                           [("tconv_wgrad", [dict(d, deps=[x] if x > 0 else []) for d in wg])])
+        return i
+
+    def dwconv(self, x, R=3, stride=1, pad=1, name="dw"):
+        """Depthwise convolution: one R x R filter per channel; weights C,R,S,1."""
+        N, H, W, C = self.shape_of(x)
+        P = (H + 2 * pad - R) // stride + 1
+        Q = (W + 2 * pad - R) // stride + 1
+        w = self.param(name + ".w", (C, R, R, 1))
+        i = self._add("dwconv", [x], [w], (N, P, Q, C), R=R, S=R, stride=stride, pad=pad)
+        bi, bo = self._bytes(x), self._bytes(i)
+        c = RIDGE_FLOP_PER_BYTE
+        self.fimpls[i] = [dict(algo="direct", ws=0, cost=(bi + bo) * c)]
+        self._pending_bops(i, [("dwconv_dgrad", [dict(algo="direct", deps=[], ws=0, cost=(bi + bo) * c)])] if x > 0 else [],
+                           [("dwconv_wgrad", [dict(algo="direct", deps=[x] if x > 0 else [], ws=0, cost=(bi + bo) * c)])])
+        return i
+
     def linear(self, x, out, name="fc"):
-        N, I = self.shape_of(x)
-        w = self.param(name + ".w", (out, I))
+        """Fully connected layer over the flattened input; a 4-D input N,H,W,C gets weights out,H,W,C."""
+        shp = self.shape_of(x)
+        N, I = shp[0], numel(shp[1:])
+        w = self.param(name + ".w", (out,) + tuple(shp[1:]))
         b = self.param(name + ".b", (out,))
         i = self._add("linear", [x], [w, b], (N, out))
         flop = 2.0 * N * I * out
@@ -289,6 +335,22 @@ def _fill_splits(rows, cols, reduction):
     return max(1, min(math.ceil(1200 / tiles), reduction // 128, 16))
 
 
+def wgrad_split_count(M, K, cols):
+    """Reduction splits of a K x cols weight-gradient GEMM that sums over M output positions:
+    enough waves to keep loads in flight on 256 CUs (about 16 per CU), at least 8 reduction steps
+    of 16 rows per split, and at most 128 MiB of partial sums.  The tile shape follows the kernel
+    library's choice for that GEMM."""
+    if K <= 64:
+        tile_rows, tile_cols, waves = (64, 256, 4) if cols % 256 == 0 else (64, 64, 1)
+    elif cols <= 64:
+        tile_rows, tile_cols, waves = (256, 64, 4) if K >= 256 else (128, 64, 2)
+    else:
+        tile_rows, tile_cols, waves = (128, 128, 4)
+    tiles = math.ceil(K / tile_rows) * math.ceil(cols / tile_cols)
+    sp = math.ceil(4096 / (tiles * waves))
+    return max(1, min(sp, M // 128, (128 << 20) // (4 * K * cols)))
+
+
 def _align(b, a=256):
     return (int(b) + a - 1) // a * a
 
@@ -318,29 +380,8 @@ def resnet50(batch=184, hw=224, classes=1000, widths=(64, 128, 256, 512), depths
     x = g.ext("x", "f32", (batch, hw, hw, 3))
     labels = g.ext("labels", "i32", (batch,))
 
-    def splits_for(ref_in, K, R, stride, pad):
-        if wgrad_splits is not None:
-            return wgrad_splits
-        N, H, W, C = g.shape_of(ref_in)
-        P = (H + 2 * pad - R) // stride + 1
-        M = N * P * P
-        # enough waves to keep loads in flight on 256 CUs (about 16 per CU), at least 8 reduction
-        # steps of 16 rows per split, and at most 128 MiB of partial sums.  The tile shape follows
-        # the kernel library's choice for a K x (C*R*R) weight-gradient GEMM.
-        cols = C * R * R
-        if K <= 64:
-            tile_rows, tile_cols, waves = (64, 256, 4) if cols % 256 == 0 else (64, 64, 1)
-        elif cols <= 64:
-            tile_rows, tile_cols, waves = (256, 64, 4) if K >= 256 else (128, 64, 2)
-        else:
-            tile_rows, tile_cols, waves = (128, 128, 4)
-        tiles = math.ceil(K / tile_rows) * math.ceil(C * R * R / tile_cols)
-        sp = math.ceil(4096 / (tiles * waves))
-        sp = max(1, min(sp, M // 128, (128 << 20) // (4 * K * C * R * R)))
-        return (sp,)
-
     def cbr(a, K, R, stride, pad, name, relu=True):
-        c = g.conv(a, K, R, stride=stride, pad=pad, name=name, wgrad_splits=splits_for(a, K, R, stride, pad))
+        c = g.conv(a, K, R, stride=stride, pad=pad, name=name, wgrad_splits=wgrad_splits)
         n = g.bn(c, name=name.replace("conv", "bn"))
         return g.relu(n) if relu else n
 
@@ -363,6 +404,129 @@ def resnet50(batch=184, hw=224, classes=1000, widths=(64, 128, 256, 512), depths
             s = g.add(h, sk)
             a = g.relu(s)
             g.end_block()
+    g.begin_block("head")
+    p = g.avgpool(a)
+    f = g.linear(p, classes, name="fc")
+    g.softmaxce(f, labels)
+    g.end_block()
+    return g
+
+
+def _cbr(g, a, K, R, stride, pad, name, six=False):
+    c = g.conv(a, K, R, stride=stride, pad=pad, name=name + ".conv")
+    n = g.bn(c, name=name + ".bn")
+    return g.relu(n, six=six)
+
+
+def vgg16_bn(batch=176, hw=224, classes=1000, widths=(64, 128, 256, 512, 512), convs=(2, 2, 3, 3, 3), fc=4096):
+    """VGG-16 with BatchNorm: 13 conv3x3-BN-ReLU triples in five stages, each closed by a 2x2
+    max-pool, then three fully connected layers (no dropout).  One block per triple; the pool
+    joins the last triple of its stage."""
+    g = Graph()
+    x = g.ext("x", "f32", (batch, hw, hw, 3))
+    labels = g.ext("labels", "i32", (batch,))
+    a = x
+    for si, (wd, cnt) in enumerate(zip(widths, convs)):
+        for ci in range(cnt):
+            g.begin_block(f"s{si + 1}c{ci}")
+            a = _cbr(g, a, wd, 3, 1, 1, f"s{si + 1}c{ci}")
+            if ci == cnt - 1:
+                a = g.maxpool(a, 2, 2, 0)
+            g.end_block()
+    g.begin_block("fc1")
+    a = g.relu(g.linear(a, fc, name="fc1"))
+    g.end_block()
+    g.begin_block("fc2")
+    a = g.relu(g.linear(a, fc, name="fc2"))
+    g.end_block()
+    g.begin_block("head")
+    f = g.linear(a, classes, name="fc3")
+    g.softmaxce(f, labels)
+    g.end_block()
+    return g
+
+
+def unet(batch=11, h=416, w=608, classes=2, base=64, depth=4):
+    """Encoder-decoder with skip connections: `depth` levels of two conv3x3-BN-ReLU triples and a
+    2x2 max-pool, a bottleneck, then per level a 2x2 stride-2 transposed convolution, channel
+    concatenation with the skip tensor and two more triples; a 1x1 convolution gives per-pixel
+    class scores for a cross-entropy averaged over batch and pixels.  One block per level."""
+    assert h % (1 << depth) == 0 and w % (1 << depth) == 0
+    g = Graph()
+    x = g.ext("x", "f32", (batch, h, w, 3))
+    labels = g.ext("labels", "i32", (batch, h, w))
+    a = x
+    skips = []
+    for d in range(depth):
+        wd = base << d
+        g.begin_block(f"down{d}")
+        a = _cbr(g, a, wd, 3, 1, 1, f"down{d}a")
+        a = _cbr(g, a, wd, 3, 1, 1, f"down{d}b")
+        g.end_block()
+        skips.append(a)
+        g.begin_block(f"pool{d}")
+        a = g.maxpool(a, 2, 2, 0)
+        g.end_block()
+    g.begin_block("mid")
+    a = _cbr(g, a, base << depth, 3, 1, 1, "mida")
+    a = _cbr(g, a, base << depth, 3, 1, 1, "midb")
+    g.end_block()
+    for d in reversed(range(depth)):
+        wd = base << d
+        g.begin_block(f"up{d}")
+        u = g.tconv(a, wd, 2, 2, name=f"up{d}.tconv")
+        a = g.concat(skips[d], u)
+        a = _cbr(g, a, wd, 3, 1, 1, f"up{d}a")
+        a = _cbr(g, a, wd, 3, 1, 1, f"up{d}b")
+        g.end_block()
+    g.begin_block("head")
+    f = g.conv(a, classes, 1, stride=1, pad=0, name="out.conv")
+    g.softmaxce(f, labels)
+    g.end_block()
+    return g
+
+
+MOBILENET_V2_STAGES = ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1))
+
+
+def mobilenet_v2(batch=272, hw=224, classes=1000, stages=MOBILENET_V2_STAGES, stem=32, last=1280):
+    """Inverted-residual network: per block a 1x1 expansion (factor t), a depthwise 3x3 and a linear
+    1x1 projection, each followed by BatchNorm, ReLU6 after the first two; identity skip when the
+    block keeps shape.  `stages` rows are (t, channels, repeats, stride of the first repeat).
+    Blocks are the triples, so that a schedule can recompute the depthwise ones."""
+    g = Graph()
+    x = g.ext("x", "f32", (batch, hw, hw, 3))
+    labels = g.ext("labels", "i32", (batch,))
+    g.begin_block("stem")
+    a = _cbr(g, x, stem, 3, 2, 1, "stem", six=True)
+    g.end_block()
+    cin = stem
+    bi = 0
+    for t, cout, reps, stride0 in stages:
+        for r in range(reps):
+            stride = stride0 if r == 0 else 1
+            nm = f"b{bi}"
+            h = a
+            if t != 1:
+                g.begin_block(nm + ".expand")
+                h = _cbr(g, h, cin * t, 1, 1, 0, nm + ".expand", six=True)
+                g.end_block()
+            g.begin_block(nm + ".dw")
+            d = g.dwconv(h, 3, stride, 1, name=nm + ".dw")
+            h = g.relu(g.bn(d, name=nm + ".dw.bn"), six=True)
+            g.end_block()
+            g.begin_block(nm + ".project")
+            p = g.conv(h, cout, 1, stride=1, pad=0, name=nm + ".project.conv")
+            h = g.bn(p, name=nm + ".project.bn")
+            if stride == 1 and cin == cout:
+                h = g.add(h, a)
+            g.end_block()
+            a = h
+            cin = cout
+            bi += 1
+    g.begin_block("last")
+    a = _cbr(g, a, last, 1, 1, 0, "last", six=True)
+    g.end_block()
     g.begin_block("head")
     p = g.avgpool(a)
     f = g.linear(p, classes, name="fc")

@@ -227,8 +227,14 @@ def block_checkpoint_set(g: Graph, bimpl, checkpoint_blocks):
                 for d in deps_of(g, b["k"], bimpl[b["k"]]):
                     if d in own:
                         F.add(d)
-        main = [i for i in nodes if not g.is_aux(i)]
-        F.add(main[-1])
+        main = [i for i in nodes if not g.is_aux(i) and not g.nodes[i - 1].attrs.get("persist")]
+        if main:
+            F.add(main[-1])
+    # an intermediate tensor is written while its creator runs: keep it with a kept creator
+    for b in g.bops:
+        for d in deps_of(g, b["k"], bimpl[b["k"]]):
+            if g.is_aux(d) and g.nodes[d - 1].ins[0] in F:
+                F.add(d)
     return F
 
 
