@@ -64,6 +64,39 @@ int monet_maxpool_fwd(void *stream, const float *x, float *y, uint8_t *idx,
 int monet_maxpool_bwd(void *stream, const float *dy, const float *x, const uint8_t *idx, float *dx,
                       int N, int H, int W, int C, int k, int stride, int pad, int accumulate);
 
+/* Transposed convolution without padding (the up-sampling layer of encoder-decoder networks):
+ * y[N,(H-1)*stride+R,(W-1)*stride+S,K] = sum_c x[n,h,v,c] * w[c,r,s,k] scattered to (h*stride+r, v*stride+s).
+ * w is C,R,S,K.  Runs on the convolution kernels above with the roles of the operands exchanged. */
+int monet_tconv_fwd(void *stream, const float *x, const float *w, float *y,
+                    int N, int H, int W, int C, int K, int R, int S, int stride);
+int monet_tconv_dgrad(void *stream, const float *dy, const float *w, float *dx,
+                      int N, int H, int W, int C, int K, int R, int S, int stride, int accumulate);
+int monet_tconv_wgrad(void *stream, const float *x, const float *dy, float *dw,
+                      int N, int H, int W, int C, int K, int R, int S, int stride,
+                      int splits, float *ws, size_t ws_bytes);
+
+/* Depthwise convolution: one R x S filter per channel (R*S <= 9), w is C,R,S; zero padding.
+ * wgrad needs scratch of at least R*S*C floats (more lets more workgroups share the reduction). */
+int monet_dwconv_fwd(void *stream, const float *x, const float *w, float *y,
+                     int N, int H, int W, int C, int R, int S, int stride, int pad);
+int monet_dwconv_dgrad(void *stream, const float *dy, const float *w, float *dx,
+                       int N, int H, int W, int C, int R, int S, int stride, int pad, int accumulate);
+int monet_dwconv_wgrad(void *stream, const float *x, const float *dy, float *dw,
+                       int N, int H, int W, int C, int R, int S, int stride, int pad,
+                       float *scratch, size_t scratch_bytes);
+
+/* dst[row][0..cols) (+)= src[row][0..cols) for `rows` rows that are src_ld / dst_ld floats apart
+ * (channel concatenation and its backward; base pointers already offset to the first column). */
+int monet_column_copy(void *stream, const float *src, int64_t src_ld, float *dst, int64_t dst_ld,
+                      int cols, int64_t rows, int accumulate);
+
+/* Mean over rows of -log softmax(logits[row])[labels[row]] for rows of few classes (per-pixel scores),
+ * and its gradient; scratch >= 4 KiB. */
+int monet_softmaxce_rows_fwd(void *stream, const float *logits, const int32_t *labels, float *loss,
+                             int64_t rows, int classes, float *scratch, size_t scratch_bytes);
+int monet_softmaxce_rows_bwd(void *stream, const float *logits, const int32_t *labels, float *dlogits,
+                             int64_t rows, int classes, int accumulate);
+
 /* Tuning aid: force the workgroup tile of the three convolution kernels (0: 128x128, 1: 256x64,
  * 2: 64x256, 3: 128x64, 4: 64x128, 5: 64x64 as rows x columns of the implicit GEMM); -1 restores
  * the built-in choice.  Process-wide, not thread-safe. */

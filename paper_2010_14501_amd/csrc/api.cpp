@@ -165,10 +165,26 @@ ConvShape conv_shape(const Graph &g, const Node &n) {
     cs.P = (int)n.shape[1]; cs.Q = (int)n.shape[2];
     return cs;
 }
+// A transposed convolution x[N,H,W,C] -> y[N,P,Q,K] with filter C,R,S,K is the adjoint of the convolution
+// y-shaped -> x-shaped with that same array read as its K',R,S,C' filter (K' = C, C' = K): forward = that
+// convolution's input gradient, input gradient = its forward, filter gradient = its filter gradient with
+// input and output-gradient exchanged.  This returns the shape of that convolution.
+ConvShape tconv_adjoint_shape(const Graph &g, const Node &n) {
+    const auto &is = g.shape_of(n.ins[0]);
+    ConvShape cs;
+    cs.N = (int)is[0]; cs.H = (int)n.shape[1]; cs.W = (int)n.shape[2]; cs.C = (int)n.shape[3];
+    cs.K = (int)is[3]; cs.R = n.attr_int("R"); cs.S = n.attr_int("S");
+    cs.stride = n.attr_int("stride", 1); cs.pad = 0;
+    cs.P = (int)is[1]; cs.Q = (int)is[2];
+    if ((cs.H - cs.R) / cs.stride + 1 != cs.P || (cs.W - cs.S) / cs.stride + 1 != cs.Q || (cs.H - cs.R) % cs.stride || (cs.W - cs.S) % cs.stride)
+        throw KernelError("transposed convolution: output extent does not match (H-1)*stride+R");
+    return cs;
+}
+int64_t numel_of(const std::vector<int64_t> &s);
 ConvShape linear_shape(const Graph &g, const Node &n) {   // a linear layer is a 1x1 convolution on a 1x1 image
     const auto &is = g.shape_of(n.ins[0]);
     ConvShape cs;
-    cs.N = (int)is[0]; cs.H = 1; cs.W = 1; cs.C = (int)is[1];
+    cs.N = (int)is[0]; cs.H = 1; cs.W = 1; cs.C = (int)(numel_of(is) / is[0]);
     cs.K = (int)n.shape[1]; cs.R = 1; cs.S = 1; cs.stride = 1; cs.pad = 0; cs.P = 1; cs.Q = 1;
     return cs;
 }
@@ -204,6 +220,15 @@ void run_forward(const StepCtx &c, const Launch &L) {
         const FwdImpl &im = n.fimpls[L.impl];
         conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
                  (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+    } else if (op == "tconv") {
+        conv_dgrad(c.st, in0, c.weights[n.pars[0]], out, tconv_adjoint_shape(g, n), false);
+    } else if (op == "dwconv") {
+        dwconv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n));
+    } else if (op == "concat") {
+        const int Ca = (int)g.shape_of(n.ins[0]).back(), Cb = (int)g.shape_of(n.ins[1]).back();
+        const int64_t rows = numel_of(n.shape) / (Ca + Cb);
+        column_copy(c.st, in0, Ca, out, Ca + Cb, Ca, rows, false);
+        column_copy(c.st, (const float *)c.ptr(L.a[1]), Cb, out + Ca, Ca + Cb, Cb, rows, false);
     } else if (op == "bn") {
         int C = (int)n.shape.back();
         int64_t rows = numel_of(n.shape) / C;
@@ -222,10 +247,17 @@ void run_forward(const StepCtx &c, const Launch &L) {
         avgpool_fwd(c.st, in0, out, (int)is[0], (int)(is[1] * is[2]), (int)is[3]);
     } else if (op == "linear") {
         const auto &is = g.shape_of(n.ins[0]);
-        linear_fwd(c.st, in0, c.weights[n.pars[0]], c.weights[n.pars[1]], out, (int)is[0], (int)is[1], (int)n.shape[1]);
+        linear_fwd(c.st, in0, c.weights[n.pars[0]], c.weights[n.pars[1]], out, (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1]);
     } else if (op == "softmaxce") {
         const auto &is = g.shape_of(n.ins[0]);
-        softmaxce_fwd(c.st, in0, (const int32_t *)c.ptr(L.a[1]), out, (int)is[0], (int)is[1], c.scratch());
+        const int classes = (int)is.back();
+        const int64_t rows = numel_of(is) / classes;
+        // few classes (per-pixel scores): one thread per row; many classes: one workgroup per row
+        if (classes <= 32) softmaxce_rows_fwd(c.st, in0, (const int32_t *)c.ptr(L.a[1]), out, rows, classes, c.scratch(), c.scratch_bytes());
+        else {
+            if ((size_t)rows * 4 > c.scratch_bytes()) throw KernelError("softmaxce: scratch too small for the row losses");
+            softmaxce_fwd(c.st, in0, (const int32_t *)c.ptr(L.a[1]), out, (int)rows, classes, c.scratch());
+        }
     } else if (op == "sumloss") {
         sumloss_fwd(c.st, in0, out, numel_of(g.shape_of(n.ins[0])), c.scratch(), c.scratch_bytes());
     } else {
@@ -249,6 +281,22 @@ void run_backward(const StepCtx &c, const Launch &L) {
     } else if (kd == "conv_dgrad") {
         conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0, splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
                    (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+    } else if (kd == "tconv_wgrad") {
+        // filter gradient of the adjoint convolution: its input is this operator's output gradient, its
+        // output gradient this operator's input
+        conv_wgrad(c.st, gy, (const float *)dep, c.grads[n.pars[0]], tconv_adjoint_shape(g, n), splits_of(im.algo, im.extra),
+                   (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+    } else if (kd == "tconv_dgrad") {
+        conv_fwd(c.st, gy, c.weights[n.pars[0]], d0, tconv_adjoint_shape(g, n), 1, nullptr, 0, acc0);
+    } else if (kd == "dwconv_wgrad") {
+        dwconv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), c.scratch(), c.scratch_bytes());
+    } else if (kd == "dwconv_dgrad") {
+        dwconv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0);
+    } else if (kd == "concat_bwd") {
+        const int Ca = (int)g.shape_of(n.ins[0]).back(), Cb = (int)g.shape_of(n.ins[1]).back();
+        const int64_t rows = numel_of(n.shape) / (Ca + Cb);
+        if (n.ins[0] > 0) column_copy(c.st, gy, Ca + Cb, d0, Ca, Ca, rows, acc0);
+        if (n.ins[1] > 0) column_copy(c.st, gy + Ca, Ca + Cb, (float *)c.ptr(L.a[3]), Cb, Cb, rows, (L.flags & 2) != 0);
     } else if (kd == "bn_bwd") {
         int C = (int)n.shape.back();
         int64_t rows = numel_of(n.shape) / C;
@@ -269,14 +317,17 @@ void run_backward(const StepCtx &c, const Launch &L) {
         avgpool_bwd(c.st, gy, d0, (int)is[0], (int)(is[1] * is[2]), (int)is[3], acc0);
     } else if (kd == "linear_wgrad") {
         const auto &is = g.shape_of(n.ins[0]);
-        linear_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], c.grads[n.pars[1]], (int)is[0], (int)is[1], (int)n.shape[1]);
+        linear_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], c.grads[n.pars[1]], (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1]);
     } else if (kd == "linear_dgrad") {
         const auto &is = g.shape_of(n.ins[0]);
-        linear_dgrad(c.st, gy, c.weights[n.pars[0]], d0, (int)is[0], (int)is[1], (int)n.shape[1], acc0);
+        linear_dgrad(c.st, gy, c.weights[n.pars[0]], d0, (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1], acc0);
     } else if (kd == "softmaxce_bwd") {
         const auto &is = g.shape_of(n.ins[0]);
         Ref lab; lab.region = R_EXT; lab.off = -n.ins[1];
-        softmaxce_bwd(c.st, (const float *)dep, (const int32_t *)c.ptr(lab), d0, (int)is[0], (int)is[1], acc0);
+        const int classes = (int)is.back();
+        const int64_t rows = numel_of(is) / classes;
+        if (classes <= 32) softmaxce_rows_bwd(c.st, (const float *)dep, (const int32_t *)c.ptr(lab), d0, rows, classes, acc0);
+        else softmaxce_bwd(c.st, (const float *)dep, (const int32_t *)c.ptr(lab), d0, (int)rows, classes, acc0);
     } else if (kd == "sumloss_bwd") {
         int64_t cnt = numel_of(g.shape_of(n.ins[0]));
         if (acc0) throw KernelError("sumloss_bwd cannot accumulate");
@@ -537,6 +588,8 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         label = b.kind;
         if (b.kind == "conv_wgrad") conv_cost(conv_shape(g, n), "conv_wgrad");
         else if (b.kind == "conv_dgrad") conv_cost(conv_shape(g, n), "conv_dgrad");
+        else if (b.kind == "tconv_wgrad") conv_cost(tconv_adjoint_shape(g, n), "tconv_wgrad");
+        else if (b.kind == "tconv_dgrad") conv_cost(tconv_adjoint_shape(g, n), "tconv_dgrad");
         else if (b.kind == "linear_wgrad") conv_cost(linear_shape(g, n), "linear_wgrad");
         else if (b.kind == "linear_dgrad") conv_cost(linear_shape(g, n), "linear_dgrad");
         else if (b.kind == "bn_bwd") bytes = 5 * e;                      // reduce pass reads dy,t; apply pass reads dy,t, writes dx
@@ -546,6 +599,8 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
             double in = 4.0 * (double)numel_of(g.shape_of(n.ins[0]));
             bytes = in + (b.impls[L.impl].algo == "from_index" ? 1.25 * e : e + in);
         } else if (b.kind == "add_bwd") bytes = 4 * e;
+        else if (b.kind == "concat_bwd") bytes = 2 * e;
+        else if (b.kind == "dwconv_dgrad" || b.kind == "dwconv_wgrad") bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e;
         else if (b.kind == "avgpool_bwd") bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e;
         else bytes = 2.0 * 4.0 * (double)numel_of(g.shape_of(n.ins[0]));
         if ((b.kind == "relu_bwd" || b.kind == "relu6_bwd" || b.kind == "bn_bwd" || b.kind == "conv_dgrad") && (L.flags & 1)) bytes += e;
@@ -554,6 +609,8 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         double e = 4.0 * (double)numel_of(n.shape);
         label = n.op + "_fwd";
         if (n.op == "conv") conv_cost(conv_shape(g, n), "conv_fwd");
+        else if (n.op == "tconv") conv_cost(tconv_adjoint_shape(g, n), "tconv_fwd");
+        else if (n.op == "concat") bytes = 2 * e;
         else if (n.op == "linear") conv_cost(linear_shape(g, n), "linear_fwd");
         else if (n.op == "bn") {
             if (L.kind == EV_RUN_FWD) bytes = 3 * e;                     // statistics pass + apply pass
@@ -677,4 +734,47 @@ extern "C" int monet_conv_force_tile(int cfg) {
 }
 extern "C" int monet_copy(void *stream, const float *src, float *dst, int64_t n) {
     return guarded([&] { copy_or_accumulate((hipStream_t)stream, src, dst, n, false); });
+}
+
+// transposed convolution through the convolution it is the adjoint of (see tconv_adjoint_shape)
+static ConvShape mk_tconv_adjoint(int N, int H, int W, int C, int K, int R, int S, int stride) {
+    ConvShape cs{N, 0, 0, K, C, R, S, stride, 0, H, W};
+    if (stride > 0) {
+        cs.H = (H - 1) * stride + R;
+        cs.W = (W - 1) * stride + S;
+    }
+    return cs;
+}
+extern "C" int monet_tconv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S, int stride) {
+    return guarded([&] { conv_dgrad((hipStream_t)stream, x, w, y, mk_tconv_adjoint(N, H, W, C, K, R, S, stride), false); });
+}
+extern "C" int monet_tconv_dgrad(void *stream, const float *dy, const float *w, float *dx, int N, int H, int W, int C, int K, int R, int S,
+                                 int stride, int accumulate) {
+    return guarded([&] { conv_fwd((hipStream_t)stream, dy, w, dx, mk_tconv_adjoint(N, H, W, C, K, R, S, stride), 1, nullptr, 0, accumulate != 0); });
+}
+extern "C" int monet_tconv_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R, int S,
+                                 int stride, int splits, float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_wgrad((hipStream_t)stream, dy, x, dw, mk_tconv_adjoint(N, H, W, C, K, R, S, stride), splits, ws, ws_bytes); });
+}
+extern "C" int monet_dwconv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int R, int S, int stride, int pad) {
+    return guarded([&] { dwconv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, C, R, S, stride, pad)); });
+}
+extern "C" int monet_dwconv_dgrad(void *stream, const float *dy, const float *w, float *dx, int N, int H, int W, int C, int R, int S, int stride,
+                                  int pad, int accumulate) {
+    return guarded([&] { dwconv_dgrad((hipStream_t)stream, dy, w, dx, mk_conv(N, H, W, C, C, R, S, stride, pad), accumulate != 0); });
+}
+extern "C" int monet_dwconv_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int R, int S, int stride,
+                                  int pad, float *scratch, size_t scratch_bytes) {
+    return guarded([&] { dwconv_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, C, R, S, stride, pad), scratch, scratch_bytes); });
+}
+extern "C" int monet_column_copy(void *stream, const float *src, int64_t src_ld, float *dst, int64_t dst_ld, int cols, int64_t rows, int accumulate) {
+    return guarded([&] { column_copy((hipStream_t)stream, src, src_ld, dst, dst_ld, cols, rows, accumulate != 0); });
+}
+extern "C" int monet_softmaxce_rows_fwd(void *stream, const float *logits, const int32_t *labels, float *loss, int64_t rows, int classes,
+                                        float *scratch, size_t scratch_bytes) {
+    return guarded([&] { softmaxce_rows_fwd((hipStream_t)stream, logits, labels, loss, rows, classes, scratch, scratch_bytes); });
+}
+extern "C" int monet_softmaxce_rows_bwd(void *stream, const float *logits, const int32_t *labels, float *dlogits, int64_t rows, int classes,
+                                        int accumulate) {
+    return guarded([&] { softmaxce_rows_bwd((hipStream_t)stream, logits, labels, dlogits, rows, classes, accumulate != 0); });
 }

@@ -488,7 +488,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 ? 3 : 2)) void conv_til
     // ---------------- epilogue: lane holds column l32 of rows 8*(v/4) + 4*g + v%4 of each 32x32 block
     float *out = ta.out;
     out += (int64_t)split * ta.out_elems;
-    const bool do_acc = MODE == DGRAD && ta.accumulate && nsplit == 1;
+    const bool do_acc = MODE != WGRAD && ta.accumulate && nsplit == 1;
     if (FAST && (ta.Ng & 3) == 0) {
         // Vector path: each wave transposes its 64x64 result through a private 16x64 LDS patch, four
         // passes of 16 rows, and writes whole 16-byte pieces, 256 contiguous bytes per row.
@@ -546,7 +546,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 ? 3 : 2)) void conv_til
                 if (col < ta.Ng) {
                     float *dst = out + orow * ta.Ng + col;
                     float r = acc[mi][ni][v];
-                    if (MODE == DGRAD && ta.accumulate && nsplit == 1) r += *dst;
+                    if (do_acc) r += *dst;
                     *dst = r;
                 }
             }
@@ -660,7 +660,8 @@ static float *split_target(float *out, int64_t out_elems, int &splits, float *ws
     return ws;
 }
 
-void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
+void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,
+              bool accumulate) {
     check_shape(cs);
     TileArgs ta{};
     ta.a = x; ta.b = w; ta.cs = cs;
@@ -668,9 +669,10 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
     ta.out_elems = ta.Mg * ta.Ng;
     ta.out = split_target(y, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_fwd");
     ta.splits = splits;
+    ta.accumulate = accumulate ? 1 : 0;
     bool fast = cs.C % BK == 0;
     launch_cfg<FWD>(st, ta, fast, 1, pick_cfg(FWD, ta.Mg, ta.Ng));
-    if (splits > 1) launch_split_reduce(st, ws, y, ta.out_elems, splits, false);
+    if (splits > 1) launch_split_reduce(st, ws, y, ta.out_elems, splits, accumulate);
 }
 
 void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits, float *ws,

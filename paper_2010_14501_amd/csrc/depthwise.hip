@@ -1,0 +1,374 @@
+// Bandwidth-bound operators of the segmentation and mobile networks: depthwise convolution
+// (forward, input gradient, filter gradient), copies between tensors of different row length
+// (channel concatenation and its backward), and cross-entropy over rows with few classes
+// (per-pixel losses).  A depthwise filter touches one channel only, so there is no contraction to
+// hand to the matrix cores: every output element costs R*S multiply-adds and the kernels are bound
+// by HBM traffic (one read of the input, one write of the output).  NHWC, fp32, four channels per
+// thread, filters staged in LDS in tap-major order so that four neighbouring channels are one
+// 16-byte LDS read.
+#include "kernels.hpp"
+
+namespace monet {
+
+namespace {
+
+int grid_cap(int64_t items, int per_block, int cap) {
+    int64_t g = (items + per_block - 1) / per_block;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(g, cap));
+}
+
+__device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
+__device__ inline void fma4(float4 &a, const float4 &x, const float4 &w) {
+    a.x += x.x * w.x; a.y += x.y * w.y; a.z += x.z * w.z; a.w += x.w * w.w;
+}
+
+// filters are stored C,R,S (channel-major); LDS copy is [tap][C]
+__device__ inline void stage_filters(float *wl, const float *__restrict__ w, int C, int taps) {
+    for (int i = threadIdx.x; i < C * taps; i += blockDim.x) {
+        int c = i / taps, t = i - c * taps;
+        wl[t * C + c] = w[i];
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------------ forward
+// V = 4: C % 4 == 0, one thread per (pixel, four channels); V = 1: any C, one thread per element.
+template <int V>
+__global__ __launch_bounds__(256) void dw_fwd_kernel(const float *__restrict__ x, const float *__restrict__ w, float *__restrict__ y,
+                                                     ConvShape cs) {
+    extern __shared__ float wl[];
+    const int C = cs.C, taps = cs.R * cs.S, CV = C / V;
+    stage_filters(wl, w, C, taps);
+    const int64_t total = cs.M() * CV;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int cv = (int)(i % CV);
+        int64_t pix = i / CV;
+        const int q = (int)(pix % cs.Q); pix /= cs.Q;
+        const int p = (int)(pix % cs.P);
+        const int n = (int)(pix / cs.P);
+        const float *xn = x + (int64_t)n * cs.H * cs.W * C + cv * V;
+        float4 acc = make_float4(0, 0, 0, 0);
+        for (int r = 0; r < cs.R; ++r) {
+            const int h = p * cs.stride + r - cs.pad;
+            if ((unsigned)h >= (unsigned)cs.H) continue;
+            for (int s = 0; s < cs.S; ++s) {
+                const int v = q * cs.stride + s - cs.pad;
+                if ((unsigned)v >= (unsigned)cs.W) continue;
+                const float *px = xn + ((int64_t)h * cs.W + v) * C;
+                const float *pw = wl + (r * cs.S + s) * C + cv * V;
+                if (V == 4) fma4(acc, ld4(px), *(const float4 *)pw);
+                else acc.x += px[0] * pw[0];
+            }
+        }
+        if (V == 4) *(float4 *)(y + i * 4) = acc;
+        else y[i] = acc.x;
+    }
+}
+
+// ------------------------------------------------------------------ input gradient
+template <int V, bool ACC>
+__global__ __launch_bounds__(256) void dw_dgrad_kernel(const float *__restrict__ dy, const float *__restrict__ w, float *dx, ConvShape cs) {
+    extern __shared__ float wl[];
+    const int C = cs.C, taps = cs.R * cs.S, CV = C / V;
+    stage_filters(wl, w, C, taps);
+    const int64_t total = (int64_t)cs.N * cs.H * cs.W * CV;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int cv = (int)(i % CV);
+        int64_t pix = i / CV;
+        const int v = (int)(pix % cs.W); pix /= cs.W;
+        const int h = (int)(pix % cs.H);
+        const int n = (int)(pix / cs.H);
+        const float *gn = dy + (int64_t)n * cs.P * cs.Q * C + cv * V;
+        float4 acc = make_float4(0, 0, 0, 0);
+        for (int r = 0; r < cs.R; ++r) {
+            const int hp = h + cs.pad - r;
+            if (hp < 0 || hp % cs.stride) continue;
+            const int p = hp / cs.stride;
+            if (p >= cs.P) continue;
+            for (int s = 0; s < cs.S; ++s) {
+                const int vq = v + cs.pad - s;
+                if (vq < 0 || vq % cs.stride) continue;
+                const int q = vq / cs.stride;
+                if (q >= cs.Q) continue;
+                const float *pg = gn + ((int64_t)p * cs.Q + q) * C;
+                const float *pw = wl + (r * cs.S + s) * C + cv * V;
+                if (V == 4) fma4(acc, ld4(pg), *(const float4 *)pw);
+                else acc.x += pg[0] * pw[0];
+            }
+        }
+        if (V == 4) {
+            float4 *d = (float4 *)(dx + i * 4);
+            if (ACC) { float4 o = *d; acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w; }
+            *d = acc;
+        } else {
+            dx[i] = ACC ? dx[i] + acc.x : acc.x;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ filter gradient
+// Two levels, both in a fixed order (no float atomics): block (slab, channel chunk) sums its pixels into
+// part[slab][tap][C]; the second kernel adds the slabs.  blockDim = (CL, 256 / CL): x = channel lane
+// (V channels each), y = pixel lane.
+constexpr int DW_MAX_TAPS = 9;
+
+template <int V>
+__global__ __launch_bounds__(256) void dw_wgrad_partial(const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part,
+                                                        ConvShape cs, int64_t pix_per_slab) {
+    extern __shared__ float red[];   // [blockDim.y][taps][CL * V]
+    const int C = cs.C, CV = C / V, taps = cs.R * cs.S;
+    const int CL = blockDim.x, PL = blockDim.y;
+    const int cv = blockIdx.y * CL + threadIdx.x;
+    const bool live = cv < CV;
+    float4 acc[DW_MAX_TAPS];
+#pragma unroll
+    for (int t = 0; t < DW_MAX_TAPS; ++t) acc[t] = make_float4(0, 0, 0, 0);
+    const int64_t M = cs.M();
+    const int64_t p0 = blockIdx.x * pix_per_slab;
+    const int64_t p1 = p0 + pix_per_slab < M ? p0 + pix_per_slab : M;
+    if (live) {
+        for (int64_t pix = p0 + threadIdx.y; pix < p1; pix += PL) {
+            int64_t t = pix;
+            const int q = (int)(t % cs.Q); t /= cs.Q;
+            const int p = (int)(t % cs.P);
+            const int n = (int)(t / cs.P);
+            float4 g = make_float4(0, 0, 0, 0);
+            if (V == 4) g = ld4(dy + pix * C + cv * 4);
+            else g.x = dy[pix * C + cv];
+            const float *xn = x + (int64_t)n * cs.H * cs.W * C + cv * V;
+#pragma unroll
+            for (int tp = 0; tp < DW_MAX_TAPS; ++tp) {
+                if (tp >= taps) break;
+                const int r = tp / cs.S, s = tp - r * cs.S;
+                const int h = p * cs.stride + r - cs.pad, v = q * cs.stride + s - cs.pad;
+                if ((unsigned)h >= (unsigned)cs.H || (unsigned)v >= (unsigned)cs.W) continue;
+                const float *px = xn + ((int64_t)h * cs.W + v) * C;
+                if (V == 4) fma4(acc[tp], ld4(px), g);
+                else acc[tp].x += px[0] * g.x;
+            }
+        }
+    }
+    // pixel lanes -> lane 0, in lane order
+    const int width = CL * V;
+#pragma unroll
+    for (int tp = 0; tp < DW_MAX_TAPS; ++tp) {
+        if (tp >= taps) break;
+        float *dst = red + ((size_t)threadIdx.y * taps + tp) * width + threadIdx.x * V;
+        if (V == 4) *(float4 *)dst = acc[tp];
+        else dst[0] = acc[tp].x;
+    }
+    __syncthreads();
+    if (threadIdx.y == 0 && live) {
+        for (int tp = 0; tp < taps; ++tp) {
+            float4 s = make_float4(0, 0, 0, 0);
+            for (int l = 0; l < PL; ++l) {
+                const float *src = red + ((size_t)l * taps + tp) * width + threadIdx.x * V;
+                if (V == 4) { float4 a = *(const float4 *)src; s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w; }
+                else s.x += src[0];
+            }
+            float *out = part + ((size_t)blockIdx.x * taps + tp) * C + cv * V;
+            if (V == 4) *(float4 *)out = s;
+            else out[0] = s.x;
+        }
+    }
+}
+
+// dw[c][tap] = sum over slabs, slab order
+__global__ __launch_bounds__(256) void dw_wgrad_final(const float *__restrict__ part, float *__restrict__ dw, int C, int taps, int slabs) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;   // over tap-major (tap, c)
+    if (i >= C * taps) return;
+    const int tp = i / C, c = i - tp * C;
+    float s = 0;
+    for (int b = 0; b < slabs; ++b) s += part[((size_t)b * taps + tp) * C + c];
+    dw[c * taps + tp] = s;
+}
+
+void check_dw(const ConvShape &cs, const char *who) {
+    if (cs.K != cs.C) throw KernelError(std::string(who) + ": depthwise needs K == C");
+    if (cs.R * cs.S > DW_MAX_TAPS) throw KernelError(std::string(who) + ": at most 9 filter taps");
+    if (cs.N <= 0 || cs.C <= 0 || cs.P <= 0 || cs.Q <= 0 || cs.stride <= 0) throw KernelError(std::string(who) + ": bad shape");
+    if (cs.P != (cs.H + 2 * cs.pad - cs.R) / cs.stride + 1 || cs.Q != (cs.W + 2 * cs.pad - cs.S) / cs.stride + 1)
+        throw KernelError(std::string(who) + ": output extent does not match the input");
+    if ((size_t)cs.C * cs.R * cs.S * 4 > 64 * 1024) throw KernelError(std::string(who) + ": filters do not fit in LDS");
+}
+
+}  // namespace
+
+void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs) {
+    check_dw(cs, "dwconv_fwd");
+    const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
+    if (cs.C % 4 == 0) {
+        int grid = grid_cap(cs.M() * (cs.C / 4), 256, 8192);
+        hipLaunchKernelGGL((dw_fwd_kernel<4>), dim3(grid), dim3(256), lds, st, x, w, y, cs);
+    } else {
+        int grid = grid_cap(cs.M() * cs.C, 256, 8192);
+        hipLaunchKernelGGL((dw_fwd_kernel<1>), dim3(grid), dim3(256), lds, st, x, w, y, cs);
+    }
+    hip_check(hipGetLastError(), "dwconv_fwd launch");
+}
+
+void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate) {
+    check_dw(cs, "dwconv_dgrad");
+    const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
+    const int64_t pixels = (int64_t)cs.N * cs.H * cs.W;
+#define DG(V, ACC) hipLaunchKernelGGL((dw_dgrad_kernel<V, ACC>), dim3(grid), dim3(256), lds, st, dy, w, dx, cs)
+    if (cs.C % 4 == 0) {
+        int grid = grid_cap(pixels * (cs.C / 4), 256, 8192);
+        if (accumulate) DG(4, true); else DG(4, false);
+    } else {
+        int grid = grid_cap(pixels * cs.C, 256, 8192);
+        if (accumulate) DG(1, true); else DG(1, false);
+    }
+#undef DG
+    hip_check(hipGetLastError(), "dwconv_dgrad launch");
+}
+
+void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *scratch, size_t scratch_bytes) {
+    check_dw(cs, "dwconv_wgrad");
+    const int taps = cs.R * cs.S;
+    const int V = cs.C % 4 == 0 ? 4 : 1;
+    const int CV = cs.C / V;
+    int CL = 1;
+    while (CL < CV && CL < 64) CL <<= 1;
+    const int PL = 256 / CL;
+    const int chunks = (CV + CL - 1) / CL;
+    const int64_t M = cs.M();
+    const size_t slab_bytes = (size_t)taps * cs.C * 4;
+    int64_t slabs = std::min<int64_t>({(int64_t)1024, (int64_t)(scratch_bytes / slab_bytes), (M + 4 * PL - 1) / (4 * PL)});
+    if (slabs < 1) throw KernelError("dwconv_wgrad: scratch too small");
+    const int64_t pps = (M + slabs - 1) / slabs;
+    slabs = (M + pps - 1) / pps;
+    const size_t lds = (size_t)PL * taps * CL * V * 4;
+    if (lds > 64 * 1024) throw KernelError("dwconv_wgrad: reduction buffer does not fit in LDS");
+    if (V == 4) hipLaunchKernelGGL((dw_wgrad_partial<4>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs, pps);
+    else hipLaunchKernelGGL((dw_wgrad_partial<1>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs, pps);
+    hipLaunchKernelGGL(dw_wgrad_final, dim3((cs.C * taps + 255) / 256), dim3(256), 0, st, (const float *)scratch, dw, cs.C, taps, (int)slabs);
+    hip_check(hipGetLastError(), "dwconv_wgrad launch");
+}
+
+// ------------------------------------------------------------------ copies between row lengths
+namespace {
+
+template <int V, bool ACC>
+__global__ __launch_bounds__(256) void column_copy_kernel(const float *__restrict__ src, int64_t src_ld, float *dst, int64_t dst_ld, int cols,
+                                                          int64_t rows) {
+    const int CV = cols / V;
+    const int64_t total = rows * CV;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = i / CV;
+        const int c = (int)(i - row * CV) * V;
+        const float *s = src + row * src_ld + c;
+        float *d = dst + row * dst_ld + c;
+        if (V == 4) {
+            float4 v = ld4(s);
+            if (ACC) { float4 o = *(float4 *)d; v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w; }
+            *(float4 *)d = v;
+        } else {
+            d[0] = ACC ? d[0] + s[0] : s[0];
+        }
+    }
+}
+
+}  // namespace
+
+// dst[row][0..cols) (+)= src[row][0..cols), rows of src / dst are src_ld / dst_ld floats apart (the caller
+// offsets the base pointers to the first column).
+void column_copy(hipStream_t st, const float *src, int64_t src_ld, float *dst, int64_t dst_ld, int cols, int64_t rows, bool accumulate) {
+    if (rows <= 0 || cols <= 0) return;
+    if (src_ld < cols || dst_ld < cols) throw KernelError("column_copy: row length shorter than the copied columns");
+    const bool vec = cols % 4 == 0 && src_ld % 4 == 0 && dst_ld % 4 == 0 && ((uintptr_t)src % 16) == 0 && ((uintptr_t)dst % 16) == 0;
+#define CC(V, ACC) hipLaunchKernelGGL((column_copy_kernel<V, ACC>), dim3(grid), dim3(256), 0, st, src, src_ld, dst, dst_ld, cols, rows)
+    if (vec) {
+        int grid = grid_cap(rows * (cols / 4), 256 * 4, 8192);
+        if (accumulate) CC(4, true); else CC(4, false);
+    } else {
+        int grid = grid_cap(rows * cols, 256 * 4, 8192);
+        if (accumulate) CC(1, true); else CC(1, false);
+    }
+#undef CC
+    hip_check(hipGetLastError(), "column_copy launch");
+}
+
+// ------------------------------------------------------------------ cross-entropy over many short rows
+namespace {
+
+constexpr int CE_BLOCKS = 1024;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+// one thread per row; per-block partial sums of the row losses, fixed order
+__global__ __launch_bounds__(256) void ce_rows_fwd_kernel(const float *__restrict__ logits, const int32_t *__restrict__ labels,
+                                                          float *__restrict__ part, int64_t rows, int classes) {
+    __shared__ float sh[4];
+    float mine = 0;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (int64_t)gridDim.x * blockDim.x) {
+        const float *z = logits + r * classes;
+        float m = z[0];
+        for (int c = 1; c < classes; ++c) m = fmaxf(m, z[c]);
+        float s = 0;
+        for (int c = 0; c < classes; ++c) s += expf(z[c] - m);
+        mine += logf(s) - (z[labels[r]] - m);
+    }
+    mine = wave_sum(mine);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
+__global__ __launch_bounds__(256) void ce_rows_final_kernel(const float *__restrict__ part, float *__restrict__ loss, int n, float scale) {
+    __shared__ double sh[256];
+    double s = 0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) s += (double)part[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) loss[0] = (float)(sh[0] * (double)scale);
+}
+
+template <bool ACC>
+__global__ __launch_bounds__(256) void ce_rows_bwd_kernel(const float *__restrict__ logits, const int32_t *__restrict__ labels, float *dlogits,
+                                                          int64_t rows, int classes, float inv_rows) {
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < rows; r += (int64_t)gridDim.x * blockDim.x) {
+        const float *z = logits + r * classes;
+        float m = z[0];
+        for (int c = 1; c < classes; ++c) m = fmaxf(m, z[c]);
+        float s = 0;
+        for (int c = 0; c < classes; ++c) s += expf(z[c] - m);
+        const float inv = 1.0f / s;
+        const int lab = labels[r];
+        float *d = dlogits + r * classes;
+        for (int c = 0; c < classes; ++c) {
+            float g = (expf(z[c] - m) * inv - (c == lab ? 1.0f : 0.0f)) * inv_rows;
+            d[c] = ACC ? d[c] + g : g;
+        }
+    }
+}
+
+}  // namespace
+
+void softmaxce_rows_fwd(hipStream_t st, const float *logits, const int32_t *labels, float *loss, int64_t rows, int classes, float *scratch,
+                        size_t scratch_bytes) {
+    if (rows <= 0 || classes <= 0) throw KernelError("softmaxce: bad shape");
+    int grid = grid_cap(rows, 256, CE_BLOCKS);
+    if ((size_t)grid * 4 > scratch_bytes) throw KernelError("softmaxce: scratch too small");
+    hipLaunchKernelGGL(ce_rows_fwd_kernel, dim3(grid), dim3(256), 0, st, logits, labels, scratch, rows, classes);
+    hipLaunchKernelGGL(ce_rows_final_kernel, dim3(1), dim3(256), 0, st, (const float *)scratch, loss, grid, 1.0f / (float)rows);
+    hip_check(hipGetLastError(), "softmaxce rows forward launch");
+}
+
+void softmaxce_rows_bwd(hipStream_t st, const float *logits, const int32_t *labels, float *dlogits, int64_t rows, int classes, bool accumulate) {
+    if (rows <= 0 || classes <= 0) throw KernelError("softmaxce: bad shape");
+    int grid = grid_cap(rows, 256, 8192);
+    if (accumulate) hipLaunchKernelGGL((ce_rows_bwd_kernel<true>), dim3(grid), dim3(256), 0, st, logits, labels, dlogits, rows, classes, 1.0f / (float)rows);
+    else hipLaunchKernelGGL((ce_rows_bwd_kernel<false>), dim3(grid), dim3(256), 0, st, logits, labels, dlogits, rows, classes, 1.0f / (float)rows);
+    hip_check(hipGetLastError(), "softmaxce rows backward launch");
+}
+
+}  // namespace monet

@@ -31,14 +31,21 @@ struct ConvShape {
 // ---- convolution (implicit GEMM on fp32 MFMA)
 // Every variant can cut its reduction into `splits` ranges: partial results go to ws (splits * |output|
 // floats) and are added in range order.  splits == 1 needs no workspace.
+// y (+)= conv(x, w)
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits = 1, float *ws = nullptr,
-              size_t ws_bytes = 0);
+              size_t ws_bytes = 0, bool accumulate = false);
 // dx (+)= transpose-conv of dy with w
 void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits = 1,
                 float *ws = nullptr, size_t ws_bytes = 0);
 // dw = sum over N,P,Q
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws,
                 size_t ws_bytes);
+
+// ---- depthwise convolution (K == C, filters C,R,S; at most 9 taps); HBM-bound, no matrix cores
+void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);
+void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate);
+// two-level fixed-order reduction; scratch holds slabs * R*S*C floats
+void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *scratch, size_t scratch_bytes);
 
 // tuning aid: cfg 0..5 forces tile shape (2x2, 4x1, 1x4, 2x1, 1x2, 1x1 waves of 64x64); -1 restores the heuristic
 void conv_force_tile(int cfg);
@@ -87,6 +94,9 @@ void copy_or_accumulate(hipStream_t st, const float *src, float *dst, int64_t n,
 void fill_f32(hipStream_t st, float *dst, int64_t n, float v);
 void fill_u32(hipStream_t st, uint32_t *dst, int64_t n, uint32_t v);
 
+// dst[row][0..cols) (+)= src[row][0..cols); consecutive rows are src_ld / dst_ld floats apart
+void column_copy(hipStream_t st, const float *src, int64_t src_ld, float *dst, int64_t dst_ld, int cols, int64_t rows, bool accumulate);
+
 // ---- linear layer: y[N,out] = x[N,in] w[out,in]^T + b
 void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out);
 void linear_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, float *db, int N, int in, int out);
@@ -97,6 +107,10 @@ void softmaxce_fwd(hipStream_t st, const float *logits, const int32_t *labels, f
                    float *scratch);
 void softmaxce_bwd(hipStream_t st, const float *logits, const int32_t *labels, float *dlogits, int N, int classes,
                    bool accumulate);
+// the same loss for many rows of few classes (per-pixel scores): one thread per row; scratch >= 1024 floats
+void softmaxce_rows_fwd(hipStream_t st, const float *logits, const int32_t *labels, float *loss, int64_t rows, int classes, float *scratch,
+                        size_t scratch_bytes);
+void softmaxce_rows_bwd(hipStream_t st, const float *logits, const int32_t *labels, float *dlogits, int64_t rows, int classes, bool accumulate);
 void sumloss_fwd(hipStream_t st, const float *x, float *loss, int64_t n, float *scratch, size_t scratch_bytes);
 
 }  // namespace monet

@@ -255,6 +255,11 @@ static void check_declared_deps(const Graph &g) {
             };
             if (b.kind == "conv_wgrad") { known = (algo == "direct" || algo == "splitk"); input0(); }
             else if (b.kind == "conv_dgrad") { known = (algo == "igemm" || algo == "igemm_splitk"); }
+            else if (b.kind == "tconv_wgrad") { known = (algo == "direct" || algo == "splitk"); input0(); }
+            else if (b.kind == "tconv_dgrad") { known = algo == "igemm"; }
+            else if (b.kind == "dwconv_wgrad") { known = algo == "direct"; input0(); }
+            else if (b.kind == "dwconv_dgrad") { known = algo == "direct"; }
+            else if (b.kind == "concat_bwd") { known = algo == "copy"; }
             else if (b.kind == "linear_wgrad") { known = algo == "gemm"; input0(); }
             else if (b.kind == "linear_dgrad") { known = algo == "gemm"; }
             else if (b.kind == "bn_bwd") {
@@ -564,7 +569,7 @@ void Plan::lower() {
         }
         for (int d : D) fwd_ref(d, who);
         if (!D.empty()) L.a[1] = fwd_ref(D[0], who);
-        else if (b.kind == "conv_wgrad" || b.kind == "linear_wgrad") L.a[1] = fwd_ref(n.ins[0], who);
+        else if (b.kind.size() > 6 && b.kind.compare(b.kind.size() - 6, 6, "_wgrad") == 0) L.a[1] = fwd_ref(n.ins[0], who);
         uint32_t acc = 0;
         for (int p : grad_positions(g, b)) {
             int j = n.ins[p];

@@ -92,8 +92,19 @@ def load_library():
     lib.monet_copy.argtypes = [vp, vp, vp, i64]
     lib.monet_conv_force_tile.argtypes = [i32]
     lib.monet_conv_force_tile.restype = i32
+    lib.monet_tconv_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 8
+    lib.monet_tconv_dgrad.argtypes = [vp, vp, vp, vp] + [i32] * 9
+    lib.monet_tconv_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp, sz]
+    lib.monet_dwconv_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 8
+    lib.monet_dwconv_dgrad.argtypes = [vp, vp, vp, vp] + [i32] * 9
+    lib.monet_dwconv_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 8 + [vp, sz]
+    lib.monet_column_copy.argtypes = [vp, vp, i64, vp, i64, i32, i64, i32]
+    lib.monet_softmaxce_rows_fwd.argtypes = [vp, vp, vp, vp, i64, i32, vp, sz]
+    lib.monet_softmaxce_rows_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32]
     for name in ("monet_conv_fwd", "monet_conv_dgrad", "monet_conv_wgrad", "monet_bn_stats", "monet_bn_apply", "monet_bn_bwd",
-                 "monet_relu_fwd", "monet_relu_bwd", "monet_maxpool_fwd", "monet_maxpool_bwd", "monet_copy"):
+                 "monet_relu_fwd", "monet_relu_bwd", "monet_maxpool_fwd", "monet_maxpool_bwd", "monet_copy",
+                 "monet_tconv_fwd", "monet_tconv_dgrad", "monet_tconv_wgrad", "monet_dwconv_fwd", "monet_dwconv_dgrad",
+                 "monet_dwconv_wgrad", "monet_column_copy", "monet_softmaxce_rows_fwd", "monet_softmaxce_rows_bwd"):
         getattr(lib, name).restype = i32
     _LIB = lib
     return lib

@@ -55,6 +55,38 @@ def test_trace_matches_oracle_on_resnet_shapes():
         check_against_oracle(g, sch)
 
 
+@pytest.mark.parametrize("net", ["vgg", "unet", "mbv2"])
+def test_trace_matches_oracle_on_the_other_network_families(net):
+    if net == "vgg":
+        g = graphs.vgg16_bn(batch=2, hw=32, classes=10, widths=(8, 16, 16, 32, 32), fc=64)
+    elif net == "unet":
+        g = graphs.unet(batch=2, h=32, w=48, classes=2, base=8, depth=4)
+    else:
+        g = graphs.mobilenet_v2(batch=2, hw=32, classes=10, stem=8, last=64,
+                                stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 16, 2, 2), (6, 24, 1, 1)))
+    bimpl = schedules.choose_bimpls(g, schedules.DEFAULT_VARIANTS)
+    keep = {b for b in range(len(g.blocks)) if b % 2 == 0} | {len(g.blocks) - 1}
+    alternate = schedules.expand(g, schedules.block_checkpoint_set(g, bimpl, keep), bimpl)
+    recomputes = []
+    for sch in (schedules.store_everything_schedule(g),
+                schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS),
+                schedules.block_output_schedule(g), alternate):
+        plan = check_against_oracle(g, sch)
+        recomputes.append(sum(1 for e in plan.trace_tuples() if e[0] == M.RUN_RECOMPUTE))
+    assert recomputes[0] == recomputes[1] == 0 and recomputes[2] > 0 and recomputes[3] > 0
+
+
+def test_full_size_plans_of_the_other_network_families():
+    """VGG-16 b176, UNet b11 at 416x608 and MobileNetV2 b272 lower at their full sizes; recomputing
+    block internals cuts the peak well below store-everything."""
+    for g in (graphs.vgg16_bn(), graphs.unet(), graphs.mobilenet_v2()):
+        lean = M.Plan(g.text(), schedules.block_output_schedule(g).text())
+        store = M.Plan(g.text(), schedules.store_everything_schedule(g).text())
+        assert lean.exact_peak <= lean.predicted_peak
+        assert lean.exact_peak < 0.75 * store.exact_peak
+        assert lean.arena_bytes - lean.persistent_bytes <= 1.3 * lean.exact_peak
+
+
 def test_full_resnet50_plan_fragmentation_is_small():
     g = graphs.resnet50(batch=184)
     sch = schedules.block_output_schedule(g)
