@@ -211,7 +211,7 @@ def test_network_step_against_oracle(name):
         assert peak == want["peak"] == run.plan.exact_peak <= run.plan.predicted_peak, sname
         assert abs(run.loss_value() - ref["loss"]) < ACT_TOL * abs(ref["loss"]), sname
         got[sname] = run.grads_numpy()
-        worst = compare_grads(got[sname], ref)
+        worst = compare_grads(got[sname], ref, g=g)
         print(f"{name}/{sname}: peak {peak}, recomputes {want['recomputes']}, worst gradient error {worst:.2e}")
     # recomputation alone must not change a bit
     for sname in ("block_outputs", "alternate"):
