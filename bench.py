@@ -7,7 +7,7 @@ saving, then the backward pass with recomputation -- of the ResNet-50-shaped net
 schedule with the lean operator variants, through libmonet.so.  Inputs, weights and the arena
 are resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_b184|tiny_chain]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_b184|vgg16_b176|unet_b11|mobilenetv2_b272|tiny_chain]
 """
 import argparse
 import json
@@ -27,6 +27,16 @@ def build_workload(name):
     if name == "resnet50_b184":
         g = graphs.resnet50(batch=184)
         return g, schedules.block_output_schedule(g), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient"
+    lean = "keep block outputs, recompute block internals; lean operator variants"
+    if name == "vgg16_b176":
+        g = graphs.vgg16_bn(batch=176)
+        return g, schedules.block_output_schedule(g), 176, lean
+    if name == "unet_b11":
+        g = graphs.unet(batch=11)
+        return g, schedules.block_output_schedule(g), 11, lean
+    if name == "mobilenetv2_b272":
+        g = graphs.mobilenet_v2(batch=272)
+        return g, schedules.block_output_schedule(g), 272, lean
     if name == "tiny_chain":
         g = graphs.tiny_chain()
         return g, schedules.tiny_chain_schedule(g, {0, 2}), 2, "checkpoint blocks {0,2}, recompute {1,3}; lean variants"
@@ -47,6 +57,18 @@ def cpu_baseline(workload):
         batch = 16
         g = graphs.resnet50(batch=batch)
         sample = "same ResNet-50 graph at batch 16 (224x224, 1000 classes), one store-everything fp64 step"
+    elif workload == "vgg16_b176":
+        batch = 4
+        g = graphs.vgg16_bn(batch=batch)
+        sample = "same VGG-16 graph at batch 4 (224x224), one store-everything fp64 step"
+    elif workload == "unet_b11":
+        batch = 1
+        g = graphs.unet(batch=batch, h=208, w=304)
+        sample = "same UNet graph at batch 1 and half resolution (208x304), one store-everything fp64 step"
+    elif workload == "mobilenetv2_b272":
+        batch = 16
+        g = graphs.mobilenet_v2(batch=batch)
+        sample = "same MobileNetV2 graph at batch 16 (224x224), one store-everything fp64 step"
     else:
         batch = 2
         g = graphs.tiny_chain()

@@ -28,11 +28,11 @@ from .graphs import Graph
 
 DEFAULT_VARIANTS = dict(
     bn_bwd="from_output", relu_bwd="from_mask", relu6_bwd="from_mask", maxpool_bwd="from_index",
-    conv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=True,
+    conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=True,
 )
 STANDARD_VARIANTS = dict(
     bn_bwd="from_input", relu_bwd="from_output", relu6_bwd="from_output", maxpool_bwd="from_input",
-    conv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=False,
+    conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=False,
 )
 
 
