@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # 256 CUs x 256 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of a kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by what the
+# same counters read for a plain copy (profiles/step_resnet50_b184_hbm_traffic.txt); counters cannot be read
+# from inside this process, so the figure is the recorded one and null for anything not profiled.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("resnet50_b184", "conv_fwd"): 451.8e6}
 
 
 def build_workload(name):
@@ -91,6 +95,8 @@ def main():
     ap.add_argument("--workload", default="resnet50_b184")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="run only a plain device copy of this many MiB (counter calibration) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (the step has no collectives); use --gpus 1")
@@ -98,6 +104,20 @@ def main():
     import torch
     if not torch.cuda.is_available():
         raise SystemExit("bench.py: no GPU visible; the training step exists only as gfx950 kernels")
+    if args.copy_calibration:
+        # plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales the counters of the step
+        from paper_2010_14501_amd import monet
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.randn(n, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            monet.call("monet_copy", None, src.data_ptr(), dst.data_ptr(), n)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 20
+        print(json.dumps({"copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n, "launches": 20, "gbs": 8 * n / dt / 1e9}))
+        return
     from workloads import tensors
     from paper_2010_14501_amd.runner import StepRunner
 
@@ -170,7 +190,8 @@ def main():
         else:
             roof = {"bound": "hbm", "achieved": d["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["gbs"] / HBM_PEAK_GBS}
         roof.update({"kernel": dom, "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
-                     "traffic": None})
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, dom)),
+                     "algorithmic_bytes_per_launch": d["bytes"] / d["launches"]})
         out["roofline"] = roof
         out["classes"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 4), "tflops": round(v["tflops"], 2),
                               "gbs": round(v["gbs"], 1)} for k, v in sorted(classes.items(), key=lambda kv: -kv[1]["ms"])}
