@@ -198,6 +198,32 @@ def test_tie_resolution_with_strict_decisions_changes_nothing():
     assert all(np.array_equal(tied["grads"][p], plain["grads"][p]) for p in plain["grads"])
 
 
+@pytest.mark.parametrize("net", ["vgg", "unet", "mbv2"])
+def test_recomputing_schedules_reach_the_plain_gradients(net):
+    """Section 3: a tensor that is not stored is recomputed, so the result does not change.  The fp64
+    interpreter, which really deletes freed arrays, must give the store-everything gradients."""
+    from oracle import network as onet, schedule as osch
+    from workloads import graphs, schedules, tensors
+    if net == "vgg":
+        g = graphs.vgg16_bn(batch=2, hw=32, classes=10, widths=(8, 16, 16, 32, 32), fc=64)
+    elif net == "unet":
+        g = graphs.unet(batch=2, h=32, w=48, classes=2, base=8, depth=4)
+    else:
+        g = graphs.mobilenet_v2(batch=2, hw=32, classes=10, stem=8, last=64,
+                                stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 16, 2, 2), (6, 24, 1, 1)))
+    exts, params = tensors.make_inputs(g, seed=1, gamma_beta="random")
+    oe, op = tensors.oracle_inputs(exts, params)
+    plain = onet.store_everything_step(g.text(), oe, op)
+    top = max(np.linalg.norm(v) for v in plain["grads"].values())
+    for sch in (schedules.store_everything_schedule(g), schedules.block_output_schedule(g)):
+        got = osch.interpret(g.text(), sch.text(), oe, op)
+        assert abs(got["loss"] - plain["loss"]) < 1e-12 * abs(plain["loss"])
+        for p, want in plain["grads"].items():
+            # measured against the largest gradient: some BatchNorm shift gradients vanish identically
+            assert np.linalg.norm(got["grads"][p] - want) < 1e-12 * top, p
+    assert got["recomputes"] > 0
+
+
 def test_mask_of_a_matrix_is_packed_row_major():
     p = np.zeros((2, 70), bool)
     p[0, 0] = p[0, 65] = p[1, 3] = True       # element numbers 0, 65, 73
