@@ -31,16 +31,31 @@ def build_workload(name):
     if name == "resnet50_b184":
         g = graphs.resnet50(batch=184)
         return g, schedules.block_output_schedule(g), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient"
-    lean = "keep block outputs, recompute block internals; lean operator variants"
-    if name == "vgg16_b176":
-        g = graphs.vgg16_bn(batch=176)
-        return g, schedules.block_output_schedule(g), 176, lean
-    if name == "unet_b11":
-        g = graphs.unet(batch=11)
-        return g, schedules.block_output_schedule(g), 11, lean
-    if name == "mobilenetv2_b272":
-        g = graphs.mobilenet_v2(batch=272)
-        return g, schedules.block_output_schedule(g), 272, lean
+    if name.startswith("resnet50_b184_"):        # same network under another schedule
+        g = graphs.resnet50(batch=184)
+        kind = name[len("resnet50_b184_"):]
+        if kind == "store_everything":
+            return g, schedules.store_everything_schedule(g), 184, "store everything, standard variants (plain back-propagation)"
+        if kind == "store_everything_lean":
+            return g, schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS), 184, "store everything the lean variants read"
+        raise SystemExit(f"unknown workload {name}")
+    lean = "; lean operator variants"
+    nets = {"vgg16_b176": (lambda: graphs.vgg16_bn(batch=176), 176, schedules.vgg_alternate_schedule,
+                           "every second convolution triple recomputed"),
+            "unet_b11": (lambda: graphs.unet(batch=11), 11, schedules.unet_skip_schedule,
+                         "forward pass keeps the skip tensors only"),
+            "mobilenetv2_b272": (lambda: graphs.mobilenet_v2(batch=272), 272, schedules.mobilenet_depthwise_schedule,
+                                 "depthwise triples recomputed")}
+    for base, (make, batch, named, desc) in nets.items():
+        if name == base:
+            g = make()
+            return g, named(g), batch, desc + lean
+        if name == base + "_block_outputs":
+            g = make()
+            return g, schedules.block_output_schedule(g), batch, "keep block outputs, recompute block internals" + lean
+        if name == base + "_store_everything":
+            g = make()
+            return g, schedules.store_everything_schedule(g), batch, "store everything, standard variants"
     if name == "tiny_chain":
         g = graphs.tiny_chain()
         return g, schedules.tiny_chain_schedule(g, {0, 2}), 2, "checkpoint blocks {0,2}, recompute {1,3}; lean variants"
@@ -57,19 +72,19 @@ def cpu_baseline(workload):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count()
-    if workload == "resnet50_b184":
+    if workload.startswith("resnet50_b184"):
         batch = 16
         g = graphs.resnet50(batch=batch)
         sample = "same ResNet-50 graph at batch 16 (224x224, 1000 classes), one store-everything fp64 step"
-    elif workload == "vgg16_b176":
+    elif workload.startswith("vgg16_b176"):
         batch = 4
         g = graphs.vgg16_bn(batch=batch)
         sample = "same VGG-16 graph at batch 4 (224x224), one store-everything fp64 step"
-    elif workload == "unet_b11":
+    elif workload.startswith("unet_b11"):
         batch = 1
         g = graphs.unet(batch=batch, h=208, w=304)
         sample = "same UNet graph at batch 1 and half resolution (208x304), one store-everything fp64 step"
-    elif workload == "mobilenetv2_b272":
+    elif workload.startswith("mobilenetv2_b272"):
         batch = 16
         g = graphs.mobilenet_v2(batch=batch)
         sample = "same MobileNetV2 graph at batch 16 (224x224), one store-everything fp64 step"

@@ -276,3 +276,28 @@ def block_output_schedule(g: Graph, variants=None, blocks=None):
             if g.is_aux(d) and g.nodes[d - 1].ins[0] in F:
                 F.add(d)
     return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True), conv_algo=variants.get("conv_fwd", "igemm"))
+
+
+def block_checkpoint_schedule(g: Graph, keep, variants=None):
+    """Segment rule: blocks whose index is in `keep` hold what their backward reads, the others are recomputed."""
+    variants = DEFAULT_VARIANTS if variants is None else variants
+    bimpl = choose_bimpls(g, variants)
+    F = block_checkpoint_set(g, bimpl, set(keep))
+    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True), conv_algo=variants.get("conv_fwd", "igemm"))
+
+
+def vgg_alternate_schedule(g: Graph, variants=None):
+    """VGG: every second convolution triple of a stage is recomputed (blocks named s<stage>c<index>)."""
+    keep = {i for i, (name, _) in enumerate(g.blocks) if not (name.startswith("s") and int(name.split("c")[1]) % 2 == 1)}
+    return block_checkpoint_schedule(g, keep, variants)
+
+
+def unet_skip_schedule(g: Graph, variants=None):
+    """UNet: the forward pass keeps the skip tensors (outputs of the down blocks) only."""
+    return block_output_schedule(g, variants, blocks={i for i, (name, _) in enumerate(g.blocks) if name.startswith("down")})
+
+
+def mobilenet_depthwise_schedule(g: Graph, variants=None):
+    """MobileNetV2: the depthwise triples (blocks named *.dw) are recomputed, everything else is kept."""
+    keep = {i for i, (name, _) in enumerate(g.blocks) if not name.endswith(".dw")}
+    return block_checkpoint_schedule(g, keep, variants)
