@@ -12,6 +12,8 @@ namespace monet {
 
 namespace {
 
+typedef float f4 __attribute__((ext_vector_type(4)));
+
 struct BnGeom {
     int C4;      // float4 column groups
     int TPR;     // threads that share a row
@@ -53,14 +55,31 @@ __global__ __launch_bounds__(256) void bn_stats_partial(const float *__restrict_
     const int64_t r1 = r0 + slab < rows ? r0 + slab : rows;
     float pv[4] = {0, 0, 0, 0}, s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0};
     float n = 0;
-    if (cg < C4) {
-        for (int64_t r = r0 + tr; r < r1; r += RPP) {
-            float4 v = ((const float4 *)x)[r * C4 + cg];
-            float vv[4] = {v.x, v.y, v.z, v.w};
-            if (n == 0) {
+    if (cg < C4 && r0 + tr < r1) {
+        // pivot = the thread's first element; rows are then taken four at a time so that four loads are in flight
+        const f4 *xp = (const f4 *)x + cg;
+        const f4 p = __builtin_nontemporal_load(xp + (r0 + tr) * C4);
+        pv[0] = p.x; pv[1] = p.y; pv[2] = p.z; pv[3] = p.w;
+        int64_t r = r0 + tr;
+        for (; r + 3 * RPP < r1; r += 4 * RPP) {
+            f4 v[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) pv[j] = vv[j];
+            for (int u = 0; u < 4; ++u) v[u] = __builtin_nontemporal_load(xp + (r + u * RPP) * C4);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float d = vv[j] - pv[j];
+                    s1[j] += d;
+                    s2[j] += d * d;
+                }
             }
+            n += 4;
+        }
+        for (; r < r1; r += RPP) {
+            const f4 v = __builtin_nontemporal_load(xp + r * C4);
+            float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float d = vv[j] - pv[j];
@@ -108,32 +127,45 @@ __global__ __launch_bounds__(256) void bn_stats_partial(const float *__restrict_
     }
 }
 
-// Block = 16 channels x 16 slab lanes.  Lane sl merges slabs sl, sl+16, ... in order, then the 16
-// lanes of a channel are merged by a fixed tree.
+// Block = FIN_CH channels x FIN_LANES slab lanes.  Lane sl merges slabs sl, sl+FIN_LANES, ... in order,
+// then the lanes of a channel are merged by a fixed tree.  Few channels per block and many lanes keep
+// the dependent chain per thread short: these kernels are latency-bound, not bandwidth-bound.
+constexpr int FIN_CH = 4, FIN_LANES = 64;
 __global__ __launch_bounds__(256) void bn_stats_final(const float *__restrict__ part, float *__restrict__ stats, int64_t rows,
                                                       int C, int G, int64_t slab, float eps) {
     __shared__ float sh_n[256], sh_mean[256], sh_m2[256];
-    const int cl = threadIdx.x & 15, sl = threadIdx.x >> 4;
-    const int c = blockIdx.x * 16 + cl;
+    const int cl = threadIdx.x & (FIN_CH - 1), sl = threadIdx.x / FIN_CH;
+    const int c = blockIdx.x * FIN_CH + cl;
     float n = 0, mean = 0, m2 = 0;
     if (c < C) {
-        for (int g = sl; g < G; g += 16) {
-            int64_t r0 = (int64_t)g * slab;
-            int64_t cnt = r0 + slab < rows ? slab : rows - r0;
-            if (cnt <= 0) break;
-            float nb = (float)cnt;
-            float mb = part[((int64_t)g * C + c) * 2 + 0], qb = part[((int64_t)g * C + c) * 2 + 1];
-            float nt = n + nb, d = mb - mean;
-            mean = n > 0 ? mean + d * (nb / nt) : mb;
-            m2 = m2 + qb + (n > 0 ? d * d * (n * nb / nt) : 0.0f);
-            n = nt;
+        // loads of four slabs are issued together, then merged in slab order
+        for (int g0 = sl; g0 < G; g0 += 4 * FIN_LANES) {
+            float mb[4], qb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * FIN_LANES;
+                const float2 p = g < G ? *(const float2 *)(part + ((int64_t)g * C + c) * 2) : make_float2(0, 0);
+                mb[u] = p.x; qb[u] = p.y;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * FIN_LANES;
+                const int64_t r0 = (int64_t)g * slab;
+                const int64_t cnt = g < G ? (r0 + slab < rows ? slab : rows - r0) : 0;
+                if (cnt <= 0) continue;
+                float nb = (float)cnt;
+                float nt = n + nb, d = mb[u] - mean;
+                mean = n > 0 ? mean + d * (nb / nt) : mb[u];
+                m2 = m2 + qb[u] + (n > 0 ? d * d * (n * nb / nt) : 0.0f);
+                n = nt;
+            }
         }
     }
     sh_n[threadIdx.x] = n; sh_mean[threadIdx.x] = mean; sh_m2[threadIdx.x] = m2;
     __syncthreads();
-    for (int half = 8; half > 0; half >>= 1) {
+    for (int half = FIN_LANES / 2; half > 0; half >>= 1) {
         if (sl < half) {
-            int a = threadIdx.x, b = (sl + half) * 16 + cl;
+            int a = threadIdx.x, b = (sl + half) * FIN_CH + cl;
             float na = sh_n[a], nb = sh_n[b], nt = na + nb;
             if (nb > 0) {
                 float ma = sh_mean[a], mb = sh_mean[b], d = mb - ma;
@@ -155,7 +187,7 @@ void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C,
     if (rows <= 0) throw KernelError("BatchNorm: no rows");
     BnGeom g = bn_geom(rows, C, (int64_t)(scratch_bytes / 4), 2);
     hipLaunchKernelGGL(bn_stats_partial, dim3(g.G, g.CB), dim3(256), 0, st, x, scratch, rows, C, g.TPR, g.slab);
-    hipLaunchKernelGGL(bn_stats_final, dim3((C + 15) / 16), dim3(256), 0, st, (const float *)scratch, stats, rows, C, g.G, g.slab, eps);
+    hipLaunchKernelGGL(bn_stats_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, stats, rows, C, g.G, g.slab, eps);
     hip_check(hipGetLastError(), "bn_stats launch");
 }
 
@@ -163,12 +195,12 @@ void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C,
 __global__ __launch_bounds__(256) void bn_apply_kernel(const float *x, float *y, const float *__restrict__ gamma,
                                                        const float *__restrict__ beta, const float *__restrict__ stats,
                                                        int64_t total4, int C) {
+    // One contiguous range per workgroup (a multiple of 256 float4, so a thread keeps its channel group
+    // whenever C/4 divides 256), four float4 per thread in flight, streaming loads and stores.
+    constexpr int U = 4;
     const int C4 = C / 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool fixed = (stride % C4) == 0;     // then every element this thread visits has the same channels
+    const bool fixed = (256 % C4) == 0;
     float a[4], b[4];
-    int cg = (int)(i % C4);
     auto load_ab = [&](int g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -178,21 +210,36 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float *x, float *y,
             b[j] = beta[c] - stats[c] * s;
         }
     };
-    if (fixed) load_ab(cg);
-    for (; i < total4; i += stride) {
-        if (!fixed) load_ab((int)(i % C4));
-        float4 v = ((const float4 *)x)[i];
-        ((float4 *)y)[i] = make_float4(v.x * a[0] + b[0], v.y * a[1] + b[1], v.z * a[2] + b[2], v.w * a[3] + b[3]);
+    const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const int64_t r0 = (int64_t)blockIdx.x * per;
+    const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
+    if (fixed) load_ab((int)(threadIdx.x % C4));
+    for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
+        f4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u * 256 < r1) v[u] = __builtin_nontemporal_load((const f4 *)x + base + u * 256);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            if (!fixed) load_ab((int)(i % C4));
+            __builtin_nontemporal_store(f4{v[u].x * a[0] + b[0], v[u].y * a[1] + b[1], v[u].z * a[2] + b[2], v[u].w * a[3] + b[3]}, (f4 *)y + i);
+        }
     }
+}
+
+// one workgroup per 2048 float4 (32 KiB), up to 64 Ki workgroups
+static int stream_grid(int64_t total4) {
+    int64_t want = (total4 + 2047) / 2048;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(want, 65536));
 }
 
 void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, const float *beta, const float *stats, int64_t rows, int C) {
     if (C % 4) throw KernelError("BatchNorm: C must be a multiple of 4");
     int64_t total4 = rows * (C / 4);
     if (total4 <= 0) return;
-    int64_t want = (total4 + 256 * 4 - 1) / (256 * 4);
-    int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, 8192));
-    if (grid > 2) grid &= ~1;   // keep the thread count a multiple of the usual power-of-two channel groups
+    int grid = stream_grid(total4);
     hipLaunchKernelGGL(bn_apply_kernel, dim3(grid), dim3(256), 0, st, x, y, gamma, beta, stats, total4, C);
     hip_check(hipGetLastError(), "bn_apply launch");
 }
@@ -222,10 +269,7 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
             if (FROM_OUT) { sc[j] = 1.0f / gamma[c]; sh[j] = -beta[c] * sc[j]; }
             else { sc[j] = stats[C + c]; sh[j] = -stats[c] * sc[j]; }
         }
-        for (int64_t r = r0 + tr; r < r1; r += RPP) {
-            const int64_t i4 = r * C4 + cg;
-            float4 g = ((const float4 *)dy)[i4];
-            float4 v = ((const float4 *)t)[i4];
+        auto accumulate = [&](const f4 &g, const f4 &v, int64_t i4) {
             float gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w};
             if (mask) {     // the incoming gradient still has to pass a ReLU: keep it where the sign bit is set
                 unsigned bits = (unsigned)(mask[i4 >> 4] >> ((i4 & 15) * 4)) & 15u;
@@ -237,6 +281,19 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
                 sb[j] += gg[j];
                 sg[j] += gg[j] * (vv[j] * sc[j] + sh[j]);
             }
+        };
+        // rows two at a time: four 16-byte loads in flight per thread
+        int64_t r = r0 + tr;
+        for (; r + RPP < r1; r += 2 * RPP) {
+            const int64_t ia = r * C4 + cg, ib = (r + RPP) * C4 + cg;
+            const f4 ga = __builtin_nontemporal_load((const f4 *)dy + ia), va = __builtin_nontemporal_load((const f4 *)t + ia);
+            const f4 gb = __builtin_nontemporal_load((const f4 *)dy + ib), vb = __builtin_nontemporal_load((const f4 *)t + ib);
+            accumulate(ga, va, ia);
+            accumulate(gb, vb, ib);
+        }
+        for (; r < r1; r += RPP) {
+            const int64_t ia = r * C4 + cg;
+            accumulate(__builtin_nontemporal_load((const f4 *)dy + ia), __builtin_nontemporal_load((const f4 *)t + ia), ia);
         }
     }
 #pragma unroll
@@ -266,25 +323,32 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
     }
 }
 
-// Block = 16 channels x 16 slab lanes (lane sl adds slabs sl, sl+16, ... in order, then a fixed
+// Block = FIN_CH channels x FIN_LANES slab lanes (lane sl adds slabs sl, sl+FIN_LANES, ... in order, then a fixed
 // tree); writes dbeta, dgamma and, for the apply pass, coef[c] = dbeta/m, coef[C+c] = dgamma/m
 __global__ __launch_bounds__(256) void bn_bwd_final(const float *__restrict__ part, float *__restrict__ dgamma,
                                                     float *__restrict__ dbeta, float *__restrict__ coef, int64_t rows, int C, int G) {
     __shared__ float sh_b[256], sh_g[256];
-    const int cl = threadIdx.x & 15, sl = threadIdx.x >> 4;
-    const int c = blockIdx.x * 16 + cl;
+    const int cl = threadIdx.x & (FIN_CH - 1), sl = threadIdx.x / FIN_CH;
+    const int c = blockIdx.x * FIN_CH + cl;
     float b = 0, g = 0;
     if (c < C)
-        for (int s = sl; s < G; s += 16) {
-            b += part[((int64_t)s * C + c) * 2 + 0];
-            g += part[((int64_t)s * C + c) * 2 + 1];
+        for (int s0 = sl; s0 < G; s0 += 4 * FIN_LANES) {
+            float2 p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u * FIN_LANES;
+                p[u] = s < G ? *(const float2 *)(part + ((int64_t)s * C + c) * 2) : make_float2(0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (s0 + u * FIN_LANES < G) { b += p[u].x; g += p[u].y; }
         }
     sh_b[threadIdx.x] = b; sh_g[threadIdx.x] = g;
     __syncthreads();
-    for (int half = 8; half > 0; half >>= 1) {
+    for (int half = FIN_LANES / 2; half > 0; half >>= 1) {
         if (sl < half) {
-            sh_b[threadIdx.x] += sh_b[(sl + half) * 16 + cl];
-            sh_g[threadIdx.x] += sh_g[(sl + half) * 16 + cl];
+            sh_b[threadIdx.x] += sh_b[(sl + half) * FIN_CH + cl];
+            sh_g[threadIdx.x] += sh_g[(sl + half) * FIN_CH + cl];
         }
         __syncthreads();
     }
@@ -303,10 +367,10 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
                                                     const float *__restrict__ gamma, const float *__restrict__ beta,
                                                     const float *__restrict__ stats, const float *__restrict__ coef, float *dx,
                                                     int64_t total4, int C) {
+    // same streaming pattern as bn_apply_kernel
+    constexpr int U = 4;
     const int C4 = C / 4;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool fixed = (stride % C4) == 0;
+    const bool fixed = (256 % C4) == 0;
     float sc[4], sh[4], a[4], mb[4], mg[4];
     auto load = [&](int g) {
 #pragma unroll
@@ -319,24 +383,40 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
             mg[j] = coef[C + c];
         }
     };
-    if (fixed) load((int)(i % C4));
-    for (; i < total4; i += stride) {
-        if (!fixed) load((int)(i % C4));
-        float4 g = ((const float4 *)dy)[i];
-        float4 v = ((const float4 *)t)[i];
-        float gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w}, r[4];
-        if (mask) {
-            unsigned bits = (unsigned)(mask[i >> 4] >> ((i & 15) * 4)) & 15u;
+    const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const int64_t r0 = (int64_t)blockIdx.x * per;
+    const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
+    if (fixed) load((int)(threadIdx.x % C4));
+    for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
+        f4 g[U], v[U], o[U];
+        unsigned bits[U];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) gg[j] = (bits >> j) & 1 ? gg[j] : 0.0f;
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            g[u] = __builtin_nontemporal_load((const f4 *)dy + i);
+            v[u] = __builtin_nontemporal_load((const f4 *)t + i);
+            if (ACC) o[u] = __builtin_nontemporal_load((const f4 *)dx + i);
+            if (mask) bits[u] = (unsigned)(mask[i >> 4] >> ((i & 15) * 4)) & 15u;
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float xh = vv[j] * sc[j] + sh[j];
-            r[j] = a[j] * (gg[j] - mb[j] - xh * mg[j]);
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            if (!fixed) load((int)(i % C4));
+            float gg[4] = {g[u].x, g[u].y, g[u].z, g[u].w}, vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, r[4];
+            if (mask) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gg[j] = (bits[u] >> j) & 1 ? gg[j] : 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float xh = vv[j] * sc[j] + sh[j];
+                r[j] = a[j] * (gg[j] - mb[j] - xh * mg[j]);
+            }
+            if (ACC) { r[0] += o[u].x; r[1] += o[u].y; r[2] += o[u].z; r[3] += o[u].w; }
+            __builtin_nontemporal_store(f4{r[0], r[1], r[2], r[3]}, (f4 *)dx + i);
         }
-        if (ACC) { float4 o = ((float4 *)dx)[i]; r[0] += o.x; r[1] += o.y; r[2] += o.z; r[3] += o.w; }
-        ((float4 *)dx)[i] = make_float4(r[0], r[1], r[2], r[3]);
     }
 }
 
@@ -349,11 +429,9 @@ void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, c
     float *coef = scratch + (int64_t)g.G * C * 2;
     if (from_output) hipLaunchKernelGGL((bn_bwd_partial<true>), dim3(g.G, g.CB), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
     else hipLaunchKernelGGL((bn_bwd_partial<false>), dim3(g.G, g.CB), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
-    hipLaunchKernelGGL(bn_bwd_final, dim3((C + 15) / 16), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
+    hipLaunchKernelGGL(bn_bwd_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
     int64_t total4 = rows * (C / 4);
-    int64_t want = (total4 + 256 * 4 - 1) / (256 * 4);
-    int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, 8192));
-    if (grid > 2) grid &= ~1;
+    int grid = stream_grid(total4);
 #define BA(F, A) hipLaunchKernelGGL((bn_bwd_apply<F, A>), dim3(grid), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, (const float *)coef, dx, total4, C)
     if (from_output) { if (accumulate) BA(true, true); else BA(true, false); }
     else             { if (accumulate) BA(false, true); else BA(false, false); }

@@ -122,15 +122,34 @@ void relu_bwd(hipStream_t st, const float *dz, const void *t, int mode, float *d
 // ------------------------------------------------------------------ add / copy / fill
 template <int OP>   // 0: y = a + b, 1: y = a, 2: y += a
 __global__ __launch_bounds__(256) void ew_kernel(const float *__restrict__ a, const float *__restrict__ b, float *y, int64_t n) {
+    // one contiguous range per workgroup, four 16-byte pieces per thread in flight, streaming loads and
+    // stores (the measured fastest form of a plain copy on this chip: about 6 TB/s read + write at 1 GiB)
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    constexpr int U = 4;
     const int64_t n4 = n / 4;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        float4 va = ((const float4 *)a)[i];
-        float4 r;
-        if (OP == 0) { float4 vb = ((const float4 *)b)[i]; r = make_float4(va.x + vb.x, va.y + vb.y, va.z + vb.z, va.w + vb.w); }
-        else if (OP == 1) r = va;
-        else { float4 vy = ((float4 *)y)[i]; r = make_float4(vy.x + va.x, vy.y + va.y, vy.z + va.z, vy.w + va.w); }
-        ((float4 *)y)[i] = r;
+    const int64_t per = ((n4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const int64_t r0 = (int64_t)blockIdx.x * per;
+    const int64_t r1 = r0 + per < n4 ? r0 + per : n4;
+    for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
+        f4 va[U], vb[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            va[u] = __builtin_nontemporal_load((const f4 *)a + i);
+            if (OP == 0) vb[u] = __builtin_nontemporal_load((const f4 *)b + i);
+            if (OP == 2) vb[u] = __builtin_nontemporal_load((const f4 *)y + i);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            f4 r = va[u];
+            if (OP == 0) r = va[u] + vb[u];
+            if (OP == 2) r = vb[u] + va[u];
+            __builtin_nontemporal_store(r, (f4 *)y + i);
+        }
     }
     for (int64_t i = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         if (OP == 0) y[i] = a[i] + b[i];
@@ -141,13 +160,13 @@ __global__ __launch_bounds__(256) void ew_kernel(const float *__restrict__ a, co
 
 void add_fwd(hipStream_t st, const float *a, const float *b, float *y, int64_t n) {
     if (n <= 0) return;
-    hipLaunchKernelGGL((ew_kernel<0>), dim3(grid_for(n, 1024, 16384)), dim3(256), 0, st, a, b, y, n);
+    hipLaunchKernelGGL((ew_kernel<0>), dim3(grid_for(n, 8192, 65536)), dim3(256), 0, st, a, b, y, n);
     hip_check(hipGetLastError(), "add_fwd launch");
 }
 
 void copy_or_accumulate(hipStream_t st, const float *src, float *dst, int64_t n, bool accumulate) {
     if (n <= 0) return;
-    int grid = grid_for(n, 1024, 16384);
+    int grid = grid_for(n, 8192, 65536);
     if (accumulate) hipLaunchKernelGGL((ew_kernel<2>), dim3(grid), dim3(256), 0, st, src, (const float *)nullptr, dst, n);
     else hipLaunchKernelGGL((ew_kernel<1>), dim3(grid), dim3(256), 0, st, src, (const float *)nullptr, dst, n);
     hip_check(hipGetLastError(), "copy launch");

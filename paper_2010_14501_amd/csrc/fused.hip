@@ -14,6 +14,8 @@ namespace monet {
 
 namespace {
 
+typedef float f4 __attribute__((ext_vector_type(4)));
+
 // spreads the low 16 bits of x to bit positions 0, 4, 8, ..., 60
 __device__ inline uint64_t spread16(uint64_t x) {
     x &= 0xFFFFull;
@@ -31,10 +33,13 @@ template <bool BN, bool ADD, bool PRE_OUT, bool SIX, bool MASK>
 __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const float *x2, const float *__restrict__ gamma,
                                                         const float *__restrict__ beta, const float *__restrict__ stats, int C,
                                                         float *out_pre, float *out, uint64_t *__restrict__ mask, int64_t total4) {
+    // Each workgroup streams one contiguous range (a multiple of 256 float4, so that wave boundaries fall
+    // on mask words and a thread's channel group stays fixed whenever C/4 divides 256), four float4 per
+    // thread in flight, streaming (non-temporal) loads and stores: tensors here are far larger than any cache.
+    constexpr int U = 4;
     const int lane = threadIdx.x & 63;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int C4 = BN ? C / 4 : 1;
-    const bool fixed = BN && (stride % C4) == 0;
+    const bool fixed = BN && (256 % C4) == 0;
     float a[4] = {1, 1, 1, 1}, b[4] = {0, 0, 0, 0};
     auto load_ab = [&](int g) {
 #pragma unroll
@@ -45,46 +50,59 @@ __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const fl
             b[j] = beta[c] - stats[c] * s;
         }
     };
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (BN && fixed) load_ab((int)(i % C4));
-    for (; i - lane < total4; i += stride) {      // i - lane is the wave's first index: the trip count is wave-uniform
-        const bool valid = i < total4;
-        float4 v = make_float4(0, 0, 0, 0);
-        if (valid) {
-            v = ((const float4 *)x)[i];
-            if (ADD) { float4 w = ((const float4 *)x2)[i]; v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w; }
-            if (BN) {
-                if (!fixed) load_ab((int)(i % C4));
-                v.x = v.x * a[0] + b[0]; v.y = v.y * a[1] + b[1]; v.z = v.z * a[2] + b[2]; v.w = v.w * a[3] + b[3];
-            }
-            if (PRE_OUT) ((float4 *)out_pre)[i] = v;
-        }
-        float e[4] = {v.x, v.y, v.z, v.w}, r[4];
-        bool pass[4];
+    const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const int64_t r0 = (int64_t)blockIdx.x * per;
+    const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
+    if (BN && fixed) load_ab((int)(threadIdx.x % C4));
+    for (int64_t base = r0 + threadIdx.x; base - lane < r1; base += U * 256) {      // base - lane: wave-uniform trip count
+        f4 v[U];
+        bool valid[U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            pass[j] = valid && (SIX ? (e[j] > 0.0f && e[j] < 6.0f) : (e[j] > 0.0f));
-            r[j] = e[j] > 0.0f ? e[j] : 0.0f;
-            if (SIX) r[j] = r[j] < 6.0f ? r[j] : 6.0f;
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            valid[u] = i < r1;
+            v[u] = f4{0, 0, 0, 0};
+            if (valid[u]) {
+                v[u] = __builtin_nontemporal_load((const f4 *)x + i);
+                if (ADD) v[u] += __builtin_nontemporal_load((const f4 *)x2 + i);
+            }
         }
-        if (valid) ((float4 *)out)[i] = make_float4(r[0], r[1], r[2], r[3]);
-        if (MASK) {
-            uint64_t b0 = __ballot(pass[0]), b1 = __ballot(pass[1]), b2 = __ballot(pass[2]), b3 = __ballot(pass[3]);
-            if (lane < 4) {
-                int sh = 16 * lane;
-                uint64_t word = spread16(b0 >> sh) | (spread16(b1 >> sh) << 1) | (spread16(b2 >> sh) << 2) | (spread16(b3 >> sh) << 3);
-                int64_t first4 = i - lane + 16 * lane;          // first float4 index covered by this word
-                if (first4 < total4) mask[(i - lane) / 16 + lane] = word;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i - lane >= r1) break;                                                // whole wave beyond the range
+            if (valid[u] && BN) {
+                if (!fixed) load_ab((int)(i % C4));
+                v[u].x = v[u].x * a[0] + b[0]; v[u].y = v[u].y * a[1] + b[1]; v[u].z = v[u].z * a[2] + b[2]; v[u].w = v[u].w * a[3] + b[3];
+            }
+            if (valid[u] && PRE_OUT) __builtin_nontemporal_store(v[u], (f4 *)out_pre + i);
+            float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, r[4];
+            bool pass[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                pass[j] = valid[u] && (SIX ? (e[j] > 0.0f && e[j] < 6.0f) : (e[j] > 0.0f));
+                r[j] = e[j] > 0.0f ? e[j] : 0.0f;
+                if (SIX) r[j] = r[j] < 6.0f ? r[j] : 6.0f;
+            }
+            if (valid[u]) __builtin_nontemporal_store(f4{r[0], r[1], r[2], r[3]}, (f4 *)out + i);
+            if (MASK) {
+                uint64_t b0 = __ballot(pass[0]), b1 = __ballot(pass[1]), b2 = __ballot(pass[2]), b3 = __ballot(pass[3]);
+                if (lane < 4) {
+                    int sh = 16 * lane;
+                    uint64_t word = spread16(b0 >> sh) | (spread16(b1 >> sh) << 1) | (spread16(b2 >> sh) << 2) | (spread16(b3 >> sh) << 3);
+                    int64_t first4 = i - lane + 16 * lane;          // first float4 index covered by this word
+                    if (first4 < total4) mask[(i - lane) / 16 + lane] = word;
+                }
             }
         }
     }
 }
 
+// one workgroup per 2048 float4 (32 KiB) up to 64 Ki workgroups: many short contiguous streams measured
+// fastest for a plain copy on this chip
 int chain_grid(int64_t total4) {
-    int64_t want = (total4 + 256 * 4 - 1) / (256 * 4);
-    int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, 8192));
-    if (grid > 2) grid &= ~1;
-    return grid;
+    int64_t want = (total4 + 2047) / 2048;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(want, 65536));
 }
 
 }  // namespace
@@ -119,33 +137,47 @@ namespace {
 template <int MODE, bool SIX>
 __global__ __launch_bounds__(256) void relu_bwd_fanout_kernel(const float *__restrict__ dz, const void *__restrict__ t, float *d0, int acc0,
                                                               float *d1, int acc1, int64_t total4) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total4; i += stride) {
-        float4 g = ((const float4 *)dz)[i];
-        float gg[4] = {g.x, g.y, g.z, g.w}, r[4];
-        if (MODE == RELU_FROM_MASK) {
-            uint64_t word = ((const uint64_t *)t)[i >> 4];
-            unsigned bits = (unsigned)(word >> ((i & 15) * 4)) & 15u;
+    // contiguous range per workgroup, four float4 per thread in flight, streaming loads and stores
+    constexpr int U = 4;
+    const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const int64_t r0 = (int64_t)blockIdx.x * per;
+    const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
+    for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
+        f4 g[U], f[U], p0[U], p1[U];
+        unsigned bits[U];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) r[j] = (bits >> j) & 1 ? gg[j] : 0.0f;
-        } else {
-            float4 f = ((const float4 *)t)[i];
-            float ff[4] = {f.x, f.y, f.z, f.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                bool pass = SIX ? (ff[j] > 0.0f && ff[j] < 6.0f) : (ff[j] > 0.0f);
-                r[j] = pass ? gg[j] : 0.0f;
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            g[u] = __builtin_nontemporal_load((const f4 *)dz + i);
+            if (MODE == RELU_FROM_MASK) {
+                uint64_t word = ((const uint64_t *)t)[i >> 4];
+                bits[u] = (unsigned)(word >> ((i & 15) * 4)) & 15u;
+            } else {
+                f[u] = __builtin_nontemporal_load((const f4 *)t + i);
             }
+            if (d0 && acc0) p0[u] = __builtin_nontemporal_load((const f4 *)d0 + i);
+            if (d1 && acc1) p1[u] = __builtin_nontemporal_load((const f4 *)d1 + i);
         }
-        if (d0) {
-            float4 o = make_float4(r[0], r[1], r[2], r[3]);
-            if (acc0) { float4 p = ((float4 *)d0)[i]; o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w; }
-            ((float4 *)d0)[i] = o;
-        }
-        if (d1) {
-            float4 o = make_float4(r[0], r[1], r[2], r[3]);
-            if (acc1) { float4 p = ((float4 *)d1)[i]; o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w; }
-            ((float4 *)d1)[i] = o;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = base + u * 256;
+            if (i >= r1) continue;
+            float gg[4] = {g[u].x, g[u].y, g[u].z, g[u].w}, r[4];
+            if (MODE == RELU_FROM_MASK) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = (bits[u] >> j) & 1 ? gg[j] : 0.0f;
+            } else {
+                float ff[4] = {f[u].x, f[u].y, f[u].z, f[u].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    bool pass = SIX ? (ff[j] > 0.0f && ff[j] < 6.0f) : (ff[j] > 0.0f);
+                    r[j] = pass ? gg[j] : 0.0f;
+                }
+            }
+            const f4 o = f4{r[0], r[1], r[2], r[3]};
+            if (d0) __builtin_nontemporal_store(acc0 ? o + p0[u] : o, (f4 *)d0 + i);
+            if (d1) __builtin_nontemporal_store(acc1 ? o + p1[u] : o, (f4 *)d1 + i);
         }
     }
 }
