@@ -54,6 +54,11 @@ __global__ __launch_bounds__(256) void relu_fwd_kernel(const float *x, float *y,
 
 void relu_fwd(hipStream_t st, const float *x, float *y, uint64_t *mask, int64_t n, bool six) {
     if (n <= 0) return;
+    // whole float4s: the 16-byte streaming kernel (same predicate, same mask words); this one takes the rest
+    if (n % 4 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)y % 16) == 0) {
+        fwd_chain(st, x, nullptr, nullptr, nullptr, nullptr, 0, nullptr, y, mask, n, six);
+        return;
+    }
     constexpr int U = 8;
     int grid = grid_for(n, 256 * U, 16384);
 #define RL(SIX, MASK) hipLaunchKernelGGL((relu_fwd_kernel<U, SIX, MASK>), dim3(grid), dim3(256), 0, st, x, y, mask, n)
@@ -102,6 +107,11 @@ __global__ __launch_bounds__(256) void relu_bwd_kernel(const float *__restrict__
 
 void relu_bwd(hipStream_t st, const float *dz, const void *t, int mode, float *dx, int64_t n, bool six, bool accumulate) {
     if (n <= 0) return;
+    if (n % 4 == 0 && ((uintptr_t)dz % 16) == 0 && ((uintptr_t)dx % 16) == 0 && ((uintptr_t)t % 16) == 0 &&
+        (mode == RELU_FROM_MASK || mode == RELU_FROM_INPUT || mode == RELU_FROM_OUTPUT)) {
+        relu_bwd_fanout(st, dz, t, mode, dx, accumulate, nullptr, false, n, six);
+        return;
+    }
     constexpr int U = 8;
     int grid = grid_for(n, 256 * U, 16384);
 #define RB(MODE, SIX, ACC) hipLaunchKernelGGL((relu_bwd_kernel<U, MODE, SIX, ACC>), dim3(grid), dim3(256), 0, st, dz, t, dx, n)
