@@ -173,14 +173,216 @@ __global__ __launch_bounds__(256) void dw_wgrad_partial(const float *__restrict_
     }
 }
 
-// dw[c][tap] = sum over slabs, slab order
+// dw[c][tap] = sum over slabs.  Block = 4 outputs (consecutive channels of one tap) x 64 slab lanes: lane l
+// adds slabs l, l+64, ... in order (four loads in flight), then the lanes are added by a fixed tree.  A
+// single thread per output would be a chain of `slabs` dependent loads.
 __global__ __launch_bounds__(256) void dw_wgrad_final(const float *__restrict__ part, float *__restrict__ dw, int C, int taps, int slabs) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;   // over tap-major (tap, c)
-    if (i >= C * taps) return;
-    const int tp = i / C, c = i - tp * C;
+    __shared__ float sh[256];
+    const int ol = threadIdx.x & 3, sl = threadIdx.x >> 2;
+    const int i = blockIdx.x * 4 + ol;                      // over tap-major (tap, c)
+    const bool live = i < C * taps;
+    const int tp = live ? i / C : 0, c = live ? i - tp * C : 0;
     float s = 0;
-    for (int b = 0; b < slabs; ++b) s += part[((size_t)b * taps + tp) * C + c];
-    dw[c * taps + tp] = s;
+    if (live)
+        for (int b0 = sl; b0 < slabs; b0 += 4 * 64) {
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = b0 + u * 64;
+                v[u] = b < slabs ? part[((size_t)b * taps + tp) * C + c] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (b0 + u * 64 < slabs) s += v[u];
+        }
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int half = 32; half > 0; half >>= 1) {
+        if (sl < half) sh[threadIdx.x] += sh[(sl + half) * 4 + ol];
+        __syncthreads();
+    }
+    if (sl == 0 && live) dw[c * taps + tp] = sh[ol];
+}
+
+// ------------------------------------------------------------------ 3x3 filters, C % 4 == 0
+// The common case, with the tap loops unrolled at compile time: all nine 16-byte loads of a thread are
+// issued before the first multiply-add (out-of-range taps load the image's first pixel and are zeroed),
+// and no integer division is left in the inner loop.
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void dw3_fwd_kernel(const float *__restrict__ x, const float *__restrict__ w, float *__restrict__ y,
+                                                      ConvShape cs, int64_t pix_per_block) {
+    // blockDim = (CL, 256 / CL): x = channel group, y = pixel lane; a block owns the pixel range
+    // [blockIdx.x * pix_per_block, ...) and steps through it without divisions
+    extern __shared__ float wl[];
+    const int C = cs.C, C4 = C / 4;
+    {   // filters: all threads of the 2-D block take part
+        const int tid = threadIdx.y * blockDim.x + threadIdx.x;
+        for (int i = tid; i < C * 9; i += 256) {
+            int c = i / 9, t = i - c * 9;
+            wl[t * C + c] = w[i];
+        }
+        __syncthreads();
+    }
+    const int CL = blockDim.x, PL = blockDim.y;
+    const int cv = blockIdx.y * CL + threadIdx.x;
+    if (cv >= C4) return;
+    const int64_t M = cs.M();
+    const int64_t p0 = (int64_t)blockIdx.x * pix_per_block;
+    const int64_t p1 = p0 + pix_per_block < M ? p0 + pix_per_block : M;
+    int64_t pix = p0 + threadIdx.y;
+    if (pix >= p1) return;
+    int q = (int)(pix % cs.Q);
+    int64_t t2 = pix / cs.Q;
+    int p = (int)(t2 % cs.P);
+    int n = (int)(t2 / cs.P);
+    f4 wv[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) wv[t] = *(const f4 *)(wl + t * C + cv * 4);
+    for (; pix < p1; pix += PL) {
+        const int h0 = p * cs.stride - cs.pad, v0 = q * cs.stride - cs.pad;
+        const f4 *xn = (const f4 *)x + (int64_t)n * cs.H * cs.W * C4 + cv;
+        f4 xv[9];
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int h = h0 + r, v = v0 + s;
+                const bool ok = (unsigned)h < (unsigned)cs.H && (unsigned)v < (unsigned)cs.W;
+                const f4 t = xn[ok ? (h * cs.W + v) * C4 : 0];
+                xv[r * 3 + s] = ok ? t : f4{0, 0, 0, 0};
+            }
+        f4 acc = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc += xv[t] * wv[t];
+        ((f4 *)y)[pix * C4 + cv] = acc;
+        q += PL;
+        while (q >= cs.Q) { q -= cs.Q; if (++p == cs.P) { p = 0; ++n; } }
+    }
+}
+
+template <bool ACC>
+__global__ __launch_bounds__(256) void dw3_dgrad_kernel(const float *__restrict__ dy, const float *__restrict__ w, float *dx, ConvShape cs,
+                                                        int64_t pix_per_block) {
+    // same block shape and stepping as dw3_fwd_kernel, over the pixels of dx
+    extern __shared__ float wl[];
+    const int C = cs.C, C4 = C / 4, st = cs.stride;
+    {
+        const int tid = threadIdx.y * blockDim.x + threadIdx.x;
+        for (int i = tid; i < C * 9; i += 256) {
+            int c = i / 9, t = i - c * 9;
+            wl[t * C + c] = w[i];
+        }
+        __syncthreads();
+    }
+    const int CL = blockDim.x, PL = blockDim.y;
+    const int cv = blockIdx.y * CL + threadIdx.x;
+    if (cv >= C4) return;
+    const int64_t M = (int64_t)cs.N * cs.H * cs.W;
+    const int64_t p0 = (int64_t)blockIdx.x * pix_per_block;
+    const int64_t p1 = p0 + pix_per_block < M ? p0 + pix_per_block : M;
+    int64_t pix = p0 + threadIdx.y;
+    if (pix >= p1) return;
+    int v = (int)(pix % cs.W);
+    int64_t t2 = pix / cs.W;
+    int h = (int)(t2 % cs.H);
+    int n = (int)(t2 / cs.H);
+    f4 wv[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) wv[t] = *(const f4 *)(wl + t * C + cv * 4);
+    for (; pix < p1; pix += PL) {
+        const f4 *gn = (const f4 *)dy + (int64_t)n * cs.P * cs.Q * C4 + cv;
+        f4 gv[9];
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int hp = h + cs.pad - r, vq = v + cs.pad - s;
+                const int p = st == 1 ? hp : (st == 2 ? hp >> 1 : hp / st), q = st == 1 ? vq : (st == 2 ? vq >> 1 : vq / st);
+                const bool ok = hp >= 0 && vq >= 0 && p * st == hp && q * st == vq && p < cs.P && q < cs.Q;
+                const f4 t = gn[ok ? (p * cs.Q + q) * C4 : 0];
+                gv[r * 3 + s] = ok ? t : f4{0, 0, 0, 0};
+            }
+        f4 acc = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc += gv[t] * wv[t];
+        f4 *d = (f4 *)dx + pix * C4 + cv;
+        if (ACC) acc += *d;
+        *d = acc;
+        v += PL;
+        while (v >= cs.W) { v -= cs.W; if (++h == cs.H) { h = 0; ++n; } }
+    }
+}
+
+// blockDim = (CL, 256 / CL) as in dw_wgrad_partial; part[slab][tap][C]
+__global__ __launch_bounds__(256) void dw3_wgrad_partial(const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part,
+                                                         ConvShape cs, int64_t pix_per_slab) {
+    extern __shared__ float red[];   // [blockDim.y][9][CL * 4]
+    const int C = cs.C, C4 = C / 4;
+    const int CL = blockDim.x, PL = blockDim.y;
+    const int cv = blockIdx.y * CL + threadIdx.x;
+    const bool live = cv < C4;
+    f4 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = f4{0, 0, 0, 0};
+    const int64_t M = cs.M();
+    const int64_t p0 = blockIdx.x * pix_per_slab;
+    const int64_t p1 = p0 + pix_per_slab < M ? p0 + pix_per_slab : M;
+    if (live) {
+        int64_t pix = p0 + threadIdx.y;
+        // position of the thread's first pixel; afterwards advanced by PL pixels without divisions
+        int q = (int)(pix % cs.Q);
+        int64_t t2 = pix / cs.Q;
+        int p = (int)(t2 % cs.P);
+        int n = (int)(t2 / cs.P);
+        for (; pix < p1; pix += PL) {
+            const f4 g = ((const f4 *)dy)[pix * C4 + cv];
+            const f4 *xn = (const f4 *)x + (int64_t)n * cs.H * cs.W * C4 + cv;
+            const int h0 = p * cs.stride - cs.pad, v0 = q * cs.stride - cs.pad;
+            f4 xv[9];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) {
+                    const int h = h0 + r, v = v0 + s;
+                    const bool ok = (unsigned)h < (unsigned)cs.H && (unsigned)v < (unsigned)cs.W;
+                    const f4 t = xn[ok ? ((int64_t)h * cs.W + v) * C4 : 0];
+                    xv[r * 3 + s] = ok ? t : f4{0, 0, 0, 0};
+                }
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc[t] += xv[t] * g;
+            q += PL;
+            while (q >= cs.Q) { q -= cs.Q; if (++p == cs.P) { p = 0; ++n; } }
+        }
+    }
+    const int width = CL * 4;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) *(f4 *)(red + ((size_t)threadIdx.y * 9 + t) * width + threadIdx.x * 4) = acc[t];
+    __syncthreads();
+    // pixel lanes are added in lane order by the 9 * CL threads (tap, channel group) of the block
+    for (int j = threadIdx.y * CL + threadIdx.x; j < 9 * CL; j += CL * PL) {
+        const int t = j / CL, cl = j - t * CL;
+        const int c4 = blockIdx.y * CL + cl;
+        if (c4 >= C4) continue;
+        f4 s = f4{0, 0, 0, 0};
+        for (int l = 0; l < PL; ++l) s += *(const f4 *)(red + ((size_t)l * 9 + t) * width + cl * 4);
+        *(f4 *)(part + ((size_t)blockIdx.x * 9 + t) * C + c4 * 4) = s;
+    }
+}
+
+// block shape of the 3x3 kernels: CL channel groups (power of two, at most 64) x PL pixel lanes, 16 pixels per thread
+struct Dw3Geom { int CL, PL, chunks; unsigned blocks; int64_t pix_per_block; };
+Dw3Geom dw3_geom(int C4, int64_t pixels) {
+    Dw3Geom g;
+    g.CL = 1;
+    while (g.CL < C4 && g.CL < 64) g.CL <<= 1;
+    g.PL = 256 / g.CL;
+    g.chunks = (C4 + g.CL - 1) / g.CL;
+    g.pix_per_block = (int64_t)g.PL * 16;
+    int64_t blocks = (pixels + g.pix_per_block - 1) / g.pix_per_block;
+    if (blocks > 0x7fffffff) throw KernelError("depthwise: too many pixels");
+    g.blocks = (unsigned)std::max<int64_t>(1, blocks);
+    return g;
 }
 
 void check_dw(const ConvShape &cs, const char *who) {
@@ -190,6 +392,8 @@ void check_dw(const ConvShape &cs, const char *who) {
     if (cs.P != (cs.H + 2 * cs.pad - cs.R) / cs.stride + 1 || cs.Q != (cs.W + 2 * cs.pad - cs.S) / cs.stride + 1)
         throw KernelError(std::string(who) + ": output extent does not match the input");
     if ((size_t)cs.C * cs.R * cs.S * 4 > 64 * 1024) throw KernelError(std::string(who) + ": filters do not fit in LDS");
+    if ((int64_t)cs.H * cs.W * cs.C >= (1ll << 31) || (int64_t)cs.P * cs.Q * cs.C >= (1ll << 31))
+        throw KernelError(std::string(who) + ": one image must hold fewer than 2^31 elements");
 }
 
 }  // namespace
@@ -197,7 +401,10 @@ void check_dw(const ConvShape &cs, const char *who) {
 void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs) {
     check_dw(cs, "dwconv_fwd");
     const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
-    if (cs.C % 4 == 0) {
+    if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
+        const Dw3Geom gm = dw3_geom(cs.C / 4, cs.M());
+        hipLaunchKernelGGL(dw3_fwd_kernel, dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, x, w, y, cs, gm.pix_per_block);
+    } else if (cs.C % 4 == 0) {
         int grid = grid_cap(cs.M() * (cs.C / 4), 256, 8192);
         hipLaunchKernelGGL((dw_fwd_kernel<4>), dim3(grid), dim3(256), lds, st, x, w, y, cs);
     } else {
@@ -212,7 +419,11 @@ void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, co
     const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
     const int64_t pixels = (int64_t)cs.N * cs.H * cs.W;
 #define DG(V, ACC) hipLaunchKernelGGL((dw_dgrad_kernel<V, ACC>), dim3(grid), dim3(256), lds, st, dy, w, dx, cs)
-    if (cs.C % 4 == 0) {
+    if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
+        const Dw3Geom gm = dw3_geom(cs.C / 4, pixels);
+        if (accumulate) hipLaunchKernelGGL((dw3_dgrad_kernel<true>), dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, dy, w, dx, cs, gm.pix_per_block);
+        else hipLaunchKernelGGL((dw3_dgrad_kernel<false>), dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, dy, w, dx, cs, gm.pix_per_block);
+    } else if (cs.C % 4 == 0) {
         int grid = grid_cap(pixels * (cs.C / 4), 256, 8192);
         if (accumulate) DG(4, true); else DG(4, false);
     } else {
@@ -234,15 +445,16 @@ void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, co
     const int chunks = (CV + CL - 1) / CL;
     const int64_t M = cs.M();
     const size_t slab_bytes = (size_t)taps * cs.C * 4;
-    int64_t slabs = std::min<int64_t>({(int64_t)1024, (int64_t)(scratch_bytes / slab_bytes), (M + 4 * PL - 1) / (4 * PL)});
+    int64_t slabs = std::min<int64_t>({(int64_t)4096, (int64_t)(scratch_bytes / slab_bytes), (M + 4 * PL - 1) / (4 * PL)});
     if (slabs < 1) throw KernelError("dwconv_wgrad: scratch too small");
     const int64_t pps = (M + slabs - 1) / slabs;
     slabs = (M + pps - 1) / pps;
     const size_t lds = (size_t)PL * taps * CL * V * 4;
     if (lds > 64 * 1024) throw KernelError("dwconv_wgrad: reduction buffer does not fit in LDS");
-    if (V == 4) hipLaunchKernelGGL((dw_wgrad_partial<4>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs, pps);
+    if (V == 4 && cs.R == 3 && cs.S == 3) hipLaunchKernelGGL(dw3_wgrad_partial, dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs, pps);
+    else if (V == 4) hipLaunchKernelGGL((dw_wgrad_partial<4>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs, pps);
     else hipLaunchKernelGGL((dw_wgrad_partial<1>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs, pps);
-    hipLaunchKernelGGL(dw_wgrad_final, dim3((cs.C * taps + 255) / 256), dim3(256), 0, st, (const float *)scratch, dw, cs.C, taps, (int)slabs);
+    hipLaunchKernelGGL(dw_wgrad_final, dim3((cs.C * taps + 3) / 4), dim3(256), 0, st, (const float *)scratch, dw, cs.C, taps, (int)slabs);
     hip_check(hipGetLastError(), "dwconv_wgrad launch");
 }
 
