@@ -38,6 +38,17 @@ def build_workload(name):
             return g, schedules.store_everything_schedule(g), 184, "store everything, standard variants (plain back-propagation)"
         if kind == "store_everything_lean":
             return g, schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS), 184, "store everything the lean variants read"
+        if kind.startswith("budget_"):
+            # block-level greedy search on the measured operator costs, peak budget = fraction of store-everything
+            from workloads import search
+            from paper_2010_14501_amd import costs, monet
+            frac = float(kind[len("budget_"):])
+            tau = costs.read_table(os.path.join(ROOT, "workloads", "measured", "costs_resnet50_b184.txt"))
+            store = monet.Plan(g.text(), schedules.store_everything_schedule(g).text()).exact_peak
+            levels, sch, peak, ms = search.greedy(g, tau, frac * store, monet.Plan)
+            return g, sch, 184, (f"greedy block-level search, budget {frac:.2f} x store-everything peak "
+                                 f"({frac * store / 1e9:.2f} GB); block levels {''.join(map(str, levels))}; "
+                                 f"predicted recomputation {ms:.1f} ms; lean variants")
         raise SystemExit(f"unknown workload {name}")
     lean = "; lean operator variants"
     nets = {"vgg16_b176": (lambda: graphs.vgg16_bn(batch=176), 176, schedules.vgg_alternate_schedule,

@@ -266,8 +266,14 @@ def store_everything_schedule(g: Graph, variants=None):
 
 def block_output_schedule(g: Graph, variants=None, blocks=None):
     """Keep block outputs only; block internals are recomputed in backward."""
+    return schedule_for_saved_set(g, block_output_set(g, blocks), variants)
+
+
+def schedule_for_saved_set(g: Graph, F, variants=None):
+    """Schedule that keeps exactly the forward tensors F (plus the intermediate tensors of kept creators
+    that a backward operator reads) and recomputes everything else it needs."""
     variants = DEFAULT_VARIANTS if variants is None else variants
-    F = block_output_set(g, blocks)
+    F = set(F)
     bimpl = choose_bimpls(g, variants, saved=F)
     # an aux tensor can only be written while its creator runs: where the creator's output is
     # kept, keep the aux tensor its backward reads as well (max-pool window index)
