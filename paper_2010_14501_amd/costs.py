@@ -97,6 +97,7 @@ def main():
     plain = dict(std, conv_wgrad="direct", tconv_wgrad="direct", conv_dgrad="igemm", conv_fwd="igemm",
                  relu_bwd="from_input", relu6_bwd="from_input")
     scheds = [schedules.block_output_schedule(g, lean),            # lean variants + recomputation
+              schedules.store_everything_schedule(g, lean),        # every ReLU backward from its mask
               schedules.store_everything_schedule(g, std),         # standard variants, split convolutions
               schedules.store_everything_schedule(g, plain)]       # workspace-free convolutions, ReLU from input
     tau = measure(g.text(), [s.text() for s in scheds], exts, params, args.steps)
