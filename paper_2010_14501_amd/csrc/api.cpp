@@ -247,7 +247,8 @@ void run_forward(const StepCtx &c, const Launch &L) {
         avgpool_fwd(c.st, in0, out, (int)is[0], (int)(is[1] * is[2]), (int)is[3]);
     } else if (op == "linear") {
         const auto &is = g.shape_of(n.ins[0]);
-        linear_fwd(c.st, in0, c.weights[n.pars[0]], c.weights[n.pars[1]], out, (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1]);
+        linear_fwd(c.st, in0, c.weights[n.pars[0]], c.weights[n.pars[1]], out, (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1],
+                   c.scratch(), c.scratch_bytes());
     } else if (op == "softmaxce") {
         const auto &is = g.shape_of(n.ins[0]);
         const int classes = (int)is.back();
@@ -320,7 +321,8 @@ void run_backward(const StepCtx &c, const Launch &L) {
         linear_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], c.grads[n.pars[1]], (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1]);
     } else if (kd == "linear_dgrad") {
         const auto &is = g.shape_of(n.ins[0]);
-        linear_dgrad(c.st, gy, c.weights[n.pars[0]], d0, (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1], acc0);
+        linear_dgrad(c.st, gy, c.weights[n.pars[0]], d0, (int)is[0], (int)(numel_of(is) / is[0]), (int)n.shape[1], acc0, c.scratch(),
+                     c.scratch_bytes());
     } else if (kd == "softmaxce_bwd") {
         const auto &is = g.shape_of(n.ins[0]);
         Ref lab; lab.region = R_EXT; lab.off = -n.ins[1];
@@ -651,9 +653,19 @@ namespace monet {
 void linear_bias_add(hipStream_t st, float *y, const float *b, int N, int out);
 void linear_bias_grad(hipStream_t st, const float *dy, float *db, int N, int out);
 
-void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out) {
+// A batch of a few hundred rows gives a handful of output tiles: the reduction is cut into ranges (partial
+// results in the caller's scratch, added in range order) until about a thousand workgroups exist.
+static int linear_splits(int64_t rows, int64_t cols, int64_t reduction, int64_t out_elems, size_t scratch_bytes) {
+    int64_t tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
+    int64_t sp = std::min<int64_t>({(1024 + tiles - 1) / tiles, reduction / 128, (int64_t)(scratch_bytes / (4 * out_elems)), (int64_t)64});
+    return (int)std::max<int64_t>(1, sp);
+}
+
+void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out, float *scratch,
+                size_t scratch_bytes) {
     ConvShape cs{N, 1, 1, in, out, 1, 1, 1, 0, 1, 1};
-    conv_fwd(st, x, w, y, cs);
+    const int sp = scratch ? linear_splits(N, out, in, (int64_t)N * out, scratch_bytes) : 1;
+    conv_fwd(st, x, w, y, cs, sp, sp > 1 ? scratch : nullptr, sp > 1 ? scratch_bytes : 0);
     linear_bias_add(st, y, b, N, out);
 }
 void linear_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, float *db, int N, int in, int out) {
@@ -661,9 +673,11 @@ void linear_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, fl
     conv_wgrad(st, x, dy, dw, cs, 1, nullptr, 0);
     linear_bias_grad(st, dy, db, N, out);
 }
-void linear_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, int N, int in, int out, bool accumulate) {
+void linear_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, int N, int in, int out, bool accumulate, float *scratch,
+                  size_t scratch_bytes) {
     ConvShape cs{N, 1, 1, in, out, 1, 1, 1, 0, 1, 1};
-    conv_dgrad(st, dy, w, dx, cs, accumulate);
+    const int sp = scratch ? linear_splits(N, in, out, (int64_t)N * in, scratch_bytes) : 1;
+    conv_dgrad(st, dy, w, dx, cs, accumulate, sp, sp > 1 ? scratch : nullptr, sp > 1 ? scratch_bytes : 0);
 }
 
 }  // namespace monet

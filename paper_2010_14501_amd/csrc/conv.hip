@@ -65,11 +65,12 @@ struct TileArgs {
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
 template <int MODE, int WM, int WN, bool FAST>
-__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 ? 4 : 2)) void conv_tile_kernel(TileArgs ta) {
-    // Four-wave tiles run four workgroups per CU (4 x 40 KiB of LDS, 128 registers per lane) and prefetch one
-    // reduction step; the smaller tiles keep two register stages (loads two steps ahead) at two waves per SIMD.
-    // Measured on the ResNet-50 layer set: 4 waves / 1 stage beats 3 waves / 2 stages by 2-3 %.
-    constexpr int STAGES = (WM * WN == 4) ? 1 : 2;
+__global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN == 4 ? 3 : 2))) void conv_tile_kernel(TileArgs ta) {
+    // The square four-wave tile runs four workgroups per CU (4 x 40 KiB of LDS, 128 registers per lane) and
+    // prefetches one reduction step; the other tiles keep two register stages (loads two steps ahead) at three
+    // (256x64, 64x256: 50 KiB of LDS) or two waves per SIMD.  Measured on the ResNet-50 layer set: 4 waves /
+    // 1 stage beats 3 waves / 2 stages by 2-3 % for the square tile.
+    constexpr int STAGES = (WM == 2 && WN == 2) ? 1 : 2;
     constexpr int BM = 64 * WM, BN = 64 * WN, NT = 64 * WM * WN;
     constexpr bool A_KC = (MODE != WGRAD);          // A operand reduction-contiguous?
     constexpr bool B_KC = (MODE == FWD);

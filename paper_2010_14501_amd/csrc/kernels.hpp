@@ -98,9 +98,12 @@ void fill_u32(hipStream_t st, uint32_t *dst, int64_t n, uint32_t v);
 void column_copy(hipStream_t st, const float *src, int64_t src_ld, float *dst, int64_t dst_ld, int cols, int64_t rows, bool accumulate);
 
 // ---- linear layer: y[N,out] = x[N,in] w[out,in]^T + b
-void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out);
+// scratch (may be null): device memory for partial results of a split reduction
+void linear_fwd(hipStream_t st, const float *x, const float *w, const float *b, float *y, int N, int in, int out, float *scratch = nullptr,
+                size_t scratch_bytes = 0);
 void linear_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, float *db, int N, int in, int out);
-void linear_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, int N, int in, int out, bool accumulate);
+void linear_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, int N, int in, int out, bool accumulate,
+                  float *scratch = nullptr, size_t scratch_bytes = 0);
 
 // ---- losses; scratch >= N floats
 void softmaxce_fwd(hipStream_t st, const float *logits, const int32_t *labels, float *loss, int N, int classes,
