@@ -1,0 +1,167 @@
+"""Parity at the full size of the headline configuration (ResNet-50, batch 184, 224x224), in the launch
+configuration bench.py times.  The fp64 oracle cannot run this step in reasonable time, so the checks
+are: sampled outputs the oracle computes one by one, per-kernel checks on the GPU's own tensors,
+identities that hold at any size, and bit-identity of the gradients under a different schedule."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import numerics as nm
+from workloads import graphs, schedules, search, tensors
+from paper_2010_14501_amd import costs
+import paper_2010_14501_amd as M
+from paper_2010_14501_amd.runner import StepRunner
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def full():
+    g = graphs.resnet50(batch=184)
+    exts, params = tensors.make_inputs(g, seed=0)
+    sch = schedules.block_output_schedule(g)          # the schedule bench.py runs
+    run = StepRunner(g.text(), sch.text(), exts, params)
+    peak = run.step()
+    return g, exts, params, run, peak, run.grads_numpy(), run.loss_value()
+
+
+def test_peak_and_loss_at_full_size(full):
+    g, exts, params, run, peak, grads, loss = full
+    assert peak == run.plan.exact_peak <= run.plan.predicted_peak
+    store = M.Plan(g.text(), schedules.store_everything_schedule(g).text()).exact_peak
+    assert peak < 0.35 * store
+    # random weights, uniform labels: the loss sits near log(classes) and every gradient is finite
+    assert abs(loss - np.log(1000.0)) < 1.5
+    assert all(np.isfinite(v).all() for v in grads.values())
+
+
+def test_gradients_do_not_depend_on_the_schedule_at_full_size(full):
+    """Same operator variants, different saved sets (the searched schedule at half the store-everything peak
+    recomputes about half as much): every gradient bit must be the same."""
+    g, exts, params, run, peak, grads, loss = full
+    tau = costs.read_table(os.path.join(ROOT, "workloads", "measured", "costs_resnet50_b184.txt"))
+    store = M.Plan(g.text(), schedules.store_everything_schedule(g).text()).exact_peak
+    levels, sch, peak2, ms = search.greedy(g, tau, 0.53 * store, M.Plan)
+    assert 2 in levels and peak2 <= 0.53 * store
+    other = StepRunner(g.text(), sch.text(), exts, params)
+    assert other.step() == peak2
+    got = other.grads_numpy()
+    assert other.loss_value() == loss
+    differing = [p for p in grads if not np.array_equal(grads[p], got[p])]
+    assert not differing, differing
+
+
+def test_identities_that_hold_at_any_size(full):
+    g, exts, params, run, peak, grads, loss = full
+    # softmax cross-entropy: every row of the logit gradient sums to zero, so the bias gradient of the last
+    # layer sums to zero
+    fc_b = [pid for pid, name, shp in g.params if name == "fc.b"][0]
+    assert abs(grads[fc_b].sum()) < 1e-4 * np.abs(grads[fc_b]).sum()
+    # a convolution followed by training-mode BatchNorm is invariant to the scale of each filter, so each
+    # filter is orthogonal to its gradient (up to the eps in the variance)
+    worst = 0.0
+    for n in g.nodes:
+        if n.op != "bn":
+            continue
+        conv = g.nodes[n.ins[0] - 1]
+        if conv.op != "conv":
+            continue
+        w, dw = params[conv.pars[0]].astype(np.float64), grads[conv.pars[0]].astype(np.float64)
+        K = w.shape[0]
+        dots = np.abs((w.reshape(K, -1) * dw.reshape(K, -1)).sum(axis=1))
+        scale = np.linalg.norm(w.reshape(K, -1), axis=1) * np.linalg.norm(dw.reshape(K, -1), axis=1)
+        worst = max(worst, float((dots / np.maximum(scale, 1e-30)).max()))
+    assert worst < 2e-3, worst
+
+
+def filter_orthogonality(g, params, grads):
+    """max over BatchNorm-followed (depthwise) convolutions and filters of |<w_k, dw_k>| / (|w_k| |dw_k|)."""
+    worst = 0.0
+    for n in g.nodes:
+        if n.op != "bn":
+            continue
+        conv = g.nodes[n.ins[0] - 1]
+        if conv.op not in ("conv", "dwconv"):
+            continue
+        w, dw = params[conv.pars[0]].astype(np.float64), grads[conv.pars[0]].astype(np.float64)
+        K = w.shape[0]
+        dots = np.abs((w.reshape(K, -1) * dw.reshape(K, -1)).sum(axis=1))
+        scale = np.linalg.norm(w.reshape(K, -1), axis=1) * np.linalg.norm(dw.reshape(K, -1), axis=1)
+        worst = max(worst, float((dots / np.maximum(scale, 1e-30)).max()))
+    return worst
+
+
+OTHER = {
+    "vgg16_b176": (lambda: graphs.vgg16_bn(batch=176), schedules.vgg_alternate_schedule),
+    "unet_b11": (lambda: graphs.unet(batch=11), schedules.unet_skip_schedule),
+    "mobilenetv2_b272": (lambda: graphs.mobilenet_v2(batch=272), schedules.mobilenet_depthwise_schedule),
+}
+
+
+@pytest.mark.parametrize("name", list(OTHER))
+def test_other_configurations_at_full_size(name):
+    """VGG-16 b176, UNet b11 at 416x608, MobileNetV2 b272 under their named schedules: the executor's peak is
+    the plan's, gradients are finite, bit-identical under the block-output schedule, and every filter that
+    feeds a BatchNorm is orthogonal to its gradient."""
+    make, named = OTHER[name]
+    g = make()
+    exts, params = tensors.make_inputs(g, seed=0)
+    results = []
+    for sch in (named(g), schedules.block_output_schedule(g)):
+        run = StepRunner(g.text(), sch.text(), exts, params)
+        peak = run.step()
+        assert peak == run.plan.exact_peak <= run.plan.predicted_peak
+        results.append((run.grads_numpy(), run.loss_value(), peak))
+        del run
+    (ga, la, pa), (gb, lb, pb) = results
+    assert pa != pb and la == lb and np.isfinite(la)
+    assert all(np.isfinite(v).all() for v in ga.values())
+    differing = [p for p in ga if not np.array_equal(ga[p], gb[p])]
+    assert not differing, differing
+    assert filter_orthogonality(g, params, ga) < 2e-3
+
+
+def test_sampled_stem_outputs_and_statistics(full):
+    """Stop the step after the stem's BatchNorm: sampled convolution outputs against the oracle's dot product
+    for that element, the statistics against fp64 on the GPU's own convolution output."""
+    import torch
+    g, exts, params, _, _, _, _ = full
+    sch = schedules.store_everything_schedule(g, dict(schedules.DEFAULT_VARIANTS, inplace=False))
+    run = StepRunner(g.text(), sch.text(), exts, params)
+    trace = run.plan.trace()
+    conv, bn = g.nodes[0], g.nodes[1]
+    assert conv.op == "conv" and bn.op == "bn"
+    ev = [i for i, e in enumerate(trace) if e["kind"] == M.RUN_FWD and e["node"] == bn.id][0]
+    run.plan.set_stop_after(ev)
+    run.step()
+    torch.cuda.synchronize()
+    y = run.read(run.plan.tensor_offset(ev, conv.id), conv.shape)          # N,P,Q,K fp32
+    x = exts[0].astype(np.float64)
+    w = params[conv.pars[0]].astype(np.float64)                             # K,R,S,C
+    rng = np.random.default_rng(7)
+    N, P, Q, K = conv.shape
+    R, st, pad = conv.attrs["R"], conv.attrs["stride"], conv.attrs["pad"]
+    H, W = x.shape[1], x.shape[2]
+    picks = [(0, 0, 0, 0), (N - 1, P - 1, Q - 1, K - 1), (N - 1, 0, Q - 1, 5)]
+    picks += [tuple(int(rng.integers(0, d)) for d in (N, P, Q, K)) for _ in range(500)]
+    scale = float(np.sqrt(np.mean(y.astype(np.float64) ** 2)))
+    for n, p, q, k in picks:
+        acc = 0.0
+        for r in range(R):
+            h = p * st + r - pad
+            if not 0 <= h < H:
+                continue
+            for s in range(R):
+                v = q * st + s - pad
+                if 0 <= v < W:
+                    acc += float(np.dot(x[n, h, v, :], w[k, r, s, :]))
+        assert abs(y[n, p, q, k] - acc) < 1e-4 * scale, (n, p, q, k)
+    # statistics of 2.3 million rows per channel
+    rows = y.reshape(-1, K).astype(np.float64)
+    mean, invstd = nm.bn_stats(np.ascontiguousarray(rows.T)[None, :, :, None], float(bn.attrs["eps"]))
+    got = run.read(run.plan.bn_stats_offset(bn.id), (2 * K,))
+    assert np.abs(got[:K] - mean).max() < 1e-5 * np.abs(mean).max() + 1e-6
+    assert np.abs(got[K:] / invstd - 1).max() < 1e-5
