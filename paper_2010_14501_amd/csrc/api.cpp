@@ -20,10 +20,12 @@ void build_programs(monet_plan *p);
 }
 
 // One entry of the step program: a single operator launch, or two neighbours run as one fused kernel.
-enum { FUSE_NONE = 0, FUSE_BN_RELU_FWD, FUSE_ADD_RELU_FWD, FUSE_RELU_BN_BWD, FUSE_RELU_ADD_BWD };
+enum { FUSE_NONE = 0, FUSE_BN_RELU_FWD, FUSE_ADD_RELU_FWD, FUSE_RELU_BN_BWD, FUSE_RELU_ADD_BWD,
+       FUSE_BN_ADD_RELU_FWD, FUSE_RELU_ADD_BN_BWD };   // the last two join three launches (tail of a residual block)
 struct ProgStep {
     int fuse;
-    size_t a, b;   // indices into Plan::launches (b only when fused)
+    size_t a, b, c;   // indices into Plan::launches (b when fused, c when three are fused)
+    size_t last() const { return fuse == FUSE_NONE ? a : ((fuse == FUSE_BN_ADD_RELU_FWD || fuse == FUSE_RELU_ADD_BN_BWD) ? c : b); }
 };
 
 struct monet_plan {
@@ -412,19 +414,113 @@ int fusable(const Plan &pl, const Launch &L1, const Launch &L2) {
     return spans_conflict(ins, outs) ? FUSE_NONE : f;
 }
 
+// true if the forward tensor of `node` is released between two events of the trace (exclusive)
+bool freed_between(const Plan &pl, int node, size_t ev_from, size_t ev_to) {
+    for (size_t e = ev_from + 1; e < ev_to && e < pl.events.size(); ++e)
+        if (pl.events[e].kind == EV_FREE && pl.events[e].node == node && pl.events[e].aux == T_FWD) return true;
+    return false;
+}
+
+// BatchNorm -> add -> ReLU in the forward direction.  Returns the input position of the BatchNorm in the add, or -1.
+int triple_fwd(const Plan &pl, const Launch &L1, const Launch &L2, const Launch &L3) {
+    const Graph &g = pl.g;
+    if (L1.kind == EV_RUN_BWD || L2.kind == EV_RUN_BWD || L3.kind == EV_RUN_BWD) return -1;
+    const Node &bn = g.nodes[L1.id], &ad = g.nodes[L2.id], &re = g.nodes[L3.id];
+    if (bn.op != "bn" || ad.op != "add" || (re.op != "relu" && re.op != "relu6")) return -1;
+    if (re.ins[0] != ad.id || ad.ins.size() != 2 || ad.ins[0] == ad.ins[1]) return -1;
+    const int pos = ad.ins[0] == bn.id ? 0 : (ad.ins[1] == bn.id ? 1 : -1);
+    if (pos < 0 || bn.shape.back() % 4 || numel_of(re.shape) % 4) return -1;
+    std::vector<Span> ins, outs;
+    ins.push_back({L1.a[0], bn.bytes, true});
+    ins.push_back({L2.a[1 - pos], ad.bytes, true});
+    if (!freed_between(pl, bn.id, L2.event, L3.event)) outs.push_back({L1.a[2], bn.bytes, false});
+    if (!(L3.flags & 1)) outs.push_back({L2.a[2], ad.bytes, false});
+    outs.push_back({L3.a[2], re.bytes, false});
+    if (L3.flags & 2) outs.push_back({L3.a[3], g.nodes[re.aux_children[0]].bytes, false});
+    return spans_conflict(ins, outs) ? -1 : pos;
+}
+
+// ReLU backward -> add backward -> BatchNorm backward of one of the add's inputs.  Returns that input's position, or -1.
+int triple_bwd(const Plan &pl, const Launch &L1, const Launch &L2, const Launch &L3) {
+    const Graph &g = pl.g;
+    if (L1.kind != EV_RUN_BWD || L2.kind != EV_RUN_BWD || L3.kind != EV_RUN_BWD) return -1;
+    const Bop &b1 = g.bops[L1.id], &b2 = g.bops[L2.id], &b3 = g.bops[L3.id];
+    if ((b1.kind != "relu_bwd" && b1.kind != "relu6_bwd") || b2.kind != "add_bwd" || b3.kind != "bn_bwd") return -1;
+    const Node &re = g.nodes[b1.node], &ad = g.nodes[b2.node], &bn = g.nodes[b3.node];
+    if (re.ins[0] != ad.id || ad.ins.size() != 2 || ad.ins[0] == ad.ins[1]) return -1;
+    const int pos = ad.ins[0] == bn.id ? 0 : (ad.ins[1] == bn.id ? 1 : -1);
+    if (pos < 0 || (L1.flags & 1) || ((L2.flags >> pos) & 1)) return -1;    // both gradients in between are written fresh
+    if (bn.shape.back() % 4 || numel_of(re.shape) % 4) return -1;
+    const bool from_mask = b1.impls[L1.impl].algo == "from_mask";
+    std::vector<Span> ins, outs;
+    ins.push_back({L1.a[0], re.bytes, true});
+    ins.push_back({L1.a[1], from_mask ? g.nodes[re.aux_children[0]].bytes : re.bytes, !from_mask});
+    ins.push_back({L3.a[1], bn.bytes, true});
+    outs.push_back({L3.a[2], bn.bytes, false});
+    if (ad.ins[1 - pos] > 0) outs.push_back({L2.a[2 + (1 - pos)], ad.bytes, false});
+    return spans_conflict(ins, outs) ? -1 : pos;
+}
+
 void build_programs(monet_plan *p) {
     const Plan &pl = p->plan;
-    for (size_t i = 0; i < pl.launches.size(); ++i) p->prog_plain.push_back(ProgStep{FUSE_NONE, i, i});
-    for (size_t i = 0; i < pl.launches.size(); ++i) {
-        int f = i + 1 < pl.launches.size() ? fusable(pl, pl.launches[i], pl.launches[i + 1]) : FUSE_NONE;
-        if (f) { p->prog_fused.push_back(ProgStep{f, i, i + 1}); ++i; }
-        else p->prog_fused.push_back(ProgStep{FUSE_NONE, i, i});
+    const size_t n = pl.launches.size();
+    for (size_t i = 0; i < n; ++i) p->prog_plain.push_back(ProgStep{FUSE_NONE, i, i, i});
+    for (size_t i = 0; i < n; ++i) {
+        if (i + 2 < n) {
+            if (triple_fwd(pl, pl.launches[i], pl.launches[i + 1], pl.launches[i + 2]) >= 0) {
+                p->prog_fused.push_back(ProgStep{FUSE_BN_ADD_RELU_FWD, i, i + 1, i + 2});
+                i += 2;
+                continue;
+            }
+            if (triple_bwd(pl, pl.launches[i], pl.launches[i + 1], pl.launches[i + 2]) >= 0) {
+                p->prog_fused.push_back(ProgStep{FUSE_RELU_ADD_BN_BWD, i, i + 1, i + 2});
+                i += 2;
+                continue;
+            }
+        }
+        int f = i + 1 < n ? fusable(pl, pl.launches[i], pl.launches[i + 1]) : FUSE_NONE;
+        if (f) { p->prog_fused.push_back(ProgStep{f, i, i + 1, i + 1}); ++i; }
+        else p->prog_fused.push_back(ProgStep{FUSE_NONE, i, i, i});
     }
 }
 
 void run_fused(const StepCtx &c, const ProgStep &ps) {
     const Graph &g = c.mp->plan.g;
+    const Plan &pl = c.mp->plan;
     const Launch &L1 = c.mp->plan.launches[ps.a], &L2 = c.mp->plan.launches[ps.b];
+    if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
+        const Launch &L3 = pl.launches[ps.c];
+        const Node &bn = g.nodes[L1.id], &ad = g.nodes[L2.id], &re = g.nodes[L3.id];
+        const int pos = ad.ins[0] == bn.id ? 0 : 1;
+        const float *x = (const float *)c.ptr(L1.a[0]);
+        const float *other = (const float *)c.ptr(L2.a[1 - pos]);
+        // tensors between the operators are written only if something later still reads them
+        float *out_bn = freed_between(pl, bn.id, L2.event, L3.event) ? nullptr : (float *)c.ptr(L1.a[2]);
+        float *out_pre = (L3.flags & 1) ? nullptr : (float *)c.ptr(L2.a[2]);
+        float *out = (float *)c.ptr(L3.a[2]);
+        uint64_t *mask = (L3.flags & 2) ? (uint64_t *)c.ptr(L3.a[3]) : nullptr;
+        const int64_t n = numel_of(re.shape);
+        const int C = (int)bn.shape.back();
+        float *stats = c.bn_stats(L1.id);
+        if (L1.kind == EV_RUN_FWD) bn_stats(c.st, x, stats, n / C, C, (float)bn.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
+        fwd_chain(c.st, x, other, c.weights[bn.pars[0]], c.weights[bn.pars[1]], stats, C, out_bn, out_pre, out, mask, n, re.op == "relu6");
+        return;
+    }
+    if (ps.fuse == FUSE_RELU_ADD_BN_BWD) {
+        const Launch &L3 = pl.launches[ps.c];
+        const Bop &b1 = g.bops[L1.id], &b2 = g.bops[L2.id], &b3 = g.bops[L3.id];
+        const Node &re = g.nodes[b1.node], &ad = g.nodes[b2.node], &bn = g.nodes[b3.node];
+        const int pos = ad.ins[0] == bn.id ? 0 : 1, oth = 1 - pos;
+        const std::string &algo = b1.impls[L1.impl].algo;
+        const int mode = algo == "from_input" ? RELU_FROM_INPUT : (algo == "from_output" ? RELU_FROM_OUTPUT : RELU_FROM_MASK);
+        float *side = ad.ins[oth] > 0 ? (float *)c.ptr(L2.a[2 + oth]) : nullptr;
+        const int C = (int)bn.shape.back();
+        bn_bwd(c.st, (const float *)c.ptr(L1.a[0]), (const float *)c.ptr(L3.a[1]), b3.impls[L3.impl].algo == "from_output",
+               c.weights[bn.pars[0]], c.weights[bn.pars[1]], c.bn_stats(b3.node), (float *)c.ptr(L3.a[2]), c.grads[bn.pars[0]],
+               c.grads[bn.pars[1]], numel_of(re.shape) / C, C, (L3.flags & 1) != 0, c.scratch(), c.scratch_bytes(), c.ptr(L1.a[1]), mode,
+               b1.kind == "relu6_bwd", side, ((L2.flags >> oth) & 1) != 0);
+        return;
+    }
     if (ps.fuse == FUSE_BN_RELU_FWD || ps.fuse == FUSE_ADD_RELU_FWD) {
         const Node &n1 = g.nodes[L1.id], &n2 = g.nodes[L2.id];
         const float *x = (const float *)c.ptr(L1.a[0]);
@@ -439,9 +535,9 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
             float *stats = c.bn_stats(L1.id);
             if (L1.kind == EV_RUN_FWD)
                 bn_stats(c.st, x, stats, n / C, C, (float)n1.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
-            fwd_chain(c.st, x, nullptr, c.weights[n1.pars[0]], c.weights[n1.pars[1]], stats, C, pre, out, mask, n, six);
+            fwd_chain(c.st, x, nullptr, c.weights[n1.pars[0]], c.weights[n1.pars[1]], stats, C, nullptr, pre, out, mask, n, six);
         } else {
-            fwd_chain(c.st, x, (const float *)c.ptr(L1.a[1]), nullptr, nullptr, nullptr, 0, pre, out, mask, n, six);
+            fwd_chain(c.st, x, (const float *)c.ptr(L1.a[1]), nullptr, nullptr, nullptr, 0, nullptr, pre, out, mask, n, six);
         }
         return;
     }
@@ -457,7 +553,7 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
         const int C = (int)bn.shape.back();
         bn_bwd(c.st, dz, (const float *)c.ptr(L2.a[1]), b2.impls[L2.impl].algo == "from_output", c.weights[bn.pars[0]], c.weights[bn.pars[1]],
                c.bn_stats(b2.node), (float *)c.ptr(L2.a[2]), c.grads[bn.pars[0]], c.grads[bn.pars[1]], n / C, C, (L2.flags & 1) != 0, c.scratch(),
-               c.scratch_bytes(), (const uint64_t *)t);
+               c.scratch_bytes(), t, RELU_FROM_MASK, six);
     } else {
         const Node &ad = g.nodes[b2.node];
         int mode = algo == "from_input" ? RELU_FROM_INPUT : (algo == "from_output" ? RELU_FROM_OUTPUT : RELU_FROM_MASK);
@@ -496,8 +592,7 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
         const std::vector<ProgStep> &prog = fuse ? p->prog_fused : p->prog_plain;
         for (size_t si = 0; si < prog.size(); ++si) {
             const ProgStep &ps = prog[si];
-            const size_t li_last = ps.fuse ? ps.b : ps.a;
-            const Launch &Llast = pl.launches[li_last];
+            const Launch &Llast = pl.launches[ps.last()];
             if (p->stop_after >= 0 && (int64_t)Llast.event > p->stop_after) break;
             for (; next_event <= Llast.event; ++next_event) {
                 const monet_event &e = pl.events[next_event];
@@ -551,7 +646,23 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
         double e, bytes;
         const char *label;
-        if (ps.fuse == FUSE_BN_RELU_FWD || ps.fuse == FUSE_ADD_RELU_FWD) {
+        if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
+            const Launch &L3 = p->plan.launches[ps.c];
+            e = 4.0 * (double)numel_of(g.nodes[L3.id].shape);
+            const bool keep_bn = !freed_between(p->plan, L.id, L2.event, L3.event), pre = !(L3.flags & 1), mk = L3.flags & 2;
+            bytes = 2 * e + (keep_bn ? e : 0) + (pre ? e : 0) + e + (mk ? e / 32 : 0) + (L.kind == EV_RUN_FWD ? e : 0);
+            label = L.kind == EV_RUN_FWD ? "bn_add_relu_fwd" : "bn_add_relu_apply";
+        } else if (ps.fuse == FUSE_RELU_ADD_BN_BWD) {
+            const Launch &L3 = p->plan.launches[ps.c];
+            const Bop &b1 = g.bops[L.id];
+            const Node &ad = g.nodes[g.bops[L2.id].node];
+            const int pos = ad.ins[0] == g.bops[L3.id].node ? 0 : 1, oth = 1 - pos;
+            e = 4.0 * (double)numel_of(g.nodes[b1.node].shape);
+            const double t = b1.impls[L.impl].algo == "from_mask" ? e / 32 : e;
+            bytes = 2 * (e + t + e) + e + ((L3.flags & 1) ? e : 0);                 // two passes over dz, gate, bn tensor; dx
+            if (ad.ins[oth] > 0) bytes += e + (((L2.flags >> oth) & 1) ? e : 0);    // the other branch's gradient
+            label = "relu_add_bn_bwd";
+        } else if (ps.fuse == FUSE_BN_RELU_FWD || ps.fuse == FUSE_ADD_RELU_FWD) {
             e = 4.0 * (double)numel_of(g.nodes[L2.id].shape);
             const bool pre = !(L2.flags & 1), mk = L2.flags & 2;
             bytes = (ps.fuse == FUSE_ADD_RELU_FWD ? 2 : 1) * e + (pre ? e : 0) + e + (mk ? e / 32 : 0);

@@ -248,8 +248,25 @@ void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, cons
 // xhat = (x - mean)*invstd            (from the input)
 //      = (y - beta)/gamma             (from the output; gamma must be non-zero)
 // dbeta = sum dy, dgamma = sum dy*xhat, dx = gamma*invstd*(dy - dbeta/m - xhat*dgamma/m)
-template <bool FROM_OUT>
-__global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ dy, const uint64_t *__restrict__ mask,
+// RM: how the incoming gradient is gated before use (a ReLU backward folded in): 0 not at all, 1 by the 1-bit
+// sign code in rt, 2 by rt > 0, 3 by 0 < rt < 6 (rt = the ReLU's float input or output).
+template <int RM>
+__device__ inline void relu_gate(float (&gg)[4], unsigned bits, const f4 &rv) {
+    if (RM == 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) gg[j] = (bits >> j) & 1 ? gg[j] : 0.0f;
+    } else if (RM >= 2) {
+        const float rr[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool pass = RM == 3 ? (rr[j] > 0.0f && rr[j] < 6.0f) : (rr[j] > 0.0f);
+            gg[j] = pass ? gg[j] : 0.0f;
+        }
+    }
+}
+
+template <bool FROM_OUT, int RM>
+__global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ dy, const void *__restrict__ rt,
                                                       const float *__restrict__ t, const float *__restrict__ gamma, const float *__restrict__ beta,
                                                       const float *__restrict__ stats, float *__restrict__ part, int64_t rows,
                                                       int C, int TPR, int64_t slab) {
@@ -269,13 +286,13 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
             if (FROM_OUT) { sc[j] = 1.0f / gamma[c]; sh[j] = -beta[c] * sc[j]; }
             else { sc[j] = stats[C + c]; sh[j] = -stats[c] * sc[j]; }
         }
-        auto accumulate = [&](const f4 &g, const f4 &v, int64_t i4) {
+        const uint64_t *mask = (const uint64_t *)rt;
+        auto accumulate = [&](const f4 &g, const f4 &v, const f4 &rv, int64_t i4) {
             float gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w};
-            if (mask) {     // the incoming gradient still has to pass a ReLU: keep it where the sign bit is set
-                unsigned bits = (unsigned)(mask[i4 >> 4] >> ((i4 & 15) * 4)) & 15u;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) gg[j] = (bits >> j) & 1 ? gg[j] : 0.0f;
-            }
+            // the incoming gradient may still have to pass a ReLU
+            unsigned bits = 0;
+            if (RM == 1) bits = (unsigned)(mask[i4 >> 4] >> ((i4 & 15) * 4)) & 15u;
+            relu_gate<RM>(gg, bits, rv);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 sb[j] += gg[j];
@@ -288,12 +305,16 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
             const int64_t ia = r * C4 + cg, ib = (r + RPP) * C4 + cg;
             const f4 ga = __builtin_nontemporal_load((const f4 *)dy + ia), va = __builtin_nontemporal_load((const f4 *)t + ia);
             const f4 gb = __builtin_nontemporal_load((const f4 *)dy + ib), vb = __builtin_nontemporal_load((const f4 *)t + ib);
-            accumulate(ga, va, ia);
-            accumulate(gb, vb, ib);
+            f4 ra = f4{0, 0, 0, 0}, rb = f4{0, 0, 0, 0};
+            if (RM >= 2) { ra = __builtin_nontemporal_load((const f4 *)rt + ia); rb = __builtin_nontemporal_load((const f4 *)rt + ib); }
+            accumulate(ga, va, ra, ia);
+            accumulate(gb, vb, rb, ib);
         }
         for (; r < r1; r += RPP) {
             const int64_t ia = r * C4 + cg;
-            accumulate(__builtin_nontemporal_load((const f4 *)dy + ia), __builtin_nontemporal_load((const f4 *)t + ia), ia);
+            f4 ra = f4{0, 0, 0, 0};
+            if (RM >= 2) ra = __builtin_nontemporal_load((const f4 *)rt + ia);
+            accumulate(__builtin_nontemporal_load((const f4 *)dy + ia), __builtin_nontemporal_load((const f4 *)t + ia), ra, ia);
         }
     }
 #pragma unroll
@@ -361,12 +382,15 @@ __global__ __launch_bounds__(256) void bn_bwd_final(const float *__restrict__ pa
     }
 }
 
-template <bool FROM_OUT, bool ACC>
-__global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy, const uint64_t *__restrict__ mask,
+// side (may be null): a second tensor that receives (or accumulates) the gated incoming gradient itself -- the
+// other branch of a residual add whose backward is folded in.
+template <bool FROM_OUT, int RM>
+__global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy, const void *__restrict__ rt,
                                                     const float *__restrict__ t,
                                                     const float *__restrict__ gamma, const float *__restrict__ beta,
                                                     const float *__restrict__ stats, const float *__restrict__ coef, float *dx,
-                                                    int64_t total4, int C) {
+                                                    int acc, float *side, int side_acc, int64_t total4, int C) {
+    const uint64_t *mask = (const uint64_t *)rt;
     // same streaming pattern as bn_apply_kernel
     constexpr int U = 4;
     const int C4 = C / 4;
@@ -388,16 +412,20 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
     const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
     if (fixed) load((int)(threadIdx.x % C4));
     for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
-        f4 g[U], v[U], o[U];
+        f4 g[U], v[U], o[U], rv[U], so[U];
         unsigned bits[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * 256;
+            bits[u] = 0;
+            rv[u] = f4{0, 0, 0, 0};
             if (i >= r1) continue;
             g[u] = __builtin_nontemporal_load((const f4 *)dy + i);
             v[u] = __builtin_nontemporal_load((const f4 *)t + i);
-            if (ACC) o[u] = __builtin_nontemporal_load((const f4 *)dx + i);
-            if (mask) bits[u] = (unsigned)(mask[i >> 4] >> ((i & 15) * 4)) & 15u;
+            if (acc) o[u] = __builtin_nontemporal_load((const f4 *)dx + i);
+            if (RM == 1) bits[u] = (unsigned)(mask[i >> 4] >> ((i & 15) * 4)) & 15u;
+            if (RM >= 2) rv[u] = __builtin_nontemporal_load((const f4 *)rt + i);
+            if (side && side_acc) so[u] = __builtin_nontemporal_load((const f4 *)side + i);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -405,16 +433,17 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
             if (i >= r1) continue;
             if (!fixed) load((int)(i % C4));
             float gg[4] = {g[u].x, g[u].y, g[u].z, g[u].w}, vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, r[4];
-            if (mask) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) gg[j] = (bits[u] >> j) & 1 ? gg[j] : 0.0f;
+            relu_gate<RM>(gg, bits[u], rv[u]);
+            if (side) {
+                const f4 sg = f4{gg[0], gg[1], gg[2], gg[3]};
+                __builtin_nontemporal_store(side_acc ? sg + so[u] : sg, (f4 *)side + i);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float xh = vv[j] * sc[j] + sh[j];
                 r[j] = a[j] * (gg[j] - mb[j] - xh * mg[j]);
             }
-            if (ACC) { r[0] += o[u].x; r[1] += o[u].y; r[2] += o[u].z; r[3] += o[u].w; }
+            if (acc) { r[0] += o[u].x; r[1] += o[u].y; r[2] += o[u].z; r[3] += o[u].w; }
             __builtin_nontemporal_store(f4{r[0], r[1], r[2], r[3]}, (f4 *)dx + i);
         }
     }
@@ -422,20 +451,33 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
 
 void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, const float *gamma, const float *beta,
             const float *stats, float *dx, float *dgamma, float *dbeta, int64_t rows, int C, bool accumulate, float *scratch,
-            size_t scratch_bytes, const uint64_t *mask) {
+            size_t scratch_bytes, const void *relu_t, int relu_mode, bool six, float *side, bool side_acc) {
     if (rows <= 0) throw KernelError("BatchNorm: no rows");
+    int rm = 0;
+    if (relu_t) {
+        if (relu_mode == RELU_FROM_MASK) rm = 1;
+        else if (relu_mode == RELU_FROM_INPUT || relu_mode == RELU_FROM_OUTPUT) rm = six ? 3 : 2;
+        else throw KernelError("BatchNorm backward: unknown ReLU mode");
+    }
     int64_t floats = (int64_t)(scratch_bytes / 4) - 2 * C;    // tail of the scratch holds the two coefficient vectors
     BnGeom g = bn_geom(rows, C, floats, 2);
     float *coef = scratch + (int64_t)g.G * C * 2;
-    if (from_output) hipLaunchKernelGGL((bn_bwd_partial<true>), dim3(g.G, g.CB), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
-    else hipLaunchKernelGGL((bn_bwd_partial<false>), dim3(g.G, g.CB), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab);
+    const int64_t total4 = rows * (C / 4);
+    const int grid = stream_grid(total4);
+    const int acc = accumulate ? 1 : 0, sacc = side_acc ? 1 : 0;
+#define BP(F, RM) hipLaunchKernelGGL((bn_bwd_partial<F, RM>), dim3(g.G, g.CB), dim3(256), 0, st, dy, relu_t, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab)
+#define BA(F, RM) hipLaunchKernelGGL((bn_bwd_apply<F, RM>), dim3(grid), dim3(256), 0, st, dy, relu_t, t, gamma, beta, stats, (const float *)coef, dx, acc, side, sacc, total4, C)
+#define BOTH(STEP)                                                                 \
+    do {                                                                           \
+        if (from_output) { switch (rm) { case 0: STEP(true, 0); break; case 1: STEP(true, 1); break; case 2: STEP(true, 2); break; default: STEP(true, 3); } } \
+        else             { switch (rm) { case 0: STEP(false, 0); break; case 1: STEP(false, 1); break; case 2: STEP(false, 2); break; default: STEP(false, 3); } } \
+    } while (0)
+    BOTH(BP);
     hipLaunchKernelGGL(bn_bwd_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
-    int64_t total4 = rows * (C / 4);
-    int grid = stream_grid(total4);
-#define BA(F, A) hipLaunchKernelGGL((bn_bwd_apply<F, A>), dim3(grid), dim3(256), 0, st, dy, mask, t, gamma, beta, stats, (const float *)coef, dx, total4, C)
-    if (from_output) { if (accumulate) BA(true, true); else BA(true, false); }
-    else             { if (accumulate) BA(false, true); else BA(false, false); }
+    BOTH(BA);
+#undef BOTH
 #undef BA
+#undef BP
     hip_check(hipGetLastError(), "bn_bwd launch");
 }
 

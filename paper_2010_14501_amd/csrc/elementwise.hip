@@ -56,7 +56,7 @@ void relu_fwd(hipStream_t st, const float *x, float *y, uint64_t *mask, int64_t 
     if (n <= 0) return;
     // whole float4s: the 16-byte streaming kernel (same predicate, same mask words); this one takes the rest
     if (n % 4 == 0 && ((uintptr_t)x % 16) == 0 && ((uintptr_t)y % 16) == 0) {
-        fwd_chain(st, x, nullptr, nullptr, nullptr, nullptr, 0, nullptr, y, mask, n, six);
+        fwd_chain(st, x, nullptr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, y, mask, n, six);
         return;
     }
     constexpr int U = 8;

@@ -29,10 +29,15 @@ __device__ inline uint64_t spread16(uint64_t x) {
 // Each thread owns four consecutive elements (one float4); a wave owns 256 consecutive elements,
 // i.e. four mask words.  Word w of the wave collects, from lanes 16w..16w+15, bit 4*(l-16w)+j of
 // element j of lane l: four ballots (one per j), each cut to the 16 lanes of the word and spread.
-template <bool BN, bool ADD, bool PRE_OUT, bool SIX, bool MASK>
+//
+// v = x; BN: v = a*v + b, kept in out_bn if that tensor has to exist; ADD: v += x2, kept in out_pre if
+// that tensor has to exist; out = relu(v); mask bits.  BN and ADD together are the tail of a residual
+// block (BatchNorm -> add -> ReLU) in one pass.
+template <bool BN, bool ADD, bool SIX, bool MASK>
 __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const float *x2, const float *__restrict__ gamma,
                                                         const float *__restrict__ beta, const float *__restrict__ stats, int C,
-                                                        float *out_pre, float *out, uint64_t *__restrict__ mask, int64_t total4) {
+                                                        float *out_bn, float *out_pre, float *out, uint64_t *__restrict__ mask,
+                                                        int64_t total4) {
     // Each workgroup streams one contiguous range (a multiple of 256 float4, so that wave boundaries fall
     // on mask words and a thread's channel group stays fixed whenever C/4 divides 256), four float4 per
     // thread in flight, streaming (non-temporal) loads and stores: tensors here are far larger than any cache.
@@ -55,16 +60,17 @@ __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const fl
     const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
     if (BN && fixed) load_ab((int)(threadIdx.x % C4));
     for (int64_t base = r0 + threadIdx.x; base - lane < r1; base += U * 256) {      // base - lane: wave-uniform trip count
-        f4 v[U];
+        f4 v[U], w[U];
         bool valid[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t i = base + u * 256;
             valid[u] = i < r1;
             v[u] = f4{0, 0, 0, 0};
+            w[u] = f4{0, 0, 0, 0};
             if (valid[u]) {
                 v[u] = __builtin_nontemporal_load((const f4 *)x + i);
-                if (ADD) v[u] += __builtin_nontemporal_load((const f4 *)x2 + i);
+                if (ADD) w[u] = __builtin_nontemporal_load((const f4 *)x2 + i);
             }
         }
 #pragma unroll
@@ -74,8 +80,10 @@ __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const fl
             if (valid[u] && BN) {
                 if (!fixed) load_ab((int)(i % C4));
                 v[u].x = v[u].x * a[0] + b[0]; v[u].y = v[u].y * a[1] + b[1]; v[u].z = v[u].z * a[2] + b[2]; v[u].w = v[u].w * a[3] + b[3];
+                if (out_bn) __builtin_nontemporal_store(v[u], (f4 *)out_bn + i);
             }
-            if (valid[u] && PRE_OUT) __builtin_nontemporal_store(v[u], (f4 *)out_pre + i);
+            if (ADD) v[u] += w[u];
+            if (valid[u] && out_pre) __builtin_nontemporal_store(v[u], (f4 *)out_pre + i);
             float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, r[4];
             bool pass[4];
 #pragma unroll
@@ -108,23 +116,22 @@ int chain_grid(int64_t total4) {
 }  // namespace
 
 void fwd_chain(hipStream_t st, const float *x, const float *x2, const float *gamma, const float *beta, const float *stats, int C,
-               float *out_pre, float *out, uint64_t *mask, int64_t n, bool six) {
+               float *out_bn, float *out_pre, float *out, uint64_t *mask, int64_t n, bool six) {
     if (n <= 0) return;
     if (n % 4) throw KernelError("fused forward: element count must be a multiple of 4");
-    const bool bn = gamma != nullptr, add = x2 != nullptr, pre = out_pre != nullptr, mk = mask != nullptr;
-    if (bn && add) throw KernelError("fused forward: BatchNorm and add cannot be combined");
+    const bool bn = gamma != nullptr, add = x2 != nullptr, mk = mask != nullptr;
     if (bn && C % 4) throw KernelError("fused forward: C must be a multiple of 4");
+    if (!bn && out_bn) throw KernelError("fused forward: BatchNorm output requested without BatchNorm");
     const int64_t total4 = n / 4;
     const int grid = chain_grid(total4);
-#define FC(BN, ADD, PRE, SIX, MK) \
-    hipLaunchKernelGGL((fwd_chain_kernel<BN, ADD, PRE, SIX, MK>), dim3(grid), dim3(256), 0, st, x, x2, gamma, beta, stats, C, out_pre, out, mask, total4)
-#define FC_MK(BN, ADD, PRE, SIX) do { if (mk) FC(BN, ADD, PRE, SIX, true); else FC(BN, ADD, PRE, SIX, false); } while (0)
-#define FC_SIX(BN, ADD, PRE) do { if (six) FC_MK(BN, ADD, PRE, true); else FC_MK(BN, ADD, PRE, false); } while (0)
-#define FC_PRE(BN, ADD) do { if (pre) FC_SIX(BN, ADD, true); else FC_SIX(BN, ADD, false); } while (0)
-    if (bn) FC_PRE(true, false);
-    else if (add) FC_PRE(false, true);
-    else FC_PRE(false, false);
-#undef FC_PRE
+#define FC(BN, ADD, SIX, MK) \
+    hipLaunchKernelGGL((fwd_chain_kernel<BN, ADD, SIX, MK>), dim3(grid), dim3(256), 0, st, x, x2, gamma, beta, stats, C, out_bn, out_pre, out, mask, total4)
+#define FC_MK(BN, ADD, SIX) do { if (mk) FC(BN, ADD, SIX, true); else FC(BN, ADD, SIX, false); } while (0)
+#define FC_SIX(BN, ADD) do { if (six) FC_MK(BN, ADD, true); else FC_MK(BN, ADD, false); } while (0)
+    if (bn && add) FC_SIX(true, true);
+    else if (bn) FC_SIX(true, false);
+    else if (add) FC_SIX(false, true);
+    else FC_SIX(false, false);
 #undef FC_SIX
 #undef FC_MK
 #undef FC

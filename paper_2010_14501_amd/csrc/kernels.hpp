@@ -57,17 +57,20 @@ void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C,
               size_t scratch_bytes);
 void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, const float *beta, const float *stats,
               int64_t rows, int C);
-// t is the BatchNorm input (from_output = false) or its own output (true).  With `mask`, dy is first passed
-// through a ReLU backward given by that 1-bit sign code (fused ReLU-backward + BatchNorm-backward).
+// t is the BatchNorm input (from_output = false) or its own output (true).  With relu_t, dy is first passed through
+// a ReLU backward (relu_mode: a ReluBwdMode; relu_t = that ReLU's input, output or 1-bit sign code) -- fused
+// ReLU-backward + BatchNorm-backward; `side` (may be null) then also receives, or accumulates, the gated dy
+// itself: the other branch of a residual add between the two.
 void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, const float *gamma, const float *beta,
             const float *stats, float *dx, float *dgamma, float *dbeta, int64_t rows, int C, bool accumulate,
-            float *scratch, size_t scratch_bytes, const uint64_t *mask = nullptr);
+            float *scratch, size_t scratch_bytes, const void *relu_t = nullptr, int relu_mode = -1, bool six = false,
+            float *side = nullptr, bool side_acc = false);
 
 // ---- fused neighbours (same arithmetic as the separate kernels)
-// out = relu(f(x)) with f = BatchNorm apply (gamma != null), x + x2 (x2 != null) or identity; out_pre (may be null)
-// receives f(x); mask (may be null) the sign code.  out and out_pre may alias x.
+// v = x; if gamma: v = BatchNorm apply of v (kept in out_bn unless null); if x2: v += x2; out_pre (may be null)
+// receives v; out = relu(v); mask (may be null) the sign code.  Outputs may alias an input at the same index.
 void fwd_chain(hipStream_t st, const float *x, const float *x2, const float *gamma, const float *beta, const float *stats, int C,
-               float *out_pre, float *out, uint64_t *mask, int64_t n, bool six);
+               float *out_bn, float *out_pre, float *out, uint64_t *mask, int64_t n, bool six);
 // ReLU backward written (or accumulated) into up to two gradient tensors
 void relu_bwd_fanout(hipStream_t st, const float *dz, const void *t, int mode, float *d0, bool acc0, float *d1, bool acc1, int64_t n,
                      bool six);
