@@ -4,6 +4,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <deque>
 #include <sstream>
 
 namespace monet {
@@ -439,13 +440,46 @@ void Plan::lower() {
         monet_event e{kind, stage, node, impl, aux, 0, bytes, live};
         events.push_back(e);
     };
+    // Physical reuse of freed blocks is delayed around bandwidth-bound operators.  The executor may run up to
+    // three neighbouring operators of that kind (BatchNorm, add, ReLU and their backward operators) as one
+    // kernel; an output of the last must then not sit on memory that an earlier one still reads.  So a block
+    // freed right after such a launch goes back to the allocator only once two more launches have been
+    // placed, or as soon as a launch of another kind (which ends any such run) is placed; until then only a
+    // request of exactly its size may take it.  The events and the
+    // live-byte count follow the algorithms exactly; the delay only concerns which offsets later allocations take.
+    constexpr size_t kReuseLag = 2;
+    struct Pending { size_t when; int64_t off, bytes; };
+    std::deque<Pending> pending;
+    auto chainable = [&](const Launch &L) {
+        if (L.kind == EV_RUN_BWD) {
+            const std::string &kd = g.bops[L.id].kind;
+            return kd == "relu_bwd" || kd == "relu6_bwd" || kd == "add_bwd" || kd == "bn_bwd";
+        }
+        const std::string &op = g.nodes[L.id].op;
+        return op == "bn" || op == "add" || op == "relu" || op == "relu6";
+    };
+    auto flush_pending = [&](bool all) {
+        while (!pending.empty() && (all || pending.front().when + kReuseLag <= launches.size())) {
+            arena.release(pending.front().off, pending.front().bytes);
+            pending.pop_front();
+        }
+    };
+    // called before the allocations of the launch that is about to be placed
+    auto begin_launch = [&](bool is_chainable) { flush_pending(!is_chainable); };
     auto arena_alloc = [&](int stage, int node, int cls, int64_t bytes) {
-        int64_t off = arena.alloc(bytes);
+        flush_pending(false);
+        int64_t off = -1;
+        // a waiting block of exactly this size may be taken whole: element i of the new tensor then sits on
+        // element i of the old one, which the same thread of a fused kernel has read before it writes
+        for (auto it = pending.begin(); it != pending.end(); ++it)
+            if (it->bytes == bytes) { off = it->off; pending.erase(it); break; }
+        if (off < 0) off = arena.alloc(bytes);
         ev(EV_ALLOC, stage, node, -1, cls, bytes);
         return off;
     };
     auto arena_free = [&](int stage, int node, int cls, int64_t off, int64_t bytes) {
-        arena.release(off, bytes);
+        if (!launches.empty() && chainable(launches.back())) pending.push_back(Pending{launches.size(), off, bytes});
+        else arena.release(off, bytes);
         ev(EV_FREE, stage, node, -1, cls, bytes);
         poison.push_back(PoisonFill{launches.size(), off, bytes});
     };
@@ -471,6 +505,7 @@ void Plan::lower() {
         Launch L;
         L.kind = kind; L.id = i; L.impl = l;
         L.flags = (im.inplace ? 1u : 0u) | (emit.empty() ? 0u : 2u);
+        begin_launch(chainable(L));
         for (size_t p = 0; p < n.ins.size() && p < 2; ++p) L.a[p] = fwd_ref(n.ins[p], who);
         if (n.persist) { L.a[2].region = R_PERSIST; L.a[2].off = loss_off; }
         else if (im.inplace) L.a[2] = L.a[0];
@@ -562,6 +597,7 @@ void Plan::lower() {
         std::string who = "backward operator " + std::to_string(k);
         Launch L;
         L.kind = EV_RUN_BWD; L.id = k; L.impl = l;
+        begin_launch(chainable(L));
         if (!n.persist) {
             auto gi = grads.find(b.node);
             if (gi == grads.end()) throw PlanError(MONET_BAD_GRAPH, who + " has no incoming gradient");
@@ -601,6 +637,7 @@ void Plan::lower() {
     if (!held.empty() || !grads.empty() || live != 0)
         throw PlanError(MONET_INFEASIBLE, "tensors are left in memory after the last stage");
     exact_peak = peak;
+    flush_pending(true);
     dynamic_bytes = arena.high;
 }
 

@@ -90,8 +90,29 @@ def deps_of(g: Graph, k, l):
     return [d for d in g.bimpls[k][l]["deps"] if d > 0]
 
 
-def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm_splitk"):
-    """Schedule for forward-saved set F (node ids) and backward impl choice {k: l}."""
+def residual_tail_stages(g: Graph):
+    """{k of a ReLU backward: k of the BatchNorm backward two stages later} for block tails
+    BatchNorm -> add -> ReLU, whose backward operators run back to back (k, k-1, k-2)."""
+    out = {}
+    for b in g.bops:
+        k = b["k"]
+        if b["kind"] not in ("relu_bwd", "relu6_bwd") or k < 3:
+            continue
+        relu = g.nodes[b["node"] - 1]
+        b1, b2 = g.bops[k - 2], g.bops[k - 3]          # stages k-1 and k-2
+        if b1["kind"] != "add_bwd" or b1["node"] != relu.ins[0] or b2["kind"] != "bn_bwd":
+            continue
+        if b2["node"] in g.nodes[b1["node"] - 1].ins:
+            out[k] = k - 2
+    return out
+
+
+def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm_splitk", hoist_residual_tail=False):
+    """Schedule for forward-saved set F (node ids) and backward impl choice {k: l}.
+
+    With `hoist_residual_tail`, what the BatchNorm backward at the tail of a residual block needs is already
+    recomputed in the stage of the block's final ReLU backward, two stages earlier: the three backward
+    operators then run back to back (and can share a kernel) instead of having the recomputation between them."""
     N, B = len(g.nodes), len(g.bops)
     sch = Schedule(N, B)
     F = set(F)
@@ -140,8 +161,10 @@ def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm_splitk"):
     for k in range(1, B + 1):
         for d in deps_of(g, k, bimpl[k]):
             dep_stages.setdefault(d, []).append(k)
+    hoisted = residual_tail_stages(g) if hoist_residual_tail else {}
     for k in range(B, 0, -1):
         need = deps_of(g, k, bimpl[k])
+        early = deps_of(g, hoisted[k], bimpl[hoisted[k]]) if k in hoisted else []
         todo = set()
 
         def want(t):
@@ -175,6 +198,10 @@ def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm_splitk"):
             want(t)
         for t in need:
             last_use[t] = k
+        for t in early:
+            want(t)
+        for t in early:
+            last_use[t] = hoisted[k]
         for t in todo:
             born[t] = k
         present |= todo
@@ -281,7 +308,8 @@ def schedule_for_saved_set(g: Graph, F, variants=None):
         for d in deps_of(g, b["k"], bimpl[b["k"]]):
             if g.is_aux(d) and g.nodes[d - 1].ins[0] in F:
                 F.add(d)
-    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True), conv_algo=variants.get("conv_fwd", "igemm"))
+    return expand(g, F, bimpl, allow_inplace=variants.get("inplace", True), conv_algo=variants.get("conv_fwd", "igemm"),
+                  hoist_residual_tail=True)
 
 
 def block_checkpoint_schedule(g: Graph, keep, variants=None):
