@@ -22,14 +22,26 @@
 extern "C" {
 #endif
 
-/* All three convolution kernels take `splits`: 1 = no workspace; > 1 cuts the reduction into that
- * many ranges whose partial results go to ws (>= splits * |output| floats, device memory) and are then
- * added in range order -- more workgroups for layers whose output is small, at the price of workspace.
+/* All three convolution kernels take `splits`: > 1 cuts the reduction into that many ranges -- more workgroups
+ * for layers whose result is small, at the price of workspace (device memory, contents irrelevant before and
+ * after the call).  The partial results are always added in range order, so a result depends on `splits` and
+ * the workspace size only.
+ *   splits > 1: ws >= splits * |result| floats; a second kernel adds the partial results.
+ *   fwd, dgrad with splits == 1 and a workspace: only the tiles of the ragged last round (beyond a multiple of
+ *     the 256 CUs) are cut, as far as the workspace allows (monet_conv_workspace_bytes gives the useful size);
+ *     their partial tiles wait in ws and the workgroup that finishes a tile last adds them.  Arrival counts live
+ *     in a table inside the library: convolution calls that overlap in time on one GPU (different streams) must
+ *     not both pass such a workspace.  With ws == NULL nothing is cut.
+ * Appendix D's workspace / speed trade-off of convolution algorithms is this choice.
  *
  * y[N,P,Q,K] = cross-correlation of x[N,H,W,C] with w[K,R,S,C], zero padding, no bias. */
 int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
                    int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                    int splits, float *ws, size_t ws_bytes);
+/* Workspace bytes for monet_conv_fwd (which = 0) / monet_conv_dgrad (which = 1) of this shape with `splits` ranges;
+ * for splits == 1 the size that lets the ragged last round be cut as far as it pays (0: nothing to gain).
+ * Negative: error code. */
+int64_t monet_conv_workspace_bytes(int which, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int splits);
 /* dx[N,H,W,C] (+)= gradient of the above wrt x, from dy[N,P,Q,K]. */
 int monet_conv_dgrad(void *stream, const float *dy, const float *w, float *dx,
                      int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int accumulate,

@@ -768,7 +768,7 @@ void linear_bias_grad(hipStream_t st, const float *dy, float *db, int N, int out
 // results in the caller's scratch, added in range order) until about a thousand workgroups exist.
 static int linear_splits(int64_t rows, int64_t cols, int64_t reduction, int64_t out_elems, size_t scratch_bytes) {
     int64_t tiles = ((rows + 127) / 128) * ((cols + 127) / 128);
-    int64_t sp = std::min<int64_t>({(1024 + tiles - 1) / tiles, reduction / 128, (int64_t)(scratch_bytes / (4 * out_elems)), (int64_t)64});
+    int64_t sp = std::min<int64_t>({1024 / tiles, reduction / 128, (int64_t)(scratch_bytes / (4 * out_elems)), (int64_t)64});
     return (int)std::max<int64_t>(1, sp);
 }
 
@@ -814,6 +814,15 @@ static PoolShape mk_pool(int N, int H, int W, int C, int k, int stride, int pad)
 extern "C" int monet_conv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
                               int stride, int pad, int splits, float *ws, size_t ws_bytes) {
     return guarded([&] { conv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad), splits, ws, ws_bytes); });
+}
+extern "C" int64_t monet_conv_workspace_bytes(int which, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int splits) {
+    int64_t bytes = -1;
+    int rc = guarded([&] {
+        if (which != 0 && which != 1) throw KernelError("monet_conv_workspace_bytes: which must be 0 (forward) or 1 (input gradient)");
+        if (splits < 1) throw KernelError("monet_conv_workspace_bytes: splits must be >= 1");
+        bytes = (int64_t)conv_workspace_bytes(which, mk_conv(N, H, W, C, K, R, S, stride, pad), splits);
+    });
+    return rc == MONET_OK ? bytes : (int64_t)rc;
 }
 extern "C" int monet_conv_dgrad(void *stream, const float *dy, const float *w, float *dx, int N, int H, int W, int C, int K, int R, int S,
                                 int stride, int pad, int accumulate, int splits, float *ws, size_t ws_bytes) {

@@ -59,8 +59,18 @@ struct TileArgs {
     int64_t total_tiles;
     int splits;                // reduction splits (>= 1); split z writes partial result z
     int64_t out_elems;         // elements of one (partial) result
-    int accumulate;            // DGRAD, splits == 1: add into dx
+    int accumulate;            // FWD/DGRAD, whole result only: add into the output
+    // Split tiles that meet inside the kernel (FWD/DGRAD): tiles [main_tiles, total_tiles) are cut into
+    // meet_splits reduction ranges, each workgroup leaves its partial tile in `part`, and the one that
+    // arrives last adds the parts in range order and writes the result.  Tiles below main_tiles are whole.
+    int64_t main_tiles;        // multiple of 8
+    int meet_splits;           // <= 1: off
+    float *part;               // (class, tile - main_tiles, range) x 64 x threads floats, register order
 };
+
+// arrivals per split tile; zero whenever no convolution kernel is running (the last arrival puts its entry back)
+constexpr int MEET_SLOTS = 1 << 16;
+__device__ unsigned g_meet_arrivals[MEET_SLOTS];
 
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
@@ -89,12 +99,35 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     const int l32 = lane & 31, g = lane >> 5;
 
     // XCD-aware order of the (tile, split) work items
-    const int nsplit = ta.splits;
-    const int64_t per_xcd = gridDim.x / NUM_XCD;
-    const int64_t item = (int64_t)(blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
-    if (item >= ta.total_tiles * nsplit) return;
-    const int split = (int)(item / ta.total_tiles);
-    const int64_t logical = item - (int64_t)split * ta.total_tiles;
+    int nsplit = ta.splits, split;
+    int64_t logical;
+    bool meet = false;
+    if (MODE != WGRAD && ta.meet_splits > 1) {
+        // every XCD takes its share of the whole tiles first, then its share of the split ones, so the short
+        // items come last everywhere and fill the ragged end of the launch
+        const int64_t xcd = blockIdx.x % NUM_XCD, idx = blockIdx.x / NUM_XCD;
+        const int64_t pm = ta.main_tiles / NUM_XCD;
+        if (idx < pm) {
+            logical = xcd * pm + idx;
+            split = 0;
+            nsplit = 1;
+        } else {
+            const int64_t nt = (ta.total_tiles - ta.main_tiles) * ta.meet_splits;
+            const int64_t pt = (nt + NUM_XCD - 1) / NUM_XCD;
+            const int64_t j = xcd * pt + (idx - pm);
+            if (idx - pm >= pt || j >= nt) return;
+            logical = ta.main_tiles + j / ta.meet_splits;
+            split = (int)(j % ta.meet_splits);
+            nsplit = ta.meet_splits;
+            meet = true;
+        }
+    } else {
+        const int64_t per_xcd = gridDim.x / NUM_XCD;
+        const int64_t item = (int64_t)(blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+        if (item >= ta.total_tiles * nsplit) return;
+        split = (int)(item / ta.total_tiles);
+        logical = item - (int64_t)split * ta.total_tiles;
+    }
     const int tile_n = (int)(logical % ta.tiles_n);
     const int64_t tile_m = logical / ta.tiles_n;
     const int64_t row0 = tile_m * BM;
@@ -507,8 +540,54 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
 
     // ---------------- epilogue: lane holds column l32 of rows 8*(v/4) + 4*g + v%4 of each 32x32 block
     float *out = ta.out;
-    out += (int64_t)split * ta.out_elems;
-    const bool do_acc = MODE != WGRAD && ta.accumulate && nsplit == 1;
+    if (!meet) out += (int64_t)split * ta.out_elems;
+    const bool do_acc = MODE != WGRAD && ta.accumulate && (nsplit == 1 || meet);
+    if (MODE != WGRAD && meet) {
+        // Leave this range's partial tile (register order: 16 float4 per lane, each wave instruction writes
+        // 1 KiB in a row), then count the arrival.  Release before the count and acquire after it order the
+        // parts of the other workgroups, on whichever XCD they ran, before the loads below.
+        const int64_t uid = (MODE == DGRAD ? (int64_t)blockIdx.z * (ta.total_tiles - ta.main_tiles) : 0) + (logical - ta.main_tiles);
+        float *tile_part = ta.part + uid * nsplit * (int64_t)(64 * NT);
+        {
+            float4 *mine = (float4 *)(tile_part + (int64_t)split * (64 * NT));
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const floatx16 &a = acc[b >> 1][b & 1];
+                    mine[(b * 4 + q4) * NT + tid] = float4{a[4 * q4], a[4 * q4 + 1], a[4 * q4 + 2], a[4 * q4 + 3]};
+                }
+        }
+        __threadfence();
+        __syncthreads();                                       // also: every wave is done with the operand tiles in LDS
+        unsigned *slot = (unsigned *)&As[0][0];                // LDS is full (four workgroups per CU): borrow a word
+        if (tid == 0) *slot = atomicAdd(&g_meet_arrivals[uid], 1u);
+        __syncthreads();
+        const unsigned arrived = *slot;
+        if (arrived != (unsigned)(nsplit - 1)) return;
+        __threadfence();
+        if (tid == 0) g_meet_arrivals[uid] = 0;
+        // last to arrive: add the parts in range order (its own comes back from memory like the others, so
+        // the sum does not depend on which range arrived last)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            floatx16 t;
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                float4 v = ((const float4 *)tile_part)[(b * 4 + q4) * NT + tid];
+                t[4 * q4] = v.x; t[4 * q4 + 1] = v.y; t[4 * q4 + 2] = v.z; t[4 * q4 + 3] = v.w;
+            }
+            for (int z = 1; z < nsplit; ++z) {
+                const float4 *src = (const float4 *)(tile_part + (int64_t)z * (64 * NT));
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 v = src[(b * 4 + q4) * NT + tid];
+                    t[4 * q4] += v.x; t[4 * q4 + 1] += v.y; t[4 * q4 + 2] += v.z; t[4 * q4 + 3] += v.w;
+                }
+            }
+            acc[b >> 1][b & 1] = t;
+        }
+    }
     if (FAST && (ta.Ng & 3) == 0) {
         // Vector path: each wave transposes its 64x64 result through a private 16x64 LDS patch, four
         // passes of 16 rows, and writes whole 16-byte pieces, 256 contiguous bytes per row.
@@ -625,18 +704,57 @@ void check_shape(const ConvShape &cs) {
     if (cs.stride > 8) throw KernelError("conv: stride too large");
 }
 
+// How a launch divides its reduction.  `splits` > 1 asks for that many ranges on every tile: partial results go
+// to `splits` full-size slabs that a second kernel adds in range order.  `splits` == 1 with a workspace (FWD /
+// DGRAD at stride 1) lets the ragged last round, the tiles beyond a multiple of the CU count, be cut as far as the
+// workspace allows; those partial tiles meet inside the kernel.  (Letting every tile of a launch meet that way
+// was measured too: the device-wide release each split workgroup performs costs more than the second kernel.)
+constexpr int NUM_CU = 256;
+
 template <int MODE, int WM, int WN>
-void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim) {
+void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim, float *out, int splits, float *ws, size_t ws_bytes, int64_t steps,
+                 bool accumulate, const char *who) {
     constexpr int BM = 64 * WM, BN = 64 * WN, NT = 64 * WM * WN;
+    if (splits < 1) throw KernelError(std::string(who) + ": splits must be >= 1");
+    if (splits > steps) splits = (int)std::max<int64_t>(steps, 1);
     int64_t tiles_m = (ta.Mg + BM - 1) / BM;
     ta.tiles_n = (ta.Ng + BN - 1) / BN;
     ta.total_tiles = tiles_m * ta.tiles_n;
-    int64_t blocks = (ta.total_tiles * ta.splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    ta.out = out;
+    ta.splits = 1;
+    ta.accumulate = accumulate ? 1 : 0;
+    ta.main_tiles = 0;
+    ta.meet_splits = 0;
+    ta.part = nullptr;
+    const size_t tile_bytes = (size_t)BM * BN * sizeof(float);
+    bool slabs = false;
+    if (splits > 1) {
+        if (!ws || ws_bytes < (size_t)splits * ta.out_elems * 4) throw KernelError(std::string(who) + ": workspace too small for the requested splits");
+        slabs = true;
+        ta.out = ws;
+        ta.splits = splits;
+    } else if (MODE != WGRAD && zdim == 1 && ws && ta.total_tiles % NUM_CU) {
+        const int64_t tail = ta.total_tiles % NUM_CU;
+        int64_t s = std::min<int64_t>({NUM_CU / tail, steps / 4, 16, (int64_t)(ws_bytes / (tail * tile_bytes))});
+        if (s >= 2) {
+            ta.main_tiles = ta.total_tiles - tail;
+            ta.meet_splits = (int)s;
+            ta.part = ws;
+        }
+    }
+    int64_t blocks;
+    if (ta.meet_splits > 1) {
+        const int64_t nt = (ta.total_tiles - ta.main_tiles) * ta.meet_splits;
+        blocks = (ta.main_tiles / NUM_XCD + (nt + NUM_XCD - 1) / NUM_XCD) * NUM_XCD;
+    } else {
+        blocks = (ta.total_tiles * ta.splits + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
+    }
     if (blocks > 0x7fffffffll) throw KernelError("conv: too many tiles");
     dim3 grid((unsigned)blocks, 1, (unsigned)zdim);
     if (fast) hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true>), grid, dim3(NT), 0, st, ta);
     else hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, false>), grid, dim3(NT), 0, st, ta);
     hip_check(hipGetLastError(), "conv launch");
+    if (slabs) launch_split_reduce(st, ws, out, ta.out_elems, splits, MODE != WGRAD && accumulate);
 }
 
 // Tile shapes: index -> waves (rows x columns of 64x64 wave tiles)
@@ -655,15 +773,15 @@ int pick_cfg(int mode, int64_t Mg, int64_t Ng) {
     return Ng <= 64 ? 1 : 0;
 }
 
-template <int MODE>
-void launch_cfg(hipStream_t st, const TileArgs &ta, bool fast, int zdim, int cfg) {
+template <int MODE, class... Rest>
+void launch_cfg(int cfg, Rest... rest) {
     switch (cfg) {
-        case 0: launch_tile<MODE, 2, 2>(st, ta, fast, zdim); break;
-        case 1: launch_tile<MODE, 4, 1>(st, ta, fast, zdim); break;
-        case 2: launch_tile<MODE, 1, 4>(st, ta, fast, zdim); break;
-        case 3: launch_tile<MODE, 2, 1>(st, ta, fast, zdim); break;
-        case 4: launch_tile<MODE, 1, 2>(st, ta, fast, zdim); break;
-        default: launch_tile<MODE, 1, 1>(st, ta, fast, zdim); break;
+        case 0: launch_tile<MODE, 2, 2>(rest...); break;
+        case 1: launch_tile<MODE, 4, 1>(rest...); break;
+        case 2: launch_tile<MODE, 1, 4>(rest...); break;
+        case 3: launch_tile<MODE, 2, 1>(rest...); break;
+        case 4: launch_tile<MODE, 1, 2>(rest...); break;
+        default: launch_tile<MODE, 1, 1>(rest...); break;
     }
 }
 
@@ -671,13 +789,29 @@ void launch_cfg(hipStream_t st, const TileArgs &ta, bool fast, int zdim, int cfg
 
 void conv_force_tile(int cfg) { g_cfg_override = cfg; }
 
-// splits > 1: partial results go to ws (splits * |out| floats) and are added in split order
-static float *split_target(float *out, int64_t out_elems, int &splits, float *ws, size_t ws_bytes, int64_t steps, const char *who) {
-    if (splits < 1) throw KernelError(std::string(who) + ": splits must be >= 1");
-    if (splits > steps) splits = (int)std::max<int64_t>(steps, 1);
-    if (splits == 1) return out;
-    if (!ws || ws_bytes < (size_t)splits * out_elems * 4) throw KernelError(std::string(who) + ": workspace too small for the requested splits");
-    return ws;
+namespace {
+struct SplitGemm { int64_t rows, cols, steps; int classes; };
+SplitGemm split_gemm_of(int which, const ConvShape &cs) {
+    if (which == 0) return {cs.M(), cs.K, (cs.RSC() + BK - 1) / BK, 1};
+    const int st = cs.stride;
+    return {(int64_t)cs.N * ((cs.H + st - 1) / st) * ((cs.W + st - 1) / st), cs.C,
+            ((int64_t)std::max(1, cs.R / st) * std::max(1, cs.S / st) * cs.K + BK - 1) / BK, st * st};
+}
+}  // namespace
+
+size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
+    check_shape(cs);
+    const SplitGemm sg = split_gemm_of(which, cs);
+    if (splits > sg.steps) splits = (int)std::max<int64_t>(sg.steps, 1);
+    if (splits > 1) return (size_t)splits * 4 * (which == 0 ? cs.M() * cs.K : (int64_t)cs.N * cs.H * cs.W * cs.C);
+    static const int shape[6][2] = {{128, 128}, {256, 64}, {64, 256}, {128, 64}, {64, 128}, {64, 64}};
+    const int cfg = pick_cfg(FWD, sg.rows, sg.cols);
+    const int64_t bm = shape[cfg][0], bn = shape[cfg][1];
+    const int64_t tiles = ((sg.rows + bm - 1) / bm) * ((sg.cols + bn - 1) / bn);
+    const int64_t tail = tiles % NUM_CU;
+    if (sg.classes != 1 || tail == 0) return 0;
+    const int64_t s = std::min<int64_t>({NUM_CU / tail, sg.steps / 4, 16});
+    return s >= 2 ? (size_t)(s * tail * bm * bn * 4) : 0;
 }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,
@@ -687,12 +821,8 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
     ta.a = x; ta.b = w; ta.cs = cs;
     ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
     ta.out_elems = ta.Mg * ta.Ng;
-    ta.out = split_target(y, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_fwd");
-    ta.splits = splits;
-    ta.accumulate = accumulate ? 1 : 0;
     bool fast = cs.C % BK == 0;
-    launch_cfg<FWD>(st, ta, fast, 1, pick_cfg(FWD, ta.Mg, ta.Ng));
-    if (splits > 1) launch_split_reduce(st, ws, y, ta.out_elems, splits, accumulate);
+    launch_cfg<FWD>(pick_cfg(FWD, ta.Mg, ta.Ng), st, ta, fast, 1, y, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, accumulate, "conv_fwd");
 }
 
 void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits, float *ws,
@@ -700,20 +830,13 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
     check_shape(cs);
     TileArgs ta{};
     ta.a = dy; ta.b = w; ta.cs = cs;
-    const int stc = cs.stride;
-    ta.Mg = (int64_t)cs.N * ((cs.H + stc - 1) / stc) * ((cs.W + stc - 1) / stc);   // rows of residue class (0,0), the largest
+    const SplitGemm sg = split_gemm_of(1, cs);   // rows of residue class (0,0), the largest; the shortest class reduction bounds the splits
+    ta.Mg = sg.rows;
     ta.Ng = cs.C;
     ta.Kg = 0;   // per class, computed in the kernel
     ta.out_elems = (int64_t)cs.N * cs.H * cs.W * cs.C;
-    // the shortest class reduction bounds the useful number of splits
-    int64_t min_steps = ((int64_t)std::max(1, cs.R / stc) * std::max(1, cs.S / stc) * cs.K + BK - 1) / BK;
-    ta.out = split_target(dx, ta.out_elems, splits, ws, ws_bytes, min_steps, "conv_dgrad");
-    ta.splits = splits;
-    ta.accumulate = accumulate ? 1 : 0;
     bool fast = cs.K % BK == 0 && cs.C % 4 == 0;
-    int zdim = stc * stc;
-    launch_cfg<DGRAD>(st, ta, fast, zdim, pick_cfg(DGRAD, ta.Mg, ta.Ng));
-    if (splits > 1) launch_split_reduce(st, ws, dx, ta.out_elems, splits, accumulate);
+    launch_cfg<DGRAD>(pick_cfg(DGRAD, ta.Mg, ta.Ng), st, ta, fast, sg.classes, dx, splits, ws, ws_bytes, sg.steps, accumulate, "conv_dgrad");
 }
 
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
@@ -722,11 +845,8 @@ void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, cons
     ta.a = dy; ta.b = x; ta.cs = cs;
     ta.Mg = cs.K; ta.Ng = (int)cs.RSC(); ta.Kg = cs.M();
     ta.out_elems = (int64_t)cs.K * cs.RSC();
-    ta.out = split_target(dw, ta.out_elems, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, "conv_wgrad");
-    ta.splits = splits;
     bool fast = cs.K % 4 == 0 && cs.C % 4 == 0;
-    launch_cfg<WGRAD>(st, ta, fast, 1, pick_cfg(WGRAD, ta.Mg, ta.Ng));
-    if (splits > 1) launch_split_reduce(st, ws, dw, ta.out_elems, splits, false);
+    launch_cfg<WGRAD>(pick_cfg(WGRAD, ta.Mg, ta.Ng), st, ta, fast, 1, dw, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, false, "conv_wgrad");
 }
 
 }  // namespace monet

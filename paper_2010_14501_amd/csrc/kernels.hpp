@@ -49,6 +49,9 @@ void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, co
 
 // tuning aid: cfg 0..5 forces tile shape (2x2, 4x1, 1x4, 2x1, 1x2, 1x1 waves of 64x64); -1 restores the heuristic
 void conv_force_tile(int cfg);
+// workspace bytes of conv_fwd (which = 0) / conv_dgrad (which = 1) for `splits` ranges; for splits = 1 the bytes
+// with which the ragged last round of tiles is cut as far as it pays (0 if there is nothing to gain)
+size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits);
 
 // ---- BatchNorm over rows x C (rows = N*H*W), training mode, biased variance
 constexpr int64_t kBnScratchFloats = 1 << 20;

@@ -61,7 +61,8 @@ def test_conv_trio_matches_oracle(case):
     monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, None, 0)
     want = wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad))
     assert rel(y.cpu().numpy(), want) < ACT_TOL
-    big = torch.empty(5 * max(y.numel(), N * H * W * C), dtype=torch.float32, device="cuda")     # split workspace
+    need = max(monet.call("monet_conv_workspace_bytes", which, N, H, W, C, K, R, R, stride, pad, 5) for which in (0, 1))
+    big = torch.empty(need // 4, dtype=torch.float32, device="cuda")     # split workspace
     for splits in (2, 5):
         y.fill_(float("nan"))
         monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad,
@@ -90,6 +91,38 @@ def test_conv_trio_matches_oracle(case):
         monet.call("monet_conv_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, R, R, stride, pad,
                    splits, ws.data_ptr(), ws.numel() * 4)
         assert rel(gw.cpu().numpy(), want) < GRAD_TOL, splits
+
+
+def test_conv_ragged_last_round_is_split_and_counts_reset():
+    """More than 256 tiles and not a multiple of it: with a workspace the tiles of the last round are cut and meet
+    inside the kernel.  Several calls in a row (the arrival table has to be back at zero each time), forward and
+    input gradient with accumulation, against the oracle and against the uncut kernel."""
+    torch = torch_mod()
+    N, H, W, C, K, R, stride, pad = 48, 28, 28, 128, 128, 1, 1, 0          # 37632 rows = 294 tiles of 128
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / C)))
+    dy = rng.standard_normal((N, H, W, K), dtype=np.float32)
+    xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
+    dx, dwt, ddy = dev(x), dev(w), dev(dy)
+    need = [monet.call("monet_conv_workspace_bytes", which, N, H, W, C, K, R, R, stride, pad, 1) for which in (0, 1)]
+    assert need[0] == need[1] == 2 * 38 * 128 * 128 * 4                      # 38 tiles beyond 256, two ranges of four steps
+    ws = torch.full((need[0] // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    want_y = wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad))
+    want_dx = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, stride, pad))
+    y0 = torch.empty((N, H, W, K), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y0.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, None, 0)
+    for rep in range(3):
+        y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, ws.data_ptr(), need[0])
+        assert rel(y.cpu().numpy(), want_y) < ACT_TOL, rep
+        assert torch.equal(y[:32], y0[:32])                                   # whole tiles: same kernel path, same bits
+        assert rel(y.cpu().numpy(), y0.cpu().numpy()) < 1e-6
+        gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0, 1, ws.data_ptr(), need[1])
+        assert rel(gx.cpu().numpy(), want_dx) < GRAD_TOL, rep
+        monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, 1, ws.data_ptr(), need[1])
+        assert rel(gx.cpu().numpy(), 2 * want_dx) < GRAD_TOL, rep
 
 
 def test_conv_wgrad_rejects_small_workspace():

@@ -113,13 +113,14 @@ class Graph:
         self.fimpls[i] = [dict(algo="igemm", ws=0, cost=flop)]
         # Layers with few output tiles leave most of the 256 CUs idle: offer a variant that cuts the
         # reduction into `splits` ranges (more workgroups) and pays for it with workspace.
-        sp = _fill_splits(N * P * Q, K, C * R * S)
-        if sp > 1:
-            self.fimpls[i].append(dict(algo="igemm_splitk", ws=_align(sp * 4 * N * P * Q * K), cost=flop * 0.8, splits=sp))
+        sp, ws = conv_split_plan(N * P * Q, K, C * R * S)
+        if ws:
+            self.fimpls[i].append(dict(algo="igemm_splitk", ws=ws, cost=flop * 0.8, splits=sp))
         dg = [dict(algo="igemm", deps=[], ws=0, cost=flop)]
-        sp = _fill_splits(N * H * W // (stride * stride), C, max(1, R // stride) * max(1, S // stride) * K)
-        if sp > 1:
-            dg.append(dict(algo="igemm_splitk", deps=[], ws=_align(sp * 4 * N * H * W * C), cost=flop * 0.8, splits=sp))
+        sp, ws = conv_split_plan(N * math.ceil(H / stride) * math.ceil(W / stride), C,
+                                 max(1, R // stride) * max(1, S // stride) * K, stride * stride, N * H * W * C)
+        if ws:
+            dg.append(dict(algo="igemm_splitk", deps=[], ws=ws, cost=flop * 0.8, splits=sp))
         wbytes = 4 * K * R * S * C
         wg = [dict(algo="direct", ws=0, cost=flop * 4.0)]
         for sp in wgrad_splits:
@@ -326,13 +327,40 @@ class Graph:
         return "\n".join(out) + "\n"
 
 
-def _fill_splits(rows, cols, reduction):
-    """Reduction splits for a rows x cols GEMM with 128x128 tiles: aim at about four workgroups per CU,
-    keep at least eight reduction steps of 16 per split."""
-    tiles = math.ceil(rows / 128) * math.ceil(cols / 128)
-    if tiles >= 1024:
-        return 1
-    return max(1, min(math.ceil(1200 / tiles), reduction // 128, 16))
+def conv_split_plan(rows, cols, reduction, classes=1, out_elems=None):
+    """(splits, workspace bytes) of the reduction-split variant of a forward / input-gradient GEMM with a
+    rows x cols result per residue class (`classes` = stride^2 and `out_elems` = |dx| for the input gradient),
+    or (1, 0) where the plain variant is as fast.
+
+    The kernel library works on 128x128 tiles (256x64 for results up to 64 columns wide), one workgroup per
+    tile and reduction range, and a CU's time grows with the number of workgroups it is handed: a launch costs
+    ceil(workgroups / 256) rounds.  Rules read off a sweep over the ResNet-50 b184 layers:
+      * fewer than two tiles per CU (or fewer than eight with stride > 1): cut every tile into the number of
+        ranges s (at most 16, at least 128 reduction elements each) that minimises rounds / s, with 1 % per range
+        for the slabs of partial results a second kernel adds;
+      * otherwise, stride 1, at least 48 reduction steps of 16: `splits` stays 1 and a workspace lets the library
+        cut only the tiles beyond a multiple of 256, into as many ranges as keep them within one round (their
+        parts are added inside the kernel; with a short reduction the device-wide release this needs costs
+        more than the idle CUs);
+      * otherwise: plain."""
+    bm, bn = (256, 64) if cols <= 64 else (128, 128)
+    tiles = math.ceil(rows / bm) * math.ceil(cols / bn)
+    steps = math.ceil(reduction / 16)
+    items = tiles * classes
+    out_elems = rows * cols * classes if out_elems is None else out_elems
+    if items < (512 if classes == 1 else 2048):
+        best, best_cost = 1, None
+        for s in range(1, max(1, min(16, reduction // 128)) + 1):
+            cost = math.ceil(items * s / 256) / s * (1 + 0.01 * s)
+            if best_cost is None or cost < best_cost - 1e-9:
+                best, best_cost = s, cost
+        return (best, _align(best * 4 * out_elems)) if best > 1 else (1, 0)
+    tail = tiles % 256
+    if classes == 1 and tail and steps >= 48:
+        s = min(256 // tail, steps // 4, 16)
+        if s >= 2:
+            return 1, _align(s * tail * 4 * bm * bn)
+    return 1, 0
 
 
 def wgrad_split_count(M, K, cols):
@@ -347,7 +375,9 @@ def wgrad_split_count(M, K, cols):
     else:
         tile_rows, tile_cols, waves = (128, 128, 4)
     tiles = math.ceil(K / tile_rows) * math.ceil(cols / tile_cols)
-    sp = math.ceil(4096 / (tiles * waves))
+    # a CU's time grows with the number of workgroups it is handed, so the total stays at or just under a
+    # whole number of workgroups per CU (1024 four-wave workgroups = 4 per CU): one workgroup over costs a full round
+    sp = max(1, 4096 // (tiles * waves))
     return max(1, min(sp, M // 128, (128 << 20) // (4 * K * cols)))
 
 
