@@ -56,7 +56,9 @@ def build_workload(name):
             "unet_b11": (lambda: graphs.unet(batch=11), 11, schedules.unet_skip_schedule,
                          "forward pass keeps the skip tensors only"),
             "mobilenetv2_b272": (lambda: graphs.mobilenet_v2(batch=272), 272, schedules.mobilenet_depthwise_schedule,
-                                 "depthwise triples recomputed")}
+                                 "depthwise triples recomputed"),
+            "googlenet_b320": (lambda: graphs.googlenet(batch=320), 320, schedules.googlenet_alternate_schedule,
+                               "every second block (stem stage / inception module) recomputed")}
     for base, (make, batch, named, desc) in nets.items():
         if name == base:
             g = make()
@@ -99,6 +101,10 @@ def cpu_baseline(workload):
         batch = 16
         g = graphs.mobilenet_v2(batch=batch)
         sample = "same MobileNetV2 graph at batch 16 (224x224), one store-everything fp64 step"
+    elif workload.startswith("googlenet_b320"):
+        batch = 32
+        g = graphs.googlenet(batch=batch)
+        sample = "same inception graph at batch 32 (224x224), one store-everything fp64 step"
     else:
         batch = 2
         g = graphs.tiny_chain()

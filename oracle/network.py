@@ -28,9 +28,10 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, dec
 
     `get(ref)` returns an input array.  BatchNorm statistics are taken from
     `stats[n.id]` on recomputation (Appendix D: statistics are reused) and
-    written there otherwise.  `ties` = (band, {relu node: boolean array}) resolves ReLU
-    decisions that fp32 cannot decide (see numerics.resolve_pass); the decisions taken are
-    written to `decisions[n.id]` so that the backward operator takes the same ones.
+    written there otherwise.  `ties` = (band, {relu node: boolean array, max-pool node: tap indices})
+    resolves ReLU decisions and window maxima that fp32 cannot decide (see numerics.resolve_pass,
+    numerics.resolve_argmax); the decisions taken are written to `decisions[n.id]` so that the backward
+    operator takes the same ones.
     """
     a = n.attrs
     x = get(n.ins[0])
@@ -58,6 +59,9 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, dec
         aux["mask"] = lambda: nm.pack_mask(passes)
     elif n.op == "maxpool":
         y, idx = nm.maxpool_fwd(x, int(a["k"]), int(a["stride"]), int(a["pad"]))
+        if ties is not None and n.id in ties[1]:
+            idx, undecided = nm.resolve_argmax(x, idx, y, ties[1][n.id], ties[0], int(a["k"]), int(a["stride"]), int(a["pad"]))
+            decisions[n.id] = (idx, undecided)
         aux["poolidx"] = lambda: idx
     elif n.op == "tconv":
         y = nm.tconv2d_fwd(x, params[n.pars[0]], int(a["stride"]))
@@ -132,7 +136,9 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
     if kind == "maxpool_bwd":
         xs = nchw_shape(g.shape_of(n.ins[0]))
         k, st, pd = int(a["k"]), int(a["stride"]), int(a["pad"])
-        if algo == "from_input":
+        if decisions is not None and n.id in decisions:
+            dx = nm.maxpool_bwd_from_index(gy, decisions[n.id][0], xs, k, st, pd)
+        elif algo == "from_input":
             dx = nm.maxpool_bwd_from_input(gy, get(n.ins[0]), k, st, pd)
         elif algo == "from_index":
             dx = nm.maxpool_bwd_from_index(gy, get(g.aux_children[n.id][0]), xs, k, st, pd)

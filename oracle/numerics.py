@@ -288,6 +288,28 @@ def maxpool_fwd(x, k, stride, pad):
     return best, idx
 
 
+def resolve_argmax(x, idx, best, given, band, k, stride, pad):
+    """Window maxima that fp32 cannot tell apart.
+
+    An fp32 computation reproduces x only to within the activation tolerance, so a tap whose value lies
+    within band * rms(x) of the window maximum is as valid a (sub)gradient route as the maximum itself.
+    `given` names one tap per window (r*k+s); it is taken where it is such a tap, the strict choice `idx`
+    stands everywhere else (also where `given` points at padding or outside the window).  The forward value
+    stays the maximum.  Returns (indices, undecided) with undecided = windows where `given` replaced `idx`."""
+    N, C, H, W = x.shape
+    P, Q = best.shape[2:]
+    xp = np.full((N, C, H + 2 * pad, W + 2 * pad), -np.inf, F64)
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    val = np.full(best.shape, -np.inf, F64)
+    for r in range(k):
+        for s in range(k):
+            win = xp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
+            val = np.where(given == r * k + s, win, val)
+    lim = band * np.sqrt(np.mean(x * x))
+    undecided = (given != idx) & (best - val < lim)
+    return np.where(undecided, given, idx).astype(np.uint8), undecided
+
+
 def maxpool_bwd_from_index(dy, idx, x_shape, k, stride, pad):
     N, C, H, W = x_shape
     _, _, P, Q = dy.shape

@@ -42,7 +42,7 @@ def to_oracle_shape(shape):
 
 
 def gpu_relu_decisions(g, exts, params):
-    """ReLU pass bits as the GPU took them, and its BatchNorm outputs: a store-everything run (the lean
+    """ReLU pass bits and max-pool tap indices as the GPU took them, and its BatchNorm outputs: a store-everything run (the lean
     variants keep every mask, nothing in place), stopped after the last forward operator."""
     import torch
     import paper_2010_14501_amd as M
@@ -63,14 +63,17 @@ def gpu_relu_decisions(g, exts, params):
             relu = g.nodes[n.ins[0] - 1]
             words = run.read(off, (n.shape[0],), torch.int64).view(np.uint64)
             out[relu.id] = nm.unpack_mask(words, to_oracle_shape(relu.shape))
+        elif n.op == "poolidx":
+            pool = g.nodes[n.ins[0] - 1]
+            out[pool.id] = np.ascontiguousarray(np.transpose(run.read(off, n.shape, torch.uint8), (0, 3, 1, 2)))
         elif n.op == "bn":
             acts[n.id] = run.read(off, n.shape)
     return out, acts
 
 
 def oracle_with_gpu_ties(g, exts, params):
-    """Store-everything oracle step in which ReLU decisions inside the undecidable band follow the
-    GPU; checks that every decided bit is bit-exact.  Returns (ref, stats dict, gpu BatchNorm outputs)."""
+    """Store-everything oracle step in which ReLU decisions and max-pool taps inside the undecidable band
+    follow the GPU; checks that every decided bit / index is bit-exact.  Returns (ref, stats dict, gpu BatchNorm outputs)."""
     oe, op = tensors.oracle_inputs(exts, params)
     gpu_bits, gpu_bn = gpu_relu_decisions(g, exts, params)
     ref = onet.store_everything_step(g.text(), oe, op, ties=(UNDECIDED_BAND, gpu_bits))
@@ -78,6 +81,13 @@ def oracle_with_gpu_ties(g, exts, params):
     for node, (passes, undecided) in ref["decisions"].items():
         n = g.nodes[node - 1]
         x = ref["acts"][n.ins[0]]
+        if n.op == "maxpool":       # tap indices: outside the undecidable windows the GPU's choice is the oracle's
+            strict = nm.maxpool_fwd(x, n.attrs["k"], n.attrs["stride"], n.attrs["pad"])[1]
+            assert np.array_equal(gpu_bits[node][~undecided], strict[~undecided]), node
+            flips += int(undecided.sum())
+            undecided_total += int(undecided.sum())
+            total += strict.size
+            continue
         strict = (x > 0) & (x < 6) if n.op == "relu6" else (x > 0)
         assert np.array_equal(gpu_bits[node][~undecided], strict[~undecided]), node
         flips += int((gpu_bits[node][undecided] != strict[undecided]).sum())

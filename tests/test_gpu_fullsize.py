@@ -98,12 +98,13 @@ OTHER = {
     "vgg16_b176": (lambda: graphs.vgg16_bn(batch=176), schedules.vgg_alternate_schedule),
     "unet_b11": (lambda: graphs.unet(batch=11), schedules.unet_skip_schedule),
     "mobilenetv2_b272": (lambda: graphs.mobilenet_v2(batch=272), schedules.mobilenet_depthwise_schedule),
+    "googlenet_b320": (lambda: graphs.googlenet(batch=320), schedules.googlenet_alternate_schedule),
 }
 
 
 @pytest.mark.parametrize("name", list(OTHER))
 def test_other_configurations_at_full_size(name):
-    """VGG-16 b176, UNet b11 at 416x608, MobileNetV2 b272 under their named schedules: the executor's peak is
+    """VGG-16 b176, UNet b11 at 416x608, MobileNetV2 b272, the inception network b320 under their named schedules: the executor's peak is
     the plan's, gradients are finite, bit-identical under the block-output schedule, and every filter that
     feeds a BatchNorm is orthogonal to its gradient."""
     make, named = OTHER[name]

@@ -41,6 +41,7 @@ CONV_CASES = [
     (2, 32, 32, 3, 64, 7, 2, 3),        # stem: C=3 takes the scalar-load path
     (1, 9, 9, 20, 24, 3, 1, 1),         # C % 16 != 0 and K % 16 != 0
     (5, 7, 7, 512, 512, 3, 1, 1),       # deep reduction (4608)
+    (2, 14, 14, 160, 320, 3, 1, 1),     # an inception 3x3: channel counts that are multiples of 16 but not of 128
 ]
 
 
@@ -136,7 +137,7 @@ def test_conv_wgrad_rejects_small_workspace():
         monet.call("monet_conv_fwd", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 2, 16, 16, 16, 16, 3, 3, 1, 1, 4, t.data_ptr(), 64)
 
 
-BN_CASES = [(2 * 16 * 16, 16), (3 * 14 * 14, 64), (1000, 256), (77, 2048), (5 * 33 * 31, 128), (4096, 24)]
+BN_CASES = [(2 * 16 * 16, 16), (3 * 14 * 14, 64), (1000, 256), (77, 2048), (5 * 33 * 31, 128), (4096, 24), (2 * 14 * 14, 320)]
 
 
 @pytest.mark.parametrize("rows,C", BN_CASES)

@@ -182,12 +182,21 @@ def alternate_blocks_schedule(g):
     return schedules.expand(g, F, bimpl, allow_inplace=True, conv_algo=schedules.DEFAULT_VARIANTS["conv_fwd"])
 
 
+def small_googlenet():
+    # 64x64 input: the second module still sees 4x4 positions, i.e. 32 samples per BatchNorm channel
+    return graphs.googlenet(batch=2, hw=64, classes=10, stem=(8, 8, 16),
+                            inceptions=(("a", 8, (8, 12), (4, 8), 4), "pool", ("b", 12, (8, 16), (4, 8), 8)))
+
+
 NETS = {
-    "vgg": small_vgg, "unet": small_unet, "mbv2": small_mbv2,
+    "vgg": small_vgg, "unet": small_unet, "mbv2": small_mbv2, "googlenet": small_googlenet,
     # full channel widths at a resolution the fp64 oracle manages
     "vgg_wide": lambda: graphs.vgg16_bn(batch=2, hw=32, classes=1000, fc=512),
     "unet_wide": lambda: graphs.unet(batch=1, h=32, w=48),
     "mbv2_wide": lambda: graphs.mobilenet_v2(batch=2, hw=64),
+    # the inception network at its real geometry: on smaller maps the 3x3 / stride-1 pool branch turns nearly constant
+    # over the positions and its BatchNorm ill-conditioned, which says nothing about the kernels
+    "googlenet_wide": lambda: graphs.googlenet(batch=2, hw=224),
 }
 
 

@@ -198,7 +198,67 @@ def test_tie_resolution_with_strict_decisions_changes_nothing():
     assert all(np.array_equal(tied["grads"][p], plain["grads"][p]) for p in plain["grads"])
 
 
-@pytest.mark.parametrize("net", ["vgg", "unet", "mbv2"])
+SMALL_INCEPTIONS = (("a", 8, (8, 12), (4, 8), 4), "pool", ("b", 12, (8, 16), (4, 8), 8))
+
+
+def test_window_maxima_within_the_band_follow_the_given_tap():
+    """2x2 / stride-2 pooling of a hand-made 4x4 map: a tap 1e-6 below the maximum may be taken instead
+    (the gradient then goes there), one far below it, padding, or an index outside the window may not."""
+    x = np.array([[1.0, 1.0 - 1e-6, 5.0, 2.0],
+                  [0.5, 0.2, 4.0, 3.0],
+                  [7.0, 7.0, -1.0, -2.0],
+                  [6.0, 1.0, -3.0, -1.0 - 1e-7]]).reshape(1, 1, 4, 4)
+    best, idx = nm.maxpool_fwd(x, 2, 2, 0)
+    assert best.ravel().tolist() == [1.0, 5.0, 7.0, -1.0] and idx.ravel().tolist() == [0, 0, 0, 0]   # first maximum wins
+    given = np.array([1, 3, 1, 200], np.uint8).reshape(1, 1, 2, 2)       # near-tie, far below, exact tie, invalid
+    got, undecided = nm.resolve_argmax(x, idx, best, given, 1e-3, 2, 2, 0)
+    assert got.ravel().tolist() == [1, 0, 1, 0] and undecided.ravel().tolist() == [True, False, True, False]
+    dy = np.array([10.0, 20.0, 30.0, 40.0]).reshape(1, 1, 2, 2)
+    dx = nm.maxpool_bwd_from_index(dy, got, x.shape, 2, 2, 0)
+    want = np.zeros((4, 4)); want[0, 1] = 10; want[0, 2] = 20; want[2, 1] = 30; want[2, 2] = 40
+    assert np.array_equal(dx[0, 0], want)
+    # with padding: the given tap points into the padding ring and is refused
+    best, idx = nm.maxpool_fwd(x, 3, 2, 1)
+    given = np.zeros(idx.shape, np.uint8)                                  # tap (0,0): padding for the first row / column of windows
+    got, undecided = nm.resolve_argmax(x, idx, best, given, 1e-3, 3, 2, 1)
+    assert np.array_equal(got[0, 0, 0, :], idx[0, 0, 0, :]) and not undecided[0, 0, 0, :].any()
+    # the oracle's own indices as the given ones change nothing
+    got, undecided = nm.resolve_argmax(x, idx, best, idx, 1e-3, 3, 2, 1)
+    assert np.array_equal(got, idx) and not undecided.any()
+
+
+def test_tie_resolution_with_the_strict_window_maxima_changes_nothing():
+    """Handing the step its own max-pool indices must reproduce the plain step exactly.  Handing it the next tap
+    everywhere changes an index only where that tap ties with the maximum exactly (all-zero windows after a
+    ReLU; a stride-1 pool over a stride-2 pool sees the same element twice): the gradient then takes another
+    route to the same place, so the result agrees to rounding."""
+    from oracle import network as onet
+    from workloads import graphs, tensors
+    g = graphs.googlenet(batch=2, hw=32, classes=10, stem=(8, 8, 16), inceptions=SMALL_INCEPTIONS)
+    exts, params = tensors.make_inputs(g, seed=5, gamma_beta="random")
+    oe, op = tensors.oracle_inputs(exts, params)
+    plain = onet.store_everything_step(g.text(), oe, op)
+    own, shifted = {}, {}
+    for n in g.nodes:
+        if n.op == "maxpool":
+            idx = nm.maxpool_fwd(plain["acts"][n.ins[0]], n.attrs["k"], n.attrs["stride"], n.attrs["pad"])[1]
+            own[n.id] = idx
+            shifted[n.id] = ((idx + 1) % (n.attrs["k"] ** 2)).astype(np.uint8)
+    assert len(own) >= 5
+    tied = onet.store_everything_step(g.text(), oe, op, ties=(1e-9, own))
+    assert tied["loss"] == plain["loss"]
+    assert all(np.array_equal(tied["grads"][p], plain["grads"][p]) for p in plain["grads"])
+    assert all(np.array_equal(tied["decisions"][i][0], own[i]) and not tied["decisions"][i][1].any() for i in own)
+    tied = onet.store_everything_step(g.text(), oe, op, ties=(1e-9, shifted))
+    assert tied["loss"] == plain["loss"]
+    top = max(np.linalg.norm(v) for v in plain["grads"].values())
+    assert all(np.linalg.norm(tied["grads"][p] - plain["grads"][p]) < 1e-13 * top for p in plain["grads"])
+    for i in own:
+        changed = tied["decisions"][i][0] != own[i]
+        assert np.array_equal(changed, tied["decisions"][i][1]) and changed.mean() < 0.5
+
+
+@pytest.mark.parametrize("net", ["vgg", "unet", "mbv2", "googlenet"])
 def test_recomputing_schedules_reach_the_plain_gradients(net):
     """Section 3: a tensor that is not stored is recomputed, so the result does not change.  The fp64
     interpreter, which really deletes freed arrays, must give the store-everything gradients."""
@@ -208,6 +268,8 @@ def test_recomputing_schedules_reach_the_plain_gradients(net):
         g = graphs.vgg16_bn(batch=2, hw=32, classes=10, widths=(8, 16, 16, 32, 32), fc=64)
     elif net == "unet":
         g = graphs.unet(batch=2, h=32, w=48, classes=2, base=8, depth=4)
+    elif net == "googlenet":
+        g = graphs.googlenet(batch=2, hw=32, classes=10, stem=(8, 8, 16), inceptions=SMALL_INCEPTIONS)
     else:
         g = graphs.mobilenet_v2(batch=2, hw=32, classes=10, stem=8, last=64,
                                 stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 16, 2, 2), (6, 24, 1, 1)))

@@ -55,12 +55,15 @@ def test_trace_matches_oracle_on_resnet_shapes():
         check_against_oracle(g, sch)
 
 
-@pytest.mark.parametrize("net", ["vgg", "unet", "mbv2"])
+@pytest.mark.parametrize("net", ["vgg", "unet", "mbv2", "googlenet"])
 def test_trace_matches_oracle_on_the_other_network_families(net):
     if net == "vgg":
         g = graphs.vgg16_bn(batch=2, hw=32, classes=10, widths=(8, 16, 16, 32, 32), fc=64)
     elif net == "unet":
         g = graphs.unet(batch=2, h=32, w=48, classes=2, base=8, depth=4)
+    elif net == "googlenet":
+        g = graphs.googlenet(batch=2, hw=32, classes=10, stem=(8, 8, 16),
+                             inceptions=(("a", 8, (8, 12), (4, 8), 4), "pool", ("b", 12, (8, 16), (4, 8), 8)))
     else:
         g = graphs.mobilenet_v2(batch=2, hw=32, classes=10, stem=8, last=64,
                                 stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 16, 2, 2), (6, 24, 1, 1)))
@@ -77,9 +80,9 @@ def test_trace_matches_oracle_on_the_other_network_families(net):
 
 
 def test_full_size_plans_of_the_other_network_families():
-    """VGG-16 b176, UNet b11 at 416x608 and MobileNetV2 b272 lower at their full sizes; recomputing
-    block internals cuts the peak well below store-everything."""
-    for g in (graphs.vgg16_bn(), graphs.unet(), graphs.mobilenet_v2()):
+    """VGG-16 b176, UNet b11 at 416x608, MobileNetV2 b272 and the inception network b320 lower at their full
+    sizes; recomputing block internals cuts the peak well below store-everything."""
+    for g in (graphs.vgg16_bn(), graphs.unet(), graphs.mobilenet_v2(), graphs.googlenet()):
         lean = M.Plan(g.text(), schedules.block_output_schedule(g).text())
         store = M.Plan(g.text(), schedules.store_everything_schedule(g).text())
         assert lean.exact_peak <= lean.predicted_peak

@@ -563,3 +563,55 @@ def mobilenet_v2(batch=272, hw=224, classes=1000, stages=MOBILENET_V2_STAGES, st
     g.softmaxce(f, labels)
     g.end_block()
     return g
+
+
+# (1x1, (3x3 reduce, 3x3), (5x5 reduce, 5x5), pool projection) per inception module, and where the 3x3 / stride-2
+# max-pools sit (after 3b and 4e): the published table of the architecture
+GOOGLENET_INCEPTIONS = (
+    ("3a", 64, (96, 128), (16, 32), 32), ("3b", 128, (128, 192), (32, 96), 64), "pool",
+    ("4a", 192, (96, 208), (16, 48), 64), ("4b", 160, (112, 224), (24, 64), 64), ("4c", 128, (128, 256), (24, 64), 64),
+    ("4d", 112, (144, 288), (32, 64), 64), ("4e", 256, (160, 320), (32, 128), 128), "pool",
+    ("5a", 256, (160, 320), (32, 128), 128), ("5b", 384, (192, 384), (48, 128), 128),
+)
+
+
+def googlenet(batch=320, hw=224, classes=1000, stem=(64, 64, 192), inceptions=GOOGLENET_INCEPTIONS):
+    """Inception network with BatchNorm after every convolution (no auxiliary classifiers, no dropout):
+    conv7x7/2 - pool - conv1x1 - conv3x3 - pool, then inception modules of four parallel branches
+    (1x1 | 1x1-3x3 | 1x1-5x5 | pool3x3/1-1x1) joined along the channels, stride-2 pools between the groups,
+    global average pool and one linear layer.  One block per stem stage and per module; the four branch outputs
+    are joined pairwise, so every element is copied twice on the way into the module output."""
+    g = Graph()
+    x = g.ext("x", "f32", (batch, hw, hw, 3))
+    labels = g.ext("labels", "i32", (batch,))
+    g.begin_block("stem1")
+    a = g.maxpool(_cbr(g, x, stem[0], 7, 2, 3, "conv1"), 3, 2, 1)
+    g.end_block()
+    g.begin_block("stem2")
+    a = _cbr(g, a, stem[1], 1, 1, 0, "conv2")
+    g.end_block()
+    g.begin_block("stem3")
+    a = g.maxpool(_cbr(g, a, stem[2], 3, 1, 1, "conv3"), 3, 2, 1)
+    g.end_block()
+    pending_pool = False
+    for spec in inceptions:
+        if spec == "pool":
+            pending_pool = True
+            continue
+        nm, c1, (r3, c3), (r5, c5), cp = spec
+        g.begin_block("inc" + nm)
+        if pending_pool:                      # the pool between two groups opens the next module's block
+            a = g.maxpool(a, 3, 2, 1)
+            pending_pool = False
+        b1 = _cbr(g, a, c1, 1, 1, 0, nm + ".b1")
+        b2 = _cbr(g, _cbr(g, a, r3, 1, 1, 0, nm + ".b2r"), c3, 3, 1, 1, nm + ".b2")
+        b3 = _cbr(g, _cbr(g, a, r5, 1, 1, 0, nm + ".b3r"), c5, 5, 1, 2, nm + ".b3")
+        b4 = _cbr(g, g.maxpool(a, 3, 1, 1), cp, 1, 1, 0, nm + ".b4")
+        a = g.concat(g.concat(b1, b2), g.concat(b3, b4))
+        g.end_block()
+    g.begin_block("head")
+    p = g.avgpool(a)
+    f = g.linear(p, classes, name="fc")
+    g.softmaxce(f, labels)
+    g.end_block()
+    return g

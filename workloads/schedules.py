@@ -335,3 +335,10 @@ def mobilenet_depthwise_schedule(g: Graph, variants=None):
     """MobileNetV2: the depthwise triples (blocks named *.dw) are recomputed, everything else is kept."""
     keep = {i for i, (name, _) in enumerate(g.blocks) if not name.endswith(".dw")}
     return block_checkpoint_schedule(g, keep, variants)
+
+
+def googlenet_alternate_schedule(g: Graph, variants=None):
+    """Inception network: every second block (stem stage or inception module) keeps what its backward reads,
+    the others are recomputed from the kept block outputs around them."""
+    keep = {b for b in range(len(g.blocks)) if b % 2 == 0} | {len(g.blocks) - 1}
+    return block_checkpoint_schedule(g, keep, variants)
