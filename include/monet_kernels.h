@@ -38,6 +38,14 @@ extern "C" {
 int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
                    int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                    int splits, float *ws, size_t ws_bytes);
+/* monet_conv_fwd followed by monet_bn_stats of its output, with the statistics' first level computed in the
+ * convolution's epilogue instead of a pass over y (the largest of the fusions the executor applies between a
+ * convolution and the BatchNorm behind it).  Needs C % 16 == 0 and K % 4 == 0; ws / ws_bytes as for monet_conv_fwd
+ * with splits == 1; scratch >= 8 * (G + ceil(G / 64)) * K bytes with G = ceil(N*P*Q / 64).  `stats` is bit-identical to monet_bn_stats(y)
+ * called with the same scratch size. */
+int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y,
+                            int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
+                            float *ws, size_t ws_bytes, float *stats, float eps, float *scratch, size_t scratch_bytes);
 /* Workspace bytes for monet_conv_fwd (which = 0) / monet_conv_dgrad (which = 1) of this shape with `splits` ranges;
  * for splits == 1 the size that lets the ragged last round be cut as far as it pays (0: nothing to gain).
  * Negative: error code. */

@@ -31,6 +31,9 @@ struct ProgStep {
 struct monet_plan {
     Plan plan;
     std::vector<ProgStep> prog_plain, prog_fused;
+    // per launch: a forward convolution whose epilogue also leaves the partial statistics of the BatchNorm that
+    // runs next (feeds_stats), and that BatchNorm launch (stats_fed), which then only merges them
+    std::vector<char> feeds_stats, stats_fed;
     bool fusion = true;
     bool timed_fused = false;
     char *base = nullptr;      // device memory bound by the caller
@@ -156,6 +159,9 @@ struct StepCtx {
     float *scratch() const { return (float *)(mp->base + mp->plan.scratch_off); }
     size_t scratch_bytes() const { return (size_t)mp->plan.scratch_bytes; }
     float *bn_stats(int node) const { return (float *)(mp->base + mp->plan.bn_stats_off.at(node)); }
+    size_t index_of(const Launch &L) const { return (size_t)(&L - mp->plan.launches.data()); }
+    bool feeds_stats(const Launch &L) const { return mp->feeds_stats[index_of(L)] != 0; }
+    bool stats_fed(const Launch &L) const { return mp->stats_fed[index_of(L)] != 0; }
 };
 
 ConvShape conv_shape(const Graph &g, const Node &n) {
@@ -221,7 +227,7 @@ void run_forward(const StepCtx &c, const Launch &L) {
     if (op == "conv") {
         const FwdImpl &im = n.fimpls[L.impl];
         conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
-                 (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+                 (size_t)(im.ws > 0 ? align_up(im.ws) : 0), false, c.feeds_stats(L) ? c.scratch() : nullptr);
     } else if (op == "tconv") {
         conv_dgrad(c.st, in0, c.weights[n.pars[0]], out, tconv_adjoint_shape(g, n), false);
     } else if (op == "dwconv") {
@@ -236,7 +242,8 @@ void run_forward(const StepCtx &c, const Launch &L) {
         int64_t rows = numel_of(n.shape) / C;
         float *stats = c.bn_stats(L.id);
         // statistics are computed by the forward pass and reused when the node is recomputed
-        if (L.kind == EV_RUN_FWD) bn_stats(c.st, in0, stats, rows, C, (float)n.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
+        if (L.kind == EV_RUN_FWD)
+            bn_stats(c.st, in0, stats, rows, C, (float)n.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes(), c.stats_fed(L));
         bn_apply(c.st, in0, out, c.weights[n.pars[0]], c.weights[n.pars[1]], stats, rows, C);
     } else if (op == "relu" || op == "relu6") {
         relu_fwd(c.st, in0, out, (L.flags & 2) ? (uint64_t *)c.ptr(L.a[3]) : nullptr, numel_of(n.shape), op == "relu6");
@@ -461,9 +468,26 @@ int triple_bwd(const Plan &pl, const Launch &L1, const Launch &L2, const Launch 
     return spans_conflict(ins, outs) ? -1 : pos;
 }
 
+// Forward convolution directly followed by the first run of the BatchNorm of its output: the statistics' partial
+// results come out of the convolution's epilogue, bit-identical to the stand-alone kernel's (tile_stats.hpp), so
+// this is independent of launch fusion and of the schedule.
+bool conv_feeds_bn_stats(const Plan &pl, const Launch &L1, const Launch &L2) {
+    const Graph &g = pl.g;
+    if (L1.kind != EV_RUN_FWD || L2.kind != EV_RUN_FWD) return false;
+    const Node &cv = g.nodes[L1.id], &bn = g.nodes[L2.id];
+    if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
+    const ConvShape cs = conv_shape(g, cv);
+    if (cs.C % 16 || cs.K % 4 || splits_of(cv.fimpls[L1.impl].algo, cv.fimpls[L1.impl].extra) != 1) return false;
+    return bn_stats_in_row_groups(cs.M(), cs.K, (size_t)pl.scratch_bytes);
+}
+
 void build_programs(monet_plan *p) {
     const Plan &pl = p->plan;
     const size_t n = pl.launches.size();
+    p->feeds_stats.assign(n, 0);
+    p->stats_fed.assign(n, 0);
+    for (size_t i = 0; i + 1 < n; ++i)
+        if (conv_feeds_bn_stats(pl, pl.launches[i], pl.launches[i + 1])) p->feeds_stats[i] = p->stats_fed[i + 1] = 1;
     for (size_t i = 0; i < n; ++i) p->prog_plain.push_back(ProgStep{FUSE_NONE, i, i, i});
     for (size_t i = 0; i < n; ++i) {
         if (i + 2 < n) {
@@ -502,7 +526,8 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
         const int64_t n = numel_of(re.shape);
         const int C = (int)bn.shape.back();
         float *stats = c.bn_stats(L1.id);
-        if (L1.kind == EV_RUN_FWD) bn_stats(c.st, x, stats, n / C, C, (float)bn.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
+        if (L1.kind == EV_RUN_FWD)
+            bn_stats(c.st, x, stats, n / C, C, (float)bn.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes(), c.stats_fed(L1));
         fwd_chain(c.st, x, other, c.weights[bn.pars[0]], c.weights[bn.pars[1]], stats, C, out_bn, out_pre, out, mask, n, re.op == "relu6");
         return;
     }
@@ -534,7 +559,7 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
             const int C = (int)n1.shape.back();
             float *stats = c.bn_stats(L1.id);
             if (L1.kind == EV_RUN_FWD)
-                bn_stats(c.st, x, stats, n / C, C, (float)n1.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes());
+                bn_stats(c.st, x, stats, n / C, C, (float)n1.attr_f("eps", 1e-5), c.scratch(), c.scratch_bytes(), c.stats_fed(L1));
             fwd_chain(c.st, x, nullptr, c.weights[n1.pars[0]], c.weights[n1.pars[1]], stats, C, nullptr, pre, out, mask, n, six);
         } else {
             fwd_chain(c.st, x, (const float *)c.ptr(L1.a[1]), nullptr, nullptr, nullptr, 0, nullptr, pre, out, mask, n, six);
@@ -650,7 +675,8 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
             const Launch &L3 = p->plan.launches[ps.c];
             e = 4.0 * (double)numel_of(g.nodes[L3.id].shape);
             const bool keep_bn = !freed_between(p->plan, L.id, L2.event, L3.event), pre = !(L3.flags & 1), mk = L3.flags & 2;
-            bytes = 2 * e + (keep_bn ? e : 0) + (pre ? e : 0) + e + (mk ? e / 32 : 0) + (L.kind == EV_RUN_FWD ? e : 0);
+            // + the statistics pass, unless the convolution before it already left the partial results
+            bytes = 2 * e + (keep_bn ? e : 0) + (pre ? e : 0) + e + (mk ? e / 32 : 0) + (L.kind == EV_RUN_FWD && !p->stats_fed[ps.a] ? e : 0);
             label = L.kind == EV_RUN_FWD ? "bn_add_relu_fwd" : "bn_add_relu_apply";
         } else if (ps.fuse == FUSE_RELU_ADD_BN_BWD) {
             const Launch &L3 = p->plan.launches[ps.c];
@@ -666,7 +692,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
             e = 4.0 * (double)numel_of(g.nodes[L2.id].shape);
             const bool pre = !(L2.flags & 1), mk = L2.flags & 2;
             bytes = (ps.fuse == FUSE_ADD_RELU_FWD ? 2 : 1) * e + (pre ? e : 0) + e + (mk ? e / 32 : 0);
-            if (ps.fuse == FUSE_BN_RELU_FWD && L.kind == EV_RUN_FWD) bytes += e;        // statistics pass
+            if (ps.fuse == FUSE_BN_RELU_FWD && L.kind == EV_RUN_FWD && !p->stats_fed[ps.a]) bytes += e;        // statistics pass
             label = ps.fuse == FUSE_ADD_RELU_FWD ? "add_relu_fwd" : (L.kind == EV_RUN_FWD ? "bn_relu_fwd" : "bn_relu_apply");
         } else {
             const Bop &b1 = g.bops[L.id];
@@ -726,7 +752,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         else if (n.op == "concat") bytes = 2 * e;
         else if (n.op == "linear") conv_cost(linear_shape(g, n), "linear_fwd");
         else if (n.op == "bn") {
-            if (L.kind == EV_RUN_FWD) bytes = 3 * e;                     // statistics pass + apply pass
+            if (L.kind == EV_RUN_FWD) bytes = (p->stats_fed[ps.a] ? 2 : 3) * e;   // statistics pass (unless fed by the convolution) + apply pass
             else { bytes = 2 * e; label = "bn_apply"; }                  // recomputation reuses the statistics
         } else if (n.op == "relu" || n.op == "relu6") bytes = (2.0 + ((L.flags & 2) ? 1.0 / 32 : 0.0)) * e;
         else if (n.op == "maxpool") bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e * ((L.flags & 2) ? 1.25 : 1.0);
@@ -814,6 +840,17 @@ static PoolShape mk_pool(int N, int H, int W, int C, int k, int stride, int pad)
 extern "C" int monet_conv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
                               int stride, int pad, int splits, float *ws, size_t ws_bytes) {
     return guarded([&] { conv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad), splits, ws, ws_bytes); });
+}
+extern "C" int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
+                                       int stride, int pad, float *ws, size_t ws_bytes, float *stats, float eps, float *scratch,
+                                       size_t scratch_bytes) {
+    return guarded([&] {
+        const ConvShape cs = mk_conv(N, H, W, C, K, R, S, stride, pad);
+        if (!bn_stats_in_row_groups(cs.M(), cs.K, scratch_bytes))
+            throw KernelError("monet_conv_fwd_bn_stats: scratch too small for 2 floats per 64 output rows and channel");
+        conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, scratch);
+        bn_stats((hipStream_t)stream, y, stats, cs.M(), cs.K, eps, scratch, scratch_bytes, true);
+    });
 }
 extern "C" int64_t monet_conv_workspace_bytes(int which, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int splits) {
     int64_t bytes = -1;

@@ -7,6 +7,7 @@
 // no floating-point atomics.  Variance is accumulated around a per-thread pivot and merged with
 // the pairwise (Chan) update, never as E[x^2]-mean^2.
 #include "kernels.hpp"
+#include "tile_stats.hpp"
 
 namespace monet {
 
@@ -127,6 +128,69 @@ __global__ __launch_bounds__(256) void bn_stats_partial(const float *__restrict_
     }
 }
 
+// The same partial results in groups of 64 rows (see tile_stats.hpp): one wave per (row group, 64 columns),
+// no LDS, sixteen 16-byte loads per lane in flight.  Wave u of the launch takes group u / chunks, columns
+// 64 * (u % chunks).
+__global__ __launch_bounds__(256) void bn_stats_rows64(const float *__restrict__ x, float *__restrict__ part, int64_t rows, int C,
+                                                        int chunks, int64_t units) {
+    const int lane = threadIdx.x & 63;
+    const int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (u >= units) return;
+    const int64_t grp = u / chunks;
+    const int col = (int)(u % chunks) * 64 + 4 * (lane & 15);
+    const int64_t r0 = grp * STAT_ROWS + (lane >> 4);
+    f4 v[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int64_t r = r0 + 16 * (t >> 2) + 4 * (t & 3);
+        v[t] = f4{0, 0, 0, 0};
+        if (r < rows && col < C) v[t] = __builtin_nontemporal_load((const f4 *)(x + r * C + col));
+    }
+    LaneStats ls;
+    ls.init();
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int64_t r = r0 + 16 * (t >> 2) + 4 * (t & 3);
+        if (r < rows && col < C) ls.add(v[t].x, v[t].y, v[t].z, v[t].w);
+    }
+    float n, mean[4], m2[4];
+    merge_lane_stats(ls, lane, n, mean, m2);
+    store_group_stats(part, grp, C, col, lane, mean, m2);
+}
+
+// Second level for tensors with many row groups: one wave per (64 consecutive groups, 64 channels) merges them in
+// group order, lane = channel, so every load instruction reads 512 contiguous bytes; eight loads in flight.
+constexpr int FOLD = 64;
+__global__ __launch_bounds__(256) void bn_stats_fold(const float *__restrict__ part, float *__restrict__ folded, int64_t rows, int C,
+                                                      int64_t groups, int chunks, int64_t units) {
+#pragma clang fp contract(off)
+    const int lane = threadIdx.x & 63;
+    const int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (u >= units) return;
+    const int64_t sg = u / chunks;
+    const int c = (int)(u % chunks) * 64 + lane;
+    if (c >= C) return;
+    const int64_t g0 = sg * FOLD, g1 = g0 + FOLD < groups ? g0 + FOLD : groups;
+    float n = 0, mean = 0, m2 = 0;
+    for (int64_t gb = g0; gb < g1; gb += 8) {
+        float2 p[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) p[t] = gb + t < g1 ? *(const float2 *)(part + ((gb + t) * C + c) * 2) : make_float2(0, 0);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int64_t g = gb + t;
+            if (g >= g1) break;
+            const int64_t r0 = g * STAT_ROWS;
+            const float nb = (float)(r0 + STAT_ROWS < rows ? STAT_ROWS : rows - r0);
+            const float nt = n + nb, d = p[t].x - mean;
+            mean = n > 0 ? mean + d * (nb / nt) : p[t].x;
+            m2 = m2 + p[t].y + (n > 0 ? d * d * (n * nb / nt) : 0.0f);
+            n = nt;
+        }
+    }
+    *(float2 *)(folded + (sg * C + c) * 2) = make_float2(mean, m2);
+}
+
 // Block = FIN_CH channels x FIN_LANES slab lanes.  Lane sl merges slabs sl, sl+FIN_LANES, ... in order,
 // then the lanes of a channel are merged by a fixed tree.  Few channels per block and many lanes keep
 // the dependent chain per thread short: these kernels are latency-bound, not bandwidth-bound.
@@ -183,8 +247,43 @@ __global__ __launch_bounds__(256) void bn_stats_final(const float *__restrict__ 
     }
 }
 
-void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch, size_t scratch_bytes) {
+// more row groups than this are first merged 64 at a time (bn_stats_fold)
+constexpr int64_t FOLD_ABOVE = 4096;   // measured: below this the extra launch costs more than the longer final merge
+
+bool bn_stats_in_row_groups(int64_t rows, int C, size_t scratch_bytes) {
+    if (rows <= 0 || C % 4) return false;
+    const int64_t groups = (rows + STAT_ROWS - 1) / STAT_ROWS;
+    const int64_t folded = groups > FOLD_ABOVE ? (groups + FOLD - 1) / FOLD : 0;
+    return (size_t)(groups + folded) * C * 2 * sizeof(float) <= scratch_bytes;
+}
+
+void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch, size_t scratch_bytes,
+              bool partials_ready) {
     if (rows <= 0) throw KernelError("BatchNorm: no rows");
+    if (bn_stats_in_row_groups(rows, C, scratch_bytes)) {
+        const int64_t groups = (rows + STAT_ROWS - 1) / STAT_ROWS;
+        if (!partials_ready) {
+            const int chunks = (C + 63) / 64;
+            const int64_t units = groups * chunks;
+            hipLaunchKernelGGL(bn_stats_rows64, dim3((unsigned)((units + 3) / 4)), dim3(256), 0, st, x, scratch, rows, C, chunks, units);
+        }
+        if (groups > FOLD_ABOVE) {
+            const int64_t folded = (groups + FOLD - 1) / FOLD;
+            float *second = scratch + groups * C * 2;
+            const int chunks = (C + 63) / 64;
+            const int64_t units = folded * chunks;
+            hipLaunchKernelGGL(bn_stats_fold, dim3((unsigned)((units + 3) / 4)), dim3(256), 0, st, (const float *)scratch, second, rows, C,
+                               groups, chunks, units);
+            hipLaunchKernelGGL(bn_stats_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)second, stats, rows, C,
+                               (int)folded, (int64_t)STAT_ROWS * FOLD, eps);
+        } else {
+            hipLaunchKernelGGL(bn_stats_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, stats, rows, C,
+                               (int)groups, (int64_t)STAT_ROWS, eps);
+        }
+        hip_check(hipGetLastError(), "bn_stats launch");
+        return;
+    }
+    if (partials_ready) throw KernelError("BatchNorm: partial statistics announced for a tensor that does not use row groups");
     BnGeom g = bn_geom(rows, C, (int64_t)(scratch_bytes / 4), 2);
     hipLaunchKernelGGL(bn_stats_partial, dim3(g.G, g.CB), dim3(256), 0, st, x, scratch, rows, C, g.TPR, g.slab);
     hipLaunchKernelGGL(bn_stats_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, stats, rows, C, g.G, g.slab, eps);

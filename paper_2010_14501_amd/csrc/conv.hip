@@ -34,6 +34,7 @@
 // split) with the tile index fastest, so a launch with few tiles and many splits (weight
 // gradients) still spreads over all XCDs and the tiles of one split share their operand rows.
 #include "kernels.hpp"
+#include "tile_stats.hpp"
 
 namespace monet {
 
@@ -66,6 +67,7 @@ struct TileArgs {
     int64_t main_tiles;        // multiple of 8
     int meet_splits;           // <= 1: off
     float *part;               // (class, tile - main_tiles, range) x 64 x threads floats, register order
+    float *stats_part;         // FWD, whole results only: BatchNorm partial statistics of the output (tile_stats.hpp), or null
 };
 
 // arrivals per split tile; zero whenever no convolution kernel is running (the last arrival puts its entry back)
@@ -594,6 +596,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         constexpr int NW = WM * WN;
         __syncthreads();   // every wave has finished reading the operand tiles
         float *stage = (2 * A_SZ >= NW * 1024 ? &As[0][0] : &Bs[0][0]) + wave * 1024;
+        const bool want_stats = MODE == FWD && ta.stats_part != nullptr;
+        LaneStats ls;
+        ls.init();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int mi = q >> 1, vbase = 8 * (q & 1);
@@ -620,8 +625,16 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                     float4 *dst = (float4 *)(out + orow * ta.Ng + col);
                     if (do_acc) { float4 o = *dst; val.x += o.x; val.y += o.y; val.z += o.z; val.w += o.w; }
                     *dst = val;
+                    if (MODE == FWD && want_stats) ls.add(val.x, val.y, val.z, val.w);
                 }
             }
+        }
+        if (MODE == FWD && want_stats) {
+            // this wave's 64 rows are one row group of the statistics; lanes l, l^16, l^32, l^48 share their columns
+            float n, mean[4], m2[4];
+            merge_lane_stats(ls, lane, n, mean, m2);
+            const int64_t first = row0 + wm * 64;
+            if (first < Mg) store_group_stats(ta.stats_part, first / STAT_ROWS, ta.Ng, col0 + wn * 64 + 4 * (lane & 15), lane, mean, m2);
         }
         return;
     }
@@ -815,13 +828,16 @@ size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
 }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,
-              bool accumulate) {
+              bool accumulate, float *stats_part) {
     check_shape(cs);
     TileArgs ta{};
     ta.a = x; ta.b = w; ta.cs = cs;
     ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
     ta.out_elems = ta.Mg * ta.Ng;
     bool fast = cs.C % BK == 0;
+    if (stats_part && (!fast || cs.K % 4 || splits != 1 || accumulate))
+        throw KernelError("conv_fwd: statistics in the epilogue need C % 16 == 0, K % 4 == 0, splits == 1 and no accumulation");
+    ta.stats_part = stats_part;
     launch_cfg<FWD>(pick_cfg(FWD, ta.Mg, ta.Ng), st, ta, fast, 1, y, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, accumulate, "conv_fwd");
 }
 

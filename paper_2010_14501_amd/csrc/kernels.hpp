@@ -32,8 +32,10 @@ struct ConvShape {
 // Every variant can cut its reduction into `splits` ranges: partial results go to ws (splits * |output|
 // floats) and are added in range order.  splits == 1 needs no workspace.
 // y (+)= conv(x, w)
+// stats_part: if given, the epilogue also leaves BatchNorm's partial statistics of y (groups of 64 rows, the
+// layout bn_stats() reads with partials_ready) there; needs C % 16 == 0, K % 4 == 0, splits == 1, no accumulation.
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits = 1, float *ws = nullptr,
-              size_t ws_bytes = 0, bool accumulate = false);
+              size_t ws_bytes = 0, bool accumulate = false, float *stats_part = nullptr);
 // dx (+)= transpose-conv of dy with w
 void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits = 1,
                 float *ws = nullptr, size_t ws_bytes = 0);
@@ -56,8 +58,12 @@ size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits);
 // ---- BatchNorm over rows x C (rows = N*H*W), training mode, biased variance
 constexpr int64_t kBnScratchFloats = 1 << 20;
 // stats = mean[C] followed by invstd[C]; scratch holds per-slab partials
+// partials_ready: the producer of x (a forward convolution given `stats_part`) has already left the per-group
+// partial results in `scratch`; only the final merge runs.  Allowed only where bn_stats_in_row_groups() holds.
 void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch,
-              size_t scratch_bytes);
+              size_t scratch_bytes, bool partials_ready = false);
+// true if the statistics of a rows x C tensor are built from groups of 64 rows (scratch: 2 floats per group and channel)
+bool bn_stats_in_row_groups(int64_t rows, int C, size_t scratch_bytes);
 void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, const float *beta, const float *stats,
               int64_t rows, int C);
 // t is the BatchNorm input (from_output = false) or its own output (true).  With relu_t, dy is first passed through

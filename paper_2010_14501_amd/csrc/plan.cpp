@@ -732,7 +732,9 @@ void Plan::build(const std::string &graph_text, const std::string &schedule_text
             off += align_up(2 * g.nodes[i].shape.back() * 4);
         }
     scratch_off = off;
-    scratch_bytes = 8ll << 20;
+    // holds the partial results of the two-level reductions; the largest user is BatchNorm's forward statistics
+    // in groups of 64 rows (2 floats per group and channel: 72 MB for VGG-16's first layers at batch 176)
+    scratch_bytes = 96ll << 20;
     off += scratch_bytes;
     persistent_bytes = off;
     lower();

@@ -126,6 +126,48 @@ def test_conv_ragged_last_round_is_split_and_counts_reset():
         assert rel(gx.cpu().numpy(), 2 * want_dx) < GRAD_TOL, rep
 
 
+@pytest.mark.parametrize("case", [
+    (3, 14, 14, 64, 128, 3, 1, 1),      # ragged last row group (588 rows)
+    (2, 28, 28, 64, 256, 1, 1, 0),      # two column tiles
+    (2, 15, 13, 32, 80, 3, 2, 1),       # stride 2, a column tile that is only partly used (80 of 128)
+    (2, 28, 28, 128, 64, 1, 2, 0),      # the 256x64 tile: four row groups per workgroup
+    (48, 28, 28, 128, 128, 1, 1, 0),    # ragged last round cut and met inside the kernel
+])
+def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
+    """BatchNorm's forward statistics come out of the convolution's epilogue with the same bits as from a pass
+    over the convolution's output, and match the oracle."""
+    torch = torch_mod()
+    N, H, W, C, K, R, stride, pad = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    w += np.float32(0.05)                                                # non-zero channel means
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    dx, dwt = dev(x), dev(w)
+    rows = N * P * Q
+    groups = (rows + 63) // 64
+    sb = 8 * (groups + (groups + 63) // 64) * K                      # first and second level of the statistics
+    scratch = torch.full((sb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    need = monet.call("monet_conv_workspace_bytes", 0, N, H, W, C, K, R, R, stride, pad, 1)
+    ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda")
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    fused = torch.full((2 * K,), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd_bn_stats", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad,
+               ws.data_ptr() if need else None, need, fused.data_ptr(), 1e-5, scratch.data_ptr(), sb)
+    y2 = torch.empty_like(y)
+    monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y2.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1,
+               ws.data_ptr() if need else None, need)
+    assert torch.equal(y, y2)
+    alone = torch.full((2 * K,), float("nan"), dtype=torch.float32, device="cuda")
+    scratch.fill_(float("nan"))
+    monet.call("monet_bn_stats", None, y2.data_ptr(), alone.data_ptr(), rows, K, 1e-5, scratch.data_ptr(), sb)
+    assert torch.equal(fused, alone)
+    mean, invstd = nm.bn_stats(wt.act_to_oracle(y2.cpu().numpy()), 1e-5)
+    got = fused.cpu().numpy()
+    assert rel(got[:K], mean) < ACT_TOL and rel(got[K:], invstd) < ACT_TOL
+
+
 def test_conv_wgrad_rejects_small_workspace():
     torch = torch_mod()
     t = torch.zeros(16 * 16 * 16 * 2, device="cuda")
