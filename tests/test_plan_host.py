@@ -101,6 +101,66 @@ def test_full_resnet50_plan_fragmentation_is_small():
     assert plan.exact_peak < 0.6 * store.exact_peak
 
 
+def _small_nets():
+    yield graphs.tiny_chain()
+    yield graphs.resnet50(batch=2, hw=32, classes=10, widths=(8, 16, 16, 32), depths=(2, 2, 2, 2), stem=8)
+    yield graphs.googlenet(batch=2, hw=32, classes=10, stem=(8, 8, 16),
+                           inceptions=(("a", 8, (8, 12), (4, 8), 4), "pool", ("b", 12, (8, 16), (4, 8), 8)))
+    yield graphs.mobilenet_v2(batch=2, hw=32, classes=10, stem=8, last=64, stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 12, 1, 1)))
+
+
+def test_live_tensors_never_share_arena_bytes():
+    """At every launch the tensors the plan holds (forward and gradient) occupy pairwise disjoint byte ranges,
+    except an in-place result, which sits exactly on its input.  The allocator hands freed blocks out again late
+    and whole near BatchNorm / add / ReLU launches; that must never put two live tensors on the same bytes."""
+    checked = 0
+    for g in _small_nets():
+        for sch in (schedules.store_everything_schedule(g), schedules.block_output_schedule(g)):
+            plan = M.Plan(g.text(), sch.text())
+            launch_events = [i for i, e in enumerate(plan.trace()) if e["kind"] in (M.RUN_FWD, M.RUN_RECOMPUTE, M.RUN_BWD)]
+            for ev in launch_events:
+                spans = []
+                for n in g.nodes:
+                    for is_grad in (False, True):
+                        off = plan.tensor_offset(ev, n.id, is_grad)
+                        if off >= 0:
+                            count = 1
+                            for d in n.shape:
+                                count *= d
+                            nbytes = {"mask": 8, "poolidx": 1}.get(n.op, 4) * count      # 64-bit mask words, 8-bit tap indices
+                            spans.append((off, off + nbytes, n.id, is_grad))
+                spans.sort()
+                for (a0, a1, an, ag), (b0, b1, bn, bg) in zip(spans, spans[1:]):
+                    assert a1 <= b0 or (a0 == b0 and a1 == b1 and not ag and not bg), (ev, (an, ag, a0, a1), (bn, bg, b0, b1))
+                checked += len(spans)
+    assert checked > 10000
+
+
+def test_graph_builder_workspaces_are_the_library_s():
+    """The workspace a graph declares for a reduction-split convolution is what the kernel library asks for: all of
+    it for `splits` ranges on every tile, and for splits = 1 exactly the size with which the library cuts the ragged
+    last round (a smaller one would cut less, a larger one would be wasted peak memory)."""
+    from paper_2010_14501_amd import monet
+    seen = 0
+    for g in (graphs.resnet50(batch=184), graphs.vgg16_bn(), graphs.unet(), graphs.mobilenet_v2(), graphs.googlenet()):
+        by_id = {n.id: n for n in g.nodes}
+        for n in g.nodes:
+            if n.op != "conv" or n.ins[0] <= 0:
+                continue
+            N, H, W, C = by_id[n.ins[0]].shape
+            K, a = n.shape[-1], n.attrs
+            shape = (N, H, W, C, K, a["R"], a["S"], a["stride"], a["pad"])
+            impls = [(0, i) for i in g.fimpls[n.id]]
+            impls += [(1, i) for b in g.bops if b["node"] == n.id and b["kind"] == "conv_dgrad" for i in g.bimpls[b["k"]]]
+            for which, impl in impls:
+                if impl["algo"] != "igemm_splitk":
+                    continue
+                need = monet.call("monet_conv_workspace_bytes", which, *shape, impl["splits"])
+                assert impl["ws"] == (need + 255) // 256 * 256 and need > 0, (g.params[n.pars[0]][1], which, impl, need)
+                seen += 1
+    assert seen > 60
+
+
 def _edit(text, drop=None, add=None):
     lines = text.splitlines()
     if drop is not None:
