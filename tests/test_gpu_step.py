@@ -99,6 +99,28 @@ def test_tiny_chain_all_16_subsets(tiny):
                 first[variants_name] = got
 
 
+def test_tiny_chain_schedules_of_the_integer_program(tiny):
+    """Schedules chosen by the 0-1 program of Section 4 (per-tensor bits, per-operator variants, in-place
+    recomputation) run like any other: peak as interpreted, within the budget the program was given, loss and
+    gradients within tolerance of the oracle."""
+    from workloads import ilp
+    g, exts, params, ref = tiny
+    store = M.Plan(g.text(), schedules.store_everything_schedule(g).text()).predicted_peak
+    peaks = []
+    for frac in (0.8, 0.6, 0.45):
+        budget = int(frac * store)
+        sch, obj, status = ilp.solve(g, budget, time_limit=120)
+        assert sch is not None, status
+        want = osch.interpret(g.text(), sch.text())
+        run = StepRunner(g.text(), sch.text(), exts, params, poison=True)
+        peak = run.step()
+        assert peak == want["peak"] == run.plan.exact_peak <= run.plan.predicted_peak <= budget, frac
+        assert abs(run.loss_value() - ref["loss"]) < ACT_TOL * abs(ref["loss"])
+        compare_grads(run.grads_numpy(), ref)
+        peaks.append(peak)
+    assert peaks[0] > peaks[-1]
+
+
 def test_tiny_chain_intermediates_and_masks(tiny):
     """Stop the step where tensors are still in memory and compare them with the oracle's."""
     g, exts, params, ref = tiny

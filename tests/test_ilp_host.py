@@ -1,0 +1,78 @@
+"""The 0-1 integer program of Section 4 (workloads/ilp.py) on graphs small enough to solve in seconds.
+
+Every solution is checked by parties that share no code with the program: the oracle's validator (Eq. 7, Eq. 8,
+Appendix C.3 / D), its closed-form memory model (the predicted peak is the quantity the program bounds), its
+objective (Eq. 9) and the executor's own lowering; optimality is checked against the brute-force search over
+checkpointed-block subsets, whose schedules are a subset of the program's feasible set."""
+import pytest
+
+from oracle import schedule as osch
+from oracle import search as osearch
+from workloads import graphs, ilp, schedules
+import paper_2010_14501_amd as M
+
+
+def check(g, sch, budget, obj):
+    gt, st = g.text(), sch.text()
+    og = osch.OGraph(gt)
+    osch.validate(og, osch.OSchedule(st, og))
+    cf = osch.closed_form(gt, st)
+    plan = M.Plan(gt, st)
+    assert cf["predicted_peak"] == plan.predicted_peak <= budget
+    assert cf["exact_peak"] == plan.exact_peak == osch.interpret(gt, st)["peak"]
+    assert abs(osch.objective(gt, st) - obj) <= 1e-9 * obj
+    return plan
+
+
+def test_tiny_chain_program_against_brute_force():
+    g = graphs.tiny_chain()
+    gt = g.text()
+    store = M.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
+    costs = []
+    for frac in (1.0, 0.8, 0.6, 0.45):
+        budget = int(frac * store)
+        sch, obj, status = ilp.solve(g, budget, time_limit=120)
+        assert sch is not None, (frac, status)
+        check(g, sch, budget, obj)
+        bf = osearch.brute_force(g, budget)
+        if bf is not None:
+            assert obj <= bf[0] * (1 + 1e-9), (frac, obj, bf[:4])
+        costs.append(obj)
+    assert costs == sorted(costs) and costs[0] < costs[-1]            # less memory never makes the step cheaper
+    # with the whole store-everything footprint available nothing is recomputed
+    sch, obj, _ = ilp.solve(g, store)
+    assert not any(sch.r[k] for k in sch.r)
+
+
+def test_program_reports_infeasibility():
+    g = graphs.tiny_chain()
+    sch, obj, status = ilp.solve(g, 20000)          # less than a single activation plus its gradient
+    assert sch is None
+
+
+def test_program_uses_the_cost_table_it_is_given():
+    """Making one backward variant free must make the program choose it wherever the budget allows."""
+    g = graphs.tiny_chain()
+    store = M.Plan(g.text(), schedules.store_everything_schedule(g).text()).predicted_peak
+    tau = {}
+    for b in g.bops:
+        if b["kind"] == "relu_bwd":
+            for l, d in enumerate(g.bimpls[b["k"]]):
+                tau[("b", b["k"], l)] = 0.0 if d["algo"] == "from_input" else 1e9
+    sch, obj, _ = ilp.solve(g, store, tau=tau)
+    for b in g.bops:
+        if b["kind"] == "relu_bwd":
+            assert g.bimpls[b["k"]][sch.stage_impl[b["k"]]]["algo"] == "from_input"
+    og = osch.OGraph(g.text())
+    osch.validate(og, osch.OSchedule(sch.text(), og))
+
+
+def test_small_resnet_program_beats_the_block_heuristic():
+    g = graphs.resnet50(batch=2, hw=32, classes=10, widths=(8, 16), depths=(1, 1), stem=8)
+    gt = g.text()
+    block = M.Plan(gt, schedules.block_output_schedule(g).text())
+    budget = block.predicted_peak
+    sch, obj, status = ilp.solve(g, budget, time_limit=240, mip_rel_gap=0.02)
+    assert sch is not None, status
+    check(g, sch, budget, obj)
+    assert obj <= osch.objective(gt, schedules.block_output_schedule(g).text()) * (1 + 1e-9)

@@ -14,8 +14,8 @@ Format:
     r <k> <i> impl=<l>                  r^k_i = 1 (aux nodes: impl=-1)
     s <k> <i>                           s^{k-1}_i = 1
 
-The ILP that would choose these bits is not part of this build.  `expand`
-stands in for it on a fixed policy: given the set F of tensors kept by the
+The integer program that chooses these bits lives in `ilp.py` (small graphs);
+`expand` is a fixed policy for everything else: given the set F of tensors kept by the
 forward pass and one backward implementation per operator, it recomputes a
 missing dependency from the nearest tensors still held, and keeps every
 tensor exactly until its last use (each tensor is recomputed at most once).
