@@ -26,18 +26,22 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("resnet50_b184", "conv_fwd"): 455.6e6}
 
 
-def build_workload(name):
+def build_workload(name, variants=None):
     from workloads import graphs, schedules
+    if name.endswith("_igemm"):          # the same workload with every convolution on the implicit GEMM (no Winograd form)
+        g, sch, batch, desc = build_workload(name[:-len("_igemm")], schedules.IGEMM_VARIANTS)
+        return g, sch, batch, desc + "; implicit-GEMM convolutions only"
+    lean_variants = schedules.DEFAULT_VARIANTS if variants is None else variants
     if name == "resnet50_b184":
         g = graphs.resnet50(batch=184)
-        return g, schedules.block_output_schedule(g), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient"
+        return g, schedules.block_output_schedule(g, lean_variants), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient, Winograd for the 3x3 layers with 256+ channels"
     if name.startswith("resnet50_b184_"):        # same network under another schedule
         g = graphs.resnet50(batch=184)
         kind = name[len("resnet50_b184_"):]
         if kind == "store_everything":
             return g, schedules.store_everything_schedule(g), 184, "store everything, standard variants (plain back-propagation)"
         if kind == "store_everything_lean":
-            return g, schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS), 184, "store everything the lean variants read"
+            return g, schedules.store_everything_schedule(g, lean_variants), 184, "store everything the lean variants read"
         if kind.startswith("budget_"):
             # block-level greedy search on the measured operator costs, peak budget = fraction of store-everything
             from workloads import search
@@ -45,7 +49,7 @@ def build_workload(name):
             frac = float(kind[len("budget_"):])
             tau = costs.read_table(os.path.join(ROOT, "workloads", "measured", "costs_resnet50_b184.txt"))
             store = monet.Plan(g.text(), schedules.store_everything_schedule(g).text()).exact_peak
-            levels, sch, peak, ms = search.greedy(g, tau, frac * store, monet.Plan)
+            levels, sch, peak, ms = search.greedy(g, tau, frac * store, monet.Plan, variants=lean_variants)
             return g, sch, 184, (f"greedy block-level search, budget {frac:.2f} x store-everything peak "
                                  f"({frac * store / 1e9:.2f} GB); block levels {''.join(map(str, levels))}; "
                                  f"predicted recomputation {ms:.1f} ms; lean variants")
@@ -62,16 +66,16 @@ def build_workload(name):
     for base, (make, batch, named, desc) in nets.items():
         if name == base:
             g = make()
-            return g, named(g), batch, desc + lean
+            return g, named(g, lean_variants), batch, desc + lean
         if name == base + "_block_outputs":
             g = make()
-            return g, schedules.block_output_schedule(g), batch, "keep block outputs, recompute block internals" + lean
+            return g, schedules.block_output_schedule(g, lean_variants), batch, "keep block outputs, recompute block internals" + lean
         if name == base + "_store_everything":
             g = make()
             return g, schedules.store_everything_schedule(g), batch, "store everything, standard variants"
     if name == "tiny_chain":
         g = graphs.tiny_chain()
-        return g, schedules.tiny_chain_schedule(g, {0, 2}), 2, "checkpoint blocks {0,2}, recompute {1,3}; lean variants"
+        return g, schedules.tiny_chain_schedule(g, {0, 2}, lean_variants), 2, "checkpoint blocks {0,2}, recompute {1,3}; lean variants"
     raise SystemExit(f"unknown workload {name}")
 
 

@@ -46,6 +46,13 @@ int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
 int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y,
                             int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                             float *ws, size_t ws_bytes, float *stats, float eps, float *scratch, size_t scratch_bytes);
+/* Winograd F(2x2, 3x3) form of a 3x3 / stride 1 / pad 1 convolution (Section 4 lists it among the implementations an
+ * operator chooses from; Appendix D: workspace against time).  adjoint == 0: out = y[N,H,W,K] from in = x[N,H,W,C]
+ * (needs C % 16 == 0, K % 4 == 0).  adjoint != 0: out = dx[N,H,W,C] (+)= from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).
+ * ws >= monet_conv_winograd_workspace_bytes (16 transformed filters + 4 x input + 4 x output), device memory. */
+int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
+                        int adjoint, int accumulate, float *ws, size_t ws_bytes);
+int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K);
 /* Workspace bytes for monet_conv_fwd (which = 0) / monet_conv_dgrad (which = 1) of this shape with `splits` ranges;
  * for splits == 1 the size that lets the ragged last round be cut as far as it pays (0: nothing to gain).
  * Negative: error code. */

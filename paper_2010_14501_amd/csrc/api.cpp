@@ -226,8 +226,12 @@ void run_forward(const StepCtx &c, const Launch &L) {
     const std::string &op = n.op;
     if (op == "conv") {
         const FwdImpl &im = n.fimpls[L.impl];
-        conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
-                 (size_t)(im.ws > 0 ? align_up(im.ws) : 0), false, c.feeds_stats(L) ? c.scratch() : nullptr);
+        if (im.algo == "winograd")
+            conv_winograd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), false, false, (float *)c.ptr(L.a[4]),
+                          (size_t)align_up(im.ws));
+        else
+            conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
+                     (size_t)(im.ws > 0 ? align_up(im.ws) : 0), false, c.feeds_stats(L) ? c.scratch() : nullptr);
     } else if (op == "tconv") {
         conv_dgrad(c.st, in0, c.weights[n.pars[0]], out, tconv_adjoint_shape(g, n), false);
     } else if (op == "dwconv") {
@@ -289,8 +293,11 @@ void run_backward(const StepCtx &c, const Launch &L) {
         conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits_of(im.algo, im.extra),
                    (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "conv_dgrad") {
-        conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0, splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
-                   (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+        if (im.algo == "winograd")
+            conv_winograd(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), true, acc0, (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
+        else
+            conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0, splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
+                       (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "tconv_wgrad") {
         // filter gradient of the adjoint convolution: its input is this operator's output gradient, its
         // output gradient this operator's input
@@ -477,6 +484,7 @@ bool conv_feeds_bn_stats(const Plan &pl, const Launch &L1, const Launch &L2) {
     const Node &cv = g.nodes[L1.id], &bn = g.nodes[L2.id];
     if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
     const ConvShape cs = conv_shape(g, cv);
+    if (cv.fimpls[L1.impl].algo == "winograd") return false;
     if (cs.C % 16 || cs.K % 4 || splits_of(cv.fimpls[L1.impl].algo, cv.fimpls[L1.impl].extra) != 1) return false;
     return bn_stats_in_row_groups(cs.M(), cs.K, (size_t)pl.scratch_bytes);
 }
@@ -851,6 +859,17 @@ extern "C" int monet_conv_fwd_bn_stats(void *stream, const float *x, const float
         conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, scratch);
         bn_stats((hipStream_t)stream, y, stats, cs.M(), cs.K, eps, scratch, scratch_bytes, true);
     });
+}
+extern "C" int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
+                                   int adjoint, int accumulate, float *ws, size_t ws_bytes) {
+    return guarded([&] {
+        conv_winograd((hipStream_t)stream, in, w, out, mk_conv(N, H, W, C, K, 3, 3, 1, 1), adjoint != 0, accumulate != 0, ws, ws_bytes);
+    });
+}
+extern "C" int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K) {
+    int64_t bytes = -1;
+    int rc = guarded([&] { bytes = (int64_t)winograd_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1)); });
+    return rc == MONET_OK ? bytes : (int64_t)rc;
 }
 extern "C" int64_t monet_conv_workspace_bytes(int which, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int splits) {
     int64_t bytes = -1;

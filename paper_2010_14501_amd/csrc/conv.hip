@@ -68,6 +68,7 @@ struct TileArgs {
     int meet_splits;           // <= 1: off
     float *part;               // (class, tile - main_tiles, range) x 64 x threads floats, register order
     float *stats_part;         // FWD, whole results only: BatchNorm partial statistics of the output (tile_stats.hpp), or null
+    int64_t batch_a, batch_b, batch_out;   // FWD with gridDim.z > 1: z-th GEMM of a batch, operands and result this many floats apart
 };
 
 // arrivals per split tile; zero whenever no convolution kernel is running (the last arrival puts its entry back)
@@ -101,6 +102,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     constexpr int KTAB = 256;
     __shared__ int2 ktab[HAS_KTAB ? KTAB : 1];   // x = ((r*W + s)*C + c), y = r | s << 8, or y < 0 beyond the reduction
 
+    if (MODE == FWD) {     // batched GEMMs (the 16 products of a Winograd convolution) share one launch
+        ta.a += (int64_t)blockIdx.z * ta.batch_a;
+        ta.b += (int64_t)blockIdx.z * ta.batch_b;
+        ta.out += (int64_t)blockIdx.z * ta.batch_out;
+    }
     const ConvShape &cs = ta.cs;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -858,6 +864,18 @@ size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
     if (sg.classes != 1 || tail == 0) return 0;
     const int64_t s = std::min<int64_t>({NUM_CU / tail, sg.steps / 4, 16});
     return s >= 2 ? (size_t)(s * tail * bm * bn * 4) : 0;
+}
+
+void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red) {
+    if (batch < 1 || rows < 1 || cols < 1 || red < 1 || red % BK || cols % 4) throw KernelError("gemm_batched: bad shape");
+    ConvShape cs{1, 1, (int)rows, red, cols, 1, 1, 1, 0, 1, (int)rows};
+    check_shape(cs);
+    TileArgs ta{};
+    ta.a = a; ta.b = b; ta.cs = cs;
+    ta.Mg = rows; ta.Ng = cols; ta.Kg = red;
+    ta.out_elems = rows * cols;
+    ta.batch_a = rows * red; ta.batch_b = (int64_t)cols * red; ta.batch_out = rows * cols;
+    launch_cfg<FWD>(pick_cfg(FWD, ta.Mg, ta.Ng), st, ta, true, batch, out, 1, nullptr, 0, (int64_t)red / BK, false, "gemm_batched");
 }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,

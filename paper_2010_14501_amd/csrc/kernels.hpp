@@ -43,6 +43,16 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws,
                 size_t ws_bytes);
 
+// `batch` independent GEMMs out[z][rows][cols] = a[z][rows][red] b[z][cols][red]^T in one launch (red % 16 == 0, cols % 4 == 0)
+void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red);
+// Winograd F(2x2, 3x3) for 3x3 / stride 1 / pad 1 layers.  adjoint = false: out = y[N,H,W,K] from in = x[N,H,W,C] (C % 16 == 0,
+// K % 4 == 0); adjoint = true: out = dx[N,H,W,C] from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).  Workspace: 16 transformed
+// filters, 4x the input and 4x the output (winograd_workspace_bytes).
+bool winograd_applies(const ConvShape &cs, bool adjoint);
+size_t winograd_workspace_bytes(const ConvShape &cs);
+void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, bool adjoint, bool accumulate,
+                   float *ws, size_t ws_bytes);
+
 // ---- depthwise convolution (K == C, filters C,R,S; at most 9 taps); HBM-bound, no matrix cores
 void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);
 void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate);

@@ -168,6 +168,39 @@ def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
     assert rel(got[:K], mean) < ACT_TOL and rel(got[K:], invstd) < ACT_TOL
 
 
+@pytest.mark.parametrize("case", [
+    (2, 14, 14, 64, 128),       # even map
+    (3, 7, 9, 32, 48),          # odd sizes: the last tile row / column is half outside the map
+    (1, 5, 5, 16, 16),          # smallest aligned channel counts
+    (5, 7, 7, 512, 512),        # deep reduction
+    (2, 56, 56, 64, 64),        # many tiles (1568 per GEMM)
+])
+def test_winograd_convolution_matches_oracle(case):
+    """F(2x2, 3x3) forward and input gradient (written and accumulated) against the oracle's direct definitions."""
+    torch = torch_mod()
+    N, H, W, C, K = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, 3, 3, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (9 * C))))
+    dy = rng.standard_normal((N, H, W, K), dtype=np.float32)
+    xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
+    dx, dwt, ddy = dev(x), dev(w), dev(dy)
+    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K)
+    assert need == 16 * 4 * (K * C + N * ((H + 1) // 2) * ((W + 1) // 2) * (C + K))
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need)
+    assert rel(y.cpu().numpy(), wt.act_from_oracle(nm.conv2d_fwd(xo, wo, 1, 1))) < ACT_TOL
+    gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
+    want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, 1, 1))
+    monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, 1, 0, ws.data_ptr(), need)
+    assert rel(gx.cpu().numpy(), want) < GRAD_TOL
+    monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, 1, 1, ws.data_ptr(), need)
+    assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    with pytest.raises(monet.MonetError):
+        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need - 4)
+
+
 def test_conv_wgrad_rejects_small_workspace():
     torch = torch_mod()
     t = torch.zeros(16 * 16 * 16 * 2, device="cuda")

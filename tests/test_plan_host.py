@@ -153,6 +153,10 @@ def test_graph_builder_workspaces_are_the_library_s():
             impls = [(0, i) for i in g.fimpls[n.id]]
             impls += [(1, i) for b in g.bops if b["node"] == n.id and b["kind"] == "conv_dgrad" for i in g.bimpls[b["k"]]]
             for which, impl in impls:
+                if impl["algo"] == "winograd":
+                    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K)
+                    assert impl["ws"] == (need + 255) // 256 * 256, (g.params[n.pars[0]][1], which, impl, need)
+                    seen += 1
                 if impl["algo"] != "igemm_splitk":
                     continue
                 need = monet.call("monet_conv_workspace_bytes", which, *shape, impl["splits"])

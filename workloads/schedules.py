@@ -26,10 +26,15 @@ from __future__ import annotations
 
 from .graphs import Graph
 
+# A tuple names implementations in order of preference: the first one the operator offers is taken (the graph
+# offers the workspace-hungry convolution variants only where they were measured to pay).
 DEFAULT_VARIANTS = dict(
     bn_bwd="from_output", relu_bwd="from_mask", relu6_bwd="from_mask", maxpool_bwd="from_index",
-    conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=True,
+    conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad=("winograd", "igemm_splitk"), conv_fwd=("winograd", "igemm_splitk"),
+    inplace=True,
 )
+# the same without the Winograd form: every convolution on the implicit GEMM
+IGEMM_VARIANTS = dict(DEFAULT_VARIANTS, conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk")
 STANDARD_VARIANTS = dict(
     bn_bwd="from_input", relu_bwd="from_output", relu6_bwd="from_output", maxpool_bwd="from_input",
     conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=False,
@@ -73,11 +78,11 @@ def choose_bimpls(g: Graph, variants, saved=None):
             want = want.get(node, want.get(None))
         impls = g.bimpls[k]
         l = 0
-        if want is not None:
-            for j, d in enumerate(impls):
-                if d["algo"] == want:
-                    l = j
-                    break
+        for name in ((want,) if isinstance(want, str) else (want or ())):
+            found = [j for j, d in enumerate(impls) if d["algo"] == name]
+            if found:
+                l = found[0]
+                break
         if saved is not None and kind in ("relu_bwd", "relu6_bwd"):
             aux = g.aux_of(node)
             if impls[l]["algo"] == "from_mask" and node in saved and aux not in saved:
@@ -129,10 +134,12 @@ def expand(g: Graph, F, bimpl, allow_inplace=True, conv_algo="igemm_splitk", hoi
     def pick_fimpl(i, inplace):
         n = g.nodes[i - 1]
         if n.op == "conv":
-            try:
-                return g.fimpl_index(i, conv_algo)
-            except KeyError:        # the preferred variant is only offered where it pays
-                return 0
+            for name in ((conv_algo,) if isinstance(conv_algo, str) else conv_algo):
+                try:
+                    return g.fimpl_index(i, name)
+                except KeyError:        # a preferred variant is only offered where it pays
+                    continue
+            return 0
         if inplace:
             return g.fimpl_index(i, "inplace")
         return 0
