@@ -77,7 +77,8 @@ __device__ unsigned g_meet_arrivals[MEET_SLOTS];
 
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
-template <int MODE, int WM, int WN, bool FAST>
+// TAG only names the use in profiles: 0 a convolution, 1 / 2 the batched GEMMs of a Winograd forward / input gradient
+template <int MODE, int WM, int WN, bool FAST, int TAG = 0>
 __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN == 4 ? 3 : 2))) void conv_tile_kernel(TileArgs ta) {
     // The square four-wave tile runs four workgroups per CU (4 x 40 KiB of LDS, 128 registers per lane) and
     // prefetches one reduction step; the other tiles keep two register stages (loads two steps ahead) at three
@@ -763,7 +764,7 @@ void check_shape(const ConvShape &cs) {
 // was measured too: the device-wide release each split workgroup performs costs more than the second kernel.)
 constexpr int NUM_CU = 256;
 
-template <int MODE, int WM, int WN>
+template <int MODE, int WM, int WN, int TAG = 0>
 void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim, float *out, int splits, float *ws, size_t ws_bytes, int64_t steps,
                  bool accumulate, const char *who) {
     constexpr int BM = 64 * WM, BN = 64 * WN, NT = 64 * WM * WN;
@@ -803,8 +804,13 @@ void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim, float *out, i
     }
     if (blocks > 0x7fffffffll) throw KernelError("conv: too many tiles");
     dim3 grid((unsigned)blocks, 1, (unsigned)zdim);
-    if (fast) hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true>), grid, dim3(NT), 0, st, ta);
-    else hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, false>), grid, dim3(NT), 0, st, ta);
+    if constexpr (TAG != 0) {
+        if (!fast) throw KernelError("conv: batched GEMMs need aligned shapes");
+        hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true, TAG>), grid, dim3(NT), 0, st, ta);
+    } else {
+        if (fast) hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true>), grid, dim3(NT), 0, st, ta);
+        else hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, false>), grid, dim3(NT), 0, st, ta);
+    }
     hip_check(hipGetLastError(), "conv launch");
     if (slabs) launch_split_reduce(st, ws, out, ta.out_elems, splits, MODE != WGRAD && accumulate);
 }
@@ -837,6 +843,13 @@ void launch_cfg(int cfg, Rest... rest) {
     }
 }
 
+// the batched GEMMs only ever see the two tile shapes the forward heuristic picks
+template <int TAG, class... Rest>
+void launch_batched(int cfg, Rest... rest) {
+    if (cfg == 1) launch_tile<FWD, 4, 1, TAG>(rest...);
+    else launch_tile<FWD, 2, 2, TAG>(rest...);
+}
+
 }  // namespace
 
 void conv_force_tile(int cfg) { g_cfg_override = cfg; }
@@ -866,7 +879,7 @@ size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
     return s >= 2 ? (size_t)(s * tail * bm * bn * 4) : 0;
 }
 
-void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red) {
+void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red, bool adjoint_use) {
     if (batch < 1 || rows < 1 || cols < 1 || red < 1 || red % BK || cols % 4) throw KernelError("gemm_batched: bad shape");
     ConvShape cs{1, 1, (int)rows, red, cols, 1, 1, 1, 0, 1, (int)rows};
     check_shape(cs);
@@ -875,7 +888,9 @@ void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, in
     ta.Mg = rows; ta.Ng = cols; ta.Kg = red;
     ta.out_elems = rows * cols;
     ta.batch_a = rows * red; ta.batch_b = (int64_t)cols * red; ta.batch_out = rows * cols;
-    launch_cfg<FWD>(pick_cfg(FWD, ta.Mg, ta.Ng), st, ta, true, batch, out, 1, nullptr, 0, (int64_t)red / BK, false, "gemm_batched");
+    const int cfg = cols <= 64 ? 1 : 0;
+    if (adjoint_use) launch_batched<2>(cfg, st, ta, true, batch, out, 1, (float *)nullptr, (size_t)0, (int64_t)red / BK, false, "gemm_batched");
+    else launch_batched<1>(cfg, st, ta, true, batch, out, 1, (float *)nullptr, (size_t)0, (int64_t)red / BK, false, "gemm_batched");
 }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,

@@ -44,7 +44,9 @@ void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, cons
                 size_t ws_bytes);
 
 // `batch` independent GEMMs out[z][rows][cols] = a[z][rows][red] b[z][cols][red]^T in one launch (red % 16 == 0, cols % 4 == 0)
-void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red);
+// (adjoint_use only picks the kernel's name in profiles: the GEMMs of an input gradient are listed apart from a forward pass's)
+void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red,
+                  bool adjoint_use = false);
 // Winograd F(2x2, 3x3) for 3x3 / stride 1 / pad 1 layers.  adjoint = false: out = y[N,H,W,K] from in = x[N,H,W,C] (C % 16 == 0,
 // K % 4 == 0); adjoint = true: out = dx[N,H,W,C] from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).  Workspace: 16 transformed
 // filters, 4x the input and 4x the output (winograd_workspace_bytes).

@@ -20,7 +20,10 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 // one thread per (output channel row, reduction channel column) of the 16 transformed filters
-__global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w, float *__restrict__ U, int K, int C, int adjoint) {
+// (ADJ, here and below: forward pass or input gradient -- two names in a profile, and for the filter two layouts)
+template <bool ADJ>
+__global__ __launch_bounds__(256) void wino_filter_kernel(const float *__restrict__ w, float *__restrict__ U, int K, int C) {
+    constexpr int adjoint = ADJ ? 1 : 0;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int rows = adjoint ? C : K, cols = adjoint ? K : C;
     if (idx >= (int64_t)rows * cols) return;
@@ -56,6 +59,7 @@ struct WinoGeom {
 };
 
 // one thread per (tile, four channels): V[z][tile][c] = (B^T d B)[z]
+template <bool ADJ>
 __global__ __launch_bounds__(256) void wino_input_kernel(const float *__restrict__ x, float *__restrict__ V, WinoGeom gm, int C) {
     const int C4 = C / 4;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -96,6 +100,7 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const float *__restrict
 }
 
 // one thread per (tile, four channels): the 2x2 outputs A^T m A, written or accumulated
+template <bool ADJ>
 __global__ __launch_bounds__(256) void wino_output_kernel(const float *__restrict__ M, float *y, WinoGeom gm, int K, int accumulate) {
     const int K4 = K / 4;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -163,15 +168,19 @@ void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, 
     const int red = adjoint ? cs.K : cs.C, outc = adjoint ? cs.C : cs.K;
     if (gm.T * (std::max(red, outc) / 4) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd: shape too large");
     float *U = ws, *V = U + (size_t)16 * cs.K * cs.C, *M = V + (size_t)16 * gm.T * red;
-    const int64_t fe = (int64_t)cs.K * cs.C;
-    hipLaunchKernelGGL(wino_filter_kernel, dim3((unsigned)((fe + 255) / 256)), dim3(256), 0, st, w, U, cs.K, cs.C, adjoint ? 1 : 0);
-    const int64_t ie = gm.T * (red / 4);
-    hipLaunchKernelGGL(wino_input_kernel, dim3((unsigned)((ie + 255) / 256)), dim3(256), 0, st, in, V, gm, red);
+    const int64_t fe = (int64_t)cs.K * cs.C, ie = gm.T * (red / 4), oe = gm.T * (outc / 4);
+    const dim3 fg((unsigned)((fe + 255) / 256)), ig((unsigned)((ie + 255) / 256)), og((unsigned)((oe + 255) / 256)), blk(256);
+    if (adjoint) {
+        hipLaunchKernelGGL(wino_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
+        hipLaunchKernelGGL(wino_input_kernel<true>, ig, blk, 0, st, in, V, gm, red);
+    } else {
+        hipLaunchKernelGGL(wino_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
+        hipLaunchKernelGGL(wino_input_kernel<false>, ig, blk, 0, st, in, V, gm, red);
+    }
     hip_check(hipGetLastError(), "winograd transform launch");
-    gemm_batched(st, V, U, M, 16, gm.T, outc, red);
-    const int64_t oe = gm.T * (outc / 4);
-    hipLaunchKernelGGL(wino_output_kernel, dim3((unsigned)((oe + 255) / 256)), dim3(256), 0, st, (const float *)M, out, gm, outc,
-                       accumulate ? 1 : 0);
+    gemm_batched(st, V, U, M, 16, gm.T, outc, red, adjoint);
+    if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, accumulate ? 1 : 0);
+    else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, accumulate ? 1 : 0);
     hip_check(hipGetLastError(), "winograd output launch");
 }
 

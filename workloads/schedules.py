@@ -37,7 +37,8 @@ DEFAULT_VARIANTS = dict(
 IGEMM_VARIANTS = dict(DEFAULT_VARIANTS, conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk")
 STANDARD_VARIANTS = dict(
     bn_bwd="from_input", relu_bwd="from_output", relu6_bwd="from_output", maxpool_bwd="from_input",
-    conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk", inplace=False,
+    conv_wgrad="splitk", tconv_wgrad="splitk", conv_dgrad=("winograd", "igemm_splitk"), conv_fwd=("winograd", "igemm_splitk"),
+    inplace=False,
 )
 
 
