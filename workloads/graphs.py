@@ -118,9 +118,10 @@ class Graph:
             self.fimpls[i].append(dict(algo="igemm_splitk", ws=ws, cost=flop * 0.8, splits=sp))
         # Winograd F(2x2, 3x3): 2.25x fewer multiplications for 16 transformed filters, 4x the input and 4x the
         # output as workspace.  Offered where it was measured faster than the implicit GEMM: 3x3 / stride 1 / pad 1
-        # with at least 256 channels on both sides (1.4-1.8x; only 1.04-1.2x at 128 for a workspace of 8x the layer's
-        # activations, slower at 64).
-        wino = R == 3 and S == 3 and stride == 1 and pad == 1 and C % 16 == 0 and K % 16 == 0 and min(C, K) >= 256
+        # with at least 256 channels on both sides (1.4-1.8x), or at least 128 on maps up to 28x28 (1.2-1.5x); at 128
+        # channels on large maps it gains 4 % for a workspace of 8x the layer's activations, at 64 it is slower.
+        wino = (R == 3 and S == 3 and stride == 1 and pad == 1 and C % 16 == 0 and K % 16 == 0
+                and (min(C, K) >= 256 or (min(C, K) >= 128 and H * W <= 28 * 28)))
         wino_ws = _align(16 * 4 * (K * C + N * ((H + 1) // 2) * ((W + 1) // 2) * (C + K)))
         if wino:
             self.fimpls[i].append(dict(algo="winograd", ws=wino_ws, cost=flop * 0.6))
