@@ -53,6 +53,12 @@ int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float 
 int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
                         int adjoint, int accumulate, float *ws, size_t ws_bytes);
 int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K);
+/* Filter gradient of such a layer in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
+ * (C % 4 == 0, K % 4 == 0); ws >= monet_conv_winograd_wgrad_workspace_bytes (4 x input + 4 x output gradient, 16 transformed
+ * filter gradients and their partial sums). */
+int monet_conv_winograd_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K,
+                              float *ws, size_t ws_bytes);
+int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K);
 /* Workspace bytes for monet_conv_fwd (which = 0) / monet_conv_dgrad (which = 1) of this shape with `splits` ranges;
  * for splits == 1 the size that lets the ragged last round be cut as far as it pays (0: nothing to gain).
  * Negative: error code. */

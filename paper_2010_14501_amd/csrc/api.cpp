@@ -290,8 +290,12 @@ void run_backward(const StepCtx &c, const Launch &L) {
     const bool acc0 = L.flags & 1;
     const std::string &kd = b.kind;
     if (kd == "conv_wgrad") {
-        conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits_of(im.algo, im.extra),
-                   (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
+        if (im.algo == "winograd")
+            conv_winograd_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), (float *)c.ptr(L.a[4]),
+                                (size_t)align_up(im.ws));
+        else
+            conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits_of(im.algo, im.extra),
+                       (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "conv_dgrad") {
         if (im.algo == "winograd")
             conv_winograd(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), true, acc0, (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
@@ -865,6 +869,15 @@ extern "C" int monet_conv_winograd(void *stream, const float *in, const float *w
     return guarded([&] {
         conv_winograd((hipStream_t)stream, in, w, out, mk_conv(N, H, W, C, K, 3, 3, 1, 1), adjoint != 0, accumulate != 0, ws, ws_bytes);
     });
+}
+extern "C" int monet_conv_winograd_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K,
+                                         float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_winograd_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, 3, 3, 1, 1), ws, ws_bytes); });
+}
+extern "C" int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K) {
+    int64_t bytes = -1;
+    int rc = guarded([&] { bytes = (int64_t)winograd_wgrad_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1)); });
+    return rc == MONET_OK ? bytes : (int64_t)rc;
 }
 extern "C" int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K) {
     int64_t bytes = -1;

@@ -68,7 +68,7 @@ struct TileArgs {
     int meet_splits;           // <= 1: off
     float *part;               // (class, tile - main_tiles, range) x 64 x threads floats, register order
     float *stats_part;         // FWD, whole results only: BatchNorm partial statistics of the output (tile_stats.hpp), or null
-    int64_t batch_a, batch_b, batch_out;   // FWD with gridDim.z > 1: z-th GEMM of a batch, operands and result this many floats apart
+    int64_t batch_a, batch_b, batch_out;   // FWD / WGRAD with gridDim.z > 1: z-th GEMM of a batch, operands and result this many floats apart
 };
 
 // arrivals per split tile; zero whenever no convolution kernel is running (the last arrival puts its entry back)
@@ -77,7 +77,8 @@ __device__ unsigned g_meet_arrivals[MEET_SLOTS];
 
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
-// TAG only names the use in profiles: 0 a convolution, 1 / 2 the batched GEMMs of a Winograd forward / input gradient
+// TAG only names the use in profiles: 0 a convolution, 1 / 2 / 3 the batched GEMMs of a Winograd forward / input gradient /
+// filter gradient
 template <int MODE, int WM, int WN, bool FAST, int TAG = 0>
 __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN == 4 ? 3 : 2))) void conv_tile_kernel(TileArgs ta) {
     // The square four-wave tile runs four workgroups per CU (4 x 40 KiB of LDS, 128 registers per lane) and
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     constexpr int KTAB = 256;
     __shared__ int2 ktab[HAS_KTAB ? KTAB : 1];   // x = ((r*W + s)*C + c), y = r | s << 8, or y < 0 beyond the reduction
 
-    if (MODE == FWD) {     // batched GEMMs (the 16 products of a Winograd convolution) share one launch
+    if (MODE != DGRAD) {   // batched GEMMs (the 16 products of a Winograd convolution) share one launch
         ta.a += (int64_t)blockIdx.z * ta.batch_a;
         ta.b += (int64_t)blockIdx.z * ta.batch_b;
         ta.out += (int64_t)blockIdx.z * ta.batch_out;
@@ -891,6 +892,21 @@ void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, in
     const int cfg = cols <= 64 ? 1 : 0;
     if (adjoint_use) launch_batched<2>(cfg, st, ta, true, batch, out, 1, (float *)nullptr, (size_t)0, (int64_t)red / BK, false, "gemm_batched");
     else launch_batched<1>(cfg, st, ta, true, batch, out, 1, (float *)nullptr, (size_t)0, (int64_t)red / BK, false, "gemm_batched");
+}
+
+// out[z][m][n] = sum_t a[z][t][m] b[z][t][n]: the reduction runs over the rows of both operands (weight-gradient form);
+// `splits` partial results per GEMM go to ws (splits * batch * m * n floats) and are added in range order
+void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t red, int m, int n, int splits,
+                     float *ws, size_t ws_bytes) {
+    if (batch < 1 || red < 1 || m < 1 || n < 1 || m % 4 || n % 4) throw KernelError("gemm_tn_batched: bad shape");
+    ConvShape cs{1, 1, (int)red, n, m, 1, 1, 1, 0, 1, (int)red};
+    check_shape(cs);
+    TileArgs ta{};
+    ta.a = a; ta.b = b; ta.cs = cs;
+    ta.Mg = m; ta.Ng = n; ta.Kg = red;
+    ta.out_elems = (int64_t)batch * m * n;
+    ta.batch_a = red * m; ta.batch_b = red * n; ta.batch_out = (int64_t)m * n;
+    launch_tile<WGRAD, 2, 2, 3>(st, ta, true, batch, out, splits, ws, ws_bytes, (red + BK - 1) / BK, false, "gemm_tn_batched");
 }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,

@@ -199,6 +199,12 @@ def test_winograd_convolution_matches_oracle(case):
     assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
     with pytest.raises(monet.MonetError):
         monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need - 4)
+    # filter gradient in the transformed domain
+    need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K)
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    gw = torch.full((K, 3, 3, C), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, ws.data_ptr(), need)
+    assert rel(gw.cpu().numpy(), wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, 3, 3, 1, 1))) < GRAD_TOL
 
 
 def test_conv_wgrad_rejects_small_workspace():

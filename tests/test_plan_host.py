@@ -150,6 +150,13 @@ def test_graph_builder_workspaces_are_the_library_s():
             N, H, W, C = by_id[n.ins[0]].shape
             K, a = n.shape[-1], n.attrs
             shape = (N, H, W, C, K, a["R"], a["S"], a["stride"], a["pad"])
+            for b in g.bops:
+                if b["node"] == n.id and b["kind"] == "conv_wgrad":
+                    for impl in g.bimpls[b["k"]]:
+                        if impl["algo"] == "winograd":
+                            need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K)
+                            assert impl["ws"] == (need + 255) // 256 * 256, (g.params[n.pars[0]][1], impl, need)
+                            seen += 1
             impls = [(0, i) for i in g.fimpls[n.id]]
             impls += [(1, i) for b in g.bops if b["node"] == n.id and b["kind"] == "conv_dgrad" for i in g.bimpls[b["k"]]]
             for which, impl in impls:

@@ -136,6 +136,11 @@ class Graph:
         wg = [dict(algo="direct", ws=0, cost=flop * 4.0)]
         for sp in wgrad_splits:
             wg.append(dict(algo="splitk", ws=_align(sp * wbytes), cost=flop * (1.0 + 0.02 * sp), splits=sp))
+        if wino:      # the filter gradient in the same transformed domain (measured 1.2-1.85x where it is offered)
+            T = N * ((H + 1) // 2) * ((W + 1) // 2)
+            ranges = max(1, min(1024 // (16 * math.ceil(K / 128) * math.ceil(C / 128)), T // 128))
+            wg.append(dict(algo="winograd", cost=flop * 0.65,
+                           ws=_align(4 * (16 * T * (C + K) + 16 * K * C * (1 + (ranges if ranges > 1 else 0))))))
         self._pending_bops(i, [("conv_dgrad", dg)] if x > 0 else [],
                            [("conv_wgrad", [dict(d, deps=[x] if x > 0 else []) for d in wg])])
         return i
