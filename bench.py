@@ -34,7 +34,7 @@ def build_workload(name, variants=None):
     lean_variants = schedules.DEFAULT_VARIANTS if variants is None else variants
     if name == "resnet50_b184":
         g = graphs.resnet50(batch=184)
-        return g, schedules.block_output_schedule(g, lean_variants), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient, Winograd for the 3x3 layers with 256+ channels"
+        return g, schedules.block_output_schedule(g, lean_variants), 184, "keep block outputs, recompute block internals; BN backward from output, ReLU backward from 1-bit mask, in-place BN/ReLU, split-K weight gradient, Winograd F(4x4, 3x3) for the 3x3 / stride-1 layers"
     if name.startswith("resnet50_b184_"):        # same network under another schedule
         g = graphs.resnet50(batch=184)
         kind = name[len("resnet50_b184_"):]

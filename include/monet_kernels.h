@@ -46,19 +46,21 @@ int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
 int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y,
                             int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                             float *ws, size_t ws_bytes, float *stats, float eps, float *scratch, size_t scratch_bytes);
-/* Winograd F(2x2, 3x3) form of a 3x3 / stride 1 / pad 1 convolution (Section 4 lists it among the implementations an
- * operator chooses from; Appendix D: workspace against time).  adjoint == 0: out = y[N,H,W,K] from in = x[N,H,W,C]
- * (needs C % 16 == 0, K % 4 == 0).  adjoint != 0: out = dx[N,H,W,C] (+)= from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).
- * ws >= monet_conv_winograd_workspace_bytes (16 transformed filters + 4 x input + 4 x output), device memory. */
+/* Winograd F(m x m, 3x3) form of a 3x3 / stride 1 / pad 1 convolution, m = 2 or 4 (Section 4 lists Winograd among the
+ * implementations an operator chooses from; Appendix D: workspace against time).  adjoint == 0: out = y[N,H,W,K] from
+ * in = x[N,H,W,C] (needs C % 16 == 0, K % 4 == 0).  adjoint != 0: out = dx[N,H,W,C] (+)= from in = dy[N,H,W,K]
+ * (K % 16 == 0, C % 4 == 0).  ws >= monet_conv_winograd_workspace_bytes ((m+2)^2 transformed filters and (m+2)^2 / m^2
+ * times the input and the output: 4 x for m = 2, 2.25 x for m = 4), device memory.  m = 4 needs 4 x fewer
+ * multiplications than the direct form (m = 2: 2.25 x) and rounds about ten times more coarsely. */
 int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
-                        int adjoint, int accumulate, float *ws, size_t ws_bytes);
-int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K);
+                        int m, int adjoint, int accumulate, float *ws, size_t ws_bytes);
+int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K, int m);
 /* Filter gradient of such a layer in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
- * (C % 4 == 0, K % 4 == 0); ws >= monet_conv_winograd_wgrad_workspace_bytes (4 x input + 4 x output gradient, 16 transformed
- * filter gradients and their partial sums). */
+ * (C % 4 == 0, K % 4 == 0); ws >= monet_conv_winograd_wgrad_workspace_bytes (the transformed input and output gradient,
+ * (m+2)^2 transformed filter gradients and their partial sums). */
 int monet_conv_winograd_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K,
-                              float *ws, size_t ws_bytes);
-int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K);
+                              int m, float *ws, size_t ws_bytes);
+int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K, int m);
 /* Workspace bytes for monet_conv_fwd (which = 0) / monet_conv_dgrad (which = 1) of this shape with `splits` ranges;
  * for splits == 1 the size that lets the ragged last round be cut as far as it pays (0: nothing to gain).
  * Negative: error code. */

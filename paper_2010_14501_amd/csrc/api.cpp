@@ -211,6 +211,9 @@ int64_t numel_of(const std::vector<int64_t> &s) {
 }
 
 // number of reduction splits an implementation record asks for ("splitk" / "igemm_splitk" carry splits=S)
+// output tile edge of a Winograd implementation name, 0 for any other
+int winograd_tile(const std::string &algo) { return algo == "winograd" ? 2 : algo == "winograd4" ? 4 : 0; }
+
 int splits_of(const std::string &algo, const Attrs &extra) {
     if (algo.find("splitk") == std::string::npos) return 1;
     auto it = extra.find("splits");
@@ -226,8 +229,8 @@ void run_forward(const StepCtx &c, const Launch &L) {
     const std::string &op = n.op;
     if (op == "conv") {
         const FwdImpl &im = n.fimpls[L.impl];
-        if (im.algo == "winograd")
-            conv_winograd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), false, false, (float *)c.ptr(L.a[4]),
+        if (const int m = winograd_tile(im.algo))
+            conv_winograd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), m, false, false, (float *)c.ptr(L.a[4]),
                           (size_t)align_up(im.ws));
         else
             conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
@@ -290,15 +293,15 @@ void run_backward(const StepCtx &c, const Launch &L) {
     const bool acc0 = L.flags & 1;
     const std::string &kd = b.kind;
     if (kd == "conv_wgrad") {
-        if (im.algo == "winograd")
-            conv_winograd_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), (float *)c.ptr(L.a[4]),
+        if (const int m = winograd_tile(im.algo))
+            conv_winograd_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), m, (float *)c.ptr(L.a[4]),
                                 (size_t)align_up(im.ws));
         else
             conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits_of(im.algo, im.extra),
                        (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "conv_dgrad") {
-        if (im.algo == "winograd")
-            conv_winograd(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), true, acc0, (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
+        if (const int m = winograd_tile(im.algo))
+            conv_winograd(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), m, true, acc0, (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
         else
             conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0, splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
                        (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
@@ -488,7 +491,7 @@ bool conv_feeds_bn_stats(const Plan &pl, const Launch &L1, const Launch &L2) {
     const Node &cv = g.nodes[L1.id], &bn = g.nodes[L2.id];
     if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
     const ConvShape cs = conv_shape(g, cv);
-    if (cv.fimpls[L1.impl].algo == "winograd") return false;
+    if (winograd_tile(cv.fimpls[L1.impl].algo)) return false;
     if (cs.C % 16 || cs.K % 4 || splits_of(cv.fimpls[L1.impl].algo, cv.fimpls[L1.impl].extra) != 1) return false;
     return bn_stats_in_row_groups(cs.M(), cs.K, (size_t)pl.scratch_bytes);
 }
@@ -865,23 +868,23 @@ extern "C" int monet_conv_fwd_bn_stats(void *stream, const float *x, const float
     });
 }
 extern "C" int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
-                                   int adjoint, int accumulate, float *ws, size_t ws_bytes) {
+                                   int m, int adjoint, int accumulate, float *ws, size_t ws_bytes) {
     return guarded([&] {
-        conv_winograd((hipStream_t)stream, in, w, out, mk_conv(N, H, W, C, K, 3, 3, 1, 1), adjoint != 0, accumulate != 0, ws, ws_bytes);
+        conv_winograd((hipStream_t)stream, in, w, out, mk_conv(N, H, W, C, K, 3, 3, 1, 1), m, adjoint != 0, accumulate != 0, ws, ws_bytes);
     });
 }
 extern "C" int monet_conv_winograd_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K,
-                                         float *ws, size_t ws_bytes) {
-    return guarded([&] { conv_winograd_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, 3, 3, 1, 1), ws, ws_bytes); });
+                                         int m, float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_winograd_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, 3, 3, 1, 1), m, ws, ws_bytes); });
 }
-extern "C" int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K) {
+extern "C" int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K, int m) {
     int64_t bytes = -1;
-    int rc = guarded([&] { bytes = (int64_t)winograd_wgrad_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1)); });
+    int rc = guarded([&] { bytes = (int64_t)winograd_wgrad_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1), m); });
     return rc == MONET_OK ? bytes : (int64_t)rc;
 }
-extern "C" int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K) {
+extern "C" int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K, int m) {
     int64_t bytes = -1;
-    int rc = guarded([&] { bytes = (int64_t)winograd_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1)); });
+    int rc = guarded([&] { bytes = (int64_t)winograd_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1), m); });
     return rc == MONET_OK ? bytes : (int64_t)rc;
 }
 extern "C" int64_t monet_conv_workspace_bytes(int which, int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int splits) {

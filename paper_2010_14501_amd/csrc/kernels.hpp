@@ -49,17 +49,17 @@ void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, in
                   bool adjoint_use = false);
 void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t red, int m, int n, int splits,
                      float *ws, size_t ws_bytes);
-// Winograd F(2x2, 3x3) for 3x3 / stride 1 / pad 1 layers.  adjoint = false: out = y[N,H,W,K] from in = x[N,H,W,C] (C % 16 == 0,
-// K % 4 == 0); adjoint = true: out = dx[N,H,W,C] from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).  Workspace: 16 transformed
-// filters, 4x the input and 4x the output (winograd_workspace_bytes).
+// Winograd F(m x m, 3x3), m = 2 or 4, for 3x3 / stride 1 / pad 1 layers.  adjoint = false: out = y[N,H,W,K] from in = x[N,H,W,C]
+// (C % 16 == 0, K % 4 == 0); adjoint = true: out = dx[N,H,W,C] from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).  Workspace:
+// (m+2)^2 transformed filters and (m+2)^2 / m^2 times the input and the output (winograd_workspace_bytes).
 bool winograd_applies(const ConvShape &cs, bool adjoint);
-size_t winograd_workspace_bytes(const ConvShape &cs);
-void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, bool adjoint, bool accumulate,
+size_t winograd_workspace_bytes(const ConvShape &cs, int m);
+void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, int m, bool adjoint, bool accumulate,
                    float *ws, size_t ws_bytes);
 // filter gradient in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
 // (C % 4 == 0, K % 4 == 0); workspace winograd_wgrad_workspace_bytes
-size_t winograd_wgrad_workspace_bytes(const ConvShape &cs);
-void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *ws, size_t ws_bytes);
+size_t winograd_wgrad_workspace_bytes(const ConvShape &cs, int m);
+void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int m, float *ws, size_t ws_bytes);
 
 // ---- depthwise convolution (K == C, filters C,R,S; at most 9 taps); HBM-bound, no matrix cores
 void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);

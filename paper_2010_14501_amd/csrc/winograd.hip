@@ -11,6 +11,12 @@
 // 4x the output as workspace and the traffic to fill and drain it, so it pays where channels are many and maps
 // small.  The input gradient of such a layer is the same computation on dy with the filter turned by 180 degrees
 // and its two channel axes exchanged (`adjoint`).
+//
+// The same scheme with 4x4 output tiles, F(4x4, 3x3), is the second set of kernels below: 6x6 input tiles, 36 GEMMs,
+// 4x fewer multiplications than the direct form and 2.25x the input plus 2.25x the output as workspace (Lavin and
+// Gray's matrices for the interpolation points 0, +-1, +-2 and infinity).  Its transforms have entries up to 8 and
+// down to 1/24, so it rounds about ten times more coarsely than F(2x2, 3x3); both stay far inside the tolerances
+// the parity tests use.
 #include "kernels.hpp"
 
 namespace monet {
@@ -204,12 +210,223 @@ __global__ __launch_bounds__(256) void wino_filter_back_kernel(const float *__re
     }
 }
 
-WinoGeom geom_of(const ConvShape &cs) {
+// ---------------------------------------------------------------- F(4x4, 3x3)
+typedef float f2 __attribute__((ext_vector_type(2)));
+
+// the five one-dimensional maps of F(4, 3)
+//   B^T = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0; 0 2 -1 -2 1 0; 0 4 0 -5 0 1]
+//   G   = [1/4 0 0; -1/6 -1/6 -1/6; -1/6 1/6 -1/6; 1/24 1/12 1/6; 1/24 -1/12 1/6; 0 0 1]
+//   A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]
+template <typename V>
+__device__ inline void w4_bt(V v0, V v1, V v2, V v3, V v4, V v5, V (&o)[6]) {
+    o[0] = 4.0f * v0 - 5.0f * v2 + v4;
+    o[1] = (v3 + v4) - 4.0f * (v1 + v2);
+    o[2] = 4.0f * (v1 - v2) + (v4 - v3);
+    o[3] = 2.0f * (v3 - v1) + (v4 - v2);
+    o[4] = 2.0f * (v1 - v3) + (v4 - v2);
+    o[5] = 4.0f * v1 - 5.0f * v3 + v5;
+}
+__device__ inline void w4_g(float g0, float g1, float g2, float (&o)[6]) {
+    o[0] = 0.25f * g0;
+    o[1] = (-1.0f / 6.0f) * (g0 + g1 + g2);
+    o[2] = (-1.0f / 6.0f) * (g0 - g1 + g2);
+    o[3] = (1.0f / 24.0f) * g0 + (1.0f / 12.0f) * g1 + (1.0f / 6.0f) * g2;
+    o[4] = (1.0f / 24.0f) * g0 - (1.0f / 12.0f) * g1 + (1.0f / 6.0f) * g2;
+    o[5] = g2;
+}
+template <typename V>
+__device__ inline void w4_at(V m0, V m1, V m2, V m3, V m4, V m5, V (&o)[4]) {
+    const V p = m1 + m2, q = m1 - m2, r = m3 + m4, t = m3 - m4;
+    o[0] = m0 + p + r;
+    o[1] = q + 2.0f * t;
+    o[2] = p + 4.0f * r;
+    o[3] = q + 8.0f * t + m5;
+}
+template <typename V>
+__device__ inline void w4_a(V e0, V e1, V e2, V e3, V (&o)[6]) {      // A e: the transpose of w4_at's map
+    o[0] = e0;
+    o[1] = (e0 + e2) + (e1 + e3);
+    o[2] = (e0 + e2) - (e1 + e3);
+    o[3] = (e0 + 4.0f * e2) + (2.0f * e1 + 8.0f * e3);
+    o[4] = (e0 + 4.0f * e2) - (2.0f * e1 + 8.0f * e3);
+    o[5] = e3;
+}
+__device__ inline void w4_gt(float u0, float u1, float u2, float u3, float u4, float u5, float (&o)[3]) {   // G^T u
+    o[0] = 0.25f * u0 - (1.0f / 6.0f) * (u1 + u2) + (1.0f / 24.0f) * (u3 + u4);
+    o[1] = (1.0f / 6.0f) * (u2 - u1) + (1.0f / 12.0f) * (u3 - u4);
+    o[2] = (1.0f / 6.0f) * ((u3 + u4) - (u1 + u2)) + u5;
+}
+
+// one thread per (output channel row, reduction channel column) of the 36 transformed filters
+template <bool ADJ>
+__global__ __launch_bounds__(256) void wino4_filter_kernel(const float *__restrict__ w, float *__restrict__ U, int K, int C) {
+    constexpr int adjoint = ADJ ? 1 : 0;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int rows = adjoint ? C : K, cols = adjoint ? K : C;
+    const int64_t plane = (int64_t)rows * cols;
+    if (idx >= plane) return;
+    const int row = (int)(idx / cols), col = (int)(idx % cols);
+    float g[3][3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+            g[r][s] = adjoint ? w[((int64_t)col * 9 + (2 - r) * 3 + (2 - s)) * C + row] : w[((int64_t)row * 9 + r * 3 + s) * C + col];
+    float t[3][6];      // t[s][a] = (G g)[a][s]
+#pragma unroll
+    for (int s = 0; s < 3; ++s) w4_g(g[0][s], g[1][s], g[2][s], t[s]);
+#pragma unroll
+    for (int a = 0; a < 6; ++a) {
+        float u[6];
+        w4_g(t[0][a], t[1][a], t[2][a], u);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) U[(6 * a + b) * plane + idx] = u[b];
+    }
+}
+
+// one thread per (tile, two channels): V[z][tile][c] = (B^T d B)[z] of the 6x6 input tile
+template <int USE>
+__global__ __launch_bounds__(256) void wino4_input_kernel(const float *__restrict__ x, float *__restrict__ V, WinoGeom gm, int C) {
+    const int C2 = C / 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= gm.T * C2) return;
+    const int c2 = (int)(idx % C2);
+    const int64_t t = idx / C2;
+    const int tj = (int)(t % gm.tw);
+    const int64_t r = t / gm.tw;
+    const int ti = (int)(r % gm.th), n = (int)(r / gm.th);
+    const int h0 = 4 * ti - 1, w0 = 4 * tj - 1;
+    f2 m[6][6];      // m[b][a] = (B^T d)[a][b]
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        f2 d[6];
+        const int w = w0 + b;
+#pragma unroll
+        for (int a = 0; a < 6; ++a) {
+            const int h = h0 + a;
+            d[a] = f2{0, 0};
+            if ((unsigned)h < (unsigned)gm.H && (unsigned)w < (unsigned)gm.W)
+                d[a] = *(const f2 *)(x + (((int64_t)n * gm.H + h) * gm.W + w) * C + 2 * c2);
+        }
+        w4_bt(d[0], d[1], d[2], d[3], d[4], d[5], m[b]);
+    }
+    const int64_t plane = gm.T * C;
+    float *dst = V + t * C + 2 * c2;
+#pragma unroll
+    for (int a = 0; a < 6; ++a) {
+        f2 o[6];
+        w4_bt(m[0][a], m[1][a], m[2][a], m[3][a], m[4][a], m[5][a], o);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) *(f2 *)(dst + (6 * a + b) * plane) = o[b];
+    }
+}
+
+// one thread per (tile, two channels): the 4x4 outputs A^T m A, written or accumulated
+template <bool ADJ>
+__global__ __launch_bounds__(256) void wino4_output_kernel(const float *__restrict__ M, float *y, WinoGeom gm, int K, int accumulate) {
+    const int K2 = K / 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= gm.T * K2) return;
+    const int k2 = (int)(idx % K2);
+    const int64_t t = idx / K2;
+    const int tj = (int)(t % gm.tw);
+    const int64_t r = t / gm.tw;
+    const int ti = (int)(r % gm.th), n = (int)(r / gm.th);
+    const int64_t plane = gm.T * K;
+    const float *src = M + t * K + 2 * k2;
+    f2 s[6][4];      // s[b][a] = (A^T m)[a][b]
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        f2 m[6];
+#pragma unroll
+        for (int a = 0; a < 6; ++a) m[a] = *(const f2 *)(src + (6 * a + b) * plane);
+        w4_at(m[0], m[1], m[2], m[3], m[4], m[5], s[b]);
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int h = 4 * ti + a;
+        if (h >= gm.H) continue;
+        f2 o[4];
+        w4_at(s[0][a], s[1][a], s[2][a], s[3][a], s[4][a], s[5][a], o);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int w = 4 * tj + b;
+            if (w >= gm.W) continue;
+            f2 *dst = (f2 *)(y + (((int64_t)n * gm.H + h) * gm.W + w) * K + 2 * k2);
+            *dst = accumulate ? *dst + o[b] : o[b];
+        }
+    }
+}
+
+// one thread per (tile, two channels): D[z][tile][k] = (A dy A^T)[z] for the 4x4 output-gradient tile
+__global__ __launch_bounds__(256) void wino4_dy_kernel(const float *__restrict__ dy, float *__restrict__ D, WinoGeom gm, int K) {
+    const int K2 = K / 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= gm.T * K2) return;
+    const int k2 = (int)(idx % K2);
+    const int64_t t = idx / K2;
+    const int tj = (int)(t % gm.tw);
+    const int64_t r = t / gm.tw;
+    const int ti = (int)(r % gm.th), n = (int)(r / gm.th);
+    f2 m[4][6];      // m[b][a] = (A dy)[a][b]
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        f2 e[4];
+        const int w = 4 * tj + b;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int h = 4 * ti + a;
+            e[a] = f2{0, 0};
+            if (h < gm.H && w < gm.W) e[a] = *(const f2 *)(dy + (((int64_t)n * gm.H + h) * gm.W + w) * K + 2 * k2);
+        }
+        w4_a(e[0], e[1], e[2], e[3], m[b]);
+    }
+    const int64_t plane = gm.T * K;
+    float *dst = D + t * K + 2 * k2;
+#pragma unroll
+    for (int a = 0; a < 6; ++a) {
+        f2 o[6];
+        w4_a(m[0][a], m[1][a], m[2][a], m[3][a], o);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) *(f2 *)(dst + (6 * a + b) * plane) = o[b];
+    }
+}
+
+// one thread per (k, c): dw[k][r][s][c] = (G^T dU G)[r][s]
+__global__ __launch_bounds__(256) void wino4_filter_back_kernel(const float *__restrict__ dU, float *__restrict__ dw, int K, int C) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t plane = (int64_t)K * C;
+    if (idx >= plane) return;
+    const int k = (int)(idx / C), c = (int)(idx % C);
+    float t[6][3];      // t[b][r] = (G^T dU)[r][b]
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        float u[6];
+#pragma unroll
+        for (int a = 0; a < 6; ++a) u[a] = dU[(6 * a + b) * plane + idx];
+        w4_gt(u[0], u[1], u[2], u[3], u[4], u[5], t[b]);
+    }
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        float o[3];
+        w4_gt(t[0][r], t[1][r], t[2][r], t[3][r], t[4][r], t[5][r], o);
+        float *dst = dw + ((int64_t)k * 9 + r * 3) * C + c;
+        dst[0] = o[0];
+        dst[C] = o[1];
+        dst[2 * C] = o[2];
+    }
+}
+
+WinoGeom geom_of(const ConvShape &cs, int m) {
     WinoGeom gm;
     gm.N = cs.N; gm.H = cs.H; gm.W = cs.W;
-    gm.th = (cs.H + 1) / 2; gm.tw = (cs.W + 1) / 2;
+    gm.th = (cs.H + m - 1) / m; gm.tw = (cs.W + m - 1) / m;
     gm.T = (int64_t)cs.N * gm.th * gm.tw;
     return gm;
+}
+
+void check_tile(int m, const char *who) {
+    if (m != 2 && m != 4) throw KernelError(std::string(who) + ": output tile edge must be 2 or 4");
 }
 
 }  // namespace
@@ -220,67 +437,95 @@ bool winograd_applies(const ConvShape &cs, bool adjoint) {
     return red % 16 == 0 && out % 4 == 0;
 }
 
-size_t winograd_workspace_bytes(const ConvShape &cs) {
-    const WinoGeom gm = geom_of(cs);
-    return (size_t)16 * ((size_t)cs.K * cs.C + (size_t)gm.T * cs.C + (size_t)gm.T * cs.K) * sizeof(float);
+size_t winograd_workspace_bytes(const ConvShape &cs, int m) {
+    check_tile(m, "winograd_workspace_bytes");
+    const WinoGeom gm = geom_of(cs, m);
+    return (size_t)((m + 2) * (m + 2)) * ((size_t)cs.K * cs.C + (size_t)gm.T * cs.C + (size_t)gm.T * cs.K) * sizeof(float);
 }
 
 // adjoint = false: y[N,H,W,K] (+)= conv3x3(x[N,H,W,C], w[K,3,3,C]);  adjoint = true: in = dy[N,H,W,K], out = dx[N,H,W,C] (+)=
-void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, bool adjoint, bool accumulate,
+void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, int m, bool adjoint, bool accumulate,
                    float *ws, size_t ws_bytes) {
+    check_tile(m, "conv_winograd");
     if (!winograd_applies(cs, adjoint)) throw KernelError("conv_winograd: needs a 3x3 / stride 1 / pad 1 layer with aligned channel counts");
-    if (!ws || ws_bytes < winograd_workspace_bytes(cs)) throw KernelError("conv_winograd: workspace too small");
-    const WinoGeom gm = geom_of(cs);
-    const int red = adjoint ? cs.K : cs.C, outc = adjoint ? cs.C : cs.K;
-    if (gm.T * (std::max(red, outc) / 4) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd: shape too large");
-    float *U = ws, *V = U + (size_t)16 * cs.K * cs.C, *M = V + (size_t)16 * gm.T * red;
-    const int64_t fe = (int64_t)cs.K * cs.C, ie = gm.T * (red / 4), oe = gm.T * (outc / 4);
+    if (!ws || ws_bytes < winograd_workspace_bytes(cs, m)) throw KernelError("conv_winograd: workspace too small");
+    const WinoGeom gm = geom_of(cs, m);
+    const int red = adjoint ? cs.K : cs.C, outc = adjoint ? cs.C : cs.K, planes = (m + 2) * (m + 2), vec = m == 2 ? 4 : 2;
+    if (gm.T * (std::max(red, outc) / vec) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd: shape too large");
+    float *U = ws, *V = U + (size_t)planes * cs.K * cs.C, *M = V + (size_t)planes * gm.T * red;
+    const int64_t fe = (int64_t)cs.K * cs.C, ie = gm.T * (red / vec), oe = gm.T * (outc / vec);
     const dim3 fg((unsigned)((fe + 255) / 256)), ig((unsigned)((ie + 255) / 256)), og((unsigned)((oe + 255) / 256)), blk(256);
-    if (adjoint) {
-        hipLaunchKernelGGL(wino_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
-        hipLaunchKernelGGL(wino_input_kernel<1>, ig, blk, 0, st, in, V, gm, red);
+    if (m == 2) {
+        if (adjoint) {
+            hipLaunchKernelGGL(wino_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
+            hipLaunchKernelGGL(wino_input_kernel<1>, ig, blk, 0, st, in, V, gm, red);
+        } else {
+            hipLaunchKernelGGL(wino_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
+            hipLaunchKernelGGL(wino_input_kernel<0>, ig, blk, 0, st, in, V, gm, red);
+        }
     } else {
-        hipLaunchKernelGGL(wino_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
-        hipLaunchKernelGGL(wino_input_kernel<0>, ig, blk, 0, st, in, V, gm, red);
+        if (adjoint) {
+            hipLaunchKernelGGL(wino4_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
+            hipLaunchKernelGGL(wino4_input_kernel<1>, ig, blk, 0, st, in, V, gm, red);
+        } else {
+            hipLaunchKernelGGL(wino4_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
+            hipLaunchKernelGGL(wino4_input_kernel<0>, ig, blk, 0, st, in, V, gm, red);
+        }
     }
     hip_check(hipGetLastError(), "winograd transform launch");
-    gemm_batched(st, V, U, M, 16, gm.T, outc, red, adjoint);
-    if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, accumulate ? 1 : 0);
-    else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, accumulate ? 1 : 0);
+    gemm_batched(st, V, U, M, planes, gm.T, outc, red, adjoint);
+    const int acc = accumulate ? 1 : 0;
+    if (m == 2) {
+        if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
+        else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
+    } else {
+        if (adjoint) hipLaunchKernelGGL(wino4_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
+        else hipLaunchKernelGGL(wino4_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
+    }
     hip_check(hipGetLastError(), "winograd output launch");
 }
 
 namespace {
-// ranges of tiles per GEMM of the filter gradient: 16 x (K/128) x (C/128) output tiles, about 1024 workgroups in all,
+// ranges of tiles per GEMM of the filter gradient: planes x (K/128) x (C/128) output tiles, about 1024 workgroups in all,
 // at least eight reduction steps each
-int wgrad_ranges(const ConvShape &cs, int64_t T) {
-    const int64_t tiles = 16 * ((cs.K + 127) / 128) * ((cs.C + 127) / 128);
+int wgrad_ranges(const ConvShape &cs, int64_t T, int planes) {
+    const int64_t tiles = (int64_t)planes * ((cs.K + 127) / 128) * ((cs.C + 127) / 128);
     return (int)std::max<int64_t>(1, std::min<int64_t>(1024 / tiles, T / 128));
 }
 }  // namespace
 
-size_t winograd_wgrad_workspace_bytes(const ConvShape &cs) {
-    const WinoGeom gm = geom_of(cs);
-    const int sp = wgrad_ranges(cs, gm.T);
-    const size_t filt = (size_t)16 * cs.K * cs.C;
-    return ((size_t)16 * gm.T * (cs.C + cs.K) + filt + (sp > 1 ? (size_t)sp * filt : 0)) * sizeof(float);
+size_t winograd_wgrad_workspace_bytes(const ConvShape &cs, int m) {
+    check_tile(m, "winograd_wgrad_workspace_bytes");
+    const WinoGeom gm = geom_of(cs, m);
+    const int planes = (m + 2) * (m + 2), sp = wgrad_ranges(cs, gm.T, planes);
+    const size_t filt = (size_t)planes * cs.K * cs.C;
+    return ((size_t)planes * gm.T * (cs.C + cs.K) + filt + (sp > 1 ? (size_t)sp * filt : 0)) * sizeof(float);
 }
 
-void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *ws, size_t ws_bytes) {
+void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int m, float *ws, size_t ws_bytes) {
+    check_tile(m, "conv_winograd_wgrad");
     if (cs.R != 3 || cs.S != 3 || cs.stride != 1 || cs.pad != 1 || cs.C % 4 || cs.K % 4)
         throw KernelError("conv_winograd_wgrad: needs a 3x3 / stride 1 / pad 1 layer with channel counts that are multiples of 4");
-    if (!ws || ws_bytes < winograd_wgrad_workspace_bytes(cs)) throw KernelError("conv_winograd_wgrad: workspace too small");
-    const WinoGeom gm = geom_of(cs);
-    if (gm.T * (std::max(cs.C, cs.K) / 4) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd_wgrad: shape too large");
-    const int sp = wgrad_ranges(cs, gm.T);
-    const size_t filt = (size_t)16 * cs.K * cs.C;
-    float *V = ws, *D = V + (size_t)16 * gm.T * cs.C, *dU = D + (size_t)16 * gm.T * cs.K, *slabs = dU + filt;
-    const int64_t ie = gm.T * (cs.C / 4), de = gm.T * (cs.K / 4), fe = (int64_t)cs.K * cs.C;
-    hipLaunchKernelGGL(wino_input_kernel<2>, dim3((unsigned)((ie + 255) / 256)), dim3(256), 0, st, x, V, gm, cs.C);
-    hipLaunchKernelGGL(wino_dy_kernel, dim3((unsigned)((de + 255) / 256)), dim3(256), 0, st, dy, D, gm, cs.K);
+    if (!ws || ws_bytes < winograd_wgrad_workspace_bytes(cs, m)) throw KernelError("conv_winograd_wgrad: workspace too small");
+    const WinoGeom gm = geom_of(cs, m);
+    const int planes = (m + 2) * (m + 2), vec = m == 2 ? 4 : 2;
+    if (gm.T * (std::max(cs.C, cs.K) / vec) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd_wgrad: shape too large");
+    const int sp = wgrad_ranges(cs, gm.T, planes);
+    const size_t filt = (size_t)planes * cs.K * cs.C;
+    float *V = ws, *D = V + (size_t)planes * gm.T * cs.C, *dU = D + (size_t)planes * gm.T * cs.K, *slabs = dU + filt;
+    const int64_t ie = gm.T * (cs.C / vec), de = gm.T * (cs.K / vec), fe = (int64_t)cs.K * cs.C;
+    const dim3 ig((unsigned)((ie + 255) / 256)), dg((unsigned)((de + 255) / 256)), fg((unsigned)((fe + 255) / 256)), blk(256);
+    if (m == 2) {
+        hipLaunchKernelGGL(wino_input_kernel<2>, ig, blk, 0, st, x, V, gm, cs.C);
+        hipLaunchKernelGGL(wino_dy_kernel, dg, blk, 0, st, dy, D, gm, cs.K);
+    } else {
+        hipLaunchKernelGGL(wino4_input_kernel<2>, ig, blk, 0, st, x, V, gm, cs.C);
+        hipLaunchKernelGGL(wino4_dy_kernel, dg, blk, 0, st, dy, D, gm, cs.K);
+    }
     hip_check(hipGetLastError(), "winograd transform launch");
-    gemm_tn_batched(st, D, V, dU, 16, gm.T, cs.K, cs.C, sp, sp > 1 ? slabs : nullptr, sp > 1 ? (size_t)sp * filt * sizeof(float) : 0);
-    hipLaunchKernelGGL(wino_filter_back_kernel, dim3((unsigned)((fe + 255) / 256)), dim3(256), 0, st, (const float *)dU, dw, cs.K, cs.C);
+    gemm_tn_batched(st, D, V, dU, planes, gm.T, cs.K, cs.C, sp, sp > 1 ? slabs : nullptr, sp > 1 ? (size_t)sp * filt * sizeof(float) : 0);
+    if (m == 2) hipLaunchKernelGGL(wino_filter_back_kernel, fg, blk, 0, st, (const float *)dU, dw, cs.K, cs.C);
+    else hipLaunchKernelGGL(wino4_filter_back_kernel, fg, blk, 0, st, (const float *)dU, dw, cs.K, cs.C);
     hip_check(hipGetLastError(), "winograd filter gradient launch");
 }
 

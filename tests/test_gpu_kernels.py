@@ -168,15 +168,18 @@ def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
     assert rel(got[:K], mean) < ACT_TOL and rel(got[K:], invstd) < ACT_TOL
 
 
+@pytest.mark.parametrize("m", [2, 4])
 @pytest.mark.parametrize("case", [
-    (2, 14, 14, 64, 128),       # even map
-    (3, 7, 9, 32, 48),          # odd sizes: the last tile row / column is half outside the map
+    (2, 14, 14, 64, 128),       # even map (for 4x4 tiles: the last tile row / column is half outside)
+    (3, 7, 9, 32, 48),          # odd sizes: the last tile row / column is partly outside the map
     (1, 5, 5, 16, 16),          # smallest aligned channel counts
     (5, 7, 7, 512, 512),        # deep reduction
-    (2, 56, 56, 64, 64),        # many tiles (1568 per GEMM)
+    (2, 56, 56, 64, 64),        # many tiles (1568 resp. 392 per GEMM)
+    (1, 3, 2, 16, 16),          # a map smaller than one 4x4 tile
 ])
-def test_winograd_convolution_matches_oracle(case):
-    """F(2x2, 3x3) forward and input gradient (written and accumulated) against the oracle's direct definitions."""
+def test_winograd_convolution_matches_oracle(case, m):
+    """F(2x2, 3x3) and F(4x4, 3x3): forward, input gradient (written and accumulated) and filter gradient against the
+    oracle's direct definitions."""
     torch = torch_mod()
     N, H, W, C, K = case
     rng = np.random.default_rng(hash(case) % (2 ** 32))
@@ -185,25 +188,28 @@ def test_winograd_convolution_matches_oracle(case):
     dy = rng.standard_normal((N, H, W, K), dtype=np.float32)
     xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
     dx, dwt, ddy = dev(x), dev(w), dev(dy)
-    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K)
-    assert need == 16 * 4 * (K * C + N * ((H + 1) // 2) * ((W + 1) // 2) * (C + K))
+    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K, m)
+    tiles = N * ((H + m - 1) // m) * ((W + m - 1) // m)
+    assert need == (m + 2) ** 2 * 4 * (K * C + tiles * (C + K))
     ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
     y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
-    monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need)
+    monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, m, 0, 0, ws.data_ptr(), need)
     assert rel(y.cpu().numpy(), wt.act_from_oracle(nm.conv2d_fwd(xo, wo, 1, 1))) < ACT_TOL
     gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
     want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, 1, 1))
-    monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, 1, 0, ws.data_ptr(), need)
+    monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, m, 1, 0, ws.data_ptr(), need)
     assert rel(gx.cpu().numpy(), want) < GRAD_TOL
-    monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, 1, 1, ws.data_ptr(), need)
+    monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, m, 1, 1, ws.data_ptr(), need)
     assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
     with pytest.raises(monet.MonetError):
-        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need - 4)
+        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, m, 0, 0, ws.data_ptr(), need - 4)
+    with pytest.raises(monet.MonetError):
+        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 3, 0, 0, ws.data_ptr(), need)
     # filter gradient in the transformed domain
-    need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K)
+    need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K, m)
     ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
     gw = torch.full((K, 3, 3, C), float("nan"), dtype=torch.float32, device="cuda")
-    monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, ws.data_ptr(), need)
+    monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, m, ws.data_ptr(), need)
     assert rel(gw.cpu().numpy(), wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, 3, 3, 1, 1))) < GRAD_TOL
 
 

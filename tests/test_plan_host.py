@@ -153,15 +153,15 @@ def test_graph_builder_workspaces_are_the_library_s():
             for b in g.bops:
                 if b["node"] == n.id and b["kind"] == "conv_wgrad":
                     for impl in g.bimpls[b["k"]]:
-                        if impl["algo"] == "winograd":
-                            need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K)
+                        if impl["algo"] in ("winograd", "winograd4"):
+                            need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K, 2 if impl["algo"] == "winograd" else 4)
                             assert impl["ws"] == (need + 255) // 256 * 256, (g.params[n.pars[0]][1], impl, need)
                             seen += 1
             impls = [(0, i) for i in g.fimpls[n.id]]
             impls += [(1, i) for b in g.bops if b["node"] == n.id and b["kind"] == "conv_dgrad" for i in g.bimpls[b["k"]]]
             for which, impl in impls:
-                if impl["algo"] == "winograd":
-                    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K)
+                if impl["algo"] in ("winograd", "winograd4"):
+                    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K, 2 if impl["algo"] == "winograd" else 4)
                     assert impl["ws"] == (need + 255) // 256 * 256, (g.params[n.pars[0]][1], which, impl, need)
                     seen += 1
                 if impl["algo"] != "igemm_splitk":

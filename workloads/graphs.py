@@ -120,14 +120,33 @@ class Graph:
         # output as workspace.  Offered where it was measured faster than the implicit GEMM: 3x3 / stride 1 / pad 1
         # with at least 256 channels on both sides (1.4-1.8x), or at least 128 on maps up to 28x28 (1.2-1.5x); at 128
         # channels on large maps it gains 4 % for a workspace of 8x the layer's activations, at 64 it is slower.
-        wino = (R == 3 and S == 3 and stride == 1 and pad == 1 and C % 16 == 0 and K % 16 == 0
-                and (min(C, K) >= 256 or (min(C, K) >= 128 and H * W <= 28 * 28)))
-        wino_ws = _align(16 * 4 * (K * C + N * ((H + 1) // 2) * ((W + 1) // 2) * (C + K)))
+        eligible = R == 3 and S == 3 and stride == 1 and pad == 1 and C % 16 == 0 and K % 16 == 0
+        wino = eligible and (min(C, K) >= 256 or (min(C, K) >= 128 and H * W <= 28 * 28))
+        # F(4x4, 3x3): 4x fewer multiplications, 36 transformed filters, 2.25x the input and 2.25x the output as
+        # workspace.  Measured 1.2-1.4x faster than the implicit GEMM at 64 channels and 2-3x from 128 up (forward
+        # and input gradient); the filter gradient gains 1.4-2.5x from 96 channels up and loses at 64.  Offered from
+        # 128 channels, and from 64 on maps up to 56x56: on the large 64-channel maps of VGG-16 and UNet a gain of
+        # 1.2x would cost a workspace of several GB at the very point where the step's memory peaks.
+        wino4 = eligible and (min(C, K) >= 128 or (min(C, K) >= 64 and H * W <= 56 * 56))
+        wino4_wgrad = wino4 and min(C, K) >= 96
+
+        def wino_ws(m):
+            return _align((m + 2) ** 2 * 4 * (K * C + N * math.ceil(H / m) * math.ceil(W / m) * (C + K)))
+
+        def wino_wgrad_ws(m):      # mirrors the library's choice of reduction ranges
+            planes, T = (m + 2) ** 2, N * math.ceil(H / m) * math.ceil(W / m)
+            ranges = max(1, min(1024 // (planes * math.ceil(K / 128) * math.ceil(C / 128)), T // 128))
+            return _align(4 * (planes * T * (C + K) + planes * K * C * (1 + (ranges if ranges > 1 else 0))))
+
         if wino:
-            self.fimpls[i].append(dict(algo="winograd", ws=wino_ws, cost=flop * 0.6))
+            self.fimpls[i].append(dict(algo="winograd", ws=wino_ws(2), cost=flop * 0.6))
+        if wino4:
+            self.fimpls[i].append(dict(algo="winograd4", ws=wino_ws(4), cost=flop * 0.4))
         dg = [dict(algo="igemm", deps=[], ws=0, cost=flop)]
         if wino:
-            dg.append(dict(algo="winograd", deps=[], ws=wino_ws, cost=flop * 0.6))
+            dg.append(dict(algo="winograd", deps=[], ws=wino_ws(2), cost=flop * 0.6))
+        if wino4:
+            dg.append(dict(algo="winograd4", deps=[], ws=wino_ws(4), cost=flop * 0.4))
         sp, ws = conv_split_plan(N * math.ceil(H / stride) * math.ceil(W / stride), C,
                                  max(1, R // stride) * max(1, S // stride) * K, stride * stride, N * H * W * C)
         if ws:
@@ -137,10 +156,9 @@ class Graph:
         for sp in wgrad_splits:
             wg.append(dict(algo="splitk", ws=_align(sp * wbytes), cost=flop * (1.0 + 0.02 * sp), splits=sp))
         if wino:      # the filter gradient in the same transformed domain (measured 1.2-1.85x where it is offered)
-            T = N * ((H + 1) // 2) * ((W + 1) // 2)
-            ranges = max(1, min(1024 // (16 * math.ceil(K / 128) * math.ceil(C / 128)), T // 128))
-            wg.append(dict(algo="winograd", cost=flop * 0.65,
-                           ws=_align(4 * (16 * T * (C + K) + 16 * K * C * (1 + (ranges if ranges > 1 else 0))))))
+            wg.append(dict(algo="winograd", cost=flop * 0.65, ws=wino_wgrad_ws(2)))
+        if wino4_wgrad:
+            wg.append(dict(algo="winograd4", cost=flop * 0.45, ws=wino_wgrad_ws(4)))
         self._pending_bops(i, [("conv_dgrad", dg)] if x > 0 else [],
                            [("conv_wgrad", [dict(d, deps=[x] if x > 0 else []) for d in wg])])
         return i
