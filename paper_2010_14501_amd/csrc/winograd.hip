@@ -15,8 +15,8 @@
 // The same scheme with 4x4 output tiles, F(4x4, 3x3), is the second set of kernels below: 6x6 input tiles, 36 GEMMs,
 // 4x fewer multiplications than the direct form and 2.25x the input plus 2.25x the output as workspace (Lavin and
 // Gray's matrices for the interpolation points 0, +-1, +-2 and infinity).  Its transforms have entries up to 8 and
-// down to 1/24, so it rounds about ten times more coarsely than F(2x2, 3x3); both stay far inside the tolerances
-// the parity tests use.
+// down to 1/24, so it rounds about five times more coarsely than F(2x2, 3x3) (normwise error of one layer about 2e-6 against
+// 4e-7); both stay far inside the tolerances the parity tests use.
 #include "kernels.hpp"
 
 namespace monet {
