@@ -53,6 +53,14 @@ def build_workload(name, variants=None):
             return g, sch, 184, (f"greedy block-level search, budget {frac:.2f} x store-everything peak "
                                  f"({frac * store / 1e9:.2f} GB); block levels {''.join(map(str, levels))}; "
                                  f"predicted recomputation {ms:.1f} ms; lean variants")
+        if kind.startswith("ilp_"):
+            # a schedule the 0-1 program found (python -m workloads.ilp), kept as text beside the cost table it was priced with
+            path = os.path.join(ROOT, "workloads", "measured", f"ilp_resnet50_b184_{kind[len('ilp_'):]}.sched")
+            with open(path) as fh:
+                lines = fh.read().splitlines()
+            head = " ".join(l[1:].strip() for l in lines if l.startswith("#"))
+            body = "\n".join(l for l in lines if not l.startswith("#")) + "\n"
+            return g, schedules.StoredSchedule(body), 184, "0-1 integer program: " + head
         raise SystemExit(f"unknown workload {name}")
     lean = "; lean operator variants"
     nets = {"vgg16_b176": (lambda: graphs.vgg16_bn(batch=176), 176, schedules.vgg_alternate_schedule,

@@ -100,3 +100,45 @@ def test_program_trades_convolution_workspace_for_time():
     assert not any(a.startswith("winograd") for a in seen[1]) and "igemm_splitk" in seen[1]
     assert all(a == "igemm" for a in seen[2])
     assert costs == sorted(costs)
+
+
+def test_block_window_restricts_the_program_without_leaving_it():
+    """`recompute_blocks` = w only removes recomputation variables: every solution is still a valid schedule within
+    the budget, it can never be cheaper than the unrestricted optimum, and a wider window is never worse."""
+    g = graphs.tiny_chain(blocks=5)
+    gt = g.text()
+    budget = M.Plan(gt, schedules.block_output_schedule(g).text()).predicted_peak
+    objs = []
+    for w in (0, 1, None):
+        sch, obj, status = ilp.solve(g, budget, time_limit=120, recompute_blocks=w)
+        assert sch is not None, (w, status)
+        check(g, sch, budget, obj)
+        if w is not None:       # nothing outside the window is recomputed
+            blocks = {i: b for b, (_, ids) in enumerate(g.blocks) for i in ids}
+            for b in g.bops:
+                own = blocks.get(b["node"])
+                for i in sch.r[b["k"]]:
+                    if own is not None and i in blocks:
+                        assert own - w <= blocks[i] <= own, (w, b["k"], i)
+        objs.append(obj)
+    assert objs[0] >= objs[1] * (1 - 1e-9) >= objs[2] * (1 - 2e-9)
+    # keeping block outputs and recomputing inside blocks is itself block-local, so w = 0 is at least as good
+    assert objs[0] <= osch.objective(gt, schedules.block_output_schedule(g).text()) * (1 + 1e-9)
+
+
+def test_committed_full_size_solution_is_a_valid_schedule_within_its_budget():
+    """The ResNet-50 b184 schedule the program found (kept as text; bench.py runs it) passes the oracle's validator
+    and the executor's lowering, and its predicted peak is within the budget its header states."""
+    import re
+    import bench
+    g, sch, batch, desc = bench.build_workload("resnet50_b184_ilp_0.31")
+    gt, st = g.text(), sch.text()
+    og = osch.OGraph(gt)
+    osch.validate(og, osch.OSchedule(st, og))
+    plan = M.Plan(gt, st)
+    budget_gb = float(re.search(r"budget ([0-9.]+) GB", desc).group(1))
+    assert plan.predicted_peak <= budget_gb * 1e9 * (1 + 1e-3)
+    assert plan.exact_peak <= plan.predicted_peak
+    store = M.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
+    assert plan.predicted_peak < 0.32 * store
+    assert sum(1 for e in plan.trace_tuples() if e[0] == M.RUN_RECOMPUTE) > 50

@@ -20,6 +20,10 @@ intermediate (aux) nodes and what lies outside the accounting follow the executo
 operator, aux nodes only with their creator, persistent nodes never saved or recomputed, a held tensor is not
 recomputed).
 
+The memory rows use running sums per stage (continuous P_i >= P_{i-1} + |i| u_{k,i}, Q_i >= Q_{i+1} + |i+1| s^k_{i+1}),
+which keeps every row at a handful of entries; sizes are in MiB.  `recompute_blocks` optionally removes the
+recomputation variables outside a window of builder blocks, which is what makes a 225-node network solvable in minutes.
+
 `solve` returns a `schedules.Schedule`; the executor's own lowering (`monet_plan_load`) and the oracle's validator
 accept or reject it like any other schedule, and their predicted peak is the quantity bounded here.
 """
@@ -50,10 +54,12 @@ class _Vars:
         self.n = 0
         self.integer = []
         self.cost = []
+        self.ub = []
 
-    def new(self, integer=True, cost=0.0):
+    def new(self, integer=True, cost=0.0, ub=1.0):
         self.integer.append(1 if integer else 0)
         self.cost.append(cost)
+        self.ub.append(ub)
         self.n += 1
         return self.n - 1
 
@@ -78,15 +84,33 @@ class _Rows:
         self.hi.append(hi)
 
 
-def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, allow_inplace=True):
+def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, allow_inplace=True, recompute_blocks=None):
     """Cheapest schedule whose predicted peak (the L-bar bound) stays within `budget_bytes`.
 
     `tau` optionally maps ("f", node, l) / ("r", node, l) / ("b", k, l) to a cost; missing entries fall back to
-    the graph's own cost fields.  Returns (schedule, objective value, solver status string); schedule is None
-    if the program is infeasible or no solution was found in time."""
+    the graph's own cost fields.  `recompute_blocks` = w restricts the program: stage k may recompute only nodes of
+    the builder's block that holds the stage's own node and of the w blocks before it (every solution of the
+    restricted program is one of the full program; large networks become solvable in minutes).  Returns (schedule,
+    objective value, solver status string); schedule is None if the program is infeasible or no solution was found
+    in time."""
     N, B = len(g.nodes), len(g.bops)
     tau = tau or {}
-    sz = {i: node_bytes(g, i) for i in range(1, N + 1)}
+    MB = 1.0 / (1 << 20)                 # memory rows are written in MiB: coefficients of order 1 .. 1e5
+    sz = {i: node_bytes(g, i) * MB for i in range(1, N + 1)}
+    budget = float(budget_bytes) * MB
+
+    def wsb(d):
+        return float(_align(d["ws"])) * MB if d["ws"] else 0.0
+
+    blk, nb = {}, 0                      # block index of every node; nodes outside the builder's blocks form their own
+    in_block = {i: b for b, (_, ids) in enumerate(g.blocks) for i in ids}
+    last = None
+    for i in range(1, N + 1):
+        cur = in_block.get(i, ("solo", i))
+        if cur != last and not g.is_aux(i):
+            nb += 1
+            last = cur
+        blk[i] = nb
     is_aux = {i: g.is_aux(i) for i in range(1, N + 1)}
     persist = {i: bool(g.nodes[i - 1].attrs.get("persist")) for i in range(1, N + 1)}
     ins = {i: [j for j in g.nodes[i - 1].ins if j > 0] for i in range(1, N + 1)}
@@ -129,7 +153,7 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
             if persist[i]:
                 continue
             allowed = i <= fk[k] or (is_aux[i] and ins[i][0] == fk[k])     # Appendix B: nothing beyond the stage's own node
-            if allowed:
+            if allowed and (recompute_blocks is None or blk[i] >= blk[fk[k]] - recompute_blocks):
                 rv[k][i] = V.new()
                 if not is_aux[i]:
                     drc[k][i] = [V.new(cost=fcost(i, l, "r")) for l in range(len(g.fimpls[i]))]
@@ -162,7 +186,7 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
                 R.add([(dfw[i][l], 1.0)], 0.0, 0.0)
             else:
                 R.add([(dfw[i][l], 1.0)] + S(B, j), hi=1.0)          # the overwritten input is not saved
-        terms = [(dfw[i][l], float(_align(g.fimpls[i][l]["ws"]) if g.fimpls[i][l]["ws"] else 0)) for l in range(len(g.fimpls[i]))]
+        terms = [(dfw[i][l], wsb(g.fimpls[i][l])) for l in range(len(g.fimpls[i]))]
         const = 0.0
         if not persist[i]:
             const += sz[i]
@@ -174,7 +198,7 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
         for j in range(1, i):
             if j not in Lset and not persist[j]:
                 terms += [(v, float(sz[j]) * w) for v, w in S(B, j)]
-        R.add(terms, hi=float(budget_bytes) - const)
+        R.add(terms, hi=budget - const)
     # aux tensors exist only where their creator ran: in the forward pass always, so s^N of an aux node is free
 
     # ---- gradient tensors (constants of the graph)
@@ -191,7 +215,8 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
             dies[b["node"]] = min(dies.get(b["node"], B + 1), k)
     Lhat = {k: sum(sz[j] for j in born if born[j] > k >= dies.get(j, 0)) for k in range(1, B + 1)}
     ynew = {k: sum(sz[j] for j in born if born[j] == k) for k in range(1, B + 1)}
-    BIG = float(sum(sz.values()) + max([_align(d["ws"]) for i in g.fimpls for d in g.fimpls[i]] + [0]) + max(Lhat.values()) + max(ynew.values()))
+    BIG = float(sum(sz.values()) + max([wsb(d) for i in g.fimpls for d in g.fimpls[i]] + [0]) + max(Lhat.values()) + max(ynew.values()))
+    total = float(sum(sz.values()))
 
     # ---- stages
     for k in range(1, B + 1):
@@ -240,31 +265,49 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
                 for t in consumers[j]:      # an earlier consumer has read it already; a later one would read the overwritten buffer
                     if t > i and t in rv[k]:
                         R.add([(q, 1.0), (rv[k][t], 1.0)], hi=1.0)
+        # Running sums keep the memory rows sparse: P[i] >= sum of u_{k,j} |j| over j <= i (what is present up to
+        # node i), Q[i] >= sum of s^k_j |j| over j > i (what entered the stage beyond i).  Memory is only bounded from
+        # above, so ">=" defines them well enough.
+        P, Q = {0: None}, {N: None}
+        for i in range(1, N + 1):
+            if i in uv[k]:
+                P[i] = V.new(integer=False, ub=total)
+                R.add([(P[i], 1.0), (uv[k][i], -sz[i])] + ([(P[i - 1], -1.0)] if P[i - 1] is not None else []), lo=0.0)
+            else:
+                P[i] = P[i - 1]
+        for i in range(N - 1, -1, -1):
+            nxt = S(k, i + 1)
+            if nxt:
+                Q[i] = V.new(integer=False, ub=total)
+                R.add([(Q[i], 1.0)] + [(v, -sz[i + 1] * w) for v, w in nxt] + ([(Q[i + 1], -1.0)] if Q[i + 1] is not None else []), lo=0.0)
+            else:
+                Q[i] = Q[i + 1]
+
+        def run(var):
+            return [(var, 1.0)] if var is not None else []
+
         # backward memory (Eq. 10)
-        terms = [(dbw[k][l], float(_align(g.bimpls[k][l]["ws"]) if g.bimpls[k][l]["ws"] else 0)) for l in range(len(deps))]
-        terms += [(uv[k][i], float(sz[i])) for i in uv[k]]
-        R.add(terms, hi=float(budget_bytes) - ynew[k] - Lhat[k])
+        terms = [(dbw[k][l], wsb(g.bimpls[k][l])) for l in range(len(deps))]
+        R.add(terms + run(P[N]), hi=budget - ynew[k] - Lhat[k])
         # recomputation memory, L-bar bound (Eq. 11 with Appendix B / C.2)
         for i in range(1, N + 1):
             if persist[i]:
                 continue
-            later = [(v, float(sz[j]) * w) for j in range(i + 1, N + 1) if not persist[j] for v, w in S(k, j)]
             # no recomputation of i: what is held or needed up to i, what entered the stage beyond i
-            keep = [(uv[k][j], float(sz[j])) for j in range(1, i + 1) if j in uv[k]]
-            R.add(keep + later, hi=float(budget_bytes) - Lhat[k])
+            R.add(run(P[i]) + run(Q[i]), hi=budget - Lhat[k])
             if i not in rv[k] or is_aux[i]:
                 continue
             Lset = set(Lstat[i])
             const = Lhat[k] + sum(sz[j] for j in Lset)
-            terms = [(drc[k][i][l], float(_align(g.fimpls[i][l]["ws"]) if g.fimpls[i][l]["ws"] else 0) - (sz[i] if inplace(i, l) else 0.0))
-                     for l in range(len(g.fimpls[i]))]
-            terms += [(rv[k][i], float(sz[i]) + BIG)]
-            terms += [(rv[k][c], float(sz[c])) for c in aux_children[i] if c in rv[k]]
-            terms += [(uv[k][j], float(sz[j])) for j in range(1, i) if j in uv[k] and j not in Lset]
-            R.add(terms + later, hi=float(budget_bytes) - const + BIG)
+            terms = [(drc[k][i][l], wsb(g.fimpls[i][l]) - (sz[i] if inplace(i, l) else 0.0)) for l in range(len(g.fimpls[i]))]
+            terms += [(rv[k][i], sz[i] + BIG)]
+            terms += [(rv[k][c], sz[c]) for c in aux_children[i] if c in rv[k]]
+            # present before i, apart from the tensors the L-bar bound counts as constants
+            terms += run(P[i - 1]) + [(uv[k][j], -sz[j]) for j in Lset if j in uv[k]]
+            R.add(terms + run(Q[i]), hi=budget - const + BIG)
     A = sparse.csr_matrix((R.v, (R.r, R.c)), shape=(len(R.lo), V.n))
     res = milp(c=np.array(V.cost), constraints=LinearConstraint(A, np.array(R.lo), np.array(R.hi)),
-               integrality=np.array(V.integer), bounds=Bounds(np.zeros(V.n), np.ones(V.n)),
+               integrality=np.array(V.integer), bounds=Bounds(np.zeros(V.n), np.array(V.ub)),
                options=dict(time_limit=float(time_limit), mip_rel_gap=float(mip_rel_gap), disp=False))
     status = res.message
     if res.x is None:
@@ -283,3 +326,43 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
                 sch.r[k][i] = -1 if is_aux[i] else int(np.argmax([res.x[v] for v in drc[k][i]]))
         sch.s[k] = {i for i in sv[k - 1] if x[sv[k - 1][i]]}
     return sch, float(res.fun), status
+
+
+def main():
+    """Solve one of the full-size workloads and write the schedule as text (header lines start with '#')."""
+    import argparse
+    import os
+    import time
+    from . import graphs, schedules
+    from paper_2010_14501_amd import costs, monet
+    ap = argparse.ArgumentParser(description=main.__doc__)
+    ap.add_argument("--workload", default="resnet50_b184", choices=["resnet50_b184"])
+    ap.add_argument("--budget", type=float, required=True, help="fraction of the store-everything predicted peak")
+    ap.add_argument("--recompute-blocks", type=int, default=0, help="-1: unrestricted")
+    ap.add_argument("--time-limit", type=float, default=900.0)
+    ap.add_argument("--gap", type=float, default=0.02)
+    ap.add_argument("--out", required=True)
+    args = ap.parse_args()
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    g = graphs.resnet50(batch=184)
+    tau = costs.read_table(os.path.join(root, "workloads", "measured", "costs_resnet50_b184.txt"))
+    gt = g.text()
+    store = monet.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
+    t0 = time.time()
+    sch, obj, status = solve(g, int(args.budget * store), tau=tau, time_limit=args.time_limit, mip_rel_gap=args.gap,
+                             recompute_blocks=None if args.recompute_blocks < 0 else args.recompute_blocks)
+    secs = time.time() - t0
+    if sch is None:
+        raise SystemExit(f"no schedule after {secs:.0f} s: {status}")
+    plan = monet.Plan(gt, sch.text())
+    head = [f"# python -m workloads.ilp --workload {args.workload} --budget {args.budget} --recompute-blocks {args.recompute_blocks}"
+            f" --time-limit {args.time_limit:g} --gap {args.gap:g} --out {args.out}",
+            f"# budget {args.budget * store / 1e9:.3f} GB = {args.budget:g} x store-everything; objective (Eq. 9, measured costs) {obj:.2f} ms;"
+            f" predicted peak {plan.predicted_peak / 1e9:.3f} GB; solved in {secs:.0f} s: {status}"]
+    with open(args.out, "w") as fh:
+        fh.write("\n".join(head) + "\n" + sch.text())
+    print("\n".join(head))
+
+
+if __name__ == "__main__":
+    main()

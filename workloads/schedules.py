@@ -67,6 +67,16 @@ class Schedule:
         return "\n".join(out) + "\n"
 
 
+class StoredSchedule:
+    """A schedule kept as the text the executor reads (e.g. one a solver run wrote to a file)."""
+
+    def __init__(self, text):
+        self._text = text
+
+    def text(self):
+        return self._text
+
+
 def choose_bimpls(g: Graph, variants, saved=None):
     """One implementation index per backward operator, from per-kind names.
 
