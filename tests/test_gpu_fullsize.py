@@ -54,6 +54,24 @@ def test_gradients_do_not_depend_on_the_schedule_at_full_size(full):
     assert not differing, differing
 
 
+def test_integer_program_schedule_at_full_size(full):
+    """The schedule the 0-1 program found for 0.31 x the store-everything peak (other saved sets *and* other operator
+    implementations than the block-output schedule): the executor's peak is the plan's and within the budget, the
+    loss and every gradient agree with the block-output run within the gradient tolerance."""
+    import bench
+    g, exts, params, run, peak, grads, loss = full
+    g2, sch, batch, desc = bench.build_workload("resnet50_b184_ilp_0.31")
+    assert g2.text() == g.text()
+    store = M.Plan(g.text(), schedules.store_everything_schedule(g).text()).predicted_peak
+    other = StepRunner(g.text(), sch.text(), exts, params)
+    assert other.step() == other.plan.exact_peak <= other.plan.predicted_peak <= 0.31 * store
+    assert abs(other.loss_value() - loss) < 1e-4 * abs(loss)
+    got = other.grads_numpy()
+    for p in grads:
+        a, b = got[p].astype(np.float64), grads[p].astype(np.float64)
+        assert np.linalg.norm(a - b) <= 1e-3 * np.linalg.norm(b), p
+
+
 def test_identities_that_hold_at_any_size(full):
     g, exts, params, run, peak, grads, loss = full
     # softmax cross-entropy: every row of the logit gradient sums to zero, so the bias gradient of the last
