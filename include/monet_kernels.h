@@ -46,6 +46,16 @@ int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
 int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y,
                             int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                             float *ws, size_t ws_bytes, float *stats, float eps, float *scratch, size_t scratch_bytes);
+/* monet_conv_fwd followed by monet_bn_apply of its output in place, with the apply step (one multiply-add per
+ * element) done in the convolution's epilogue: the form a recomputed convolution takes when the BatchNorm behind it
+ * is recomputed in place, because then the statistics are the forward pass's (Section 3: recomputation repeats the
+ * forward operator; Appendix D: in-place operators).  `stats` = mean[K] then 1/sqrt(var+eps)[K] as monet_bn_stats
+ * leaves them, `gamma`, `beta` [K].  winograd_m = 0: implicit GEMM (needs C % 16 == 0, K % 4 == 0; ws / ws_bytes as for
+ * monet_conv_fwd with splits == 1); winograd_m = 2 or 4: the Winograd form below (3x3 / stride 1 / pad 1 only, its
+ * workspace).  y is bit-identical to the two separate calls. */
+int monet_conv_fwd_bn_apply(void *stream, const float *x, const float *w, float *y,
+                            int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int winograd_m,
+                            float *ws, size_t ws_bytes, const float *gamma, const float *beta, const float *stats);
 /* Winograd F(m x m, 3x3) form of a 3x3 / stride 1 / pad 1 convolution, m = 2 or 4 (Section 4 lists Winograd among the
  * implementations an operator chooses from; Appendix D: workspace against time).  adjoint == 0: out = y[N,H,W,K] from
  * in = x[N,H,W,C] (needs C % 16 == 0, K % 4 == 0).  adjoint != 0: out = dx[N,H,W,C] (+)= from in = dy[N,H,W,K]

@@ -21,6 +21,7 @@ void build_programs(monet_plan *p);
 
 // One entry of the step program: a single operator launch, or two neighbours run as one fused kernel.
 enum { FUSE_NONE = 0, FUSE_BN_RELU_FWD, FUSE_ADD_RELU_FWD, FUSE_RELU_BN_BWD, FUSE_RELU_ADD_BWD,
+       FUSE_CONV_BN_APPLY,                             // a recomputed convolution applies its in-place BatchNorm in the epilogue
        FUSE_BN_ADD_RELU_FWD, FUSE_RELU_ADD_BN_BWD };   // the last two join three launches (tail of a residual block)
 struct ProgStep {
     int fuse;
@@ -221,7 +222,7 @@ int splits_of(const std::string &algo, const Attrs &extra) {
     return std::stoi(it->second);
 }
 
-void run_forward(const StepCtx &c, const Launch &L) {
+void run_forward(const StepCtx &c, const Launch &L, const BnAffine *affine = nullptr) {
     const Graph &g = c.mp->plan.g;
     const Node &n = g.nodes[L.id];
     const float *in0 = (const float *)c.ptr(L.a[0]);
@@ -231,10 +232,10 @@ void run_forward(const StepCtx &c, const Launch &L) {
         const FwdImpl &im = n.fimpls[L.impl];
         if (const int m = winograd_tile(im.algo))
             conv_winograd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), m, false, false, (float *)c.ptr(L.a[4]),
-                          (size_t)align_up(im.ws));
+                          (size_t)align_up(im.ws), affine);
         else
             conv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
-                     (size_t)(im.ws > 0 ? align_up(im.ws) : 0), false, c.feeds_stats(L) ? c.scratch() : nullptr);
+                     (size_t)(im.ws > 0 ? align_up(im.ws) : 0), false, c.feeds_stats(L) ? c.scratch() : nullptr, affine);
     } else if (op == "tconv") {
         conv_dgrad(c.st, in0, c.weights[n.pars[0]], out, tconv_adjoint_shape(g, n), false);
     } else if (op == "dwconv") {
@@ -496,6 +497,22 @@ bool conv_feeds_bn_stats(const Plan &pl, const Launch &L1, const Launch &L2) {
     return bn_stats_in_row_groups(cs.M(), cs.K, (size_t)pl.scratch_bytes);
 }
 
+// A recomputed convolution followed by the recomputation of its BatchNorm, in place: the statistics are the forward
+// pass's, so the apply step is one multiply-add per element in the convolution's epilogue (bn_affine.hpp: the bits
+// bn_apply would write), and the convolution's raw output, which the in-place BatchNorm overwrites anyway, never
+// reaches memory.
+bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
+    const Graph &g = pl.g;
+    if (L1.kind != EV_RUN_RECOMPUTE || L2.kind != EV_RUN_RECOMPUTE) return false;
+    const Node &cv = g.nodes[L1.id], &bn = g.nodes[L2.id];
+    if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
+    if (!(L2.flags & 1) || L2.a[2].region != L1.a[2].region || L2.a[2].off != L1.a[2].off) return false;
+    const ConvShape cs = conv_shape(g, cv);
+    const FwdImpl &im = cv.fimpls[L1.impl];
+    if (winograd_tile(im.algo)) return winograd_applies(cs, false);
+    return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
+}
+
 void build_programs(monet_plan *p) {
     const Plan &pl = p->plan;
     const size_t n = pl.launches.size();
@@ -517,6 +534,11 @@ void build_programs(monet_plan *p) {
                 continue;
             }
         }
+        if (i + 1 < n && conv_applies_bn(pl, pl.launches[i], pl.launches[i + 1])) {
+            p->prog_fused.push_back(ProgStep{FUSE_CONV_BN_APPLY, i, i + 1, i + 1});
+            ++i;
+            continue;
+        }
         int f = i + 1 < n ? fusable(pl, pl.launches[i], pl.launches[i + 1]) : FUSE_NONE;
         if (f) { p->prog_fused.push_back(ProgStep{f, i, i + 1, i + 1}); ++i; }
         else p->prog_fused.push_back(ProgStep{FUSE_NONE, i, i, i});
@@ -527,6 +549,12 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
     const Graph &g = c.mp->plan.g;
     const Plan &pl = c.mp->plan;
     const Launch &L1 = c.mp->plan.launches[ps.a], &L2 = c.mp->plan.launches[ps.b];
+    if (ps.fuse == FUSE_CONV_BN_APPLY) {
+        const Node &bn = g.nodes[L2.id];
+        const BnAffine affine{c.weights[bn.pars[0]], c.weights[bn.pars[1]], c.bn_stats(L2.id)};
+        run_forward(c, L1, &affine);
+        return;
+    }
     if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
         const Launch &L3 = pl.launches[ps.c];
         const Node &bn = g.nodes[L1.id], &ad = g.nodes[L2.id], &re = g.nodes[L3.id];
@@ -686,7 +714,12 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
         double e, bytes;
         const char *label;
-        if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
+        if (ps.fuse == FUSE_CONV_BN_APPLY) {
+            const ConvShape cs = conv_shape(g, g.nodes[L.id]);
+            out->flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
+            bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * cs.K * (double)cs.RSC() + 4.0 * (double)cs.M() * cs.K;
+            label = "conv_fwd";
+        } else if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
             const Launch &L3 = p->plan.launches[ps.c];
             e = 4.0 * (double)numel_of(g.nodes[L3.id].shape);
             const bool keep_bn = !freed_between(p->plan, L.id, L2.event, L3.event), pre = !(L3.flags & 1), mk = L3.flags & 2;
@@ -865,6 +898,16 @@ extern "C" int monet_conv_fwd_bn_stats(void *stream, const float *x, const float
             throw KernelError("monet_conv_fwd_bn_stats: scratch too small for 2 floats per 64 output rows and channel");
         conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, scratch);
         bn_stats((hipStream_t)stream, y, stats, cs.M(), cs.K, eps, scratch, scratch_bytes, true);
+    });
+}
+extern "C" int monet_conv_fwd_bn_apply(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
+                                       int stride, int pad, int winograd_m, float *ws, size_t ws_bytes, const float *gamma, const float *beta,
+                                       const float *stats) {
+    return guarded([&] {
+        const ConvShape cs = mk_conv(N, H, W, C, K, R, S, stride, pad);
+        const BnAffine affine{gamma, beta, stats};
+        if (winograd_m) conv_winograd((hipStream_t)stream, x, w, y, cs, winograd_m, false, false, ws, ws_bytes, &affine);
+        else conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, nullptr, &affine);
     });
 }
 extern "C" int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,

@@ -6,6 +6,7 @@
 // tree per block, then one pass over the slab partials), so results are bitwise reproducible:
 // no floating-point atomics.  Variance is accumulated around a per-thread pivot and merged with
 // the pairwise (Chan) update, never as E[x^2]-mean^2.
+#include "bn_affine.hpp"
 #include "kernels.hpp"
 #include "tile_stats.hpp"
 
@@ -303,10 +304,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float *x, float *y,
     auto load_ab = [&](int g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            int c = g * 4 + j;
-            float s = gamma[c] * stats[C + c];
-            a[j] = s;
-            b[j] = beta[c] - stats[c] * s;
+            bn_affine_coeffs(gamma, beta, stats, C, g * 4 + j, a[j], b[j]);
         }
     };
     const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
@@ -323,7 +321,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float *x, float *y,
             const int64_t i = base + u * 256;
             if (i >= r1) continue;
             if (!fixed) load_ab((int)(i % C4));
-            __builtin_nontemporal_store(f4{v[u].x * a[0] + b[0], v[u].y * a[1] + b[1], v[u].z * a[2] + b[2], v[u].w * a[3] + b[3]}, (f4 *)y + i);
+            __builtin_nontemporal_store(f4{bn_affine(v[u].x, a[0], b[0]), bn_affine(v[u].y, a[1], b[1]), bn_affine(v[u].z, a[2], b[2]), bn_affine(v[u].w, a[3], b[3])}, (f4 *)y + i);
         }
     }
 }

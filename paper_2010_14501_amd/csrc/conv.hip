@@ -33,6 +33,7 @@
 // round-robin, so logical item = (id mod 8) * (grid/8) + id / 8.  A work item is (tile, reduction
 // split) with the tile index fastest, so a launch with few tiles and many splits (weight
 // gradients) still spreads over all XCDs and the tiles of one split share their operand rows.
+#include "bn_affine.hpp"
 #include "kernels.hpp"
 #include "tile_stats.hpp"
 
@@ -68,6 +69,7 @@ struct TileArgs {
     int meet_splits;           // <= 1: off
     float *part;               // (class, tile - main_tiles, range) x 64 x threads floats, register order
     float *stats_part;         // FWD, whole results only: BatchNorm partial statistics of the output (tile_stats.hpp), or null
+    BnAffine affine;           // FWD, whole results only: BatchNorm apply step of the output in the epilogue (gamma == null: off)
     int64_t batch_a, batch_b, batch_out;   // FWD / WGRAD with gridDim.z > 1: z-th GEMM of a batch, operands and result this many floats apart
 };
 
@@ -640,6 +642,16 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         const bool want_stats = MODE == FWD && ta.stats_part != nullptr;
         LaneStats ls;
         ls.init();
+        // a lane writes the same four columns in every pass: one pair of BatchNorm coefficients each
+        const bool want_affine = MODE == FWD && ta.affine.gamma != nullptr;
+        float bn_a[4] = {1, 1, 1, 1}, bn_b[4] = {0, 0, 0, 0};
+        if (MODE == FWD && want_affine) {
+            const int c0 = col0 + wn * 64 + 4 * (lane & 15);
+            if (c0 < ta.Ng) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bn_affine_coeffs(ta.affine.gamma, ta.affine.beta, ta.affine.stats, ta.Ng, c0 + j, bn_a[j], bn_b[j]);
+            }
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int mi = q >> 1, vbase = 8 * (q & 1);
@@ -665,6 +677,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                     }
                     float4 *dst = (float4 *)(out + orow * ta.Ng + col);
                     if (do_acc) { float4 o = *dst; val.x += o.x; val.y += o.y; val.z += o.z; val.w += o.w; }
+                    if (MODE == FWD && want_affine)
+                        val = float4{bn_affine(val.x, bn_a[0], bn_b[0]), bn_affine(val.y, bn_a[1], bn_b[1]), bn_affine(val.z, bn_a[2], bn_b[2]),
+                                     bn_affine(val.w, bn_a[3], bn_b[3])};
                     *dst = val;
                     if (MODE == FWD && want_stats) ls.add(val.x, val.y, val.z, val.w);
                 }
@@ -910,16 +925,19 @@ void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out,
 }
 
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,
-              bool accumulate, float *stats_part) {
+              bool accumulate, float *stats_part, const BnAffine *affine) {
     check_shape(cs);
     TileArgs ta{};
     ta.a = x; ta.b = w; ta.cs = cs;
     ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
     ta.out_elems = ta.Mg * ta.Ng;
     bool fast = cs.C % BK == 0;
-    if (stats_part && (!fast || cs.K % 4 || splits != 1 || accumulate))
-        throw KernelError("conv_fwd: statistics in the epilogue need C % 16 == 0, K % 4 == 0, splits == 1 and no accumulation");
+    if ((stats_part || affine) && (!fast || cs.K % 4 || splits != 1 || accumulate))
+        throw KernelError("conv_fwd: statistics or BatchNorm in the epilogue need C % 16 == 0, K % 4 == 0, splits == 1 and no accumulation");
+    if (stats_part && affine) throw KernelError("conv_fwd: either the statistics of the output or its BatchNorm apply step, not both");
+    if (affine && (!affine->gamma || !affine->beta || !affine->stats)) throw KernelError("conv_fwd: incomplete BatchNorm coefficients");
     ta.stats_part = stats_part;
+    if (affine) ta.affine = *affine;
     launch_cfg<FWD>(pick_cfg(FWD, ta.Mg, ta.Ng), st, ta, fast, 1, y, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, accumulate, "conv_fwd");
 }
 

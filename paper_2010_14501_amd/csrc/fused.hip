@@ -8,6 +8,7 @@
 //   backward: ReLU(6) backward (mask / output / input) feeding up to two gradient tensors
 //             (the residual add's backward is a fan-out), each written or accumulated
 // The BatchNorm backward that takes its incoming gradient through a ReLU mask lives in bn.hip.
+#include "bn_affine.hpp"
 #include "kernels.hpp"
 
 namespace monet {
@@ -49,10 +50,7 @@ __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const fl
     auto load_ab = [&](int g) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            int c = g * 4 + j;
-            float s = gamma[c] * stats[C + c];
-            a[j] = s;
-            b[j] = beta[c] - stats[c] * s;
+            bn_affine_coeffs(gamma, beta, stats, C, g * 4 + j, a[j], b[j]);
         }
     };
     const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
@@ -79,7 +77,7 @@ __global__ __launch_bounds__(256) void fwd_chain_kernel(const float *x, const fl
             if (i - lane >= r1) break;                                                // whole wave beyond the range
             if (valid[u] && BN) {
                 if (!fixed) load_ab((int)(i % C4));
-                v[u].x = v[u].x * a[0] + b[0]; v[u].y = v[u].y * a[1] + b[1]; v[u].z = v[u].z * a[2] + b[2]; v[u].w = v[u].w * a[3] + b[3];
+                v[u] = f4{bn_affine(v[u].x, a[0], b[0]), bn_affine(v[u].y, a[1], b[1]), bn_affine(v[u].z, a[2], b[2]), bn_affine(v[u].w, a[3], b[3])};
                 if (out_bn) __builtin_nontemporal_store(v[u], (f4 *)out_bn + i);
             }
             if (ADD) v[u] += w[u];

@@ -28,14 +28,22 @@ struct ConvShape {
     __host__ __device__ int64_t RSC() const { return (int64_t)R * S * C; }
 };
 
+// A BatchNorm apply step folded into the kernel that produces its input (a recomputed convolution, whose
+// statistics are known): device pointers gamma[K], beta[K], stats = mean[K] followed by invstd[K]; the kernel then
+// writes gamma * (y - mean) * invstd + beta, with the bits bn_apply() would produce from y.
+struct BnAffine {
+    const float *gamma = nullptr, *beta = nullptr, *stats = nullptr;
+};
+
 // ---- convolution (implicit GEMM on fp32 MFMA)
 // Every variant can cut its reduction into `splits` ranges: partial results go to ws (splits * |output|
 // floats) and are added in range order.  splits == 1 needs no workspace.
 // y (+)= conv(x, w)
 // stats_part: if given, the epilogue also leaves BatchNorm's partial statistics of y (groups of 64 rows, the
 // layout bn_stats() reads with partials_ready) there; needs C % 16 == 0, K % 4 == 0, splits == 1, no accumulation.
+// affine: if given, the BatchNorm apply step of y in the epilogue (same conditions as stats_part; not both).
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits = 1, float *ws = nullptr,
-              size_t ws_bytes = 0, bool accumulate = false, float *stats_part = nullptr);
+              size_t ws_bytes = 0, bool accumulate = false, float *stats_part = nullptr, const BnAffine *affine = nullptr);
 // dx (+)= transpose-conv of dy with w
 void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate, int splits = 1,
                 float *ws = nullptr, size_t ws_bytes = 0);
@@ -54,8 +62,9 @@ void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out,
 // (m+2)^2 transformed filters and (m+2)^2 / m^2 times the input and the output (winograd_workspace_bytes).
 bool winograd_applies(const ConvShape &cs, bool adjoint);
 size_t winograd_workspace_bytes(const ConvShape &cs, int m);
+// affine (forward only, no accumulation): the BatchNorm apply step of y in the output transform
 void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, int m, bool adjoint, bool accumulate,
-                   float *ws, size_t ws_bytes);
+                   float *ws, size_t ws_bytes, const BnAffine *affine = nullptr);
 // filter gradient in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
 // (C % 4 == 0, K % 4 == 0); workspace winograd_wgrad_workspace_bytes
 size_t winograd_wgrad_workspace_bytes(const ConvShape &cs, int m);

@@ -17,6 +17,7 @@
 // Gray's matrices for the interpolation points 0, +-1, +-2 and infinity).  Its transforms have entries up to 8 and
 // down to 1/24, so it rounds about five times more coarsely than F(2x2, 3x3) (normwise error of one layer about 2e-6 against
 // 4e-7); both stay far inside the tolerances the parity tests use.
+#include "bn_affine.hpp"
 #include "kernels.hpp"
 
 namespace monet {
@@ -108,11 +109,16 @@ __global__ __launch_bounds__(256) void wino_input_kernel(const float *__restrict
 
 // one thread per (tile, four channels): the 2x2 outputs A^T m A, written or accumulated
 template <bool ADJ>
-__global__ __launch_bounds__(256) void wino_output_kernel(const float *__restrict__ M, float *y, WinoGeom gm, int K, int accumulate) {
+__global__ __launch_bounds__(256) void wino_output_kernel(const float *__restrict__ M, float *y, WinoGeom gm, int K, int accumulate, BnAffine bn) {
     const int K4 = K / 4;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= gm.T * K4) return;
     const int k4 = (int)(idx % K4);
+    float bn_a[4] = {1, 1, 1, 1}, bn_b[4] = {0, 0, 0, 0};
+    if (!ADJ && bn.gamma) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bn_affine_coeffs(bn.gamma, bn.beta, bn.stats, K, 4 * k4 + j, bn_a[j], bn_b[j]);
+    }
     const int64_t t = idx / K4;
     const int tj = (int)(t % gm.tw);
     const int64_t r = t / gm.tw;
@@ -140,7 +146,9 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const float *__restric
             const int w = 2 * tj + b;
             if (w >= gm.W) continue;
             f4 *dst = (f4 *)(y + (((int64_t)n * gm.H + h) * gm.W + w) * K + 4 * k4);
-            *dst = accumulate ? *dst + o[b] : o[b];
+            f4 v = accumulate ? *dst + o[b] : o[b];
+            if (!ADJ && bn.gamma) v = f4{bn_affine(v.x, bn_a[0], bn_b[0]), bn_affine(v.y, bn_a[1], bn_b[1]), bn_affine(v.z, bn_a[2], bn_b[2]), bn_affine(v.w, bn_a[3], bn_b[3])};
+            *dst = v;
         }
     }
 }
@@ -323,11 +331,16 @@ __global__ __launch_bounds__(256) void wino4_input_kernel(const float *__restric
 
 // one thread per (tile, two channels): the 4x4 outputs A^T m A, written or accumulated
 template <bool ADJ>
-__global__ __launch_bounds__(256) void wino4_output_kernel(const float *__restrict__ M, float *y, WinoGeom gm, int K, int accumulate) {
+__global__ __launch_bounds__(256) void wino4_output_kernel(const float *__restrict__ M, float *y, WinoGeom gm, int K, int accumulate, BnAffine bn) {
     const int K2 = K / 2;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= gm.T * K2) return;
     const int k2 = (int)(idx % K2);
+    float bn_a[2] = {1, 1}, bn_b[2] = {0, 0};
+    if (!ADJ && bn.gamma) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bn_affine_coeffs(bn.gamma, bn.beta, bn.stats, K, 2 * k2 + j, bn_a[j], bn_b[j]);
+    }
     const int64_t t = idx / K2;
     const int tj = (int)(t % gm.tw);
     const int64_t r = t / gm.tw;
@@ -353,7 +366,9 @@ __global__ __launch_bounds__(256) void wino4_output_kernel(const float *__restri
             const int w = 4 * tj + b;
             if (w >= gm.W) continue;
             f2 *dst = (f2 *)(y + (((int64_t)n * gm.H + h) * gm.W + w) * K + 2 * k2);
-            *dst = accumulate ? *dst + o[b] : o[b];
+            f2 v = accumulate ? *dst + o[b] : o[b];
+            if (!ADJ && bn.gamma) v = f2{bn_affine(v.x, bn_a[0], bn_b[0]), bn_affine(v.y, bn_a[1], bn_b[1])};
+            *dst = v;
         }
     }
 }
@@ -445,8 +460,11 @@ size_t winograd_workspace_bytes(const ConvShape &cs, int m) {
 
 // adjoint = false: y[N,H,W,K] (+)= conv3x3(x[N,H,W,C], w[K,3,3,C]);  adjoint = true: in = dy[N,H,W,K], out = dx[N,H,W,C] (+)=
 void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, int m, bool adjoint, bool accumulate,
-                   float *ws, size_t ws_bytes) {
+                   float *ws, size_t ws_bytes, const BnAffine *affine) {
     check_tile(m, "conv_winograd");
+    if (affine && (adjoint || accumulate || !affine->gamma || !affine->beta || !affine->stats))
+        throw KernelError("conv_winograd: a BatchNorm apply step goes with the forward form, without accumulation, and needs all coefficients");
+    const BnAffine bn = affine ? *affine : BnAffine{};
     if (!winograd_applies(cs, adjoint)) throw KernelError("conv_winograd: needs a 3x3 / stride 1 / pad 1 layer with aligned channel counts");
     if (!ws || ws_bytes < winograd_workspace_bytes(cs, m)) throw KernelError("conv_winograd: workspace too small");
     const WinoGeom gm = geom_of(cs, m);
@@ -476,11 +494,11 @@ void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, 
     gemm_batched(st, V, U, M, planes, gm.T, outc, red, adjoint);
     const int acc = accumulate ? 1 : 0;
     if (m == 2) {
-        if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
-        else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
+        if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
+        else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
     } else {
-        if (adjoint) hipLaunchKernelGGL(wino4_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
-        else hipLaunchKernelGGL(wino4_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc);
+        if (adjoint) hipLaunchKernelGGL(wino4_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
+        else hipLaunchKernelGGL(wino4_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
     }
     hip_check(hipGetLastError(), "winograd output launch");
 }

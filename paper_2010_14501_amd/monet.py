@@ -81,6 +81,8 @@ def load_library():
     f = C.c_float
     lib.monet_conv_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz]
     lib.monet_conv_fwd_bn_stats.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp, sz, vp, f, vp, sz]
+    lib.monet_conv_fwd_bn_apply.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz, vp, vp, vp]
+    lib.monet_conv_fwd_bn_apply.restype = i32
     lib.monet_conv_winograd.argtypes = [vp, vp, vp, vp] + [i32] * 8 + [vp, sz]
     lib.monet_conv_winograd_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 6 + [vp, sz]
     lib.monet_conv_winograd_wgrad_workspace_bytes.argtypes = [i32] * 6

@@ -168,6 +168,54 @@ def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
     assert rel(got[:K], mean) < ACT_TOL and rel(got[K:], invstd) < ACT_TOL
 
 
+@pytest.mark.parametrize("case", [
+    (3, 14, 14, 64, 128, 3, 1, 1, 0),      # implicit GEMM, ragged rows
+    (2, 28, 28, 64, 256, 1, 1, 0, 0),      # two column tiles
+    (2, 15, 13, 32, 80, 3, 2, 1, 0),       # stride 2, a column tile that is only partly used
+    (2, 28, 28, 128, 64, 1, 2, 0, 0),      # the 256x64 tile
+    (48, 28, 28, 128, 128, 1, 1, 0, 0),    # ragged last round cut and met inside the kernel
+    (3, 14, 14, 64, 128, 3, 1, 1, 2),      # Winograd, 2x2 output tiles
+    (3, 14, 14, 64, 128, 3, 1, 1, 4),      # Winograd, 4x4 output tiles (last tile row / column partly outside)
+    (2, 9, 7, 32, 48, 3, 1, 1, 4),
+])
+def test_batchnorm_apply_in_the_conv_epilogue_is_the_stand_alone_bits(case):
+    """A recomputed convolution that applies the BatchNorm behind it in its epilogue writes exactly what the
+    convolution followed by the in-place apply kernel writes (implicit GEMM and both Winograd forms)."""
+    torch = torch_mod()
+    N, H, W, C, K, R, stride, pad, m = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    gamma = rng.uniform(0.5, 1.5, K).astype(np.float32)
+    beta = rng.standard_normal(K, dtype=np.float32)
+    stats = np.concatenate([rng.standard_normal(K, dtype=np.float32) * np.float32(0.3), rng.uniform(0.5, 2.0, K).astype(np.float32)])
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    dx, dwt, dg_, db_, dst = dev(x), dev(w), dev(gamma), dev(beta), dev(stats)
+    if m:
+        need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K, m)
+    else:
+        need = monet.call("monet_conv_workspace_bytes", 0, N, H, W, C, K, R, R, stride, pad, 1)
+    ws = torch.empty(max(need // 4, 1), dtype=torch.float32, device="cuda")
+    wsp = ws.data_ptr() if need else None
+    fused = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), fused.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+               wsp, need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr())
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    if m:
+        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, m, 0, 0, wsp, need)
+    else:
+        monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, wsp, need)
+    monet.call("monet_bn_apply", None, y.data_ptr(), y.data_ptr(), dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), N * P * Q, K)
+    assert torch.equal(fused, y)
+    yo = nm.conv2d_fwd(wt.act_to_oracle(x), wt.weight_to_oracle(w), stride, pad)
+    want = nm.bn_apply(yo, gamma.astype(np.float64), beta.astype(np.float64), stats[:K].astype(np.float64), stats[K:].astype(np.float64))
+    assert rel(fused.cpu().numpy(), wt.act_from_oracle(want)) < ACT_TOL
+    with pytest.raises(monet.MonetError):       # no Winograd form with 3x3 output tiles
+        monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), fused.data_ptr(), N, H, W, C, K, R, R, stride, pad, 3,
+                   wsp, need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr())
+
+
 @pytest.mark.parametrize("m", [2, 4])
 @pytest.mark.parametrize("case", [
     (2, 14, 14, 64, 128),       # even map (for 4x4 tiles: the last tile row / column is half outside)
