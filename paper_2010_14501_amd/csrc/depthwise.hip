@@ -370,6 +370,204 @@ __global__ __launch_bounds__(256) void dw3_wgrad_partial(const float *__restrict
     }
 }
 
+// ------------------------------------------------------------------ 3x3 filters, C % 4 == 0, pad 1: row segments
+// One thread per (image row of the output, segment of L consecutive outputs, four channels).  The 3 x ((L-1)*STRIDE + 3)
+// inputs under the segment are loaded once and every one of them serves up to three outputs from registers: 3.9 loads
+// per output at L = 7 and stride 1 instead of 9, which is what moves these kernels from the L1 / address-unit limit
+// towards the HBM one (L = 7 divides every map width of a 224-pixel network).  FLIP turns the filter by 180
+// degrees: with stride 1 the input gradient is the forward operator applied to dy with the flipped filter.  Lanes
+// that are neighbours in x are neighbours in channels, so each load instruction covers whole pixels.  Work items are
+// ordered (image, row, segment, channels) and every XCD takes one contiguous share of them (workgroups go to the
+// eight XCDs in turn), so that the three output rows that read an input row find it in the same L2.
+// workgroup b of a grid of nb (a multiple of 8) -> position in the XCD-contiguous order
+__device__ inline int64_t xcd_block(unsigned b, unsigned nb) { return (int64_t)(b & 7) * (nb >> 3) + (b >> 3); }
+
+template <int STRIDE, int L, bool FLIP, bool ACC>
+__global__ __launch_bounds__(256) void dw3_row_kernel(const float *__restrict__ in, const float *__restrict__ w, float *out, int N, int H, int W,
+                                                      int P, int Q, int C4, int segs, int64_t items) {
+    constexpr int COLS = (L - 1) * STRIDE + 3;
+    const int64_t i = xcd_block(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    if (i >= items) return;
+    const int cv = (int)(i % C4);
+    int64_t t = i / C4;
+    const int seg = (int)(t % segs); t /= segs;
+    const int p = (int)(t % P);
+    const int n = (int)(t / P);
+    const int q0 = seg * L;
+    f4 wv[9];      // filters are stored C,3,3: 36 consecutive floats for the thread's four channels
+    {
+        const float *wp = w + (int64_t)cv * 36;
+#pragma unroll
+        for (int tp = 0; tp < 9; ++tp) {
+            const int src = FLIP ? 8 - tp : tp;
+            wv[tp] = f4{wp[src], wp[9 + src], wp[18 + src], wp[27 + src]};
+        }
+    }
+    const f4 *base = (const f4 *)in + (int64_t)n * H * W * C4 + cv;
+    const int h0 = p * STRIDE - 1, v0 = q0 * STRIDE - 1;
+    f4 xv[3][COLS];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int h = h0 + r;
+        const bool hok = (unsigned)h < (unsigned)H;
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+            const int v = v0 + c;
+            const bool ok = hok && (unsigned)v < (unsigned)W;
+            const f4 ld = base[ok ? ((int64_t)h * W + v) * C4 : 0];
+            xv[r][c] = ok ? ld : f4{0, 0, 0, 0};
+        }
+    }
+    f4 *dst = (f4 *)out + (((int64_t)n * P + p) * Q + q0) * C4 + cv;
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        if (q0 + j >= Q) break;
+        f4 acc = f4{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx) acc += xv[r][j * STRIDE + sx] * wv[r * 3 + sx];
+        if (ACC) acc += dst[(int64_t)j * C4];
+        dst[(int64_t)j * C4] = acc;
+    }
+}
+
+template <int STRIDE, int L, bool FLIP, bool ACC>
+void launch_dw3_row(hipStream_t st, const float *in, const float *w, float *out, int N, int H, int W, int P, int Q, int C) {
+    const int segs = (Q + L - 1) / L;
+    const int64_t items = (int64_t)N * P * segs * (C / 4);
+    const int64_t blocks = ((items + 255) / 256 + 7) / 8 * 8;
+    if (blocks > 0x7fffffffll) throw KernelError("depthwise: too many work items");
+    hipLaunchKernelGGL((dw3_row_kernel<STRIDE, L, FLIP, ACC>), dim3((unsigned)blocks), dim3(256), 0, st, in, w, out, N, H, W, P, Q, C / 4, segs,
+                       items);
+}
+
+// Input gradient for stride 2 (pad 1): the 2x2 block of dx at (2p', 2q') reads the 2x2 block of dy at (p', q') --
+//   dx[2p'  ][2q'  ] = dy[p'][q'] w11                      dx[2p'  ][2q'+1] = dy[p'][q'+1] w10 + dy[p'][q'] w12
+//   dx[2p'+1][2q'  ] = dy[p'+1][q'] w01 + dy[p'][q'] w21   dx[2p'+1][2q'+1] = dy[p'+1][q'+1] w00 + dy[p'+1][q'] w02
+//                                                                           + dy[p'][q'+1] w20 + dy[p'][q'] w22
+// One thread per (dy row pair, segment of L block columns, four channels): 2 (L + 1) loads for 4 L outputs, where a
+// kernel over dx pixels tests nine taps each.  The kernel is bound by writing dx, four times the size of dy.
+template <int L, bool ACC>
+__global__ __launch_bounds__(256) void dw3_dgrad_s2_kernel(const float *__restrict__ dy, const float *__restrict__ w, float *dx, int N, int H, int W,
+                                                           int P, int Q, int C4, int rows2, int segs, int64_t items) {
+    const int64_t i = xcd_block(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    if (i >= items) return;
+    const int cv = (int)(i % C4);
+    int64_t t = i / C4;
+    const int seg = (int)(t % segs); t /= segs;
+    const int pp = (int)(t % rows2);
+    const int n = (int)(t / rows2);
+    const int q0 = seg * L;
+    f4 wv[9];
+    {
+        const float *wp = w + (int64_t)cv * 36;
+#pragma unroll
+        for (int tp = 0; tp < 9; ++tp) wv[tp] = f4{wp[tp], wp[9 + tp], wp[18 + tp], wp[27 + tp]};
+    }
+    const f4 *base = (const f4 *)dy + (int64_t)n * P * Q * C4 + cv;
+    f4 g[2][L + 1];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int c = 0; c <= L; ++c) {
+            const bool ok = pp + r < P && q0 + c < Q;
+            const f4 ld = base[ok ? ((int64_t)(pp + r) * Q + q0 + c) * C4 : 0];
+            g[r][c] = ok ? ld : f4{0, 0, 0, 0};
+        }
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        const int v = 2 * (q0 + j);
+        if (v >= W) break;
+        const f4 a = g[0][j], b = g[0][j + 1], c = g[1][j], d = g[1][j + 1];
+        f4 o[2][2];
+        o[0][0] = a * wv[4];
+        o[0][1] = b * wv[3] + a * wv[5];
+        o[1][0] = c * wv[1] + a * wv[7];
+        o[1][1] = d * wv[0] + c * wv[2] + b * wv[6] + a * wv[8];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int h = 2 * pp + r;
+            if (h >= H) continue;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                if (v + e >= W) continue;
+                f4 *dst = (f4 *)dx + (((int64_t)n * H + h) * W + v + e) * C4 + cv;
+                *dst = ACC ? *dst + o[r][e] : o[r][e];
+            }
+        }
+    }
+}
+
+// Filter gradient over row segments (pad 1): blockDim = (CL, 256 / CL) as in dw_wgrad_partial, but a pixel lane
+// takes whole segments of L consecutive outputs of one row: it loads the L output gradients and, row by row, the
+// (L-1)*STRIDE + 3 inputs under them, and every input serves up to three taps from registers (3.9 + 1 loads per
+// output pixel at L = 7 and stride 1 instead of 10).  Slab `blockIdx.x` owns segments [blockIdx.x * per_slab, ...);
+// sums are formed per lane in segment order, then over the lanes in lane order, then over the slabs by
+// dw_wgrad_final: a fixed order throughout.
+template <int STRIDE, int L>
+__global__ __launch_bounds__(256) void dw3_wgrad_row_partial(const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part,
+                                                             int N, int H, int W, int P, int Q, int C, int segs, int64_t items, int64_t per_slab) {
+    constexpr int COLS = (L - 1) * STRIDE + 3;
+    extern __shared__ float red[];   // [blockDim.y][9][CL * 4]
+    const int C4 = C / 4;
+    const int CL = blockDim.x, PL = blockDim.y;
+    const int cv = blockIdx.y * CL + threadIdx.x;
+    const bool live = cv < C4;
+    f4 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = f4{0, 0, 0, 0};
+    const int64_t i0 = (int64_t)blockIdx.x * per_slab;
+    const int64_t i1 = i0 + per_slab < items ? i0 + per_slab : items;
+    if (live) {
+        for (int64_t it = i0 + threadIdx.y; it < i1; it += PL) {
+            const int seg = (int)(it % segs);
+            const int64_t row = it / segs;
+            const int p = (int)(row % P), n = (int)(row / P);
+            const int q0 = seg * L;
+            const f4 *gp = (const f4 *)dy + (((int64_t)n * P + p) * Q + q0) * C4 + cv;
+            f4 g[L];
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                const bool ok = q0 + j < Q;
+                const f4 ld = gp[ok ? (int64_t)j * C4 : 0];
+                g[j] = ok ? ld : f4{0, 0, 0, 0};
+            }
+            const f4 *xn = (const f4 *)x + (int64_t)n * H * W * C4 + cv;
+            const int h0 = p * STRIDE - 1, v0 = q0 * STRIDE - 1;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int h = h0 + r;
+                const bool hok = (unsigned)h < (unsigned)H;
+                f4 xv[COLS];
+#pragma unroll
+                for (int c = 0; c < COLS; ++c) {
+                    const int v = v0 + c;
+                    const bool ok = hok && (unsigned)v < (unsigned)W;
+                    const f4 ld = xn[ok ? ((int64_t)h * W + v) * C4 : 0];
+                    xv[c] = ok ? ld : f4{0, 0, 0, 0};
+                }
+#pragma unroll
+                for (int sx = 0; sx < 3; ++sx)
+#pragma unroll
+                    for (int j = 0; j < L; ++j) acc[r * 3 + sx] += xv[j * STRIDE + sx] * g[j];
+            }
+        }
+    }
+    const int width = CL * 4;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) *(f4 *)(red + ((size_t)threadIdx.y * 9 + t) * width + threadIdx.x * 4) = acc[t];
+    __syncthreads();
+    for (int j = threadIdx.y * CL + threadIdx.x; j < 9 * CL; j += CL * PL) {
+        const int t = j / CL, cl = j - t * CL;
+        const int c4 = blockIdx.y * CL + cl;
+        if (c4 >= C4) continue;
+        f4 sum = f4{0, 0, 0, 0};
+        for (int l = 0; l < PL; ++l) sum += *(const f4 *)(red + ((size_t)l * 9 + t) * width + cl * 4);
+        *(f4 *)(part + ((size_t)blockIdx.x * 9 + t) * C + c4 * 4) = sum;
+    }
+}
+
 // block shape of the 3x3 kernels: CL channel groups (power of two, at most 64) x PL pixel lanes, 16 pixels per thread
 struct Dw3Geom { int CL, PL, chunks; unsigned blocks; int64_t pix_per_block; };
 Dw3Geom dw3_geom(int C4, int64_t pixels) {
@@ -401,7 +599,11 @@ void check_dw(const ConvShape &cs, const char *who) {
 void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs) {
     check_dw(cs, "dwconv_fwd");
     const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
-    if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
+    if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 1) {
+        launch_dw3_row<1, 7, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C);
+    } else if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 2) {
+        launch_dw3_row<2, 4, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C);
+    } else if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
         const Dw3Geom gm = dw3_geom(cs.C / 4, cs.M());
         hipLaunchKernelGGL(dw3_fwd_kernel, dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, x, w, y, cs, gm.pix_per_block);
     } else if (cs.C % 4 == 0) {
@@ -419,7 +621,23 @@ void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, co
     const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
     const int64_t pixels = (int64_t)cs.N * cs.H * cs.W;
 #define DG(V, ACC) hipLaunchKernelGGL((dw_dgrad_kernel<V, ACC>), dim3(grid), dim3(256), lds, st, dy, w, dx, cs)
-    if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
+    if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 1) {
+        // stride 1: the forward operator on dy (same extent as dx) with the filter turned by 180 degrees
+        if (accumulate) launch_dw3_row<1, 7, true, true>(st, dy, w, dx, cs.N, cs.P, cs.Q, cs.H, cs.W, cs.C);
+        else launch_dw3_row<1, 7, true, false>(st, dy, w, dx, cs.N, cs.P, cs.Q, cs.H, cs.W, cs.C);
+    } else if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 2) {
+        constexpr int L = 4;
+        const int rows2 = (cs.H + 1) / 2, segs = ((cs.W + 1) / 2 + L - 1) / L;
+        const int64_t items = (int64_t)cs.N * rows2 * segs * (cs.C / 4);
+        const int64_t blocks = ((items + 255) / 256 + 7) / 8 * 8;
+        if (blocks > 0x7fffffffll) throw KernelError("depthwise: too many work items");
+        if (accumulate)
+            hipLaunchKernelGGL((dw3_dgrad_s2_kernel<L, true>), dim3((unsigned)blocks), dim3(256), 0, st, dy, w, dx, cs.N, cs.H, cs.W, cs.P, cs.Q,
+                               cs.C / 4, rows2, segs, items);
+        else
+            hipLaunchKernelGGL((dw3_dgrad_s2_kernel<L, false>), dim3((unsigned)blocks), dim3(256), 0, st, dy, w, dx, cs.N, cs.H, cs.W, cs.P, cs.Q,
+                               cs.C / 4, rows2, segs, items);
+    } else if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
         const Dw3Geom gm = dw3_geom(cs.C / 4, pixels);
         if (accumulate) hipLaunchKernelGGL((dw3_dgrad_kernel<true>), dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, dy, w, dx, cs, gm.pix_per_block);
         else hipLaunchKernelGGL((dw3_dgrad_kernel<false>), dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, dy, w, dx, cs, gm.pix_per_block);
@@ -445,6 +663,27 @@ void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, co
     const int chunks = (CV + CL - 1) / CL;
     const int64_t M = cs.M();
     const size_t slab_bytes = (size_t)taps * cs.C * 4;
+    if (V == 4 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && (cs.stride == 1 || cs.stride == 2)) {
+        const int L = cs.stride == 1 ? 7 : 4;
+        const int segs = (cs.Q + L - 1) / L;
+        const int64_t items = (int64_t)cs.N * cs.P * segs;
+        // about 2048 workgroups in all, at least two segments per pixel lane
+        int64_t slabs = std::min<int64_t>({std::max<int64_t>(1, 2048 / chunks), (int64_t)(scratch_bytes / slab_bytes), (items + 2 * PL - 1) / (2 * PL)});
+        if (slabs < 1) throw KernelError("dwconv_wgrad: scratch too small");
+        const int64_t per = (items + slabs - 1) / slabs;
+        slabs = (items + per - 1) / per;
+        const size_t lds = (size_t)PL * 9 * CL * 4 * 4;
+        if (lds > 64 * 1024) throw KernelError("dwconv_wgrad: reduction buffer does not fit in LDS");
+        if (cs.stride == 1)
+            hipLaunchKernelGGL((dw3_wgrad_row_partial<1, 7>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs.N, cs.H, cs.W,
+                               cs.P, cs.Q, cs.C, segs, items, per);
+        else
+            hipLaunchKernelGGL((dw3_wgrad_row_partial<2, 4>), dim3((unsigned)slabs, chunks), dim3(CL, PL), lds, st, x, dy, scratch, cs.N, cs.H, cs.W,
+                               cs.P, cs.Q, cs.C, segs, items, per);
+        hipLaunchKernelGGL(dw_wgrad_final, dim3((cs.C * taps + 3) / 4), dim3(256), 0, st, (const float *)scratch, dw, cs.C, taps, (int)slabs);
+        hip_check(hipGetLastError(), "dwconv_wgrad launch");
+        return;
+    }
     int64_t slabs = std::min<int64_t>({(int64_t)4096, (int64_t)(scratch_bytes / slab_bytes), (M + 4 * PL - 1) / (4 * PL)});
     if (slabs < 1) throw KernelError("dwconv_wgrad: scratch too small");
     const int64_t pps = (M + slabs - 1) / slabs;

@@ -73,6 +73,8 @@ DW_CASES = [
     (1, 9, 11, 10, 3, 1, 1),        # C % 4 != 0: scalar path
     (2, 8, 8, 24, 3, 2, 0),         # no padding
     (4, 56, 56, 144, 3, 2, 1),      # many slabs in the filter-gradient reduction
+    (3, 7, 5, 16, 3, 1, 1),         # rows shorter than one segment of the row kernels
+    (2, 112, 112, 32, 3, 1, 1),     # long rows: many segments, the last one ragged
 ]
 
 
