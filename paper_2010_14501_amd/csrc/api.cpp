@@ -239,7 +239,7 @@ void run_forward(const StepCtx &c, const Launch &L, const BnAffine *affine = nul
     } else if (op == "tconv") {
         conv_dgrad(c.st, in0, c.weights[n.pars[0]], out, tconv_adjoint_shape(g, n), false);
     } else if (op == "dwconv") {
-        dwconv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n));
+        dwconv_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), affine);
     } else if (op == "concat") {
         const int Ca = (int)g.shape_of(n.ins[0]).back(), Cb = (int)g.shape_of(n.ins[1]).back();
         const int64_t rows = numel_of(n.shape) / (Ca + Cb);
@@ -505,9 +505,10 @@ bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
     const Graph &g = pl.g;
     if (L1.kind != EV_RUN_RECOMPUTE || L2.kind != EV_RUN_RECOMPUTE) return false;
     const Node &cv = g.nodes[L1.id], &bn = g.nodes[L2.id];
-    if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
+    if ((cv.op != "conv" && cv.op != "dwconv") || bn.op != "bn" || bn.ins[0] != cv.id) return false;
     if (!(L2.flags & 1) || L2.a[2].region != L1.a[2].region || L2.a[2].off != L1.a[2].off) return false;
     const ConvShape cs = conv_shape(g, cv);
+    if (cv.op == "dwconv") return dwconv_fwd_takes_affine(cs);
     const FwdImpl &im = cv.fimpls[L1.impl];
     if (winograd_tile(im.algo)) return winograd_applies(cs, false);
     return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
@@ -716,9 +717,14 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         const char *label;
         if (ps.fuse == FUSE_CONV_BN_APPLY) {
             const ConvShape cs = conv_shape(g, g.nodes[L.id]);
-            out->flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
-            bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * cs.K * (double)cs.RSC() + 4.0 * (double)cs.M() * cs.K;
-            label = "conv_fwd";
+            if (g.nodes[L.id].op == "dwconv") {
+                bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * (double)cs.M() * cs.K;
+                label = "dwconv_fwd";
+            } else {
+                out->flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
+                bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * cs.K * (double)cs.RSC() + 4.0 * (double)cs.M() * cs.K;
+                label = "conv_fwd";
+            }
         } else if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
             const Launch &L3 = p->plan.launches[ps.c];
             e = 4.0 * (double)numel_of(g.nodes[L3.id].shape);

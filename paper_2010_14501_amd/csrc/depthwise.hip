@@ -6,6 +6,7 @@
 // by HBM traffic (one read of the input, one write of the output).  NHWC, fp32, four channels per
 // thread, filters staged in LDS in tap-major order so that four neighbouring channels are one
 // 16-byte LDS read.
+#include "bn_affine.hpp"
 #include "kernels.hpp"
 
 namespace monet {
@@ -384,7 +385,7 @@ __device__ inline int64_t xcd_block(unsigned b, unsigned nb) { return (int64_t)(
 
 template <int STRIDE, int L, bool FLIP, bool ACC>
 __global__ __launch_bounds__(256) void dw3_row_kernel(const float *__restrict__ in, const float *__restrict__ w, float *out, int N, int H, int W,
-                                                      int P, int Q, int C4, int segs, int64_t items) {
+                                                      int P, int Q, int C4, int segs, int64_t items, BnAffine bn) {
     constexpr int COLS = (L - 1) * STRIDE + 3;
     const int64_t i = xcd_block(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
     if (i >= items) return;
@@ -419,6 +420,13 @@ __global__ __launch_bounds__(256) void dw3_row_kernel(const float *__restrict__ 
         }
     }
     f4 *dst = (f4 *)out + (((int64_t)n * P + p) * Q + q0) * C4 + cv;
+    // optional BatchNorm apply step of the result (a recomputed forward operator whose statistics are known)
+    const bool affine = !FLIP && !ACC && bn.gamma != nullptr;
+    float bn_a[4] = {1, 1, 1, 1}, bn_b[4] = {0, 0, 0, 0};
+    if (affine) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bn_affine_coeffs(bn.gamma, bn.beta, bn.stats, 4 * C4, 4 * cv + j, bn_a[j], bn_b[j]);
+    }
 #pragma unroll
     for (int j = 0; j < L; ++j) {
         if (q0 + j >= Q) break;
@@ -428,18 +436,20 @@ __global__ __launch_bounds__(256) void dw3_row_kernel(const float *__restrict__ 
 #pragma unroll
             for (int sx = 0; sx < 3; ++sx) acc += xv[r][j * STRIDE + sx] * wv[r * 3 + sx];
         if (ACC) acc += dst[(int64_t)j * C4];
+        if (affine) acc = f4{bn_affine(acc.x, bn_a[0], bn_b[0]), bn_affine(acc.y, bn_a[1], bn_b[1]), bn_affine(acc.z, bn_a[2], bn_b[2]), bn_affine(acc.w, bn_a[3], bn_b[3])};
         dst[(int64_t)j * C4] = acc;
     }
 }
 
 template <int STRIDE, int L, bool FLIP, bool ACC>
-void launch_dw3_row(hipStream_t st, const float *in, const float *w, float *out, int N, int H, int W, int P, int Q, int C) {
+void launch_dw3_row(hipStream_t st, const float *in, const float *w, float *out, int N, int H, int W, int P, int Q, int C,
+                    const BnAffine &bn = BnAffine{}) {
     const int segs = (Q + L - 1) / L;
     const int64_t items = (int64_t)N * P * segs * (C / 4);
     const int64_t blocks = ((items + 255) / 256 + 7) / 8 * 8;
     if (blocks > 0x7fffffffll) throw KernelError("depthwise: too many work items");
     hipLaunchKernelGGL((dw3_row_kernel<STRIDE, L, FLIP, ACC>), dim3((unsigned)blocks), dim3(256), 0, st, in, w, out, N, H, W, P, Q, C / 4, segs,
-                       items);
+                       items, bn);
 }
 
 // Input gradient for stride 2 (pad 1): the 2x2 block of dx at (2p', 2q') reads the 2x2 block of dy at (p', q') --
@@ -596,13 +606,20 @@ void check_dw(const ConvShape &cs, const char *who) {
 
 }  // namespace
 
-void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs) {
+bool dwconv_fwd_takes_affine(const ConvShape &cs) {
+    return cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && (cs.stride == 1 || cs.stride == 2);
+}
+
+void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, const BnAffine *affine) {
     check_dw(cs, "dwconv_fwd");
     const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
+    if (affine && (!dwconv_fwd_takes_affine(cs) || !affine->gamma || !affine->beta || !affine->stats))
+        throw KernelError("dwconv_fwd: BatchNorm in the same kernel needs a 3x3 / pad 1 layer of stride 1 or 2 with C % 4 == 0 and all coefficients");
+    const BnAffine bn = affine ? *affine : BnAffine{};
     if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 1) {
-        launch_dw3_row<1, 7, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C);
+        launch_dw3_row<1, 7, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C, bn);
     } else if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 2) {
-        launch_dw3_row<2, 4, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C);
+        launch_dw3_row<2, 4, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C, bn);
     } else if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3) {
         const Dw3Geom gm = dw3_geom(cs.C / 4, cs.M());
         hipLaunchKernelGGL(dw3_fwd_kernel, dim3(gm.blocks, gm.chunks), dim3(gm.CL, gm.PL), lds, st, x, w, y, cs, gm.pix_per_block);

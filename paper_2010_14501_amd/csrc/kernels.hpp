@@ -71,7 +71,9 @@ size_t winograd_wgrad_workspace_bytes(const ConvShape &cs, int m);
 void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int m, float *ws, size_t ws_bytes);
 
 // ---- depthwise convolution (K == C, filters C,R,S; at most 9 taps); HBM-bound, no matrix cores
-void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);
+// affine: the BatchNorm apply step of y in the same kernel (only where dwconv_fwd_takes_affine)
+void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, const BnAffine *affine = nullptr);
+bool dwconv_fwd_takes_affine(const ConvShape &cs);
 void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, const ConvShape &cs, bool accumulate);
 // two-level fixed-order reduction; scratch holds slabs * R*S*C floats
 void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *scratch, size_t scratch_bytes);

@@ -253,9 +253,14 @@ def test_resnet50_reduced_batch_against_oracle(batch):
 def test_fused_neighbours_give_identical_bits():
     """The executor launches BN-apply/add + ReLU and ReLU-backward + BN-backward/add-backward as one
     kernel each; results must not differ from the one-kernel-per-operator path by a single bit."""
+    small_mobilenet = graphs.mobilenet_v2(batch=2, hw=32, classes=10, stem=8, last=64,
+                                          stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 16, 2, 2), (6, 24, 1, 1)))
+    wide_resnet = graphs.resnet50(batch=2, hw=32, classes=10, widths=(64, 128), depths=(2, 1), stem=16)   # Winograd layers
     for g, sched in ((graphs.tiny_chain(), lambda g: schedules.tiny_chain_schedule(g, {0, 2})),
                      (small_resnet(), schedules.block_output_schedule),
-                     (small_resnet(), schedules.store_everything_schedule)):
+                     (small_resnet(), schedules.store_everything_schedule),
+                     (small_mobilenet, schedules.mobilenet_depthwise_schedule),      # recomputed depthwise conv + BatchNorm
+                     (wide_resnet, schedules.block_output_schedule)):
         exts, params = tensors.make_inputs(g, seed=4, gamma_beta="random")
         sch = sched(g)
         run = StepRunner(g.text(), sch.text(), exts, params)
@@ -269,5 +274,11 @@ def test_fused_neighbours_give_identical_bits():
         plain, loss_p = run.grads_numpy(), run.loss_value()
         assert loss_f == loss_p
         assert all(np.array_equal(fused[p], plain[p]) for p in fused)
-        labels = {l[0] for l in StepRunner(g.text(), sch.text(), exts, params).plan.launches()}
+        fused_list = StepRunner(g.text(), sch.text(), exts, params).plan.launches()
+        labels = {l[0] for l in fused_list}
         assert labels & {"bn_relu_fwd", "bn_relu_apply", "relu_bn_bwd", "add_relu_fwd", "relu_add_bwd"}
+    # the last two graphs recompute convolutions whose in-place BatchNorm goes into the convolution's kernel:
+    # fewer BatchNorm apply launches than recomputed BatchNorm operators
+    recomputed_bn = sum(1 for e in run.plan.trace_tuples() if e[0] == M.RUN_RECOMPUTE and g.nodes[e[2] - 1].op == "bn")
+    apply_launches = sum(1 for l in fused_list if l[0] in ("bn_apply", "bn_relu_apply", "bn_add_relu_apply"))
+    assert recomputed_bn > 0 and apply_launches < recomputed_bn
