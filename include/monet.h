@@ -155,8 +155,9 @@ typedef struct monet_launch_info {
     int32_t id;
     int32_t impl;
     uint32_t flags;
-    double flops;
+    double flops;            /* algorithmic: the direct form's 2 * multiply-adds */
     double bytes;
+    double issued_flops;     /* what the kernels put on the matrix cores: less than `flops` for a Winograd implementation */
     char label[32];
 } monet_launch_info;
 

@@ -704,6 +704,14 @@ static const std::vector<ProgStep> &current_program(const monet_plan *p) {
 
 extern "C" int monet_plan_num_launches(const monet_plan *p) { return p ? (int)current_program(p).size() : MONET_BAD_ARGUMENT; }
 
+// flop a convolution implementation issues: the algorithmic count, or for Winograd F(m x m, 3x3) the (m+2)^2 GEMMs over the tiles
+static double issued_conv_flops(const ConvShape &cs, const std::string &algo) {
+    const int m = winograd_tile(algo);
+    if (!m) return 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
+    const double tiles = (double)cs.N * ((cs.H + m - 1) / m) * ((cs.W + m - 1) / m);
+    return 2.0 * (m + 2) * (m + 2) * tiles * cs.K * cs.C;
+}
+
 extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_launch_info *out) {
     if (!p || !out || index >= current_program(p).size()) { g_err = "monet_plan_launch_info: bad argument"; return MONET_BAD_ARGUMENT; }
     const Graph &g = p->plan.g;
@@ -722,6 +730,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
                 label = "dwconv_fwd";
             } else {
                 out->flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
+                out->issued_flops = issued_conv_flops(cs, g.nodes[L.id].fimpls[L.impl].algo);
                 bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * cs.K * (double)cs.RSC() + 4.0 * (double)cs.M() * cs.K;
                 label = "conv_fwd";
             }
@@ -767,7 +776,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
     }
     out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
     std::string label;
-    double flops = 0, bytes = 0;
+    double flops = 0, bytes = 0, issued = -1;
     auto conv_cost = [&](const ConvShape &cs, const char *which) {
         flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
         double x = 4.0 * cs.N * cs.H * cs.W * cs.C, w = 4.0 * cs.K * (double)cs.RSC(), y = 4.0 * (double)cs.M() * cs.K;
@@ -779,8 +788,10 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         const Node &n = g.nodes[b.node];
         double e = 4.0 * (double)numel_of(n.shape);
         label = b.kind;
-        if (b.kind == "conv_wgrad") conv_cost(conv_shape(g, n), "conv_wgrad");
-        else if (b.kind == "conv_dgrad") conv_cost(conv_shape(g, n), "conv_dgrad");
+        if (b.kind == "conv_wgrad" || b.kind == "conv_dgrad") {
+            conv_cost(conv_shape(g, n), b.kind.c_str());
+            issued = issued_conv_flops(conv_shape(g, n), b.impls[L.impl].algo);
+        }
         else if (b.kind == "tconv_wgrad") conv_cost(tconv_adjoint_shape(g, n), "tconv_wgrad");
         else if (b.kind == "tconv_dgrad") conv_cost(tconv_adjoint_shape(g, n), "tconv_dgrad");
         else if (b.kind == "linear_wgrad") conv_cost(linear_shape(g, n), "linear_wgrad");
@@ -801,8 +812,10 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         const Node &n = g.nodes[L.id];
         double e = 4.0 * (double)numel_of(n.shape);
         label = n.op + "_fwd";
-        if (n.op == "conv") conv_cost(conv_shape(g, n), "conv_fwd");
-        else if (n.op == "tconv") conv_cost(tconv_adjoint_shape(g, n), "tconv_fwd");
+        if (n.op == "conv") {
+            conv_cost(conv_shape(g, n), "conv_fwd");
+            issued = issued_conv_flops(conv_shape(g, n), n.fimpls[L.impl].algo);
+        } else if (n.op == "tconv") conv_cost(tconv_adjoint_shape(g, n), "tconv_fwd");
         else if (n.op == "concat") bytes = 2 * e;
         else if (n.op == "linear") conv_cost(linear_shape(g, n), "linear_fwd");
         else if (n.op == "bn") {
@@ -814,6 +827,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         else bytes = 4.0 * (double)numel_of(g.shape_of(n.ins[0])) + e;
     }
     out->flops = flops;
+    out->issued_flops = issued < 0 ? flops : issued;
     out->bytes = bytes;
     std::strncpy(out->label, label.c_str(), sizeof(out->label) - 1);
     return MONET_OK;

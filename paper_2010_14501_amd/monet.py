@@ -18,7 +18,7 @@ _LIB = None
 
 class LaunchInfo(C.Structure):
     _fields_ = [("kind", C.c_int32), ("id", C.c_int32), ("impl", C.c_int32), ("flags", C.c_uint32),
-                ("flops", C.c_double), ("bytes", C.c_double), ("label", C.c_char * 32)]
+                ("flops", C.c_double), ("bytes", C.c_double), ("issued_flops", C.c_double), ("label", C.c_char * 32)]
 
 
 class MonetError(RuntimeError):
@@ -191,13 +191,15 @@ class Plan:
     def bn_stats_offset(self, node):
         return self._lib.monet_plan_bn_stats_offset(self._h, node)
 
-    def launches(self):
-        """[(label, kind, id, impl, flops, bytes)] per operator launch, in execution order."""
+    def launches(self, issued=False):
+        """[(label, kind, id, impl, flops, bytes)] per operator launch, in execution order (with issued=True a seventh
+        entry: the flop the kernels issue, which a Winograd implementation cuts below the algorithmic count)."""
         out = []
         for i in range(_check(self._lib.monet_plan_num_launches(self._h))):
             li = LaunchInfo()
             _check(self._lib.monet_plan_launch_info(self._h, i, C.byref(li)))
-            out.append((li.label.decode(), li.kind, li.id, li.impl, li.flops, li.bytes))
+            rec = (li.label.decode(), li.kind, li.id, li.impl, li.flops, li.bytes)
+            out.append(rec + (li.issued_flops,) if issued else rec)
         return out
 
     def set_fusion(self, on):
