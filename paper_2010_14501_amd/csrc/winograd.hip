@@ -452,10 +452,36 @@ bool winograd_applies(const ConvShape &cs, bool adjoint) {
     return red % 16 == 0 && out % 4 == 0;
 }
 
+// Workspace: the transformed filters, then the transformed input and the products of one chunk of whole images.
+// A layer is worked through in as many chunks as the workspace asks for (the filters are transformed once); chunks
+// whose transformed tensors hold about half a GiB cost 0-2 % of time against a single chunk and cap the workspace
+// of the largest layers (5 GB for 176 x 112 x 112 x 128) at a tenth -- the knob Appendix D describes.
+constexpr size_t WINO_CHUNK_BYTES = (size_t)512 << 20;
+
+namespace {
+struct WinoPlan {
+    size_t filt, per_img;      // floats: all transformed filters; transformed input + products of one image
+    int imgs;                  // images per chunk
+};
+WinoPlan wino_plan(const ConvShape &cs, int m, size_t ws_bytes, bool recommend) {
+    const int planes = (m + 2) * (m + 2);
+    WinoPlan wp;
+    wp.filt = (size_t)planes * cs.K * cs.C;
+    wp.per_img = (size_t)planes * ((cs.H + m - 1) / m) * ((cs.W + m - 1) / m) * ((size_t)cs.C + cs.K);
+    if (recommend) {
+        wp.imgs = (int)std::min<size_t>((size_t)cs.N, std::max<size_t>(1, (WINO_CHUNK_BYTES / 4 + wp.per_img - 1) / wp.per_img));
+    } else {
+        const size_t have = ws_bytes / sizeof(float);
+        wp.imgs = have > wp.filt ? (int)std::min<size_t>((size_t)cs.N, (have - wp.filt) / wp.per_img) : 0;
+    }
+    return wp;
+}
+}  // namespace
+
 size_t winograd_workspace_bytes(const ConvShape &cs, int m) {
     check_tile(m, "winograd_workspace_bytes");
-    const WinoGeom gm = geom_of(cs, m);
-    return (size_t)((m + 2) * (m + 2)) * ((size_t)cs.K * cs.C + (size_t)gm.T * cs.C + (size_t)gm.T * cs.K) * sizeof(float);
+    const WinoPlan wp = wino_plan(cs, m, 0, true);
+    return (wp.filt + (size_t)wp.imgs * wp.per_img) * sizeof(float);
 }
 
 // adjoint = false: y[N,H,W,K] (+)= conv3x3(x[N,H,W,C], w[K,3,3,C]);  adjoint = true: in = dy[N,H,W,K], out = dx[N,H,W,C] (+)=
@@ -466,41 +492,49 @@ void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, 
         throw KernelError("conv_winograd: a BatchNorm apply step goes with the forward form, without accumulation, and needs all coefficients");
     const BnAffine bn = affine ? *affine : BnAffine{};
     if (!winograd_applies(cs, adjoint)) throw KernelError("conv_winograd: needs a 3x3 / stride 1 / pad 1 layer with aligned channel counts");
-    if (!ws || ws_bytes < winograd_workspace_bytes(cs, m)) throw KernelError("conv_winograd: workspace too small");
-    const WinoGeom gm = geom_of(cs, m);
+    const WinoPlan wp = wino_plan(cs, m, ws_bytes, false);
+    if (!ws || wp.imgs < 1) throw KernelError("conv_winograd: workspace too small for the transformed filters and one image");
     const int red = adjoint ? cs.K : cs.C, outc = adjoint ? cs.C : cs.K, planes = (m + 2) * (m + 2), vec = m == 2 ? 4 : 2;
-    if (gm.T * (std::max(red, outc) / vec) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd: shape too large");
-    float *U = ws, *V = U + (size_t)planes * cs.K * cs.C, *M = V + (size_t)planes * gm.T * red;
-    const int64_t fe = (int64_t)cs.K * cs.C, ie = gm.T * (red / vec), oe = gm.T * (outc / vec);
-    const dim3 fg((unsigned)((fe + 255) / 256)), ig((unsigned)((ie + 255) / 256)), og((unsigned)((oe + 255) / 256)), blk(256);
+    float *U = ws;
+    const int64_t fe = (int64_t)cs.K * cs.C;
+    const dim3 fg((unsigned)((fe + 255) / 256)), blk(256);
     if (m == 2) {
-        if (adjoint) {
-            hipLaunchKernelGGL(wino_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
-            hipLaunchKernelGGL(wino_input_kernel<1>, ig, blk, 0, st, in, V, gm, red);
-        } else {
-            hipLaunchKernelGGL(wino_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
-            hipLaunchKernelGGL(wino_input_kernel<0>, ig, blk, 0, st, in, V, gm, red);
-        }
+        if (adjoint) hipLaunchKernelGGL(wino_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
+        else hipLaunchKernelGGL(wino_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
     } else {
-        if (adjoint) {
-            hipLaunchKernelGGL(wino4_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
-            hipLaunchKernelGGL(wino4_input_kernel<1>, ig, blk, 0, st, in, V, gm, red);
-        } else {
-            hipLaunchKernelGGL(wino4_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
-            hipLaunchKernelGGL(wino4_input_kernel<0>, ig, blk, 0, st, in, V, gm, red);
-        }
+        if (adjoint) hipLaunchKernelGGL(wino4_filter_kernel<true>, fg, blk, 0, st, w, U, cs.K, cs.C);
+        else hipLaunchKernelGGL(wino4_filter_kernel<false>, fg, blk, 0, st, w, U, cs.K, cs.C);
     }
-    hip_check(hipGetLastError(), "winograd transform launch");
-    gemm_batched(st, V, U, M, planes, gm.T, outc, red, adjoint);
+    hip_check(hipGetLastError(), "winograd filter transform launch");
     const int acc = accumulate ? 1 : 0;
-    if (m == 2) {
-        if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
-        else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
-    } else {
-        if (adjoint) hipLaunchKernelGGL(wino4_output_kernel<true>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
-        else hipLaunchKernelGGL(wino4_output_kernel<false>, og, blk, 0, st, (const float *)M, out, gm, outc, acc, bn);
+    for (int img0 = 0; img0 < cs.N; img0 += wp.imgs) {
+        ConvShape part = cs;
+        part.N = std::min(wp.imgs, cs.N - img0);
+        const WinoGeom gm = geom_of(part, m);
+        if (gm.T * (std::max(red, outc) / vec) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd: shape too large");
+        const float *pin = in + (size_t)img0 * cs.H * cs.W * red;
+        float *pout = out + (size_t)img0 * cs.H * cs.W * outc;
+        float *V = U + wp.filt, *M = V + (size_t)planes * gm.T * red;
+        const int64_t ie = gm.T * (red / vec), oe = gm.T * (outc / vec);
+        const dim3 ig((unsigned)((ie + 255) / 256)), og((unsigned)((oe + 255) / 256));
+        if (m == 2) {
+            if (adjoint) hipLaunchKernelGGL(wino_input_kernel<1>, ig, blk, 0, st, pin, V, gm, red);
+            else hipLaunchKernelGGL(wino_input_kernel<0>, ig, blk, 0, st, pin, V, gm, red);
+        } else {
+            if (adjoint) hipLaunchKernelGGL(wino4_input_kernel<1>, ig, blk, 0, st, pin, V, gm, red);
+            else hipLaunchKernelGGL(wino4_input_kernel<0>, ig, blk, 0, st, pin, V, gm, red);
+        }
+        hip_check(hipGetLastError(), "winograd transform launch");
+        gemm_batched(st, V, U, M, planes, gm.T, outc, red, adjoint);
+        if (m == 2) {
+            if (adjoint) hipLaunchKernelGGL(wino_output_kernel<true>, og, blk, 0, st, (const float *)M, pout, gm, outc, acc, bn);
+            else hipLaunchKernelGGL(wino_output_kernel<false>, og, blk, 0, st, (const float *)M, pout, gm, outc, acc, bn);
+        } else {
+            if (adjoint) hipLaunchKernelGGL(wino4_output_kernel<true>, og, blk, 0, st, (const float *)M, pout, gm, outc, acc, bn);
+            else hipLaunchKernelGGL(wino4_output_kernel<false>, og, blk, 0, st, (const float *)M, pout, gm, outc, acc, bn);
+        }
+        hip_check(hipGetLastError(), "winograd output launch");
     }
-    hip_check(hipGetLastError(), "winograd output launch");
 }
 
 namespace {
@@ -510,38 +544,74 @@ int wgrad_ranges(const ConvShape &cs, int64_t T, int planes) {
     const int64_t tiles = (int64_t)planes * ((cs.K + 127) / 128) * ((cs.C + 127) / 128);
     return (int)std::max<int64_t>(1, std::min<int64_t>(1024 / tiles, T / 128));
 }
+
+// Filter gradient: transformed input and output gradient of one chunk of images, the transformed filter gradient and
+// one more buffer of its size for a chunk's share (added to the former chunk after chunk, i.e. in a fixed order), and
+// the partial sums of a chunk's reduction ranges.
+struct WinoWgradPlan {
+    size_t filt, per_img;
+    int imgs, ranges;
+    size_t floats() const { return (size_t)imgs * per_img + 2 * filt + (ranges > 1 ? (size_t)ranges * filt : 0); }
+};
+WinoWgradPlan wino_wgrad_plan(const ConvShape &cs, int m, int imgs) {
+    const int planes = (m + 2) * (m + 2);
+    WinoWgradPlan wp;
+    wp.filt = (size_t)planes * cs.K * cs.C;
+    const int64_t tiles_img = (int64_t)((cs.H + m - 1) / m) * ((cs.W + m - 1) / m);
+    wp.per_img = (size_t)planes * tiles_img * ((size_t)cs.C + cs.K);
+    wp.imgs = imgs > 0 ? imgs : (int)std::min<size_t>((size_t)cs.N, std::max<size_t>(1, (WINO_CHUNK_BYTES / 4 + wp.per_img - 1) / wp.per_img));
+    wp.ranges = wgrad_ranges(cs, (int64_t)wp.imgs * tiles_img, planes);
+    return wp;
+}
 }  // namespace
 
 size_t winograd_wgrad_workspace_bytes(const ConvShape &cs, int m) {
     check_tile(m, "winograd_wgrad_workspace_bytes");
-    const WinoGeom gm = geom_of(cs, m);
-    const int planes = (m + 2) * (m + 2), sp = wgrad_ranges(cs, gm.T, planes);
-    const size_t filt = (size_t)planes * cs.K * cs.C;
-    return ((size_t)planes * gm.T * (cs.C + cs.K) + filt + (sp > 1 ? (size_t)sp * filt : 0)) * sizeof(float);
+    return wino_wgrad_plan(cs, m, 0).floats() * sizeof(float);
 }
 
 void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int m, float *ws, size_t ws_bytes) {
     check_tile(m, "conv_winograd_wgrad");
     if (cs.R != 3 || cs.S != 3 || cs.stride != 1 || cs.pad != 1 || cs.C % 4 || cs.K % 4)
         throw KernelError("conv_winograd_wgrad: needs a 3x3 / stride 1 / pad 1 layer with channel counts that are multiples of 4");
-    if (!ws || ws_bytes < winograd_wgrad_workspace_bytes(cs, m)) throw KernelError("conv_winograd_wgrad: workspace too small");
-    const WinoGeom gm = geom_of(cs, m);
-    const int planes = (m + 2) * (m + 2), vec = m == 2 ? 4 : 2;
-    if (gm.T * (std::max(cs.C, cs.K) / vec) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd_wgrad: shape too large");
-    const int sp = wgrad_ranges(cs, gm.T, planes);
-    const size_t filt = (size_t)planes * cs.K * cs.C;
-    float *V = ws, *D = V + (size_t)planes * gm.T * cs.C, *dU = D + (size_t)planes * gm.T * cs.K, *slabs = dU + filt;
-    const int64_t ie = gm.T * (cs.C / vec), de = gm.T * (cs.K / vec), fe = (int64_t)cs.K * cs.C;
-    const dim3 ig((unsigned)((ie + 255) / 256)), dg((unsigned)((de + 255) / 256)), fg((unsigned)((fe + 255) / 256)), blk(256);
-    if (m == 2) {
-        hipLaunchKernelGGL(wino_input_kernel<2>, ig, blk, 0, st, x, V, gm, cs.C);
-        hipLaunchKernelGGL(wino_dy_kernel, dg, blk, 0, st, dy, D, gm, cs.K);
-    } else {
-        hipLaunchKernelGGL(wino4_input_kernel<2>, ig, blk, 0, st, x, V, gm, cs.C);
-        hipLaunchKernelGGL(wino4_dy_kernel, dg, blk, 0, st, dy, D, gm, cs.K);
+    // the largest chunk the workspace holds
+    WinoWgradPlan wp = wino_wgrad_plan(cs, m, cs.N);
+    if (!ws || wp.floats() * sizeof(float) > ws_bytes) {
+        int lo = 0, hi = cs.N;                        // floats() grows with imgs over the range that matters: bisect
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) / 2;
+            if (ws && wino_wgrad_plan(cs, m, mid).floats() * sizeof(float) <= ws_bytes) lo = mid; else hi = mid;
+        }
+        if (lo < 1) throw KernelError("conv_winograd_wgrad: workspace too small");
+        wp = wino_wgrad_plan(cs, m, lo);
     }
-    hip_check(hipGetLastError(), "winograd transform launch");
-    gemm_tn_batched(st, D, V, dU, planes, gm.T, cs.K, cs.C, sp, sp > 1 ? slabs : nullptr, sp > 1 ? (size_t)sp * filt * sizeof(float) : 0);
+    const int planes = (m + 2) * (m + 2), vec = m == 2 ? 4 : 2;
+    float *VD = ws, *dU = VD + (size_t)wp.imgs * wp.per_img, *share = dU + wp.filt, *slabs = share + wp.filt;
+    const dim3 blk(256);
+    for (int img0 = 0; img0 < cs.N; img0 += wp.imgs) {
+        ConvShape part = cs;
+        part.N = std::min(wp.imgs, cs.N - img0);
+        const WinoGeom gm = geom_of(part, m);
+        if (gm.T * (std::max(cs.C, cs.K) / vec) / 256 >= 0x7fffffffll || gm.T >= (1 << 24)) throw KernelError("conv_winograd_wgrad: shape too large");
+        float *V = VD, *D = V + (size_t)planes * gm.T * cs.C;
+        const float *px = x + (size_t)img0 * cs.H * cs.W * cs.C, *pdy = dy + (size_t)img0 * cs.H * cs.W * cs.K;
+        const int64_t ie = gm.T * (cs.C / vec), de = gm.T * (cs.K / vec);
+        const dim3 ig((unsigned)((ie + 255) / 256)), dg((unsigned)((de + 255) / 256));
+        if (m == 2) {
+            hipLaunchKernelGGL(wino_input_kernel<2>, ig, blk, 0, st, px, V, gm, cs.C);
+            hipLaunchKernelGGL(wino_dy_kernel, dg, blk, 0, st, pdy, D, gm, cs.K);
+        } else {
+            hipLaunchKernelGGL(wino4_input_kernel<2>, ig, blk, 0, st, px, V, gm, cs.C);
+            hipLaunchKernelGGL(wino4_dy_kernel, dg, blk, 0, st, pdy, D, gm, cs.K);
+        }
+        hip_check(hipGetLastError(), "winograd transform launch");
+        const int sp = std::min(wp.ranges, wgrad_ranges(cs, gm.T, planes));      // the last chunk may be shorter
+        gemm_tn_batched(st, D, V, img0 == 0 ? dU : share, planes, gm.T, cs.K, cs.C, sp, sp > 1 ? slabs : nullptr,
+                        sp > 1 ? (size_t)sp * wp.filt * sizeof(float) : 0);
+        if (img0 > 0) copy_or_accumulate(st, share, dU, (int64_t)wp.filt, true);
+    }
+    const int64_t fe = (int64_t)cs.K * cs.C;
+    const dim3 fg((unsigned)((fe + 255) / 256));
     if (m == 2) hipLaunchKernelGGL(wino_filter_back_kernel, fg, blk, 0, st, (const float *)dU, dw, cs.K, cs.C);
     else hipLaunchKernelGGL(wino4_filter_back_kernel, fg, blk, 0, st, (const float *)dU, dw, cs.K, cs.C);
     hip_check(hipGetLastError(), "winograd filter gradient launch");

@@ -250,15 +250,31 @@ def test_winograd_convolution_matches_oracle(case, m):
     monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, m, 1, 1, ws.data_ptr(), need)
     assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
     with pytest.raises(monet.MonetError):
-        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, m, 0, 0, ws.data_ptr(), need - 4)
-    with pytest.raises(monet.MonetError):
         monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 3, 0, 0, ws.data_ptr(), need)
+    # a workspace that holds one image at a time: the layer goes through in N chunks, with the same bits
+    per_img = (m + 2) ** 2 * 4 * ((H + m - 1) // m) * ((W + m - 1) // m) * (C + K)
+    small = (m + 2) ** 2 * 4 * K * C + per_img + 64
+    if N > 1:
+        y2 = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y2.data_ptr(), N, H, W, C, K, m, 0, 0, ws.data_ptr(), small)
+        assert torch.equal(y, y2)
+    with pytest.raises(monet.MonetError):
+        monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, m, 0, 0, ws.data_ptr(), small - per_img)
     # filter gradient in the transformed domain
     need = monet.call("monet_conv_winograd_wgrad_workspace_bytes", N, H, W, C, K, m)
     ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
     gw = torch.full((K, 3, 3, C), float("nan"), dtype=torch.float32, device="cuda")
     monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, m, ws.data_ptr(), need)
-    assert rel(gw.cpu().numpy(), wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, 3, 3, 1, 1))) < GRAD_TOL
+    want_w = wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, 3, 3, 1, 1))
+    assert rel(gw.cpu().numpy(), want_w) < GRAD_TOL
+    if N > 1:       # in chunks of one image: the chunks' shares are added in image order
+        planes, tiles_img = (m + 2) ** 2, ((H + m - 1) // m) * ((W + m - 1) // m)
+        ranges = max(1, min(1024 // (planes * ((K + 127) // 128) * ((C + 127) // 128)), tiles_img // 128))
+        small = per_img + planes * 4 * K * C * (2 + (ranges if ranges > 1 else 0))
+        ws.fill_(float("nan"))
+        gw.fill_(float("nan"))
+        monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, m, ws.data_ptr(), min(small, need))
+        assert rel(gw.cpu().numpy(), want_w) < GRAD_TOL
 
 
 def test_conv_wgrad_rejects_small_workspace():

@@ -122,21 +122,31 @@ class Graph:
         # channels on large maps it gains 4 % for a workspace of 8x the layer's activations, at 64 it is slower.
         eligible = R == 3 and S == 3 and stride == 1 and pad == 1 and C % 16 == 0 and K % 16 == 0
         wino = eligible and (min(C, K) >= 256 or (min(C, K) >= 128 and H * W <= 28 * 28))
-        # F(4x4, 3x3): 4x fewer multiplications, 36 transformed filters, 2.25x the input and 2.25x the output as
-        # workspace.  Measured 1.2-1.4x faster than the implicit GEMM at 64 channels and 2-3x from 128 up (forward
-        # and input gradient); the filter gradient gains 1.4-2.5x from 96 channels up and loses at 64.  Offered from
-        # 128 channels, and from 64 on maps up to 56x56: on the large 64-channel maps of VGG-16 and UNet a gain of
-        # 1.2x would cost a workspace of several GB at the very point where the step's memory peaks.
-        wino4 = eligible and (min(C, K) >= 128 or (min(C, K) >= 64 and H * W <= 56 * 56))
+        # F(4x4, 3x3): 4x fewer multiplications, 36 transformed filters, 2.25x the input and 2.25x the output of a
+        # chunk of images as workspace.  Measured 1.2-1.4x faster than the implicit GEMM at 64 channels and 2-3x
+        # from 128 up (forward and input gradient); the filter gradient gains 1.4-2.5x from 96 channels up and
+        # loses at 64.
+        wino4 = eligible and min(C, K) >= 64
         wino4_wgrad = wino4 and min(C, K) >= 96
 
-        def wino_ws(m):
-            return _align((m + 2) ** 2 * 4 * (K * C + N * math.ceil(H / m) * math.ceil(W / m) * (C + K)))
+        # Workspace of the Winograd forms (mirrors the library): the transformed filters, plus the transformed input and
+        # the products of one chunk of whole images -- the library works through a layer in chunks of about half a GiB
+        # of transformed tensors, which costs 0-2 % of time and caps the workspace of the largest layers at a tenth.
+        def wino_chunk(m):
+            planes = (m + 2) ** 2
+            per_img = planes * math.ceil(H / m) * math.ceil(W / m) * (C + K)
+            imgs = min(N, max(1, -(-((512 << 20) // 4) // per_img)))
+            return planes, per_img, imgs
 
-        def wino_wgrad_ws(m):      # mirrors the library's choice of reduction ranges
-            planes, T = (m + 2) ** 2, N * math.ceil(H / m) * math.ceil(W / m)
-            ranges = max(1, min(1024 // (planes * math.ceil(K / 128) * math.ceil(C / 128)), T // 128))
-            return _align(4 * (planes * T * (C + K) + planes * K * C * (1 + (ranges if ranges > 1 else 0))))
+        def wino_ws(m):
+            planes, per_img, imgs = wino_chunk(m)
+            return _align(4 * (planes * K * C + imgs * per_img))
+
+        def wino_wgrad_ws(m):      # + the transformed filter gradient, a chunk's share of it, partial sums of its reduction ranges
+            planes, per_img, imgs = wino_chunk(m)
+            tiles = imgs * math.ceil(H / m) * math.ceil(W / m)
+            ranges = max(1, min(1024 // (planes * math.ceil(K / 128) * math.ceil(C / 128)), tiles // 128))
+            return _align(4 * (imgs * per_img + planes * K * C * (2 + (ranges if ranges > 1 else 0))))
 
         if wino:
             self.fimpls[i].append(dict(algo="winograd", ws=wino_ws(2), cost=flop * 0.6))
