@@ -59,16 +59,23 @@ int monet_conv_fwd_bn_apply(void *stream, const float *x, const float *w, float 
 /* Winograd F(m x m, 3x3) form of a 3x3 / stride 1 / pad 1 convolution, m = 2 or 4 (Section 4 lists Winograd among the
  * implementations an operator chooses from; Appendix D: workspace against time).  adjoint == 0: out = y[N,H,W,K] from
  * in = x[N,H,W,C] (needs C % 16 == 0, K % 4 == 0).  adjoint != 0: out = dx[N,H,W,C] (+)= from in = dy[N,H,W,K]
- * (K % 16 == 0, C % 4 == 0).  ws >= monet_conv_winograd_workspace_bytes ((m+2)^2 transformed filters and (m+2)^2 / m^2
- * times the input and the output: 4 x for m = 2, 2.25 x for m = 4), device memory.  m = 4 needs 4 x fewer
+ * (K % 16 == 0, C % 4 == 0).  Workspace (device memory): P = (m+2)^2 transformed filters (P*K*C floats) plus, per image
+ * of a chunk, P * ceil(H/m) * ceil(W/m) * (C + K) floats of transformed input and products (4 x the image's input and
+ * output for m = 2, 2.25 x for m = 4).  The layer is worked through in chunks of as many whole images as ws holds: any
+ * ws_bytes from the filters plus one image up is accepted, the result does not depend on it, and
+ * monet_conv_winograd_workspace_bytes returns the size for chunks of about half a GiB (or the whole batch if smaller),
+ * below which the launches get too small to run at full rate.  Smaller: error.  m = 4 needs 4 x fewer
  * multiplications than the direct form (m = 2: 2.25 x) and rounds about five times more coarsely (normwise error of
  * one layer about 2e-6). */
 int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
                         int m, int adjoint, int accumulate, float *ws, size_t ws_bytes);
 int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K, int m);
 /* Filter gradient of such a layer in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
- * (C % 4 == 0, K % 4 == 0); ws >= monet_conv_winograd_wgrad_workspace_bytes (the transformed input and output gradient,
- * (m+2)^2 transformed filter gradients and their partial sums). */
+ * (C % 4 == 0, K % 4 == 0).  Workspace: the transformed input and output gradient of one chunk of images (as above),
+ * two buffers of P*K*C floats (the transformed filter gradient and one chunk's share of it, added chunk after chunk)
+ * and up to 1024 / (P * ceil(K/128) * ceil(C/128)) more of them for the partial sums of a chunk's reduction ranges;
+ * monet_conv_winograd_wgrad_workspace_bytes returns the size for chunks of about half a GiB, smaller sizes down to one
+ * image per chunk are accepted (the result then differs by rounding: another order of the sum over images). */
 int monet_conv_winograd_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K,
                               int m, float *ws, size_t ws_bytes);
 int64_t monet_conv_winograd_wgrad_workspace_bytes(int N, int H, int W, int C, int K, int m);

@@ -59,7 +59,8 @@ void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out,
                      float *ws, size_t ws_bytes);
 // Winograd F(m x m, 3x3), m = 2 or 4, for 3x3 / stride 1 / pad 1 layers.  adjoint = false: out = y[N,H,W,K] from in = x[N,H,W,C]
 // (C % 16 == 0, K % 4 == 0); adjoint = true: out = dx[N,H,W,C] from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).  Workspace:
-// (m+2)^2 transformed filters and (m+2)^2 / m^2 times the input and the output (winograd_workspace_bytes).
+// (m+2)^2 transformed filters and (m+2)^2 / m^2 times the input and the output of one chunk of whole images; the layer
+// goes through in as many chunks as the workspace asks for (winograd_workspace_bytes: chunks of about half a GiB).
 bool winograd_applies(const ConvShape &cs, bool adjoint);
 size_t winograd_workspace_bytes(const ConvShape &cs, int m);
 // affine (forward only, no accumulation): the BatchNorm apply step of y in the output transform
