@@ -26,6 +26,16 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("resnet50_b184", "conv_fwd"): 533.8e6}
 
 
+def _stored_schedule(path, batch):
+    """A schedule the 0-1 program found (python -m workloads.ilp), kept as text beside the cost table it was priced with."""
+    from workloads import schedules
+    with open(path) as fh:
+        lines = fh.read().splitlines()
+    head = " ".join(l[1:].strip() for l in lines if l.startswith("#"))
+    body = "\n".join(l for l in lines if not l.startswith("#")) + "\n"
+    return schedules.StoredSchedule(body), batch, "0-1 integer program: " + head
+
+
 def build_workload(name, variants=None):
     from workloads import graphs, schedules
     if name.endswith("_igemm"):          # the same workload with every convolution on the implicit GEMM (no Winograd form)
@@ -54,13 +64,7 @@ def build_workload(name, variants=None):
                                  f"({frac * store / 1e9:.2f} GB); block levels {''.join(map(str, levels))}; "
                                  f"predicted recomputation {ms:.1f} ms; lean variants")
         if kind.startswith("ilp_"):
-            # a schedule the 0-1 program found (python -m workloads.ilp), kept as text beside the cost table it was priced with
-            path = os.path.join(ROOT, "workloads", "measured", f"ilp_resnet50_b184_{kind[len('ilp_'):]}.sched")
-            with open(path) as fh:
-                lines = fh.read().splitlines()
-            head = " ".join(l[1:].strip() for l in lines if l.startswith("#"))
-            body = "\n".join(l for l in lines if not l.startswith("#")) + "\n"
-            return g, schedules.StoredSchedule(body), 184, "0-1 integer program: " + head
+            return (g,) + _stored_schedule(os.path.join(ROOT, "workloads", "measured", f"ilp_resnet50_b184_{kind[len('ilp_'):]}.sched"), 184)
         raise SystemExit(f"unknown workload {name}")
     lean = "; lean operator variants"
     nets = {"vgg16_b176": (lambda: graphs.vgg16_bn(batch=176), 176, schedules.vgg_alternate_schedule,
@@ -72,6 +76,10 @@ def build_workload(name, variants=None):
             "googlenet_b320": (lambda: graphs.googlenet(batch=320), 320, schedules.googlenet_alternate_schedule,
                                "every second block (stem stage / inception module) recomputed")}
     for base, (make, batch, named, desc) in nets.items():
+        if name.startswith(base + "_ilp_"):
+            g = make()
+            path = os.path.join(ROOT, "workloads", "measured", f"ilp_{base}_{name[len(base) + 5:]}.sched")
+            return (g,) + _stored_schedule(path, batch)
         if name == base:
             g = make()
             return g, named(g, lean_variants), batch, desc + lean

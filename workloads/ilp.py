@@ -336,7 +336,9 @@ def main():
     from . import graphs, schedules
     from paper_2010_14501_amd import costs, monet
     ap = argparse.ArgumentParser(description=main.__doc__)
-    ap.add_argument("--workload", default="resnet50_b184", choices=["resnet50_b184"])
+    makers = {"resnet50_b184": lambda: graphs.resnet50(batch=184), "vgg16_b176": lambda: graphs.vgg16_bn(batch=176),
+              "unet_b11": lambda: graphs.unet(batch=11), "mobilenetv2_b272": lambda: graphs.mobilenet_v2(batch=272)}
+    ap.add_argument("--workload", default="resnet50_b184", choices=sorted(makers))
     ap.add_argument("--budget", type=float, required=True, help="fraction of the store-everything predicted peak")
     ap.add_argument("--recompute-blocks", type=int, default=0, help="-1: unrestricted")
     ap.add_argument("--time-limit", type=float, default=900.0)
@@ -344,8 +346,8 @@ def main():
     ap.add_argument("--out", required=True)
     args = ap.parse_args()
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    g = graphs.resnet50(batch=184)
-    tau = costs.read_table(os.path.join(root, "workloads", "measured", "costs_resnet50_b184.txt"))
+    g = makers[args.workload]()
+    tau = costs.read_table(os.path.join(root, "workloads", "measured", f"costs_{args.workload}.txt"))
     gt = g.text()
     store = monet.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
     t0 = time.time()
