@@ -141,6 +141,20 @@ def test_other_configurations_at_full_size(name):
     differing = [p for p in ga if not np.array_equal(ga[p], gb[p])]
     assert not differing, differing
     assert filter_orthogonality(g, params, ga) < 2e-3
+    if name == "vgg16_b176":
+        # the schedule the 0-1 program found for 0.45 x the store-everything peak: other saved sets and other operator
+        # implementations, the same loss and gradients within the gradient tolerance, the peak within its budget
+        import bench
+        g2, sch, _, _ = bench.build_workload("vgg16_b176_ilp_0.45")
+        assert g2.text() == g.text()
+        store = M.Plan(g.text(), schedules.store_everything_schedule(g).text()).predicted_peak
+        run = StepRunner(g.text(), sch.text(), exts, params)
+        assert run.step() == run.plan.exact_peak <= run.plan.predicted_peak <= 0.45 * store
+        assert abs(run.loss_value() - la) < 1e-4 * abs(la)
+        got = run.grads_numpy()
+        for p in ga:
+            a, b = got[p].astype(np.float64), ga[p].astype(np.float64)
+            assert np.linalg.norm(a - b) <= 1e-3 * np.linalg.norm(b), p
 
 
 def test_sampled_stem_outputs_and_statistics(full):
