@@ -348,14 +348,6 @@ def main():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     g = makers[args.workload]()
     tau = costs.read_table(os.path.join(root, "workloads", "measured", f"costs_{args.workload}.txt"))
-    # The table prices every operator on its own.  One launch fusion is certain whatever else the program decides: an
-    # in-place recomputation of a BatchNorm needs the convolution before it recomputed in the same stage (Appendix C.3),
-    # and the executor then applies the BatchNorm in that convolution's epilogue -- the apply pass costs nothing.
-    for n in g.nodes:
-        if n.op == "bn" and n.ins[0] > 0 and g.nodes[n.ins[0] - 1].op in ("conv", "dwconv"):
-            for l, d in enumerate(g.fimpls[n.id]):
-                if d.get("inplace") and ("r", n.id, l) in tau:
-                    tau[("r", n.id, l)] = 0.05 * tau[("r", n.id, l)]
     gt = g.text()
     store = monet.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
     t0 = time.time()
