@@ -459,6 +459,13 @@ bool winograd_applies(const ConvShape &cs, bool adjoint) {
 constexpr size_t WINO_CHUNK_BYTES = (size_t)512 << 20;
 
 namespace {
+// the chunks of a layer are made equal: ceil(N / cap) chunks of ceil(N / chunks) images (0 stays 0)
+int even_chunk(int N, int cap) {
+    if (cap < 1) return 0;
+    const int chunks = (N + cap - 1) / cap;
+    return (N + chunks - 1) / chunks;
+}
+
 struct WinoPlan {
     size_t filt, per_img;      // floats: all transformed filters; transformed input + products of one image
     int imgs;                  // images per chunk
@@ -474,6 +481,7 @@ WinoPlan wino_plan(const ConvShape &cs, int m, size_t ws_bytes, bool recommend) 
         const size_t have = ws_bytes / sizeof(float);
         wp.imgs = have > wp.filt ? (int)std::min<size_t>((size_t)cs.N, (have - wp.filt) / wp.per_img) : 0;
     }
+    wp.imgs = even_chunk(cs.N, wp.imgs);
     return wp;
 }
 }  // namespace
@@ -560,6 +568,7 @@ WinoWgradPlan wino_wgrad_plan(const ConvShape &cs, int m, int imgs) {
     const int64_t tiles_img = (int64_t)((cs.H + m - 1) / m) * ((cs.W + m - 1) / m);
     wp.per_img = (size_t)planes * tiles_img * ((size_t)cs.C + cs.K);
     wp.imgs = imgs > 0 ? imgs : (int)std::min<size_t>((size_t)cs.N, std::max<size_t>(1, (WINO_CHUNK_BYTES / 4 + wp.per_img - 1) / wp.per_img));
+    wp.imgs = even_chunk(cs.N, wp.imgs);
     wp.ranges = wgrad_ranges(cs, (int64_t)wp.imgs * tiles_img, planes);
     return wp;
 }

@@ -135,8 +135,9 @@ class Graph:
         def wino_chunk(m):
             planes = (m + 2) ** 2
             per_img = planes * math.ceil(H / m) * math.ceil(W / m) * (C + K)
-            imgs = min(N, max(1, -(-((512 << 20) // 4) // per_img)))
-            return planes, per_img, imgs
+            cap = min(N, max(1, -(-((512 << 20) // 4) // per_img)))
+            chunks = -(-N // cap)
+            return planes, per_img, -(-N // chunks)          # equal chunks
 
         def wino_ws(m):
             planes, per_img, imgs = wino_chunk(m)
