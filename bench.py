@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of a kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by what the
 # same counters read for a plain copy (profiles/step_resnet50_b184_hbm_traffic.txt); counters cannot be read
 # from inside this process, so the figure is the recorded one and null for anything not profiled.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("resnet50_b184", "conv_fwd"): 534.1e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("resnet50_b184", "conv_fwd"): 399.2e6}
 
 
 def _stored_schedule(path, batch):

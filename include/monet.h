@@ -148,7 +148,7 @@ int monet_plan_set_stop_after(monet_plan *plan, int64_t event_index);
  * are algorithmic figures (2*M*N*K of the contraction; bytes of the tensors the operator
  * must read and write once), used to place measured time against the roofline.
  *   kind  2 forward, 3 recomputation, 4 backward;  id = node (kind 2,3) or backward operator k
- *   label e.g. "conv_fwd", "conv_dgrad", "conv_wgrad", "bn_fwd", "bn_apply", "bn_bwd",
+ *   label e.g. "conv_fwd", "conv_dgrad", "conv_wgrad" (implicit GEMM; "..._winograd" for the Winograd forms), "bn_fwd", "bn_apply", "bn_bwd",
  *         "relu_fwd", "relu_bwd", "maxpool_fwd", ... */
 typedef struct monet_launch_info {
     int32_t kind;

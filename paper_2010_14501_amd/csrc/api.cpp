@@ -732,7 +732,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
                 out->flops = 2.0 * (double)cs.M() * cs.K * (double)cs.RSC();
                 out->issued_flops = issued_conv_flops(cs, g.nodes[L.id].fimpls[L.impl].algo);
                 bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * cs.K * (double)cs.RSC() + 4.0 * (double)cs.M() * cs.K;
-                label = "conv_fwd";
+                label = winograd_tile(g.nodes[L.id].fimpls[L.impl].algo) ? "conv_fwd_winograd" : "conv_fwd";
             }
         } else if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
             const Launch &L3 = p->plan.launches[ps.c];
@@ -789,7 +789,8 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         double e = 4.0 * (double)numel_of(n.shape);
         label = b.kind;
         if (b.kind == "conv_wgrad" || b.kind == "conv_dgrad") {
-            conv_cost(conv_shape(g, n), b.kind.c_str());
+            // the Winograd forms (transform kernels + batched GEMMs) are classes of their own
+            conv_cost(conv_shape(g, n), (b.kind + (winograd_tile(b.impls[L.impl].algo) ? "_winograd" : "")).c_str());
             issued = issued_conv_flops(conv_shape(g, n), b.impls[L.impl].algo);
         }
         else if (b.kind == "tconv_wgrad") conv_cost(tconv_adjoint_shape(g, n), "tconv_wgrad");
@@ -813,7 +814,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         double e = 4.0 * (double)numel_of(n.shape);
         label = n.op + "_fwd";
         if (n.op == "conv") {
-            conv_cost(conv_shape(g, n), "conv_fwd");
+            conv_cost(conv_shape(g, n), winograd_tile(n.fimpls[L.impl].algo) ? "conv_fwd_winograd" : "conv_fwd");
             issued = issued_conv_flops(conv_shape(g, n), n.fimpls[L.impl].algo);
         } else if (n.op == "tconv") conv_cost(tconv_adjoint_shape(g, n), "tconv_fwd");
         else if (n.op == "concat") bytes = 2 * e;
