@@ -308,12 +308,73 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const float *__restric
     }
 }
 
+// The same gather from the stored window index with window edge and stride known at compile time: the (at most
+// ceil(K / STRIDE)^2) windows that contain a pixel are enumerated without divisions and all their loads are issued
+// before the first use.  One thread per (pixel, four channels), one pass, no grid-stride loop.
+template <int K, int STRIDE, bool ACC>
+__global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ idx, float *dx, PoolShape ps) {
+    constexpr int CAND = (K + STRIDE - 1) / STRIDE;
+    const int C4 = ps.C / 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)ps.N * ps.H * ps.W * C4) return;
+    const int c4 = (int)(i % C4);
+    int64_t pix = i / C4;
+    const int w = (int)(pix % ps.W);
+    pix /= ps.W;
+    const int h = (int)(pix % ps.H);
+    const int n = (int)(pix / ps.H);
+    const int p_hi = STRIDE == 1 ? h + ps.pad : (STRIDE == 2 ? (h + ps.pad) >> 1 : (h + ps.pad) / STRIDE);
+    const int q_hi = STRIDE == 1 ? w + ps.pad : (STRIDE == 2 ? (w + ps.pad) >> 1 : (w + ps.pad) / STRIDE);
+    float4 g[CAND][CAND];
+    uchar4 ix[CAND][CAND];
+    int mine[CAND][CAND];
+#pragma unroll
+    for (int a = 0; a < CAND; ++a)
+#pragma unroll
+        for (int b = 0; b < CAND; ++b) {
+            const int p = p_hi - a, q = q_hi - b;
+            const int r = h - (p * STRIDE - ps.pad), sx = w - (q * STRIDE - ps.pad);      // position inside window (p, q)
+            const bool ok = p >= 0 && p < ps.P && q >= 0 && q < ps.Q && r < K && sx < K;
+            const int64_t o = ok ? (((int64_t)n * ps.P + p) * ps.Q + q) * C4 + c4 : 0;
+            g[a][b] = ((const float4 *)dy)[o];
+            ix[a][b] = ((const uchar4 *)idx)[o];
+            mine[a][b] = ok ? r * K + sx : -1;
+        }
+    // accumulate in the order of the general kernel: windows by ascending p, then ascending q
+    float acc[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int a = CAND - 1; a >= 0; --a)
+#pragma unroll
+        for (int b = CAND - 1; b >= 0; --b) {
+            const float gg[4] = {g[a][b].x, g[a][b].y, g[a][b].z, g[a][b].w};
+            const int sel[4] = {ix[a][b].x, ix[a][b].y, ix[a][b].z, ix[a][b].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (sel[j] == mine[a][b]) acc[j] += gg[j];
+        }
+    float4 r = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    if (ACC) { float4 o = ((float4 *)dx)[i]; r.x += o.x; r.y += o.y; r.z += o.z; r.w += o.w; }
+    ((float4 *)dx)[i] = r;
+}
+
 void maxpool_bwd(hipStream_t st, const float *dy, const float *x, const uint8_t *idx, float *dx, const PoolShape &ps,
                  bool accumulate) {
     if (ps.C % 4) throw KernelError("maxpool: C must be a multiple of 4");
     if (!idx && !x) throw KernelError("maxpool_bwd: needs the input or the index");
     int64_t total = (int64_t)ps.N * ps.H * ps.W * (ps.C / 4);
     if (total <= 0) return;
+    if (idx && (total + 255) / 256 <= 0x7fffffffll && ps.pad >= 0 && ps.pad < ps.k &&
+        ((ps.k == 3 && (ps.stride == 1 || ps.stride == 2)) || (ps.k == 2 && ps.stride == 2))) {
+        const dim3 g1((unsigned)((total + 255) / 256)), blk(256);
+#define MPI(K, S) do { if (accumulate) hipLaunchKernelGGL((maxpool_bwd_idx_kernel<K, S, true>), g1, blk, 0, st, dy, idx, dx, ps); \
+                       else hipLaunchKernelGGL((maxpool_bwd_idx_kernel<K, S, false>), g1, blk, 0, st, dy, idx, dx, ps); } while (0)
+        if (ps.k == 3 && ps.stride == 1) MPI(3, 1);
+        else if (ps.k == 3) MPI(3, 2);
+        else MPI(2, 2);
+#undef MPI
+        hip_check(hipGetLastError(), "maxpool_bwd launch");
+        return;
+    }
     int grid = grid_for(total, 256, 1 << 16);
 #define MP(F, A) hipLaunchKernelGGL((maxpool_bwd_kernel<F, A>), dim3(grid), dim3(256), 0, st, dy, x, idx, dx, ps)
     if (idx) { if (accumulate) MP(true, true); else MP(true, false); }
