@@ -90,7 +90,7 @@ def main():
     from workloads import graphs, schedules, tensors
     makers = {"resnet50_b184": lambda: graphs.resnet50(batch=184), "vgg16_b176": lambda: graphs.vgg16_bn(batch=176),
               "unet_b11": lambda: graphs.unet(batch=11), "mobilenetv2_b272": lambda: graphs.mobilenet_v2(batch=272),
-              "tiny_chain": graphs.tiny_chain}
+              "googlenet_b320": lambda: graphs.googlenet(batch=320), "tiny_chain": graphs.tiny_chain}
     g = makers[args.workload]()
     exts, params = tensors.make_inputs(g, seed=0)
     lean, std = schedules.DEFAULT_VARIANTS, schedules.STANDARD_VARIANTS

@@ -337,7 +337,8 @@ def main():
     from paper_2010_14501_amd import costs, monet
     ap = argparse.ArgumentParser(description=main.__doc__)
     makers = {"resnet50_b184": lambda: graphs.resnet50(batch=184), "vgg16_b176": lambda: graphs.vgg16_bn(batch=176),
-              "unet_b11": lambda: graphs.unet(batch=11), "mobilenetv2_b272": lambda: graphs.mobilenet_v2(batch=272)}
+              "unet_b11": lambda: graphs.unet(batch=11), "mobilenetv2_b272": lambda: graphs.mobilenet_v2(batch=272),
+              "googlenet_b320": lambda: graphs.googlenet(batch=320)}
     ap.add_argument("--workload", default="resnet50_b184", choices=sorted(makers))
     ap.add_argument("--budget", type=float, required=True, help="fraction of the store-everything predicted peak")
     ap.add_argument("--recompute-blocks", type=int, default=0, help="-1: unrestricted")
