@@ -23,15 +23,12 @@ def nchw_shape(shape):
     return tuple(shape)
 
 
-def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, decisions=None):
+def forward_op(g: OGraph, n, get, params, stats, recompute=False):
     """Output of node n (and its aux outputs as a dict op->array).
 
     `get(ref)` returns an input array.  BatchNorm statistics are taken from
     `stats[n.id]` on recomputation (Appendix D: statistics are reused) and
-    written there otherwise.  `ties` = (band, {relu node: boolean array, max-pool node: tap indices})
-    resolves ReLU decisions and window maxima that fp32 cannot decide (see numerics.resolve_pass,
-    numerics.resolve_argmax); the decisions taken are written to `decisions[n.id]` so that the backward
-    operator takes the same ones.
+    written there otherwise.
     """
     a = n.attrs
     x = get(n.ins[0])
@@ -48,20 +45,10 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, dec
             stats[n.id] = (mean, invstd)
     elif n.op in ("relu", "relu6"):
         six = n.op == "relu6"
-        passes = nm.relu6_pass(x) if six else nm.relu_pass(x)
-        if ties is not None and n.id in ties[1]:
-            passes, undecided = nm.resolve_pass(x, passes, ties[1][n.id], ties[0], six)
-            decisions[n.id] = (passes, undecided)
-            # an element that does not pass sits on the nearer saturation value (0, or 6 for ReLU6)
-            y = np.where(passes, x, np.where(x < 3.0, 0.0, 6.0) if six else 0.0)
-        else:
-            y = nm.relu6_fwd(x) if six else nm.relu_fwd(x)
-        aux["mask"] = lambda: nm.pack_mask(passes)
+        y = nm.relu6_fwd(x) if six else nm.relu_fwd(x)
+        aux["mask"] = lambda: nm.pack_mask(nm.relu6_pass(x) if six else nm.relu_pass(x))
     elif n.op == "maxpool":
         y, idx = nm.maxpool_fwd(x, int(a["k"]), int(a["stride"]), int(a["pad"]))
-        if ties is not None and n.id in ties[1]:
-            idx, undecided = nm.resolve_argmax(x, idx, y, ties[1][n.id], ties[0], int(a["k"]), int(a["stride"]), int(a["pad"]))
-            decisions[n.id] = (idx, undecided)
         aux["poolidx"] = lambda: idx
     elif n.op == "tconv":
         y = nm.tconv2d_fwd(x, params[n.pars[0]], int(a["stride"]))
@@ -84,7 +71,7 @@ def forward_op(g: OGraph, n, get, params, stats, recompute=False, ties=None, dec
     return y, aux
 
 
-def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
+def backward_op(g: OGraph, bop, algo, gy, get, params, stats):
     """(input gradients {input position: array}, parameter gradients {pid: array}).
 
     `get(ref)` returns a forward tensor the chosen implementation depends on.
@@ -122,9 +109,7 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
         return {0: dx}, {n.pars[0]: dg, n.pars[1]: db}
     if kind in ("relu_bwd", "relu6_bwd"):
         six = kind == "relu6_bwd"
-        if decisions is not None and n.id in decisions:
-            dx = gy * decisions[n.id][0]
-        elif algo == "from_input":
+        if algo == "from_input":
             dx = (nm.relu6_bwd_from_input if six else nm.relu_bwd_from_input)(gy, get(n.ins[0]))
         elif algo == "from_output":
             dx = (nm.relu6_bwd_from_output if six else nm.relu_bwd_from_output)(gy, get(n.id))
@@ -136,9 +121,7 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
     if kind == "maxpool_bwd":
         xs = nchw_shape(g.shape_of(n.ins[0]))
         k, st, pd = int(a["k"]), int(a["stride"]), int(a["pad"])
-        if decisions is not None and n.id in decisions:
-            dx = nm.maxpool_bwd_from_index(gy, decisions[n.id][0], xs, k, st, pd)
-        elif algo == "from_input":
+        if algo == "from_input":
             dx = nm.maxpool_bwd_from_input(gy, get(n.ins[0]), k, st, pd)
         elif algo == "from_index":
             dx = nm.maxpool_bwd_from_index(gy, get(g.aux_children[n.id][0]), xs, k, st, pd)
@@ -161,13 +144,16 @@ def backward_op(g: OGraph, bop, algo, gy, get, params, stats, decisions=None):
     raise ValueError(kind)
 
 
-def store_everything_step(graph_text, exts, params, ties=None):
+def store_everything_step(graph_text, exts, params, forward=None, backward=None):
     """Plain training step.  Returns dict(loss, acts{i: array}, aux{i: array}, grads{pid: array},
-    agrads{i: array}, stats{i: (mean, invstd)}, decisions{relu node: (passes, undecided)}).
+    agrads{i: array}, stats{i: (mean, invstd)}).
 
-    `ties` = (band, {relu node: boolean array}): see forward_op."""
+    `forward` / `backward` stand in for `forward_op` / `backward_op` (same arguments, same results) when a
+    caller wants to look at, or wrap, the operators one by one; left out, the definitions above are used."""
     g = OGraph(graph_text)
-    acts, auxv, stats, decisions = {}, {}, {}, {}
+    forward = forward_op if forward is None else forward
+    backward = backward_op if backward is None else backward
+    acts, auxv, stats = {}, {}, {}
 
     def get(ref):
         return exts[ref] if ref <= 0 else acts[ref]
@@ -176,7 +162,7 @@ def store_everything_step(graph_text, exts, params, ties=None):
         n = g.nodes[i]
         if n.is_aux:
             continue
-        y, aux = forward_op(g, n, get, params, stats, ties=ties, decisions=decisions)
+        y, aux = forward(g, n, get, params, stats)
         acts[i] = y
         for c in g.aux_children[i]:
             auxv[c] = aux[g.nodes[c].op]()
@@ -192,11 +178,11 @@ def store_everything_step(graph_text, exts, params, ties=None):
         bop = g.bops[k]
         n = g.nodes[bop.node]
         gy = None if n.persist else agrads[n.id]
-        din, dpar = backward_op(g, bop, bop.impls[0]["algo"], gy, get_any, params, stats, decisions)
+        din, dpar = backward(g, bop, bop.impls[0]["algo"], gy, get_any, params, stats)
         for pos, d in din.items():
             j = n.ins[pos]
             if j > 0:
                 agrads[j] = agrads[j] + d if j in agrads else d.copy()
         for pid, d in dpar.items():
             grads[pid] = d
-    return dict(loss=loss, acts=acts, aux=auxv, grads=grads, agrads=agrads, stats=stats, decisions=decisions)
+    return dict(loss=loss, acts=acts, aux=auxv, grads=grads, agrads=agrads, stats=stats)

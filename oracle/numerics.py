@@ -53,7 +53,8 @@ def conv2d_wgrad(x, dy, R, S, stride, pad):
     for r in range(R):
         for s in range(S):
             win = xp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
-            dw[:, :, r, s] = np.einsum("nkpq,ncpq->kc", dy, win, optimize=True)
+            for n in range(N):      # sum over p,q as one matrix product per image: (K x PQ) (PQ x C)
+                dw[:, :, r, s] += dy[n].reshape(K, P * Q) @ np.ascontiguousarray(win[n]).reshape(C, P * Q).T
     return dw
 
 
@@ -105,7 +106,8 @@ def tconv2d_wgrad(x, dy, R, S, stride):
     for r in range(R):
         for s in range(S):
             win = dy[:, :, r:r + stride * (H - 1) + 1:stride, s:s + stride * (W - 1) + 1:stride]
-            dw[:, :, r, s] = np.einsum("nchv,nkhv->ck", x, win, optimize=True)
+            for n in range(N):      # sum over h,v as one matrix product per image: (C x HW) (HW x K)
+                dw[:, :, r, s] += x[n].reshape(C, H * W) @ np.ascontiguousarray(win[n]).reshape(K, H * W).T
     return dw
 
 
@@ -215,21 +217,6 @@ def relu6_pass(x):
     return (x > 0) & (x < 6)
 
 
-def resolve_pass(x, passes, given, band, six=False):
-    """Sign decisions where a pre-activation is too close to a kink to be decided in fp32.
-
-    An fp32 computation reproduces x only to within the activation tolerance, so for
-    |x| < band * rms(x) (and, for ReLU6, |x - 6| below the same bound) either decision is a valid
-    result.  `given` says which one to take there; everywhere else the strict predicate stands.
-    Returns (decisions, undecided) as boolean arrays.
-    """
-    lim = band * np.sqrt(np.mean(x * x))
-    undecided = np.abs(x) < lim
-    if six:
-        undecided |= np.abs(x - 6.0) < lim
-    return np.where(undecided, given, passes), undecided
-
-
 def pack_mask(pass_nchw):
     """1-bit code: bit (e & 63) of little-endian 64-bit word (e >> 6), e = N,H,W,C linear index."""
     stored = np.transpose(pass_nchw, (0, 2, 3, 1)) if pass_nchw.ndim == 4 else pass_nchw
@@ -286,28 +273,6 @@ def maxpool_fwd(x, k, stride, pad):
             best = np.where(take, win, best)
             idx = np.where(take, np.uint8(r * k + s), idx)
     return best, idx
-
-
-def resolve_argmax(x, idx, best, given, band, k, stride, pad):
-    """Window maxima that fp32 cannot tell apart.
-
-    An fp32 computation reproduces x only to within the activation tolerance, so a tap whose value lies
-    within band * rms(x) of the window maximum is as valid a (sub)gradient route as the maximum itself.
-    `given` names one tap per window (r*k+s); it is taken where it is such a tap, the strict choice `idx`
-    stands everywhere else (also where `given` points at padding or outside the window).  The forward value
-    stays the maximum.  Returns (indices, undecided) with undecided = windows where `given` replaced `idx`."""
-    N, C, H, W = x.shape
-    P, Q = best.shape[2:]
-    xp = np.full((N, C, H + 2 * pad, W + 2 * pad), -np.inf, F64)
-    xp[:, :, pad:pad + H, pad:pad + W] = x
-    val = np.full(best.shape, -np.inf, F64)
-    for r in range(k):
-        for s in range(k):
-            win = xp[:, :, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
-            val = np.where(given == r * k + s, win, val)
-    lim = band * np.sqrt(np.mean(x * x))
-    undecided = (given != idx) & (best - val < lim)
-    return np.where(undecided, given, idx).astype(np.uint8), undecided
 
 
 def maxpool_bwd_from_index(dy, idx, x_shape, k, stride, pad):

@@ -1,4 +1,4 @@
-"""Builds libmonet.so (host planner + gfx950 kernels) and the oracle's C parts, in-tree."""
+"""Builds libmonet.so (host planner + gfx950 kernels) in-tree."""
 import os
 import subprocess
 import sys

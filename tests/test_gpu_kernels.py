@@ -11,7 +11,7 @@ from paper_2010_14501_amd import monet
 
 pytestmark = pytest.mark.gpu
 
-ACT_TOL, GRAD_TOL = 1e-4, 1e-3
+from parity_util import ACT_TOL, GRAD_TOL, rel, check_close
 
 
 def torch_mod():
@@ -22,13 +22,6 @@ def torch_mod():
 def dev(a):
     torch = torch_mod()
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
-
-
-def rel(got, want):
-    want = np.asarray(want, np.float64)
-    d = np.linalg.norm(np.asarray(got, np.float64) - want)
-    n = np.linalg.norm(want)
-    return d if n == 0 else d / n
 
 
 CONV_CASES = [
@@ -61,29 +54,29 @@ def test_conv_trio_matches_oracle(case):
     y = torch.empty((N, P, Q, K), dtype=torch.float32, device="cuda")
     monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, None, 0)
     want = wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad))
-    assert rel(y.cpu().numpy(), want) < ACT_TOL
+    check_close(y.cpu().numpy(), want, ACT_TOL)
     need = max(monet.call("monet_conv_workspace_bytes", which, N, H, W, C, K, R, R, stride, pad, 5) for which in (0, 1))
     big = torch.empty(need // 4, dtype=torch.float32, device="cuda")     # split workspace
     for splits in (2, 5):
         y.fill_(float("nan"))
         monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad,
                    splits, big.data_ptr(), big.numel() * 4)
-        assert rel(y.cpu().numpy(), want) < ACT_TOL, splits
+        check_close(y.cpu().numpy(), want, ACT_TOL, what=splits)
     # input gradient, plain and accumulating
     gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
     monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0, 1, None, 0)
     want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, stride, pad))
-    assert rel(gx.cpu().numpy(), want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), want, GRAD_TOL)
     monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, 1, None, 0)
-    assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), 2 * want, GRAD_TOL)
     for splits in (2, 5):
         gx.fill_(float("nan"))
         monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0,
                    splits, big.data_ptr(), big.numel() * 4)
-        assert rel(gx.cpu().numpy(), want) < GRAD_TOL, splits
+        check_close(gx.cpu().numpy(), want, GRAD_TOL, what=splits)
         monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1,
                    splits, big.data_ptr(), big.numel() * 4)
-        assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL, splits
+        check_close(gx.cpu().numpy(), 2 * want, GRAD_TOL, what=splits)
     # weight gradient: no workspace, and split with workspace
     want = wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, R, R, stride, pad))
     for splits in (1, 3, 8):
@@ -91,7 +84,7 @@ def test_conv_trio_matches_oracle(case):
         ws = torch.empty(splits * K * R * R * C, dtype=torch.float32, device="cuda")
         monet.call("monet_conv_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, R, R, stride, pad,
                    splits, ws.data_ptr(), ws.numel() * 4)
-        assert rel(gw.cpu().numpy(), want) < GRAD_TOL, splits
+        check_close(gw.cpu().numpy(), want, GRAD_TOL, what=splits)
 
 
 def test_conv_ragged_last_round_is_split_and_counts_reset():
@@ -116,14 +109,14 @@ def test_conv_ragged_last_round_is_split_and_counts_reset():
     for rep in range(3):
         y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, ws.data_ptr(), need[0])
-        assert rel(y.cpu().numpy(), want_y) < ACT_TOL, rep
+        check_close(y.cpu().numpy(), want_y, ACT_TOL, what=rep)
         assert torch.equal(y[:32], y0[:32])                                   # whole tiles: same kernel path, same bits
         assert rel(y.cpu().numpy(), y0.cpu().numpy()) < 1e-6
         gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0, 1, ws.data_ptr(), need[1])
-        assert rel(gx.cpu().numpy(), want_dx) < GRAD_TOL, rep
+        check_close(gx.cpu().numpy(), want_dx, GRAD_TOL, what=rep)
         monet.call("monet_conv_dgrad", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, 1, ws.data_ptr(), need[1])
-        assert rel(gx.cpu().numpy(), 2 * want_dx) < GRAD_TOL, rep
+        check_close(gx.cpu().numpy(), 2 * want_dx, GRAD_TOL, what=rep)
 
 
 @pytest.mark.parametrize("case", [
@@ -165,7 +158,8 @@ def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
     assert torch.equal(fused, alone)
     mean, invstd = nm.bn_stats(wt.act_to_oracle(y2.cpu().numpy()), 1e-5)
     got = fused.cpu().numpy()
-    assert rel(got[:K], mean) < ACT_TOL and rel(got[K:], invstd) < ACT_TOL
+    check_close(got[:K], mean, ACT_TOL)
+    check_close(got[K:], invstd, ACT_TOL)
 
 
 @pytest.mark.parametrize("case", [
@@ -210,7 +204,7 @@ def test_batchnorm_apply_in_the_conv_epilogue_is_the_stand_alone_bits(case):
     assert torch.equal(fused, y)
     yo = nm.conv2d_fwd(wt.act_to_oracle(x), wt.weight_to_oracle(w), stride, pad)
     want = nm.bn_apply(yo, gamma.astype(np.float64), beta.astype(np.float64), stats[:K].astype(np.float64), stats[K:].astype(np.float64))
-    assert rel(fused.cpu().numpy(), wt.act_from_oracle(want)) < ACT_TOL
+    check_close(fused.cpu().numpy(), wt.act_from_oracle(want), ACT_TOL)
     with pytest.raises(monet.MonetError):       # no Winograd form with 3x3 output tiles
         monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), fused.data_ptr(), N, H, W, C, K, R, R, stride, pad, 3,
                    wsp, need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr())
@@ -242,13 +236,13 @@ def test_winograd_convolution_matches_oracle(case, m):
     ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
     y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
     monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, m, 0, 0, ws.data_ptr(), need)
-    assert rel(y.cpu().numpy(), wt.act_from_oracle(nm.conv2d_fwd(xo, wo, 1, 1))) < ACT_TOL
+    check_close(y.cpu().numpy(), wt.act_from_oracle(nm.conv2d_fwd(xo, wo, 1, 1)), ACT_TOL)
     gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
     want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, 1, 1))
     monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, m, 1, 0, ws.data_ptr(), need)
-    assert rel(gx.cpu().numpy(), want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), want, GRAD_TOL)
     monet.call("monet_conv_winograd", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, m, 1, 1, ws.data_ptr(), need)
-    assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), 2 * want, GRAD_TOL)
     with pytest.raises(monet.MonetError):
         monet.call("monet_conv_winograd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 3, 0, 0, ws.data_ptr(), need)
     # a workspace that holds one image at a time: the layer goes through in N chunks, with the same bits
@@ -270,7 +264,7 @@ def test_winograd_convolution_matches_oracle(case, m):
     gw = torch.full((K, 3, 3, C), float("nan"), dtype=torch.float32, device="cuda")
     monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, m, ws.data_ptr(), need)
     want_w = wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, 3, 3, 1, 1))
-    assert rel(gw.cpu().numpy(), want_w) < GRAD_TOL
+    check_close(gw.cpu().numpy(), want_w, GRAD_TOL)
     if N > 1:       # in chunks of one image: the chunks' shares are added in image order
         planes, tiles_img = (m + 2) ** 2, ((H + m - 1) // m) * ((W + m - 1) // m)
         ranges = max(1, min(1024 // (planes * ((K + 127) // 128) * ((C + 127) // 128)), tiles_img // 128))
@@ -278,7 +272,7 @@ def test_winograd_convolution_matches_oracle(case, m):
         ws.fill_(float("nan"))
         gw.fill_(float("nan"))
         monet.call("monet_conv_winograd_wgrad", None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, m, ws.data_ptr(), min(small, need))
-        assert rel(gw.cpu().numpy(), want_w) < GRAD_TOL
+        check_close(gw.cpu().numpy(), want_w, GRAD_TOL)
 
 
 def test_conv_wgrad_rejects_small_workspace():
@@ -317,7 +311,7 @@ def test_batchnorm_matches_oracle(rows, C):
     assert rel(st[:C], mean) < 1e-5 and rel(st[C:], invstd) < 1e-5
     y = torch.empty_like(dx_)
     monet.call("monet_bn_apply", None, dx_.data_ptr(), y.data_ptr(), dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(), rows, C)
-    assert rel(y.cpu().numpy(), yo.reshape(rows, C)) < ACT_TOL
+    check_close(y.cpu().numpy(), yo.reshape(rows, C), ACT_TOL)
     # in place
     xin = dx_.clone()
     monet.call("monet_bn_apply", None, xin.data_ptr(), xin.data_ptr(), dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(), rows, C)
@@ -328,11 +322,12 @@ def test_batchnorm_matches_oracle(rows, C):
         gb = torch.empty(C, dtype=torch.float32, device="cuda")
         monet.call("monet_bn_bwd", None, dd.data_ptr(), t.data_ptr(), from_output, dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(),
                    gx.data_ptr(), gg.data_ptr(), gb.data_ptr(), rows, C, 0, scratch.data_ptr(), scratch.numel() * 4)
-        assert rel(gx.cpu().numpy(), dxo.reshape(rows, C)) < GRAD_TOL
-        assert rel(gg.cpu().numpy(), dgo) < GRAD_TOL and rel(gb.cpu().numpy(), dbo) < GRAD_TOL
+        check_close(gx.cpu().numpy(), dxo.reshape(rows, C), GRAD_TOL)
+        check_close(gg.cpu().numpy(), dgo, GRAD_TOL)
+        check_close(gb.cpu().numpy(), dbo, GRAD_TOL)
         monet.call("monet_bn_bwd", None, dd.data_ptr(), t.data_ptr(), from_output, dg_.data_ptr(), dbeta_.data_ptr(), stats.data_ptr(),
                    gx.data_ptr(), gg.data_ptr(), gb.data_ptr(), rows, C, 1, scratch.data_ptr(), scratch.numel() * 4)
-        assert rel(gx.cpu().numpy(), 2 * dxo.reshape(rows, C)) < GRAD_TOL
+        check_close(gx.cpu().numpy(), 2 * dxo.reshape(rows, C), GRAD_TOL)
 
 
 def test_batchnorm_statistics_with_large_offset():

@@ -11,7 +11,8 @@ from oracle import schedule as osch
 from workloads import graphs, schedules, tensors as wt
 from paper_2010_14501_amd import monet
 from paper_2010_14501_amd.runner import StepRunner
-from parity_util import ACT_TOL, GRAD_TOL, rel, compare_grads, oracle_with_gpu_ties
+from parity_util import (ACT_TOL, GRAD_TOL, DEEP_ACT_TOL, DECISION_BAND, rel, check_close, compare_grads,
+                         oracle_with_gpu_decisions)
 
 pytestmark = pytest.mark.gpu
 
@@ -48,20 +49,20 @@ def test_tconv_trio_matches_oracle(case):
     dx_, dw_, ddy = dev(x), dev(w), dev(dy)
     y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
     monet.call("monet_tconv_fwd", None, dx_.data_ptr(), dw_.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride)
-    assert rel(y.cpu().numpy(), wt.act_from_oracle(nm.tconv2d_fwd(xo, wo, stride))) < ACT_TOL
+    check_close(y.cpu().numpy(), wt.act_from_oracle(nm.tconv2d_fwd(xo, wo, stride)), ACT_TOL)
     gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
     want = wt.act_from_oracle(nm.tconv2d_dgrad(dyo, wo, stride))
     monet.call("monet_tconv_dgrad", None, ddy.data_ptr(), dw_.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, 0)
-    assert rel(gx.cpu().numpy(), want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), want, GRAD_TOL)
     monet.call("monet_tconv_dgrad", None, ddy.data_ptr(), dw_.data_ptr(), gx.data_ptr(), N, H, W, C, K, R, R, stride, 1)
-    assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), 2 * want, GRAD_TOL)
     want = wt.weight_from_oracle(nm.tconv2d_wgrad(xo, dyo, R, R, stride))
     ws = torch.empty(4 * w.size, dtype=torch.float32, device="cuda")
     for splits in (1, 3):
         gw = torch.full((C, R, R, K), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_tconv_wgrad", None, dx_.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, R, R, stride,
                    splits, ws.data_ptr(), ws.numel() * 4)
-        assert rel(gw.cpu().numpy(), want) < GRAD_TOL, splits
+        check_close(gw.cpu().numpy(), want, GRAD_TOL, what=splits)
 
 
 # ------------------------------------------------------------------ depthwise convolution
@@ -91,20 +92,20 @@ def test_dwconv_trio_matches_oracle(case):
     dx_, dw_, ddy = dev(x), dev(w), dev(dy)
     y = torch.full((N, P, Q, C), float("nan"), dtype=torch.float32, device="cuda")
     monet.call("monet_dwconv_fwd", None, dx_.data_ptr(), dw_.data_ptr(), y.data_ptr(), N, H, W, C, R, R, stride, pad)
-    assert rel(y.cpu().numpy(), wt.act_from_oracle(nm.dwconv2d_fwd(xo, wo, stride, pad))) < ACT_TOL
+    check_close(y.cpu().numpy(), wt.act_from_oracle(nm.dwconv2d_fwd(xo, wo, stride, pad)), ACT_TOL)
     gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
     want = wt.act_from_oracle(nm.dwconv2d_dgrad(dyo, wo, xo.shape, stride, pad))
     monet.call("monet_dwconv_dgrad", None, ddy.data_ptr(), dw_.data_ptr(), gx.data_ptr(), N, H, W, C, R, R, stride, pad, 0)
-    assert rel(gx.cpu().numpy(), want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), want, GRAD_TOL)
     monet.call("monet_dwconv_dgrad", None, ddy.data_ptr(), dw_.data_ptr(), gx.data_ptr(), N, H, W, C, R, R, stride, pad, 1)
-    assert rel(gx.cpu().numpy(), 2 * want) < GRAD_TOL
+    check_close(gx.cpu().numpy(), 2 * want, GRAD_TOL)
     want = wt.weight_from_oracle(nm.dwconv2d_wgrad(xo, dyo, R, R, stride, pad))
     for scratch_floats in (R * R * C, 1 << 20):     # one slab only, and many slabs
         scratch = torch.empty(scratch_floats, dtype=torch.float32, device="cuda")
         gw = torch.full((C, R, R, 1), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_dwconv_wgrad", None, dx_.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, R, R, stride, pad,
                    scratch.data_ptr(), scratch.numel() * 4)
-        assert rel(gw.cpu().numpy(), want) < GRAD_TOL, scratch_floats
+        check_close(gw.cpu().numpy(), want, GRAD_TOL, what=scratch_floats)
     # the reduction order is fixed: two runs give the same bits
     gw2 = torch.empty_like(gw)
     monet.call("monet_dwconv_wgrad", None, dx_.data_ptr(), ddy.data_ptr(), gw2.data_ptr(), N, H, W, C, R, R, stride, pad,
@@ -157,9 +158,9 @@ def test_softmaxce_rows_matches_oracle(rows, classes):
     g = torch.full((rows, classes), 1.0, dtype=torch.float32, device="cuda")
     wantg = nm.softmaxce_bwd(z.astype(np.float64), lab)
     monet.call("monet_softmaxce_rows_bwd", None, dz.data_ptr(), dl.data_ptr(), g.data_ptr(), rows, classes, 0)
-    assert rel(g.cpu().numpy(), wantg) < GRAD_TOL
+    check_close(g.cpu().numpy(), wantg, GRAD_TOL)
     monet.call("monet_softmaxce_rows_bwd", None, dz.data_ptr(), dl.data_ptr(), g.data_ptr(), rows, classes, 1)
-    assert rel(g.cpu().numpy(), 2 * wantg) < GRAD_TOL
+    check_close(g.cpu().numpy(), 2 * wantg, GRAD_TOL)
 
 
 # ------------------------------------------------------------------ whole steps
@@ -176,12 +177,12 @@ def small_mbv2():
                                stages=((1, 8, 1, 1), (6, 12, 2, 2), (6, 16, 2, 2), (6, 24, 1, 1)))
 
 
-def alternate_blocks_schedule(g):
+def alternate_blocks_schedule(g, variants=schedules.DEFAULT_VARIANTS):
     """Every second block is recomputed (its own tensors are not kept)."""
     keep = {b for b in range(len(g.blocks)) if b % 2 == 0} | {len(g.blocks) - 1}
-    bimpl = schedules.choose_bimpls(g, schedules.DEFAULT_VARIANTS)
+    bimpl = schedules.choose_bimpls(g, variants)
     F = schedules.block_checkpoint_set(g, bimpl, keep)
-    return schedules.expand(g, F, bimpl, allow_inplace=True, conv_algo=schedules.DEFAULT_VARIANTS["conv_fwd"])
+    return schedules.expand(g, F, bimpl, allow_inplace=True, conv_algo=variants["conv_fwd"])
 
 
 def small_googlenet():
@@ -199,22 +200,32 @@ NETS = {
     # the inception network at its real geometry: on smaller maps the 3x3 / stride-1 pool branch turns nearly constant
     # over the positions and its BatchNorm ill-conditioned, which says nothing about the kernels
     "googlenet_wide": lambda: graphs.googlenet(batch=2, hw=224),
+    # the networks of the paper's model list at their input sizes, at the batch the fp64 oracle does in a minute:
+    # only these reach F(4x4) Winograd on 224x224x64 maps and its chunked workspace, 112-pixel depthwise rows,
+    # non-square 416x608 maps and 2x2 pools on large maps
+    "vgg_full": lambda: graphs.vgg16_bn(batch=2),
+    "mbv2_full": lambda: graphs.mobilenet_v2(batch=2),
+    "unet_full": lambda: graphs.unet(batch=1),
 }
+VARIANT_SETS = {"default": schedules.DEFAULT_VARIANTS, "igemm": schedules.IGEMM_VARIANTS}
+CASES = [(name, "default") for name in NETS] + [(name, "igemm") for name in NETS if name.endswith("_full")]
 
 
-@pytest.mark.parametrize("name", list(NETS))
-def test_network_step_against_oracle(name):
+@pytest.mark.parametrize("name,vname", CASES)
+def test_network_step_against_oracle(name, vname):
     g = NETS[name]()
+    variants = VARIANT_SETS[vname]
     exts, params = wt.make_inputs(g, seed=3, gamma_beta="random")
-    ref, st, _ = oracle_with_gpu_ties(g, exts, params)
-    print(f"{name}: {st['flips']} sign bits differ, all among the {st['undecided']} undecided of {st['total']}; "
-          f"worst BatchNorm-output error {st['worst_act']:.2e}")
-    assert st["undecided"] < 4e-3 * st["total"]
-    assert st["worst_act"] < 3 * ACT_TOL
+    ref, st, _ = oracle_with_gpu_decisions(g, exts, params, variants)
+    print(f"{name} {vname}: {st['differ']} of {st['total']} decisions differ, farthest from the kink {st['max_dist']:.2e} rms "
+          f"(band {DECISION_BAND:.0e}); worst BatchNorm-output error {st['worst_act']:.2e} normwise, "
+          f"{st['worst_act_maxabs']:.2e} rms element-wise")
+    assert st["differ"] < 1e-4 * st["total"] + 8
+    assert st["worst_act"] < DEEP_ACT_TOL and st["worst_act_maxabs"] < 50 * DEEP_ACT_TOL
     got = {}
-    for sname, make in (("store", lambda g: schedules.store_everything_schedule(g, schedules.DEFAULT_VARIANTS)),
-                        ("block_outputs", schedules.block_output_schedule),
-                        ("alternate", alternate_blocks_schedule)):
+    for sname, make in (("store", lambda g: schedules.store_everything_schedule(g, variants)),
+                        ("block_outputs", lambda g: schedules.block_output_schedule(g, variants)),
+                        ("alternate", lambda g: alternate_blocks_schedule(g, variants))):
         sch = make(g)
         want = osch.interpret(g.text(), sch.text())
         run = StepRunner(g.text(), sch.text(), exts, params, poison=True)
@@ -223,7 +234,8 @@ def test_network_step_against_oracle(name):
         assert abs(run.loss_value() - ref["loss"]) < ACT_TOL * abs(ref["loss"]), sname
         got[sname] = run.grads_numpy()
         worst = compare_grads(got[sname], ref, g=g)
-        print(f"{name}/{sname}: peak {peak}, recomputes {want['recomputes']}, worst gradient error {worst:.2e}")
+        print(f"{name} {vname}/{sname}: peak {peak}, recomputes {want['recomputes']}, worst gradient error {worst:.2e}")
+        del run
     # recomputation alone must not change a bit
     for sname in ("block_outputs", "alternate"):
         same = [np.array_equal(got["store"][p], got[sname][p]) for p in got["store"]]

@@ -162,6 +162,18 @@ def test_mask_strict_predicate_and_roundtrip():
     assert np.array_equal(nm.relu_bwd_from_output(dz, nm.relu_fwd(xs)), nm.relu_bwd_from_input(dz, xs))
 
 
+def test_relu_forward_values_by_hand():
+    """Forward values on hand-picked inputs: negative, both zeros and NaN give +0, positives pass unchanged;
+    ReLU6 also passes 6 itself and holds everything above it at 6."""
+    with np.errstate(invalid="ignore"):
+        y = nm.relu_fwd(np.array([-1.0, 0.0, -0.0, 2.0, np.nan, 7.5, -np.inf, np.inf]))
+        y6 = nm.relu6_fwd(np.array([-1.0, 0.0, -0.0, 3.0, 6.0, 7.0, np.nan, 5.999, np.inf]))
+    assert y.tolist() == [0.0, 0.0, 0.0, 2.0, 0.0, 7.5, 0.0, np.inf]
+    assert not np.signbit(y[:5]).any()
+    assert y6.tolist() == [0.0, 0.0, 0.0, 3.0, 6.0, 6.0, 0.0, 5.999, 6.0]
+    assert not np.signbit(y6).any()
+
+
 def test_relu6_variants_agree():
     x = RNG.standard_normal((2, 3, 4, 5)) * 4
     dz = RNG.standard_normal(x.shape)

@@ -176,86 +176,7 @@ def test_linear_over_flattened_image():
     assert rel(nm.linear_fwd(x2, w2, b), x2 @ w2.T + b) < 1e-15
 
 
-def test_tie_resolution_with_strict_decisions_changes_nothing():
-    """Handing the step its own strict ReLU / ReLU6 decisions as the tie-breaking input must reproduce
-    the plain step exactly (in particular a ReLU6 element above 6 stays at 6)."""
-    from oracle import network as onet
-    from workloads import graphs, tensors
-    g = graphs.mobilenet_v2(batch=2, hw=16, classes=5, stem=8, last=32, stages=((1, 8, 1, 1), (6, 12, 2, 2)))
-    exts, params = tensors.make_inputs(g, seed=5, gamma_beta="random")
-    params = {p: (3.0 * v if g.params[p][1].endswith(".gamma") else v) for p, v in params.items()}   # push values past 6
-    oe, op = tensors.oracle_inputs(exts, params)
-    plain = onet.store_everything_step(g.text(), oe, op)
-    strict, above = {}, 0
-    for n in g.nodes:
-        if n.op == "relu6":
-            x = plain["acts"][n.ins[0]]
-            strict[n.id] = (x > 0) & (x < 6)
-            above += int((x > 6).sum())
-    assert above > 0
-    tied = onet.store_everything_step(g.text(), oe, op, ties=(1e-3, strict))
-    assert tied["loss"] == plain["loss"]
-    assert all(np.array_equal(tied["grads"][p], plain["grads"][p]) for p in plain["grads"])
-
-
 SMALL_INCEPTIONS = (("a", 8, (8, 12), (4, 8), 4), "pool", ("b", 12, (8, 16), (4, 8), 8))
-
-
-def test_window_maxima_within_the_band_follow_the_given_tap():
-    """2x2 / stride-2 pooling of a hand-made 4x4 map: a tap 1e-6 below the maximum may be taken instead
-    (the gradient then goes there), one far below it, padding, or an index outside the window may not."""
-    x = np.array([[1.0, 1.0 - 1e-6, 5.0, 2.0],
-                  [0.5, 0.2, 4.0, 3.0],
-                  [7.0, 7.0, -1.0, -2.0],
-                  [6.0, 1.0, -3.0, -1.0 - 1e-7]]).reshape(1, 1, 4, 4)
-    best, idx = nm.maxpool_fwd(x, 2, 2, 0)
-    assert best.ravel().tolist() == [1.0, 5.0, 7.0, -1.0] and idx.ravel().tolist() == [0, 0, 0, 0]   # first maximum wins
-    given = np.array([1, 3, 1, 200], np.uint8).reshape(1, 1, 2, 2)       # near-tie, far below, exact tie, invalid
-    got, undecided = nm.resolve_argmax(x, idx, best, given, 1e-3, 2, 2, 0)
-    assert got.ravel().tolist() == [1, 0, 1, 0] and undecided.ravel().tolist() == [True, False, True, False]
-    dy = np.array([10.0, 20.0, 30.0, 40.0]).reshape(1, 1, 2, 2)
-    dx = nm.maxpool_bwd_from_index(dy, got, x.shape, 2, 2, 0)
-    want = np.zeros((4, 4)); want[0, 1] = 10; want[0, 2] = 20; want[2, 1] = 30; want[2, 2] = 40
-    assert np.array_equal(dx[0, 0], want)
-    # with padding: the given tap points into the padding ring and is refused
-    best, idx = nm.maxpool_fwd(x, 3, 2, 1)
-    given = np.zeros(idx.shape, np.uint8)                                  # tap (0,0): padding for the first row / column of windows
-    got, undecided = nm.resolve_argmax(x, idx, best, given, 1e-3, 3, 2, 1)
-    assert np.array_equal(got[0, 0, 0, :], idx[0, 0, 0, :]) and not undecided[0, 0, 0, :].any()
-    # the oracle's own indices as the given ones change nothing
-    got, undecided = nm.resolve_argmax(x, idx, best, idx, 1e-3, 3, 2, 1)
-    assert np.array_equal(got, idx) and not undecided.any()
-
-
-def test_tie_resolution_with_the_strict_window_maxima_changes_nothing():
-    """Handing the step its own max-pool indices must reproduce the plain step exactly.  Handing it the next tap
-    everywhere changes an index only where that tap ties with the maximum exactly (all-zero windows after a
-    ReLU; a stride-1 pool over a stride-2 pool sees the same element twice): the gradient then takes another
-    route to the same place, so the result agrees to rounding."""
-    from oracle import network as onet
-    from workloads import graphs, tensors
-    g = graphs.googlenet(batch=2, hw=32, classes=10, stem=(8, 8, 16), inceptions=SMALL_INCEPTIONS)
-    exts, params = tensors.make_inputs(g, seed=5, gamma_beta="random")
-    oe, op = tensors.oracle_inputs(exts, params)
-    plain = onet.store_everything_step(g.text(), oe, op)
-    own, shifted = {}, {}
-    for n in g.nodes:
-        if n.op == "maxpool":
-            idx = nm.maxpool_fwd(plain["acts"][n.ins[0]], n.attrs["k"], n.attrs["stride"], n.attrs["pad"])[1]
-            own[n.id] = idx
-            shifted[n.id] = ((idx + 1) % (n.attrs["k"] ** 2)).astype(np.uint8)
-    assert len(own) >= 5
-    tied = onet.store_everything_step(g.text(), oe, op, ties=(1e-9, own))
-    assert tied["loss"] == plain["loss"]
-    assert all(np.array_equal(tied["grads"][p], plain["grads"][p]) for p in plain["grads"])
-    assert all(np.array_equal(tied["decisions"][i][0], own[i]) and not tied["decisions"][i][1].any() for i in own)
-    tied = onet.store_everything_step(g.text(), oe, op, ties=(1e-9, shifted))
-    assert tied["loss"] == plain["loss"]
-    top = max(np.linalg.norm(v) for v in plain["grads"].values())
-    assert all(np.linalg.norm(tied["grads"][p] - plain["grads"][p]) < 1e-13 * top for p in plain["grads"])
-    for i in own:
-        changed = tied["decisions"][i][0] != own[i]
-        assert np.array_equal(changed, tied["decisions"][i][1]) and changed.mean() < 0.5
 
 
 @pytest.mark.parametrize("net", ["vgg", "unet", "mbv2", "googlenet"])
