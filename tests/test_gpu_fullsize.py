@@ -198,3 +198,95 @@ def test_sampled_stem_outputs_and_statistics(full):
     got = run.read(run.plan.bn_stats_offset(bn.id), (2 * K,))
     assert np.abs(got[:K] - mean).max() < 1e-5 * np.abs(mean).max() + 1e-6
     assert np.abs(got[K:] / invstd - 1).max() < 1e-5
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def test_sampled_outputs_of_headline_layers_in_their_launch_configuration():
+    """Three more layers of the batch-184 network, called through the kernel entry points with the workspace and
+    split count the graph declares for them (what the timed step launches): a Winograd F(4x4) layer worked through in
+    chunks (layer1's 3x3 at 56x56x64, forward and input gradient), a 1x1 layer whose ragged last round of tiles is cut
+    and met inside the kernel (layer3's 1024 -> 256 at 14x14, 564 tiles), and a filter gradient split over its
+    reduction (the same layer, 36 064 positions).  Sampled elements against the oracle's definition evaluated on the
+    crop (forward, input gradient) or the channel pair (filter gradient) that element depends on."""
+    import torch
+    from paper_2010_14501_amd import monet
+    N = 184
+    rng = np.random.default_rng(11)
+
+    def sample(shape, count):
+        corners = [tuple(0 for _ in shape), tuple(d - 1 for d in shape)]
+        return corners + [tuple(int(rng.integers(0, d)) for d in shape) for _ in range(count)]
+
+    # ---- Winograd F(4x4, 3x3), chunked workspace
+    H = W = 56
+    C = K = 64
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = rng.standard_normal((K, 3, 3, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (9 * C)))
+    need = monet.call("monet_conv_winograd_workspace_bytes", N, H, W, C, K, 4)
+    per_image = 36 * 14 * 14 * (C + K) * 4
+    assert (need - 36 * K * C * 4) // per_image < N            # several chunks, as in the timed step
+    ws = torch.empty(need // 4, dtype=torch.float32, device="cuda")
+    dx_, dw_ = _dev(x), _dev(w)
+    y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_winograd", None, dx_.data_ptr(), dw_.data_ptr(), y.data_ptr(), N, H, W, C, K, 4, 0, 0, ws.data_ptr(), need)
+    gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_winograd", None, dx_.data_ptr(), dw_.data_ptr(), gx.data_ptr(), N, H, W, C, K, 4, 1, 0, ws.data_ptr(), need)
+    torch.cuda.synchronize()
+    y, gx = y.cpu().numpy(), gx.cpu().numpy()
+    assert np.isfinite(y).all() and np.isfinite(gx).all()
+    wo = tensors.weight_to_oracle(w)
+    ys, gs = float(np.sqrt(np.mean(y.astype(np.float64) ** 2))), float(np.sqrt(np.mean(gx.astype(np.float64) ** 2)))
+    for n, p, q, k in sample((N, H, W, K), 300):
+        crop = np.zeros((1, C, 3, 3))
+        h0, h1, v0, v1 = max(p - 1, 0), min(p + 2, H), max(q - 1, 0), min(q + 2, W)
+        crop[0, :, h0 - p + 1:h1 - p + 1, v0 - q + 1:v1 - q + 1] = np.transpose(x[n, h0:h1, v0:v1, :], (2, 0, 1))
+        want = nm.conv2d_fwd(crop, wo[k:k + 1], 1, 0)[0, 0, 0, 0]
+        assert abs(y[n, p, q, k] - want) < 1e-4 * ys, ("winograd fwd", n, p, q, k)
+        # the input gradient of the same layer read as a convolution of x with the filter (here C == K): the centre of
+        # the definition's scatter over a 3x3 crop holds all nine contributions
+        c = k
+        want = nm.conv2d_dgrad(crop, wo, (1, K, 3, 3), 1, 1)[0, c, 1, 1]
+        assert abs(gx[n, p, q, c] - want) < 1e-3 * gs, ("winograd dgrad", n, p, q, c)
+    del ws, y, gx, dx_, dw_
+
+    # ---- 1x1, 1024 -> 256 at 14x14: tiles beyond two rounds of 256 are cut; and its filter gradient, split
+    H = W = 14
+    C, K = 1024, 256
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = rng.standard_normal((K, 1, 1, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / C))
+    dy = rng.standard_normal((N, H, W, K), dtype=np.float32)
+    splits, ws_bytes = graphs.conv_split_plan(N * H * W, K, C)
+    assert splits == 1 and ws_bytes > 0
+    assert ws_bytes <= monet.call("monet_conv_workspace_bytes", 0, N, H, W, C, K, 1, 1, 1, 0, 1)
+    ws = torch.full((ws_bytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    dx_, dw_, ddy = _dev(x), _dev(w), _dev(dy)
+    y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd", None, dx_.data_ptr(), dw_.data_ptr(), y.data_ptr(), N, H, W, C, K, 1, 1, 1, 0, 1, ws.data_ptr(), ws_bytes)
+    wsplits = graphs.wgrad_split_count(N * H * W, K, C)
+    assert wsplits > 1
+    wws = torch.full((wsplits * K * C,), float("nan"), dtype=torch.float32, device="cuda")
+    gw = torch.full((K, 1, 1, C), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_wgrad", None, dx_.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, C, K, 1, 1, 1, 0,
+               wsplits, wws.data_ptr(), wws.numel() * 4)
+    torch.cuda.synchronize()
+    y, gw = y.cpu().numpy(), gw.cpu().numpy()
+    assert np.isfinite(y).all() and np.isfinite(gw).all()
+    wo = tensors.weight_to_oracle(w)
+    ys = float(np.sqrt(np.mean(y.astype(np.float64) ** 2)))
+    rows = N * H * W
+    # the last rows belong to the cut tiles: sample them densely, and the rest at random
+    picks = sample((N, H, W, K), 300) + [(N - 1, int(rng.integers(0, H)), int(rng.integers(0, W)), int(rng.integers(0, K))) for _ in range(200)]
+    for n, p, q, k in picks:
+        want = nm.conv2d_fwd(np.transpose(x[n:n + 1, p:p + 1, q:q + 1, :], (0, 3, 1, 2)).astype(np.float64), wo[k:k + 1], 1, 0)[0, 0, 0, 0]
+        assert abs(y[n, p, q, k] - want) < 1e-4 * ys, ("cut 1x1 fwd", n, p, q, k)
+    gs = float(np.sqrt(np.mean(gw.astype(np.float64) ** 2)))
+    for k, _, _, c in sample((K, 1, 1, C), 150):
+        xc = x[:, :, :, c].astype(np.float64)[:, None]
+        dk = dy[:, :, :, k].astype(np.float64)[:, None]
+        want = nm.conv2d_wgrad(xc, dk, 1, 1, 1, 0)[0, 0, 0, 0]
+        assert abs(gw[k, 0, 0, c] - want) < 1e-3 * gs, ("split wgrad", k, c)
+    assert rows == 36064
