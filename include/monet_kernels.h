@@ -96,6 +96,14 @@ int monet_conv_wgrad(void *stream, const float *x, const float *dy, float *dw,
  * scratch: >= 4 MiB of device memory for slab partials. */
 int monet_bn_stats(void *stream, const float *x, float *stats, int64_t rows, int C, float eps,
                    float *scratch, size_t scratch_bytes);
+/* monet_bn_stats for callers that cannot allocate device memory or pass a scratch buffer (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the partial results live in a 4 MiB array inside the library,
+ * one copy per GPU, held until the process ends.  Allocates nothing.  `stats` is bit-identical to monet_bn_stats called
+ * with a 4 MiB scratch.  Limits: C a multiple of 4 and at most 8192, rows at most 2^31; beyond them the call returns an
+ * error and enqueues nothing.  All calls on one GPU share the array (it keeps the last call's contents; every value a
+ * call reads it has written itself, so nothing needs clearing): calls that overlap in time on one GPU, e.g. on two
+ * streams, race and must be serialised by the caller. */
+int monet_bn_stats_static(void *stream, const float *x, float *stats, int64_t rows, int C, float eps);
 /* y = gamma*(x-mean)*invstd + beta; y may alias x (in-place variant). */
 int monet_bn_apply(void *stream, const float *x, float *y, const float *gamma, const float *beta,
                    const float *stats, int64_t rows, int C);

@@ -973,6 +973,9 @@ extern "C" int monet_conv_wgrad(void *stream, const float *x, const float *dy, f
 extern "C" int monet_bn_stats(void *stream, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch, size_t scratch_bytes) {
     return guarded([&] { bn_stats((hipStream_t)stream, x, stats, rows, C, eps, scratch, scratch_bytes); });
 }
+extern "C" int monet_bn_stats_static(void *stream, const float *x, float *stats, int64_t rows, int C, float eps) {
+    return guarded([&] { bn_stats_static((hipStream_t)stream, x, stats, rows, C, eps); });
+}
 extern "C" int monet_bn_apply(void *stream, const float *x, float *y, const float *gamma, const float *beta, const float *stats,
                               int64_t rows, int C) {
     return guarded([&] { bn_apply((hipStream_t)stream, x, y, gamma, beta, stats, rows, C); });

@@ -10,6 +10,8 @@
 #include "kernels.hpp"
 #include "tile_stats.hpp"
 
+#include <mutex>
+
 namespace monet {
 
 namespace {
@@ -289,6 +291,43 @@ void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C,
     hipLaunchKernelGGL(bn_stats_partial, dim3(g.G, g.CB), dim3(256), 0, st, x, scratch, rows, C, g.TPR, g.slab);
     hipLaunchKernelGGL(bn_stats_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, stats, rows, C, g.G, g.slab, eps);
     hip_check(hipGetLastError(), "bn_stats launch");
+}
+
+// ------------------------------------------------------------------ statistics without caller scratch
+// For callers that cannot allocate device memory: the slab / row-group partial results go to a file-scope device
+// array instead of a scratch argument.  In host code the array's name is only a stand-in: its device address is looked
+// up once per device (each GPU holds its own copy) and only that address is handed to kernels.
+constexpr size_t kStaticScratchBytes = 4u << 20;
+static __device__ __align__(256) unsigned char static_scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex static_scratch_mutex;
+float *static_scratch_ptr[kMaxDevices] = {};
+
+float *static_scratch_on_current_device() {
+    int dev = -1;
+    hip_check(hipGetDevice(&dev), "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) throw KernelError("BatchNorm statistics: device index out of range");
+    std::lock_guard<std::mutex> lock(static_scratch_mutex);
+    if (!static_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        hip_check(hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch)), "hipGetSymbolAddress(static_scratch)");
+        if (!ptr) throw KernelError("BatchNorm statistics: no address for the static scratch");
+        static_scratch_ptr[dev] = (float *)ptr;
+    }
+    return static_scratch_ptr[dev];
+}
+}  // namespace
+
+void bn_stats_static(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps) {
+    if (rows <= 0) throw KernelError("BatchNorm: no rows");
+    if (C <= 0 || C % 4 || C > kBnStaticMaxC)
+        throw KernelError("BatchNorm statistics without scratch: C must be a multiple of 4, at most " + std::to_string(kBnStaticMaxC));
+    if (rows > kBnStaticMaxRows)
+        throw KernelError("BatchNorm statistics without scratch: at most " + std::to_string(kBnStaticMaxRows) + " rows");
+    // every partial result the merge kernels read is written by the first kernel of the same call: nothing to clear
+    bn_stats(st, x, stats, rows, C, eps, static_scratch_on_current_device(), kStaticScratchBytes);
 }
 
 // ------------------------------------------------------------------ apply: y = gamma*(x-mean)*invstd + beta.  y may alias x.

@@ -92,6 +92,11 @@ constexpr int64_t kBnScratchFloats = 1 << 20;
 // partial results in `scratch`; only the final merge runs.  Allowed only where bn_stats_in_row_groups() holds.
 void bn_stats(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps, float *scratch,
               size_t scratch_bytes, bool partials_ready = false);
+// The same with the partial results in a 4 MiB array inside the library (no scratch argument, no allocation); result
+// bit-identical to bn_stats() with a 4 MiB scratch.  Calls that overlap in time on one GPU share the array and race.
+constexpr int kBnStaticMaxC = 8192;
+constexpr int64_t kBnStaticMaxRows = (int64_t)1 << 31;
+void bn_stats_static(hipStream_t st, const float *x, float *stats, int64_t rows, int C, float eps);
 // true if the statistics of a rows x C tensor are built from groups of 64 rows (scratch: 2 floats per group and channel)
 bool bn_stats_in_row_groups(int64_t rows, int C, size_t scratch_bytes);
 void bn_apply(hipStream_t st, const float *x, float *y, const float *gamma, const float *beta, const float *stats,

@@ -94,6 +94,7 @@ def load_library():
     lib.monet_conv_dgrad.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [vp, sz]
     lib.monet_conv_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz]
     lib.monet_bn_stats.argtypes = [vp, vp, vp, i64, i32, f, vp, sz]
+    lib.monet_bn_stats_static.argtypes = [vp, vp, vp, i64, i32, f]
     lib.monet_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32]
     lib.monet_bn_bwd.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, i64, i32, i32, vp, sz]
     lib.monet_relu_fwd.argtypes = [vp, vp, vp, vp, i64, i32]
@@ -112,7 +113,7 @@ def load_library():
     lib.monet_column_copy.argtypes = [vp, vp, i64, vp, i64, i32, i64, i32]
     lib.monet_softmaxce_rows_fwd.argtypes = [vp, vp, vp, vp, i64, i32, vp, sz]
     lib.monet_softmaxce_rows_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32]
-    for name in ("monet_conv_fwd", "monet_conv_dgrad", "monet_conv_wgrad", "monet_bn_stats", "monet_bn_apply", "monet_bn_bwd",
+    for name in ("monet_conv_fwd", "monet_conv_dgrad", "monet_conv_wgrad", "monet_bn_stats", "monet_bn_stats_static", "monet_bn_apply", "monet_bn_bwd",
                  "monet_relu_fwd", "monet_relu_bwd", "monet_maxpool_fwd", "monet_maxpool_bwd", "monet_copy",
                  "monet_tconv_fwd", "monet_tconv_dgrad", "monet_tconv_wgrad", "monet_dwconv_fwd", "monet_dwconv_dgrad",
                  "monet_dwconv_wgrad", "monet_column_copy", "monet_softmaxce_rows_fwd", "monet_softmaxce_rows_bwd"):
