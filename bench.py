@@ -20,10 +20,15 @@ sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3      # 256 CUs x 256 flop/clk x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of a kernel class, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by what the
-# same counters read for a plain copy (profiles/step_resnet50_b184_hbm_traffic.txt); counters cannot be read
-# from inside this process, so the figure is the recorded one and null for anything not profiled.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("resnet50_b184", "conv_fwd"): 399.2e6}
+# HBM bytes per launch of a kernel class come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by what the same
+# counters read for a plain copy; counters cannot be read from inside this process, so the figure is the one recorded in
+# profiles/step_<workload>_hbm_traffic.txt (written by `python -m paper_2010_14501_amd.profsum traffic`), null if that
+# workload was not profiled.
+
+
+def recorded_traffic(workload, label):
+    from paper_2010_14501_amd import profsum
+    return profsum.read_traffic(os.path.join(ROOT, "profiles", f"step_{workload}_hbm_traffic.txt"), label)
 
 
 def _stored_schedule(path, batch):
@@ -212,10 +217,20 @@ def main():
         "loss": loss,
     }
 
+    # what the step launches, per class (static: from the plan's launch list)
+    info = run.plan.launches(issued=True)
+    static = {}
+    for (label, kind, _id, impl, flops, nbytes, issued) in info:
+        c = static.setdefault(label, {"launches": 0, "flops": 0.0, "bytes": 0.0, "issued": 0.0})
+        c["launches"] += 1
+        c["flops"] += flops
+        c["bytes"] += nbytes
+        c["issued"] += issued
+    out["launch_classes"] = static
+
     if not args.no_roofline:
         # second pass over the same steps with a pair of HIP events around every operator launch
         import numpy as np
-        info = run.plan.launches(issued=True)
         run.plan.set_timing(True)
         tot = np.zeros(len(info))
         n_timed = max(3, min(args.steps, 10))
@@ -224,31 +239,33 @@ def main():
             tot += run.plan.read_timing()
         run.plan.set_timing(False)
         tot /= n_timed                                   # ms per launch, averaged over steps
-        classes = {}
-        for (label, kind, _id, impl, flops, nbytes, issued), ms in zip(info, tot):
-            c = classes.setdefault(label, {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0, "issued": 0.0})
-            c["launches"] += 1
-            c["ms"] += float(ms)
-            c["flops"] += flops
-            c["bytes"] += nbytes
-            c["issued"] += issued
+        classes = {k: dict(v, ms=0.0) for k, v in static.items()}
+        for (label, *_), ms in zip(info, tot):
+            classes[label]["ms"] += float(ms)
         for c in classes.values():
             c["tflops"] = c["flops"] / (c["ms"] * 1e-3) / 1e12 if c["ms"] > 0 else 0.0
             c["issued_tflops"] = c["issued"] / (c["ms"] * 1e-3) / 1e12 if c["ms"] > 0 else 0.0
             c["gbs"] = c["bytes"] / (c["ms"] * 1e-3) / 1e9 if c["ms"] > 0 else 0.0
+
+        def mfma_entry(c):
+            # held against the peak: the flop the kernels put on the matrix cores (a Winograd form issues 1/4 to 1/2.25 of
+            # the direct form's); `algorithmic` is the direct form's flop per second, the figure the metric counts
+            return {"bound": "mfma", "achieved": c["issued_tflops"], "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": c["issued_tflops"] / MFMA_F32_PEAK_TFLOPS, "algorithmic": c["tflops"]}
+
         dom = max(classes, key=lambda k: classes[k]["ms"])
         d = classes[dom]
         if d["flops"] > 0:
-            # achieved: algorithmic flop (the direct form's) per second; issued: what the kernels put on the matrix cores
-            # in that time -- lower where Winograd layers cut the multiplications, and the figure to hold against the peak
-            roof = {"bound": "mfma", "achieved": d["tflops"], "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": d["tflops"] / MFMA_F32_PEAK_TFLOPS, "issued": d["issued_tflops"],
-                    "frac_issued": d["issued_tflops"] / MFMA_F32_PEAK_TFLOPS}
+            roof = mfma_entry(d)
         else:
             roof = {"bound": "hbm", "achieved": d["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["gbs"] / HBM_PEAK_GBS}
         roof.update({"kernel": dom, "launches_per_step": d["launches"], "avg_launch_ms": d["ms"] / d["launches"],
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, dom)),
+                     "traffic": recorded_traffic(args.workload, dom),
                      "algorithmic_bytes_per_launch": d["bytes"] / d["launches"]})
+        # every convolution class beside the dominant one (implicit GEMM and Winograd forms, all three modes)
+        roof["conv_classes"] = {k: dict(mfma_entry(v), ms=round(v["ms"], 3), launches=v["launches"],
+                                        traffic=recorded_traffic(args.workload, k))
+                                for k, v in classes.items() if k.startswith("conv_") and v["flops"] > 0}
         out["roofline"] = roof
         out["classes"] = {k: {"launches": v["launches"], "ms": round(v["ms"], 4), "tflops": round(v["tflops"], 2),
                               "issued_tflops": round(v["issued_tflops"], 2), "gbs": round(v["gbs"], 1)}

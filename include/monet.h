@@ -21,7 +21,12 @@
  *   - Functions returning int / int64_t return a negative monet_status on
  *     failure; monet_last_error() then holds a message naming the violated
  *     constraint or the failing call.  No C++ exception crosses this boundary.
- *   - A plan is not re-entrant: one monet_step at a time per plan.
+ *   - A plan is not re-entrant: one monet_step at a time per plan.  Beyond that, one step at a
+ *     time per process and GPU: convolution launches whose last round of tiles is cut count
+ *     their arrivals in one table inside the library, so two steps (of one plan or of two) that
+ *     overlap in time on different streams of one GPU would corrupt each other's results.
+ *     monet_step zeroes that table at its start, so a step that was broken off by an error
+ *     leaves nothing behind for the next one.
  *   - Activations are N,H,W,C fp32; convolution weights K,R,S,C; linear
  *     weights out,in; the ReLU sign code is one bit per element, bit (e & 63) of
  *     little-endian 64-bit word (e >> 6), e = N,H,W,C linear index, tail bits

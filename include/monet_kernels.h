@@ -38,6 +38,11 @@ extern "C" {
 int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
                    int N, int H, int W, int C, int K, int R, int S, int stride, int pad,
                    int splits, float *ws, size_t ws_bytes);
+/* Puts the arrival table of the cut tiles back to zero (one small kernel on `stream`).  The convolution kernels leave
+ * every entry at zero when they finish; a caller whose sequence of launches was broken off by an error (or by a reset of
+ * the stream) calls this before the next monet_conv_fwd / monet_conv_dgrad that passes a workspace with splits == 1.
+ * monet_step does it at the start of every step. */
+int monet_conv_reset_arrivals(void *stream);
 /* monet_conv_fwd followed by monet_bn_stats of its output, with the statistics' first level computed in the
  * convolution's epilogue instead of a pass over y (the largest of the fusions the executor applies between a
  * convolution and the BatchNorm behind it).  Needs C % 16 == 0 and K % 4 == 0; ws / ws_bytes as for monet_conv_fwd

@@ -648,6 +648,8 @@ extern "C" int64_t monet_step(monet_plan *p, void *hip_stream, const void *const
     int rc = guarded([&] {
         const Plan &pl = p->plan;
         StepCtx c{p, (hipStream_t)hip_stream, inputs, weights, grads};
+        // arrival counts of cut convolution tiles start at zero whatever an earlier, failed step left behind
+        conv_reset_arrivals(c.st);
         // arena accounting: replay the trace's alloc/free records against the launches
         int64_t live = 0;
         size_t next_event = 0, next_poison = 0;
@@ -909,6 +911,9 @@ static PoolShape mk_pool(int N, int H, int W, int C, int k, int stride, int pad)
 extern "C" int monet_conv_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
                               int stride, int pad, int splits, float *ws, size_t ws_bytes) {
     return guarded([&] { conv_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad), splits, ws, ws_bytes); });
+}
+extern "C" int monet_conv_reset_arrivals(void *stream) {
+    return guarded([&] { conv_reset_arrivals((hipStream_t)stream); });
 }
 extern "C" int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
                                        int stride, int pad, float *ws, size_t ws_bytes, float *stats, float eps, float *scratch,

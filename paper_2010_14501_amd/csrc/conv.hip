@@ -77,6 +77,9 @@ struct TileArgs {
 constexpr int MEET_SLOTS = 1 << 16;
 __device__ unsigned g_meet_arrivals[MEET_SLOTS];
 
+// puts every entry back to zero (a step that ended in an error may have left counts behind)
+__global__ __launch_bounds__(256) void meet_reset_kernel() { g_meet_arrivals[blockIdx.x * 256 + threadIdx.x] = 0; }
+
 __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
 // TAG only names the use in profiles: 0 a convolution, 1 / 2 / 3 the batched GEMMs of a Winograd forward / input gradient /
@@ -879,6 +882,11 @@ SplitGemm split_gemm_of(int which, const ConvShape &cs) {
             ((int64_t)std::max(1, cs.R / st) * std::max(1, cs.S / st) * cs.K + BK - 1) / BK, st * st};
 }
 }  // namespace
+
+void conv_reset_arrivals(hipStream_t st) {
+    hipLaunchKernelGGL(meet_reset_kernel, dim3(MEET_SLOTS / 256), dim3(256), 0, st);
+    hip_check(hipGetLastError(), "arrival table reset launch");
+}
 
 size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
     check_shape(cs);

@@ -84,6 +84,9 @@ void conv_force_tile(int cfg);
 // workspace bytes of conv_fwd (which = 0) / conv_dgrad (which = 1) for `splits` ranges; for splits = 1 the bytes
 // with which the ragged last round of tiles is cut as far as it pays (0 if there is nothing to gain)
 size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits);
+// Zeroes the table in which the cut tiles of forward / input-gradient launches count their arrivals.  The kernels put
+// every entry back themselves; this is for a stream on which an earlier sequence of launches ended in an error.
+void conv_reset_arrivals(hipStream_t st);
 
 // ---- BatchNorm over rows x C (rows = N*H*W), training mode, biased variance
 constexpr int64_t kBnScratchFloats = 1 << 20;

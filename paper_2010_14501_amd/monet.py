@@ -93,6 +93,8 @@ def load_library():
     lib.monet_conv_workspace_bytes.restype = i64
     lib.monet_conv_dgrad.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [vp, sz]
     lib.monet_conv_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz]
+    lib.monet_conv_reset_arrivals.argtypes = [vp]
+    lib.monet_conv_reset_arrivals.restype = i32
     lib.monet_bn_stats.argtypes = [vp, vp, vp, i64, i32, f, vp, sz]
     lib.monet_bn_stats_static.argtypes = [vp, vp, vp, i64, i32, f]
     lib.monet_bn_apply.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32]

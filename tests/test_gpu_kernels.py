@@ -106,7 +106,13 @@ def test_conv_ragged_last_round_is_split_and_counts_reset():
     want_dx = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, stride, pad))
     y0 = torch.empty((N, H, W, K), dtype=torch.float32, device="cuda")
     monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y0.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, None, 0)
+    # a refused call (workspace announced smaller than two partial results) enqueues nothing and leaves the table alone;
+    # an explicit reset of the table between good calls changes nothing either
+    with pytest.raises(monet.MonetError):
+        monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y0.data_ptr(), N, H, W, C, K, R, R, stride, pad, 2, ws.data_ptr(), 1024)
     for rep in range(3):
+        if rep == 1:
+            monet.call("monet_conv_reset_arrivals", None)
         y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, ws.data_ptr(), need[0])
         check_close(y.cpu().numpy(), want_y, ACT_TOL, what=rep)
