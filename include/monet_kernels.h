@@ -57,7 +57,8 @@ int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float 
  * forward operator; Appendix D: in-place operators).  `stats` = mean[K] then 1/sqrt(var+eps)[K] as monet_bn_stats
  * leaves them, `gamma`, `beta` [K].  winograd_m = 0: implicit GEMM (needs C % 16 == 0, K % 4 == 0; ws / ws_bytes as for
  * monet_conv_fwd with splits == 1); winograd_m = 2 or 4: the Winograd form below (3x3 / stride 1 / pad 1 only, its
- * workspace).  y is bit-identical to the two separate calls. */
+ * workspace); winograd_m = 5: the one-kernel F(4x4) form (monet_conv_winograd_fused, its workspace).  y is bit-identical
+ * to the two separate calls. */
 int monet_conv_fwd_bn_apply(void *stream, const float *x, const float *w, float *y,
                             int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int winograd_m,
                             float *ws, size_t ws_bytes, const float *gamma, const float *beta, const float *stats);
@@ -75,6 +76,16 @@ int monet_conv_fwd_bn_apply(void *stream, const float *x, const float *w, float 
 int monet_conv_winograd(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
                         int m, int adjoint, int accumulate, float *ws, size_t ws_bytes);
 int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K, int m);
+/* The same convolution (m = 4) in one kernel: input transform, the 36 products and the output transform without the
+ * transformed tensors ever reaching memory -- the small-workspace end of Appendix D's trade-off.  Workspace: the
+ * transformed filters only, 36 * round_up(out channels, 64) * reduction channels floats
+ * (monet_conv_winograd_fused_workspace_bytes; out = K, reduction = C for the forward pass, exchanged for adjoint != 0).
+ * Needs reduction channels % 8 == 0.  Reads the input once per 64 output channels, so it is the faster form for layers
+ * with few channels on large maps and the slower one for many channels.  Same arithmetic as monet_conv_winograd with
+ * m = 4 (results agree to rounding; the sums over channels run in the same order). */
+int monet_conv_winograd_fused(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
+                              int adjoint, int accumulate, float *ws, size_t ws_bytes);
+int64_t monet_conv_winograd_fused_workspace_bytes(int N, int H, int W, int C, int K, int adjoint);
 /* Filter gradient of such a layer in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
  * (C % 4 == 0, K % 4 == 0).  Workspace: the transformed input and output gradient of one chunk of images (as above),
  * two buffers of P*K*C floats (the transformed filter gradient and one chunk's share of it, added chunk after chunk)

@@ -932,7 +932,8 @@ extern "C" int monet_conv_fwd_bn_apply(void *stream, const float *x, const float
     return guarded([&] {
         const ConvShape cs = mk_conv(N, H, W, C, K, R, S, stride, pad);
         const BnAffine affine{gamma, beta, stats};
-        if (winograd_m) conv_winograd((hipStream_t)stream, x, w, y, cs, winograd_m, false, false, ws, ws_bytes, &affine);
+        if (winograd_m == 5) conv_winograd_fused((hipStream_t)stream, x, w, y, cs, false, false, ws, ws_bytes, &affine);
+        else if (winograd_m) conv_winograd((hipStream_t)stream, x, w, y, cs, winograd_m, false, false, ws, ws_bytes, &affine);
         else conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, nullptr, &affine);
     });
 }
@@ -941,6 +942,17 @@ extern "C" int monet_conv_winograd(void *stream, const float *in, const float *w
     return guarded([&] {
         conv_winograd((hipStream_t)stream, in, w, out, mk_conv(N, H, W, C, K, 3, 3, 1, 1), m, adjoint != 0, accumulate != 0, ws, ws_bytes);
     });
+}
+extern "C" int monet_conv_winograd_fused(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
+                                         int adjoint, int accumulate, float *ws, size_t ws_bytes) {
+    return guarded([&] {
+        conv_winograd_fused((hipStream_t)stream, in, w, out, mk_conv(N, H, W, C, K, 3, 3, 1, 1), adjoint != 0, accumulate != 0, ws, ws_bytes);
+    });
+}
+extern "C" int64_t monet_conv_winograd_fused_workspace_bytes(int N, int H, int W, int C, int K, int adjoint) {
+    int64_t bytes = -1;
+    int rc = guarded([&] { bytes = (int64_t)winograd_fused_workspace_bytes(mk_conv(N, H, W, C, K, 3, 3, 1, 1), adjoint != 0); });
+    return rc == MONET_OK ? bytes : (int64_t)rc;
 }
 extern "C" int monet_conv_winograd_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K,
                                          int m, float *ws, size_t ws_bytes) {

@@ -57,6 +57,12 @@ void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, in
                   bool adjoint_use = false);
 void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t red, int m, int n, int splits,
                      float *ws, size_t ws_bytes);
+// Winograd F(4x4, 3x3) in one kernel (transformed input and products stay on chip): workspace = the transformed filters
+// only, 36 * round_up(out channels, 64) * reduction channels floats.  Needs reduction channels % 8 == 0.
+bool winograd_fused_applies(const ConvShape &cs, bool adjoint);
+size_t winograd_fused_workspace_bytes(const ConvShape &cs, bool adjoint);
+void conv_winograd_fused(hipStream_t st, const float *in, const float *w, float *out, const ConvShape &cs, bool adjoint, bool accumulate,
+                         float *ws, size_t ws_bytes, const BnAffine *affine = nullptr);
 // Winograd F(m x m, 3x3), m = 2 or 4, for 3x3 / stride 1 / pad 1 layers.  adjoint = false: out = y[N,H,W,K] from in = x[N,H,W,C]
 // (C % 16 == 0, K % 4 == 0); adjoint = true: out = dx[N,H,W,C] from in = dy[N,H,W,K] (K % 16 == 0, C % 4 == 0).  Workspace:
 // (m+2)^2 transformed filters and (m+2)^2 / m^2 times the input and the output of one chunk of whole images; the layer

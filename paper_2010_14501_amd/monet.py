@@ -84,6 +84,10 @@ def load_library():
     lib.monet_conv_fwd_bn_apply.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz, vp, vp, vp]
     lib.monet_conv_fwd_bn_apply.restype = i32
     lib.monet_conv_winograd.argtypes = [vp, vp, vp, vp] + [i32] * 8 + [vp, sz]
+    lib.monet_conv_winograd_fused.argtypes = [vp, vp, vp, vp] + [i32] * 7 + [vp, sz]
+    lib.monet_conv_winograd_fused.restype = i32
+    lib.monet_conv_winograd_fused_workspace_bytes.argtypes = [i32] * 6
+    lib.monet_conv_winograd_fused_workspace_bytes.restype = i64
     lib.monet_conv_winograd_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 6 + [vp, sz]
     lib.monet_conv_winograd_wgrad_workspace_bytes.argtypes = [i32] * 6
     lib.monet_conv_winograd_wgrad_workspace_bytes.restype = i64

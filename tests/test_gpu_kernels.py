@@ -281,6 +281,64 @@ def test_winograd_convolution_matches_oracle(case, m):
         check_close(gw.cpu().numpy(), want_w, GRAD_TOL)
 
 
+@pytest.mark.parametrize("case", [
+    (2, 14, 14, 64, 128),       # two blocks of 64 output channels; the last tile row / column is half outside the map
+    (3, 7, 9, 32, 48),          # odd sizes, output channels no multiple of 32, fewer tiles than a workgroup takes
+    (1, 5, 5, 8, 4),            # smallest channel counts
+    (2, 7, 7, 512, 512),        # deep reduction (64 chunks), eight channel blocks
+    (3, 56, 56, 64, 64),        # many tiles: 588 per channel block, ragged last workgroup (588 = 18 * 32 + 12)
+    (1, 3, 2, 16, 16),          # a map smaller than one 4x4 tile
+    (2, 12, 20, 24, 40),        # reduction channels a multiple of 8 only, 40 output channels (second half mostly padding)
+])
+def test_fused_winograd_convolution_matches_oracle(case):
+    """F(4x4, 3x3) in one kernel (no transformed tensors in memory): forward, input gradient written and accumulated,
+    and the forward form with a BatchNorm apply step, against the oracle's direct definitions."""
+    torch = torch_mod()
+    N, H, W, C, K = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, 3, 3, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (9 * C))))
+    dy = rng.standard_normal((N, H, W, K), dtype=np.float32)
+    xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
+    dx, dwt, ddy = dev(x), dev(w), dev(dy)
+    need = monet.call("monet_conv_winograd_fused_workspace_bytes", N, H, W, C, K, 0)
+    assert need == 36 * 4 * ((K + 63) // 64 * 64) * C
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    y = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_winograd_fused", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need)
+    want_y = nm.conv2d_fwd(xo, wo, 1, 1)
+    check_close(y.cpu().numpy(), wt.act_from_oracle(want_y), ACT_TOL)
+    with pytest.raises(monet.MonetError):
+        monet.call("monet_conv_winograd_fused", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, 0, 0, ws.data_ptr(), need - 4)
+    # BatchNorm apply step in the epilogue: the bits of the stand-alone apply kernel on the stored output
+    gamma = rng.uniform(0.5, 1.5, K).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    stats = np.concatenate([0.1 * rng.standard_normal(K), rng.uniform(0.5, 2.0, K)]).astype(np.float32)
+    dg_, db_, dst = dev(gamma), dev(beta), dev(stats)
+    fused = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), fused.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
+               ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr())
+    if K % 4 == 0:
+        monet.call("monet_bn_apply", None, y.data_ptr(), y.data_ptr(), dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), N * H * W, K)
+        assert torch.equal(fused, y)
+    want = nm.bn_apply(want_y, gamma.astype(np.float64), beta.astype(np.float64), stats[:K].astype(np.float64), stats[K:].astype(np.float64))
+    check_close(fused.cpu().numpy(), wt.act_from_oracle(want), ACT_TOL)
+    # input gradient: reduction over K, which must be a multiple of 8
+    if K % 8 == 0:
+        need = monet.call("monet_conv_winograd_fused_workspace_bytes", N, H, W, C, K, 1)
+        assert need == 36 * 4 * ((C + 63) // 64 * 64) * K
+        ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
+        want = wt.act_from_oracle(nm.conv2d_dgrad(dyo, wo, xo.shape, 1, 1))
+        monet.call("monet_conv_winograd_fused", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, 1, 0, ws.data_ptr(), need)
+        check_close(gx.cpu().numpy(), want, GRAD_TOL)
+        monet.call("monet_conv_winograd_fused", None, ddy.data_ptr(), dwt.data_ptr(), gx.data_ptr(), N, H, W, C, K, 1, 1, ws.data_ptr(), need)
+        check_close(gx.cpu().numpy(), 2 * want, GRAD_TOL)
+    else:
+        with pytest.raises(monet.MonetError):
+            monet.call("monet_conv_winograd_fused", None, ddy.data_ptr(), dwt.data_ptr(), dx.data_ptr(), N, H, W, C, K, 1, 0, ws.data_ptr(), need)
+
+
 def test_conv_wgrad_rejects_small_workspace():
     torch = torch_mod()
     t = torch.zeros(16 * 16 * 16 * 2, device="cuda")
