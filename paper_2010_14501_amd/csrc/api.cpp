@@ -213,7 +213,9 @@ int64_t numel_of(const std::vector<int64_t> &s) {
 
 // number of reduction splits an implementation record asks for ("splitk" / "igemm_splitk" carry splits=S)
 // output tile edge of a Winograd implementation name, 0 for any other
-int winograd_tile(const std::string &algo) { return algo == "winograd" ? 2 : algo == "winograd4" ? 4 : 0; }
+int winograd_tile(const std::string &algo) { return algo == "winograd" ? 2 : (algo == "winograd4" || algo == "winograd4f") ? 4 : 0; }
+// the one-kernel F(4x4) form (workspace: transformed filters only)
+bool winograd_is_fused(const std::string &algo) { return algo == "winograd4f"; }
 
 int splits_of(const std::string &algo, const Attrs &extra) {
     if (algo.find("splitk") == std::string::npos) return 1;
@@ -230,7 +232,10 @@ void run_forward(const StepCtx &c, const Launch &L, const BnAffine *affine = nul
     const std::string &op = n.op;
     if (op == "conv") {
         const FwdImpl &im = n.fimpls[L.impl];
-        if (const int m = winograd_tile(im.algo))
+        if (winograd_is_fused(im.algo))
+            conv_winograd_fused(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), false, false, (float *)c.ptr(L.a[4]),
+                                (size_t)align_up(im.ws), affine);
+        else if (const int m = winograd_tile(im.algo))
             conv_winograd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), m, false, false, (float *)c.ptr(L.a[4]),
                           (size_t)align_up(im.ws), affine);
         else
@@ -301,7 +306,9 @@ void run_backward(const StepCtx &c, const Launch &L) {
             conv_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), splits_of(im.algo, im.extra),
                        (float *)c.ptr(L.a[4]), (size_t)(im.ws > 0 ? align_up(im.ws) : 0));
     } else if (kd == "conv_dgrad") {
-        if (const int m = winograd_tile(im.algo))
+        if (winograd_is_fused(im.algo))
+            conv_winograd_fused(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), true, acc0, (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
+        else if (const int m = winograd_tile(im.algo))
             conv_winograd(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), m, true, acc0, (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
         else
             conv_dgrad(c.st, gy, c.weights[n.pars[0]], d0, conv_shape(g, n), acc0, splits_of(im.algo, im.extra), (float *)c.ptr(L.a[4]),
@@ -510,6 +517,7 @@ bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
     const ConvShape cs = conv_shape(g, cv);
     if (cv.op == "dwconv") return dwconv_fwd_takes_affine(cs);
     const FwdImpl &im = cv.fimpls[L1.impl];
+    if (winograd_is_fused(im.algo)) return winograd_fused_applies(cs, false);
     if (winograd_tile(im.algo)) return winograd_applies(cs, false);
     return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
 }

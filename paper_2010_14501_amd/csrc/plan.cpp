@@ -255,7 +255,7 @@ static void check_declared_deps(const Graph &g) {
                 want.push_back(n.aux_children[0]);
             };
             if (b.kind == "conv_wgrad") { known = (algo == "direct" || algo == "splitk" || algo == "winograd" || algo == "winograd4"); input0(); }
-            else if (b.kind == "conv_dgrad") { known = (algo == "igemm" || algo == "igemm_splitk" || algo == "winograd" || algo == "winograd4"); }
+            else if (b.kind == "conv_dgrad") { known = (algo == "igemm" || algo == "igemm_splitk" || algo == "winograd" || algo == "winograd4" || algo == "winograd4f"); }
             else if (b.kind == "tconv_wgrad") { known = (algo == "direct" || algo == "splitk"); input0(); }
             else if (b.kind == "tconv_dgrad") { known = algo == "igemm"; }
             else if (b.kind == "dwconv_wgrad") { known = algo == "direct"; input0(); }

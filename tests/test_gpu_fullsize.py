@@ -67,8 +67,17 @@ def test_integer_program_schedule_at_full_size(full):
     assert other.step() == other.plan.exact_peak <= other.plan.predicted_peak <= 0.31 * store
     assert abs(other.loss_value() - loss) < 1e-4 * abs(loss)
     got = other.grads_numpy()
-    for p in grads:
-        a, b = got[p].astype(np.float64), grads[p].astype(np.float64)
+    del other
+    # Reference: the block-output run with the convolution implementations the stored schedule was priced with (Winograd
+    # through the workspace).  Two runs whose convolutions round differently take a few of the 1.7 billion ReLU sign
+    # decisions of this batch differently, which moves single gradient tensors by percent (measured 4e-2 between any two
+    # implementation sets), so only runs with matching implementations on the 3x3 layers compare at the gradient tolerance.
+    ref = StepRunner(g.text(), schedules.block_output_schedule(g, schedules.WINOGRAD_WS_VARIANTS).text(), exts, params)
+    ref.step()
+    want = ref.grads_numpy()
+    assert abs(ref.loss_value() - loss) < 1e-4 * abs(loss)
+    for p in want:
+        a, b = got[p].astype(np.float64), want[p].astype(np.float64)
         assert np.linalg.norm(a - b) <= 1e-3 * np.linalg.norm(b), p
 
 
@@ -152,8 +161,13 @@ def test_other_configurations_at_full_size(name):
         assert run.step() == run.plan.exact_peak <= run.plan.predicted_peak <= 0.45 * store
         assert abs(run.loss_value() - la) < 1e-4 * abs(la)
         got = run.grads_numpy()
-        for p in ga:
-            a, b = got[p].astype(np.float64), ga[p].astype(np.float64)
+        del run
+        # reference with the convolution implementations the stored schedule was priced with (see the ResNet-50 test above)
+        ref = StepRunner(g.text(), named(g, schedules.WINOGRAD_WS_VARIANTS).text(), exts, params)
+        ref.step()
+        want = ref.grads_numpy()
+        for p in want:
+            a, b = got[p].astype(np.float64), want[p].astype(np.float64)
             assert np.linalg.norm(a - b) <= 1e-3 * np.linalg.norm(b), p
 
 

@@ -79,10 +79,12 @@ def test_small_resnet_program_beats_the_block_heuristic():
 
 
 def test_program_trades_convolution_workspace_for_time():
-    """Two 3x3 layers with 128 channels offer four forward / input-gradient implementations (plain, reduction split,
-    Winograd with 2x2 and with 4x4 output tiles) of growing workspace and falling cost.  With memory to spare the program
-    takes the cheapest Winograd form everywhere; as the budget shrinks it falls back to the smaller Winograd form, to the
-    split form, then to the workspace-free one (Appendix D's trade-off), and the objective never improves."""
+    """Two 3x3 layers with 128 channels offer five forward / input-gradient implementations (plain, reduction split,
+    Winograd with 2x2 output tiles, with 4x4 tiles through a workspace and with 4x4 tiles in one kernel) of differing
+    workspace and cost.  With memory to spare the program takes the cheapest form everywhere (the one-kernel Winograd,
+    which also needs less workspace than the other 4x4 form and so dominates it); as the budget shrinks it falls back to
+    the smaller 2x2 form, to the split form, then to the workspace-free one (Appendix D's trade-off), and the objective
+    never improves."""
     g = graphs.tiny_chain(batch=2, hw=8, channels=128, blocks=2)
     gt = g.text()
     store = M.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
@@ -96,7 +98,7 @@ def test_program_trades_convolution_workspace_for_time():
         algos += [g.bimpls[b["k"]][sch.stage_impl[b["k"]]]["algo"] for b in g.bops if b["kind"] == "conv_dgrad"]
         seen.append(algos)
         costs.append(obj)
-    assert all(a == "winograd4" for a in seen[0])
+    assert all(a == "winograd4f" for a in seen[0])
     assert all(a == "winograd" for a in seen[1])
     assert all(a == "igemm_splitk" for a in seen[2])
     assert all(a == "igemm" for a in seen[3])

@@ -128,6 +128,13 @@ class Graph:
         # loses at 64.
         wino4 = eligible and min(C, K) >= 64
         wino4_wgrad = wino4 and min(C, K) >= 96
+        # F(4x4, 3x3) in one kernel: the transformed input and the products stay on chip, the workspace holds the 36
+        # transformed filters only (output channels padded to 64).  It reads the input once per 64 output channels and
+        # streams the filters from L2 per 32 tiles, so it wins where maps are large or channels few (measured against the
+        # workspace form, forward: x1.9 at 64 channels on 224x224 and 416x608, x1.3-1.5 at 128, x1.1 at 256 on 56x56,
+        # level at 28x28x128) and loses on small maps with many channels (x0.8 at 14x14x256 and 7x7x512).  The library
+        # addresses the input with 32-bit byte offsets: tensors of 4 GiB and more keep the workspace form.
+        wino4f = wino4 and 4 * N * H * W * max(C, K) < (1 << 32) and not (H * W <= 14 * 14 and min(C, K) >= 160)
 
         # Workspace of the Winograd forms (mirrors the library): the transformed filters, plus the transformed input and
         # the products of one chunk of whole images -- the library works through a layer in chunks of about half a GiB
@@ -153,6 +160,8 @@ class Graph:
             self.fimpls[i].append(dict(algo="winograd", ws=wino_ws(2), cost=flop * 0.6))
         if wino4:
             self.fimpls[i].append(dict(algo="winograd4", ws=wino_ws(4), cost=flop * 0.4))
+        if wino4f:
+            self.fimpls[i].append(dict(algo="winograd4f", ws=_align(4 * 36 * (-(-K // 64) * 64) * C), cost=flop * 0.3))
         dg = [dict(algo="igemm", deps=[], ws=0, cost=flop)]
         if wino:
             dg.append(dict(algo="winograd", deps=[], ws=wino_ws(2), cost=flop * 0.6))
@@ -162,6 +171,8 @@ class Graph:
                                  max(1, R // stride) * max(1, S // stride) * K, stride * stride, N * H * W * C)
         if ws:
             dg.append(dict(algo="igemm_splitk", deps=[], ws=ws, cost=flop * 0.8, splits=sp))
+        if wino4f:      # appended last: implementation indices of schedules written before this form existed stay valid
+            dg.append(dict(algo="winograd4f", deps=[], ws=_align(4 * 36 * (-(-C // 64) * 64) * K), cost=flop * 0.3))
         wbytes = 4 * K * R * S * C
         wg = [dict(algo="direct", ws=0, cost=flop * 4.0)]
         for sp in wgrad_splits:

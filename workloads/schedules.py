@@ -30,18 +30,20 @@ from .graphs import Graph
 # offers the workspace-hungry convolution variants only where they were measured to pay).
 DEFAULT_VARIANTS = dict(
     bn_bwd="from_output", relu_bwd="from_mask", relu6_bwd="from_mask", maxpool_bwd="from_index",
-    conv_wgrad=("winograd4", "winograd", "splitk"), tconv_wgrad="splitk", conv_dgrad=("winograd4", "winograd", "igemm_splitk"),
-    conv_fwd=("winograd4", "winograd", "igemm_splitk"), inplace=True,
+    conv_wgrad=("winograd4", "winograd", "splitk"), tconv_wgrad="splitk", conv_dgrad=("winograd4f", "winograd4", "winograd", "igemm_splitk"),
+    conv_fwd=("winograd4f", "winograd4", "winograd", "igemm_splitk"), inplace=True,
 )
 # the same without the Winograd form: every convolution on the implicit GEMM
 IGEMM_VARIANTS = dict(DEFAULT_VARIANTS, conv_wgrad="splitk", conv_dgrad="igemm_splitk", conv_fwd="igemm_splitk")
+# Winograd through the workspace only (transformed tensors in memory), as before the one-kernel form existed
+WINOGRAD_WS_VARIANTS = dict(DEFAULT_VARIANTS, conv_dgrad=("winograd4", "winograd", "igemm_splitk"), conv_fwd=("winograd4", "winograd", "igemm_splitk"))
 # Winograd with 2x2 output tiles where it is offered (the 4x4 form is faster and smaller wherever both are)
 WINOGRAD2_VARIANTS = dict(DEFAULT_VARIANTS, conv_wgrad=("winograd", "splitk"), conv_dgrad=("winograd", "igemm_splitk"),
                           conv_fwd=("winograd", "igemm_splitk"))
 STANDARD_VARIANTS = dict(
     bn_bwd="from_input", relu_bwd="from_output", relu6_bwd="from_output", maxpool_bwd="from_input",
-    conv_wgrad=("winograd4", "winograd", "splitk"), tconv_wgrad="splitk", conv_dgrad=("winograd4", "winograd", "igemm_splitk"),
-    conv_fwd=("winograd4", "winograd", "igemm_splitk"), inplace=False,
+    conv_wgrad=("winograd4", "winograd", "splitk"), tconv_wgrad="splitk", conv_dgrad=("winograd4f", "winograd4", "winograd", "igemm_splitk"),
+    conv_fwd=("winograd4f", "winograd4", "winograd", "igemm_splitk"), inplace=False,
 )
 
 
