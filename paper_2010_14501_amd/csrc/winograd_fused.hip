@@ -31,6 +31,24 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned u4 __attribute__((ext_vector_type(4)));
+
+// Memory is addressed through buffer instructions: address = base (a resource descriptor in scalar registers) + a 32-bit
+// per-lane byte offset + a 32-bit scalar byte offset, so that the part of an address that is the same for every lane costs
+// no vector instruction.  The descriptors span the whole 32-bit offset range (every access made through them is in bounds
+// by construction; the hardware's range check is not relied upon); word 3 is the plain 32-bit data format of this family.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, -1, 0x00020000);
+}
+__device__ __forceinline__ float buffer_load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ f4 buffer_load4(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
+    return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ void buffer_store(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 0);
+}
 
 constexpr int FT = 32;            // tiles per workgroup
 constexpr int FK = 64;            // output channels per workgroup
@@ -40,14 +58,19 @@ constexpr int MROW = 33;          // row of M[z][tile][.] in LDS
 constexpr int LDS_FLOATS = 36 * FT * MROW;               // 152 064 bytes; the two V buffers take the first 82 944
 static_assert(2 * 36 * FT * VROW <= LDS_FLOATS, "V buffers must fit");
 
-// the one-dimensional maps of F(4, 3) (the same arithmetic as the workspace form)
+// The one-dimensional maps of F(4, 3).  On this chip fp32 matrix instructions and ordinary vector arithmetic exclude each
+// other on a SIMD (measured: every vector instruction costs the matrix pipe about 4.7 cycles, whichever wave issues it),
+// so the transforms are written for the fewest instructions: B^T in twelve multiply-adds
+//   B^T = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0; 0 2 -1 -2 1 0; 0 4 0 -5 0 1]
 __device__ inline void f4_bt(float v0, float v1, float v2, float v3, float v4, float v5, float (&o)[6]) {
-    o[0] = 4.0f * v0 - 5.0f * v2 + v4;
-    o[1] = (v3 + v4) - 4.0f * (v1 + v2);
-    o[2] = 4.0f * (v1 - v2) + (v4 - v3);
-    o[3] = 2.0f * (v3 - v1) + (v4 - v2);
-    o[4] = 2.0f * (v1 - v3) + (v4 - v2);
-    o[5] = 4.0f * v1 - 5.0f * v3 + v5;
+    const float p = __builtin_fmaf(-4.0f, v2, v4), q = __builtin_fmaf(-4.0f, v1, v3);
+    const float r = v4 - v2, t = v3 - v1;
+    o[0] = __builtin_fmaf(4.0f, v0, __builtin_fmaf(-5.0f, v2, v4));
+    o[1] = p + q;
+    o[2] = p - q;
+    o[3] = __builtin_fmaf(2.0f, t, r);
+    o[4] = __builtin_fmaf(-2.0f, t, r);
+    o[5] = __builtin_fmaf(4.0f, v1, __builtin_fmaf(-5.0f, v3, v5));
 }
 __device__ inline void f4_g(float g0, float g1, float g2, float (&o)[6]) {
     o[0] = 0.25f * g0;
@@ -57,12 +80,13 @@ __device__ inline void f4_g(float g0, float g1, float g2, float (&o)[6]) {
     o[4] = (1.0f / 24.0f) * g0 - (1.0f / 12.0f) * g1 + (1.0f / 6.0f) * g2;
     o[5] = g2;
 }
+//   A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]
 __device__ inline void f4_at(float m0, float m1, float m2, float m3, float m4, float m5, float (&o)[4]) {
     const float p = m1 + m2, q = m1 - m2, r = m3 + m4, t = m3 - m4;
     o[0] = m0 + p + r;
-    o[1] = q + 2.0f * t;
-    o[2] = p + 4.0f * r;
-    o[3] = q + 8.0f * t + m5;
+    o[1] = __builtin_fmaf(2.0f, t, q);
+    o[2] = __builtin_fmaf(4.0f, r, p);
+    o[3] = __builtin_fmaf(8.0f, t, q) + m5;
 }
 
 // Transformed filters in the order the matrix-core lanes read them:
@@ -108,55 +132,86 @@ struct FusedGeom {
     int64_t items;      // ceil(T / 32) * kblocks
 };
 
-// The reduction loop of one wave: NZ positions z0 .. z0 + NZ - 1 of the 32 x 64 tile; PATCH: this wave also loads and
-// transforms the input patches (one (tile, channel) per lane and chunk).
-template <int NZ, bool PATCH>
-__device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const float *__restrict__ Up, float *lds, const FusedGeom &gm, int kb,
-                                             int64_t tb, int z0, int ptid, int lane, floatx16 (&acc)[5][2]) {
-    const int l32 = lane & 31, g = lane >> 5;
-    const int H = gm.H, W = gm.W, red = gm.red, nch = gm.nch;
-    // ---- the (tile, channel) whose patch this lane transforms
-    // Patch element (a, b) of chunk ch sits at byte x + coff[b] + roff[a] + 32 * ch: coff / roff are the lane's own 32-bit
-    // byte offsets of (image, row 0, column 4 * tj + b - 1, pc) and of row 4 * ti + a - 1, with row and column clamped into
-    // the map, so that every load is in bounds; what lies outside the map is then replaced by zero (a wave whose 8 tiles
-    // are all interior skips that).  The host checks that the tensor has fewer than 2^32 bytes.
-    const int pc = ptid & 7, pt = ptid >> 3;
-    unsigned rowok = 0, colok = 0;
-    unsigned coff[6] = {0, 0, 0, 0, 0, 0}, roff[6] = {0, 0, 0, 0, 0, 0};
-    if (PATCH) {
-        const int64_t t = tb * FT + pt;
-        if (t < gm.T) {
-            const int tj = (int)(t % gm.tw);
-            const int64_t r = t / gm.tw;
-            const int ti = (int)(r % gm.th), n = (int)(r / gm.th);
-            const int h0 = 4 * ti - 1, w0 = 4 * tj - 1;
-            const int64_t e = ((int64_t)n * H * W) * red + pc;
+// What a patch lane knows about its (tile, channel): byte offsets of the six patch columns / rows (clamped into the map) and
+// which of them exist.  Patch element (a, b) of chunk ch sits at byte x + coff[b] + roff[a] + 32 * ch; the host checks that
+// the tensor has fewer than 2^32 bytes.
+struct PatchLane {
+    unsigned coff[6], roff[6];      // column b: (image, row 0, column 4 * tj + b - 1, channel pc); row a: row 4 * ti + a - 1
+    unsigned rowok, colok;
+};
+
+// tinfo[tile] = {byte offset of output element (image, 4 * ti, 4 * tj, channel 0), rows | columns << 8 of the 4x4 output tile
+// that lie inside the map (0 for a tile beyond the last one)}: written once per tile by the patch lane of channel 0, read by
+// the output transform, which so needs no division.
+__device__ __forceinline__ PatchLane patch_lane(const FusedGeom &gm, int64_t tb, int ptid, unsigned (*tinfo)[2]) {
+    PatchLane pl;
 #pragma unroll
-            for (int a = 0; a < 6; ++a) {
-                if ((unsigned)(h0 + a) < (unsigned)H) rowok |= 1u << a;
-                if ((unsigned)(w0 + a) < (unsigned)W) colok |= 1u << a;
-                const int hc = min(max(h0 + a, 0), H - 1), wc = min(max(w0 + a, 0), W - 1);
-                roff[a] = (unsigned)((int64_t)hc * W * red * 4);
-                coff[a] = (unsigned)((e + (int64_t)wc * red) * 4);
-            }
+    for (int a = 0; a < 6; ++a) pl.coff[a] = pl.roff[a] = 0;
+    pl.rowok = pl.colok = 0;
+    const int pc = ptid & 7, pt = ptid >> 3;
+    const unsigned t = (unsigned)(tb * FT) + pt;      // the host checks that there are fewer than 2^31 tiles
+    unsigned out_off = 0, extent = 0;
+    if (t < (unsigned)gm.T) {
+        const unsigned tj = t % (unsigned)gm.tw, r = t / (unsigned)gm.tw;
+        const unsigned ti = r % (unsigned)gm.th, n = r / (unsigned)gm.th;
+        const int h0 = 4 * (int)ti - 1, w0 = 4 * (int)tj - 1;
+        const int64_t e = ((int64_t)n * gm.H * gm.W) * gm.red + pc;
+#pragma unroll
+        for (int a = 0; a < 6; ++a) {
+            if ((unsigned)(h0 + a) < (unsigned)gm.H) pl.rowok |= 1u << a;
+            if ((unsigned)(w0 + a) < (unsigned)gm.W) pl.colok |= 1u << a;
+            const int hc = min(max(h0 + a, 0), gm.H - 1), wc = min(max(w0 + a, 0), gm.W - 1);
+            pl.roff[a] = (unsigned)((int64_t)hc * gm.W * gm.red * 4);
+            pl.coff[a] = (unsigned)((e + (int64_t)wc * gm.red) * 4);
         }
+        out_off = (unsigned)((((int64_t)n * gm.H + 4 * ti) * gm.W + 4 * tj) * gm.outc * 4);
+        extent = (unsigned)min(4, gm.H - 4 * (int)ti) | ((unsigned)min(4, gm.W - 4 * (int)tj) << 8);
     }
-    const bool interior = PATCH && __all(rowok == 0x3fu && colok == 0x3fu);      // uniform over the wave
+    if (pc == 0) {
+        tinfo[pt][0] = out_off;
+        tinfo[pt][1] = extent;
+    }
+    return pl;
+}
+
+// The reduction loop of one wave: NZ positions z0 .. z0 + NZ - 1 of the 32 x 64 tile; PATCH: this wave also loads and
+// transforms the input patches (one (tile, channel) per lane and chunk); INTERIOR: all of the wave's patches lie inside
+// the map (nothing to clamp, nothing to zero).
+template <int NZ, bool PATCH, bool INTERIOR>
+__device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const float *__restrict__ Up, float *lds, const FusedGeom &gm, int kb,
+                                             int z0, int ptid, int lane, const PatchLane &pl, floatx16 (&acc)[5][2]) {
+    const int l32 = lane & 31, g = lane >> 5;
+    const int nch = gm.nch;
+    const int pc = ptid & 7, pt = ptid >> 3;
     float d[36];
+    // interior patches: row a - 1 relative to the tile's first output row goes into the scalar offset (the descriptor starts
+    // one image row before the tensor; only offsets that lead back into it are used)
+    const unsigned rowbytes = (unsigned)gm.W * gm.red * 4;
+    const __amdgpu_buffer_rsrc_t rx = buffer_of(INTERIOR ? (const char *)x - rowbytes : (const char *)x);
     auto load_patch = [&](int ch) {
         const unsigned cbytes = (unsigned)ch * (FC * 4);
+        if (INTERIOR) {
+            unsigned vb[6];
 #pragma unroll
-        for (int a = 0; a < 6; ++a)
+            for (int b = 0; b < 6; ++b) vb[b] = pl.coff[b] + pl.roff[1] + cbytes;
 #pragma unroll
-            for (int b = 0; b < 6; ++b) d[a * 6 + b] = *(const float *)((const char *)x + (coff[b] + roff[a] + cbytes));
+            for (int a = 0; a < 6; ++a)
+#pragma unroll
+                for (int b = 0; b < 6; ++b) d[a * 6 + b] = buffer_load(rx, vb[b], a * rowbytes);
+        } else {
+#pragma unroll
+            for (int a = 0; a < 6; ++a)
+#pragma unroll
+                for (int b = 0; b < 6; ++b) d[a * 6 + b] = buffer_load(rx, pl.coff[b] + pl.roff[a], cbytes);
+        }
     };
     auto transform_store = [&](float *V) {
-        if (!interior) {
+        if (!INTERIOR) {
 #pragma unroll
             for (int a = 0; a < 6; ++a)
 #pragma unroll
                 for (int b = 0; b < 6; ++b)
-                    if (!((rowok >> a) & (colok >> b) & 1u)) d[a * 6 + b] = 0.0f;
+                    if (!((pl.rowok >> a) & (pl.colok >> b) & 1u)) d[a * 6 + b] = 0.0f;
         }
         float m[6][6];      // m[b][a] = (B^T d)[a][b]
 #pragma unroll
@@ -175,29 +230,40 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
     // is multiplied (each into the registers its predecessor just left), after the patch of chunk ch + 1, which is
     // requested first and used last.
     const int o32 = gm.kblocks * 2;
-    const f4 *bbase = (const f4 *)Up + ((int64_t)z0 * o32 + 2 * kb) * nch * 64 + lane;
-    const int64_t zstride = (int64_t)o32 * nch * 64, hstride = (int64_t)nch * 64;
+    const __amdgpu_buffer_rsrc_t ru = buffer_of(Up);
+    const unsigned lane16 = (unsigned)lane * 16u;
+    const unsigned zbytes = (unsigned)o32 * nch * 1024u, hbytes = (unsigned)nch * 1024u;      // the host checks the workspace size
+    const unsigned b0bytes = ((unsigned)z0 * o32 + 2u * kb) * nch * 1024u;
     f4 bq[NZ][2];
     auto load_b = [&](int zi, int ch) {
-        const f4 *p = bbase + zi * zstride + (int64_t)ch * 64;
-        bq[zi][0] = p[0];
-        bq[zi][1] = p[hstride];
+        const unsigned so = b0bytes + zi * zbytes + (unsigned)ch * 1024u;
+        bq[zi][0] = buffer_load4(ru, lane16, so);
+        bq[zi][1] = buffer_load4(ru, lane16, so + hbytes);
     };
 
     if (PATCH) load_patch(0);
 #pragma unroll
     for (int zi = 0; zi < NZ; ++zi) load_b(zi, 0);
-    if (PATCH) transform_store(lds);
+    if (PATCH) {
+        transform_store(lds);
+        load_patch(nch > 1 ? 1 : 0);
+    }
     __syncthreads();
 
     for (int ch = 0; ch < nch; ++ch) {
         const float *Vcur = lds + (ch & 1) * (36 * FT * VROW);
         float *Vnext = lds + ((ch + 1) & 1) * (36 * FT * VROW);
-        // the last chunk requests its own operands once more instead of branching around the requests (nothing reads them)
-        const int nx = ch + 1 < nch ? ch + 1 : ch;
-        if (PATCH) load_patch(nx);
-        // The scheduler must not sink the requests towards their use (it would, to save registers): the order of the
-        // sections below is the order of issue.
+        // the last chunks request operands that exist (their own) instead of branching around the requests; nothing reads them
+        const int nx = ch + 1 < nch ? ch + 1 : ch, nx2 = ch + 2 < nch ? ch + 2 : nch - 1;
+        // A patch wave transforms first (the patch of chunk ch + 1 was requested a whole chunk ago; V[next] was last read
+        // before the barrier that ended chunk ch - 1), so that its arithmetic runs beside the other wave's matrix-core
+        // work, then requests the patch of chunk ch + 2, then multiplies.  The scheduler must not move requests towards
+        // their use (it would, to save registers): the order of the sections below is the order of issue.
+        if (PATCH) {
+            transform_store(Vnext);
+            __builtin_amdgcn_sched_barrier(0);
+            load_patch(nx2);
+        }
         __builtin_amdgcn_sched_barrier(0);
         const float *vp = Vcur + (z0 * FT + l32) * VROW + g;
         float a0 = vp[0], a1 = vp[2], a2 = vp[4], a3 = vp[6];
@@ -221,19 +287,51 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
             load_b(zi, nx);      // into the registers the products above have just read
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (PATCH) transform_store(Vnext);
         __syncthreads();      // V[next] complete; every wave is done reading V[cur]
+    }
+}
+
+// Output transform of one (tile, channel): the 36 products from LDS, A^T . A, the 16 outputs to memory.
+// EPI: 0 plain store, 1 added to what is there, 2 followed by the BatchNorm multiply-add.  WHOLE: every output of the tile
+// lies inside the map and the channel exists (no store needs a test).
+template <int EPI, bool WHOLE>
+__device__ __forceinline__ void fused_output(const float *mp, __amdgpu_buffer_rsrc_t ry, unsigned voff, unsigned orow, unsigned obytes, int nr,
+                                             int nc, float bn_a, float bn_b) {
+    float s[6][4];      // s[b][a] = (A^T m)[a][b]
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        float m[6];
+#pragma unroll
+        for (int a = 0; a < 6; ++a) m[a] = mp[(6 * a + b) * (FT * MROW)];
+        f4_at(m[0], m[1], m[2], m[3], m[4], m[5], s[b]);
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        float o[4];
+        f4_at(s[0][a], s[1][a], s[2][a], s[3][a], s[4][a], s[5][a], o);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const unsigned so = a * orow + b * obytes;
+            if (WHOLE || (a < nr && b < nc)) {
+                float v = o[b];
+                if (EPI == 1) v += buffer_load(ry, voff, so);
+                if (EPI == 2) v = bn_affine(v, bn_a, bn_b);
+                buffer_store(ry, voff, so, v);
+            }
+        }
     }
 }
 
 // Eight waves, two per SIMD: waves 0-3 multiply five positions each (z = 5w ..), waves 4-7 four positions each
 // (z = 20 + 4(w - 4) ..) and transform the input patches, so that on every SIMD the transform arithmetic of one wave runs
-// beside the matrix-core work of the other.
-template <bool ADJ>
+// beside the matrix-core work of the other.  ADJ only names the use in profiles (forward pass / input gradient).
+template <bool ADJ, int EPI>
 __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restrict__ x, const float *__restrict__ Up, float *y, FusedGeom gm,
-                                                          int accumulate, BnAffine bn) {
+                                                          BnAffine bn) {
     __shared__ float lds[LDS_FLOATS];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    __shared__ unsigned tinfo[FT][2];
+    const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // the same for the whole wave: kept in a scalar register
     // Work item: hardware deals workgroups to the 8 XCDs in turn; item = (id mod 8) * (grid / 8) + id / 8 gives each XCD a
     // contiguous share, so that neighbouring tile rows (shared halo) and the channel blocks of one tile range (same input)
     // meet in one L2.  The grid is a multiple of 8; items beyond the last one do nothing.
@@ -242,7 +340,6 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
     if (item >= gm.items) return;
     const int kb = (int)(item % gm.kblocks);
     const int64_t tb = item / gm.kblocks;
-    const int H = gm.H, W = gm.W;
 
     floatx16 acc[5][2];
 #pragma unroll
@@ -253,11 +350,21 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
             for (int i = 0; i < 16; ++i) acc[zi][h][i] = 0.0f;
     const bool heavy = wave < 4;
     const int z0 = heavy ? 5 * wave : 20 + 4 * (wave - 4), nz = heavy ? 5 : 4;
-    if (heavy) fused_reduce<5, false>(x, Up, lds, gm, kb, tb, z0, 0, lane, acc);
-    else fused_reduce<4, true>(x, Up, lds, gm, kb, tb, z0, tid - 256, lane, acc);
+    if (heavy) {
+        fused_reduce<5, false, false>(x, Up, lds, gm, kb, z0, 0, lane, PatchLane{}, acc);
+    } else {
+        const PatchLane pl = patch_lane(gm, tb, tid - 256, tinfo);      // tinfo is complete at the loop's first barrier
+        // uniform over the wave; every version of the loop meets the workgroup's barriers the same number of times
+        if (__all(pl.rowok == 0x3fu && pl.colok == 0x3fu)) fused_reduce<4, true, true>(x, Up, lds, gm, kb, z0, tid - 256, lane, pl, acc);
+        else fused_reduce<4, true, false>(x, Up, lds, gm, kb, z0, tid - 256, lane, pl, acc);
+    }
 
-    // ---- output transform, 32 channels at a time
-    const int ok_ = tid & 31, oq = tid >> 5;      // channel within the half, first of two tiles (oq, oq + 16)
+    // ---- output transform, 32 channels at a time: thread = (channel ok_ of the half, tiles oq and oq + 16).  Output element
+    // (a, b) of a tile sits at byte y + [(a * W + b) * outc * 4] + voff: the bracket is scalar, voff the thread's own 32-bit
+    // offset (tile + channel); the host checks that the output has fewer than 2^32 bytes.
+    const int ok_ = tid & 31, oq = tid >> 5;
+    const unsigned obytes = (unsigned)gm.outc * 4, orow = (unsigned)gm.W * obytes;
+    const __amdgpu_buffer_rsrc_t ry = buffer_of(y);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int kout = kb * FK + h * 32 + ok_;
@@ -272,38 +379,16 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
             }
         __syncthreads();
         float bn_a = 1.0f, bn_b = 0.0f;
-        if (!ADJ && bn.gamma && kout < gm.outc) bn_affine_coeffs(bn.gamma, bn.beta, bn.stats, gm.outc, kout, bn_a, bn_b);
+        if (EPI == 2 && kout < gm.outc) bn_affine_coeffs(bn.gamma, bn.beta, bn.stats, gm.outc, kout, bn_a, bn_b);
+#pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int tl = oq + 16 * q;
-            const int64_t t = tb * FT + tl;
-            if (t >= gm.T || kout >= gm.outc) continue;
-            const int tj = (int)(t % gm.tw);
-            const int64_t r = t / gm.tw;
-            const int ti = (int)(r % gm.th), n = (int)(r / gm.th);
-            float s[6][4];      // s[b][a] = (A^T m)[a][b]
-#pragma unroll
-            for (int b = 0; b < 6; ++b) {
-                float m[6];
-#pragma unroll
-                for (int a = 0; a < 6; ++a) m[a] = lds[((6 * a + b) * FT + tl) * MROW + ok_];
-                f4_at(m[0], m[1], m[2], m[3], m[4], m[5], s[b]);
-            }
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int hh = 4 * ti + a;
-                if (hh >= H) continue;
-                float o[4];
-                f4_at(s[0][a], s[1][a], s[2][a], s[3][a], s[4][a], s[5][a], o);
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int ww = 4 * tj + b;
-                    if (ww >= W) continue;
-                    float *dst = y + (((int64_t)n * H + hh) * W + ww) * gm.outc + kout;
-                    float v = accumulate ? *dst + o[b] : o[b];
-                    if (!ADJ && bn.gamma) v = bn_affine(v, bn_a, bn_b);
-                    *dst = v;
-                }
-            }
+            const unsigned voff = tinfo[tl][0] + (unsigned)kout * 4u;
+            unsigned ext = tinfo[tl][1];
+            if (kout >= gm.outc) ext = 0;
+            const float *mp = lds + tl * MROW + ok_;
+            if (__all(ext == (4u | (4u << 8)))) fused_output<EPI, true>(mp, ry, voff, orow, obytes, 4, 4, bn_a, bn_b);      // uniform over the wave
+            else fused_output<EPI, false>(mp, ry, voff, orow, obytes, (int)(ext & 0xff), (int)(ext >> 8), bn_a, bn_b);
         }
     }
 }
@@ -339,19 +424,22 @@ void conv_winograd_fused(hipStream_t st, const float *in, const float *w, float 
     gm.kblocks = (gm.outc + FK - 1) / FK;
     gm.items = (gm.T + FT - 1) / FT * gm.kblocks;
     const int64_t grid = (gm.items + 7) / 8 * 8;
-    if (gm.T < 1 || grid >= 0x7fffffffll || (int64_t)cs.N * cs.H * cs.W * gm.red >= ((int64_t)1 << 30))
-        throw KernelError("conv_winograd_fused: shape out of range (the input must have fewer than 2^32 bytes)");
+    if (gm.T < 1 || gm.T >= 0x7fffffffll || grid >= 0x7fffffffll || (int64_t)(cs.N * (int64_t)cs.H + 8) * cs.W * std::max(gm.red, gm.outc) * 4 >= ((int64_t)1 << 32) - 65536)
+        throw KernelError("conv_winograd_fused: shape out of range (input and output must have fewer than 2^32 bytes each)");
     const int out_pad = gm.kblocks * FK;
     const int64_t fe = (int64_t)out_pad * gm.red;
     const dim3 fg((unsigned)((fe + 255) / 256)), blk(256), wg(512);
     const BnAffine bn = affine ? *affine : BnAffine{};
-    const int acc = accumulate ? 1 : 0;
+    const dim3 gd((unsigned)grid);
     if (adjoint) {
         hipLaunchKernelGGL(wino4_filter_fused_kernel<true>, fg, blk, 0, st, w, ws, cs.K, cs.C, out_pad);
-        hipLaunchKernelGGL(wino4_fused_kernel<true>, dim3((unsigned)grid), wg, 0, st, in, (const float *)ws, out, gm, acc, bn);
+        if (accumulate) hipLaunchKernelGGL((wino4_fused_kernel<true, 1>), gd, wg, 0, st, in, (const float *)ws, out, gm, bn);
+        else hipLaunchKernelGGL((wino4_fused_kernel<true, 0>), gd, wg, 0, st, in, (const float *)ws, out, gm, bn);
     } else {
         hipLaunchKernelGGL(wino4_filter_fused_kernel<false>, fg, blk, 0, st, w, ws, cs.K, cs.C, out_pad);
-        hipLaunchKernelGGL(wino4_fused_kernel<false>, dim3((unsigned)grid), wg, 0, st, in, (const float *)ws, out, gm, acc, bn);
+        if (affine) hipLaunchKernelGGL((wino4_fused_kernel<false, 2>), gd, wg, 0, st, in, (const float *)ws, out, gm, bn);
+        else if (accumulate) hipLaunchKernelGGL((wino4_fused_kernel<false, 1>), gd, wg, 0, st, in, (const float *)ws, out, gm, bn);
+        else hipLaunchKernelGGL((wino4_fused_kernel<false, 0>), gd, wg, 0, st, in, (const float *)ws, out, gm, bn);
     }
     hip_check(hipGetLastError(), "fused winograd launch");
 }
