@@ -33,7 +33,10 @@
 // round-robin, so logical item = (id mod 8) * (grid/8) + id / 8.  A work item is (tile, reduction
 // split) with the tile index fastest, so a launch with few tiles and many splits (weight
 // gradients) still spreads over all XCDs and the tiles of one split share their operand rows.
+#include <type_traits>
+
 #include "bn_affine.hpp"
+#include "buffer_addr.hpp"
 #include "kernels.hpp"
 #include "tile_stats.hpp"
 
@@ -149,15 +152,15 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         split = (int)(item / ta.total_tiles);
         logical = item - (int64_t)split * ta.total_tiles;
     }
-    const int tile_n = (int)(logical % ta.tiles_n);
-    const int64_t tile_m = logical / ta.tiles_n;
+    const int tile_n = (int)((unsigned)logical % (unsigned)ta.tiles_n);      // the host bounds the tile count below 2^31
+    const int64_t tile_m = (unsigned)logical / (unsigned)ta.tiles_n;
     const int64_t row0 = tile_m * BM;
     const int col0 = tile_n * BN;
     const int RSC = (int)cs.RSC();
 
     // ---------------- DGRAD: residue class of this launch slice
     int64_t Mg = ta.Mg, Kg = ta.Kg;
-    int ph = 0, pw = 0, r0 = 0, s0 = 0, ns = cs.S, bh = cs.pad, bw = cs.pad, Hc = cs.H, Wc = cs.W;
+    int ph = 0, pw = 0, r0 = 0, s0 = 0, nr = cs.R, ns = cs.S, bh = cs.pad, bw = cs.pad, Hc = cs.H, Wc = cs.W;
     // blockIdx.z = residue class (DGRAD only)
     if (MODE == DGRAD) {
         const int st = cs.stride;
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         Wc = (cs.W - pw + st - 1) / st;
         r0 = (ph + cs.pad) % st;
         s0 = (pw + cs.pad) % st;
-        int nr = r0 < cs.R ? (cs.R - r0 + st - 1) / st : 0;
+        nr = r0 < cs.R ? (cs.R - r0 + st - 1) / st : 0;
         ns = s0 < cs.S ? (cs.S - s0 + st - 1) / st : 0;
         bh = (ph + cs.pad - r0) / st;
         bw = (pw + cs.pad - s0) / st;
@@ -202,18 +205,18 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             a_ok[s] = m < Mg;
             int64_t mm = a_ok[s] ? m : 0;
             if (MODE == FWD) {
-                int q = (int)(mm % cs.Q);
-                int64_t t = mm / cs.Q;
-                int p = (int)(t % cs.P);
-                int n = (int)(t / cs.P);
+                const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)cs.Q;      // rows are bounded below 2^31 by the host
+                int q = (int)(m32 % (unsigned)cs.Q);
+                int p = (int)(t % (unsigned)cs.P);
+                int n = (int)(t / (unsigned)cs.P);
                 a_h0[s] = p * cs.stride - cs.pad;
                 a_w0[s] = q * cs.stride - cs.pad;
                 a_base[s] = (int64_t)n * cs.H * cs.W * cs.C + (idx % 4) * 4;
             } else {   // DGRAD: m = (n, hc, wc) within the residue class
-                int wc = (int)(mm % Wc);
-                int64_t t = mm / Wc;
-                int hc = (int)(t % Hc);
-                int n = (int)(t / Hc);
+                const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)Wc;
+                int wc = (int)(m32 % (unsigned)Wc);
+                int hc = (int)(t % (unsigned)Hc);
+                int n = (int)(t / (unsigned)Hc);
                 a_h0[s] = hc + bh;      // p = a_h0 - tap row
                 a_w0[s] = wc + bw;
                 a_base[s] = (int64_t)n * cs.P * cs.Q * cs.K + (idx % 4) * 4;
@@ -259,13 +262,47 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 b_i2[s] |= (rs % cs.S) << 24;
                 int64_t m = kt0 * BK + b_i0[s];
                 int64_t mm = m < Kg ? m : 0;
-                w_q[s] = (int)(mm % cs.Q);
-                int64_t t = mm / cs.Q;
-                w_p[s] = (int)(t % cs.P);
-                w_n[s] = (int)(t / cs.P);
+                const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)cs.Q;
+                w_q[s] = (int)(m32 % (unsigned)cs.Q);
+                w_p[s] = (int)(t % (unsigned)cs.P);
+                w_n[s] = (int)(t / (unsigned)cs.P);
             }
         }
     }
+
+    // ---------------- aligned forward / input-gradient loaders: buffer addressing
+    // Every vector instruction takes its cycles from the matrix pipe of the same SIMD, so an address is split into what
+    // differs between lanes and never changes (a 32-bit byte offset per slot, computed once) and what changes from step
+    // to step and is the same for every lane (the filter tap and the channel block: a scalar offset).  The descriptor of
+    // the activation operand starts `a_shift` floats before the tensor, enough for the most negative tap offset and for
+    // the offset that sends an absent element (padding, rows beyond the tensor) to the tensor's first floats instead;
+    // bit t of a_taps says whether tap t of the slot exists.  The host takes this path only for tensors the 32-bit
+    // offsets can span and for filters of at most 32 taps.
+    unsigned a_voff[LA], a_taps[LA], b_voff[LB];
+    int64_t a_shift = 0;
+    if (FAST && MODE != WGRAD) {
+        const int row = MODE == FWD ? cs.W : cs.Q, inner = MODE == FWD ? cs.C : cs.K;
+        const int tr = MODE == FWD ? cs.R : nr, ts = MODE == FWD ? cs.S : ns;
+        const int64_t back = MODE == FWD ? ((int64_t)cs.pad * row + cs.pad) * inner : 0;                    // most negative slot offset
+        const int64_t reach = ((int64_t)(tr > 0 ? tr - 1 : 0) * row + (ts > 0 ? ts - 1 : 0)) * inner;       // largest tap offset
+        a_shift = MODE == FWD ? (back > reach ? back : reach) : reach;
+#pragma unroll
+        for (int s = 0; s < LA; ++s) {
+            a_voff[s] = (unsigned)((a_base[s] + ((int64_t)a_h0[s] * row + a_w0[s]) * inner + (MODE == FWD ? a_shift : 0)) * 4);
+            unsigned rows = 0, cols = 0, taps = 0;
+            for (int r = 0; r < tr; ++r)
+                if (MODE == FWD ? (unsigned)(a_h0[s] + r) < (unsigned)cs.H : (unsigned)(a_h0[s] - r) < (unsigned)cs.P) rows |= 1u << r;
+            for (int c = 0; c < ts; ++c)
+                if (MODE == FWD ? (unsigned)(a_w0[s] + c) < (unsigned)cs.W : (unsigned)(a_w0[s] - c) < (unsigned)cs.Q) cols |= 1u << c;
+            for (int r = 0; r < tr; ++r)
+                if ((rows >> r) & 1) taps |= cols << (r * ts);
+            a_taps[s] = a_ok[s] ? taps : 0u;
+        }
+#pragma unroll
+        for (int s = 0; s < LB; ++s)
+            b_voff[s] = b_ok[s] ? (unsigned)(((int64_t)b_i0[s] * RSC + b_i1[s]) * 4) : 0u;      // an absent filter row reads the tensor's start
+    }
+    const __amdgpu_buffer_rsrc_t ra = buffer_of(ta.a - a_shift), rb = buffer_of(ta.b);
 
     // ---------------- position of the next step to load (uniform over the workgroup)
     int64_t kk0 = kt0 * BK;
@@ -298,8 +335,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     // tensor's first 16 bytes instead) and zeroed when it is written to LDS: without branches around
     // the loads the compiler can count outstanding loads exactly and wait only for the older stage.
     // pm: bit s = A slot s holds data, bit 16+s = B slot s holds data.
-    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB], unsigned &pm) {
+    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB], unsigned &pm, int &full) {
         pm = 0;
+        bool every = FAST;      // every slot of this lane holds data
         // ======== A
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
@@ -308,9 +346,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             bool ok = !FAST;    // the element-wise variants zero what they do not load
             if (MODE == FWD) {
                 if (FAST) {
-                    int h = a_h0[s] + u_r, w = a_w0[s] + u_s;
-                    ok = a_ok[s] && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W;
-                    v = ld4(ok ? ta.a + a_base[s] + ((int64_t)h * cs.W + w) * cs.C + u_c : ta.a);
+                    // scalar: tap number and offset; an absent element reads float u_c of the tensor instead
+                    const unsigned tapoff = (unsigned)(((int64_t)u_r * cs.W + u_s) * cs.C);
+                    ok = (a_taps[s] >> (u_r * cs.S + u_s)) & 1u;
+                    const bf4 q = buffer_load4(ra, ok ? a_voff[s] : ((unsigned)a_shift - tapoff) * 4u, (tapoff + (unsigned)u_c) * 4u);
+                    v = make_float4(q.x, q.y, q.z, q.w);
                 } else if (HAS_KTAB && use_ktab) {
                     // branch-free: an element outside the image or the reduction reads the tensor's first word and is zeroed
                     float e[4];
@@ -342,9 +382,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             } else if (MODE == DGRAD) {
                 // reduction index = (tap row, tap column, k); FAST: K % 16 == 0 so a step stays inside one tap
                 if (FAST) {
-                    int p = a_h0[s] - u_r, q = a_w0[s] - u_s;
-                    ok = a_ok[s] && (unsigned)p < (unsigned)cs.P && (unsigned)q < (unsigned)cs.Q;
-                    v = ld4(ok ? ta.a + a_base[s] + ((int64_t)p * cs.Q + q) * cs.K + u_c : ta.a);
+                    // the descriptor starts a_shift floats early: tap (u_r, u_s) lies tapoff floats before the slot's offset
+                    const unsigned tapoff = (unsigned)(((int64_t)u_r * cs.Q + u_s) * cs.K);
+                    ok = (a_taps[s] >> (u_r * ns + u_s)) & 1u;
+                    const bf4 q = buffer_load4(ra, ok ? a_voff[s] : tapoff * 4u, ((unsigned)a_shift - tapoff + (unsigned)u_c) * 4u);
+                    v = make_float4(q.x, q.y, q.z, q.w);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -374,6 +416,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             }
             a_reg[s] = v;
             if (ok) pm |= 1u << s;
+            every = every && ok;
         }
         // ======== B
 #pragma unroll
@@ -384,7 +427,8 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             if (MODE == FWD) {
                 if (FAST) {
                     ok = b_ok[s];
-                    v = ld4(ok ? ta.b + (int64_t)b_i0[s] * RSC + kk0 + b_i1[s] : ta.b);
+                    const bf4 q = buffer_load4(rb, b_voff[s], (unsigned)kk0 * 4u);
+                    v = make_float4(q.x, q.y, q.z, q.w);
                 } else {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -396,9 +440,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 // B[red = (tap, k)][col = c] = W[k][r0 + st*tr][s0 + st*ts][c]
                 int64_t kk = kk0 + b_i0[s];
                 if (FAST) {
-                    int r = r0 + cs.stride * u_r, ss = s0 + cs.stride * u_s;
-                    ok = b_ok[s] && kk < Kg;
-                    v = ld4(ok ? ta.b + (int64_t)(u_c + b_i0[s]) * RSC + (r * cs.S + ss) * cs.C + b_i1[s] : ta.b);
+                    // K % 16 == 0: a step never reaches beyond the reduction
+                    const int r = r0 + cs.stride * u_r, ss = s0 + cs.stride * u_s;
+                    ok = b_ok[s];
+                    const bf4 q = buffer_load4(rb, b_voff[s], (unsigned)(((int64_t)u_c * RSC + (r * cs.S + ss) * cs.C) * 4));
+                    v = make_float4(q.x, q.y, q.z, q.w);
                 } else if (kk < Kg) {
                     int tap = (int)kk / cs.K, k = (int)kk % cs.K;
                     int r = r0 + cs.stride * (tap / ns), ss = s0 + cs.stride * (tap % ns);
@@ -441,7 +487,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             }
             b_reg[s] = v;
             if (ok) pm |= 1u << (16 + s);
+            every = every && ok;
         }
+        // uniform over the wave: when nothing is absent the LDS write below needs no selects (vector instructions that
+        // would take their cycles from the matrix pipe)
+        full = __all(every) ? 1 : 0;
         // ======== advance to the next step
         kk0 += BK;
         if (MODE == FWD) {
@@ -462,22 +512,27 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         }
     };
 
-    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB], unsigned pm) {
+    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB], unsigned pm, int full) {
         const float4 zero = make_float4(0, 0, 0, 0);
+        auto put = [&](auto whole) {
 #pragma unroll
-        for (int s = 0; s < LA; ++s) {
-            int idx = tid + s * NT;
-            float4 v = (pm >> s) & 1 ? a_reg[s] : zero;
-            if (A_KC) *(float4 *)&As[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
-            else *(float4 *)&As[buf][(idx / (BM / 4)) * A_LD + (idx % (BM / 4)) * 4] = v;
-        }
+            for (int s = 0; s < LA; ++s) {
+                int idx = tid + s * NT;
+                float4 v = decltype(whole)::value || ((pm >> s) & 1) ? a_reg[s] : zero;
+                if (A_KC) *(float4 *)&As[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
+                else *(float4 *)&As[buf][(idx / (BM / 4)) * A_LD + (idx % (BM / 4)) * 4] = v;
+            }
 #pragma unroll
-        for (int s = 0; s < LB; ++s) {
-            int idx = tid + s * NT;
-            float4 v = (pm >> (16 + s)) & 1 ? b_reg[s] : zero;
-            if (B_KC) *(float4 *)&Bs[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
-            else *(float4 *)&Bs[buf][(idx / (BN / 4)) * B_LD + (idx % (BN / 4)) * 4] = v;
-        }
+            for (int s = 0; s < LB; ++s) {
+                int idx = tid + s * NT;
+                float4 v = decltype(whole)::value || ((pm >> (16 + s)) & 1) ? b_reg[s] : zero;
+                if (B_KC) *(float4 *)&Bs[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
+                else *(float4 *)&Bs[buf][(idx / (BN / 4)) * B_LD + (idx % (BN / 4)) * 4] = v;
+            }
+        };
+        // uniform over the wave: a step in which no lane misses anything is written without the selects
+        if (full) put(std::true_type{});
+        else put(std::false_type{});
     };
 
     floatx16 acc[2][2];
@@ -531,24 +586,26 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     if (STAGES == 1 && kt0 < kt1) {
         const int64_t steps = kt1 - kt0;
         unsigned pm0 = 0;
-        load_tiles(a_set0, b_set0, pm0);
-        store_tiles(0, a_set0, b_set0, pm0);
+        int full0 = 0;
+        load_tiles(a_set0, b_set0, pm0, full0);
+        store_tiles(0, a_set0, b_set0, pm0, full0);
         __syncthreads();
         for (int64_t t = 0; t + 1 < steps; ++t) {
-            load_tiles(a_set0, b_set0, pm0);
+            load_tiles(a_set0, b_set0, pm0, full0);
             __builtin_amdgcn_sched_barrier(0);
             compute((int)(t & 1));
             __builtin_amdgcn_sched_barrier(0);
-            store_tiles((int)((t + 1) & 1), a_set0, b_set0, pm0);
+            store_tiles((int)((t + 1) & 1), a_set0, b_set0, pm0, full0);
             __syncthreads();
         }
         compute((int)((steps - 1) & 1));
     } else if (kt0 < kt1) {
         const int64_t steps = kt1 - kt0;
         unsigned pm0 = 0, pm1 = 0;
-        load_tiles(a_set0, b_set0, pm0);
-        if (steps > 1) load_tiles(a_set1, b_set1, pm1);
-        store_tiles(0, a_set0, b_set0, pm0);
+        int full0 = 0, full1 = 0;
+        load_tiles(a_set0, b_set0, pm0, full0);
+        if (steps > 1) load_tiles(a_set1, b_set1, pm1, full1);
+        store_tiles(0, a_set0, b_set0, pm0, full0);
         __syncthreads();
         int64_t t = 0;
         // The scheduling fences keep the order loads -> MFMAs -> LDS write -> barrier: left alone, the
@@ -557,29 +614,29 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         // each LDS write is the same on every path and the wait can name exactly the older stage.
         for (; t + 3 < steps; t += 2) {
             // even step: LDS buffer 0, next step waits in stage 1
-            load_tiles(a_set0, b_set0, pm0);
+            load_tiles(a_set0, b_set0, pm0, full0);
             __builtin_amdgcn_sched_barrier(0);
             compute(0);
             __builtin_amdgcn_sched_barrier(0);
-            store_tiles(1, a_set1, b_set1, pm1);
+            store_tiles(1, a_set1, b_set1, pm1, full1);
             __syncthreads();
             // odd step: LDS buffer 1, next step waits in stage 0
-            load_tiles(a_set1, b_set1, pm1);
+            load_tiles(a_set1, b_set1, pm1, full1);
             __builtin_amdgcn_sched_barrier(0);
             compute(1);
             __builtin_amdgcn_sched_barrier(0);
-            store_tiles(0, a_set0, b_set0, pm0);
+            store_tiles(0, a_set0, b_set0, pm0, full0);
             __syncthreads();
         }
         // Drain: one to three steps are left; step t sits in buffer 0, step t+1 (if any) in stage 1.
-        if (t + 2 < steps) load_tiles(a_set0, b_set0, pm0);
+        if (t + 2 < steps) load_tiles(a_set0, b_set0, pm0, full0);
         compute(0);
         if (t + 1 < steps) {
-            store_tiles(1, a_set1, b_set1, pm1);
+            store_tiles(1, a_set1, b_set1, pm1, full1);
             __syncthreads();
             compute(1);
             if (t + 2 < steps) {
-                store_tiles(0, a_set0, b_set0, pm0);
+                store_tiles(0, a_set0, b_set0, pm0, full0);
                 __syncthreads();
                 compute(0);
             }
@@ -939,7 +996,10 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
     ta.a = x; ta.b = w; ta.cs = cs;
     ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
     ta.out_elems = ta.Mg * ta.Ng;
-    bool fast = cs.C % BK == 0;
+    // the aligned loader addresses both operands with 32-bit byte offsets (plus one tap's reach) and keeps one bit per filter tap
+    const int64_t span32 = ((int64_t)1 << 32) - (1 << 20);
+    const int64_t reach = ((int64_t)(cs.R + cs.pad) * cs.W + cs.S + cs.pad) * cs.C * 4;
+    bool fast = cs.C % BK == 0 && cs.R * cs.S <= 32 && (int64_t)cs.N * cs.H * cs.W * cs.C * 4 + reach < span32 && cs.K * cs.RSC() * 4 < span32;
     if ((stats_part || affine) && (!fast || cs.K % 4 || splits != 1 || accumulate))
         throw KernelError("conv_fwd: statistics or BatchNorm in the epilogue need C % 16 == 0, K % 4 == 0, splits == 1 and no accumulation");
     if (stats_part && affine) throw KernelError("conv_fwd: either the statistics of the output or its BatchNorm apply step, not both");
@@ -959,7 +1019,9 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
     ta.Ng = cs.C;
     ta.Kg = 0;   // per class, computed in the kernel
     ta.out_elems = (int64_t)cs.N * cs.H * cs.W * cs.C;
-    bool fast = cs.K % BK == 0 && cs.C % 4 == 0;
+    const int64_t span32 = ((int64_t)1 << 32) - (1 << 20);
+    const int64_t reach = ((int64_t)cs.R * cs.Q + cs.S) * cs.K * 4;
+    bool fast = cs.K % BK == 0 && cs.C % 4 == 0 && cs.R * cs.S <= 32 && cs.M() * cs.K * 4 + reach < span32 && cs.K * cs.RSC() * 4 < span32;
     launch_cfg<DGRAD>(pick_cfg(DGRAD, ta.Mg, ta.Ng), st, ta, fast, sg.classes, dx, splits, ws, ws_bytes, sg.steps, accumulate, "conv_dgrad");
 }
 

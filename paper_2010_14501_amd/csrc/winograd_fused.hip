@@ -23,6 +23,7 @@
 // channel and workgroup) cost more than the workspace form's large GEMM tiles save; the graph offers this form where it
 // was measured to be faster.
 #include "bn_affine.hpp"
+#include "buffer_addr.hpp"
 #include "kernels.hpp"
 
 namespace monet {
@@ -31,24 +32,6 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef unsigned u4 __attribute__((ext_vector_type(4)));
-
-// Memory is addressed through buffer instructions: address = base (a resource descriptor in scalar registers) + a 32-bit
-// per-lane byte offset + a 32-bit scalar byte offset, so that the part of an address that is the same for every lane costs
-// no vector instruction.  The descriptors span the whole 32-bit offset range (every access made through them is in bounds
-// by construction; the hardware's range check is not relied upon); word 3 is the plain 32-bit data format of this family.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void *base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, -1, 0x00020000);
-}
-__device__ __forceinline__ float buffer_load(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
-}
-__device__ __forceinline__ f4 buffer_load4(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
-    return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
-}
-__device__ __forceinline__ void buffer_store(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff, float v) {
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 0);
-}
 
 constexpr int FT = 32;            // tiles per workgroup
 constexpr int FK = 64;            // output channels per workgroup
