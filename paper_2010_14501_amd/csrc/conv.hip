@@ -74,6 +74,8 @@ struct TileArgs {
     float *stats_part;         // FWD, whole results only: BatchNorm partial statistics of the output (tile_stats.hpp), or null
     BnAffine affine;           // FWD, whole results only: BatchNorm apply step of the output in the epilogue (gamma == null: off)
     int64_t batch_a, batch_b, batch_out;   // FWD / WGRAD with gridDim.z > 1: z-th GEMM of a batch, operands and result this many floats apart
+    // WGRAD, aligned loader: floor(n / Q) = umulhi(n, q_mul) >> q_shift for n < 2^31 (Q >= 2), likewise P
+    unsigned q_mul, q_shift, p_mul, p_shift;
 };
 
 // arrivals per split tile; zero whenever no convolution kernel is running (the last arrival puts its entry back)
@@ -111,6 +113,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     constexpr bool HAS_KTAB = !FAST && MODE == FWD && WM * WN == 4 && !(WM == 2 && WN == 2);
     constexpr int KTAB = 256;
     __shared__ int2 ktab[HAS_KTAB ? KTAB : 1];   // x = ((r*W + s)*C + c), y = r | s << 8, or y < 0 beyond the reduction
+    // Aligned filter gradient: the BK output positions a reduction step covers, decoded once per step by 16 lanes for
+    // the whole workgroup: x = byte offset of the position's window in the (shifted) input tensor, y = bit per filter
+    // tap that falls inside the image.  Two entries: the table of step j + 1 is written while step j is loaded.
+    constexpr bool ROWTAB = FAST && MODE == WGRAD;
+    __shared__ uint2 rowtab[ROWTAB ? 2 : 1][ROWTAB ? BK : 1];
 
     if (MODE != DGRAD) {   // batched GEMMs (the 16 products of a Winograd convolution) share one launch
         ta.a += (int64_t)blockIdx.z * ta.batch_a;
@@ -260,12 +267,14 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 // tap (r, s) packed for the bounds test
                 b_i1[s] |= (rs / cs.S) << 24;
                 b_i2[s] |= (rs % cs.S) << 24;
-                int64_t m = kt0 * BK + b_i0[s];
-                int64_t mm = m < Kg ? m : 0;
-                const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)cs.Q;
-                w_q[s] = (int)(m32 % (unsigned)cs.Q);
-                w_p[s] = (int)(t % (unsigned)cs.P);
-                w_n[s] = (int)(t / (unsigned)cs.P);
+                if (!FAST) {
+                    int64_t m = kt0 * BK + b_i0[s];
+                    int64_t mm = m < Kg ? m : 0;
+                    const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)cs.Q;
+                    w_q[s] = (int)(m32 % (unsigned)cs.Q);
+                    w_p[s] = (int)(t % (unsigned)cs.P);
+                    w_n[s] = (int)(t / (unsigned)cs.P);
+                }
             }
         }
     }
@@ -302,7 +311,46 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         for (int s = 0; s < LB; ++s)
             b_voff[s] = b_ok[s] ? (unsigned)(((int64_t)b_i0[s] * RSC + b_i1[s]) * 4) : 0u;      // an absent filter row reads the tensor's start
     }
-    const __amdgpu_buffer_rsrc_t ra = buffer_of(ta.a - a_shift), rb = buffer_of(ta.b);
+    // Aligned filter gradient: dy rows advance by a scalar offset; the window of an output position comes from the
+    // row table, the slot adds its tap and channel and tests its tap's bit.  The input descriptor starts b_shift floats
+    // early (a window begins up to `pad` rows and columns before the image).
+    unsigned w_tapbit[LB];
+    int64_t b_shift = 0;
+    if (FAST && MODE == WGRAD) {
+        b_shift = ((int64_t)cs.pad * cs.W + cs.pad) * cs.C;
+#pragma unroll
+        for (int s = 0; s < LA; ++s) a_voff[s] = a_ok[s] ? (unsigned)(((int64_t)a_h0[s] * cs.K + a_w0[s]) * 4) : 0u;
+#pragma unroll
+        for (int s = 0; s < LB; ++s) {
+            const int r = b_i1[s] >> 24, ss = b_i2[s] >> 24;
+            b_voff[s] = (unsigned)(((int64_t)(b_i1[s] & 0xffffff) * cs.C + (b_i2[s] & 0xffffff)) * 4);
+            w_tapbit[s] = b_ok[s] ? 1u << (r * cs.S + ss) : 0u;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t ra = buffer_of(ta.a - a_shift), rb = buffer_of(ta.b - b_shift);
+    int w_slot = 0;   // row table entry the next load_tiles reads
+    // decodes the output positions of reduction step `step` (lanes 0..BK-1 of the first wave)
+    auto fill_rows = [&](int64_t step, int slot) {
+        if (ROWTAB && tid < BK) {
+            const int64_t m = step * BK + tid;
+            unsigned pix = 0, taps = 0;
+            if (m < Kg) {
+                const unsigned m32 = (unsigned)m;
+                const unsigned t = cs.Q == 1 ? m32 : __umulhi(m32, ta.q_mul) >> ta.q_shift;
+                const unsigned q = m32 - t * (unsigned)cs.Q;
+                const unsigned n = cs.P == 1 ? t : __umulhi(t, ta.p_mul) >> ta.p_shift;
+                const unsigned pp = t - n * (unsigned)cs.P;
+                const int h0 = (int)pp * cs.stride - cs.pad, w0 = (int)q * cs.stride - cs.pad;
+                const int rlo = max(0, -h0), rhi = min(cs.R, cs.H - h0), clo = max(0, -w0), chi = min(cs.S, cs.W - w0);
+                const unsigned rows = rhi > rlo ? (unsigned)((1ull << rhi) - (1ull << rlo)) : 0u;
+                const unsigned cols = chi > clo ? (unsigned)((1ull << chi) - (1ull << clo)) : 0u;
+                for (int r = 0; r < cs.R; ++r)
+                    if ((rows >> r) & 1u) taps |= cols << (r * cs.S);
+                pix = (unsigned)((((int64_t)n * cs.H + h0) * cs.W + w0) * cs.C + b_shift) * 4u;
+            }
+            rowtab[slot][tid] = make_uint2(pix, taps);
+        }
+    };
 
     // ---------------- position of the next step to load (uniform over the workgroup)
     int64_t kk0 = kt0 * BK;
@@ -334,10 +382,16 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     // In the aligned variants every load is issued unconditionally (an out-of-range slot reads the
     // tensor's first 16 bytes instead) and zeroed when it is written to LDS: without branches around
     // the loads the compiler can count outstanding loads exactly and wait only for the older stage.
-    // pm: bit s = A slot s holds data, bit 16+s = B slot s holds data.
-    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB], unsigned &pm, int &full) {
-        pm = 0;
+    // pm: which slots hold data (lane masks, kept in scalar registers).
+    struct Present { bool a[LA], b[LB]; };
+    auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB], Present &pm, int &full) {
         bool every = FAST;      // every slot of this lane holds data
+        // aligned filter gradient: the table entries of this lane's B slots, read before anything else is issued
+        unsigned long long w_row[LB];
+        if (ROWTAB) {
+#pragma unroll
+            for (int s = 0; s < LB; ++s) w_row[s] = *(const unsigned long long *)&rowtab[w_slot][b_i0[s]];
+        }
         // ======== A
 #pragma unroll
         for (int s = 0; s < LA; ++s) {
@@ -404,8 +458,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             } else {   // WGRAD: A[red = m][row = k] = dy[m][k]
                 int64_t m = kk0 + a_h0[s];
                 if (FAST) {
-                    ok = a_ok[s] && m < Kg;
-                    v = ld4(ok ? ta.a + m * cs.K + a_w0[s] : ta.a);
+                    // an absent element (row beyond the reduction, column beyond K) reads the step's first row instead
+                    const int left = (int)(Kg - kk0 < BK ? Kg - kk0 : BK);
+                    ok = a_ok[s] && a_h0[s] < left;
+                    const bf4 q = buffer_load4(ra, ok ? a_voff[s] : 0u, (unsigned)(kk0 * cs.K) * 4u);
+                    v = make_float4(q.x, q.y, q.z, q.w);
                 } else if (m < Kg) {
                     float e[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -415,7 +472,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 }
             }
             a_reg[s] = v;
-            if (ok) pm |= 1u << s;
+            pm.a[s] = ok;
             every = every && ok;
         }
         // ======== B
@@ -458,12 +515,10 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             } else {   // WGRAD: B[red = m][col = (r,s,c)] = x[n, p*st+r-pad, q*st+s-pad, c]
                 int64_t m = kk0 + b_i0[s];
                 if (FAST) {
-                    int h0 = w_p[s] * cs.stride - cs.pad, w0 = w_q[s] * cs.stride - cs.pad;
-                    int h = h0 + (b_i1[s] >> 24), w = w0 + (b_i2[s] >> 24);
-                    ok = b_ok[s] && m < Kg && (unsigned)h < (unsigned)cs.H && (unsigned)w < (unsigned)cs.W;
-                    v = ld4(ok ? ta.b + ((int64_t)w_n[s] * cs.H * cs.W + (int64_t)h0 * cs.W + w0 + (b_i1[s] & 0xffffff)) * cs.C +
-                                     (b_i2[s] & 0xffffff)
-                               : ta.b);
+                    const unsigned pix = (unsigned)w_row[s], taps = (unsigned)(w_row[s] >> 32);
+                    ok = (taps & w_tapbit[s]) != 0u;
+                    const bf4 q = buffer_load4(rb, ok ? pix + b_voff[s] : (unsigned)b_shift * 4u, 0u);
+                    v = make_float4(q.x, q.y, q.z, q.w);
                 } else if (m < Kg) {
                     int h0 = w_p[s] * cs.stride - cs.pad, w0 = w_q[s] * cs.stride - cs.pad;
                     const float *img = ta.b + (int64_t)w_n[s] * cs.H * cs.W * cs.C;
@@ -486,7 +541,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 }
             }
             b_reg[s] = v;
-            if (ok) pm |= 1u << (16 + s);
+            pm.b[s] = ok;
             every = every && ok;
         }
         // uniform over the wave: when nothing is absent the LDS write below needs no selects (vector instructions that
@@ -500,6 +555,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         } else if (MODE == DGRAD) {
             u_c += BK;
             if (u_c >= cs.K) { u_c = 0; if (++u_s == ns) { u_s = 0; ++u_r; } }
+        } else if (FAST) {
+            // kk0 now names the step after the one just loaded: its table goes into the entry that step's loads will
+            // read; every wave finished reading that entry before the barrier that ended the previous step
+            fill_rows(kk0 / BK, w_slot ^ 1);
+            w_slot ^= 1;
         } else {
 #pragma unroll
             for (int s = 0; s < LB; ++s) {
@@ -512,20 +572,20 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         }
     };
 
-    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB], unsigned pm, int full) {
+    auto store_tiles = [&](int buf, const float4 (&a_reg)[LA], const float4 (&b_reg)[LB], const Present &pm, int full) {
         const float4 zero = make_float4(0, 0, 0, 0);
         auto put = [&](auto whole) {
 #pragma unroll
             for (int s = 0; s < LA; ++s) {
                 int idx = tid + s * NT;
-                float4 v = decltype(whole)::value || ((pm >> s) & 1) ? a_reg[s] : zero;
+                float4 v = decltype(whole)::value || pm.a[s] ? a_reg[s] : zero;
                 if (A_KC) *(float4 *)&As[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
                 else *(float4 *)&As[buf][(idx / (BM / 4)) * A_LD + (idx % (BM / 4)) * 4] = v;
             }
 #pragma unroll
             for (int s = 0; s < LB; ++s) {
                 int idx = tid + s * NT;
-                float4 v = decltype(whole)::value || ((pm >> (16 + s)) & 1) ? b_reg[s] : zero;
+                float4 v = decltype(whole)::value || pm.b[s] ? b_reg[s] : zero;
                 if (B_KC) *(float4 *)&Bs[buf][(idx / 4) * KC_LD + (idx % 4) * 4] = v;
                 else *(float4 *)&Bs[buf][(idx / (BN / 4)) * B_LD + (idx % (BN / 4)) * 4] = v;
             }
@@ -585,8 +645,12 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     // issued into stage t%2.
     if (STAGES == 1 && kt0 < kt1) {
         const int64_t steps = kt1 - kt0;
-        unsigned pm0 = 0;
+        Present pm0{};
         int full0 = 0;
+        if (ROWTAB) {
+            fill_rows(kt0, 0);
+            __syncthreads();
+        }
         load_tiles(a_set0, b_set0, pm0, full0);
         store_tiles(0, a_set0, b_set0, pm0, full0);
         __syncthreads();
@@ -601,9 +665,14 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
         compute((int)((steps - 1) & 1));
     } else if (kt0 < kt1) {
         const int64_t steps = kt1 - kt0;
-        unsigned pm0 = 0, pm1 = 0;
+        Present pm0{}, pm1{};
         int full0 = 0, full1 = 0;
+        if (ROWTAB) {
+            fill_rows(kt0, 0);
+            __syncthreads();
+        }
         load_tiles(a_set0, b_set0, pm0, full0);
+        if (ROWTAB) __syncthreads();    // the second load writes the table entry the first one read
         if (steps > 1) load_tiles(a_set1, b_set1, pm1, full1);
         store_tiles(0, a_set0, b_set0, pm0, full0);
         __syncthreads();
@@ -960,8 +1029,28 @@ size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
     return s >= 2 ? (size_t)(s * tail * bm * bn * 4) : 0;
 }
 
+namespace {
+// floor(n / d) = umulhi(n, mul) >> shift for every n < 2^31 (d >= 2): mul = ceil(2^(31 + l) / d) with l = ceil(log2 d)
+// fits 32 bits, and its excess over 2^(31 + l) / d, below d / 2^(31 + l) <= 2^-31, times n stays below one unit
+void magic_of(unsigned d, unsigned &mul, unsigned &shift) {
+    mul = 0; shift = 0;
+    if (d < 2) return;
+    unsigned l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    mul = (unsigned)((((uint64_t)1 << (31 + l)) + d - 1) / d);
+    shift = l - 1;
+}
+void set_row_magic(TileArgs &ta) {
+    magic_of((unsigned)ta.cs.Q, ta.q_mul, ta.q_shift);
+    magic_of((unsigned)ta.cs.P, ta.p_mul, ta.p_shift);
+}
+}  // namespace
+
 void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red, bool adjoint_use) {
     if (batch < 1 || rows < 1 || cols < 1 || red < 1 || red % BK || cols % 4) throw KernelError("gemm_batched: bad shape");
+    // the aligned loader addresses each operand plane with 32-bit byte offsets
+    if (rows * red * 4 >= ((int64_t)1 << 32) - (1 << 20) || (int64_t)cols * red * 4 >= ((int64_t)1 << 32) - (1 << 20))
+        throw KernelError("gemm_batched: an operand plane of 4 GiB or more");
     ConvShape cs{1, 1, (int)rows, red, cols, 1, 1, 1, 0, 1, (int)rows};
     check_shape(cs);
     TileArgs ta{};
@@ -986,6 +1075,10 @@ void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out,
     ta.Mg = m; ta.Ng = n; ta.Kg = red;
     ta.out_elems = (int64_t)batch * m * n;
     ta.batch_a = red * m; ta.batch_b = red * n; ta.batch_out = (int64_t)m * n;
+    // the aligned loader addresses each operand plane with 32-bit byte offsets
+    if (red * m * 4 >= ((int64_t)1 << 32) - (1 << 20) || red * n * 4 >= ((int64_t)1 << 32) - (1 << 20))
+        throw KernelError("gemm_tn_batched: an operand plane of 4 GiB or more");
+    set_row_magic(ta);
     launch_tile<WGRAD, 2, 2, 3>(st, ta, true, batch, out, splits, ws, ws_bytes, (red + BK - 1) / BK, false, "gemm_tn_batched");
 }
 
@@ -1031,7 +1124,12 @@ void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, cons
     ta.a = dy; ta.b = x; ta.cs = cs;
     ta.Mg = cs.K; ta.Ng = (int)cs.RSC(); ta.Kg = cs.M();
     ta.out_elems = (int64_t)cs.K * cs.RSC();
-    bool fast = cs.K % 4 == 0 && cs.C % 4 == 0;
+    // the aligned loader addresses both operands with 32-bit byte offsets and keeps one bit per filter tap
+    const int64_t span32 = ((int64_t)1 << 32) - (1 << 20);
+    const int64_t lead = ((int64_t)cs.pad * cs.W + cs.pad) * cs.C * 4;
+    bool fast = cs.K % 4 == 0 && cs.C % 4 == 0 && cs.R * cs.S <= 32 && cs.M() * cs.K * 4 < span32 &&
+                (int64_t)cs.N * cs.H * cs.W * cs.C * 4 + lead < span32;
+    set_row_magic(ta);
     launch_cfg<WGRAD>(pick_cfg(WGRAD, ta.Mg, ta.Ng), st, ta, fast, 1, dw, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, false, "conv_wgrad");
 }
 

@@ -481,6 +481,9 @@ WinoPlan wino_plan(const ConvShape &cs, int m, size_t ws_bytes, bool recommend) 
         const size_t have = ws_bytes / sizeof(float);
         wp.imgs = have > wp.filt ? (int)std::min<size_t>((size_t)cs.N, (have - wp.filt) / wp.per_img) : 0;
     }
+    // the batched GEMMs address one position's plane of a chunk with 32-bit byte offsets
+    const size_t plane_img = (size_t)((cs.H + m - 1) / m) * ((cs.W + m - 1) / m) * (size_t)std::max(cs.C, cs.K);
+    wp.imgs = (int)std::min<size_t>((size_t)wp.imgs, (((size_t)1 << 30) - ((size_t)1 << 18)) / plane_img);
     wp.imgs = even_chunk(cs.N, wp.imgs);
     return wp;
 }
