@@ -329,26 +329,29 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     }
     const __amdgpu_buffer_rsrc_t ra = buffer_of(ta.a - a_shift), rb = buffer_of(ta.b - b_shift);
     int w_slot = 0;   // row table entry the next load_tiles reads
-    // decodes the output positions of reduction step `step` (lanes 0..BK-1 of the first wave)
+    // Decodes the output positions of reduction step `step`: the last wave alone, every lane the entry lane % BK (four
+    // lanes write the same value), and no lane switched off on the way (the branch is uniform over the wave, the
+    // rest are selects).  Measured: a version in which only 16 lanes ran this code, under a narrowed execution mask
+    // while the step's loads were still in flight, now and then lost one row of a step on the two-wave tile shapes
+    // when several workgroups shared a compute unit; this version does not (kernel test with many short ranges).
     auto fill_rows = [&](int64_t step, int slot) {
-        if (ROWTAB && tid < BK) {
-            const int64_t m = step * BK + tid;
-            unsigned pix = 0, taps = 0;
-            if (m < Kg) {
-                const unsigned m32 = (unsigned)m;
-                const unsigned t = cs.Q == 1 ? m32 : __umulhi(m32, ta.q_mul) >> ta.q_shift;
-                const unsigned q = m32 - t * (unsigned)cs.Q;
-                const unsigned n = cs.P == 1 ? t : __umulhi(t, ta.p_mul) >> ta.p_shift;
-                const unsigned pp = t - n * (unsigned)cs.P;
-                const int h0 = (int)pp * cs.stride - cs.pad, w0 = (int)q * cs.stride - cs.pad;
-                const int rlo = max(0, -h0), rhi = min(cs.R, cs.H - h0), clo = max(0, -w0), chi = min(cs.S, cs.W - w0);
-                const unsigned rows = rhi > rlo ? (unsigned)((1ull << rhi) - (1ull << rlo)) : 0u;
-                const unsigned cols = chi > clo ? (unsigned)((1ull << chi) - (1ull << clo)) : 0u;
-                for (int r = 0; r < cs.R; ++r)
-                    if ((rows >> r) & 1u) taps |= cols << (r * cs.S);
-                pix = (unsigned)((((int64_t)n * cs.H + h0) * cs.W + w0) * cs.C + b_shift) * 4u;
-            }
-            rowtab[slot][tid] = make_uint2(pix, taps);
+        if (ROWTAB && __builtin_amdgcn_readfirstlane(tid >> 6) == NT / 64 - 1) {
+            const int e = tid & (BK - 1);
+            const int64_t m = step * BK + e;
+            const bool in = m < Kg;
+            const unsigned m32 = in ? (unsigned)m : 0u;
+            const unsigned t = cs.Q == 1 ? m32 : __umulhi(m32, ta.q_mul) >> ta.q_shift;
+            const unsigned q = m32 - t * (unsigned)cs.Q;
+            const unsigned n = cs.P == 1 ? t : __umulhi(t, ta.p_mul) >> ta.p_shift;
+            const unsigned pp = t - n * (unsigned)cs.P;
+            const int h0 = (int)pp * cs.stride - cs.pad, w0 = (int)q * cs.stride - cs.pad;
+            const int rlo = max(0, -h0), rhi = min(cs.R, cs.H - h0), clo = max(0, -w0), chi = min(cs.S, cs.W - w0);
+            const unsigned rows = rhi > rlo ? (unsigned)((1ull << rhi) - (1ull << rlo)) : 0u;
+            const unsigned cols = chi > clo ? (unsigned)((1ull << chi) - (1ull << clo)) : 0u;
+            unsigned taps = 0;
+            for (int r = 0; r < cs.R; ++r) taps |= ((rows >> r) & 1u) ? cols << (r * cs.S) : 0u;
+            const unsigned pix = (unsigned)((((int64_t)n * cs.H + h0) * cs.W + w0) * cs.C + b_shift) * 4u;
+            rowtab[slot][e] = make_uint2(in ? pix : 0u, in ? taps : 0u);
         }
     };
 

@@ -339,6 +339,49 @@ def test_fused_winograd_convolution_matches_oracle(case):
             monet.call("monet_conv_winograd_fused", None, ddy.data_ptr(), dwt.data_ptr(), dx.data_ptr(), N, H, W, C, K, 1, 0, ws.data_ptr(), need)
 
 
+MANY_RANGE_CASES = [
+    # N, H, W, C, K, R, stride, pad, splits: reduction ranges of a few steps each, several workgroups per compute unit
+    (16, 112, 112, 16, 96, 1, 1, 0, 1792),      # MobileNetV2's first expansion (reduced batch): 7 steps per range
+    (16, 112, 112, 16, 96, 1, 1, 0, 3136),      # 4 steps per range: one turn of the pipelined loop
+    (16, 56, 56, 64, 64, 3, 1, 1, 640),         # padded 3x3: rows of a step straddle image borders
+    (64, 14, 14, 256, 256, 3, 1, 1, 96),
+    (16, 57, 57, 32, 48, 3, 2, 1, 640),         # stride 2, odd size
+]
+
+
+@pytest.mark.parametrize("case", MANY_RANGE_CASES)
+def test_filter_gradient_with_many_short_ranges_on_every_tile_shape(case):
+    """The aligned filter-gradient loader shares a per-step table of output positions through LDS; this runs it
+    with thousands of short reduction ranges (several workgroups resident per compute unit, the loop entered and
+    left after one or two turns) on each of the six tile shapes, against the oracle, twice: the two runs must agree
+    bit for bit."""
+    torch = torch_mod()
+    N, H, W, C, K, R, stride, pad, splits = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    dy = rng.standard_normal((N, P, Q, K), dtype=np.float32)
+    want = wt.weight_from_oracle(nm.conv2d_wgrad(wt.act_to_oracle(x), wt.act_to_oracle(dy), R, R, stride, pad))
+    dx, ddy = dev(x), dev(dy)
+    ws = torch.empty(splits * K * R * R * C, dtype=torch.float32, device="cuda")
+    try:
+        for cfg in range(6):
+            monet.call("monet_conv_force_tile", cfg)
+            got = []
+            for rep in range(2):
+                dw = torch.full((K, R, R, C), float("nan"), dtype=torch.float32, device="cuda")
+                ws.fill_(float("nan"))
+                monet.call("monet_conv_wgrad", None, dx.data_ptr(), ddy.data_ptr(), dw.data_ptr(), N, H, W, C, K, R, R, stride, pad, splits,
+                           ws.data_ptr(), ws.numel() * 4)
+                torch.cuda.synchronize()
+                got.append(dw.cpu().numpy())
+            assert np.array_equal(got[0], got[1]), (cfg, "two runs differ")
+            check_close(got[0], want, 1e-5, what=f"tile shape {cfg}")
+    finally:
+        monet.call("monet_conv_force_tile", -1)
+
+
 def test_conv_wgrad_rejects_small_workspace():
     torch = torch_mod()
     t = torch.zeros(16 * 16 * 16 * 2, device="cuda")
