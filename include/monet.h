@@ -93,6 +93,11 @@ int64_t monet_plan_exact_peak(const monet_plan *plan);
  * and the no-recomputation term of Appendix C.2): always >= the exact peak. */
 int64_t monet_plan_predicted_peak(const monet_plan *plan);
 
+/* The same bound with Appendix B's tighter local sets L-dot (before backward stage k only operators up to
+ * the stage's own node can be recomputed, so only their inputs count as local):
+ * exact peak <= this <= monet_plan_predicted_peak. */
+int64_t monet_plan_predicted_peak_tight(const monet_plan *plan);
+
 /* Bytes of device memory the caller must bind: the physical high-water mark of the arena
  * (>= exact peak; the difference is fragmentation) plus the constant part (BatchNorm
  * statistics, loss scalar, reduction scratch). */

@@ -303,10 +303,12 @@ def interpret(graph_text, schedule_text, exts=None, params=None, check=True):
 def closed_form(graph_text, schedule_text):
     """Peak memory from the formulas alone.
 
-    Returns dict(m_fwd{i}, m_bwd{k}, m_rec{(i,k)}, m_rec_bar{(i,k)}, m_keep_bar{(i,k)},
-    exact_peak, predicted_peak): `exact_peak` uses the true L_i^k of Section 3,
+    Returns dict(m_fwd{i}, m_bwd{k}, m_rec{(i,k)}, m_rec_dot{(i,k)}, m_rec_bar{(i,k)}, m_keep_bar{(i,k)},
+    exact_peak, tight_peak, predicted_peak): `exact_peak` uses the true L_i^k of Section 3,
     `predicted_peak` the upper bound L-bar_i^k of Appendix B plus the
-    no-recomputation term of Appendix C.2.
+    no-recomputation term of Appendix C.2, `tight_peak` the same with Appendix B's
+    tighter set L-dot_i^k (only operators up to the stage's own node can be recomputed
+    before it, so only their inputs have to be counted as local).
     """
     g = OGraph(graph_text)
     sch = OSchedule(schedule_text, g)
@@ -343,7 +345,7 @@ def closed_form(graph_text, schedule_text):
         return sum(sz[j] for j in born if born[j] > k >= dies[j])
 
     # ---- Eq. 5 and Eq. 3
-    m_bwd, m_rec, m_rec_bar, m_keep_bar = {}, {}, {}, {}
+    m_bwd, m_rec, m_rec_dot, m_rec_bar, m_keep_bar = {}, {}, {}, {}, {}
     for k in range(B, 0, -1):
         b = g.bops[k]
         impl = b.impls[sch.stage_impl[k]]
@@ -365,14 +367,17 @@ def closed_form(graph_text, schedule_text):
                 m_rec[(i, k)] = head + sum(sz[j] for j in L_ik | S_ik | D_lt) + later
                 Lbar = {j for j in range(1, i) if any(t >= i for t in g.consumers[j])}
                 m_rec_bar[(i, k)] = head + sum(sz[j] for j in Lbar | S_ik | D_lt) + later
+                Ldot = {j for j in range(1, i) if any(i <= t <= b.node for t in g.consumers[j])}
+                m_rec_dot[(i, k)] = head + sum(sz[j] for j in Ldot | S_ik | D_lt) + later
             else:
                 S_le = {j for j in range(1, i + 1) if j in sch.s[k]}
                 D_le = {j for j in D if j <= i}
                 m_keep_bar[(i, k)] = Lhat(k) + sum(sz[j] for j in S_le | D_le) + later
     exact = max(list(m_fwd.values()) + list(m_bwd.values()) + list(m_rec.values()))
     pred = max(list(m_fwd.values()) + list(m_bwd.values()) + list(m_rec_bar.values()) + list(m_keep_bar.values()))
-    return dict(m_fwd=m_fwd, m_bwd=m_bwd, m_rec=m_rec, m_rec_bar=m_rec_bar, m_keep_bar=m_keep_bar,
-                exact_peak=exact, predicted_peak=pred)
+    tight = max(list(m_fwd.values()) + list(m_bwd.values()) + list(m_rec_dot.values()) + list(m_keep_bar.values()))
+    return dict(m_fwd=m_fwd, m_bwd=m_bwd, m_rec=m_rec, m_rec_dot=m_rec_dot, m_rec_bar=m_rec_bar, m_keep_bar=m_keep_bar,
+                exact_peak=exact, tight_peak=tight, predicted_peak=pred)
 
 
 def objective(graph_text, schedule_text):

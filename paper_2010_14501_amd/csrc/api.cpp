@@ -85,6 +85,7 @@ extern "C" int monet_plan_load(const char *graph, size_t graph_len, const char *
 extern "C" void monet_free(monet_plan *p) { delete p; }
 extern "C" int64_t monet_plan_exact_peak(const monet_plan *p) { return p ? p->plan.exact_peak : MONET_BAD_ARGUMENT; }
 extern "C" int64_t monet_plan_predicted_peak(const monet_plan *p) { return p ? p->plan.predicted_peak : MONET_BAD_ARGUMENT; }
+extern "C" int64_t monet_plan_predicted_peak_tight(const monet_plan *p) { return p ? p->plan.predicted_peak_tight : MONET_BAD_ARGUMENT; }
 extern "C" int64_t monet_plan_arena_bytes(const monet_plan *p) { return p ? p->plan.persistent_bytes + p->plan.dynamic_bytes : MONET_BAD_ARGUMENT; }
 extern "C" int64_t monet_plan_persistent_bytes(const monet_plan *p) { return p ? p->plan.persistent_bytes : MONET_BAD_ARGUMENT; }
 extern "C" int monet_plan_num_params(const monet_plan *p) { return p ? (int)p->plan.g.params.size() : MONET_BAD_ARGUMENT; }

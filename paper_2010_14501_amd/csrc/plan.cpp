@@ -660,7 +660,14 @@ void Plan::closed_form() {
             for (int t : g.nodes[j].consumers) if (t >= i) { s.insert(j); break; }
         return s;
     };
-    int64_t best = 0;
+    // L-dot_i^k (Appendix B): of those, only what an operator up to the stage's own node reads
+    auto Ldot = [&](int i, int last) {
+        std::set<int> s;
+        for (int j = 1; j < i; ++j)
+            for (int t : g.nodes[j].consumers) if (t >= i && t <= last) { s.insert(j); break; }
+        return s;
+    };
+    int64_t best = 0, tight = 0;
     for (int i = 1; i <= N; ++i) {
         const Node &n = g.nodes[i];
         if (n.aux) continue;
@@ -671,6 +678,7 @@ void Plan::closed_form() {
         for (int j : fsave) if (j < i) u.insert(j);
         best = std::max(best, ws_of(im.ws) + own_out(n, im, emit) + bytes_of_set(u));
     }
+    tight = best;
     // gradient tensors: born at the highest stage writing them, gone after the lowest stage of their node
     std::map<int, int> born, dies;
     for (int k = 1; k <= B; ++k) {
@@ -692,6 +700,7 @@ void Plan::closed_form() {
         std::set<int> u = D;
         u.insert(sch.s[k].begin(), sch.s[k].end());
         best = std::max(best, ws_of(im.ws) + yk + lhat + bytes_of_set(u));
+        tight = std::max(tight, ws_of(im.ws) + yk + lhat + bytes_of_set(u));
         const auto &enter = sch.entering(k, B, fsave);
         const auto &rk = sch.r[k];
         for (int i = 1; i <= N; ++i) {
@@ -708,14 +717,20 @@ void Plan::closed_form() {
                 for (int j : sch.s[k]) if (j < i) u2.insert(j);
                 for (int j : D) if (j < i) u2.insert(j);
                 best = std::max(best, ws_of(fi.ws) + own_out(n, fi, emit) + lhat + bytes_of_set(u2) + later);
+                std::set<int> u3 = Ldot(i, b.node);
+                for (int j : sch.s[k]) if (j < i) u3.insert(j);
+                for (int j : D) if (j < i) u3.insert(j);
+                tight = std::max(tight, ws_of(fi.ws) + own_out(n, fi, emit) + lhat + bytes_of_set(u3) + later);
             } else {
                 for (int j : sch.s[k]) if (j <= i) u2.insert(j);
                 for (int j : D) if (j <= i) u2.insert(j);
                 best = std::max(best, lhat + bytes_of_set(u2) + later);
+                tight = std::max(tight, lhat + bytes_of_set(u2) + later);
             }
         }
     }
     predicted_peak = best;
+    predicted_peak_tight = tight;
 }
 
 void Plan::build(const std::string &graph_text, const std::string &schedule_text) {

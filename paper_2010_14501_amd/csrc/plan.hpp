@@ -126,7 +126,7 @@ struct Plan {
     int64_t scratch_off = 0, scratch_bytes = 0;
     int64_t persistent_bytes = 0;
     int64_t dynamic_bytes = 0;   // physical high-water mark of the arena
-    int64_t exact_peak = 0, predicted_peak = 0;
+    int64_t exact_peak = 0, predicted_peak = 0, predicted_peak_tight = 0;
 
     void build(const std::string &graph_text, const std::string &schedule_text);
 

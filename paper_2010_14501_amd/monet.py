@@ -46,7 +46,8 @@ def load_library():
     lib.monet_last_error.restype = C.c_char_p
     lib.monet_plan_load.argtypes = [C.c_char_p, sz, C.c_char_p, sz, C.POINTER(vp)]
     lib.monet_plan_load.restype = i32
-    for name in ("monet_plan_exact_peak", "monet_plan_predicted_peak", "monet_plan_arena_bytes", "monet_plan_persistent_bytes"):
+    for name in ("monet_plan_exact_peak", "monet_plan_predicted_peak", "monet_plan_predicted_peak_tight", "monet_plan_arena_bytes",
+                 "monet_plan_persistent_bytes"):
         getattr(lib, name).argtypes = [vp]
         getattr(lib, name).restype = i64
     for name in ("monet_plan_num_params", "monet_plan_num_inputs"):
@@ -168,6 +169,7 @@ class Plan:
 
     exact_peak = property(lambda s: _check(s._lib.monet_plan_exact_peak(s._h)))
     predicted_peak = property(lambda s: _check(s._lib.monet_plan_predicted_peak(s._h)))
+    predicted_peak_tight = property(lambda s: _check(s._lib.monet_plan_predicted_peak_tight(s._h)))
     arena_bytes = property(lambda s: _check(s._lib.monet_plan_arena_bytes(s._h)))
     persistent_bytes = property(lambda s: _check(s._lib.monet_plan_persistent_bytes(s._h)))
     num_params = property(lambda s: _check(s._lib.monet_plan_num_params(s._h)))

@@ -154,3 +154,24 @@ def test_committed_full_size_solutions_are_valid_schedules_within_their_budgets(
         store = M.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak
         assert plan.predicted_peak < (float(frac) + 0.005) * store, path
         assert sum(1 for e in plan.trace_tuples() if e[0] == M.RUN_RECOMPUTE) > 0
+
+
+def test_program_with_the_tighter_local_bound():
+    """Appendix B's L-dot bound as an option of the program: every solution of the L-bar program stays feasible, so
+    the optimum (both programs solved to optimality) can only improve; the solution's tight predicted peak (closed
+    form of the oracle, and the planner's) stays within the budget and above the exact peak."""
+    g = graphs.resnet50(batch=2, hw=32, classes=10, widths=(4, 8, 8, 16), depths=(1, 1, 1, 1), stem=4)
+    gt = g.text()
+    budget = int(0.7 * M.Plan(gt, schedules.store_everything_schedule(g).text()).predicted_peak)
+    loose, obj_loose, status = ilp.solve(g, budget, time_limit=200)
+    tight, obj_tight, status_t = ilp.solve(g, budget, time_limit=200, tight_local=True)
+    assert loose is not None and tight is not None and "successfully" in status and "successfully" in status_t, (status, status_t)
+    st = tight.text()
+    og = osch.OGraph(gt)
+    osch.validate(og, osch.OSchedule(st, og))
+    cf = osch.closed_form(gt, st)
+    plan = M.Plan(gt, st)
+    assert cf["exact_peak"] == plan.exact_peak <= cf["tight_peak"] == plan.predicted_peak_tight <= budget
+    assert plan.predicted_peak_tight <= plan.predicted_peak
+    assert abs(osch.objective(gt, st) - obj_tight) <= 1e-9 * obj_tight
+    assert obj_tight <= obj_loose * (1 + 1e-9), (obj_tight, obj_loose)

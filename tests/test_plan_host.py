@@ -34,6 +34,7 @@ def check_against_oracle(g, sch):
     assert plan.trace_tuples() == want["events"]
     assert plan.exact_peak == want["peak"] == cf["exact_peak"]
     assert plan.predicted_peak == cf["predicted_peak"]
+    assert plan.exact_peak <= plan.predicted_peak_tight == cf["tight_peak"] <= plan.predicted_peak
     assert plan.arena_bytes - plan.persistent_bytes >= plan.exact_peak
     return plan
 

@@ -84,8 +84,11 @@ class _Rows:
         self.hi.append(hi)
 
 
-def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, allow_inplace=True, recompute_blocks=None):
-    """Cheapest schedule whose predicted peak (the L-bar bound) stays within `budget_bytes`.
+def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, allow_inplace=True, recompute_blocks=None,
+          tight_local=False):
+    """Cheapest schedule whose predicted peak (the L-bar bound; with `tight_local` Appendix B's tighter L-dot bound,
+    which counts as local to a recomputation before stage k only the inputs of operators up to the stage's own node)
+    stays within `budget_bytes`.
 
     `tau` optionally maps ("f", node, l) / ("r", node, l) / ("b", k, l) to a cost; missing entries fall back to
     the graph's own cost fields.  `recompute_blocks` = w restricts the program: stage k may recompute only nodes of
@@ -298,6 +301,8 @@ def solve(g: Graph, budget_bytes, tau=None, time_limit=120.0, mip_rel_gap=0.0, a
             if i not in rv[k] or is_aux[i]:
                 continue
             Lset = set(Lstat[i])
+            if tight_local:
+                Lset = {j for j in Lset if any(i <= t <= fk[k] for t in consumers[j])}
             const = Lhat[k] + sum(sz[j] for j in Lset)
             terms = [(drc[k][i][l], wsb(g.fimpls[i][l]) - (sz[i] if inplace(i, l) else 0.0)) for l in range(len(g.fimpls[i]))]
             terms += [(rv[k][i], sz[i] + BIG)]
