@@ -86,6 +86,21 @@ int64_t monet_conv_winograd_workspace_bytes(int N, int H, int W, int C, int K, i
 int monet_conv_winograd_fused(void *stream, const float *in, const float *w, float *out, int N, int H, int W, int C, int K,
                               int adjoint, int accumulate, float *ws, size_t ws_bytes);
 int64_t monet_conv_winograd_fused_workspace_bytes(int N, int H, int W, int C, int K, int adjoint);
+/* Convolution through an explicit patch matrix (Section 4 "Forward Operator Optimization" / Appendix I: the
+ * matrix-multiplication form of a convolution, one of the implementations whose workspace the solver trades against
+ * time).  The patches of a chunk of whole images are written to the workspace as rows of R*S*C floats (padded with
+ * zeros to a multiple of 16), then the chunk is one GEMM: y = col W^T (forward; accumulate != 0 adds into y), or
+ * dW = sum over chunks of dy^T col (filter gradient, chunks added in image order).  Same tensors and layouts as
+ * monet_conv_fwd / monet_conv_wgrad (device pointers, NHWC, filters K x R x S x C); needs K % 4 == 0.  ws / ws_bytes:
+ * device workspace owned by the caller; its size decides the chunk (at least the patches of one image, the padded
+ * filters and, for the filter gradient, the chunk's K x round_up(R*S*C, 16) result with its split-reduction parts;
+ * MONET_BAD_ARGUMENT otherwise).  monet_conv_im2col_workspace_bytes gives the recommended size (chunks of about
+ * 256 MiB of patches; wgrad != 0 for the filter gradient).  Results agree with the implicit GEMM to rounding. */
+int monet_conv_im2col_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
+                          int stride, int pad, int accumulate, float *ws, size_t ws_bytes);
+int monet_conv_im2col_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R, int S,
+                            int stride, int pad, float *ws, size_t ws_bytes);
+int64_t monet_conv_im2col_workspace_bytes(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int wgrad);
 /* Filter gradient of such a layer in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
  * (C % 4 == 0, K % 4 == 0).  Workspace: the transformed input and output gradient of one chunk of images (as above),
  * two buffers of P*K*C floats (the transformed filter gradient and one chunk's share of it, added chunk after chunk)

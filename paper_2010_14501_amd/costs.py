@@ -102,7 +102,8 @@ def main():
               schedules.store_everything_schedule(g, plain),       # workspace-free convolutions, ReLU from input
               schedules.block_output_schedule(g, schedules.IGEMM_VARIANTS),   # split implicit GEMM where Winograd is preferred
               schedules.block_output_schedule(g, schedules.WINOGRAD2_VARIANTS),   # Winograd with 2x2 output tiles where offered
-              schedules.block_output_schedule(g, schedules.WINOGRAD_WS_VARIANTS)]   # 4x4 tiles through the workspace where the one-kernel form is preferred
+              schedules.block_output_schedule(g, schedules.WINOGRAD_WS_VARIANTS),   # 4x4 tiles through the workspace where the one-kernel form is preferred
+              schedules.block_output_schedule(g, schedules.IM2COL_VARIANTS)]   # explicit patch matrix + GEMM for every filter larger than 1x1
     tau = measure(g.text(), [s.text() for s in scheds], exts, params, args.steps)
     lines = [f"# operator cost table, workload {args.workload}, one MI355X, fp32; times are medians of {args.steps} steps",
              f"# python -m paper_2010_14501_amd.costs --workload {args.workload} --out {args.out}"] + table_lines(g, tau)

@@ -233,7 +233,9 @@ void run_forward(const StepCtx &c, const Launch &L, const BnAffine *affine = nul
     const std::string &op = n.op;
     if (op == "conv") {
         const FwdImpl &im = n.fimpls[L.impl];
-        if (winograd_is_fused(im.algo))
+        if (im.algo == "im2col")
+            conv_im2col_fwd(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws), false);
+        else if (winograd_is_fused(im.algo))
             conv_winograd_fused(c.st, in0, c.weights[n.pars[0]], out, conv_shape(g, n), false, false, (float *)c.ptr(L.a[4]),
                                 (size_t)align_up(im.ws), affine);
         else if (const int m = winograd_tile(im.algo))
@@ -300,7 +302,9 @@ void run_backward(const StepCtx &c, const Launch &L) {
     const bool acc0 = L.flags & 1;
     const std::string &kd = b.kind;
     if (kd == "conv_wgrad") {
-        if (const int m = winograd_tile(im.algo))
+        if (im.algo == "im2col")
+            conv_im2col_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), (float *)c.ptr(L.a[4]), (size_t)align_up(im.ws));
+        else if (const int m = winograd_tile(im.algo))
             conv_winograd_wgrad(c.st, (const float *)dep, gy, c.grads[n.pars[0]], conv_shape(g, n), m, (float *)c.ptr(L.a[4]),
                                 (size_t)align_up(im.ws));
         else
@@ -500,7 +504,7 @@ bool conv_feeds_bn_stats(const Plan &pl, const Launch &L1, const Launch &L2) {
     const Node &cv = g.nodes[L1.id], &bn = g.nodes[L2.id];
     if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
     const ConvShape cs = conv_shape(g, cv);
-    if (winograd_tile(cv.fimpls[L1.impl].algo)) return false;
+    if (winograd_tile(cv.fimpls[L1.impl].algo) || cv.fimpls[L1.impl].algo == "im2col") return false;
     if (cs.C % 16 || cs.K % 4 || splits_of(cv.fimpls[L1.impl].algo, cv.fimpls[L1.impl].extra) != 1) return false;
     return bn_stats_in_row_groups(cs.M(), cs.K, (size_t)pl.scratch_bytes);
 }
@@ -518,6 +522,7 @@ bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
     const ConvShape cs = conv_shape(g, cv);
     if (cv.op == "dwconv") return dwconv_fwd_takes_affine(cs);
     const FwdImpl &im = cv.fimpls[L1.impl];
+    if (im.algo == "im2col") return false;
     if (winograd_is_fused(im.algo)) return winograd_fused_applies(cs, false);
     if (winograd_tile(im.algo)) return winograd_applies(cs, false);
     return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
@@ -1025,6 +1030,19 @@ extern "C" int monet_maxpool_fwd(void *stream, const float *x, float *y, uint8_t
 extern "C" int monet_maxpool_bwd(void *stream, const float *dy, const float *x, const uint8_t *idx, float *dx, int N, int H, int W, int C,
                                  int k, int stride, int pad, int accumulate) {
     return guarded([&] { maxpool_bwd((hipStream_t)stream, dy, x, idx, dx, mk_pool(N, H, W, C, k, stride, pad), accumulate != 0); });
+}
+extern "C" int monet_conv_im2col_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
+                                     int stride, int pad, int accumulate, float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_im2col_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, C, K, R, S, stride, pad), ws, ws_bytes, accumulate != 0); });
+}
+extern "C" int monet_conv_im2col_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R,
+                                       int S, int stride, int pad, float *ws, size_t ws_bytes) {
+    return guarded([&] { conv_im2col_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, R, S, stride, pad), ws, ws_bytes); });
+}
+extern "C" int64_t monet_conv_im2col_workspace_bytes(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int wgrad) {
+    int64_t bytes = 0;
+    int rc = guarded([&] { bytes = (int64_t)conv_im2col_workspace_bytes(mk_conv(N, H, W, C, K, R, S, stride, pad), wgrad != 0); });
+    return rc == MONET_OK ? bytes : rc;
 }
 extern "C" int monet_conv_force_tile(int cfg) {
     if (cfg < -1 || cfg > 5) { g_err = "monet_conv_force_tile: cfg must be -1..5"; return MONET_BAD_ARGUMENT; }

@@ -85,6 +85,13 @@ void dwconv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, co
 // two-level fixed-order reduction; scratch holds slabs * R*S*C floats
 void dwconv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *scratch, size_t scratch_bytes);
 
+// Convolution through an explicit patch matrix of a chunk of whole images (im2col.hip): workspace decides the chunk.
+bool conv_im2col_applies(const ConvShape &cs);
+size_t conv_im2col_workspace_bytes(const ConvShape &cs, bool wgrad);      // recommended (patches of about 256 MiB per chunk)
+void conv_im2col_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, float *ws, size_t ws_bytes,
+                     bool accumulate);
+void conv_im2col_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *ws, size_t ws_bytes);
+
 // tuning aid: cfg 0..5 forces tile shape (2x2, 4x1, 1x4, 2x1, 1x2, 1x1 waves of 64x64); -1 restores the heuristic
 void conv_force_tile(int cfg);
 // workspace bytes of conv_fwd (which = 0) / conv_dgrad (which = 1) for `splits` ranges; for splits = 1 the bytes

@@ -254,7 +254,7 @@ static void check_declared_deps(const Graph &g) {
                 if (n.aux_children.empty()) throw PlanError(MONET_BAD_GRAPH, "node " + std::to_string(n.id) + " has no intermediate node");
                 want.push_back(n.aux_children[0]);
             };
-            if (b.kind == "conv_wgrad") { known = (algo == "direct" || algo == "splitk" || algo == "winograd" || algo == "winograd4"); input0(); }
+            if (b.kind == "conv_wgrad") { known = (algo == "direct" || algo == "splitk" || algo == "winograd" || algo == "winograd4" || algo == "im2col"); input0(); }
             else if (b.kind == "conv_dgrad") { known = (algo == "igemm" || algo == "igemm_splitk" || algo == "winograd" || algo == "winograd4" || algo == "winograd4f"); }
             else if (b.kind == "tconv_wgrad") { known = (algo == "direct" || algo == "splitk"); input0(); }
             else if (b.kind == "tconv_dgrad") { known = algo == "igemm"; }

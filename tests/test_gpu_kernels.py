@@ -339,6 +339,58 @@ def test_fused_winograd_convolution_matches_oracle(case):
             monet.call("monet_conv_winograd_fused", None, ddy.data_ptr(), dwt.data_ptr(), dx.data_ptr(), N, H, W, C, K, 1, 0, ws.data_ptr(), need)
 
 
+IM2COL_CASES = [
+    # N, H, W, C, K, R, stride, pad, chunk images (0: the recommended workspace)
+    (2, 16, 16, 16, 16, 3, 1, 1, 0),
+    (5, 14, 14, 64, 128, 3, 1, 1, 2),      # three chunks, the last one ragged
+    (3, 15, 13, 32, 80, 3, 2, 1, 1),       # stride 2, odd sizes, one image per chunk
+    (2, 32, 32, 3, 64, 7, 2, 3, 0),        # stem: 147 floats per patch, padded to 160 (filters padded too)
+    (2, 9, 9, 20, 24, 3, 1, 1, 0),         # R*S*C = 180, padded to 192
+    (4, 7, 7, 512, 512, 3, 1, 1, 3),
+]
+
+
+@pytest.mark.parametrize("case", IM2COL_CASES)
+def test_convolution_through_patch_matrix_matches_oracle(case):
+    """Forward (plain and accumulating) and filter gradient of the explicit patch-matrix form against the oracle, with
+    the recommended workspace and with workspaces that force several chunks; a workspace below one image is refused."""
+    torch = torch_mod()
+    N, H, W, C, K, R, stride, pad, chunk = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, C), dtype=np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    dy = rng.standard_normal((N, P, Q, K), dtype=np.float32)
+    y0 = rng.standard_normal((N, P, Q, K), dtype=np.float32)
+    xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
+    want_y = wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad))
+    want_w = wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, R, R, stride, pad))
+    dx, dwt, ddy = dev(x), dev(w), dev(dy)
+    ld = -(-(C * R * R) // 16) * 16
+    sizes = {}
+    for wgrad in (0, 1):
+        rec = monet.call("monet_conv_im2col_workspace_bytes", N, H, W, C, K, R, R, stride, pad, wgrad)
+        if chunk:       # exactly `chunk` images of patches (+ padded filters / the gradient's tail, taken from the recommendation)
+            rec_imgs_bytes = rec - 4 * min(N, max(1, (256 << 20) // 4 // (P * Q * ld))) * P * Q * ld
+            rec = 4 * chunk * P * Q * ld + max(rec_imgs_bytes, 0) + (4 * K * ld * 260 if wgrad else 0)
+        sizes[wgrad] = rec
+    ws = torch.full((max(sizes.values()) // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    y = torch.empty((N, P, Q, K), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_im2col_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0, ws.data_ptr(), sizes[0])
+    check_close(y.cpu().numpy(), want_y, ACT_TOL, what="forward")
+    yacc = dev(y0)
+    monet.call("monet_conv_im2col_fwd", None, dx.data_ptr(), dwt.data_ptr(), yacc.data_ptr(), N, H, W, C, K, R, R, stride, pad, 1, ws.data_ptr(), sizes[0])
+    check_close(yacc.cpu().numpy(), want_y + y0, ACT_TOL, what="forward, accumulating")
+    ws.fill_(float("nan"))
+    dw = torch.full((K, R, R, C), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_im2col_wgrad", None, dx.data_ptr(), ddy.data_ptr(), dw.data_ptr(), N, H, W, C, K, R, R, stride, pad, ws.data_ptr(), sizes[1])
+    check_close(dw.cpu().numpy(), want_w, GRAD_TOL, what="filter gradient")
+    with pytest.raises(M.MonetError):
+        monet.call("monet_conv_im2col_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, C, K, R, R, stride, pad, 0, ws.data_ptr(),
+                   4 * (P * Q * ld - 16))
+
+
 MANY_RANGE_CASES = [
     # N, H, W, C, K, R, stride, pad, splits: reduction ranges of a few steps each, several workgroups per compute unit
     (16, 112, 112, 16, 96, 1, 1, 0, 1792),      # MobileNetV2's first expansion (reduced batch): 7 steps per range

@@ -207,8 +207,12 @@ NETS = {
     "mbv2_full": lambda: graphs.mobilenet_v2(batch=2),
     "unet_full": lambda: graphs.unet(batch=1),
 }
-VARIANT_SETS = {"default": schedules.DEFAULT_VARIANTS, "igemm": schedules.IGEMM_VARIANTS}
-CASES = [(name, "default") for name in NETS] + [(name, "igemm") for name in NETS if name.endswith("_full")]
+VARIANT_SETS = {"default": schedules.DEFAULT_VARIANTS, "igemm": schedules.IGEMM_VARIANTS, "im2col": schedules.IM2COL_VARIANTS}
+# the explicit patch-matrix form of every 3x3 / 7x7 convolution (forward, recomputation, filter gradient): a small
+# network of each family with 3x3 layers, the inception network at 224x224 (7x7 / stride 2 stem with 3 input channels,
+# R*S*C no multiple of 16) and VGG-16 at full resolution (several chunks per layer)
+CASES = ([(name, "default") for name in NETS] + [(name, "igemm") for name in NETS if name.endswith("_full")] +
+         [(name, "im2col") for name in ("vgg", "unet", "googlenet_wide", "vgg_full")])
 
 
 @pytest.mark.parametrize("name,vname", CASES)

@@ -162,6 +162,24 @@ class Graph:
             self.fimpls[i].append(dict(algo="winograd4", ws=wino_ws(4), cost=flop * 0.4))
         if wino4f:
             self.fimpls[i].append(dict(algo="winograd4f", ws=_align(4 * 36 * (-(-K // 64) * 64) * C), cost=flop * 0.3))
+        # Explicit patch matrix + GEMM (the matrix-multiplication form): patches of a chunk of whole images in the
+        # workspace (mirrors the library's recommendation: about 256 MiB of patches per chunk, rows padded to 16
+        # floats, a padded filter copy where R*S*C is no multiple of 16).  Offered for every filter larger than 1x1;
+        # it moves R*S times the input through memory, so it loses to the implicit GEMM almost everywhere (measured
+        # costs decide).  Appended last: implementation indices of schedules written before it existed stay valid.
+        im2col = (R * S > 1) and K % 4 == 0
+        ld = -(-(C * R * S) // 16) * 16
+
+        def col_imgs():
+            cap = max(1, min(N, (256 << 20) // 4 // (P * Q * ld)))
+            span = (((1 << 30) - (1 << 18)) // max(ld, K)) // (P * Q)
+            cap = min(cap, max(span, 1))
+            chunks = -(-N // cap)
+            return -(-N // chunks)
+
+        if im2col:
+            wpad = K * ld if ld != C * R * S else 0
+            self.fimpls[i].append(dict(algo="im2col", ws=_align(4 * (wpad + col_imgs() * P * Q * ld)), cost=flop * 1.5))
         dg = [dict(algo="igemm", deps=[], ws=0, cost=flop)]
         if wino:
             dg.append(dict(algo="winograd", deps=[], ws=wino_ws(2), cost=flop * 0.6))
@@ -181,6 +199,12 @@ class Graph:
             wg.append(dict(algo="winograd", cost=flop * 0.65, ws=wino_wgrad_ws(2)))
         if wino4_wgrad:
             wg.append(dict(algo="winograd4", cost=flop * 0.45, ws=wino_wgrad_ws(4)))
+        if im2col:      # patches of a chunk, the chunk's K x ld result and the parts of its split reduction
+            imgs = col_imgs()
+            steps = -(-(imgs * P * Q) // 16)
+            tiles = -(-K // 128) * -(-ld // 128)
+            sp = max(1, min(-(-512 // tiles), steps // 4, 256))
+            wg.append(dict(algo="im2col", cost=flop * 1.5, ws=_align(4 * (imgs * P * Q * ld + K * ld * (1 + (sp if sp > 1 else 0))))))
         self._pending_bops(i, [("conv_dgrad", dg)] if x > 0 else [],
                            [("conv_wgrad", [dict(d, deps=[x] if x > 0 else []) for d in wg])])
         return i

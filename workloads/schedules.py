@@ -40,6 +40,8 @@ WINOGRAD_WS_VARIANTS = dict(DEFAULT_VARIANTS, conv_dgrad=("winograd4", "winograd
 # Winograd with 2x2 output tiles where it is offered (the 4x4 form is faster and smaller wherever both are)
 WINOGRAD2_VARIANTS = dict(DEFAULT_VARIANTS, conv_wgrad=("winograd", "splitk"), conv_dgrad=("winograd", "igemm_splitk"),
                           conv_fwd=("winograd", "igemm_splitk"))
+# every convolution with a filter larger than 1x1 through the explicit patch matrix (forward and filter gradient)
+IM2COL_VARIANTS = dict(DEFAULT_VARIANTS, conv_wgrad=("im2col", "splitk"), conv_fwd=("im2col", "igemm_splitk"))
 STANDARD_VARIANTS = dict(
     bn_bwd="from_input", relu_bwd="from_output", relu6_bwd="from_output", maxpool_bwd="from_input",
     conv_wgrad=("winograd4", "winograd", "splitk"), tconv_wgrad="splitk", conv_dgrad=("winograd4f", "winograd4", "winograd", "igemm_splitk"),
