@@ -439,8 +439,8 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
         int64_t r = r0 + tr;
         for (; r + RPP < r1; r += 2 * RPP) {
             const int64_t ia = r * C4 + cg, ib = (r + RPP) * C4 + cg;
-            const f4 ga = __builtin_nontemporal_load((const f4 *)dy + ia), va = __builtin_nontemporal_load((const f4 *)t + ia);
-            const f4 gb = __builtin_nontemporal_load((const f4 *)dy + ib), vb = __builtin_nontemporal_load((const f4 *)t + ib);
+            const f4 ga = (*((const f4 *)dy + ia)), va = (*((const f4 *)t + ia));
+            const f4 gb = (*((const f4 *)dy + ib)), vb = (*((const f4 *)t + ib));
             f4 ra = f4{0, 0, 0, 0}, rb = f4{0, 0, 0, 0};
             if (RM >= 2) { ra = __builtin_nontemporal_load((const f4 *)rt + ia); rb = __builtin_nontemporal_load((const f4 *)rt + ib); }
             accumulate(ga, va, ra, ia);
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
             const int64_t ia = r * C4 + cg;
             f4 ra = f4{0, 0, 0, 0};
             if (RM >= 2) ra = __builtin_nontemporal_load((const f4 *)rt + ia);
-            accumulate(__builtin_nontemporal_load((const f4 *)dy + ia), __builtin_nontemporal_load((const f4 *)t + ia), ra, ia);
+            accumulate((*((const f4 *)dy + ia)), (*((const f4 *)t + ia)), ra, ia);
         }
     }
 #pragma unroll
@@ -544,7 +544,10 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
         }
     };
     const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
-    const int64_t r0 = (int64_t)blockIdx.x * per;
+    // The ranges are taken from the end of the tensor backwards and dy / t are read with ordinary (cached) loads: the
+    // partial-sum pass has just read both tensors front to back, so what it read last is what the memory-side cache
+    // still holds (measured: 2-3 % on the ResNet-50 layers against front-to-back streaming loads).
+    const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * per;
     const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
     if (fixed) load((int)(threadIdx.x % C4));
     for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
@@ -556,8 +559,8 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
             bits[u] = 0;
             rv[u] = f4{0, 0, 0, 0};
             if (i >= r1) continue;
-            g[u] = __builtin_nontemporal_load((const f4 *)dy + i);
-            v[u] = __builtin_nontemporal_load((const f4 *)t + i);
+            g[u] = (*((const f4 *)dy + i));
+            v[u] = (*((const f4 *)t + i));
             if (acc) o[u] = __builtin_nontemporal_load((const f4 *)dx + i);
             if (RM == 1) bits[u] = (unsigned)(mask[i >> 4] >> ((i & 15) * 4)) & 15u;
             if (RM >= 2) rv[u] = __builtin_nontemporal_load((const f4 *)rt + i);

@@ -68,17 +68,33 @@ def test_integer_program_schedule_at_full_size(full):
     assert abs(other.loss_value() - loss) < 1e-4 * abs(loss)
     got = other.grads_numpy()
     del other
-    # Reference: the block-output run with the convolution implementations the stored schedule was priced with (Winograd
-    # through the workspace).  Two runs whose convolutions round differently take a few of the 1.7 billion ReLU sign
-    # decisions of this batch differently, which moves single gradient tensors by percent (measured 4e-2 between any two
-    # implementation sets), so only runs with matching implementations on the 3x3 layers compare at the gradient tolerance.
+    # The stored schedule mixes convolution implementations layer by layer (and may recompute a layer with another one
+    # than the forward pass used), so no run with one variant set reproduces its roundings.  Two runs whose convolutions
+    # round differently take a few of the 1.7 billion ReLU sign decisions of this batch differently, which moves single
+    # gradient tensors by percent.  That noise is measured here, between two block-output runs that differ only in the
+    # implementation of the 3x3 layers (one kernel / through the workspace), and the stored schedule's gradients must
+    # stay within twice the largest such difference of either run; on their own they must satisfy the identity that
+    # holds at any size (each filter that feeds a BatchNorm is orthogonal to its gradient).
     ref = StepRunner(g.text(), schedules.block_output_schedule(g, schedules.WINOGRAD_WS_VARIANTS).text(), exts, params)
     ref.step()
     want = ref.grads_numpy()
     assert abs(ref.loss_value() - loss) < 1e-4 * abs(loss)
+    del ref
+    noise = cross_implementation_noise(grads, want)
+    print(f"largest gradient difference between two implementation sets: {noise:.2e}")
+    assert noise < 0.1
     for p in want:
-        a, b = got[p].astype(np.float64), want[p].astype(np.float64)
-        assert np.linalg.norm(a - b) <= 1e-3 * np.linalg.norm(b), p
+        a, b, c = got[p].astype(np.float64), want[p].astype(np.float64), grads[p].astype(np.float64)
+        d = min(np.linalg.norm(a - b) / np.linalg.norm(b), np.linalg.norm(a - c) / np.linalg.norm(c))
+        assert d <= 2 * noise + 1e-3, (p, d, noise)
+    assert filter_orthogonality(g, params, got) < 2e-3
+
+
+def cross_implementation_noise(ga, gb):
+    """Largest normwise difference of a gradient tensor between two runs of the same schedule with different
+    convolution implementations."""
+    return max(float(np.linalg.norm(ga[p].astype(np.float64) - gb[p].astype(np.float64)) / np.linalg.norm(gb[p].astype(np.float64)))
+               for p in ga)
 
 
 def test_identities_that_hold_at_any_size(full):
@@ -162,13 +178,20 @@ def test_other_configurations_at_full_size(name):
         assert abs(run.loss_value() - la) < 1e-4 * abs(la)
         got = run.grads_numpy()
         del run
-        # reference with the convolution implementations the stored schedule was priced with (see the ResNet-50 test above)
+        # reference: the named schedule with the 3x3 layers through the workspace; tolerance from the measured difference
+        # between the two implementation sets (see the ResNet-50 test above)
         ref = StepRunner(g.text(), named(g, schedules.WINOGRAD_WS_VARIANTS).text(), exts, params)
         ref.step()
         want = ref.grads_numpy()
+        del ref
+        noise = cross_implementation_noise(ga, want)
+        print(f"largest gradient difference between two implementation sets: {noise:.2e}")
+        assert noise < 0.1
         for p in want:
-            a, b = got[p].astype(np.float64), want[p].astype(np.float64)
-            assert np.linalg.norm(a - b) <= 1e-3 * np.linalg.norm(b), p
+            a, b, c = got[p].astype(np.float64), want[p].astype(np.float64), ga[p].astype(np.float64)
+            d = min(np.linalg.norm(a - b) / np.linalg.norm(b), np.linalg.norm(a - c) / np.linalg.norm(c))
+            assert d <= 2 * noise + 1e-3, (p, d, noise)
+        assert filter_orthogonality(g, params, got) < 2e-3
 
 
 def test_sampled_stem_outputs_and_statistics(full):
