@@ -27,6 +27,11 @@
  *     overlap in time on different streams of one GPU would corrupt each other's results.
  *     monet_step zeroes that table at its start, so a step that was broken off by an error
  *     leaves nothing behind for the next one.
+ *   - A BatchNorm backward implementation 'from_output' recovers the normalised input as
+ *     (y - beta) / gamma (Section 4, "Backward Operator Optimization"): every gamma of such a layer
+ *     must be non-zero, otherwise its gradients are not finite.  The library does not check the
+ *     values (they live in device memory); a schedule for a model whose gamma may reach zero must
+ *     choose 'from_input' for that layer.
  *   - Activations are N,H,W,C fp32; convolution weights K,R,S,C; linear
  *     weights out,in; the ReLU sign code is one bit per element, bit (e & 63) of
  *     little-endian 64-bit word (e >> 6), e = N,H,W,C linear index, tail bits

@@ -132,6 +132,19 @@ def cmd_counters(a):
         v = agg[k]
         if "SQ_BUSY_CU_CYCLES" in v and "SQ_VALU_MFMA_BUSY_CYCLES" in v and v["SQ_BUSY_CU_CYCLES"] > 0:
             lines.append(f"    {'MFMA busy / CU busy':<32} {v['SQ_VALU_MFMA_BUSY_CYCLES'] / v['SQ_BUSY_CU_CYCLES']:.3f}")
+        if "GRBM_GUI_ACTIVE" in v and v["GRBM_GUI_ACTIVE"] > 0:
+            # GRBM_GUI_ACTIVE is summed over the 8 XCDs: / 8 = cycles the kernel's dispatches were on the chip; x 256 CUs (x 4 SIMDs)
+            chip = v["GRBM_GUI_ACTIVE"] / 8.0
+            if "SQ_BUSY_CU_CYCLES" in v:
+                lines.append(f"    {'CU busy / (cycles x 256 CUs)':<32} {v['SQ_BUSY_CU_CYCLES'] / (chip * 256):.3f}")
+            if "SQ_VALU_MFMA_BUSY_CYCLES" in v:
+                lines.append(f"    {'MFMA busy / (cycles x 1024 SIMDs)':<32} {v['SQ_VALU_MFMA_BUSY_CYCLES'] / (chip * 1024):.3f}")
+        if "SQ_INSTS_VALU" in v and "SQ_INSTS_VALU_MFMA_MOPS_F32" in v and v["SQ_INSTS_VALU_MFMA_MOPS_F32"] > 0:
+            # one 32x32x2 fp32 instruction = 4096 flop = 8 counted units of 512 flop; SQ_INSTS_VALU counts matrix instructions too
+            mfma = v["SQ_INSTS_VALU_MFMA_MOPS_F32"] / 8.0
+            lines.append(f"    {'other vector instr. / MFMA instr.':<32} {(v['SQ_INSTS_VALU'] - mfma) / mfma:.2f}")
+        if "SQ_WAVE_CYCLES" in v and "SQ_WAIT_INST_ANY" in v and v["SQ_WAVE_CYCLES"] > 0:
+            lines.append(f"    {'any wait / wave cycles':<32} {v['SQ_WAIT_INST_ANY'] / v['SQ_WAVE_CYCLES']:.3f}")
         if "SQ_WAVE_CYCLES" in v and "SQ_WAIT_INST_LDS" in v and v["SQ_WAVE_CYCLES"] > 0:
             lines.append(f"    {'LDS wait / wave cycles':<32} {v['SQ_WAIT_INST_LDS'] / v['SQ_WAVE_CYCLES']:.3f}")
         if "SQ_LDS_BANK_CONFLICT" in v and "SQ_LDS_IDX_ACTIVE" in v and v["SQ_LDS_IDX_ACTIVE"] > 0:
