@@ -55,6 +55,11 @@ def build_workload(name, variants=None):
         kind = name[len("resnet50_b184_"):]
         if kind == "store_everything":
             return g, schedules.store_everything_schedule(g), 184, "store everything, standard variants (plain back-propagation)"
+        if kind == "keep_masks":
+            # block outputs plus the 1-bit sign masks of every ReLU: a recomputed convolution -> BatchNorm -> ReLU chain then
+            # needs no mask again, and the ReLU rides in the convolution's epilogue with the BatchNorm
+            F = schedules.block_output_set(g) | {n.id for n in g.nodes if g.is_aux(n.id) and g.nodes[n.ins[0] - 1].op in ("relu", "relu6")}
+            return g, schedules.schedule_for_saved_set(g, F, lean_variants), 184, "keep block outputs and all ReLU sign masks, recompute the rest; lean variants"
         if kind == "store_everything_lean":
             return g, schedules.store_everything_schedule(g, lean_variants), 184, "store everything the lean variants read"
         if kind.startswith("budget_"):

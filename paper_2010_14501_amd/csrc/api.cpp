@@ -22,11 +22,13 @@ void build_programs(monet_plan *p);
 // One entry of the step program: a single operator launch, or two neighbours run as one fused kernel.
 enum { FUSE_NONE = 0, FUSE_BN_RELU_FWD, FUSE_ADD_RELU_FWD, FUSE_RELU_BN_BWD, FUSE_RELU_ADD_BWD,
        FUSE_CONV_BN_APPLY,                             // a recomputed convolution applies its in-place BatchNorm in the epilogue
-       FUSE_BN_ADD_RELU_FWD, FUSE_RELU_ADD_BN_BWD };   // the last two join three launches (tail of a residual block)
+       FUSE_BN_ADD_RELU_FWD, FUSE_RELU_ADD_BN_BWD,     // these two join three launches (tail of a residual block)
+       FUSE_CONV_BN_RELU };                            // FUSE_CONV_BN_APPLY plus the in-place ReLU behind the BatchNorm (three launches)
 struct ProgStep {
     int fuse;
     size_t a, b, c;   // indices into Plan::launches (b when fused, c when three are fused)
-    size_t last() const { return fuse == FUSE_NONE ? a : ((fuse == FUSE_BN_ADD_RELU_FWD || fuse == FUSE_RELU_ADD_BN_BWD) ? c : b); }
+    bool three() const { return fuse == FUSE_BN_ADD_RELU_FWD || fuse == FUSE_RELU_ADD_BN_BWD || fuse == FUSE_CONV_BN_RELU; }
+    size_t last() const { return fuse == FUSE_NONE ? a : (three() ? c : b); }
 };
 
 struct monet_plan {
@@ -528,6 +530,29 @@ bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
     return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
 }
 
+// ... and the ReLU (ReLU6) behind that BatchNorm, recomputed without its sign mask (the mask of a lean schedule is kept
+// from the forward pass): the clamp is one more operation on the value the epilogue holds.  In place it replaces the
+// BatchNorm's output; out of place (the BatchNorm's output is kept for its own backward operator) it is written to the
+// ReLU's buffer beside it, which saves reading the tensor again and a launch.
+bool conv_applies_bn_relu(const Plan &pl, const Launch &L1, const Launch &L2, const Launch &L3) {
+    if (!conv_applies_bn(pl, L1, L2) || L3.kind != EV_RUN_RECOMPUTE) return false;
+    const Graph &g = pl.g;
+    const Node &bn = g.nodes[L2.id], &re = g.nodes[L3.id];
+    if ((re.op != "relu" && re.op != "relu6") || re.ins[0] != bn.id) return false;
+    if (L3.flags & 2) return false;                                                        // no mask written
+    const bool same = L3.a[2].region == L2.a[2].region && L3.a[2].off == L2.a[2].off;
+    if (L3.flags & 1) return same;                                                         // in place: over the BatchNorm's output
+    // out of place: the ReLU's buffer must not lie on anything the fused launch still reads (the convolution's input and
+    // workspace are read until the last tile is done, and the arena may have given the ReLU a block freed before it)
+    if (same || L3.a[2].region != R_ARENA) return false;
+    const int64_t lo = L3.a[2].off, hi = lo + 4 * numel_of(re.shape);
+    auto clear = [&](const Ref &r, int64_t bytes) { return r.region != R_ARENA || r.off + bytes <= lo || r.off >= hi; };
+    const Node &cv = g.nodes[L1.id];
+    const FwdImpl &im = cv.fimpls[L1.impl];
+    return clear(L1.a[0], 4 * numel_of(g.shape_of(cv.ins[0]))) && clear(L1.a[2], 4 * numel_of(cv.shape)) &&
+           clear(L1.a[4], im.ws > 0 ? align_up(im.ws) : 0);
+}
+
 void build_programs(monet_plan *p) {
     const Plan &pl = p->plan;
     const size_t n = pl.launches.size();
@@ -549,6 +574,11 @@ void build_programs(monet_plan *p) {
                 continue;
             }
         }
+        if (i + 2 < n && conv_applies_bn_relu(pl, pl.launches[i], pl.launches[i + 1], pl.launches[i + 2])) {
+            p->prog_fused.push_back(ProgStep{FUSE_CONV_BN_RELU, i, i + 1, i + 2});
+            i += 2;
+            continue;
+        }
         if (i + 1 < n && conv_applies_bn(pl, pl.launches[i], pl.launches[i + 1])) {
             p->prog_fused.push_back(ProgStep{FUSE_CONV_BN_APPLY, i, i + 1, i + 1});
             ++i;
@@ -564,9 +594,14 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
     const Graph &g = c.mp->plan.g;
     const Plan &pl = c.mp->plan;
     const Launch &L1 = c.mp->plan.launches[ps.a], &L2 = c.mp->plan.launches[ps.b];
-    if (ps.fuse == FUSE_CONV_BN_APPLY) {
+    if (ps.fuse == FUSE_CONV_BN_APPLY || ps.fuse == FUSE_CONV_BN_RELU) {
         const Node &bn = g.nodes[L2.id];
-        const BnAffine affine{c.weights[bn.pars[0]], c.weights[bn.pars[1]], c.bn_stats(L2.id)};
+        BnAffine affine{c.weights[bn.pars[0]], c.weights[bn.pars[1]], c.bn_stats(L2.id)};
+        if (ps.fuse == FUSE_CONV_BN_RELU) {
+            const Launch &L3 = pl.launches[ps.c];
+            affine.relu = g.nodes[L3.id].op == "relu6" ? 2 : 1;
+            affine.relu_out = (L3.flags & 1) ? nullptr : (float *)c.ptr(L3.a[2]);
+        }
         run_forward(c, L1, &affine);
         return;
     }
@@ -739,7 +774,7 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
         out->kind = L.kind; out->id = L.id; out->impl = L.impl; out->flags = L.flags;
         double e, bytes;
         const char *label;
-        if (ps.fuse == FUSE_CONV_BN_APPLY) {
+        if (ps.fuse == FUSE_CONV_BN_APPLY || ps.fuse == FUSE_CONV_BN_RELU) {
             const ConvShape cs = conv_shape(g, g.nodes[L.id]);
             if (g.nodes[L.id].op == "dwconv") {
                 bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * (double)cs.M() * cs.K;
@@ -946,6 +981,19 @@ extern "C" int monet_conv_fwd_bn_apply(void *stream, const float *x, const float
     return guarded([&] {
         const ConvShape cs = mk_conv(N, H, W, C, K, R, S, stride, pad);
         const BnAffine affine{gamma, beta, stats};
+        if (winograd_m == 5) conv_winograd_fused((hipStream_t)stream, x, w, y, cs, false, false, ws, ws_bytes, &affine);
+        else if (winograd_m) conv_winograd((hipStream_t)stream, x, w, y, cs, winograd_m, false, false, ws, ws_bytes, &affine);
+        else conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, nullptr, &affine);
+    });
+}
+extern "C" int monet_conv_fwd_bn_relu(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
+                                      int stride, int pad, int winograd_m, float *ws, size_t ws_bytes, const float *gamma, const float *beta,
+                                      const float *stats, int six, float *relu_out) {
+    return guarded([&] {
+        const ConvShape cs = mk_conv(N, H, W, C, K, R, S, stride, pad);
+        BnAffine affine{gamma, beta, stats};
+        affine.relu = six ? 2 : 1;
+        affine.relu_out = relu_out;
         if (winograd_m == 5) conv_winograd_fused((hipStream_t)stream, x, w, y, cs, false, false, ws, ws_bytes, &affine);
         else if (winograd_m) conv_winograd((hipStream_t)stream, x, w, y, cs, winograd_m, false, false, ws, ws_bytes, &affine);
         else conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, nullptr, &affine);

@@ -20,4 +20,11 @@ __device__ inline void bn_affine_coeffs(const float *__restrict__ gamma, const f
 
 __device__ inline float bn_affine(float x, float a, float b) { return __builtin_fmaf(x, a, b); }
 
+// ReLU (mode 1) / ReLU6 (mode 2) as the stand-alone kernels compute it: strict comparisons, NaN and -0.0 give +0.0
+__device__ inline float relu_clamp(float e, int mode) {
+    float r = e > 0.0f ? e : 0.0f;
+    if (mode == 2) r = r < 6.0f ? r : 6.0f;
+    return r;
+}
+
 }  // namespace monet

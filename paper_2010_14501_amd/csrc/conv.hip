@@ -812,6 +812,12 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                     if (MODE == FWD && want_affine)
                         val = float4{bn_affine(val.x, bn_a[0], bn_b[0]), bn_affine(val.y, bn_a[1], bn_b[1]), bn_affine(val.z, bn_a[2], bn_b[2]),
                                      bn_affine(val.w, bn_a[3], bn_b[3])};
+                    if (MODE == FWD && want_affine && ta.affine.relu) {
+                        const float4 rv = float4{relu_clamp(val.x, ta.affine.relu), relu_clamp(val.y, ta.affine.relu),
+                                                 relu_clamp(val.z, ta.affine.relu), relu_clamp(val.w, ta.affine.relu)};
+                        if (ta.affine.relu_out) *(float4 *)(ta.affine.relu_out + orow * ta.Ng + col) = rv;
+                        else val = rv;
+                    }
                     *dst = val;
                     if (MODE == FWD && want_stats) ls.add(val.x, val.y, val.z, val.w);
                 }

@@ -437,6 +437,11 @@ __global__ __launch_bounds__(256) void dw3_row_kernel(const float *__restrict__ 
             for (int sx = 0; sx < 3; ++sx) acc += xv[r][j * STRIDE + sx] * wv[r * 3 + sx];
         if (ACC) acc += dst[(int64_t)j * C4];
         if (affine) acc = f4{bn_affine(acc.x, bn_a[0], bn_b[0]), bn_affine(acc.y, bn_a[1], bn_b[1]), bn_affine(acc.z, bn_a[2], bn_b[2]), bn_affine(acc.w, bn_a[3], bn_b[3])};
+        if (affine && bn.relu) {
+            const f4 rv = f4{relu_clamp(acc.x, bn.relu), relu_clamp(acc.y, bn.relu), relu_clamp(acc.z, bn.relu), relu_clamp(acc.w, bn.relu)};
+            if (bn.relu_out) ((f4 *)bn.relu_out + (dst - (f4 *)out))[(int64_t)j * C4] = rv;
+            else acc = rv;
+        }
         dst[(int64_t)j * C4] = acc;
     }
 }

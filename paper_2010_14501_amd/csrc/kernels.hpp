@@ -33,6 +33,10 @@ struct ConvShape {
 // writes gamma * (y - mean) * invstd + beta, with the bits bn_apply() would produce from y.
 struct BnAffine {
     const float *gamma = nullptr, *beta = nullptr, *stats = nullptr;
+    // a ReLU (1) or ReLU6 (2) that follows the BatchNorm, applied in the same epilogue: its result replaces the BatchNorm's
+    // (relu_out == null: both in place) or goes to relu_out, a tensor of the output's shape, beside it
+    int relu = 0;
+    float *relu_out = nullptr;
 };
 
 // ---- convolution (implicit GEMM on fp32 MFMA)

@@ -148,6 +148,11 @@ __global__ __launch_bounds__(256) void wino_output_kernel(const float *__restric
             f4 *dst = (f4 *)(y + (((int64_t)n * gm.H + h) * gm.W + w) * K + 4 * k4);
             f4 v = accumulate ? *dst + o[b] : o[b];
             if (!ADJ && bn.gamma) v = f4{bn_affine(v.x, bn_a[0], bn_b[0]), bn_affine(v.y, bn_a[1], bn_b[1]), bn_affine(v.z, bn_a[2], bn_b[2]), bn_affine(v.w, bn_a[3], bn_b[3])};
+            if (!ADJ && bn.gamma && bn.relu) {
+                const f4 rv = f4{relu_clamp(v.x, bn.relu), relu_clamp(v.y, bn.relu), relu_clamp(v.z, bn.relu), relu_clamp(v.w, bn.relu)};
+                if (bn.relu_out) *(f4 *)(bn.relu_out + ((float *)dst - y)) = rv;
+                else v = rv;
+            }
             *dst = v;
         }
     }
@@ -368,6 +373,11 @@ __global__ __launch_bounds__(256) void wino4_output_kernel(const float *__restri
             f2 *dst = (f2 *)(y + (((int64_t)n * gm.H + h) * gm.W + w) * K + 2 * k2);
             f2 v = accumulate ? *dst + o[b] : o[b];
             if (!ADJ && bn.gamma) v = f2{bn_affine(v.x, bn_a[0], bn_b[0]), bn_affine(v.y, bn_a[1], bn_b[1])};
+            if (!ADJ && bn.gamma && bn.relu) {
+                const f2 rv = f2{relu_clamp(v.x, bn.relu), relu_clamp(v.y, bn.relu)};
+                if (bn.relu_out) *(f2 *)(bn.relu_out + ((float *)dst - y)) = rv;
+                else v = rv;
+            }
             *dst = v;
         }
     }

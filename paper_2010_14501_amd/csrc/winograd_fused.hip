@@ -279,7 +279,7 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
 // lies inside the map and the channel exists (no store needs a test).
 template <int EPI, bool WHOLE>
 __device__ __forceinline__ void fused_output(const float *mp, __amdgpu_buffer_rsrc_t ry, unsigned voff, unsigned orow, unsigned obytes, int nr,
-                                             int nc, float bn_a, float bn_b) {
+                                             int nc, float bn_a, float bn_b, int relu, __amdgpu_buffer_rsrc_t ry2, bool two) {
     float s[6][4];      // s[b][a] = (A^T m)[a][b]
 #pragma unroll
     for (int b = 0; b < 6; ++b) {
@@ -299,6 +299,11 @@ __device__ __forceinline__ void fused_output(const float *mp, __amdgpu_buffer_rs
                 float v = o[b];
                 if (EPI == 1) v += buffer_load(ry, voff, so);
                 if (EPI == 2) v = bn_affine(v, bn_a, bn_b);
+                if (EPI == 2 && relu) {
+                    const float rv = relu_clamp(v, relu);
+                    if (two) buffer_store(ry2, voff, so, rv);
+                    else v = rv;
+                }
                 buffer_store(ry, voff, so, v);
             }
         }
@@ -348,6 +353,8 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
     const int ok_ = tid & 31, oq = tid >> 5;
     const unsigned obytes = (unsigned)gm.outc * 4, orow = (unsigned)gm.W * obytes;
     const __amdgpu_buffer_rsrc_t ry = buffer_of(y);
+    const bool two = EPI == 2 && bn.relu && bn.relu_out != nullptr;           // ReLU output beside the BatchNorm's
+    const __amdgpu_buffer_rsrc_t ry2 = buffer_of(two ? bn.relu_out : y);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int kout = kb * FK + h * 32 + ok_;
@@ -370,8 +377,8 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
             unsigned ext = tinfo[tl][1];
             if (kout >= gm.outc) ext = 0;
             const float *mp = lds + tl * MROW + ok_;
-            if (__all(ext == (4u | (4u << 8)))) fused_output<EPI, true>(mp, ry, voff, orow, obytes, 4, 4, bn_a, bn_b);      // uniform over the wave
-            else fused_output<EPI, false>(mp, ry, voff, orow, obytes, (int)(ext & 0xff), (int)(ext >> 8), bn_a, bn_b);
+            if (__all(ext == (4u | (4u << 8)))) fused_output<EPI, true>(mp, ry, voff, orow, obytes, 4, 4, bn_a, bn_b, bn.relu, ry2, two);      // uniform over the wave
+            else fused_output<EPI, false>(mp, ry, voff, orow, obytes, (int)(ext & 0xff), (int)(ext >> 8), bn_a, bn_b, bn.relu, ry2, two);
         }
     }
 }

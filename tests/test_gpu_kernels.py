@@ -211,6 +211,28 @@ def test_batchnorm_apply_in_the_conv_epilogue_is_the_stand_alone_bits(case):
     yo = nm.conv2d_fwd(wt.act_to_oracle(x), wt.weight_to_oracle(w), stride, pad)
     want = nm.bn_apply(yo, gamma.astype(np.float64), beta.astype(np.float64), stats[:K].astype(np.float64), stats[K:].astype(np.float64))
     check_close(fused.cpu().numpy(), wt.act_from_oracle(want), ACT_TOL)
+    # ... and with the ReLU / ReLU6 behind the BatchNorm in the same epilogue: the bits of the stand-alone ReLU kernel run in
+    # place on the tensor above (values scaled so that the upper clamp of ReLU6 is reached)
+    for six in (0, 1):
+        g6 = dev(gamma * np.float32(4.0 if six else 1.0))
+        plain = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), plain.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr())
+        monet.call("monet_relu_fwd", None, plain.data_ptr(), plain.data_ptr(), None, N * P * Q * K, six)
+        both = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), both.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, None)
+        assert torch.equal(both, plain), six
+        assert float(both.min()) == 0.0 and (not six or float(both.max()) == 6.0)
+        # the ReLU's result beside the BatchNorm's (the BatchNorm output is kept for its own backward operator)
+        bn_out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+        relu_out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr())
+        want_bn = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+        monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), want_bn.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr())
+        assert torch.equal(bn_out, want_bn) and torch.equal(relu_out, plain), six
     with pytest.raises(monet.MonetError):       # no Winograd form with 3x3 output tiles
         monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), fused.data_ptr(), N, H, W, C, K, R, R, stride, pad, 3,
                    wsp, need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr())
@@ -321,6 +343,18 @@ def test_fused_winograd_convolution_matches_oracle(case):
     if K % 4 == 0:
         monet.call("monet_bn_apply", None, y.data_ptr(), y.data_ptr(), dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), N * H * W, K)
         assert torch.equal(fused, y)
+        for six in (0, 1):      # the ReLU behind the BatchNorm in the same epilogue
+            both = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+            monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), both.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
+                       ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, None)
+            plain = y.clone()
+            monet.call("monet_relu_fwd", None, plain.data_ptr(), plain.data_ptr(), None, N * H * W * K, six)
+            assert torch.equal(both, plain), six
+            bn_out = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+            relu_out = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
+            monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
+                       ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr())
+            assert torch.equal(bn_out, y) and torch.equal(relu_out, plain), six
     want = nm.bn_apply(want_y, gamma.astype(np.float64), beta.astype(np.float64), stats[:K].astype(np.float64), stats[K:].astype(np.float64))
     check_close(fused.cpu().numpy(), wt.act_from_oracle(want), ACT_TOL)
     # input gradient: reduction over K, which must be a multiple of 8

@@ -230,3 +230,31 @@ def test_fused_neighbours_give_identical_bits():
     recomputed_bn = sum(1 for e in run.plan.trace_tuples() if e[0] == M.RUN_RECOMPUTE and g.nodes[e[2] - 1].op == "bn")
     apply_launches = sum(1 for l in fused_list if l[0] in ("bn_apply", "bn_relu_apply", "bn_add_relu_apply"))
     assert recomputed_bn > 0 and apply_launches < recomputed_bn
+
+
+def test_recomputed_relu_rides_in_the_convolution_epilogue_when_its_mask_is_kept():
+    """A schedule that keeps block outputs and every ReLU's 1-bit sign mask: the recomputed convolution -> BatchNorm -> ReLU
+    chains then write no mask, and the executor runs each as one launch (BatchNorm apply and ReLU in the convolution's
+    epilogue, the ReLU's result beside the BatchNorm's where that is still needed).  Fewer launches than one by one,
+    the same bits with fusion on and off and as the block-output schedule, the oracle's gradients."""
+    g = graphs.resnet50(batch=2, hw=64, classes=10, widths=(16, 32, 64, 64), depths=(2, 2, 1, 1), stem=16)
+    exts, params = tensors.make_inputs(g, seed=5, gamma_beta="random")
+    masks = {n.id for n in g.nodes if g.is_aux(n.id) and g.nodes[n.ins[0] - 1].op in ("relu", "relu6")}
+    F = schedules.block_output_set(g)
+    grads = {}
+    for name, saved in (("blocks", F), ("blocks+masks", F | masks)):
+        sch = schedules.schedule_for_saved_set(g, saved)
+        for fusion in (True, False):
+            run = StepRunner(g.text(), sch.text(), exts, params)
+            run.plan.set_fusion(fusion)
+            labels = [l[0] for l in run.plan.launches()]
+            peak = run.step()
+            assert peak == run.plan.exact_peak == osch.interpret(g.text(), sch.text())["peak"]
+            grads[(name, fusion)] = (run.grads_numpy(), labels.count("relu_fwd"), len(labels))
+            del run
+    # with the masks kept, the recomputed ReLUs are gone from the fused program
+    assert grads[("blocks+masks", True)][1] < grads[("blocks+masks", False)][1]
+    assert grads[("blocks+masks", True)][1] < grads[("blocks", True)][1]
+    ref = grads[("blocks", False)][0]
+    for key, (got, _, _) in grads.items():
+        assert all(np.array_equal(got[p], ref[p]) for p in ref), key
