@@ -104,13 +104,22 @@ int64_t monet_conv_winograd_fused_workspace_bytes(int N, int H, int W, int C, in
  * monet_conv_fwd / monet_conv_wgrad (device pointers, NHWC, filters K x R x S x C); needs K % 4 == 0.  ws / ws_bytes:
  * device workspace owned by the caller; its size decides the chunk (at least the patches of one image, the padded
  * filters and, for the filter gradient, the chunk's K x round_up(R*S*C, 16) result with its split-reduction parts;
- * MONET_BAD_ARGUMENT otherwise).  monet_conv_im2col_workspace_bytes gives the recommended size (chunks of about
+ * a negative status otherwise).  monet_conv_im2col_workspace_bytes gives the recommended size (chunks of about
  * 256 MiB of patches; wgrad != 0 for the filter gradient).  Results agree with the implicit GEMM to rounding. */
 int monet_conv_im2col_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
                           int stride, int pad, int accumulate, float *ws, size_t ws_bytes);
 int monet_conv_im2col_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R, int S,
                             int stride, int pad, float *ws, size_t ws_bytes);
 int64_t monet_conv_im2col_workspace_bytes(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int wgrad);
+/* Filter gradient of a 1x1 / stride 1 / unpadded convolution with few channels on one side (the expansion and projection
+ * layers of an inverted-residual block on its large maps): dw[K,1,1,C] = sum over the N*H*W positions of dy[.,k] x[.,c],
+ * a reduction of the two activation tensors into a small matrix and so bound by reading them once (one more
+ * implementation of an operator in the sense of Section 4; same result as monet_conv_wgrad to rounding).  Needs
+ * C % 4 == 0, K % 4 == 0, min(C, K) <= 32, max(C, K) <= 192, splits >= 2, N*H*W >= 64 * min(splits, 256) and a device
+ * workspace of at least min(splits, 256) * K * C floats (partial results of the workgroups, added in a fixed order: two
+ * calls agree bit for bit); a negative status otherwise.  monet_conv_wgrad takes this form by itself where it applies. */
+int monet_conv_pointwise_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int splits,
+                               float *ws, size_t ws_bytes);
 /* Filter gradient of such a layer in the same transformed domain: dw[K,3,3,C] = G^T [ sum over tiles (A dy A^T) .* (B^T d B) ] G
  * (C % 4 == 0, K % 4 == 0).  Workspace: the transformed input and output gradient of one chunk of images (as above),
  * two buffers of P*K*C floats (the transformed filter gradient and one chunk's share of it, added chunk after chunk)

@@ -1092,6 +1092,10 @@ extern "C" int64_t monet_conv_im2col_workspace_bytes(int N, int H, int W, int C,
     int rc = guarded([&] { bytes = (int64_t)conv_im2col_workspace_bytes(mk_conv(N, H, W, C, K, R, S, stride, pad), wgrad != 0); });
     return rc == MONET_OK ? bytes : rc;
 }
+extern "C" int monet_conv_pointwise_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int splits,
+                                         float *ws, size_t ws_bytes) {
+    return guarded([&] { pointwise_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, 1, 1, 1, 0), splits, ws, ws_bytes); });
+}
 extern "C" int monet_conv_force_tile(int cfg) {
     if (cfg < -1 || cfg > 5) { g_err = "monet_conv_force_tile: cfg must be -1..5"; return MONET_BAD_ARGUMENT; }
     conv_force_tile(cfg);

@@ -1008,6 +1008,10 @@ void launch_batched(int cfg, Rest... rest) {
 
 void conv_force_tile(int cfg) { g_cfg_override = cfg; }
 
+void split_reduce(hipStream_t st, const float *ws, float *out, int64_t n, int splits, bool accumulate) {
+    launch_split_reduce(st, ws, out, n, splits, accumulate);
+}
+
 namespace {
 struct SplitGemm { int64_t rows, cols, steps; int classes; };
 SplitGemm split_gemm_of(int which, const ConvShape &cs) {
@@ -1129,6 +1133,11 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
 
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
     check_shape(cs);
+    // 1x1 layers with at most 32 channels on one side: streamed straight into the matrix instruction (pointwise.hip)
+    if (g_cfg_override < 0 && ws && pointwise_wgrad_applies(cs, splits, ws_bytes)) {
+        pointwise_wgrad(st, x, dy, dw, cs, splits, ws, ws_bytes);
+        return;
+    }
     TileArgs ta{};
     ta.a = dy; ta.b = x; ta.cs = cs;
     ta.Mg = cs.K; ta.Ng = (int)cs.RSC(); ta.Kg = cs.M();

@@ -96,6 +96,14 @@ void conv_im2col_fwd(hipStream_t st, const float *x, const float *w, float *y, c
                      bool accumulate);
 void conv_im2col_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *ws, size_t ws_bytes);
 
+// out[i] (+)= sum over z < splits of ws[z * n + i], in a fixed order
+void split_reduce(hipStream_t st, const float *ws, float *out, int64_t n, int splits, bool accumulate);
+// Filter gradient of a 1x1 / stride-1 convolution with at most 32 channels on one side and at most 192 on the other
+// (pointwise.hip): min(splits, 256) workgroups stream contiguous ranges of positions, their partial results (that many
+// times K * C floats of workspace) are added in a fixed order.  conv_wgrad takes this path by itself where it applies.
+bool pointwise_wgrad_applies(const ConvShape &cs, int splits, size_t ws_bytes);
+void pointwise_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes);
+
 // tuning aid: cfg 0..5 forces tile shape (2x2, 4x1, 1x4, 2x1, 1x2, 1x1 waves of 64x64); -1 restores the heuristic
 void conv_force_tile(int cfg);
 // workspace bytes of conv_fwd (which = 0) / conv_dgrad (which = 1) for `splits` ranges; for splits = 1 the bytes

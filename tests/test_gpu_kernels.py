@@ -468,6 +468,69 @@ def test_filter_gradient_with_many_short_ranges_on_every_tile_shape(case):
         monet.call("monet_conv_force_tile", -1)
 
 
+POINTWISE_WGRAD_CASES = [
+    # N, H, W, C, K, splits: the channel pairs of MobileNetV2's expansion / projection layers (each selects another
+    # combination of 16-byte and 4-byte loads of the wide side), position counts that leave a ragged tail, workgroups
+    # whose share is shorter than one group of 16 positions per wave
+    (2, 56, 56, 16, 96, 64),
+    (3, 37, 29, 16, 96, 48),
+    (2, 56, 56, 96, 24, 64),
+    (2, 56, 56, 24, 144, 64),
+    (2, 56, 56, 144, 32, 64),
+    (2, 56, 56, 32, 192, 64),
+    (2, 56, 56, 192, 32, 64),
+    (2, 56, 56, 32, 16, 64),
+    (1, 33, 31, 24, 144, 8),
+    (1, 33, 31, 144, 24, 8),
+    (5, 9, 9, 8, 40, 2),
+    (4, 75, 75, 16, 96, 300),     # more splits than workgroups: 256 partial results are used
+    (1, 17, 16, 12, 4, 4),        # 68 positions per workgroup: one group each for waves 0..3 and a tail of four rows
+]
+
+
+@pytest.mark.parametrize("case", POINTWISE_WGRAD_CASES)
+def test_pointwise_filter_gradient_streamed_into_the_matrix_instruction(case):
+    """The 1x1 filter gradient with few channels on one side, read straight from memory into the lane layout of the
+    matrix instruction: against the oracle, twice (bit-identical), and monet_conv_wgrad with the same arguments must
+    give the same bits, i.e. take this form by itself."""
+    torch = torch_mod()
+    N, H, W, C, K, splits = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, C), dtype=np.float32)
+    dy = rng.standard_normal((N, H, W, K), dtype=np.float32)
+    want = wt.weight_from_oracle(nm.conv2d_wgrad(wt.act_to_oracle(x), wt.act_to_oracle(dy), 1, 1, 1, 0))
+    dx, ddy = dev(x), dev(dy)
+    ws = torch.empty(min(splits, 256) * K * C, dtype=torch.float32, device="cuda")
+    got = []
+    for entry in ("monet_conv_pointwise_wgrad", "monet_conv_pointwise_wgrad", "monet_conv_wgrad"):
+        dw = torch.full((K, 1, 1, C), float("nan"), dtype=torch.float32, device="cuda")
+        ws.fill_(float("nan"))
+        if entry == "monet_conv_wgrad":
+            monet.call(entry, None, dx.data_ptr(), ddy.data_ptr(), dw.data_ptr(), N, H, W, C, K, 1, 1, 1, 0, splits, ws.data_ptr(), ws.numel() * 4)
+        else:
+            monet.call(entry, None, dx.data_ptr(), ddy.data_ptr(), dw.data_ptr(), N, H, W, C, K, splits, ws.data_ptr(), ws.numel() * 4)
+        torch.cuda.synchronize()
+        got.append(dw.cpu().numpy())
+    assert np.array_equal(got[0], got[1]), "two runs differ"
+    assert np.array_equal(got[0], got[2]), "monet_conv_wgrad did not take the pointwise form"
+    check_close(got[0], want, 1e-5, what="pointwise filter gradient")
+
+
+def test_pointwise_filter_gradient_refuses_what_it_is_not_for():
+    torch = torch_mod()
+    t = torch.zeros(1 << 20, device="cuda")
+    for (N, H, W, C, K, splits, ws_bytes) in [
+        (2, 56, 56, 64, 64, 16, 1 << 22),      # both sides wider than 32 channels
+        (2, 56, 56, 16, 256, 16, 1 << 22),     # wide side beyond 192
+        (2, 56, 56, 16, 96, 1, 1 << 22),       # no partial results asked for
+        (2, 56, 56, 16, 96, 16, 16 * 96 * 16 * 4 - 4),     # workspace one float short
+        (1, 8, 8, 16, 96, 16, 1 << 22),        # fewer than 64 positions per workgroup
+        (2, 56, 56, 18, 96, 16, 1 << 22),      # channels not a multiple of four
+    ]:
+        with pytest.raises(M.MonetError):
+            monet.call("monet_conv_pointwise_wgrad", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), N, H, W, C, K, splits, t.data_ptr(), ws_bytes)
+
+
 def test_conv_wgrad_rejects_small_workspace():
     torch = torch_mod()
     t = torch.zeros(16 * 16 * 16 * 2, device="cuda")
