@@ -67,11 +67,14 @@ int monet_conv_fwd_bn_apply(void *stream, const float *x, const float *w, float 
  * recomputation repeats the forward operators; Appendix D: in-place operators).  relu_out == null: y holds the ReLU's
  * result, bit-identical to monet_conv_fwd_bn_apply followed by monet_relu_fwd in place.  relu_out != null (device,
  * shape of y, must not overlap x, y or ws): y holds the BatchNorm's output as monet_conv_fwd_bn_apply leaves it and
- * relu_out the ReLU's, as monet_relu_fwd(y -> relu_out) would write it.  No mask is written. */
+ * relu_out the ReLU's, as monet_relu_fwd(y -> relu_out) would write it.  mask == null: no sign code is written (the code
+ * of a lean schedule was kept from the forward pass).  mask != null (device, ceil(N*P*Q*K / 64) words, must not overlap x,
+ * y, relu_out or ws): the ReLU's 1-bit sign code, the words monet_relu_fwd would write; needs K % 64 == 0 and
+ * winograd_m == 0 or 5 (the other forms return an error). */
 int monet_conv_fwd_bn_relu(void *stream, const float *x, const float *w, float *y,
                            int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int winograd_m,
                            float *ws, size_t ws_bytes, const float *gamma, const float *beta, const float *stats, int six,
-                           float *relu_out);
+                           float *relu_out, uint64_t *mask);
 /* Winograd F(m x m, 3x3) form of a 3x3 / stride 1 / pad 1 convolution, m = 2 or 4 (Section 4 lists Winograd among the
  * implementations an operator chooses from; Appendix D: workspace against time).  adjoint == 0: out = y[N,H,W,K] from
  * in = x[N,H,W,C] (needs C % 16 == 0, K % 4 == 0).  adjoint != 0: out = dx[N,H,W,C] (+)= from in = dy[N,H,W,K]

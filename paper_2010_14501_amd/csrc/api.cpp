@@ -530,27 +530,38 @@ bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
     return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
 }
 
-// ... and the ReLU (ReLU6) behind that BatchNorm, recomputed without its sign mask (the mask of a lean schedule is kept
-// from the forward pass): the clamp is one more operation on the value the epilogue holds.  In place it replaces the
-// BatchNorm's output; out of place (the BatchNorm's output is kept for its own backward operator) it is written to the
-// ReLU's buffer beside it, which saves reading the tensor again and a launch.
+// ... and the ReLU (ReLU6) behind that BatchNorm: the clamp is one more operation on the value the epilogue holds.  In
+// place it replaces the BatchNorm's output; out of place (the BatchNorm's output is kept for its own backward operator) it
+// is written to the ReLU's buffer beside it, which saves reading the tensor again and a launch.  A recomputed ReLU that
+// writes its sign mask again (the mask was not kept from the forward pass) rides along where the kernel can assemble the
+// mask words; elsewhere it stays a launch of its own behind the fused pair.
 bool conv_applies_bn_relu(const Plan &pl, const Launch &L1, const Launch &L2, const Launch &L3) {
     if (!conv_applies_bn(pl, L1, L2) || L3.kind != EV_RUN_RECOMPUTE) return false;
     const Graph &g = pl.g;
     const Node &bn = g.nodes[L2.id], &re = g.nodes[L3.id];
     if ((re.op != "relu" && re.op != "relu6") || re.ins[0] != bn.id) return false;
-    if (L3.flags & 2) return false;                                                        // no mask written
-    const bool same = L3.a[2].region == L2.a[2].region && L3.a[2].off == L2.a[2].off;
-    if (L3.flags & 1) return same;                                                         // in place: over the BatchNorm's output
-    // out of place: the ReLU's buffer must not lie on anything the fused launch still reads (the convolution's input and
-    // workspace are read until the last tile is done, and the arena may have given the ReLU a block freed before it)
-    if (same || L3.a[2].region != R_ARENA) return false;
-    const int64_t lo = L3.a[2].off, hi = lo + 4 * numel_of(re.shape);
-    auto clear = [&](const Ref &r, int64_t bytes) { return r.region != R_ARENA || r.off + bytes <= lo || r.off >= hi; };
     const Node &cv = g.nodes[L1.id];
     const FwdImpl &im = cv.fimpls[L1.impl];
-    return clear(L1.a[0], 4 * numel_of(g.shape_of(cv.ins[0]))) && clear(L1.a[2], 4 * numel_of(cv.shape)) &&
-           clear(L1.a[4], im.ws > 0 ? align_up(im.ws) : 0);
+    // What the fused launch writes beside the BatchNorm's output must not lie on anything it still reads (the convolution's
+    // input and workspace are read until the last tile is done, and the arena may have handed out a block freed before it)
+    auto clear_of = [&](const Ref &w, int64_t wbytes) {
+        if (w.region != R_ARENA) return false;
+        const int64_t lo = w.off, hi = lo + wbytes;
+        auto clear = [&](const Ref &r, int64_t bytes) { return r.region != R_ARENA || r.off + bytes <= lo || r.off >= hi; };
+        return clear(L1.a[0], 4 * numel_of(g.shape_of(cv.ins[0]))) && clear(L1.a[2], 4 * numel_of(cv.shape)) &&
+               clear(L1.a[4], im.ws > 0 ? align_up(im.ws) : 0);
+    };
+    if (L3.flags & 2) {
+        // the sign code comes from the epilogue too where the kernel can write it: the implicit GEMM and the one-kernel
+        // Winograd form, 64 | K (a word of the code is 64 channels of one position)
+        if (cv.op != "conv" || (winograd_tile(im.algo) && !winograd_is_fused(im.algo))) return false;
+        if (!conv_epilogue_writes_mask(conv_shape(g, cv), winograd_is_fused(im.algo))) return false;
+        if (!clear_of(L3.a[3], (numel_of(re.shape) + 63) / 64 * 8)) return false;
+    }
+    const bool same = L3.a[2].region == L2.a[2].region && L3.a[2].off == L2.a[2].off;
+    if (L3.flags & 1) return same;                                                         // in place: over the BatchNorm's output
+    if (same) return false;
+    return clear_of(L3.a[2], 4 * numel_of(re.shape));
 }
 
 void build_programs(monet_plan *p) {
@@ -601,6 +612,7 @@ void run_fused(const StepCtx &c, const ProgStep &ps) {
             const Launch &L3 = pl.launches[ps.c];
             affine.relu = g.nodes[L3.id].op == "relu6" ? 2 : 1;
             affine.relu_out = (L3.flags & 1) ? nullptr : (float *)c.ptr(L3.a[2]);
+            affine.mask = (L3.flags & 2) ? (unsigned long long *)c.ptr(L3.a[3]) : nullptr;
         }
         run_forward(c, L1, &affine);
         return;
@@ -784,6 +796,11 @@ extern "C" int monet_plan_launch_info(const monet_plan *p, size_t index, monet_l
                 out->issued_flops = issued_conv_flops(cs, g.nodes[L.id].fimpls[L.impl].algo);
                 bytes = 4.0 * cs.N * cs.H * cs.W * cs.C + 4.0 * cs.K * (double)cs.RSC() + 4.0 * (double)cs.M() * cs.K;
                 label = winograd_tile(g.nodes[L.id].fimpls[L.impl].algo) ? "conv_fwd_winograd" : "conv_fwd";
+            }
+            if (ps.fuse == FUSE_CONV_BN_RELU) {      // the ReLU's result beside the BatchNorm's, its sign mask
+                const Launch &L3 = p->plan.launches[ps.c];
+                if (!(L3.flags & 1)) bytes += 4.0 * (double)cs.M() * cs.K;
+                if (L3.flags & 2) bytes += (double)cs.M() * cs.K / 8.0;
             }
         } else if (ps.fuse == FUSE_BN_ADD_RELU_FWD) {
             const Launch &L3 = p->plan.launches[ps.c];
@@ -988,12 +1005,13 @@ extern "C" int monet_conv_fwd_bn_apply(void *stream, const float *x, const float
 }
 extern "C" int monet_conv_fwd_bn_relu(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int C, int K, int R, int S,
                                       int stride, int pad, int winograd_m, float *ws, size_t ws_bytes, const float *gamma, const float *beta,
-                                      const float *stats, int six, float *relu_out) {
+                                      const float *stats, int six, float *relu_out, uint64_t *mask) {
     return guarded([&] {
         const ConvShape cs = mk_conv(N, H, W, C, K, R, S, stride, pad);
         BnAffine affine{gamma, beta, stats};
         affine.relu = six ? 2 : 1;
         affine.relu_out = relu_out;
+        affine.mask = (unsigned long long *)mask;
         if (winograd_m == 5) conv_winograd_fused((hipStream_t)stream, x, w, y, cs, false, false, ws, ws_bytes, &affine);
         else if (winograd_m) conv_winograd((hipStream_t)stream, x, w, y, cs, winograd_m, false, false, ws, ws_bytes, &affine);
         else conv_fwd((hipStream_t)stream, x, w, y, cs, 1, ws, ws_bytes, false, nullptr, &affine);

@@ -19,6 +19,10 @@ __device__ __forceinline__ float buffer_load(__amdgpu_buffer_rsrc_t r, unsigned 
 __device__ __forceinline__ bf4 buffer_load4(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff) {
     return __builtin_bit_cast(bf4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
 }
+__device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff, bf4 v) {
+    typedef unsigned int word4 __attribute__((__vector_size__(16)));
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(word4, v), r, (int)voff, (int)soff, 0);
+}
 __device__ __forceinline__ void buffer_store(__amdgpu_buffer_rsrc_t r, unsigned voff, unsigned soff, float v) {
     __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), r, (int)voff, (int)soff, 0);
 }

@@ -74,8 +74,10 @@ struct TileArgs {
     float *stats_part;         // FWD, whole results only: BatchNorm partial statistics of the output (tile_stats.hpp), or null
     BnAffine affine;           // FWD, whole results only: BatchNorm apply step of the output in the epilogue (gamma == null: off)
     int64_t batch_a, batch_b, batch_out;   // FWD / WGRAD with gridDim.z > 1: z-th GEMM of a batch, operands and result this many floats apart
-    // WGRAD, aligned loader: floor(n / Q) = umulhi(n, q_mul) >> q_shift for n < 2^31 (Q >= 2), likewise P
-    unsigned q_mul, q_shift, p_mul, p_shift;
+    // decoding a row index into (image, row, column) without a division: floor(n / Q) = umulhi(n, q_mul) >> q_shift for
+    // n < 2^31 (Q >= 2), likewise P (forward rows, the filter gradient's reduction rows) and W, H (input-gradient rows at
+    // stride 1); set by launch_tile
+    unsigned q_mul, q_shift, p_mul, p_shift, w_mul, w_shift, h_mul, h_shift;
 };
 
 // arrivals per split tile; zero whenever no convolution kernel is running (the last arrival puts its entry back)
@@ -212,18 +214,28 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             a_ok[s] = m < Mg;
             int64_t mm = a_ok[s] ? m : 0;
             if (MODE == FWD) {
-                const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)cs.Q;      // rows are bounded below 2^31 by the host
-                int q = (int)(m32 % (unsigned)cs.Q);
-                int p = (int)(t % (unsigned)cs.P);
-                int n = (int)(t / (unsigned)cs.P);
+                const unsigned m32 = (unsigned)mm;                                 // rows are bounded below 2^31 by the host
+                const unsigned t = cs.Q == 1 ? m32 : __umulhi(m32, ta.q_mul) >> ta.q_shift;
+                const unsigned nn = cs.P == 1 ? t : __umulhi(t, ta.p_mul) >> ta.p_shift;
+                int q = (int)(m32 - t * (unsigned)cs.Q);
+                int p = (int)(t - nn * (unsigned)cs.P);
+                int n = (int)nn;
                 a_h0[s] = p * cs.stride - cs.pad;
                 a_w0[s] = q * cs.stride - cs.pad;
                 a_base[s] = (int64_t)n * cs.H * cs.W * cs.C + (idx % 4) * 4;
             } else {   // DGRAD: m = (n, hc, wc) within the residue class
-                const unsigned m32 = (unsigned)mm, t = m32 / (unsigned)Wc;
-                int wc = (int)(m32 % (unsigned)Wc);
-                int hc = (int)(t % (unsigned)Hc);
-                int n = (int)(t / (unsigned)Hc);
+                const unsigned m32 = (unsigned)mm;
+                unsigned t, nn;
+                if (cs.stride == 1) {      // the one class is the tensor itself: Wc = W, Hc = H
+                    t = cs.W == 1 ? m32 : __umulhi(m32, ta.w_mul) >> ta.w_shift;
+                    nn = cs.H == 1 ? t : __umulhi(t, ta.h_mul) >> ta.h_shift;
+                } else {
+                    t = m32 / (unsigned)Wc;
+                    nn = t / (unsigned)Hc;
+                }
+                int wc = (int)(m32 - t * (unsigned)Wc);
+                int hc = (int)(t - nn * (unsigned)Hc);
+                int n = (int)nn;
                 a_h0[s] = hc + bh;      // p = a_h0 - tap row
                 a_w0[s] = wc + bw;
                 a_base[s] = (int64_t)n * cs.P * cs.Q * cs.K + (idx % 4) * 4;
@@ -784,45 +796,90 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 for (int j = 0; j < 4; ++j) bn_affine_coeffs(ta.affine.gamma, ta.affine.beta, ta.affine.stats, ta.Ng, c0 + j, bn_a[j], bn_b[j]);
             }
         }
+        // the sign code of a ReLU applied here: per row one word per 64 columns, i.e. per wave; the values are read once more
+        // from the LDS patch with lane = column, so that one ballot is one word
+        const bool want_mask = MODE == FWD && want_affine && ta.affine.relu && ta.affine.mask != nullptr && col0 + wn * 64 < ta.Ng;
+        float bn_ac = 1.0f, bn_bc = 0.0f;
+        if (MODE == FWD && want_mask) bn_affine_coeffs(ta.affine.gamma, ta.affine.beta, ta.affine.stats, ta.Ng, col0 + wn * 64 + lane, bn_ac, bn_bc);
+        // A tile that lies inside the result whole (all but the last row of tiles and, for widths that are no multiple
+        // of the tile, the last column) writes through buffer addressing: the descriptor starts at the tile, a lane's
+        // byte offset inside the tile never changes and the row of a pass is a scalar offset, so a store costs no vector
+        // instruction for its address and none for a bounds test.
+        const bool inside = row0 + BM <= Mg && col0 + BN <= ta.Ng && ta.Ng < (1 << 24) && !(MODE == DGRAD && cs.stride > 1);
+        const unsigned row_bytes = (unsigned)ta.Ng * 4u;
+        const int64_t tile_at = (row0 + wm * 64) * ta.Ng + col0 + wn * 64;
+        const __amdgpu_buffer_rsrc_t r_out = buffer_of(out + tile_at);
+        const __amdgpu_buffer_rsrc_t r_relu = buffer_of(MODE == FWD && ta.affine.relu_out ? ta.affine.relu_out + tile_at : out + tile_at);
+        const unsigned t_voff = (unsigned)(lane >> 4) * row_bytes + 16u * (unsigned)(lane & 15);
+        auto emit = [&](auto whole_tile) {
+            constexpr bool IN = decltype(whole_tile)::value;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int mi = q >> 1, vbase = 8 * (q & 1);
+            for (int q = 0; q < 4; ++q) {
+                const int mi = q >> 1, vbase = 8 * (q & 1);
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+                for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-                for (int vv = 0; vv < 8; ++vv)
-                    stage[(8 * (vv >> 2) + 4 * g + (vv & 3)) * 64 + ni * 32 + l32] = acc[mi][ni][vbase + vv];
+                    for (int vv = 0; vv < 8; ++vv)
+                        stage[(8 * (vv >> 2) + 4 * g + (vv & 3)) * 64 + ni * 32 + l32] = acc[mi][ni][vbase + vv];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = lane + 64 * i, rl = idx >> 4, c4 = idx & 15;
-                float4 val = *(const float4 *)&stage[rl * 64 + 4 * c4];
-                const int64_t row = row0 + wm * 64 + 16 * q + rl;
-                const int col = col0 + wn * 64 + 4 * c4;
-                if (row < Mg && col < ta.Ng) {
-                    int64_t orow = row;
-                    if (MODE == DGRAD && cs.stride > 1) {
-                        int wc = (int)(row % Wc);
-                        int64_t t = row / Wc;
-                        int hc = (int)(t % Hc);
-                        int64_t n = t / Hc;
-                        orow = (n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
+                for (int i = 0; i < 4; ++i) {
+                    const int idx = lane + 64 * i, rl = idx >> 4, c4 = idx & 15;
+                    float4 val = *(const float4 *)&stage[rl * 64 + 4 * c4];
+                    const int64_t row = row0 + wm * 64 + 16 * q + rl;
+                    const int col = col0 + wn * 64 + 4 * c4;
+                    if (IN || (row < Mg && col < ta.Ng)) {
+                        const unsigned t_soff = (unsigned)(16 * q + 4 * i) * row_bytes;
+                        int64_t orow = row;
+                        if (!IN && MODE == DGRAD && cs.stride > 1) {
+                            int wc = (int)(row % Wc);
+                            int64_t t = row / Wc;
+                            int hc = (int)(t % Hc);
+                            int64_t n = t / Hc;
+                            orow = (n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
+                        }
+                        float4 *dst = (float4 *)(out + orow * ta.Ng + col);
+                        if (do_acc) {
+                            float4 o;
+                            if (IN) { const bf4 t = buffer_load4(r_out, t_voff, t_soff); o = make_float4(t.x, t.y, t.z, t.w); }
+                            else o = *dst;
+                            val.x += o.x; val.y += o.y; val.z += o.z; val.w += o.w;
+                        }
+                        if (MODE == FWD && want_affine)
+                            val = float4{bn_affine(val.x, bn_a[0], bn_b[0]), bn_affine(val.y, bn_a[1], bn_b[1]), bn_affine(val.z, bn_a[2], bn_b[2]),
+                                         bn_affine(val.w, bn_a[3], bn_b[3])};
+                        if (MODE == FWD && want_affine && ta.affine.relu) {
+                            const float4 rv = float4{relu_clamp(val.x, ta.affine.relu), relu_clamp(val.y, ta.affine.relu),
+                                                     relu_clamp(val.z, ta.affine.relu), relu_clamp(val.w, ta.affine.relu)};
+                            if (ta.affine.relu_out) {
+                                if (IN) buffer_store4(r_relu, t_voff, t_soff, bf4{rv.x, rv.y, rv.z, rv.w});
+                                else *(float4 *)(ta.affine.relu_out + orow * ta.Ng + col) = rv;
+                            } else val = rv;
+                        }
+                        if (IN) buffer_store4(r_out, t_voff, t_soff, bf4{val.x, val.y, val.z, val.w});
+                        else *dst = val;
+                        if (MODE == FWD && want_stats) {
+                            if (!IN) ls.add(val.x, val.y, val.z, val.w);
+                            else if (q == 0 && i == 0) ls.add_first(val.x, val.y, val.z, val.w);
+                            else ls.add_next(val.x, val.y, val.z, val.w);
+                        }
                     }
-                    float4 *dst = (float4 *)(out + orow * ta.Ng + col);
-                    if (do_acc) { float4 o = *dst; val.x += o.x; val.y += o.y; val.z += o.z; val.w += o.w; }
-                    if (MODE == FWD && want_affine)
-                        val = float4{bn_affine(val.x, bn_a[0], bn_b[0]), bn_affine(val.y, bn_a[1], bn_b[1]), bn_affine(val.z, bn_a[2], bn_b[2]),
-                                     bn_affine(val.w, bn_a[3], bn_b[3])};
-                    if (MODE == FWD && want_affine && ta.affine.relu) {
-                        const float4 rv = float4{relu_clamp(val.x, ta.affine.relu), relu_clamp(val.y, ta.affine.relu),
-                                                 relu_clamp(val.z, ta.affine.relu), relu_clamp(val.w, ta.affine.relu)};
-                        if (ta.affine.relu_out) *(float4 *)(ta.affine.relu_out + orow * ta.Ng + col) = rv;
-                        else val = rv;
+                }
+                if (MODE == FWD && want_mask) {      // uniform over the wave
+                    unsigned w_lo = 0, w_hi = 0;
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr) {
+                        const float e = bn_affine(stage[rr * 64 + lane], bn_ac, bn_bc);
+                        const bool pass = ta.affine.relu == 2 ? (e > 0.0f && e < 6.0f) : e > 0.0f;
+                        const unsigned long long word = __ballot(pass);
+                        if (lane == rr) { w_lo = (unsigned)word; w_hi = (unsigned)(word >> 32); }
                     }
-                    *dst = val;
-                    if (MODE == FWD && want_stats) ls.add(val.x, val.y, val.z, val.w);
+                    const int64_t mrow = row0 + wm * 64 + 16 * q + lane;       // lanes 0 .. 15 hold the words of the pass's rows
+                    if (lane < 16 && mrow < Mg) ta.affine.mask[(mrow * ta.Ng + col0 + wn * 64) >> 6] = ((unsigned long long)w_hi << 32) | w_lo;
                 }
             }
-        }
+        };
+        if (inside) emit(std::true_type{});
+        else emit(std::false_type{});
         if (MODE == FWD && want_stats) {
             // this wave's 64 rows are one row group of the statistics; lanes l, l^16, l^32, l^48 share their columns
             float n, mean[4], m2[4];
@@ -900,6 +957,23 @@ void launch_split_reduce(hipStream_t st, const float *ws, float *dw, int64_t n, 
     hip_check(hipGetLastError(), "split reduce launch");
 }
 
+// floor(n / d) = umulhi(n, mul) >> shift for every n < 2^31 (d >= 2): mul = ceil(2^(31 + l) / d) with l = ceil(log2 d)
+// fits 32 bits, and its excess over 2^(31 + l) / d, below d / 2^(31 + l) <= 2^-31, times n stays below one unit
+void magic_of(unsigned d, unsigned &mul, unsigned &shift) {
+    mul = 0; shift = 0;
+    if (d < 2) return;
+    unsigned l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    mul = (unsigned)((((uint64_t)1 << (31 + l)) + d - 1) / d);
+    shift = l - 1;
+}
+void set_row_magic(TileArgs &ta) {
+    magic_of((unsigned)ta.cs.Q, ta.q_mul, ta.q_shift);
+    magic_of((unsigned)ta.cs.P, ta.p_mul, ta.p_shift);
+    magic_of((unsigned)ta.cs.W, ta.w_mul, ta.w_shift);
+    magic_of((unsigned)ta.cs.H, ta.h_mul, ta.h_shift);
+}
+
 void check_shape(const ConvShape &cs) {
     if (cs.N <= 0 || cs.H <= 0 || cs.W <= 0 || cs.C <= 0 || cs.K <= 0 || cs.R <= 0 || cs.S <= 0 || cs.stride <= 0 || cs.pad < 0)
         throw KernelError("conv: bad shape");
@@ -923,6 +997,7 @@ void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim, float *out, i
                  bool accumulate, const char *who) {
     constexpr int BM = 64 * WM, BN = 64 * WN, NT = 64 * WM * WN;
     if (splits < 1) throw KernelError(std::string(who) + ": splits must be >= 1");
+    set_row_magic(ta);
     if (splits > steps) splits = (int)std::max<int64_t>(steps, 1);
     int64_t tiles_m = (ta.Mg + BM - 1) / BM;
     ta.tiles_n = (ta.Ng + BN - 1) / BN;
@@ -1008,6 +1083,11 @@ void launch_batched(int cfg, Rest... rest) {
 
 void conv_force_tile(int cfg) { g_cfg_override = cfg; }
 
+bool conv_epilogue_writes_mask(const ConvShape &cs, bool winograd_fused) {
+    (void)winograd_fused;      // both forms: a word of the code is 64 consecutive channels of one position
+    return cs.K % 64 == 0;
+}
+
 void split_reduce(hipStream_t st, const float *ws, float *out, int64_t n, int splits, bool accumulate) {
     launch_split_reduce(st, ws, out, n, splits, accumulate);
 }
@@ -1043,20 +1123,6 @@ size_t conv_workspace_bytes(int which, const ConvShape &cs, int splits) {
 }
 
 namespace {
-// floor(n / d) = umulhi(n, mul) >> shift for every n < 2^31 (d >= 2): mul = ceil(2^(31 + l) / d) with l = ceil(log2 d)
-// fits 32 bits, and its excess over 2^(31 + l) / d, below d / 2^(31 + l) <= 2^-31, times n stays below one unit
-void magic_of(unsigned d, unsigned &mul, unsigned &shift) {
-    mul = 0; shift = 0;
-    if (d < 2) return;
-    unsigned l = 0;
-    while (((uint64_t)1 << l) < d) ++l;
-    mul = (unsigned)((((uint64_t)1 << (31 + l)) + d - 1) / d);
-    shift = l - 1;
-}
-void set_row_magic(TileArgs &ta) {
-    magic_of((unsigned)ta.cs.Q, ta.q_mul, ta.q_shift);
-    magic_of((unsigned)ta.cs.P, ta.p_mul, ta.p_shift);
-}
 }  // namespace
 
 void gemm_batched(hipStream_t st, const float *a, const float *b, float *out, int batch, int64_t rows, int cols, int red, bool adjoint_use) {
@@ -1091,7 +1157,6 @@ void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out,
     // the aligned loader addresses each operand plane with 32-bit byte offsets
     if (red * m * 4 >= ((int64_t)1 << 32) - (1 << 20) || red * n * 4 >= ((int64_t)1 << 32) - (1 << 20))
         throw KernelError("gemm_tn_batched: an operand plane of 4 GiB or more");
-    set_row_magic(ta);
     launch_tile<WGRAD, 2, 2, 3>(st, ta, true, batch, out, splits, ws, ws_bytes, (red + BK - 1) / BK, false, "gemm_tn_batched");
 }
 
@@ -1110,6 +1175,7 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
         throw KernelError("conv_fwd: statistics or BatchNorm in the epilogue need C % 16 == 0, K % 4 == 0, splits == 1 and no accumulation");
     if (stats_part && affine) throw KernelError("conv_fwd: either the statistics of the output or its BatchNorm apply step, not both");
     if (affine && (!affine->gamma || !affine->beta || !affine->stats)) throw KernelError("conv_fwd: incomplete BatchNorm coefficients");
+    if (affine && affine->mask && (!affine->relu || cs.K % 64)) throw KernelError("conv_fwd: a sign code in the epilogue needs the ReLU and K % 64 == 0");
     ta.stats_part = stats_part;
     if (affine) ta.affine = *affine;
     launch_cfg<FWD>(pick_cfg(FWD, ta.Mg, ta.Ng), st, ta, fast, 1, y, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, accumulate, "conv_fwd");
@@ -1147,7 +1213,6 @@ void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, cons
     const int64_t lead = ((int64_t)cs.pad * cs.W + cs.pad) * cs.C * 4;
     bool fast = cs.K % 4 == 0 && cs.C % 4 == 0 && cs.R * cs.S <= 32 && cs.M() * cs.K * 4 < span32 &&
                 (int64_t)cs.N * cs.H * cs.W * cs.C * 4 + lead < span32;
-    set_row_magic(ta);
     launch_cfg<WGRAD>(pick_cfg(WGRAD, ta.Mg, ta.Ng), st, ta, fast, 1, dw, splits, ws, ws_bytes, (ta.Kg + BK - 1) / BK, false, "conv_wgrad");
 }
 

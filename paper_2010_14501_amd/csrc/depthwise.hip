@@ -620,6 +620,7 @@ void dwconv_fwd(hipStream_t st, const float *x, const float *w, float *y, const 
     const size_t lds = (size_t)cs.C * cs.R * cs.S * 4;
     if (affine && (!dwconv_fwd_takes_affine(cs) || !affine->gamma || !affine->beta || !affine->stats))
         throw KernelError("dwconv_fwd: BatchNorm in the same kernel needs a 3x3 / pad 1 layer of stride 1 or 2 with C % 4 == 0 and all coefficients");
+    if (affine && affine->mask) throw KernelError("dwconv_fwd: this kernel does not write a sign code");
     const BnAffine bn = affine ? *affine : BnAffine{};
     if (cs.C % 4 == 0 && cs.R == 3 && cs.S == 3 && cs.pad == 1 && cs.stride == 1) {
         launch_dw3_row<1, 7, false, false>(st, x, w, y, cs.N, cs.H, cs.W, cs.P, cs.Q, cs.C, bn);

@@ -37,7 +37,13 @@ struct BnAffine {
     // (relu_out == null: both in place) or goes to relu_out, a tensor of the output's shape, beside it
     int relu = 0;
     float *relu_out = nullptr;
+    // ... and that ReLU's sign code, written as relu_fwd writes it (bit (e & 63) of word (e >> 6), e the element's linear
+    // index, set where the value passes); needs a multiple of 64 output channels.  The implicit GEMM and the one-kernel
+    // Winograd form take it, the other kernels refuse it.
+    unsigned long long *mask = nullptr;
 };
+// which convolution kernels can write the sign code from their epilogue
+bool conv_epilogue_writes_mask(const ConvShape &cs, bool winograd_fused);
 
 // ---- convolution (implicit GEMM on fp32 MFMA)
 // Every variant can cut its reduction into `splits` ranges: partial results go to ws (splits * |output|

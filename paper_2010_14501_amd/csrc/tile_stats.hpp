@@ -38,6 +38,24 @@ struct LaneStats {
         }
         n += 1.0f;
     }
+    // The same for a lane whose sixteen elements all exist, the first one and the later ones: what add() does on its
+    // first call (the element becomes the reference, its own deviation is zero) and on the following ones, without
+    // the test of n.  Same bits as add() for finite values.
+    __device__ inline void add_first(float v0, float v1, float v2, float v3) {
+        pv[0] = v0; pv[1] = v1; pv[2] = v2; pv[3] = v3;
+        n = 1.0f;
+    }
+    __device__ inline void add_next(float v0, float v1, float v2, float v3) {
+#pragma clang fp contract(off)
+        const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float d = v[j] - pv[j];
+            s1[j] += d;
+            s2[j] = __builtin_fmaf(d, d, s2[j]);
+        }
+        n += 1.0f;
+    }
 };
 
 // Merges the four lanes that share their columns; afterwards each of them holds the group's row count,
@@ -56,12 +74,19 @@ __device__ inline void merge_lane_stats(const LaneStats &ls, int lane, float &n,
         const bool low = (lane & mask) == 0;
         const float n_o = __shfl_xor(n, mask);
         const float na = low ? n : n_o, nb = low ? n_o : n, nt = na + nb;   // a = the lane with the bit clear
+        // whole groups (every lane of the wave holds the same non-zero count): nb / nt is one half and na * nb / nt is
+        // na / 2, both exact, so the general formula below gives these bits without its divisions
+        const bool whole = __all(n == n_o && n > 0.0f) != 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float mean_o = __shfl_xor(mean[j], mask), m2_o = __shfl_xor(m2[j], mask);
             const float ma = low ? mean[j] : mean_o, mb = low ? mean_o : mean[j];
             const float qa = low ? m2[j] : m2_o, qb = low ? m2_o : m2[j];
-            if (nb > 0.0f) {
+            if (whole) {
+                const float d = mb - ma;
+                mean[j] = ma + d * 0.5f;
+                m2[j] = qa + qb + d * d * (na * 0.5f);
+            } else if (nb > 0.0f) {
                 const float d = mb - ma;
                 mean[j] = na > 0.0f ? ma + d * (nb / nt) : mb;
                 m2[j] = qa + qb + (na > 0.0f ? d * d * (na * nb / nt) : 0.0f);

@@ -511,6 +511,7 @@ void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, 
     check_tile(m, "conv_winograd");
     if (affine && (adjoint || accumulate || !affine->gamma || !affine->beta || !affine->stats))
         throw KernelError("conv_winograd: a BatchNorm apply step goes with the forward form, without accumulation, and needs all coefficients");
+    if (affine && affine->mask) throw KernelError("conv_winograd: this form does not write a sign code");
     const BnAffine bn = affine ? *affine : BnAffine{};
     if (!winograd_applies(cs, adjoint)) throw KernelError("conv_winograd: needs a 3x3 / stride 1 / pad 1 layer with aligned channel counts");
     const WinoPlan wp = wino_plan(cs, m, ws_bytes, false);

@@ -279,7 +279,8 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
 // lies inside the map and the channel exists (no store needs a test).
 template <int EPI, bool WHOLE>
 __device__ __forceinline__ void fused_output(const float *mp, __amdgpu_buffer_rsrc_t ry, unsigned voff, unsigned orow, unsigned obytes, int nr,
-                                             int nc, float bn_a, float bn_b, int relu, __amdgpu_buffer_rsrc_t ry2, bool two) {
+                                             int nc, float bn_a, float bn_b, int relu, __amdgpu_buffer_rsrc_t ry2, bool two,
+                                             unsigned *mask32, int lane) {
     float s[6][4];      // s[b][a] = (A^T m)[a][b]
 #pragma unroll
     for (int b = 0; b < 6; ++b) {
@@ -295,7 +296,17 @@ __device__ __forceinline__ void fused_output(const float *mp, __amdgpu_buffer_rs
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const unsigned so = a * orow + b * obytes;
-            if (WHOLE || (a < nr && b < nc)) {
+            const bool here = WHOLE || (a < nr && b < nc);
+            if (EPI == 2 && mask32) {      // uniform over the wave
+                // the sign code of the ReLU: the 32 lanes of a half wave hold 32 consecutive channels of one position, half
+                // a word of the code; its first lane writes it
+                const float e = bn_affine(o[b], bn_a, bn_b);
+                const bool pass = here && (relu == 2 ? (e > 0.0f && e < 6.0f) : e > 0.0f);
+                const unsigned long long word = __ballot(pass);
+                const unsigned half = lane < 32 ? (unsigned)word : (unsigned)(word >> 32);
+                if ((lane & 31) == 0 && here) mask32[(voff + so) >> 7] = half;
+            }
+            if (here) {
                 float v = o[b];
                 if (EPI == 1) v += buffer_load(ry, voff, so);
                 if (EPI == 2) v = bn_affine(v, bn_a, bn_b);
@@ -377,8 +388,9 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
             unsigned ext = tinfo[tl][1];
             if (kout >= gm.outc) ext = 0;
             const float *mp = lds + tl * MROW + ok_;
-            if (__all(ext == (4u | (4u << 8)))) fused_output<EPI, true>(mp, ry, voff, orow, obytes, 4, 4, bn_a, bn_b, bn.relu, ry2, two);      // uniform over the wave
-            else fused_output<EPI, false>(mp, ry, voff, orow, obytes, (int)(ext & 0xff), (int)(ext >> 8), bn_a, bn_b, bn.relu, ry2, two);
+            unsigned *mask32 = EPI == 2 && bn.relu ? (unsigned *)bn.mask : nullptr;
+            if (__all(ext == (4u | (4u << 8)))) fused_output<EPI, true>(mp, ry, voff, orow, obytes, 4, 4, bn_a, bn_b, bn.relu, ry2, two, mask32, lane);      // uniform over the wave
+            else fused_output<EPI, false>(mp, ry, voff, orow, obytes, (int)(ext & 0xff), (int)(ext >> 8), bn_a, bn_b, bn.relu, ry2, two, mask32, lane);
         }
     }
 }
@@ -400,6 +412,8 @@ void conv_winograd_fused(hipStream_t st, const float *in, const float *w, float 
                          float *ws, size_t ws_bytes, const BnAffine *affine) {
     if (affine && (adjoint || accumulate || !affine->gamma || !affine->beta || !affine->stats))
         throw KernelError("conv_winograd_fused: a BatchNorm apply step goes with the forward form, without accumulation, and needs all coefficients");
+    if (affine && affine->mask && (!affine->relu || cs.K % 64))
+        throw KernelError("conv_winograd_fused: a sign code in the epilogue needs the ReLU and K % 64 == 0");
     if (!winograd_fused_applies(cs, adjoint))
         throw KernelError("conv_winograd_fused: needs a 3x3 / stride 1 / pad 1 layer whose reduction channels are a multiple of 8");
     if (!ws || ws_bytes < winograd_fused_workspace_bytes(cs, adjoint))

@@ -84,7 +84,7 @@ def load_library():
     lib.monet_conv_fwd_bn_stats.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp, sz, vp, f, vp, sz]
     lib.monet_conv_fwd_bn_apply.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz, vp, vp, vp]
     lib.monet_conv_fwd_bn_apply.restype = i32
-    lib.monet_conv_fwd_bn_relu.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz, vp, vp, vp, i32, vp]
+    lib.monet_conv_fwd_bn_relu.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp, sz, vp, vp, vp, i32, vp, vp]
     lib.monet_conv_fwd_bn_relu.restype = i32
     lib.monet_conv_winograd.argtypes = [vp, vp, vp, vp] + [i32] * 8 + [vp, sz]
     lib.monet_conv_winograd_fused.argtypes = [vp, vp, vp, vp] + [i32] * 7 + [vp, sz]

@@ -221,18 +221,42 @@ def test_batchnorm_apply_in_the_conv_epilogue_is_the_stand_alone_bits(case):
         monet.call("monet_relu_fwd", None, plain.data_ptr(), plain.data_ptr(), None, N * P * Q * K, six)
         both = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), both.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
-                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, None)
+                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, None, None)
         assert torch.equal(both, plain), six
         assert float(both.min()) == 0.0 and (not six or float(both.max()) == 6.0)
         # the ReLU's result beside the BatchNorm's (the BatchNorm output is kept for its own backward operator)
         bn_out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
         relu_out = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
-                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr())
+                   wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr(), None)
         want_bn = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), want_bn.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
                    wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr())
         assert torch.equal(bn_out, want_bn) and torch.equal(relu_out, plain), six
+        # ... and the ReLU's sign code from the same epilogue: the words of the stand-alone kernel (64 | K; the Winograd
+        # forms with transformed tensors in memory refuse it)
+        words = (N * P * Q * K + 63) // 64
+        mask = torch.full((words,), -1, dtype=torch.int64, device="cuda")
+        if K % 64 == 0 and m == 0:
+            for out2 in (None, relu_out):
+                mask.fill_(-1)
+                if out2 is not None:
+                    out2.fill_(float("nan"))
+                bn_out.fill_(float("nan"))
+                monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+                           wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, out2.data_ptr() if out2 is not None else None,
+                           mask.data_ptr())
+                want_mask = torch.full((words,), -1, dtype=torch.int64, device="cuda")
+                scratch = torch.empty_like(want_bn)
+                monet.call("monet_relu_fwd", None, want_bn.data_ptr(), scratch.data_ptr(), want_mask.data_ptr(), N * P * Q * K, six)
+                assert torch.equal(mask, want_mask), (six, out2 is None)
+                assert torch.equal(bn_out if out2 is None else out2, plain), six
+                if out2 is not None:
+                    assert torch.equal(bn_out, want_bn)
+        else:
+            with pytest.raises(monet.MonetError):
+                monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, R, R, stride, pad, m,
+                           wsp, need, g6.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr(), mask.data_ptr())
     with pytest.raises(monet.MonetError):       # no Winograd form with 3x3 output tiles
         monet.call("monet_conv_fwd_bn_apply", None, dx.data_ptr(), dwt.data_ptr(), fused.data_ptr(), N, H, W, C, K, R, R, stride, pad, 3,
                    wsp, need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr())
@@ -346,15 +370,31 @@ def test_fused_winograd_convolution_matches_oracle(case):
         for six in (0, 1):      # the ReLU behind the BatchNorm in the same epilogue
             both = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
             monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), both.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
-                       ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, None)
+                       ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, None, None)
             plain = y.clone()
             monet.call("monet_relu_fwd", None, plain.data_ptr(), plain.data_ptr(), None, N * H * W * K, six)
             assert torch.equal(both, plain), six
             bn_out = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
             relu_out = torch.full((N, H, W, K), float("nan"), dtype=torch.float32, device="cuda")
             monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
-                       ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr())
+                       ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr(), None)
             assert torch.equal(bn_out, y) and torch.equal(relu_out, plain), six
+            words = (N * H * W * K + 63) // 64
+            mask = torch.full((words,), -1, dtype=torch.int64, device="cuda")
+            if K % 64 == 0:      # the ReLU's sign code from the same epilogue: the words of the stand-alone kernel
+                bn_out.fill_(float("nan"))
+                relu_out.fill_(float("nan"))
+                monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
+                           ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr(), mask.data_ptr())
+                want_mask = torch.full((words,), -1, dtype=torch.int64, device="cuda")
+                scratch = torch.empty_like(y)
+                monet.call("monet_relu_fwd", None, y.data_ptr(), scratch.data_ptr(), want_mask.data_ptr(), N * H * W * K, six)
+                assert torch.equal(mask, want_mask), six
+                assert torch.equal(bn_out, y) and torch.equal(relu_out, plain), six
+            else:
+                with pytest.raises(monet.MonetError):
+                    monet.call("monet_conv_fwd_bn_relu", None, dx.data_ptr(), dwt.data_ptr(), bn_out.data_ptr(), N, H, W, C, K, 3, 3, 1, 1, 5,
+                               ws.data_ptr(), need, dg_.data_ptr(), db_.data_ptr(), dst.data_ptr(), six, relu_out.data_ptr(), mask.data_ptr())
     want = nm.bn_apply(want_y, gamma.astype(np.float64), beta.astype(np.float64), stats[:K].astype(np.float64), stats[K:].astype(np.float64))
     check_close(fused.cpu().numpy(), wt.act_from_oracle(want), ACT_TOL)
     # input gradient: reduction over K, which must be a multiple of 8

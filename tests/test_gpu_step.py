@@ -241,13 +241,16 @@ def test_recomputed_relu_rides_in_the_convolution_epilogue_when_its_mask_is_kept
     exts, params = tensors.make_inputs(g, seed=5, gamma_beta="random")
     masks = {n.id for n in g.nodes if g.is_aux(n.id) and g.nodes[n.ins[0] - 1].op in ("relu", "relu6")}
     F = schedules.block_output_set(g)
-    grads = {}
+    grads, alone = {}, {}
     for name, saved in (("blocks", F), ("blocks+masks", F | masks)):
         sch = schedules.schedule_for_saved_set(g, saved)
         for fusion in (True, False):
             run = StepRunner(g.text(), sch.text(), exts, params)
             run.plan.set_fusion(fusion)
-            labels = [l[0] for l in run.plan.launches()]
+            launches = run.plan.launches()
+            labels = [l[0] for l in launches]
+            # channel counts of the ReLUs that are recomputed as launches of their own
+            alone[(name, fusion)] = sorted(g.nodes[l[2] - 1].shape[-1] for l in launches if l[0] == "relu_fwd" and l[1] == 3)
             peak = run.step()
             assert peak == run.plan.exact_peak == osch.interpret(g.text(), sch.text())["peak"]
             grads[(name, fusion)] = (run.grads_numpy(), labels.count("relu_fwd"), len(labels))
@@ -255,6 +258,10 @@ def test_recomputed_relu_rides_in_the_convolution_epilogue_when_its_mask_is_kept
     # with the masks kept, the recomputed ReLUs are gone from the fused program
     assert grads[("blocks+masks", True)][1] < grads[("blocks+masks", False)][1]
     assert grads[("blocks+masks", True)][1] < grads[("blocks", True)][1]
+    # without the masks kept, a recomputed ReLU writes its mask again: it rides in the epilogue as well where a word of the
+    # mask is 64 channels of one position (the 64-channel layers of this network), and stays a launch elsewhere
+    assert any(c % 64 == 0 for c in alone[("blocks", False)]) and alone[("blocks", True)]
+    assert all(c % 64 != 0 for c in alone[("blocks", True)])
     ref = grads[("blocks", False)][0]
     for key, (got, _, _) in grads.items():
         assert all(np.array_equal(got[p], ref[p]) for p in ref), key
