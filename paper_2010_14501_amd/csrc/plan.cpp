@@ -447,8 +447,12 @@ void Plan::lower() {
     // placed, or as soon as a launch of another kind (which ends any such run) is placed; until then only a
     // request of exactly its size may take it.  The events and the
     // live-byte count follow the algorithms exactly; the delay only concerns which offsets later allocations take.
+    // The same holds for the small workspace of a recomputed convolution (the cut tiles of the implicit GEMM, the
+    // transformed filters of the one-kernel Winograd form): the executor may run the BatchNorm and the ReLU behind it in
+    // the convolution's epilogue, whose tiles read the workspace until the last one is done, so the ReLU's buffers must
+    // not take its place.  Such a block waits the same way but is never handed to a request of its own size.
     constexpr size_t kReuseLag = 2;
-    struct Pending { size_t when; int64_t off, bytes; };
+    struct Pending { size_t when; int64_t off, bytes; bool same_size_ok; };
     std::deque<Pending> pending;
     auto chainable = [&](const Launch &L) {
         if (L.kind == EV_RUN_BWD) {
@@ -472,13 +476,20 @@ void Plan::lower() {
         // a waiting block of exactly this size may be taken whole: element i of the new tensor then sits on
         // element i of the old one, which the same thread of a fused kernel has read before it writes
         for (auto it = pending.begin(); it != pending.end(); ++it)
-            if (it->bytes == bytes) { off = it->off; pending.erase(it); break; }
+            if (it->same_size_ok && it->bytes == bytes) { off = it->off; pending.erase(it); break; }
         if (off < 0) off = arena.alloc(bytes);
         ev(EV_ALLOC, stage, node, -1, cls, bytes);
         return off;
     };
     auto arena_free = [&](int stage, int node, int cls, int64_t off, int64_t bytes) {
-        if (!launches.empty() && chainable(launches.back())) pending.push_back(Pending{launches.size(), off, bytes});
+        bool conv_ws = false;
+        if (cls == T_FWS && !launches.empty() && launches.back().kind == EV_RUN_RECOMPUTE) {
+            const Node &n = g.nodes[launches.back().id];
+            const std::string &algo = n.fimpls[launches.back().impl].algo;
+            conv_ws = n.op == "conv" && algo != "winograd" && algo != "winograd4" && algo != "im2col";
+        }
+        if (!launches.empty() && chainable(launches.back())) pending.push_back(Pending{launches.size(), off, bytes, true});
+        else if (conv_ws) pending.push_back(Pending{launches.size(), off, bytes, false});
         else arena.release(off, bytes);
         ev(EV_FREE, stage, node, -1, cls, bytes);
         poison.push_back(PoisonFill{launches.size(), off, bytes});
