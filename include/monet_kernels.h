@@ -114,6 +114,18 @@ int monet_conv_im2col_fwd(void *stream, const float *x, const float *w, float *y
 int monet_conv_im2col_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int C, int K, int R, int S,
                             int stride, int pad, float *ws, size_t ws_bytes);
 int64_t monet_conv_im2col_workspace_bytes(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int wgrad);
+/* First layers: forward pass and filter gradient of a convolution over a three-channel image (the networks of Section 5
+ * all start with one; same definitions and layouts as monet_conv_fwd / monet_conv_wgrad with C = 3, same results to
+ * rounding).  The input rows under a tile of output positions are staged in LDS as they lie in memory and read from
+ * there by the matrix instruction, so no patch matrix is formed and no load goes element by element.  Needs R == S,
+ * (R, stride) one of (7, 2), (3, 1), (3, 2), K one of 32, 64, 96, 128 and an output row of any width (rows wider than 224
+ * positions are worked through in segments); a negative status otherwise.  Filter gradient: splits >= 2 and a device
+ * workspace of min(splits, 1024, tiles) * K * R * S * 3 floats, tiles = N * ceil(P / rows per tile) * segments (partial
+ * results of the workgroups, added in a fixed order: two calls agree bit for bit).  monet_conv_fwd (splits == 1, no
+ * accumulation) and monet_conv_wgrad take these forms by themselves where they apply. */
+int monet_conv_stem_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int K, int R, int S, int stride, int pad);
+int monet_conv_stem_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int K, int R, int S, int stride,
+                          int pad, int splits, float *ws, size_t ws_bytes);
 /* Filter gradient of a 1x1 / stride 1 / unpadded convolution with few channels on one side (the expansion and projection
  * layers of an inverted-residual block on its large maps): dw[K,1,1,C] = sum over the N*H*W positions of dy[.,k] x[.,c],
  * a reduction of the two activation tensors into a small matrix and so bound by reading them once (one more

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmonet.so")
-SOURCES = ["plan.cpp", "api.cpp", "elementwise.hip", "bn.hip", "fused.hip", "depthwise.hip", "conv.hip", "winograd.hip", "winograd_fused.hip", "im2col.hip", "pointwise.hip"]
+SOURCES = ["plan.cpp", "api.cpp", "elementwise.hip", "bn.hip", "fused.hip", "depthwise.hip", "conv.hip", "winograd.hip", "winograd_fused.hip", "im2col.hip", "pointwise.hip", "stem.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1114,6 +1114,14 @@ extern "C" int monet_conv_pointwise_wgrad(void *stream, const float *x, const fl
                                          float *ws, size_t ws_bytes) {
     return guarded([&] { pointwise_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, C, K, 1, 1, 1, 0), splits, ws, ws_bytes); });
 }
+extern "C" int monet_conv_stem_fwd(void *stream, const float *x, const float *w, float *y, int N, int H, int W, int K, int R, int S, int stride,
+                                   int pad) {
+    return guarded([&] { stem_fwd((hipStream_t)stream, x, w, y, mk_conv(N, H, W, 3, K, R, S, stride, pad)); });
+}
+extern "C" int monet_conv_stem_wgrad(void *stream, const float *x, const float *dy, float *dw, int N, int H, int W, int K, int R, int S,
+                                     int stride, int pad, int splits, float *ws, size_t ws_bytes) {
+    return guarded([&] { stem_wgrad((hipStream_t)stream, x, dy, dw, mk_conv(N, H, W, 3, K, R, S, stride, pad), splits, ws, ws_bytes); });
+}
 extern "C" int monet_conv_force_tile(int cfg) {
     if (cfg < -1 || cfg > 5) { g_err = "monet_conv_force_tile: cfg must be -1..5"; return MONET_BAD_ARGUMENT; }
     conv_force_tile(cfg);

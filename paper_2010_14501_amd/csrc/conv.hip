@@ -1163,6 +1163,11 @@ void gemm_tn_batched(hipStream_t st, const float *a, const float *b, float *out,
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits, float *ws, size_t ws_bytes,
               bool accumulate, float *stats_part, const BnAffine *affine) {
     check_shape(cs);
+    // first layers (three input channels): input rows staged in LDS as they lie in memory (stem.hip)
+    if (g_cfg_override < 0 && splits == 1 && !accumulate && !stats_part && !affine && stem_applies(cs)) {
+        stem_fwd(st, x, w, y, cs);
+        return;
+    }
     TileArgs ta{};
     ta.a = x; ta.b = w; ta.cs = cs;
     ta.Mg = cs.M(); ta.Ng = cs.K; ta.Kg = cs.RSC();
@@ -1199,6 +1204,11 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
 
 void conv_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes) {
     check_shape(cs);
+    // first layers (three input channels): input rows staged in LDS as they lie in memory (stem.hip)
+    if (g_cfg_override < 0 && ws && stem_wgrad_applies(cs, splits, ws_bytes)) {
+        stem_wgrad(st, x, dy, dw, cs, splits, ws, ws_bytes);
+        return;
+    }
     // 1x1 layers with at most 32 channels on one side: streamed straight into the matrix instruction (pointwise.hip)
     if (g_cfg_override < 0 && ws && pointwise_wgrad_applies(cs, splits, ws_bytes)) {
         pointwise_wgrad(st, x, dy, dw, cs, splits, ws, ws_bytes);

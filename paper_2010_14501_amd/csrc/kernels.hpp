@@ -102,6 +102,16 @@ void conv_im2col_fwd(hipStream_t st, const float *x, const float *w, float *y, c
                      bool accumulate);
 void conv_im2col_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, float *ws, size_t ws_bytes);
 
+// First layers (three input channels; 7x7 / stride 2, 3x3 / stride 1 or 2; 32 .. 128 output channels): the input rows
+// under a tile of output positions are staged in LDS as they lie in memory and read from there by the matrix instruction
+// (stem.hip).  conv_fwd takes this path by itself where it applies.
+bool stem_applies(const ConvShape &cs);
+void stem_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs);
+// ... and their filter gradient: min(splits, 1024, tiles) workgroups leave partial results in ws (that many times
+// K * R * S * 3 floats), added in a fixed order.  conv_wgrad takes this path by itself where it applies.
+bool stem_wgrad_applies(const ConvShape &cs, int splits, size_t ws_bytes);
+void stem_wgrad(hipStream_t st, const float *x, const float *dy, float *dw, const ConvShape &cs, int splits, float *ws, size_t ws_bytes);
+
 // out[i] (+)= sum over z < splits of ws[z * n + i], in a fixed order
 void split_reduce(hipStream_t st, const float *ws, float *out, int64_t n, int splits, bool accumulate);
 // Filter gradient of a 1x1 / stride-1 convolution with at most 32 channels on one side and at most 192 on the other

@@ -96,6 +96,10 @@ def load_library():
     lib.monet_conv_im2col_fwd.restype = i32
     lib.monet_conv_im2col_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp, sz]
     lib.monet_conv_im2col_wgrad.restype = i32
+    lib.monet_conv_stem_fwd.argtypes = [vp, vp, vp, vp] + [i32] * 8
+    lib.monet_conv_stem_fwd.restype = i32
+    lib.monet_conv_stem_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp, sz]
+    lib.monet_conv_stem_wgrad.restype = i32
     lib.monet_conv_pointwise_wgrad.argtypes = [vp, vp, vp, vp] + [i32] * 6 + [vp, sz]
     lib.monet_conv_pointwise_wgrad.restype = i32
     lib.monet_conv_im2col_workspace_bytes.argtypes = [i32] * 10

@@ -508,6 +508,77 @@ def test_filter_gradient_with_many_short_ranges_on_every_tile_shape(case):
         monet.call("monet_conv_force_tile", -1)
 
 
+STEM_CASES = [
+    # N, H, W, K, R, stride, pad, splits: the first layers of the five networks at reduced batch, sizes that leave ragged
+    # tiles (odd maps, a last row tile with fewer rows, rows no multiple of four floats), rows wider than one tile
+    (2, 224, 224, 64, 7, 2, 3, 64),       # ResNet-50 / inception: two output rows per tile
+    (2, 224, 224, 32, 3, 2, 1, 64),       # MobileNetV2: one wave per position group
+    (2, 224, 224, 64, 3, 1, 1, 64),       # VGG-16: one output row per tile
+    (3, 37, 29, 64, 7, 2, 3, 16),
+    (3, 37, 29, 32, 3, 2, 1, 7),
+    (2, 33, 31, 96, 3, 1, 1, 5),
+    (1, 40, 608, 64, 3, 1, 1, 9),         # UNet: rows of 608 positions in segments of 224
+    (1, 19, 300, 128, 3, 1, 1, 4),
+    (5, 9, 9, 32, 3, 1, 1, 2),
+    (1, 7, 5, 64, 7, 2, 3, 2),            # a map smaller than the filter's reach
+]
+
+
+@pytest.mark.parametrize("case", STEM_CASES)
+def test_first_layer_forward_and_filter_gradient_from_rows_staged_in_lds(case):
+    """Convolutions of a three-channel image through the kernels that stage input rows in LDS: forward pass and filter
+    gradient against the oracle, the filter gradient twice (bit-identical), and monet_conv_fwd / monet_conv_wgrad with
+    the same arguments give the same bits, i.e. take these forms by themselves."""
+    torch = torch_mod()
+    N, H, W, K, R, stride, pad, splits = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    x = rng.standard_normal((N, H, W, 3), dtype=np.float32)
+    w = (rng.standard_normal((K, R, R, 3), dtype=np.float32) * np.float32(np.sqrt(2.0 / (3 * R * R))))
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - R) // stride + 1
+    dy = rng.standard_normal((N, P, Q, K), dtype=np.float32)
+    xo, wo, dyo = wt.act_to_oracle(x), wt.weight_to_oracle(w), wt.act_to_oracle(dy)
+    dx, dwt, ddy = dev(x), dev(w), dev(dy)
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_stem_fwd", None, dx.data_ptr(), dwt.data_ptr(), y.data_ptr(), N, H, W, K, R, R, stride, pad)
+    check_close(y.cpu().numpy(), wt.act_from_oracle(nm.conv2d_fwd(xo, wo, stride, pad)), ACT_TOL, what="forward")
+    y2 = torch.full((N, P, Q, K), float("nan"), dtype=torch.float32, device="cuda")
+    monet.call("monet_conv_fwd", None, dx.data_ptr(), dwt.data_ptr(), y2.data_ptr(), N, H, W, 3, K, R, R, stride, pad, 1, None, 0)
+    assert torch.equal(y, y2), "monet_conv_fwd did not take the first-layer form"
+    ws = torch.empty(splits * K * R * R * 3, dtype=torch.float32, device="cuda")
+    got = []
+    for entry in ("monet_conv_stem_wgrad", "monet_conv_stem_wgrad", "monet_conv_wgrad"):
+        gw = torch.full((K, R, R, 3), float("nan"), dtype=torch.float32, device="cuda")
+        ws.fill_(float("nan"))
+        if entry == "monet_conv_wgrad":
+            monet.call(entry, None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, 3, K, R, R, stride, pad, splits, ws.data_ptr(), ws.numel() * 4)
+        else:
+            monet.call(entry, None, dx.data_ptr(), ddy.data_ptr(), gw.data_ptr(), N, H, W, K, R, R, stride, pad, splits, ws.data_ptr(), ws.numel() * 4)
+        torch.cuda.synchronize()
+        got.append(gw.cpu().numpy())
+    assert np.array_equal(got[0], got[1]), "two runs differ"
+    assert np.array_equal(got[0], got[2]), "monet_conv_wgrad did not take the first-layer form"
+    check_close(got[0], wt.weight_from_oracle(nm.conv2d_wgrad(xo, dyo, R, R, stride, pad)), GRAD_TOL, what="filter gradient")
+
+
+def test_first_layer_kernels_refuse_what_they_are_not_for():
+    torch = torch_mod()
+    t = torch.zeros(1 << 20, device="cuda")
+    for (N, H, W, K, R, stride, pad) in [
+        (1, 32, 32, 48, 3, 1, 1),      # output channels no multiple of 32
+        (1, 32, 32, 64, 5, 1, 2),      # 5x5 filter
+        (1, 32, 32, 64, 7, 1, 3),      # 7x7 at stride 1
+        (1, 32, 32, 160, 3, 1, 1),     # more than four blocks of 32 output channels
+    ]:
+        with pytest.raises(M.MonetError):
+            monet.call("monet_conv_stem_fwd", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), N, H, W, K, R, R, stride, pad)
+    with pytest.raises(M.MonetError):      # no partial results asked for
+        monet.call("monet_conv_stem_wgrad", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 1, 32, 32, 64, 3, 3, 1, 1, 1, t.data_ptr(), 1 << 22)
+    with pytest.raises(M.MonetError):      # workspace one float short (five tiles of seven output rows: five workgroups)
+        monet.call("monet_conv_stem_wgrad", None, t.data_ptr(), t.data_ptr(), t.data_ptr(), 1, 32, 32, 64, 3, 3, 1, 1, 8, t.data_ptr(),
+                   5 * 64 * 27 * 4 - 4)
+
+
 POINTWISE_WGRAD_CASES = [
     # N, H, W, C, K, splits: the channel pairs of MobileNetV2's expansion / projection layers (each selects another
     # combination of 16-byte and 4-byte loads of the wide side), position counts that leave a ragged tail, workgroups
