@@ -211,9 +211,9 @@ __global__ __launch_bounds__(256, 2) void stem_fwd_kernel(const float *__restric
 // block of dw of its output channels in registers (NBC column blocks of 32) over all its tiles and leaves it in
 // part[workgroup] at the end.
 template <int R, int S, int ST>
-__global__ __launch_bounds__(256, 3) void stem_wgrad_kernel(const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, StemGeom gm) {
+__global__ __launch_bounds__(256, 2) void stem_wgrad_kernel(const float *__restrict__ x, const float *__restrict__ dy, float *__restrict__ part, StemGeom gm) {
     extern __shared__ float lds[];
-    constexpr int RUN = 3 * S, COLS = R * RUN, NBC = (COLS + 31) / 32, U = NBC >= 4 ? 4 : 16;
+    constexpr int RUN = 3 * S, COLS = R * RUN, NBC = (COLS + 31) / 32, U = NBC >= 4 ? 8 : 16;
     const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const int kb = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = blockDim.x;
