@@ -831,11 +831,10 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                         const unsigned t_soff = (unsigned)(16 * q + 4 * i) * row_bytes;
                         int64_t orow = row;
                         if (!IN && MODE == DGRAD && cs.stride > 1) {
-                            int wc = (int)(row % Wc);
-                            int64_t t = row / Wc;
-                            int hc = (int)(t % Hc);
-                            int64_t n = t / Hc;
-                            orow = (n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
+                            // rows are bounded below 2^31 by the host: 32-bit divisions
+                            const unsigned r32 = (unsigned)row, t = r32 / (unsigned)Wc, n = t / (unsigned)Hc;
+                            const int wc = (int)(r32 - t * (unsigned)Wc), hc = (int)(t - n * (unsigned)Hc);
+                            orow = ((int64_t)n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
                         }
                         float4 *dst = (float4 *)(out + orow * ta.Ng + col);
                         if (do_acc) {
@@ -897,11 +896,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             if (row >= Mg) continue;
             int64_t orow = row;
             if (MODE == DGRAD && cs.stride > 1) {   // class row (n,hc,wc) -> position (n, hc*st+ph, wc*st+pw)
-                int wc = (int)(row % Wc);
-                int64_t t = row / Wc;
-                int hc = (int)(t % Hc);
-                int64_t n = t / Hc;
-                orow = (n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
+                const unsigned r32 = (unsigned)row, t = r32 / (unsigned)Wc, n = t / (unsigned)Hc;      // rows are bounded below 2^31 by the host
+                const int wc = (int)(r32 - t * (unsigned)Wc), hc = (int)(t - n * (unsigned)Hc);
+                orow = ((int64_t)n * cs.H + (hc * cs.stride + ph)) * cs.W + (wc * cs.stride + pw);
             }
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
