@@ -9,17 +9,19 @@
 //
 // so consecutive output positions are ST*3 floats apart in LDS and no patch matrix is ever formed.  The reduction of a
 // filter row is padded from 3 S to the next even number (the matrix instruction takes two reduction indices; the filter
-// value of the padding is zero, the input value is whatever finite number follows in LDS).
+// value of the padding is zero, its input value a float of the position's own window read a second time).
 //
 // Forward: mfma_f32_32x32x2f32 with A = positions x reduction (lane (m, h) reads LDS[off(m) + r * rowlen + 2 t + h]),
 // B = the filters of 32 output channels, resident in registers for the whole launch (R * ceil(3 S / 2) values per lane).
-// A wave takes MBW blocks of 32 consecutive positions and 32 output channels; a workgroup (K / 32 waves) one tile of
-// up to 32 * MBW positions: whole output rows if they fit, else a segment of one row.  Workgroups loop over tiles.
+// A wave takes four blocks of 32 consecutive positions and 32 output channels; a workgroup (K / 32 waves per group of
+// four blocks, at most four waves) one tile of up to 224 positions: whole output rows if they fit, else a segment of
+// one row.  Workgroups loop over tiles.
 //
 // Filter gradient: dw[k][r][j] = sum_m dy[m][k] * x_row(m, r)[j]: A = dy (positions are the reduction index now, read
 // from memory in the instruction's layout: lane (k, h) loads dy[m + h][k]), B = lane (col, h) reads
-// LDS[off(m + h) + r(col) * rowlen + j(col)] with col = (r, j) flattened.  Wave nb of a workgroup owns columns
-// 32 nb .. 32 nb + 31 of all K rows; the workgroups' partial results are added in a fixed order by split_reduce.
+// LDS[off(m + h) + r(col) * rowlen + j(col)] with col = (r, j) flattened.  Wave kb of a workgroup owns the 32 output
+// channels 32 kb .. 32 kb + 31 and all R * 3 S columns; the workgroups' partial results are added in a fixed order by
+// split_reduce.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
