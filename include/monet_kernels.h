@@ -119,7 +119,9 @@ int64_t monet_conv_im2col_workspace_bytes(int N, int H, int W, int C, int K, int
  * rounding).  The input rows under a tile of output positions are staged in LDS as they lie in memory and read from
  * there by the matrix instruction, so no patch matrix is formed and no load goes element by element.  Needs R == S,
  * (R, stride) one of (7, 2), (3, 1), (3, 2), K one of 32, 64, 96, 128 and an output row of any width (rows wider than 224
- * positions are worked through in segments); a negative status otherwise.  Filter gradient: splits >= 2 and a device
+ * positions are worked through in segments); a negative status otherwise, also where the input rows under a tile exceed
+ * what the forward kernel stages per workgroup (the 7x7 filter with 32 output channels, or on rows wider than about 380
+ * pixels).  Filter gradient: splits >= 2 and a device
  * workspace of min(splits, 1024, tiles) * K * R * S * 3 floats, tiles = N * ceil(P / rows per tile) * segments (partial
  * results of the workgroups, added in a fixed order: two calls agree bit for bit).  monet_conv_fwd (splits == 1, no
  * accumulation) and monet_conv_wgrad take these forms by themselves where they apply. */
