@@ -45,7 +45,7 @@ int monet_conv_fwd(void *stream, const float *x, const float *w, float *y,
 int monet_conv_reset_arrivals(void *stream);
 /* monet_conv_fwd followed by monet_bn_stats of its output, with the statistics' first level computed in the
  * convolution's epilogue instead of a pass over y (the largest of the fusions the executor applies between a
- * convolution and the BatchNorm behind it).  Needs C % 16 == 0 and K % 4 == 0; ws / ws_bytes as for monet_conv_fwd
+ * convolution and the BatchNorm behind it).  Needs C % 16 == 0 (a 1x1 layer: C % 4 == 0) and K % 4 == 0; ws / ws_bytes as for monet_conv_fwd
  * with splits == 1; scratch >= 8 * (G + ceil(G / 64)) * K bytes with G = ceil(N*P*Q / 64).  `stats` is bit-identical to monet_bn_stats(y)
  * called with the same scratch size. */
 int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float *y,
@@ -55,7 +55,7 @@ int monet_conv_fwd_bn_stats(void *stream, const float *x, const float *w, float 
  * element) done in the convolution's epilogue: the form a recomputed convolution takes when the BatchNorm behind it
  * is recomputed in place, because then the statistics are the forward pass's (Section 3: recomputation repeats the
  * forward operator; Appendix D: in-place operators).  `stats` = mean[K] then 1/sqrt(var+eps)[K] as monet_bn_stats
- * leaves them, `gamma`, `beta` [K].  winograd_m = 0: implicit GEMM (needs C % 16 == 0, K % 4 == 0; ws / ws_bytes as for
+ * leaves them, `gamma`, `beta` [K].  winograd_m = 0: implicit GEMM (needs C % 16 == 0, or C % 4 == 0 for a 1x1 layer, and K % 4 == 0; ws / ws_bytes as for
  * monet_conv_fwd with splits == 1); winograd_m = 2 or 4: the Winograd form below (3x3 / stride 1 / pad 1 only, its
  * workspace); winograd_m = 5: the one-kernel F(4x4) form (monet_conv_winograd_fused, its workspace).  y is bit-identical
  * to the two separate calls. */

@@ -507,7 +507,7 @@ bool conv_feeds_bn_stats(const Plan &pl, const Launch &L1, const Launch &L2) {
     if (cv.op != "conv" || bn.op != "bn" || bn.ins[0] != cv.id) return false;
     const ConvShape cs = conv_shape(g, cv);
     if (winograd_tile(cv.fimpls[L1.impl].algo) || cv.fimpls[L1.impl].algo == "im2col") return false;
-    if (cs.C % 16 || cs.K % 4 || splits_of(cv.fimpls[L1.impl].algo, cv.fimpls[L1.impl].extra) != 1) return false;
+    if (!conv_fwd_aligned(cs) || cs.K % 4 || splits_of(cv.fimpls[L1.impl].algo, cv.fimpls[L1.impl].extra) != 1) return false;
     return bn_stats_in_row_groups(cs.M(), cs.K, (size_t)pl.scratch_bytes);
 }
 
@@ -527,7 +527,7 @@ bool conv_applies_bn(const Plan &pl, const Launch &L1, const Launch &L2) {
     if (im.algo == "im2col") return false;
     if (winograd_is_fused(im.algo)) return winograd_fused_applies(cs, false);
     if (winograd_tile(im.algo)) return winograd_applies(cs, false);
-    return cs.C % 16 == 0 && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
+    return conv_fwd_aligned(cs) && cs.K % 4 == 0 && splits_of(im.algo, im.extra) == 1;
 }
 
 // ... and the ReLU (ReLU6) behind that BatchNorm: the clamp is one more operation on the value the epilogue holds.  In

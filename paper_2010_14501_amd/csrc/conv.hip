@@ -91,7 +91,9 @@ __device__ inline float4 ld4(const float *p) { return *(const float4 *)p; }
 
 // TAG only names the use in profiles: 0 a convolution, 1 / 2 / 3 the batched GEMMs of a Winograd forward / input gradient /
 // filter gradient
-template <int MODE, int WM, int WN, bool FAST, int TAG = 0>
+// FAST: 0 element-wise loaders, 1 aligned loaders, 2 aligned loaders of a 1x1 layer whose last reduction step is partly
+// empty (a kernel of its own: the two tests per step would cost the other layers 2 %, measured on ResNet-50)
+template <int MODE, int WM, int WN, int FAST, int TAG = 0>
 __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN == 4 ? 3 : 2))) void conv_tile_kernel(TileArgs ta) {
     // The square four-wave tile runs four workgroups per CU (4 x 40 KiB of LDS, 128 registers per lane) and
     // prefetches one reduction step; the other tiles keep two register stages (loads two steps ahead) at three
@@ -401,6 +403,10 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
     struct Present { bool a[LA], b[LB]; };
     auto load_tiles = [&](float4 (&a_reg)[LA], float4 (&b_reg)[LB], Present &pm, int &full) {
         bool every = FAST;      // every slot of this lane holds data
+        // 1x1 layers whose reduction length is a multiple of 4 only: the last step holds `left` < 16 reduction indices
+        // (uniform over the workgroup; every other step, and every step of the other layers, is whole)
+        const int left = (int)(Kg - kk0 < BK ? Kg - kk0 : BK);
+        const bool part_step = FAST == 2 && MODE != WGRAD && left < BK;
         // aligned filter gradient: the table entries of this lane's B slots, read before anything else is issued
         unsigned long long w_row[LB];
         if (ROWTAB) {
@@ -418,6 +424,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                     // scalar: tap number and offset; an absent element reads float u_c of the tensor instead
                     const unsigned tapoff = (unsigned)(((int64_t)u_r * cs.W + u_s) * cs.C);
                     ok = (a_taps[s] >> (u_r * cs.S + u_s)) & 1u;
+                    if (part_step) ok = ok && (idx % 4) * 4 < left;
                     const bf4 q = buffer_load4(ra, ok ? a_voff[s] : ((unsigned)a_shift - tapoff) * 4u, (tapoff + (unsigned)u_c) * 4u);
                     v = make_float4(q.x, q.y, q.z, q.w);
                 } else if (HAS_KTAB && use_ktab) {
@@ -454,6 +461,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                     // the descriptor starts a_shift floats early: tap (u_r, u_s) lies tapoff floats before the slot's offset
                     const unsigned tapoff = (unsigned)(((int64_t)u_r * cs.Q + u_s) * cs.K);
                     ok = (a_taps[s] >> (u_r * ns + u_s)) & 1u;
+                    if (part_step) ok = ok && (idx % 4) * 4 < left;
                     const bf4 q = buffer_load4(ra, ok ? a_voff[s] : tapoff * 4u, ((unsigned)a_shift - tapoff + (unsigned)u_c) * 4u);
                     v = make_float4(q.x, q.y, q.z, q.w);
                 } else {
@@ -499,7 +507,10 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
             if (MODE == FWD) {
                 if (FAST) {
                     ok = b_ok[s];
-                    const bf4 q = buffer_load4(rb, b_voff[s], (unsigned)kk0 * 4u);
+                    unsigned vo = b_voff[s];
+                    // beyond the filter row's end: the row's floats kk0 .. kk0 + 3 instead (in bounds), zeroed below
+                    if (part_step && b_i1[s] >= left) { vo = ok ? vo - (unsigned)b_i1[s] * 4u : 0u; ok = false; }
+                    const bf4 q = buffer_load4(rb, vo, (unsigned)kk0 * 4u);
                     v = make_float4(q.x, q.y, q.z, q.w);
                 } else {
                     float e[4] = {0, 0, 0, 0};
@@ -512,10 +523,13 @@ __global__ __launch_bounds__(64 * WM * WN, (WM == 2 && WN == 2 ? 4 : (WM * WN ==
                 // B[red = (tap, k)][col = c] = W[k][r0 + st*tr][s0 + st*ts][c]
                 int64_t kk = kk0 + b_i0[s];
                 if (FAST) {
-                    // K % 16 == 0: a step never reaches beyond the reduction
+                    // a step reaches beyond the reduction only in the last step of a 1x1 layer with K % 16 != 0 (part_step)
                     const int r = r0 + cs.stride * u_r, ss = s0 + cs.stride * u_s;
                     ok = b_ok[s];
-                    const bf4 q = buffer_load4(rb, b_voff[s], (unsigned)(((int64_t)u_c * RSC + (r * cs.S + ss) * cs.C) * 4));
+                    unsigned vo = b_voff[s];
+                    // a filter beyond the last one: the step's first filter instead (in bounds), zeroed below
+                    if (part_step && b_i0[s] >= left) { vo = ok ? vo - (unsigned)b_i0[s] * (unsigned)RSC * 4u : 0u; ok = false; }
+                    const bf4 q = buffer_load4(rb, vo, (unsigned)(((int64_t)u_c * RSC + (r * cs.S + ss) * cs.C) * 4));
                     v = make_float4(q.x, q.y, q.z, q.w);
                 } else if (kk < Kg) {
                     int tap = (int)kk / cs.K, k = (int)kk % cs.K;
@@ -1032,10 +1046,18 @@ void launch_tile(hipStream_t st, TileArgs ta, bool fast, int zdim, float *out, i
     dim3 grid((unsigned)blocks, 1, (unsigned)zdim);
     if constexpr (TAG != 0) {
         if (!fast) throw KernelError("conv: batched GEMMs need aligned shapes");
-        hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true, TAG>), grid, dim3(NT), 0, st, ta);
+        hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, 1, TAG>), grid, dim3(NT), 0, st, ta);
     } else {
-        if (fast) hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, true>), grid, dim3(NT), 0, st, ta);
-        else hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, false>), grid, dim3(NT), 0, st, ta);
+        // a forward or input-gradient reduction that is no multiple of 16 (the host admits that for 1x1 layers only)
+        const bool part = MODE == FWD ? ta.cs.C % BK != 0 : MODE == DGRAD ? ta.cs.K % BK != 0 : false;
+        if constexpr (MODE != WGRAD) {
+            if (fast && part) { hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, 2>), grid, dim3(NT), 0, st, ta); }
+            else if (fast) { hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, 1>), grid, dim3(NT), 0, st, ta); }
+            else { hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, 0>), grid, dim3(NT), 0, st, ta); }
+        } else {
+            if (fast) { hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, 1>), grid, dim3(NT), 0, st, ta); }
+            else { hipLaunchKernelGGL((conv_tile_kernel<MODE, WM, WN, 0>), grid, dim3(NT), 0, st, ta); }
+        }
     }
     hip_check(hipGetLastError(), "conv launch");
     if (slabs) launch_split_reduce(st, ws, out, ta.out_elems, splits, MODE != WGRAD && accumulate);
@@ -1079,6 +1101,10 @@ void launch_batched(int cfg, Rest... rest) {
 }  // namespace
 
 void conv_force_tile(int cfg) { g_cfg_override = cfg; }
+
+// reduction steps of 16 must not straddle filter taps: C % 16 == 0, or a 1x1 layer (one tap) with C % 4 == 0, whose last
+// step is partly empty
+bool conv_fwd_aligned(const ConvShape &cs) { return cs.C % BK == 0 || (cs.R == 1 && cs.S == 1 && cs.C % 4 == 0); }
 
 bool conv_epilogue_writes_mask(const ConvShape &cs, bool winograd_fused) {
     (void)winograd_fused;      // both forms: a word of the code is 64 consecutive channels of one position
@@ -1172,9 +1198,9 @@ void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const Co
     // the aligned loader addresses both operands with 32-bit byte offsets (plus one tap's reach) and keeps one bit per filter tap
     const int64_t span32 = ((int64_t)1 << 32) - (1 << 20);
     const int64_t reach = ((int64_t)(cs.R + cs.pad) * cs.W + cs.S + cs.pad) * cs.C * 4;
-    bool fast = cs.C % BK == 0 && cs.R * cs.S <= 32 && (int64_t)cs.N * cs.H * cs.W * cs.C * 4 + reach < span32 && cs.K * cs.RSC() * 4 < span32;
+    bool fast = conv_fwd_aligned(cs) && cs.R * cs.S <= 32 && (int64_t)cs.N * cs.H * cs.W * cs.C * 4 + reach < span32 && cs.K * cs.RSC() * 4 < span32;
     if ((stats_part || affine) && (!fast || cs.K % 4 || splits != 1 || accumulate))
-        throw KernelError("conv_fwd: statistics or BatchNorm in the epilogue need C % 16 == 0, K % 4 == 0, splits == 1 and no accumulation");
+        throw KernelError("conv_fwd: statistics or BatchNorm in the epilogue need C % 16 == 0 (1x1: C % 4 == 0), K % 4 == 0, splits == 1 and no accumulation");
     if (stats_part && affine) throw KernelError("conv_fwd: either the statistics of the output or its BatchNorm apply step, not both");
     if (affine && (!affine->gamma || !affine->beta || !affine->stats)) throw KernelError("conv_fwd: incomplete BatchNorm coefficients");
     if (affine && affine->mask && (!affine->relu || cs.K % 64)) throw KernelError("conv_fwd: a sign code in the epilogue needs the ReLU and K % 64 == 0");
@@ -1195,7 +1221,10 @@ void conv_dgrad(hipStream_t st, const float *dy, const float *w, float *dx, cons
     ta.out_elems = (int64_t)cs.N * cs.H * cs.W * cs.C;
     const int64_t span32 = ((int64_t)1 << 32) - (1 << 20);
     const int64_t reach = ((int64_t)cs.R * cs.Q + cs.S) * cs.K * 4;
-    bool fast = cs.K % BK == 0 && cs.C % 4 == 0 && cs.R * cs.S <= 32 && cs.M() * cs.K * 4 + reach < span32 && cs.K * cs.RSC() * 4 < span32;
+    // reduction steps of 16 must not straddle filter taps: K % 16 == 0, or a 1x1 layer (one tap) with K % 4 == 0, whose last
+    // step is partly empty
+    const bool k_ok = cs.K % BK == 0 || (cs.R == 1 && cs.S == 1 && cs.K % 4 == 0);
+    bool fast = k_ok && cs.C % 4 == 0 && cs.R * cs.S <= 32 && cs.M() * cs.K * 4 + reach < span32 && cs.K * cs.RSC() * 4 < span32;
     launch_cfg<DGRAD>(pick_cfg(DGRAD, ta.Mg, ta.Ng), st, ta, fast, sg.classes, dx, splits, ws, ws_bytes, sg.steps, accumulate, "conv_dgrad");
 }
 

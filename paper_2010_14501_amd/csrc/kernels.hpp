@@ -50,8 +50,10 @@ bool conv_epilogue_writes_mask(const ConvShape &cs, bool winograd_fused);
 // floats) and are added in range order.  splits == 1 needs no workspace.
 // y (+)= conv(x, w)
 // stats_part: if given, the epilogue also leaves BatchNorm's partial statistics of y (groups of 64 rows, the
-// layout bn_stats() reads with partials_ready) there; needs C % 16 == 0, K % 4 == 0, splits == 1, no accumulation.
+// layout bn_stats() reads with partials_ready) there; needs conv_fwd_aligned(cs), K % 4 == 0, splits == 1, no accumulation.
 // affine: if given, the BatchNorm apply step of y in the epilogue (same conditions as stats_part; not both).
+// whether the forward pass takes its aligned loader: C % 16 == 0, or a 1x1 layer with C % 4 == 0
+bool conv_fwd_aligned(const ConvShape &cs);
 void conv_fwd(hipStream_t st, const float *x, const float *w, float *y, const ConvShape &cs, int splits = 1, float *ws = nullptr,
               size_t ws_bytes = 0, bool accumulate = false, float *stats_part = nullptr, const BnAffine *affine = nullptr);
 // dx (+)= transpose-conv of dy with w

@@ -35,6 +35,10 @@ CONV_CASES = [
     (1, 9, 9, 20, 24, 3, 1, 1),         # C % 16 != 0 and K % 16 != 0
     (5, 7, 7, 512, 512, 3, 1, 1),       # deep reduction (4608)
     (2, 14, 14, 160, 320, 3, 1, 1),     # an inception 3x3: channel counts that are multiples of 16 but not of 128
+    (2, 28, 28, 24, 144, 1, 1, 0),      # 1x1 with 24 input channels: aligned forward loader, last reduction step half empty
+    (2, 28, 28, 144, 24, 1, 1, 0),      # ... and 24 output channels: the same in the input gradient
+    (3, 15, 13, 40, 36, 1, 2, 0),       # both at once, stride 2, ragged rows and columns
+    (2, 9, 9, 4, 8, 1, 1, 0),           # a single, mostly empty step
 ]
 
 
@@ -131,6 +135,8 @@ def test_conv_ragged_last_round_is_split_and_counts_reset():
     (2, 15, 13, 32, 80, 3, 2, 1),       # stride 2, a column tile that is only partly used (80 of 128)
     (2, 28, 28, 128, 64, 1, 2, 0),      # the 256x64 tile: four row groups per workgroup
     (48, 28, 28, 128, 128, 1, 1, 0),    # ragged last round cut and met inside the kernel
+    (2, 28, 28, 24, 144, 1, 1, 0),      # 1x1 with 24 input channels (last reduction step half empty)
+    (3, 15, 13, 40, 36, 1, 2, 0),
 ])
 def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
     """BatchNorm's forward statistics come out of the convolution's epilogue with the same bits as from a pass
@@ -174,6 +180,7 @@ def test_statistics_from_the_conv_epilogue_are_the_stand_alone_bits(case):
     (2, 15, 13, 32, 80, 3, 2, 1, 0),       # stride 2, a column tile that is only partly used
     (2, 28, 28, 128, 64, 1, 2, 0, 0),      # the 256x64 tile
     (48, 28, 28, 128, 128, 1, 1, 0, 0),    # ragged last round cut and met inside the kernel
+    (2, 28, 28, 24, 128, 1, 1, 0, 0),      # 1x1 with 24 input channels (last reduction step half empty)
     (3, 14, 14, 64, 128, 3, 1, 1, 2),      # Winograd, 2x2 output tiles
     (3, 14, 14, 64, 128, 3, 1, 1, 4),      # Winograd, 4x4 output tiles (last tile row / column partly outside)
     (2, 9, 7, 32, 48, 3, 1, 1, 4),
