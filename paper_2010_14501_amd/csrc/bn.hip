@@ -480,6 +480,78 @@ __global__ __launch_bounds__(256) void bn_bwd_partial(const float *__restrict__ 
     }
 }
 
+// The same partial sums for channel counts whose groups of four are no power of two (24, 36, 48, 96, 144, 240, 320 ...
+// groups): there the kernel above leaves up to half of the lanes of its last column block without work.  Here a workgroup
+// has T threads, a multiple of the number of channel groups, and streams one contiguous range of float4 elements
+// (a multiple of T, so that thread t meets channel group t % C4 only); the T / C4 threads of a group are added in thread
+// order.  Same layout of `part`, one row per workgroup.
+template <bool FROM_OUT, int RM>
+__global__ __launch_bounds__(512) void bn_bwd_partial_flat(const float *__restrict__ dy, const void *__restrict__ rt,
+                                                           const float *__restrict__ t, const float *__restrict__ gamma,
+                                                           const float *__restrict__ beta, const float *__restrict__ stats,
+                                                           float *__restrict__ part, int64_t total4, int C, int64_t slab4) {
+    __shared__ float sh_b[512 * 4];
+    __shared__ float sh_g[512 * 4];
+    const int C4 = C / 4, T = blockDim.x, tid = threadIdx.x;
+    const int cg = tid % C4;
+    const int64_t r0 = (int64_t)blockIdx.x * slab4;
+    const int64_t r1 = r0 + slab4 < total4 ? r0 + slab4 : total4;
+    float sb[4] = {0, 0, 0, 0}, sg[4] = {0, 0, 0, 0};
+    float sc[4], sh[4];   // xhat = t*sc + sh
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int c = cg * 4 + j;
+        if (FROM_OUT) { sc[j] = 1.0f / gamma[c]; sh[j] = -beta[c] * sc[j]; }
+        else { sc[j] = stats[C + c]; sh[j] = -stats[c] * sc[j]; }
+    }
+    const uint64_t *mask = (const uint64_t *)rt;
+    auto accumulate = [&](const f4 &g, const f4 &v, const f4 &rv, int64_t i4) {
+        float gg[4] = {g.x, g.y, g.z, g.w}, vv[4] = {v.x, v.y, v.z, v.w};
+        unsigned bits = 0;
+        if (RM == 1) bits = (unsigned)(mask[i4 >> 4] >> ((i4 & 15) * 4)) & 15u;
+        relu_gate<RM>(gg, bits, rv);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            sb[j] += gg[j];
+            sg[j] += gg[j] * (vv[j] * sc[j] + sh[j]);
+        }
+    };
+    // two elements at a time: four 16-byte loads in flight per thread
+    int64_t i = r0 + tid;
+    for (; i + T < r1; i += 2 * (int64_t)T) {
+        const int64_t ia = i, ib = i + T;
+        const f4 ga = (*((const f4 *)dy + ia)), va = (*((const f4 *)t + ia));
+        const f4 gb = (*((const f4 *)dy + ib)), vb = (*((const f4 *)t + ib));
+        f4 ra = f4{0, 0, 0, 0}, rb = f4{0, 0, 0, 0};
+        if (RM >= 2) { ra = __builtin_nontemporal_load((const f4 *)rt + ia); rb = __builtin_nontemporal_load((const f4 *)rt + ib); }
+        accumulate(ga, va, ra, ia);
+        accumulate(gb, vb, rb, ib);
+    }
+    if (i < r1) {
+        f4 ra = f4{0, 0, 0, 0};
+        if (RM >= 2) ra = __builtin_nontemporal_load((const f4 *)rt + i);
+        accumulate((*((const f4 *)dy + i)), (*((const f4 *)t + i)), ra, i);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        sh_b[tid * 4 + j] = sb[j];
+        sh_g[tid * 4 + j] = sg[j];
+    }
+    __syncthreads();
+    if (tid < C4) {
+        float b[4] = {0, 0, 0, 0}, g[4] = {0, 0, 0, 0};
+        for (int k = tid; k < T; k += C4)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { b[j] += sh_b[k * 4 + j]; g[j] += sh_g[k * 4 + j]; }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = tid * 4 + j;
+            part[((int64_t)blockIdx.x * C + c) * 2 + 0] = b[j];
+            part[((int64_t)blockIdx.x * C + c) * 2 + 1] = g[j];
+        }
+    }
+}
+
 // Block = FIN_CH channels x FIN_LANES slab lanes (lane sl adds slabs sl, sl+FIN_LANES, ... in order, then a fixed
 // tree); writes dbeta, dgamma and, for the apply pass, coef[c] = dbeta/m, coef[C+c] = dgamma/m
 __global__ __launch_bounds__(256) void bn_bwd_final(const float *__restrict__ part, float *__restrict__ dgamma,
@@ -521,7 +593,7 @@ __global__ __launch_bounds__(256) void bn_bwd_final(const float *__restrict__ pa
 // side (may be null): a second tensor that receives (or accumulates) the gated incoming gradient itself -- the
 // other branch of a residual add whose backward is folded in.
 template <bool FROM_OUT, int RM>
-__global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy, const void *__restrict__ rt,
+__global__ __launch_bounds__(512) void bn_bwd_apply(const float *__restrict__ dy, const void *__restrict__ rt,
                                                     const float *__restrict__ t,
                                                     const float *__restrict__ gamma, const float *__restrict__ beta,
                                                     const float *__restrict__ stats, const float *__restrict__ coef, float *dx,
@@ -530,7 +602,11 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
     // same streaming pattern as bn_apply_kernel
     constexpr int U = 4;
     const int C4 = C / 4;
-    const bool fixed = (256 % C4) == 0;
+    // The workgroup has T threads, a multiple of the number of channel groups whenever the host finds one (240 threads for
+    // 24, 40, 48, 80 or 240 groups, 252 for 36, ...): a thread then meets the same four channels in every element it visits
+    // and loads their coefficients once.  Otherwise (more than 512 groups) it looks them up element by element.
+    const int T = blockDim.x;
+    const bool fixed = (T % C4) == 0;
     float sc[4], sh[4], a[4], mb[4], mg[4];
     auto load = [&](int g) {
 #pragma unroll
@@ -543,19 +619,19 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
             mg[j] = coef[C + c];
         }
     };
-    const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + 255) / 256 * 256;
+    const int64_t per = ((total4 + gridDim.x - 1) / gridDim.x + T - 1) / T * T;
     // The ranges are taken from the end of the tensor backwards and dy / t are read with ordinary (cached) loads: the
     // partial-sum pass has just read both tensors front to back, so what it read last is what the memory-side cache
     // still holds (measured: 2-3 % on the ResNet-50 layers against front-to-back streaming loads).
     const int64_t r0 = (int64_t)(gridDim.x - 1 - blockIdx.x) * per;
     const int64_t r1 = r0 + per < total4 ? r0 + per : total4;
     if (fixed) load((int)(threadIdx.x % C4));
-    for (int64_t base = r0 + threadIdx.x; base < r1; base += U * 256) {
+    for (int64_t base = r0 + threadIdx.x; base < r1; base += U * T) {
         f4 g[U], v[U], o[U], rv[U], so[U];
         unsigned bits[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t i = base + u * 256;
+            const int64_t i = base + (int64_t)u * T;
             bits[u] = 0;
             rv[u] = f4{0, 0, 0, 0};
             if (i >= r1) continue;
@@ -568,7 +644,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply(const float *__restrict__ dy
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t i = base + u * 256;
+            const int64_t i = base + (int64_t)u * T;
             if (i >= r1) continue;
             if (!fixed) load((int)(i % C4));
             float gg[4] = {g[u].x, g[u].y, g[u].z, g[u].w}, vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w}, r[4];
@@ -605,14 +681,30 @@ void bn_bwd(hipStream_t st, const float *dy, const float *t, bool from_output, c
     const int grid = stream_grid(total4);
     const int acc = accumulate ? 1 : 0, sacc = side_acc ? 1 : 0;
 #define BP(F, RM) hipLaunchKernelGGL((bn_bwd_partial<F, RM>), dim3(g.G, g.CB), dim3(256), 0, st, dy, relu_t, t, gamma, beta, stats, scratch, rows, C, g.TPR, g.slab)
-#define BA(F, RM) hipLaunchKernelGGL((bn_bwd_apply<F, RM>), dim3(grid), dim3(256), 0, st, dy, relu_t, t, gamma, beta, stats, (const float *)coef, dx, acc, side, sacc, total4, C)
+    // threads of an apply workgroup: a multiple of the channel groups (so that a thread keeps its channels), at most 256
+    // where one exists, the group count itself up to 512
+    const int C4 = C / 4;
+    const int apply_threads = 256 % C4 == 0 ? 256 : C4 <= 256 ? C4 * (256 / C4) : C4 <= 512 ? C4 : 256;
+#define BA(F, RM) hipLaunchKernelGGL((bn_bwd_apply<F, RM>), dim3(grid), dim3(apply_threads), 0, st, dy, relu_t, t, gamma, beta, stats, (const float *)coef, dx, acc, side, sacc, total4, C)
 #define BOTH(STEP)                                                                 \
     do {                                                                           \
         if (from_output) { switch (rm) { case 0: STEP(true, 0); break; case 1: STEP(true, 1); break; case 2: STEP(true, 2); break; default: STEP(true, 3); } } \
         else             { switch (rm) { case 0: STEP(false, 0); break; case 1: STEP(false, 1); break; case 2: STEP(false, 2); break; default: STEP(false, 3); } } \
     } while (0)
-    BOTH(BP);
-    hipLaunchKernelGGL(bn_bwd_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, g.G);
+    // channel groups that leave lanes of the row-shared mapping idle take the flat mapping (same thread count as the apply pass)
+    int slabs = g.G;
+    if (g.C4 % g.TPR != 0 && apply_threads % C4 == 0) {
+        const int m = apply_threads / C4;                                        // rows per sweep of a workgroup
+        const int64_t slab_rows = (g.slab + m - 1) / m * m;
+        slabs = (int)((rows + slab_rows - 1) / slab_rows);
+        const int64_t slab4 = slab_rows * C4;
+#define BF(F, RM) hipLaunchKernelGGL((bn_bwd_partial_flat<F, RM>), dim3(slabs), dim3(apply_threads), 0, st, dy, relu_t, t, gamma, beta, stats, scratch, total4, C, slab4)
+        BOTH(BF);
+#undef BF
+    } else {
+        BOTH(BP);
+    }
+    hipLaunchKernelGGL(bn_bwd_final, dim3((C + FIN_CH - 1) / FIN_CH), dim3(256), 0, st, (const float *)scratch, dgamma, dbeta, coef, rows, C, slabs);
     BOTH(BA);
 #undef BOTH
 #undef BA
