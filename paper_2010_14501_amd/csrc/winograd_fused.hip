@@ -36,6 +36,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int FT = 32;            // tiles per workgroup
 constexpr int FK = 64;            // output channels per workgroup
 constexpr int FC = 8;             // reduction channels per chunk
+constexpr int FUSED_CUS = 256;    // one workgroup per CU (LDS)
 constexpr int VROW = FC + 1;      // row of V[z][tile][.] in LDS, padded: 32 tiles x 9 words hit 32 different banks
 constexpr int MROW = 33;          // row of M[z][tile][.] in LDS
 constexpr int LDS_FLOATS = 36 * FT * MROW;               // 152 064 bytes; the two V buffers take the first 82 944
@@ -113,6 +114,10 @@ struct FusedGeom {
     int nch;            // red / 8
     int kblocks;        // ceil(outc / 64)
     int64_t items;      // ceil(T / 32) * kblocks
+    // Items [main_items, items) are worked as two half items of 32 output channels each (the ragged last round of a launch
+    // with few items: a half item takes about 0.6 of a whole one, and twice as many CUs take part).  main_items is a
+    // multiple of 8; main_items == items: no item is halved.
+    int64_t main_items;
 };
 
 // What a patch lane knows about its (tile, channel): byte offsets of the six patch columns / rows (clamped into the map) and
@@ -159,9 +164,10 @@ __device__ __forceinline__ PatchLane patch_lane(const FusedGeom &gm, int64_t tb,
 
 // The reduction loop of one wave: NZ positions z0 .. z0 + NZ - 1 of the 32 x 64 tile; PATCH: this wave also loads and
 // transforms the input patches (one (tile, channel) per lane and chunk); INTERIOR: all of the wave's patches lie inside
-// the map (nothing to clamp, nothing to zero).
-template <int NZ, bool PATCH, bool INTERIOR>
-__device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const float *__restrict__ Up, float *lds, const FusedGeom &gm, int kb,
+// the map (nothing to clamp, nothing to zero); HALF: a half item, only the block of 32 output channels ob (acc[.][0]); else
+// the blocks ob and ob + 1.
+template <int NZ, bool PATCH, bool INTERIOR, bool HALF>
+__device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const float *__restrict__ Up, float *lds, const FusedGeom &gm, int ob,
                                              int z0, int ptid, int lane, const PatchLane &pl, floatx16 (&acc)[5][2]) {
     const int l32 = lane & 31, g = lane >> 5;
     const int nch = gm.nch;
@@ -208,7 +214,7 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
         }
     };
 
-    // ---- B operands: position z0 + zi, channel blocks 2 * kb and 2 * kb + 1, chunk ch.  Loads return in the order they
+    // ---- B operands: position z0 + zi, channel blocks ob and (a whole item) ob + 1, chunk ch.  Loads return in the order they
     // were issued, so they are issued in the order of their use: the positions of chunk ch + 1 are requested while chunk ch
     // is multiplied (each into the registers its predecessor just left), after the patch of chunk ch + 1, which is
     // requested first and used last.
@@ -216,12 +222,12 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
     const __amdgpu_buffer_rsrc_t ru = buffer_of(Up);
     const unsigned lane16 = (unsigned)lane * 16u;
     const unsigned zbytes = (unsigned)o32 * nch * 1024u, hbytes = (unsigned)nch * 1024u;      // the host checks the workspace size
-    const unsigned b0bytes = ((unsigned)z0 * o32 + 2u * kb) * nch * 1024u;
+    const unsigned b0bytes = ((unsigned)z0 * o32 + (unsigned)ob) * nch * 1024u;
     f4 bq[NZ][2];
     auto load_b = [&](int zi, int ch) {
         const unsigned so = b0bytes + zi * zbytes + (unsigned)ch * 1024u;
         bq[zi][0] = buffer_load4(ru, lane16, so);
-        bq[zi][1] = buffer_load4(ru, lane16, so + hbytes);
+        if (!HALF) bq[zi][1] = buffer_load4(ru, lane16, so + hbytes);
     };
 
     if (PATCH) load_patch(0);
@@ -259,13 +265,13 @@ __device__ __forceinline__ void fused_reduce(const float *__restrict__ x, const 
             }
             __builtin_amdgcn_sched_barrier(0);
             acc[zi][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(c0, bq[zi][0].x, acc[zi][0], 0, 0, 0);
-            acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c0, bq[zi][1].x, acc[zi][1], 0, 0, 0);
+            if (!HALF) acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c0, bq[zi][1].x, acc[zi][1], 0, 0, 0);
             acc[zi][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(c1, bq[zi][0].y, acc[zi][0], 0, 0, 0);
-            acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c1, bq[zi][1].y, acc[zi][1], 0, 0, 0);
+            if (!HALF) acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c1, bq[zi][1].y, acc[zi][1], 0, 0, 0);
             acc[zi][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(c2, bq[zi][0].z, acc[zi][0], 0, 0, 0);
-            acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c2, bq[zi][1].z, acc[zi][1], 0, 0, 0);
+            if (!HALF) acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c2, bq[zi][1].z, acc[zi][1], 0, 0, 0);
             acc[zi][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(c3, bq[zi][0].w, acc[zi][0], 0, 0, 0);
-            acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c3, bq[zi][1].w, acc[zi][1], 0, 0, 0);
+            if (!HALF) acc[zi][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(c3, bq[zi][1].w, acc[zi][1], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             load_b(zi, nx);      // into the registers the products above have just read
             __builtin_amdgcn_sched_barrier(0);
@@ -334,11 +340,29 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
     // Work item: hardware deals workgroups to the 8 XCDs in turn; item = (id mod 8) * (grid / 8) + id / 8 gives each XCD a
     // contiguous share, so that neighbouring tile rows (shared halo) and the channel blocks of one tile range (same input)
     // meet in one L2.  The grid is a multiple of 8; items beyond the last one do nothing.
-    const int64_t grid = gridDim.x, id = blockIdx.x;
-    const int64_t item = (id & 7) * (grid >> 3) + (id >> 3);
-    if (item >= gm.items) return;
+    // Every XCD takes its share of the whole items first, then its share of the half items, so that the short ones come
+    // last everywhere.
+    const int64_t id = blockIdx.x, xcd = id & 7, idx = id >> 3;
+    const int64_t pm = gm.main_items >> 3;
+    int64_t item;
+    int nh = 2, hsel = 0;          // blocks of 32 output channels this workgroup computes; the first of them within the item
+    if (gm.main_items == gm.items) {      // no item is halved: a contiguous share of the items per XCD
+        item = xcd * ((int64_t)gridDim.x >> 3) + idx;
+        if (item >= gm.items) return;
+    } else if (idx < pm) {
+        item = xcd * pm + idx;
+    } else {
+        const int64_t nhalf = (gm.items - gm.main_items) * 2, pt = (nhalf + 7) >> 3;
+        const int64_t j = xcd * pt + (idx - pm);
+        if (idx - pm >= pt || j >= nhalf) return;
+        item = gm.main_items + (j >> 1);
+        nh = 1;
+        hsel = (int)(j & 1);
+    }
     const int kb = (int)(item % gm.kblocks);
     const int64_t tb = item / gm.kblocks;
+    const int ob = 2 * kb + hsel;
+    if (ob * 32 >= gm.outc) return;      // the second half of a last, half-empty channel block (uniform over the workgroup)
 
     floatx16 acc[5][2];
 #pragma unroll
@@ -350,12 +374,19 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
     const bool heavy = wave < 4;
     const int z0 = heavy ? 5 * wave : 20 + 4 * (wave - 4), nz = heavy ? 5 : 4;
     if (heavy) {
-        fused_reduce<5, false, false>(x, Up, lds, gm, kb, z0, 0, lane, PatchLane{}, acc);
+        if (nh == 2) fused_reduce<5, false, false, false>(x, Up, lds, gm, ob, z0, 0, lane, PatchLane{}, acc);
+        else fused_reduce<5, false, false, true>(x, Up, lds, gm, ob, z0, 0, lane, PatchLane{}, acc);
     } else {
         const PatchLane pl = patch_lane(gm, tb, tid - 256, tinfo);      // tinfo is complete at the loop's first barrier
         // uniform over the wave; every version of the loop meets the workgroup's barriers the same number of times
-        if (__all(pl.rowok == 0x3fu && pl.colok == 0x3fu)) fused_reduce<4, true, true>(x, Up, lds, gm, kb, z0, tid - 256, lane, pl, acc);
-        else fused_reduce<4, true, false>(x, Up, lds, gm, kb, z0, tid - 256, lane, pl, acc);
+        const bool interior = __all(pl.rowok == 0x3fu && pl.colok == 0x3fu);
+        if (nh == 2) {
+            if (interior) fused_reduce<4, true, true, false>(x, Up, lds, gm, ob, z0, tid - 256, lane, pl, acc);
+            else fused_reduce<4, true, false, false>(x, Up, lds, gm, ob, z0, tid - 256, lane, pl, acc);
+        } else {
+            if (interior) fused_reduce<4, true, true, true>(x, Up, lds, gm, ob, z0, tid - 256, lane, pl, acc);
+            else fused_reduce<4, true, false, true>(x, Up, lds, gm, ob, z0, tid - 256, lane, pl, acc);
+        }
     }
 
     // ---- output transform, 32 channels at a time: thread = (channel ok_ of the half, tiles oq and oq + 16).  Output element
@@ -368,8 +399,8 @@ __global__ __launch_bounds__(512) void wino4_fused_kernel(const float *__restric
     const __amdgpu_buffer_rsrc_t ry2 = buffer_of(two ? bn.relu_out : y);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int kout = kb * FK + h * 32 + ok_;
-        if (kb * FK + h * 32 >= gm.outc) break;       // uniform over the workgroup
+        const int kout = (ob + h) * 32 + ok_;
+        if (h >= nh || (ob + h) * 32 >= gm.outc) break;       // uniform over the workgroup
         if (h) __syncthreads();                        // the first half has been read
 #pragma unroll
         for (int zi = 0; zi < 5; ++zi)
@@ -427,7 +458,11 @@ void conv_winograd_fused(hipStream_t st, const float *in, const float *w, float 
     gm.nch = gm.red / FC;
     gm.kblocks = (gm.outc + FK - 1) / FK;
     gm.items = (gm.T + FT - 1) / FT * gm.kblocks;
-    const int64_t grid = (gm.items + 7) / 8 * 8;
+    // the ragged last round: at most half a round of whole items beyond a multiple of the CU count becomes at most one
+    // round of half items
+    gm.main_items = gm.items;
+    if (gm.items > FUSED_CUS && gm.items % FUSED_CUS && gm.items % FUSED_CUS <= FUSED_CUS / 2) gm.main_items = gm.items - gm.items % FUSED_CUS;
+    const int64_t grid = gm.main_items == gm.items ? (gm.items + 7) / 8 * 8 : gm.main_items + ((gm.items - gm.main_items) * 2 + 7) / 8 * 8;
     if (gm.T < 1 || gm.T >= 0x7fffffffll || grid >= 0x7fffffffll || (int64_t)(cs.N * (int64_t)cs.H + 8) * cs.W * std::max(gm.red, gm.outc) * 4 >= ((int64_t)1 << 32) - 65536)
         throw KernelError("conv_winograd_fused: shape out of range (input and output must have fewer than 2^32 bytes each)");
     const int out_pad = gm.kblocks * FK;

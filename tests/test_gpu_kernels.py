@@ -342,6 +342,10 @@ def test_winograd_convolution_matches_oracle(case, m):
     (3, 56, 56, 64, 64),        # many tiles: 588 per channel block, ragged last workgroup (588 = 18 * 32 + 12)
     (1, 3, 2, 16, 16),          # a map smaller than one 4x4 tile
     (2, 12, 20, 24, 40),        # reduction channels a multiple of 8 only, 40 output channels (second half mostly padding)
+    # more work items than CUs with a short remainder, which is worked as half items of 32 output channels:
+    (3, 224, 224, 8, 72),       # forward 588 items (512 + 76 halved, every second one with 8 channels in its first half and none
+                                # in its second), input gradient 294 (256 + 38 halved, 8 output channels)
+    (3, 120, 124, 8, 160),      # 264 items (256 + 8 halved) of three channel blocks, the third half empty; ragged last tile block
 ])
 def test_fused_winograd_convolution_matches_oracle(case):
     """F(4x4, 3x3) in one kernel (no transformed tensors in memory): forward, input gradient written and accumulated,
