@@ -242,7 +242,9 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const float *__restric
 template <int L, bool IDX>
 __global__ __launch_bounds__(256) void maxpool3s1_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, uint8_t *__restrict__ idx,
                                                              int N, int H, int W, int C4, int segs, int64_t items) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // a contiguous share of the items per XCD (hardware deals workgroups to the 8 XCDs in turn; the grid is a multiple of
+    // 8): the output rows that read the same input rows meet in one L2
+    const int64_t i = ((int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * 256 + threadIdx.x;
     if (i >= items) return;
     const int c4 = (int)(i % C4);
     int64_t t = i / C4;
@@ -293,8 +295,8 @@ void maxpool_fwd(hipStream_t st, const float *x, float *y, uint8_t *idx, const P
         constexpr int L = 4;
         const int segs = (ps.W + L - 1) / L;
         const int64_t items = (int64_t)ps.N * ps.H * segs * (ps.C / 4);
-        if ((items + 255) / 256 > 0x7fffffffll) throw KernelError("maxpool: too many work items");
-        const dim3 g1((unsigned)((items + 255) / 256)), blk(256);
+        if ((items + 255) / 256 >= 0x7ffffff0ll) throw KernelError("maxpool: too many work items");
+        const dim3 g1((unsigned)(((items + 255) / 256 + 7) / 8 * 8)), blk(256);
         if (idx) hipLaunchKernelGGL((maxpool3s1_fwd_kernel<L, true>), g1, blk, 0, st, x, y, idx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
         else hipLaunchKernelGGL((maxpool3s1_fwd_kernel<L, false>), g1, blk, 0, st, x, y, idx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
         hip_check(hipGetLastError(), "maxpool_fwd launch");
@@ -417,12 +419,78 @@ __global__ __launch_bounds__(256) void maxpool_bwd_idx_kernel(const float *__res
     ((float4 *)dx)[i] = r;
 }
 
+// 3x3 / stride 1 / pad 1 from the stored index over row segments, like the forward kernel: one thread per (input row, segment
+// of L consecutive pixels, four channels) loads the 3 x (L + 2) windows that contain a pixel of the segment once (gradient and
+// index); every window serves up to three pixels from registers (4.5 loads of each kind per pixel at L = 4 instead of 9).
+// Windows are added in the general kernel's order (ascending p, then ascending q): the same bits.
+template <int L, bool ACC>
+__global__ __launch_bounds__(256) void maxpool3s1_bwd_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ idx, float *dx,
+                                                             int N, int H, int W, int C4, int segs, int64_t items) {
+    // a contiguous share of the items per XCD (the grid is a multiple of 8): neighbouring rows read the same windows
+    const int64_t i = ((int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * 256 + threadIdx.x;
+    if (i >= items) return;
+    const int c4 = (int)(i % C4);
+    int64_t t = i / C4;
+    const int seg = (int)(t % segs); t /= segs;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    const int w0 = seg * L;
+    const int64_t img = (int64_t)n * H * W * C4 + c4;
+    float4 g[3][L + 2];
+    uchar4 ix[3][L + 2];
+    bool ok[3][L + 2];
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const int p = h - 1 + a;
+#pragma unroll
+        for (int b = 0; b < L + 2; ++b) {
+            const int q = w0 - 1 + b;
+            ok[a][b] = (unsigned)p < (unsigned)H && (unsigned)q < (unsigned)W;
+            const int64_t o = ok[a][b] ? img + ((int64_t)p * W + q) * C4 : 0;
+            g[a][b] = ((const float4 *)dy)[o];
+            ix[a][b] = ((const uchar4 *)idx)[o];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        if (w0 + j >= W) break;
+        float acc[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int a = 0; a < 3; ++a)
+#pragma unroll
+            for (int b = j; b < j + 3; ++b) {
+                // pixel (h, w0 + j) inside window (p, q) = (h - 1 + a, w0 - 1 + b): row 2 - a, column j - b + 2
+                const int mine = ok[a][b] ? (2 - a) * 3 + (j - b + 2) : -1;
+                const float gg[4] = {g[a][b].x, g[a][b].y, g[a][b].z, g[a][b].w};
+                const int sel[4] = {ix[a][b].x, ix[a][b].y, ix[a][b].z, ix[a][b].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (sel[e] == mine) acc[e] += gg[e];
+            }
+        const int64_t o = img + ((int64_t)h * W + w0 + j) * C4;
+        float4 r = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        if (ACC) { const float4 was = ((const float4 *)dx)[o]; r.x += was.x; r.y += was.y; r.z += was.z; r.w += was.w; }
+        ((float4 *)dx)[o] = r;
+    }
+}
+
 void maxpool_bwd(hipStream_t st, const float *dy, const float *x, const uint8_t *idx, float *dx, const PoolShape &ps,
                  bool accumulate) {
     if (ps.C % 4) throw KernelError("maxpool: C must be a multiple of 4");
     if (!idx && !x) throw KernelError("maxpool_bwd: needs the input or the index");
     int64_t total = (int64_t)ps.N * ps.H * ps.W * (ps.C / 4);
     if (total <= 0) return;
+    if (idx && ps.k == 3 && ps.stride == 1 && ps.pad == 1 && ps.P == ps.H && ps.Q == ps.W) {
+        constexpr int L = 4;
+        const int segs = (ps.W + L - 1) / L;
+        const int64_t items = (int64_t)ps.N * ps.H * segs * (ps.C / 4);
+        if ((items + 255) / 256 >= 0x7ffffff0ll) throw KernelError("maxpool_bwd: too many work items");
+        const dim3 g1((unsigned)(((items + 255) / 256 + 7) / 8 * 8)), blk(256);
+        if (accumulate) hipLaunchKernelGGL((maxpool3s1_bwd_kernel<L, true>), g1, blk, 0, st, dy, idx, dx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
+        else hipLaunchKernelGGL((maxpool3s1_bwd_kernel<L, false>), g1, blk, 0, st, dy, idx, dx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
+        hip_check(hipGetLastError(), "maxpool_bwd launch");
+        return;
+    }
     if (idx && (total + 255) / 256 <= 0x7fffffffll && ps.pad >= 0 && ps.pad < ps.k &&
         ((ps.k == 3 && (ps.stride == 1 || ps.stride == 2)) || (ps.k == 2 && ps.stride == 2))) {
         const dim3 g1((unsigned)((total + 255) / 256)), blk(256);

@@ -784,8 +784,16 @@ def test_maxpool_index_bit_exact(case):
     assert np.array_equal(y.cpu().numpy(), wt.act_from_oracle(yo).astype(np.float32))
     want = wt.act_from_oracle(nm.maxpool_bwd_from_index(wt.act_to_oracle(dy), idxo, (N, C, H, W), k, stride, pad))
     ddy = dev(dy)
+    got = {}
     for use_idx in (True, False):
         gx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device="cuda")
         monet.call("monet_maxpool_bwd", None, ddy.data_ptr(), d.data_ptr(), idx.data_ptr() if use_idx else None, gx.data_ptr(),
                    N, H, W, C, k, stride, pad, 0)
         assert rel(gx.cpu().numpy(), want) < 1e-6
+        got[use_idx] = gx.clone()
+        # added to what is there: the same sum once more (doubling is exact)
+        monet.call("monet_maxpool_bwd", None, ddy.data_ptr(), d.data_ptr(), idx.data_ptr() if use_idx else None, gx.data_ptr(),
+                   N, H, W, C, k, stride, pad, 1)
+        assert torch.equal(gx, got[use_idx] + got[use_idx])
+    # the kernels that read the stored index (row segments, compile-time windows) add the windows in the general kernel's order
+    assert torch.equal(got[True], got[False])
