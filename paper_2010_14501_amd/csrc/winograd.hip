@@ -301,7 +301,9 @@ __global__ __launch_bounds__(256) void wino4_filter_kernel(const float *__restri
 template <int USE>
 __global__ __launch_bounds__(256) void wino4_input_kernel(const float *__restrict__ x, float *__restrict__ V, WinoGeom gm, int C) {
     const int C2 = C / 2;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // a contiguous share of the tiles per XCD (hardware deals workgroups to the 8 XCDs in turn; the grid is a multiple of 8):
+    // neighbouring tile rows, which share two of their six input rows, meet in one L2
+    const int64_t idx = ((int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * 256 + threadIdx.x;
     if (idx >= gm.T * C2) return;
     const int c2 = (int)(idx % C2);
     const int64_t t = idx / C2;
@@ -538,7 +540,7 @@ void conv_winograd(hipStream_t st, const float *in, const float *w, float *out, 
         float *pout = out + (size_t)img0 * cs.H * cs.W * outc;
         float *V = U + wp.filt, *M = V + (size_t)planes * gm.T * red;
         const int64_t ie = gm.T * (red / vec), oe = gm.T * (outc / vec);
-        const dim3 ig((unsigned)((ie + 255) / 256)), og((unsigned)((oe + 255) / 256));
+        const dim3 ig((unsigned)(((ie + 255) / 256 + 7) / 8 * 8)), og((unsigned)((oe + 255) / 256));
         if (m == 2) {
             if (adjoint) hipLaunchKernelGGL(wino_input_kernel<1>, ig, blk, 0, st, pin, V, gm, red);
             else hipLaunchKernelGGL(wino_input_kernel<0>, ig, blk, 0, st, pin, V, gm, red);
@@ -619,7 +621,7 @@ void conv_winograd_wgrad(hipStream_t st, const float *x, const float *dy, float 
         float *V = VD, *D = V + (size_t)planes * gm.T * cs.C;
         const float *px = x + (size_t)img0 * cs.H * cs.W * cs.C, *pdy = dy + (size_t)img0 * cs.H * cs.W * cs.K;
         const int64_t ie = gm.T * (cs.C / vec), de = gm.T * (cs.K / vec);
-        const dim3 ig((unsigned)((ie + 255) / 256)), dg((unsigned)((de + 255) / 256));
+        const dim3 ig((unsigned)(((ie + 255) / 256 + 7) / 8 * 8)), dg((unsigned)((de + 255) / 256));
         if (m == 2) {
             hipLaunchKernelGGL(wino_input_kernel<2>, ig, blk, 0, st, px, V, gm, cs.C);
             hipLaunchKernelGGL(wino_dy_kernel, dg, blk, 0, st, pdy, D, gm, cs.K);
