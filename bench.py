@@ -7,7 +7,7 @@ saving, then the backward pass with recomputation -- of the ResNet-50-shaped net
 schedule with the lean operator variants, through libmonet.so.  Inputs, weights and the arena
 are resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_b184|vgg16_b176|unet_b11|mobilenetv2_b272|tiny_chain]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50_b184|vgg16_b176|unet_b11|mobilenetv2_b272|googlenet_b320|tiny_chain, or one of these with _store_everything, _store_everything_lean, _block_outputs, _igemm, _ilp_<budget>]
 """
 import argparse
 import json
@@ -99,6 +99,9 @@ def build_workload(name, variants=None):
         if name == base + "_store_everything":
             g = make()
             return g, schedules.store_everything_schedule(g), batch, "store everything, standard variants"
+        if name == base + "_store_everything_lean":
+            g = make()
+            return g, schedules.store_everything_schedule(g, lean_variants), batch, "store everything the lean variants read"
     if name == "tiny_chain":
         g = graphs.tiny_chain()
         return g, schedules.tiny_chain_schedule(g, {0, 2}, lean_variants), 2, "checkpoint blocks {0,2}, recompute {1,3}; lean variants"
