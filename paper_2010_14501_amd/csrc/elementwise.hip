@@ -474,6 +474,175 @@ __global__ __launch_bounds__(256) void maxpool3s1_bwd_kernel(const float *__rest
     }
 }
 
+// 3x3 / stride 1 / pad 1 from the pool's input (the standard variant: no index was kept) over row segments: one thread per
+// (input row, segment of L consecutive pixels, four channels).  For each of the three window rows p = h - 1 .. h + 1 it
+// loads the 3 x (L + 4) inputs under the L + 2 windows that touch the segment, finds each window's maximum once (the forward
+// kernel's scan: row-major, strictly greater wins, taps outside the map skipped) and adds the window's gradient to the pixel
+// it selected: 4.5 windows and 13.5 inputs loaded per pixel instead of 9 and 81.  Windows are added in the general
+// kernel's order (ascending p, then ascending q): the same bits.
+template <int L, bool ACC>
+__global__ __launch_bounds__(256) void maxpool3s1_bwd_input_kernel(const float *__restrict__ dy, const float *__restrict__ x, float *dx,
+                                                                   int N, int H, int W, int C4, int segs, int64_t items) {
+    const int64_t i = ((int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * 256 + threadIdx.x;      // a contiguous share per XCD
+    if (i >= items) return;
+    const int c4 = (int)(i % C4);
+    int64_t t = i / C4;
+    const int seg = (int)(t % segs); t /= segs;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    const int w0 = seg * L;
+    const int64_t img = (int64_t)n * H * W * C4 + c4;
+    float acc[L][4];
+#pragma unroll
+    for (int j = 0; j < L; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[j][e] = 0.0f;
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        const int p = h - 1 + a;
+        if ((unsigned)p >= (unsigned)H) continue;      // no such window row (uniform over few lanes; nothing below is shared)
+        float4 v[3][L + 4];
+        bool in[3][L + 4];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int hh = p - 1 + r;
+#pragma unroll
+            for (int c = 0; c < L + 4; ++c) {
+                const int ww = w0 - 2 + c;
+                in[r][c] = (unsigned)hh < (unsigned)H && (unsigned)ww < (unsigned)W;
+                v[r][c] = ((const float4 *)x)[in[r][c] ? img + ((int64_t)hh * W + ww) * C4 : 0];
+            }
+        }
+        float4 g[L + 2];
+        bool okq[L + 2];
+#pragma unroll
+        for (int b = 0; b < L + 2; ++b) {
+            const int q = w0 - 1 + b;
+            okq[b] = (unsigned)q < (unsigned)W;
+            g[b] = ((const float4 *)dy)[okq[b] ? img + ((int64_t)p * W + q) * C4 : 0];
+        }
+#pragma unroll
+        for (int b = 0; b < L + 2; ++b) {
+            if (!okq[b]) continue;
+            // window (p, q = w0 - 1 + b) covers columns q - 1 .. q + 1 = patch columns b .. b + 2
+            float best[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            int sel[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int sx = 0; sx < 3; ++sx) {
+                    if (!in[r][b + sx]) continue;
+                    const float vv[4] = {v[r][b + sx].x, v[r][b + sx].y, v[r][b + sx].z, v[r][b + sx].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (vv[e] > best[e]) { best[e] = vv[e]; sel[e] = r * 3 + sx; }
+                }
+            const float gg[4] = {g[b].x, g[b].y, g[b].z, g[b].w};
+            // pixel (h, w0 + j) sits at row 2 - a, column j - b + 2 of this window, for j = b - 2 .. b
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                if (j < b - 2 || j > b) continue;
+                const int mine = (2 - a) * 3 + (j - b + 2);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (sel[e] == mine) acc[j][e] += gg[e];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        if (w0 + j >= W) break;
+        const int64_t o = img + ((int64_t)h * W + w0 + j) * C4;
+        float4 r = make_float4(acc[j][0], acc[j][1], acc[j][2], acc[j][3]);
+        if (ACC) { const float4 was = ((const float4 *)dx)[o]; r.x += was.x; r.y += was.y; r.z += was.z; r.w += was.w; }
+        ((float4 *)dx)[o] = r;
+    }
+}
+
+// The same for 3x3 / stride 2 / pad 1 (the pool behind a network's first layer): a pixel row h lies in the window rows
+// p = (h + 1) / 2 - 1 and (h + 1) / 2 (the first only for odd h), the four pixels w0 .. w0 + 3 (w0 a multiple of 4) in the
+// windows q = w0 / 2 .. w0 / 2 + 2; per window row 3 x 7 inputs and 3 gradients are loaded (10.5 inputs per pixel
+// instead of 36).  Same order of windows, same bits as the general kernel.
+template <bool ACC>
+__global__ __launch_bounds__(256) void maxpool3s2_bwd_input_kernel(const float *__restrict__ dy, const float *__restrict__ x, float *dx,
+                                                                   int N, int H, int W, int P, int Q, int C4, int segs, int64_t items) {
+    constexpr int L = 4;
+    const int64_t i = ((int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) * 256 + threadIdx.x;      // a contiguous share per XCD
+    if (i >= items) return;
+    const int c4 = (int)(i % C4);
+    int64_t t = i / C4;
+    const int seg = (int)(t % segs); t /= segs;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    const int w0 = seg * L, q0 = w0 >> 1;
+    const int64_t img = (int64_t)n * H * W * C4 + c4, gimg = (int64_t)n * P * Q * C4 + c4;
+    float acc[L][4];
+#pragma unroll
+    for (int j = 0; j < L; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[j][e] = 0.0f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const int p = ((h + 1) >> 1) - 1 + a;
+        const int row = h - 2 * p + 1;                  // of pixel row h inside window row p
+        if ((unsigned)p >= (unsigned)P || row > 2) continue;
+        float4 v[3][7];
+        bool in[3][7];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int hh = 2 * p - 1 + r;
+#pragma unroll
+            for (int c = 0; c < 7; ++c) {
+                const int ww = w0 - 1 + c;
+                in[r][c] = (unsigned)hh < (unsigned)H && (unsigned)ww < (unsigned)W;
+                v[r][c] = ((const float4 *)x)[in[r][c] ? img + ((int64_t)hh * W + ww) * C4 : 0];
+            }
+        }
+        float4 g[3];
+        bool okq[3];
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            okq[b] = q0 + b < Q;
+            g[b] = ((const float4 *)dy)[okq[b] ? gimg + ((int64_t)p * Q + q0 + b) * C4 : 0];
+        }
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            if (!okq[b]) continue;
+            // window (p, q0 + b) covers columns 2 (q0 + b) - 1 .. + 1 = patch columns 2 b .. 2 b + 2
+            float best[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            int sel[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int sx = 0; sx < 3; ++sx) {
+                    if (!in[r][2 * b + sx]) continue;
+                    const float vv[4] = {v[r][2 * b + sx].x, v[r][2 * b + sx].y, v[r][2 * b + sx].z, v[r][2 * b + sx].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (vv[e] > best[e]) { best[e] = vv[e]; sel[e] = r * 3 + sx; }
+                }
+            const float gg[4] = {g[b].x, g[b].y, g[b].z, g[b].w};
+            // pixel w0 + j sits at column j - 2 b + 1 of this window, for j = 2 b - 1 .. 2 b + 1
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                if (j < 2 * b - 1 || j > 2 * b + 1) continue;
+                const int mine = row * 3 + (j - 2 * b + 1);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (sel[e] == mine) acc[j][e] += gg[e];
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        if (w0 + j >= W) break;
+        const int64_t o = img + ((int64_t)h * W + w0 + j) * C4;
+        float4 r = make_float4(acc[j][0], acc[j][1], acc[j][2], acc[j][3]);
+        if (ACC) { const float4 was = ((const float4 *)dx)[o]; r.x += was.x; r.y += was.y; r.z += was.z; r.w += was.w; }
+        ((float4 *)dx)[o] = r;
+    }
+}
+
 void maxpool_bwd(hipStream_t st, const float *dy, const float *x, const uint8_t *idx, float *dx, const PoolShape &ps,
                  bool accumulate) {
     if (ps.C % 4) throw KernelError("maxpool: C must be a multiple of 4");
@@ -488,6 +657,27 @@ void maxpool_bwd(hipStream_t st, const float *dy, const float *x, const uint8_t 
         const dim3 g1((unsigned)(((items + 255) / 256 + 7) / 8 * 8)), blk(256);
         if (accumulate) hipLaunchKernelGGL((maxpool3s1_bwd_kernel<L, true>), g1, blk, 0, st, dy, idx, dx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
         else hipLaunchKernelGGL((maxpool3s1_bwd_kernel<L, false>), g1, blk, 0, st, dy, idx, dx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
+        hip_check(hipGetLastError(), "maxpool_bwd launch");
+        return;
+    }
+    if (!idx && ps.k == 3 && ps.stride == 1 && ps.pad == 1 && ps.P == ps.H && ps.Q == ps.W) {
+        constexpr int L = 4;
+        const int segs = (ps.W + L - 1) / L;
+        const int64_t items = (int64_t)ps.N * ps.H * segs * (ps.C / 4);
+        if ((items + 255) / 256 >= 0x7ffffff0ll) throw KernelError("maxpool_bwd: too many work items");
+        const dim3 g1((unsigned)(((items + 255) / 256 + 7) / 8 * 8)), blk(256);
+        if (accumulate) hipLaunchKernelGGL((maxpool3s1_bwd_input_kernel<L, true>), g1, blk, 0, st, dy, x, dx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
+        else hipLaunchKernelGGL((maxpool3s1_bwd_input_kernel<L, false>), g1, blk, 0, st, dy, x, dx, ps.N, ps.H, ps.W, ps.C / 4, segs, items);
+        hip_check(hipGetLastError(), "maxpool_bwd launch");
+        return;
+    }
+    if (!idx && ps.k == 3 && ps.stride == 2 && ps.pad == 1) {
+        const int segs = (ps.W + 3) / 4;
+        const int64_t items = (int64_t)ps.N * ps.H * segs * (ps.C / 4);
+        if ((items + 255) / 256 >= 0x7ffffff0ll) throw KernelError("maxpool_bwd: too many work items");
+        const dim3 g1((unsigned)(((items + 255) / 256 + 7) / 8 * 8)), blk(256);
+        if (accumulate) hipLaunchKernelGGL((maxpool3s2_bwd_input_kernel<true>), g1, blk, 0, st, dy, x, dx, ps.N, ps.H, ps.W, ps.P, ps.Q, ps.C / 4, segs, items);
+        else hipLaunchKernelGGL((maxpool3s2_bwd_input_kernel<false>), g1, blk, 0, st, dy, x, dx, ps.N, ps.H, ps.W, ps.P, ps.Q, ps.C / 4, segs, items);
         hip_check(hipGetLastError(), "maxpool_bwd launch");
         return;
     }

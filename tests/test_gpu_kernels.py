@@ -766,7 +766,8 @@ def test_relu_and_mask_bit_exact(shape, six):
 
 
 @pytest.mark.parametrize("case", [(2, 16, 16, 8, 3, 2, 1), (1, 9, 7, 4, 2, 2, 0), (2, 12, 12, 64, 3, 2, 1), (1, 5, 5, 4, 3, 1, 1),
-                                  (2, 14, 14, 64, 3, 1, 1), (1, 7, 9, 8, 3, 1, 1), (3, 28, 28, 192, 3, 1, 1)])
+                                  (2, 14, 14, 64, 3, 1, 1), (1, 7, 9, 8, 3, 1, 1), (3, 28, 28, 192, 3, 1, 1),
+                                  (1, 9, 7, 8, 3, 2, 1), (2, 13, 18, 12, 3, 2, 1), (1, 6, 5, 4, 3, 1, 1)])
 def test_maxpool_index_bit_exact(case):
     torch = torch_mod()
     N, H, W, C, k, stride, pad = case
