@@ -559,6 +559,63 @@ __global__ __launch_bounds__(256) void maxpool3s1_bwd_input_kernel(const float *
     }
 }
 
+// 3x3 / stride 2 / pad 1 from the stored index over row segments of four pixels (w0 a multiple of 4): the pixels lie in the
+// window rows p = (h + 1) / 2 - 1 (odd h only) and (h + 1) / 2 and in the windows q = w0 / 2 .. w0 / 2 + 2, whose gradients
+// and indices are loaded once (1.5 loads of each kind per pixel instead of 4).  Windows are added in the general kernel's
+// order (ascending p, then ascending q): the same bits.
+template <bool ACC>
+__global__ __launch_bounds__(256) void maxpool3s2_bwd_idx_kernel(const float *__restrict__ dy, const uint8_t *__restrict__ idx, float *dx,
+                                                                 int N, int H, int W, int P, int Q, int C4, int segs, int64_t items) {
+    constexpr int L = 4;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= items) return;
+    const int c4 = (int)(i % C4);
+    int64_t t = i / C4;
+    const int seg = (int)(t % segs); t /= segs;
+    const int h = (int)(t % H);
+    const int n = (int)(t / H);
+    const int w0 = seg * L, q0 = w0 >> 1;
+    const int64_t gimg = (int64_t)n * P * Q * C4 + c4;
+    float4 g[2][3];
+    uchar4 ix[2][3];
+    int row[2];
+    bool ok[2][3];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        const int p = ((h + 1) >> 1) - 1 + a;
+        row[a] = h - 2 * p + 1;                  // of pixel row h inside window row p
+        const bool pok = (unsigned)p < (unsigned)P && row[a] <= 2;
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            ok[a][b] = pok && q0 + b < Q;
+            const int64_t o = ok[a][b] ? gimg + ((int64_t)p * Q + q0 + b) * C4 : 0;
+            g[a][b] = ((const float4 *)dy)[o];
+            ix[a][b] = ((const uchar4 *)idx)[o];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        if (w0 + j >= W) break;
+        float acc[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                if (j < 2 * b - 1 || j > 2 * b + 1) continue;      // pixel w0 + j sits at column j - 2 b + 1 of window q0 + b
+                const int mine = ok[a][b] ? row[a] * 3 + (j - 2 * b + 1) : -1;
+                const float gg[4] = {g[a][b].x, g[a][b].y, g[a][b].z, g[a][b].w};
+                const int sel[4] = {ix[a][b].x, ix[a][b].y, ix[a][b].z, ix[a][b].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (sel[e] == mine) acc[e] += gg[e];
+            }
+        const int64_t o = ((int64_t)n * H * W + (int64_t)h * W + w0 + j) * C4 + c4;
+        float4 r = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        if (ACC) { const float4 was = ((const float4 *)dx)[o]; r.x += was.x; r.y += was.y; r.z += was.z; r.w += was.w; }
+        ((float4 *)dx)[o] = r;
+    }
+}
+
 // The same for 3x3 / stride 2 / pad 1 (the pool behind a network's first layer): a pixel row h lies in the window rows
 // p = (h + 1) / 2 - 1 and (h + 1) / 2 (the first only for odd h), the four pixels w0 .. w0 + 3 (w0 a multiple of 4) in the
 // windows q = w0 / 2 .. w0 / 2 + 2; per window row 3 x 7 inputs and 3 gradients are loaded (10.5 inputs per pixel
@@ -678,6 +735,16 @@ void maxpool_bwd(hipStream_t st, const float *dy, const float *x, const uint8_t 
         const dim3 g1((unsigned)(((items + 255) / 256 + 7) / 8 * 8)), blk(256);
         if (accumulate) hipLaunchKernelGGL((maxpool3s2_bwd_input_kernel<true>), g1, blk, 0, st, dy, x, dx, ps.N, ps.H, ps.W, ps.P, ps.Q, ps.C / 4, segs, items);
         else hipLaunchKernelGGL((maxpool3s2_bwd_input_kernel<false>), g1, blk, 0, st, dy, x, dx, ps.N, ps.H, ps.W, ps.P, ps.Q, ps.C / 4, segs, items);
+        hip_check(hipGetLastError(), "maxpool_bwd launch");
+        return;
+    }
+    if (idx && ps.k == 3 && ps.stride == 2 && ps.pad == 1) {
+        const int segs = (ps.W + 3) / 4;
+        const int64_t items = (int64_t)ps.N * ps.H * segs * (ps.C / 4);
+        if ((items + 255) / 256 > 0x7fffffffll) throw KernelError("maxpool_bwd: too many work items");
+        const dim3 g1((unsigned)((items + 255) / 256)), blk(256);
+        if (accumulate) hipLaunchKernelGGL((maxpool3s2_bwd_idx_kernel<true>), g1, blk, 0, st, dy, idx, dx, ps.N, ps.H, ps.W, ps.P, ps.Q, ps.C / 4, segs, items);
+        else hipLaunchKernelGGL((maxpool3s2_bwd_idx_kernel<false>), g1, blk, 0, st, dy, idx, dx, ps.N, ps.H, ps.W, ps.P, ps.Q, ps.C / 4, segs, items);
         hip_check(hipGetLastError(), "maxpool_bwd launch");
         return;
     }
