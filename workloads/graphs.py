@@ -132,9 +132,10 @@ class Graph:
         # transformed filters only (output channels padded to 64).  It reads the input once per 64 output channels and
         # streams the filters from L2 per 32 tiles, so it wins where maps are large or channels few (measured against the
         # workspace form, forward: x1.9 at 64 channels on 224x224 and 416x608, x1.3-1.5 at 128, x1.1 at 256 on 56x56,
-        # level at 28x28x128) and loses on small maps with many channels (x0.8 at 14x14x256 and 7x7x512).  The library
+        # level at 28x28x128 and, since the ragged last round of a launch is worked as half items, at 14x14x256, where it also takes the
+        # recomputed ReLU and its mask into its epilogue) and loses on small maps with more channels (14x14x512, 7x7x512).  The library
         # addresses the input with 32-bit byte offsets: tensors of 4 GiB and more keep the workspace form.
-        wino4f = wino4 and 4 * N * H * W * max(C, K) < (1 << 32) and not (H * W <= 14 * 14 and min(C, K) >= 160)
+        wino4f = wino4 and 4 * N * H * W * max(C, K) < (1 << 32) and not (H * W <= 14 * 14 and min(C, K) >= 320)
 
         # Workspace of the Winograd forms (mirrors the library): the transformed filters, plus the transformed input and
         # the products of one chunk of whole images -- the library works through a layer in chunks of about half a GiB
