@@ -461,7 +461,7 @@ void conv_winograd_fused(hipStream_t st, const float *in, const float *w, float 
     // the ragged last round: at most half a round of whole items beyond a multiple of the CU count becomes at most one
     // round of half items
     gm.main_items = gm.items;
-    if (gm.items > FUSED_CUS && gm.items % FUSED_CUS && gm.items % FUSED_CUS <= FUSED_CUS / 2) gm.main_items = gm.items - gm.items % FUSED_CUS;
+    if (gm.items % FUSED_CUS && gm.items % FUSED_CUS <= FUSED_CUS / 2) gm.main_items = gm.items - gm.items % FUSED_CUS;      // also a launch of at most half a round
     const int64_t grid = gm.main_items == gm.items ? (gm.items + 7) / 8 * 8 : gm.main_items + ((gm.items - gm.main_items) * 2 + 7) / 8 * 8;
     if (gm.T < 1 || gm.T >= 0x7fffffffll || grid >= 0x7fffffffll || (int64_t)(cs.N * (int64_t)cs.H + 8) * cs.W * std::max(gm.red, gm.outc) * 4 >= ((int64_t)1 << 32) - 65536)
         throw KernelError("conv_winograd_fused: shape out of range (input and output must have fewer than 2^32 bytes each)");
